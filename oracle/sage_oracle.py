@@ -1,0 +1,339 @@
+"""CPU oracle for the SageAttention2 quantized attention forward pass.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain reference the GPU kernels are
+checked against.  It is imported by tests/, by the smoke check and by the benchmark's
+CPU-baseline leg and by nothing else; the product path never calls it and it shares no
+code with the HIP sources.
+
+It follows the paper's Algorithm 1 ("Implementation of SageAttention2") step by step,
+with the smoothing of Sec. 3.1 (Eq. 2 and the Delta-S decomposition), the group quantizer
+of Sec. 2.2 / Sec. 3.2 / Appendix "Per-Thread Quantization Formulation", the FP8 E4M3
+quantization of Sec. 3.3 and the two-level accumulation of Sec. 3.4.  The plain
+definition of attention (Sec. 2.1, first formula) is `ref_attn_fp64`.
+
+Precision rules (the readings this repository takes where the paper is silent):
+  * inputs are fp16/bf16 values widened exactly; all "FP32" quantities are rounded once
+    from a float64 evaluation of the stated real-valued expression;
+  * means use an exact token sum (float64), one division, one rounding to FP32;
+  * scales are delta = fl32(max|x| / qmax); codes = clip(rint(fl32(x / delta)));
+    an all-zero group has delta = 0 and codes 0;
+  * softmax is evaluated in base 2: scores are multiplied by kappa = fl32(sm_scale*log2 e)
+    and 2**x replaces e**x, which leaves softmax unchanged;  the score of one (query, key)
+    pair is the single FP32 rounding of  acc * c + D  with c = fl32(fl32(dQ*dK) * kappa)
+    and D = fl32(kappa * <qbar_i, gamma(K)_t>)  (inner product in float64);
+  * l (the softmax denominator) sums the unquantized FP32 P~ as Algorithm 1 prints it;
+  * the per-block product R = P^ V^ is the exact sum of the FP8 products rounded once to
+    FP32 (an ideal FP32 buffer), then O = fl32(fl32(alpha*O) + R).
+Parity pins for every function here live in tests/test_oracle_pins.py.
+"""
+import numpy as np
+
+LOG2E_F32 = np.float32(1.4426950408889634)
+E4M3_MAX = 448.0
+BQ_SMOOTH = 128   # tokens per Q smoothing block (Algorithm 1's b_q)
+BKV_ACC = 64      # keys per level-1 accumulation block (Algorithm 1's b_kv)
+
+f32 = np.float32
+f64 = np.float64
+
+
+# --------------------------------------------------------------------------- FP8 E4M3
+def e4m3_decode(codes):
+    """OCP FP8 E4M3 ("fn": no infinities, 0x7f/0xff are NaN) byte codes -> float64."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    s = np.where(c & 0x80, -1.0, 1.0)
+    e = (c >> 3) & 0xF
+    m = c & 0x7
+    sub = np.ldexp(m.astype(f64), -9)                      # exponent field 0: m * 2^-9
+    nor = np.ldexp(1.0 + m.astype(f64) / 8.0, e - 7)       # (1 + m/8) * 2^(e-7)
+    v = np.where(e == 0, sub, nor)
+    v = np.where((e == 15) & (m == 7), np.nan, v)
+    return s * v
+
+
+def e4m3_encode(x):
+    """Round-to-nearest-even, saturating (|x| > 448 -> +-448) encoder to E4M3 byte codes.
+
+    Sec. 3.3 only says values are cast to E4M3 with range [-448, 448]; nearest-even and
+    saturation are this repository's reading.
+    """
+    x = np.asarray(x, dtype=f64)
+    sign = np.signbit(x)
+    a = np.minimum(np.abs(x), E4M3_MAX)
+    # spacing of representable values around a: 2^(floor(log2 a) - 3), at least 2^-9
+    _, ex = np.frexp(a)                        # a = mant * 2^ex, mant in [0.5, 1)
+    e_unb = np.maximum(ex - 1, -6)             # exponent of the binade, subnormals share -6
+    step = np.ldexp(1.0, e_unb - 3)
+    q = np.rint(a / step)                      # numpy rint = ties to even; a/step is exact
+    v = q * step                               # may round up into the next binade (exact)
+    v = np.minimum(v, E4M3_MAX)
+    # re-derive the fields from the rounded value
+    _, ex2 = np.frexp(v)
+    e_unb2 = np.maximum(ex2 - 1, -6)
+    is_sub = v < 2.0 ** -6
+    mant = np.where(is_sub, np.rint(v * 2.0 ** 9), np.rint((v / np.ldexp(1.0, e_unb2) - 1.0) * 8.0))
+    efield = np.where(is_sub, 0, e_unb2 + 7)
+    code = (efield.astype(np.int64) << 3) | mant.astype(np.int64)
+    code = np.where(v == 0, 0, code)
+    code = code | np.where(sign, 0x80, 0)
+    return code.astype(np.uint8)
+
+
+# --------------------------------------------------------------------------- group maps
+def group_map(name, N, which):
+    """Token -> quantization-group index, for `which` in {"q", "k"}.
+
+    "g950":  the groups of this repository's gfx950 kernels - the tokens whose products
+             land in one lane's accumulator registers (the per-thread principle of
+             Sec. 3.2): queries {2n, 2n+1}; keys in runs of 16.
+    "nv_m16n8": the paper's own grouping for mma.m16n8k64 with b_q=128, c_w=4, b_k=64
+             (Appendix "Per-Thread Quantization Formulation", last two paragraphs):
+             within a warp's 32 queries, tokens i, 8+i, 16+i, 24+i; within a 64-key block,
+             keys congruent to {2i, 2i+1} modulo 8.
+    "per_token", "per_block" (128 queries / 64 keys), "per_tensor": the granularities the
+             paper compares against (Sec. 2.2, Sec. 2.3, Sec. 3.2).
+    """
+    n = np.arange(N)
+    if name == "g950":
+        return n // 2 if which == "q" else n // 16
+    if name == "nv_m16n8":
+        if which == "q":
+            return (n // 32) * 8 + (n % 8)
+        return (n // 64) * 4 + (n % 8) // 2
+    if name == "per_token":
+        return n
+    if name == "per_block":
+        return n // (BQ_SMOOTH if which == "q" else BKV_ACC)
+    if name == "per_tensor":
+        return np.zeros(N, dtype=np.int64)
+    raise ValueError(name)
+
+
+# --------------------------------------------------------------------------- smoothing
+def token_mean(X):
+    """Mean over the token axis (axis 0) of an [n, d] float32 array: exact sum in float64,
+    one division, one rounding to FP32 (Sec. 3.1, text under Eq. 2)."""
+    X = np.asarray(X, dtype=f64)
+    return (X.sum(axis=0) / X.shape[0]).astype(f32)
+
+
+def smooth_k(K):
+    """gamma(K) = K - mean(K) over all tokens of the head (Eq. 2; Algorithm 1 preprocessing)."""
+    kbar = token_mean(K)
+    gK = (np.asarray(K, f64) - kbar.astype(f64)).astype(f32)
+    return kbar, gK
+
+
+def smooth_q(Q, bq=BQ_SMOOTH):
+    """gamma(Q_i) = Q_i - mean(Q_i) per block of bq tokens (Eq. 2; Algorithm 1, first line
+    of the outer loop).  A ragged last block averages its valid tokens."""
+    N, d = Q.shape
+    nblk = (N + bq - 1) // bq
+    qbar = np.zeros((nblk, d), f32)
+    gQ = np.empty((N, d), f32)
+    for i in range(nblk):
+        blk = slice(i * bq, min((i + 1) * bq, N))
+        qbar[i] = token_mean(Q[blk])
+        gQ[blk] = (np.asarray(Q[blk], f64) - qbar[i].astype(f64)).astype(f32)
+    return qbar, gQ
+
+
+def delta_s(qbar, gK, kappa):
+    """D[i, t] = fl32(kappa * <qbar_i, gamma(K)_t>): the Delta-S bias of Sec. 3.1 (the
+    "GEMV" of Algorithm 1's score line), already multiplied by kappa = sm_scale * log2 e."""
+    acc = qbar.astype(f64) @ gK.astype(f64).T
+    return (f64(kappa) * acc).astype(f32)
+
+
+# --------------------------------------------------------------------------- quantizers
+def quantize_groups(X, groups, qmax):
+    """psi of Sec. 2.2 applied per quantization group of tokens (Sec. 3.2, Appendix
+    Eq. "per_thread_quant"): delta_g = max over the group's tokens and all channels of |x|,
+    divided by qmax; codes = round-to-nearest-even(x / delta_g), clipped to [-qmax, qmax].
+
+    X: [N, d] float32;  groups: [N] ints.  Returns (delta [n_groups] float32, codes [N, d] int8).
+    """
+    X = np.asarray(X, f32)
+    groups = np.asarray(groups)
+    ng = int(groups.max()) + 1
+    row_max = np.abs(X).max(axis=1)
+    gmax = np.zeros(ng, f32)
+    np.maximum.at(gmax, groups, row_max)
+    delta = (gmax / f32(qmax)).astype(f32)                 # IEEE FP32 division
+    drow = delta[groups][:, None]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ratio = (X / drow).astype(f32)                     # IEEE FP32 division
+    ratio = np.where(drow > 0, ratio, f32(0))
+    codes = np.clip(np.rint(ratio), -qmax, qmax).astype(np.int8 if qmax <= 127 else np.int32)
+    return delta, codes
+
+
+def quantize_v(V):
+    """Per-channel FP8 quantization of V (Sec. 3.3; Algorithm 1 preprocessing):
+    delta_V[c] = max_n |V[n, c]| / 448, codes = E4M3(V / delta_V)."""
+    V = np.asarray(V, f32)
+    delta = (np.abs(V).max(axis=0) / f32(E4M3_MAX)).astype(f32)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ratio = (V / delta[None, :]).astype(f32)
+    ratio = np.where(delta[None, :] > 0, ratio, f32(0))
+    return delta, e4m3_encode(ratio)
+
+
+# --------------------------------------------------------------------------- prologue
+def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SMOOTH,
+                  smooth_q_on=None, smooth_k_on=True, pv_exact=False):
+    """Everything Algorithm 1 computes before the inner loop, for one (batch, head).
+
+    Q, K, V: [N, d] float32 holding exactly representable 16-bit values.
+    mode "int4_fp8": Q and K smoothed, INT4 range [-7, 7] (SageAttn2-4b);
+    mode "int8_fp8": only K smoothed, INT8 range [-127, 127] (SageAttn2-8b, Table
+    "Two kernel implementations").  An integer `mode` is used as qmax directly, smooth_*_on
+    override the mode and pv_exact keeps P~ and V unquantized: all three exist only so the
+    pins can take the quantizers to their high-precision limit.
+    """
+    N, d = Q.shape
+    if sm_scale is None:
+        sm_scale = 1.0 / np.sqrt(d)
+    qmax = {"int4_fp8": 7, "int8_fp8": 127}[mode] if isinstance(mode, str) else int(mode)
+    if smooth_q_on is None:
+        smooth_q_on = (mode == "int4_fp8")
+    kappa = f32(f32(sm_scale) * LOG2E_F32)
+    if smooth_k_on:
+        kbar, gK = smooth_k(K)
+    else:
+        kbar, gK = np.zeros(d, f32), np.asarray(K, f32)
+    if smooth_q_on:
+        qbar, gQ = smooth_q(Q, bq)
+        D = delta_s(qbar, gK, kappa)
+    else:
+        qbar, gQ, D = None, np.asarray(Q, f32), None
+    gq, gk = group_map(gmap, N, "q"), group_map(gmap, N, "k")
+    dq, qc = quantize_groups(gQ, gq, qmax)
+    dk, kc = quantize_groups(gK, gk, qmax)
+    if pv_exact:
+        dv, vc, vdec = np.ones(d, f32), None, np.asarray(V, f64)
+    else:
+        dv, vc = quantize_v(V)
+        vdec = e4m3_decode(vc)                            # [N, d] float64, exact
+    return dict(N=N, d=d, kappa=kappa, qmax=qmax, kbar=kbar, qbar=qbar, delta_s=D,
+                q_codes=qc, q_scale=dq, q_groups=gq, k_codes=kc, k_scale=dk, k_groups=gk,
+                v_codes=vc, v_scale=dv, v_dec=vdec, pv_exact=pv_exact, bq=bq)
+
+
+# --------------------------------------------------------------------------- attention
+def _exp2_f32(x):
+    """2**x evaluated in float64 and rounded to FP32 (2**-inf = 0)."""
+    with np.errstate(under="ignore"):
+        return np.exp2(np.asarray(x, f64)).astype(f32)
+
+
+def int_scores(q_codes, k_codes):
+    """acc[r, t] = sum_c Qhat[r, c] * Khat[t, c] as exact integers (the integer Matmul of
+    Algorithm 1's score line).  A float64 matmul is exact here: |acc| <= 127^2 * d << 2^53."""
+    return np.rint(q_codes.astype(f64) @ k_codes.astype(f64).T).astype(np.int64)
+
+
+def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_state=False):
+    """Inner loop + epilogue of Algorithm 1 for the query rows `rows` (a slice or index
+    array inside ONE smoothing block) of a head prepared by `quantize_head`.
+
+    Returns the [len(rows), d] output rounded to the 16-bit type (as float32).
+    """
+    N, d, kappa = pro["N"], pro["d"], pro["kappa"]
+    rows = np.arange(N)[rows]
+    blk = int(rows[0]) // pro["bq"]
+    assert int(rows[-1]) // pro["bq"] == blk, "rows must lie in one smoothing block"
+    qc = pro["q_codes"][rows]
+    dq = pro["q_scale"][pro["q_groups"][rows]]
+    vdec = pro["v_dec"]
+    nr = len(rows)
+    m = np.full(nr, -np.inf, f32)
+    l = np.zeros(nr, f32)
+    O = np.zeros((nr, d), f32)
+    last_key = int(rows[-1]) if causal else N - 1
+    n_blocks = last_key // bkv + 1
+    for j in range(n_blocks):
+        ks = np.arange(j * bkv, min((j + 1) * bkv, N))
+        acc = int_scores(qc, pro["k_codes"][ks])
+        dk = pro["k_scale"][pro["k_groups"][ks]]
+        c = ((dq[:, None] * dk[None, :]).astype(f32) * kappa).astype(f32)
+        s = acc.astype(f64) * c.astype(f64)
+        if pro["delta_s"] is not None:
+            s = s + pro["delta_s"][blk, ks].astype(f64)[None, :]
+        S = s.astype(f32)                                 # one rounding of acc*c + D
+        if causal:
+            S = np.where(ks[None, :] > rows[:, None], f32(-np.inf), S)
+        m_new = np.maximum(m, S.max(axis=1))
+        with np.errstate(invalid="ignore"):
+            P = _exp2_f32((S - m_new[:, None]).astype(f32))
+            alpha = _exp2_f32((m - m_new).astype(f32))
+        l = ((alpha * l).astype(f32).astype(f64) + P.astype(f64).sum(axis=1)).astype(f32)
+        P448 = (P * f32(E4M3_MAX)).astype(f32)
+        Phat = P448.astype(f64) if pro["pv_exact"] else e4m3_decode(e4m3_encode(P448))
+        R = (Phat @ vdec[ks]).astype(f32)                 # exact block sum, one rounding
+        O = ((alpha[:, None] * O).astype(f32) + R).astype(f32)
+        m = m_new
+    out = (O / l[:, None]).astype(f32)
+    out = (out / f32(E4M3_MAX)).astype(f32)
+    out = (out * pro["v_scale"][None, :]).astype(f32)
+    res = _round_out(out, out_dtype)
+    if return_state:
+        return res, dict(m=m, l=l, O=O)
+    return res
+
+
+def _round_out(x, dtype):
+    if dtype == "fp16":
+        return x.astype(np.float16).astype(f32)
+    if dtype == "bf16":
+        u = np.ascontiguousarray(x, f32).view(np.uint32).astype(np.uint64)
+        u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+        return u.astype(np.uint32).view(f32).reshape(x.shape)
+    if dtype == "fp32":
+        return x
+    raise ValueError(dtype)
+
+
+def sage_attention_head(Q, K, V, causal=False, mode="int4_fp8", sm_scale=None, gmap="g950",
+                        bq=BQ_SMOOTH, bkv=BKV_ACC, out_dtype="bf16", q_blocks=None, **kw):
+    """Algorithm 1 for one (batch, head); `q_blocks` restricts the outer loop to some
+    smoothing blocks (rows of the others are left zero)."""
+    pro = quantize_head(Q, K, V, mode, sm_scale, gmap, bq, **kw)
+    N, d = Q.shape
+    out = np.zeros((N, d), f32)
+    nblk = (N + bq - 1) // bq
+    for i in (range(nblk) if q_blocks is None else q_blocks):
+        rows = slice(i * bq, min((i + 1) * bq, N))
+        out[rows] = attention_rows(pro, rows, causal, bkv, out_dtype)
+    return out, pro
+
+
+def sage_attention(q, k, v, causal=False, mode="int4_fp8", sm_scale=None, gmap="g950",
+                   bq=BQ_SMOOTH, bkv=BKV_ACC, out_dtype="bf16"):
+    """Batched form: q [B, H, N, d], k and v [B, H_kv, N, d]; query head h reads KV head
+    h // (H / H_kv).  Returns [B, H, N, d] float32 (values rounded to out_dtype)."""
+    B, H, N, d = q.shape
+    g = H // k.shape[1]
+    out = np.empty((B, H, N, d), f32)
+    for b in range(B):
+        for h in range(H):
+            out[b, h], _ = sage_attention_head(q[b, h], k[b, h // g], v[b, h // g], causal, mode,
+                                               sm_scale, gmap, bq, bkv, out_dtype)
+    return out
+
+
+# --------------------------------------------------------------------------- definition
+def ref_attn_fp64(Q, K, V, causal=False, sm_scale=None, rows=None):
+    """softmax(Q K^T * sm_scale) V in float64 (Sec. 2.1, first formula), one head;
+    `rows` restricts the queries."""
+    Q, K, V = (np.asarray(x, f64) for x in (Q, K, V))
+    N, d = Q.shape
+    if sm_scale is None:
+        sm_scale = 1.0 / np.sqrt(d)
+    ridx = np.arange(N) if rows is None else np.arange(N)[rows]
+    S = (Q[ridx] @ K.T) * sm_scale
+    if causal:
+        S = np.where(np.arange(N)[None, :] > ridx[:, None], -np.inf, S)
+    S = S - S.max(axis=1, keepdims=True)
+    P = np.exp(S)
+    return (P / P.sum(axis=1, keepdims=True)) @ V

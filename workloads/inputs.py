@@ -1,0 +1,138 @@
+"""Seeded synthetic Q, K, V with the shapes and outlier structure of the workloads this
+repository is measured on.
+
+Values are drawn in float32 with numpy's default_rng, rounded (nearest-even) to the 16-bit
+input type, and magnitudes below 2**-20 are flushed to zero so that column sums of up to
+2**17 tokens are exact in float64 in any order.  Arrays are returned as float32 holding
+exactly representable 16-bit values, laid out [B, H, N, d] (K, V: [B, H_kv, N, d]).
+Every (batch, head) slice is generated from its own seed, so a single head of a large
+configuration can be drawn without materialising the rest.
+"""
+from dataclasses import dataclass, replace
+import numpy as np
+
+
+@dataclass(frozen=True)
+class WorkloadSpec:
+    name: str
+    B: int
+    H: int
+    H_kv: int
+    N: int
+    d: int
+    dtype: str          # "fp16" | "bf16"
+    causal: bool
+    k_offset_std: float  # per-channel offset of K (shared by all tokens of a head)
+    q_offset_std: float  # per-channel offset of Q
+    n_outlier_ch: int    # channels of Q and K scaled by outlier_gain
+    outlier_gain: float
+    token_norm_max: float  # token-wise scale drawn log-uniformly from [1, token_norm_max]
+    config_id: int
+
+    def with_(self, **kw):
+        return replace(self, **kw)
+
+
+CONFIGS = {
+    # tiny case the CPU oracle finishes in seconds
+    "tiny": WorkloadSpec("tiny", 1, 2, 2, 256, 64, "fp16", False, 3.0, 1.0, 0, 1.0, 1.0, 1),
+    # language-model prefill shape; also the paper's kernel-benchmark shape (B=4, H=32)
+    "prefill4k": WorkloadSpec("prefill4k", 4, 32, 32, 4096, 128, "bf16", False, 3.0, 3.0, 4, 10.0, 1.0, 2),
+    "causal8k": WorkloadSpec("causal8k", 1, 32, 32, 8192, 128, "bf16", True, 3.0, 3.0, 4, 10.0, 1.0, 3),
+    "causal16k": WorkloadSpec("causal16k", 1, 32, 32, 16384, 128, "bf16", True, 3.0, 3.0, 4, 10.0, 1.0, 3),
+    "causal32k": WorkloadSpec("causal32k", 1, 32, 32, 32768, 128, "bf16", True, 3.0, 3.0, 4, 10.0, 1.0, 3),
+    # video-diffusion-like: ragged N, d=64, token norms vary
+    "video17k": WorkloadSpec("video17k", 2, 48, 48, 17776, 64, "bf16", False, 4.0, 4.0, 0, 1.0, 8.0, 4),
+    # long-context causal prefill with grouped KV heads (4 query heads per KV head)
+    "long128k": WorkloadSpec("long128k", 1, 32, 8, 131072, 128, "bf16", True, 3.0, 3.0, 0, 1.0, 1.0, 5),
+}
+
+
+def round_to_dtype(x, dtype):
+    """Round float32 values to the nearest fp16/bf16 value (ties to even), return float32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == "fp16":
+        return x.astype(np.float16).astype(np.float32)
+    if dtype == "bf16":
+        u = x.view(np.uint32).astype(np.uint64)
+        lsb = (u >> 16) & 1
+        u = (u + 0x7FFF + lsb) & 0xFFFF0000
+        return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+    raise ValueError(dtype)
+
+
+def _finish(x, dtype):
+    x = round_to_dtype(x, dtype)
+    x[np.abs(x) < 2.0 ** -20] = 0.0
+    return x
+
+
+def _seed(spec, seed, kind, b, h):
+    return np.random.SeedSequence([1000 * spec.config_id + seed, kind, b, h])
+
+
+def _qk_like(spec, rng, offset_std):
+    N, d = spec.N, spec.d
+    x = rng.standard_normal((N, d), dtype=np.float32)
+    if spec.token_norm_max > 1.0:
+        s = np.exp(rng.uniform(0.0, np.log(spec.token_norm_max), size=(N, 1))).astype(np.float32)
+        x *= s
+    if offset_std > 0:
+        x += (offset_std * rng.standard_normal((1, d))).astype(np.float32)
+    if spec.n_outlier_ch > 0:
+        ch = rng.choice(d, size=spec.n_outlier_ch, replace=False)
+        x[:, ch] *= np.float32(spec.outlier_gain)
+    return x
+
+
+def make_head(spec, which, b, h, seed=0):
+    """One [N, d] slice: which in {"q","k","v"}; h is a query head for q, a KV head for k, v."""
+    kind = {"q": 0, "k": 1, "v": 2}[which]
+    rng = np.random.default_rng(_seed(spec, seed, kind, b, h))
+    if which == "q":
+        x = _qk_like(spec, rng, spec.q_offset_std)
+    elif which == "k":
+        x = _qk_like(spec, rng, spec.k_offset_std)
+    else:
+        x = rng.standard_normal((spec.N, spec.d), dtype=np.float32)
+    return _finish(x, spec.dtype)
+
+
+def make_inputs(spec, seed=0, heads=None):
+    """Full tensors (or only the listed query heads `heads`, with their KV heads).
+
+    Returns dict(q=[B,H',N,d], k=[B,Hkv',N,d], v=..., q_heads=[...], kv_heads=[...]).
+    """
+    if isinstance(spec, str):
+        spec = CONFIGS[spec]
+    g = spec.H // spec.H_kv
+    q_heads = list(range(spec.H)) if heads is None else list(heads)
+    kv_heads = sorted({h // g for h in q_heads})
+    q = np.empty((spec.B, len(q_heads), spec.N, spec.d), np.float32)
+    k = np.empty((spec.B, len(kv_heads), spec.N, spec.d), np.float32)
+    v = np.empty_like(k)
+    for b in range(spec.B):
+        for i, h in enumerate(q_heads):
+            q[b, i] = make_head(spec, "q", b, h, seed)
+        for i, h in enumerate(kv_heads):
+            k[b, i] = make_head(spec, "k", b, h, seed)
+            v[b, i] = make_head(spec, "v", b, h, seed)
+    return dict(q=q, k=k, v=v, q_heads=q_heads, kv_heads=kv_heads, spec=spec)
+
+
+def flops(spec):
+    """Operation count used for TOPS: 4*B*H*N^2*d, halved under a causal mask."""
+    ops = 4.0 * spec.B * spec.H * float(spec.N) ** 2 * spec.d
+    return ops / 2 if spec.causal else ops
+
+
+def to_torch(x, dtype, device="cpu"):
+    """float32 numpy array of exactly representable values -> torch tensor of the 16-bit type."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    td = {"fp16": torch.float16, "bf16": torch.bfloat16}[dtype]
+    return t.to(device=device).to(td)
+
+
+def from_torch(t):
+    return t.detach().to("cpu").float().numpy()
