@@ -1,0 +1,135 @@
+/*
+ * sage_attn.h - C ABI of the gfx950 (MI355X) quantized attention forward pass.
+ *
+ * The library computes O = softmax(Q K^T * sm_scale) V per (batch, head) the way
+ * SageAttention2 (arXiv 2411.10958) does: K is smoothed by its per-channel token mean and Q
+ * by its per-block mean with the Delta-S bias added back (Sec. 3.1, Eq. 2), Q and K are
+ * quantized to INT4 (or INT8) codes with one scale per fine-grained token group (Sec. 3.2),
+ * P~ and V are quantized to FP8 E4M3 (Sec. 3.3) and P~V is accumulated in two levels
+ * (Sec. 3.4); the whole loop is Algorithm 1.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library never frees or
+ *     keeps them.  q and out are contiguous [B, H, N, d]; k and v are contiguous
+ *     [B, H_kv, N, d]; elements are 16-bit (fp16 or bf16, see dtype).  Query head h reads KV
+ *     head h / (H / H_kv).  N_q = N_kv = N (prefill).
+ *   - d is 64 or 128; mode and dtype take the enum values below; H must be a multiple of H_kv.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream)
+ *     and the call returns without synchronising.  Kernels of one call are ordered on that
+ *     stream; two calls that share a workspace must be ordered by the caller.
+ *   - Every function returns a status (0 = SAGE_OK).  Argument errors are found on the host
+ *     before anything is launched; nothing throws or aborts.
+ *   - Numerical edge cases are defined, not errors: an all-zero quantization group has scale 0
+ *     and codes 0; N need not be a multiple of any tile (padded keys are masked, padded
+ *     queries are not written); N >= 1.
+ */
+#ifndef SAGE_ATTN_H
+#define SAGE_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  SAGE_OK = 0,
+  SAGE_ERR_INVALID_ARG = -1,  /* null pointer, non-positive size, H % H_kv != 0 */
+  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode or dtype */
+  SAGE_ERR_WORKSPACE = -3,    /* workspace missing or smaller than sage_attn_workspace_bytes() */
+  SAGE_ERR_HIP = -4           /* a HIP call or launch failed (the HIP error is cleared) */
+};
+
+/* SageAttn2-4b: INT4 Q,K (Q and K smoothed); SageAttn2-8b: INT8 Q,K (only K smoothed).
+   Both use FP8 E4M3 P~ and V (paper, table "Two kernel implementations"). */
+enum { SAGE_MODE_INT4_FP8 = 0, SAGE_MODE_INT8_FP8 = 1 };
+enum { SAGE_DT_FP16 = 0, SAGE_DT_BF16 = 1 };
+
+/* Numerical block sizes of Algorithm 1 as this library fixes them. */
+#define SAGE_BQ_SMOOTH 128 /* tokens per Q smoothing block (b_q) */
+#define SAGE_BKV_ACC 64    /* keys per level-1 accumulation block (b_kv, Sec. 3.4) */
+/* Quantization groups (Sec. 3.2 redefined for the gfx950 MFMA accumulator layout: the
+   tokens whose products land in one lane): queries {2n, 2n+1}; keys in runs of 16. */
+#define SAGE_Q_GROUP 2
+#define SAGE_K_GROUP 16
+
+typedef struct sage_attn_args {
+  const void* q;          /* device, [B, H, N, d] */
+  const void* k;          /* device, [B, H_kv, N, d] */
+  const void* v;          /* device, [B, H_kv, N, d] */
+  void* out;              /* device, [B, H, N, d], written */
+  int B, H, H_kv, N, d;
+  int causal;             /* 0: every key visible; 1: key t visible to query r iff t <= r */
+  float sm_scale;         /* <= 0 means 1/sqrt(d) */
+  int mode;               /* SAGE_MODE_* */
+  int dtype;              /* SAGE_DT_* : type of q, k, v and out */
+  void* workspace;        /* device scratch of >= sage_attn_workspace_bytes(); 256-byte aligned */
+  size_t workspace_bytes;
+  void* stream;           /* hipStream_t, NULL = default stream */
+} sage_attn_args;
+
+/* Bytes of device scratch one call needs for these shapes (codes, scales, means, Delta-S).
+   Depends only on B, H, H_kv, N, d, mode.  Returns 0 if those are invalid. */
+size_t sage_attn_workspace_bytes(const sage_attn_args* args);
+
+/* The whole forward pass of Algorithm 1: preprocessing (smoothing, Delta-S, quantization;
+   Sec. 3.1-3.3) followed by the fused attention kernel (inner loop and epilogue). */
+int sage_attn_fwd_ex(const sage_attn_args* args);
+
+/* The two halves of sage_attn_fwd_ex, for timing them apart the way the paper's kernel
+   benchmark does (Appendix "Kernel Benchmark Setup" times the attention kernel on already
+   quantized operands).  sage_attn_core reads what sage_attn_prologue left in the workspace
+   for the same args; q, k, v are not touched by it. */
+int sage_attn_prologue(const sage_attn_args* args);
+int sage_attn_core(const sage_attn_args* args);
+
+/* Convenience form named by the problem statement (Sec. 2.1: O = softmax(QK^T/sqrt(d))V):
+   bf16 tensors, H_kv = H, default stream, and a workspace the library allocates lazily with
+   hipMalloc, grows when needed and keeps until sage_attn_release().  Not thread-safe. */
+int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int H, int N,
+                  int d, int causal, float sm_scale, int mode);
+void sage_attn_release(void);
+
+/* Output of the preprocessing stage in plain ("logical") layouts, for checking it bit by bit.
+   All pointers are device buffers the caller allocates; a NULL member is skipped.
+     q_codes [B,H,N,d] int8       codes of gamma(Q) (int4 mode) or Q (int8 mode), Sec. 3.2
+     k_codes [B,H_kv,N,d] int8    codes of gamma(K)
+     v_codes [B,H_kv,N,d] uint8   E4M3 codes of V / delta_V, Sec. 3.3
+     q_scale [B,H,ceil(N/2)] f32  delta_Q per query group
+     k_scale [B,H_kv,ceil(N/16)] f32
+     v_scale [B,H_kv,d] f32       delta_V per channel
+     k_mean  [B,H_kv,d] f32       mean(K) over tokens (Eq. 2)
+     q_mean  [B,H,ceil(N/128),d] f32   block means of Q (int4 mode only, else untouched)
+     delta_s [B,H,ceil(N/128),N] f32   kappa * <q_mean_i, gamma(K)_t>, kappa = sm_scale*log2(e)
+                                       (int4 mode only, else untouched) */
+typedef struct sage_quant_out {
+  int8_t* q_codes;
+  int8_t* k_codes;
+  uint8_t* v_codes;
+  float* q_scale;
+  float* k_scale;
+  float* v_scale;
+  float* k_mean;
+  float* q_mean;
+  float* delta_s;
+} sage_quant_out;
+
+/* Runs the preprocessing of Algorithm 1 (as sage_attn_prologue) and then copies its results
+   out of the kernel-private packed workspace layout into `out`. */
+int sage_attn_quant(const sage_attn_args* args, const sage_quant_out* out);
+
+/* Integer accumulators of the score product (Algorithm 1, Matmul(Q^_i, K^_j^T)) for one
+   128-query tile and one 64-key block, through the same MFMA device code as the attention
+   kernel.  Needs a workspace filled by sage_attn_prologue / sage_attn_quant for `args`.
+   out_acc: device, [128][64] int32, row = query 128*q_tile + r, column = key 64*kv_block + t
+   (positions beyond N hold products of zero codes). */
+int sage_attn_debug_qk(const sage_attn_args* args, int b, int h, int q_tile, int kv_block,
+                       int32_t* out_acc);
+
+const char* sage_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAGE_ATTN_H */

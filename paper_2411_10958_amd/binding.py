@@ -1,0 +1,199 @@
+"""ctypes binding of libsageattn.so: argument marshalling only.
+
+Every function here has the name and meaning of the C entry point it calls (see
+include/sage_attn.h).  Tensors are torch tensors on the GPU; their device pointers are passed
+through untouched.  There is no fallback: if the library cannot be loaded, every call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+SAGE_MODE_INT4_FP8, SAGE_MODE_INT8_FP8 = 0, 1
+SAGE_DT_FP16, SAGE_DT_BF16 = 0, 1
+_MODES = {"int4_fp8": 0, "int8_fp8": 1, 0: 0, 1: 1}
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class SageError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({sage_status_string(status)})")
+
+
+class sage_attn_args(ctypes.Structure):
+    _fields_ = [("q", ctypes.c_void_p), ("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("out", ctypes.c_void_p),
+                ("B", ctypes.c_int), ("H", ctypes.c_int), ("H_kv", ctypes.c_int),
+                ("N", ctypes.c_int), ("d", ctypes.c_int),
+                ("causal", ctypes.c_int), ("sm_scale", ctypes.c_float),
+                ("mode", ctypes.c_int), ("dtype", ctypes.c_int),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("stream", ctypes.c_void_p)]
+
+
+class sage_quant_out(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("q_codes", "k_codes", "v_codes", "q_scale", "k_scale",
+                                              "v_scale", "k_mean", "q_mean", "delta_s")]
+
+
+def lib_path():
+    return os.path.join(_PKG, "libsageattn.so")
+
+
+def load_library():
+    """Loads libsageattn.so from the package directory (built by paper_2411_10958_amd.build)."""
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise FileNotFoundError(f"{path} is missing: run `python -m paper_2411_10958_amd.build` "
+                                    "(or __graft_entry__.build()) first")
+        lib = ctypes.CDLL(path)
+        P = ctypes.POINTER
+        lib.sage_attn_workspace_bytes.restype = ctypes.c_size_t
+        lib.sage_attn_workspace_bytes.argtypes = [P(sage_attn_args)]
+        for name in ("sage_attn_fwd_ex", "sage_attn_prologue", "sage_attn_core"):
+            getattr(lib, name).restype = ctypes.c_int
+            getattr(lib, name).argtypes = [P(sage_attn_args)]
+        lib.sage_attn_fwd.restype = ctypes.c_int
+        lib.sage_attn_fwd.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 5 + [ctypes.c_float, ctypes.c_int]
+        lib.sage_attn_release.restype = None
+        lib.sage_attn_quant.restype = ctypes.c_int
+        lib.sage_attn_quant.argtypes = [P(sage_attn_args), P(sage_quant_out)]
+        lib.sage_attn_debug_qk.restype = ctypes.c_int
+        lib.sage_attn_debug_qk.argtypes = [P(sage_attn_args)] + [ctypes.c_int] * 4 + [ctypes.c_void_p]
+        lib.sage_status_string.restype = ctypes.c_char_p
+        lib.sage_status_string.argtypes = [ctypes.c_int]
+        _LIB = lib
+    return _LIB
+
+
+def sage_status_string(status):
+    return load_library().sage_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != 0:
+        raise SageError(status, where)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.bfloat16:
+        return SAGE_DT_BF16
+    if t.dtype == torch.float16:
+        return SAGE_DT_FP16
+    raise TypeError(f"q, k, v must be float16 or bfloat16, got {t.dtype}")
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None):
+    """Fills a sage_attn_args from torch tensors q [B,H,N,d], k/v [B,H_kv,N,d] (contiguous, on the
+    GPU).  `workspace` is a uint8 GPU tensor (or None); `stream` a torch.cuda.Stream (None = the
+    current one)."""
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        if not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous 4-D GPU tensor")
+    if k.shape != v.shape or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("k and v must share shape; q, k, v must share dtype")
+    B, H, N, d = q.shape
+    if k.shape[0] != B or k.shape[2] != N or k.shape[3] != d:
+        raise ValueError("k/v shape does not match q")
+    if out is not None and (out.shape != q.shape or out.dtype != q.dtype or not out.is_contiguous()):
+        raise ValueError("out must look like q")
+    a = sage_attn_args()
+    a.q, a.k, a.v, a.out = q.data_ptr(), k.data_ptr(), v.data_ptr(), (out.data_ptr() if out is not None else 0)
+    a.B, a.H, a.H_kv, a.N, a.d = B, H, k.shape[1], N, d
+    a.causal, a.sm_scale, a.mode, a.dtype = int(bool(causal)), float(sm_scale), _MODES[mode], _dtype_code(q)
+    if workspace is not None:
+        a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    else:
+        a.workspace, a.workspace_bytes = 0, 0
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    a.stream = s.cuda_stream
+    return a
+
+
+def sage_attn_workspace_bytes(args):
+    return int(load_library().sage_attn_workspace_bytes(ctypes.byref(args)))
+
+
+def _alloc_workspace(args, device):
+    need = sage_attn_workspace_bytes(args)
+    if need == 0:
+        raise SageError(load_library().sage_attn_prologue(ctypes.byref(args)) or -1, "sage_attn_workspace_bytes")
+    ws = torch.empty(need, dtype=torch.uint8, device=device)
+    args.workspace, args.workspace_bytes = ws.data_ptr(), need
+    return ws
+
+
+def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None):
+    """Whole forward pass.  Returns `out` (allocated if not given)."""
+    if out is None:
+        out = torch.empty_like(q)
+    a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream)
+    keep = _alloc_workspace(a, q.device) if workspace is None else workspace
+    _check(load_library().sage_attn_fwd_ex(ctypes.byref(a)), "sage_attn_fwd_ex")
+    del keep  # torch's caching allocator keeps the block alive for work already queued on this stream
+    return out
+
+
+def sage_attn_prologue(args):
+    _check(load_library().sage_attn_prologue(ctypes.byref(args)), "sage_attn_prologue")
+
+
+def sage_attn_core(args):
+    _check(load_library().sage_attn_core(ctypes.byref(args)), "sage_attn_core")
+
+
+def sage_attn_fwd(q, k, v, out, causal=False, sm_scale=0.0, mode="int4_fp8"):
+    """The plain C signature: bf16, H_kv == H, default stream, library-owned workspace."""
+    B, H, N, d = q.shape
+    _check(load_library().sage_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, N, d, int(bool(causal)),
+                                         float(sm_scale), _MODES[mode]), "sage_attn_fwd")
+    return out
+
+
+def sage_attn_release():
+    load_library().sage_attn_release()
+
+
+def sage_attn_quant(q, k, v, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, want=None):
+    """Preprocessing only; returns (dict of torch tensors in plain layouts, args, workspace)."""
+    a = make_args(q, k, v, None, causal, sm_scale, mode, workspace)
+    ws = _alloc_workspace(a, q.device) if workspace is None else workspace
+    B, H, N, d = q.shape
+    Hkv = k.shape[1]
+    dev = q.device
+    int4 = _MODES[mode] == 0
+    nqb = (N + 127) // 128
+    bufs = dict(
+        q_codes=torch.empty((B, H, N, d), dtype=torch.int8, device=dev),
+        k_codes=torch.empty((B, Hkv, N, d), dtype=torch.int8, device=dev),
+        v_codes=torch.empty((B, Hkv, N, d), dtype=torch.uint8, device=dev),
+        q_scale=torch.empty((B, H, (N + 1) // 2), dtype=torch.float32, device=dev),
+        k_scale=torch.empty((B, Hkv, (N + 15) // 16), dtype=torch.float32, device=dev),
+        v_scale=torch.empty((B, Hkv, d), dtype=torch.float32, device=dev),
+        k_mean=torch.empty((B, Hkv, d), dtype=torch.float32, device=dev),
+    )
+    if int4:
+        bufs["q_mean"] = torch.empty((B, H, nqb, d), dtype=torch.float32, device=dev)
+        bufs["delta_s"] = torch.empty((B, H, nqb, N), dtype=torch.float32, device=dev)
+    if want is not None:
+        bufs = {n: t for n, t in bufs.items() if n in want}
+    o = sage_quant_out()
+    for n, _ in sage_quant_out._fields_:
+        setattr(o, n, bufs[n].data_ptr() if n in bufs else 0)
+    _check(load_library().sage_attn_quant(ctypes.byref(a), ctypes.byref(o)), "sage_attn_quant")
+    return bufs, a, ws
+
+
+def sage_attn_debug_qk(args, b, h, q_tile, kv_block, device="cuda"):
+    out = torch.empty((128, 64), dtype=torch.int32, device=device)
+    _check(load_library().sage_attn_debug_qk(ctypes.byref(args), b, h, q_tile, kv_block, _ptr(out)), "sage_attn_debug_qk")
+    return out

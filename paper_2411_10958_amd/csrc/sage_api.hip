@@ -1,0 +1,157 @@
+// C ABI of libsageattn (declared in include/sage_attn.h): argument validation, workspace map,
+// kernel sequencing.  Host code only; no torch types.
+#include "sage_attn.h"
+#include "sage_common.h"
+
+#include <cmath>
+
+namespace {
+
+using namespace sage;
+
+int validate(const sage_attn_args* a, Dims* D, bool need_io) {
+  if (!a) return SAGE_ERR_INVALID_ARG;
+  if (a->B <= 0 || a->H <= 0 || a->H_kv <= 0 || a->N <= 0 || a->d <= 0) return SAGE_ERR_INVALID_ARG;
+  if (a->H % a->H_kv != 0) return SAGE_ERR_INVALID_ARG;
+  if (a->d != 64 && a->d != 128) return SAGE_ERR_UNSUPPORTED;
+  if (a->mode != SAGE_MODE_INT4_FP8 && a->mode != SAGE_MODE_INT8_FP8) return SAGE_ERR_UNSUPPORTED;
+  if (a->dtype != SAGE_DT_FP16 && a->dtype != SAGE_DT_BF16) return SAGE_ERR_UNSUPPORTED;
+  if (need_io && (!a->q || !a->k || !a->v || !a->out)) return SAGE_ERR_INVALID_ARG;
+  // grid limits of the launches below (y dimension <= 65535, tile count fits an int)
+  if ((long long)a->B * a->H > 65535) return SAGE_ERR_UNSUPPORTED;
+  const long long nQb = (a->N + BQ - 1) / BQ, nKb = (a->N + BKV - 1) / BKV;
+  if ((long long)a->B * a->H * nQb > (1LL << 30)) return SAGE_ERR_UNSUPPORTED;
+  D->B = a->B; D->H = a->H; D->Hkv = a->H_kv; D->N = a->N; D->d = a->d;
+  D->nQb = (int)nQb; D->nKb = (int)nKb;
+  D->causal = a->causal != 0;
+  D->int4 = a->mode == SAGE_MODE_INT4_FP8;
+  D->bf16 = a->dtype == SAGE_DT_BF16;
+  const float sm = a->sm_scale > 0.0f ? a->sm_scale : (float)(1.0 / std::sqrt((double)a->d));
+  D->kappa = sm * LOG2E;   // one FP32 rounding of the product of two FP32 values
+  return SAGE_OK;
+}
+
+int check_workspace(const sage_attn_args* a, const Workspace& w) {
+  if (!a->workspace || a->workspace_bytes < w.total) return SAGE_ERR_WORKSPACE;
+  if (((uintptr_t)a->workspace & 255u) != 0) return SAGE_ERR_WORKSPACE;
+  return SAGE_OK;
+}
+
+int hip_status(hipError_t e) {
+  if (e == hipSuccess) return SAGE_OK;
+  (void)hipGetLastError();
+  return SAGE_ERR_HIP;
+}
+
+void* g_ws = nullptr;      // workspace of the convenience entry point
+size_t g_ws_bytes = 0;
+
+}  // namespace
+
+extern "C" {
+
+size_t sage_attn_workspace_bytes(const sage_attn_args* args) {
+  Dims D;
+  if (validate(args, &D, false) != SAGE_OK) return 0;
+  return make_workspace(D).total;
+}
+
+int sage_attn_prologue(const sage_attn_args* args) {
+  Dims D;
+  int st = validate(args, &D, true);
+  if (st != SAGE_OK) return st;
+  const Workspace w = make_workspace(D);
+  if ((st = check_workspace(args, w)) != SAGE_OK) return st;
+  const Ptrs P = make_ptrs(args->q, args->k, args->v, args->out, args->workspace, w);
+  return hip_status(launch_prologue(D, P, (hipStream_t)args->stream));
+}
+
+int sage_attn_core(const sage_attn_args* args) {
+  Dims D;
+  int st = validate(args, &D, true);
+  if (st != SAGE_OK) return st;
+  const Workspace w = make_workspace(D);
+  if ((st = check_workspace(args, w)) != SAGE_OK) return st;
+  const Ptrs P = make_ptrs(args->q, args->k, args->v, args->out, args->workspace, w);
+  return hip_status(launch_attention(D, P, (hipStream_t)args->stream));
+}
+
+int sage_attn_fwd_ex(const sage_attn_args* args) {
+  const int st = sage_attn_prologue(args);
+  if (st != SAGE_OK) return st;
+  return sage_attn_core(args);
+}
+
+int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int H, int N, int d,
+                  int causal, float sm_scale, int mode) {
+  sage_attn_args a;
+  a.q = q; a.k = k; a.v = v; a.out = out;
+  a.B = B; a.H = H; a.H_kv = H; a.N = N; a.d = d;
+  a.causal = causal; a.sm_scale = sm_scale; a.mode = mode; a.dtype = SAGE_DT_BF16;
+  a.workspace = nullptr; a.workspace_bytes = 0; a.stream = nullptr;
+  const size_t need = sage_attn_workspace_bytes(&a);
+  if (need == 0) {
+    Dims D;
+    return validate(&a, &D, true);
+  }
+  if (need > g_ws_bytes) {
+    if (g_ws) {
+      if (hipDeviceSynchronize() != hipSuccess) return hip_status(hipErrorUnknown);
+      (void)hipFree(g_ws);
+      g_ws = nullptr; g_ws_bytes = 0;
+    }
+    if (hipMalloc(&g_ws, need) != hipSuccess) { g_ws = nullptr; return hip_status(hipErrorOutOfMemory); }
+    g_ws_bytes = need;
+  }
+  a.workspace = g_ws; a.workspace_bytes = g_ws_bytes;
+  return sage_attn_fwd_ex(&a);
+}
+
+void sage_attn_release(void) {
+  if (g_ws) {
+    (void)hipDeviceSynchronize();
+    (void)hipFree(g_ws);
+    g_ws = nullptr; g_ws_bytes = 0;
+  }
+}
+
+int sage_attn_quant(const sage_attn_args* args, const sage_quant_out* out) {
+  if (!out) return SAGE_ERR_INVALID_ARG;
+  Dims D;
+  int st = validate(args, &D, false);
+  if (st != SAGE_OK) return st;
+  if (!args->q || !args->k || !args->v) return SAGE_ERR_INVALID_ARG;
+  if ((long long)D.B * D.H * D.nQb > 65535) return SAGE_ERR_UNSUPPORTED;  // grid limit of the copy-out kernels
+  const Workspace w = make_workspace(D);
+  if ((st = check_workspace(args, w)) != SAGE_OK) return st;
+  const Ptrs P = make_ptrs(args->q, args->k, args->v, args->out, args->workspace, w);
+  if ((st = hip_status(launch_prologue(D, P, (hipStream_t)args->stream))) != SAGE_OK) return st;
+  return hip_status(launch_unpack(D, P, out, (hipStream_t)args->stream));
+}
+
+int sage_attn_debug_qk(const sage_attn_args* args, int b, int h, int q_tile, int kv_block,
+                       int32_t* out_acc) {
+  Dims D;
+  int st = validate(args, &D, false);
+  if (st != SAGE_OK) return st;
+  if (!out_acc || b < 0 || b >= D.B || h < 0 || h >= D.H || q_tile < 0 || q_tile >= D.nQb ||
+      kv_block < 0 || kv_block >= D.nKb)
+    return SAGE_ERR_INVALID_ARG;
+  const Workspace w = make_workspace(D);
+  if ((st = check_workspace(args, w)) != SAGE_OK) return st;
+  const Ptrs P = make_ptrs(args->q, args->k, args->v, args->out, args->workspace, w);
+  return hip_status(launch_debug_qk(D, P, b, h, q_tile, kv_block, out_acc, (hipStream_t)args->stream));
+}
+
+const char* sage_status_string(int status) {
+  switch (status) {
+    case SAGE_OK: return "ok";
+    case SAGE_ERR_INVALID_ARG: return "invalid argument";
+    case SAGE_ERR_UNSUPPORTED: return "unsupported head dimension, mode, dtype or size";
+    case SAGE_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+    case SAGE_ERR_HIP: return "HIP call or kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

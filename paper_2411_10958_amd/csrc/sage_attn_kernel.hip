@@ -1,0 +1,314 @@
+// Fused quantized attention kernel for gfx950: the inner loop and epilogue of the paper's
+// Algorithm 1.  One workgroup (4 wavefronts) owns one 128-query smoothing block of one
+// (batch, head); each wavefront owns 32 queries and walks the 64-key blocks.
+//
+// The score tile is computed transposed, S^T = K^ Q^^T, with v_mfma_i32_32x32x32_i8: rows are
+// keys, columns are queries, so a lane holds ONE query (column lane%32) and, thanks to the row
+// permutation baked into the packed K^ layout, 16 consecutive keys per 32-key tile.  Row max
+// and row sum are therefore lane-local plus one exchange between the two lane halves, one
+// lane needs one delta_Q and one delta_K per tile (Sec. 3.2's per-thread principle on this
+// accumulator layout), and the FP8 P~ registers are directly the B operand of
+// O^T = V^^T P~^T (v_mfma_f32_32x32x64_f8f6f4, K = 64 = one accumulation block), which is
+// issued with a zero accumulator: R is the per-block FP32 buffer of Sec. 3.4 and is folded
+// into the running O with one FP32 fma per element.
+#include "sage_common.h"
+
+namespace sage {
+
+struct AttnParams {
+  const int8_t* q_codes;
+  const int8_t* k_codes;
+  const uint8_t* v_codes;
+  const float* q_scale;
+  const float* k_scale;
+  const float* v_scale;
+  const float* delta_s;
+  void* out;
+  int H, Hkv, N, nQb, nKb, total_tiles;
+  float kappa;
+};
+
+// LDS stage: K^ block, V^ block, then 64 Delta-S floats and 4 key-group scales.
+template <int D> struct Stage {
+  static constexpr int K_CHUNKS = D * BKV / 16;        // 16-byte chunks
+  static constexpr int V_CHUNKS = D * BKV / 16;
+  static constexpr int X_CHUNKS = 32;                  // 16 chunks Delta-S + 1 chunk scales (+pad)
+  static constexpr int CHUNKS = K_CHUNKS + V_CHUNKS + X_CHUNKS;
+};
+
+// Score accumulators of one wavefront: 2 key tiles x (32 keys x 32 queries), int32.
+// lds_k: this stage's K^ chunks; qreg: the wavefront's Q^ B-operands (one per 32-channel step).
+template <int D>
+__device__ inline void qk_tile(const v4i* __restrict__ lds_k, const v4i (&qreg)[D / 32], int lane,
+                               v16i (&acc)[2]) {
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[kt][v] = 0;
+  }
+#pragma unroll
+  for (int s = 0; s < D / 32; ++s) {
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      const v4i a = lds_k[(s * 2 + kt) * 64 + lane];
+      acc[kt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qreg[s], acc[kt], 0, 0, 0);
+    }
+  }
+}
+
+template <int D, bool INT4, bool CAUSAL, bool BF16>
+__global__ void __launch_bounds__(256, 2) k_attn_fwd(const AttnParams p) {
+  constexpr int KS = D / 32;   // 32-channel steps of the score product
+  constexpr int CT = D / 32;   // 32-channel tiles of the output
+  using St = Stage<D>;
+  __shared__ v4i lds[2][St::CHUNKS];
+
+  // XCD-aware tile order: consecutive workgroup ids land on different XCDs (8 of them), so
+  // give every XCD a contiguous range of tiles - tiles of one head then share one L2.
+  const int per_xcd = (p.total_tiles + 7) / 8;
+  const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (tile >= p.total_tiles) return;
+  const int bh = tile / p.nQb;
+  const int qb = CAUSAL ? p.nQb - 1 - tile % p.nQb : tile % p.nQb;   // heavy tiles first
+  const int b = bh / p.H, h = bh % p.H;
+  const size_t bhkv = (size_t)b * p.Hkv + h / (p.H / p.Hkv);
+
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int n = lane & 31, half = lane >> 5;
+  const int q_lo = qb * BQ + w * WQ;          // first query of this wavefront
+  const int query = q_lo + n;
+
+  // ---- per-workgroup sources ----
+  const v4i* gk = reinterpret_cast<const v4i*>(p.k_codes + bhkv * (size_t)p.nKb * BKV * D);
+  const v4i* gv = reinterpret_cast<const v4i*>(p.v_codes + bhkv * (size_t)p.nKb * BKV * D);
+  const v4i* gd = INT4 ? reinterpret_cast<const v4i*>(p.delta_s + ((size_t)bh * p.nQb + qb) * p.nKb * BKV) : nullptr;
+  const v4i* gs = reinterpret_cast<const v4i*>(p.k_scale + bhkv * (size_t)p.nKb * 4);
+
+  int nblk = p.nKb;
+  if (CAUSAL) nblk = min(nblk, (qb * BQ + BQ - 1) / BKV + 1);
+
+  // global -> register staging of one block: K^ and V^ chunks, Delta-S row piece, key scales
+  constexpr int CPT = St::K_CHUNKS / 256;     // chunks per thread per operand (2 or 1)
+  v4i rk[CPT], rv[CPT], rx;
+  auto fetch = [&](int j) {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      rk[i] = gk[(size_t)j * St::K_CHUNKS + i * 256 + t];
+      rv[i] = gv[(size_t)j * St::V_CHUNKS + i * 256 + t];
+    }
+    if (t < 16) {
+      if constexpr (INT4) rx = gd[j * 16 + t]; else rx = v4i{0, 0, 0, 0};
+    } else if (t == 16) {
+      rx = gs[j];
+    }
+  };
+  auto stash = [&](int stage) {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      lds[stage][i * 256 + t] = rk[i];
+      lds[stage][St::K_CHUNKS + i * 256 + t] = rv[i];
+    }
+    if (t <= 16) lds[stage][St::K_CHUNKS + St::V_CHUNKS + t] = rx;
+  };
+
+  // ---- this wavefront's Q^ operands and scale ----
+  v4i qreg[KS];
+  {
+    const v4i* gq = reinterpret_cast<const v4i*>(p.q_codes + (size_t)bh * p.nQb * BQ * D);
+    const int qtile = qb * (BQ / WQ) + w;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qreg[s] = gq[(size_t)(qtile * KS + s) * 64 + lane];
+  }
+  const float dq = p.q_scale[((size_t)bh * p.nQb + qb) * (BQ / QGROUP) + (w * WQ + n) / QGROUP];
+
+  v16f O[CT];
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) O[ct][v] = 0.0f;
+  }
+  float m_run = -INFINITY;   // running row max of the base-2 scores
+  float l_run = 0.0f;        // this lane's share of the running row sum of 448 * P~
+
+  fetch(0);
+  stash(0);
+  __syncthreads();
+
+  for (int j = 0; j < nblk; ++j) {
+    const int stage = j & 1;
+    if (j + 1 < nblk) fetch(j + 1);
+
+    const int key0 = j * BKV;
+    // a wavefront whose queries all precede this block has nothing visible in it
+    const bool active = !CAUSAL || key0 <= q_lo + WQ - 1;
+    if (active) {
+      const v4i* lk = lds[stage];
+      const v4i* lv = lds[stage] + St::K_CHUNKS;
+      const float* lx = reinterpret_cast<const float*>(lds[stage] + St::K_CHUNKS + St::V_CHUNKS);
+
+      v16i acc[2];
+      qk_tile<D>(lk, qreg, lane, acc);
+
+      // ---- dequantize, add Delta-S (Algorithm 1, score line), in base 2 ----
+      float S[2][16];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        const float dk = lx[64 + 2 * kt + half];
+        const float c = __fmul_rn(__fmul_rn(dq, dk), p.kappa);
+        if constexpr (INT4) {
+          const v4f* dsv = reinterpret_cast<const v4f*>(lx + 32 * kt + 16 * half);
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const v4f d4 = dsv[g];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[kt][4 * g + r] = __fmaf_rn((float)acc[kt][4 * g + r], c, d4[r]);
+          }
+        } else {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) S[kt][v] = __fmul_rn((float)acc[kt][v], c);
+        }
+      }
+      // ---- masks: causal diagonal and keys beyond N ----
+      const bool need_mask = (CAUSAL && key0 + BKV - 1 > q_lo) || (key0 + BKV > p.N);
+      if (need_mask) {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int key = key0 + 32 * kt + 16 * half + v;
+            if (key >= p.N || (CAUSAL && key > query)) S[kt][v] = -INFINITY;
+          }
+        }
+      }
+      // ---- online softmax (Eq. 1 / Algorithm 1) ----
+      float mx = S[0][0];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, S[kt][v]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // 2^-inf = 0 on the first block
+      const float m_sub = m_new - LOG2_448;                          // folds the *448 of Sec. 3.3
+      m_run = m_new;
+      float ls = 0.0f;
+      v8i pb;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float e[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            e[r] = __builtin_amdgcn_exp2f(S[kt][4 * g + r] - m_sub);   // = 448 * P~
+            ls += e[r];
+          }
+          int wd = 0;
+          wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[0], e[1], wd, false);
+          wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[2], e[3], wd, true);
+          pb[kt * 4 + g] = wd;
+        }
+      }
+      l_run = __fmaf_rn(alpha, l_run, ls);
+      // ---- level 1: R = P^ V^ over this block with a zero accumulator; level 2: O = alpha*O + R
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) {
+        v8i a;
+        const v4i a0 = lv[(ct * 2 + 0) * 64 + lane];
+        const v4i a1 = lv[(ct * 2 + 1) * 64 + lane];
+        a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
+        a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
+        v16f R;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) R[v] = 0.0f;
+        R = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, R, 0, 0, 0, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) O[ct][v] = __fmaf_rn(alpha, O[ct][v], R[v]);
+      }
+    }
+    if (j + 1 < nblk) stash(stage ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue (Algorithm 1 last line): O / l / 448 * delta_V; l_run already carries the 448
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (query < p.N) {
+    unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) + ((size_t)bh * p.N + query) * D;
+    const float* dv = p.v_scale + bhkv * D;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int c0 = 32 * ct + 8 * g + 4 * half;
+        const v4f sc = *reinterpret_cast<const v4f*>(dv + c0);
+        unsigned short o4[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o4[r] = store16<BF16>(__fmul_rn(__fdiv_rn(O[ct][4 * g + r], l_tot), sc[r]));
+        *reinterpret_cast<uint2*>(orow + c0) =
+            make_uint2((unsigned)o4[0] | ((unsigned)o4[1] << 16), (unsigned)o4[2] | ((unsigned)o4[3] << 16));
+      }
+    }
+  }
+}
+
+// Integer score accumulators of one (128-query tile, 64-key block) through qk_tile.
+template <int D>
+__global__ void __launch_bounds__(256) k_debug_qk(const int8_t* __restrict__ q_codes,
+                                                  const int8_t* __restrict__ k_codes, int q_tile,
+                                                  int kv_block, int32_t* __restrict__ out) {
+  __shared__ v4i lds[D * BKV / 16];
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6, n = lane & 31, half = lane >> 5;
+  const v4i* gk = reinterpret_cast<const v4i*>(k_codes) + (size_t)kv_block * (D * BKV / 16);
+  for (int i = t; i < D * BKV / 16; i += 256) lds[i] = gk[i];
+  __syncthreads();
+  v4i qreg[D / 32];
+  const v4i* gq = reinterpret_cast<const v4i*>(q_codes);
+#pragma unroll
+  for (int s = 0; s < D / 32; ++s) qreg[s] = gq[(size_t)((q_tile * (BQ / WQ) + w) * (D / 32) + s) * 64 + lane];
+  v16i acc[2];
+  qk_tile<D>(lds, qreg, lane, acc);
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) out[(w * WQ + n) * BKV + 32 * kt + 16 * half + v] = acc[kt][v];
+  }
+}
+
+template <int D, bool INT4, bool CAUSAL, bool BF16>
+static hipError_t launch_attention_t(const Dims& Dm, const Ptrs& P, hipStream_t s) {
+  AttnParams p;
+  p.q_codes = P.q_codes; p.k_codes = P.k_codes; p.v_codes = P.v_codes;
+  p.q_scale = P.q_scale; p.k_scale = P.k_scale; p.v_scale = P.v_scale; p.delta_s = P.delta_s;
+  p.out = P.out;
+  p.H = Dm.H; p.Hkv = Dm.Hkv; p.N = Dm.N; p.nQb = Dm.nQb; p.nKb = Dm.nKb;
+  p.total_tiles = Dm.B * Dm.H * Dm.nQb;
+  p.kappa = Dm.kappa;
+  const int grid = 8 * ((p.total_tiles + 7) / 8);
+  k_attn_fwd<D, INT4, CAUSAL, BF16><<<grid, 256, 0, s>>>(p);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention(const Dims& D, const Ptrs& P, hipStream_t s) {
+#define SAGE_ATT(DD, I4, CA, BF) return launch_attention_t<DD, I4, CA, BF>(D, P, s)
+#define SAGE_ATT_BF(DD, I4, CA) do { if (D.bf16) SAGE_ATT(DD, I4, CA, true); else SAGE_ATT(DD, I4, CA, false); } while (0)
+#define SAGE_ATT_CA(DD, I4) do { if (D.causal) SAGE_ATT_BF(DD, I4, true); else SAGE_ATT_BF(DD, I4, false); } while (0)
+  if (D.d == 128) { if (D.int4) SAGE_ATT_CA(128, true); else SAGE_ATT_CA(128, false); }
+  else            { if (D.int4) SAGE_ATT_CA(64, true); else SAGE_ATT_CA(64, false); }
+#undef SAGE_ATT_CA
+#undef SAGE_ATT_BF
+#undef SAGE_ATT
+}
+
+hipError_t launch_debug_qk(const Dims& D, const Ptrs& P, int b, int h, int q_tile, int kv_block,
+                           int32_t* out, hipStream_t s) {
+  const size_t bh = (size_t)b * D.H + h;
+  const size_t bhkv = (size_t)b * D.Hkv + h / (D.H / D.Hkv);
+  const int8_t* qc = P.q_codes + bh * (size_t)D.nQb * BQ * D.d;
+  const int8_t* kc = P.k_codes + bhkv * (size_t)D.nKb * BKV * D.d;
+  if (D.d == 128) k_debug_qk<128><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
+  else k_debug_qk<64><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
+  return hipGetLastError();
+}
+
+}  // namespace sage

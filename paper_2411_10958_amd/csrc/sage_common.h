@@ -1,0 +1,155 @@
+// Internal definitions shared by the HIP sources of libsageattn: problem dimensions, the
+// workspace map and the packed ("MFMA fragment order") layouts the preprocessing kernels
+// write and the attention kernel reads.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace sage {
+
+constexpr int BQ = 128;      // queries per workgroup tile = Q smoothing block (Algorithm 1, b_q)
+constexpr int BKV = 64;      // keys per block = level-1 accumulation block (b_kv)
+constexpr int WQ = 32;       // queries per wavefront (one 32x32 MFMA column tile)
+constexpr int QGROUP = 2;    // queries per quantization group
+constexpr int KGROUP = 16;   // keys per quantization group
+constexpr float E4M3_MAX = 448.0f;
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LOG2_448 = 8.807354922057604f;
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+struct Dims {
+  int B, H, Hkv, N, d;
+  int nQb;     // ceil(N / 128) query blocks
+  int nKb;     // ceil(N / 64) key blocks
+  int causal, int4, bf16;
+  float kappa; // fl32(sm_scale * log2 e)
+};
+
+// Workspace map (all offsets multiples of 256 bytes).
+//
+// Packed layouts (one "chunk" = 16 bytes = one lane's operand piece, 64 chunks = one
+// wavefront-wide ds_read_b128 / global load):
+//   q_codes: [B*H][N_q32 tiles of 32 queries][d/32 k-steps][64 lanes] chunks.  Lane l of
+//            k-step s holds query 32*tile + l%32, channels 32*s + 16*(l/32) + 0..15
+//            (the B operand of v_mfma_i32_32x32x32_i8).
+//   k_codes: [B*Hkv][nKb blocks][d/32 k-steps][2 key tiles][64 lanes] chunks.  Lane l holds
+//            MFMA row rho = l%32 and channels 32*s + 16*(l/32) + 0..15, where row
+//            rho = 8g + 4h + r carries key 32*tile + 16h + 4g + r of the block, so that an
+//            accumulator lane (half h) ends up with 16 consecutive keys.
+//   v_codes: [B*Hkv][nKb blocks][d/32 channel tiles][2 parts][64 lanes] chunks.  Lane l holds
+//            channel 32*ct + l%32 and the 16 keys 32*part + 16*(l/32) + 0..15 of the block
+//            (the A operand of v_mfma_f32_32x32x64_f8f6f4, key order matching the order in
+//            which a lane's P~ registers come out of the score tiles).
+//   delta_s: [B*H][nQb][nKb*64] float, zero beyond N.
+//   q_scale: [B*H][nQb*64] float;  k_scale: [B*Hkv][nKb*4] float.
+struct Workspace {
+  size_t k_sum, v_max, k_mean, v_scale, q_mean, q_scale, k_scale, q_codes, k_codes, v_codes,
+      delta_s, total;
+};
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+inline Workspace make_workspace(const Dims& D) {
+  Workspace w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+  const size_t BH = (size_t)D.B * D.H, BHkv = (size_t)D.B * D.Hkv;
+  w.k_sum = take(BHkv * D.d * sizeof(double));
+  w.v_max = take(BHkv * D.d * sizeof(unsigned));
+  w.k_mean = take(BHkv * D.d * sizeof(float));
+  w.v_scale = take(BHkv * D.d * sizeof(float));
+  w.q_mean = take(BH * D.nQb * D.d * sizeof(float));
+  w.q_scale = take(BH * D.nQb * (BQ / QGROUP) * sizeof(float));
+  w.k_scale = take(BHkv * D.nKb * (BKV / KGROUP) * sizeof(float));
+  w.q_codes = take(BH * D.nQb * BQ * D.d);
+  w.k_codes = take(BHkv * D.nKb * BKV * D.d);
+  w.v_codes = take(BHkv * D.nKb * BKV * D.d);
+  w.delta_s = take(D.int4 ? BH * D.nQb * D.nKb * BKV * sizeof(float) : 0);
+  w.total = off;
+  return w;
+}
+
+struct Ptrs {
+  const void *q, *k, *v;
+  void* out;
+  double* k_sum;
+  unsigned* v_max;
+  float *k_mean, *v_scale, *q_mean, *q_scale, *k_scale, *delta_s;
+  int8_t *q_codes, *k_codes;
+  uint8_t* v_codes;
+};
+
+inline Ptrs make_ptrs(const void* q, const void* k, const void* v, void* out, void* ws,
+                      const Workspace& w) {
+  char* b = (char*)ws;
+  Ptrs p;
+  p.q = q; p.k = k; p.v = v; p.out = out;
+  p.k_sum = (double*)(b + w.k_sum);
+  p.v_max = (unsigned*)(b + w.v_max);
+  p.k_mean = (float*)(b + w.k_mean);
+  p.v_scale = (float*)(b + w.v_scale);
+  p.q_mean = (float*)(b + w.q_mean);
+  p.q_scale = (float*)(b + w.q_scale);
+  p.k_scale = (float*)(b + w.k_scale);
+  p.q_codes = (int8_t*)(b + w.q_codes);
+  p.k_codes = (int8_t*)(b + w.k_codes);
+  p.v_codes = (uint8_t*)(b + w.v_codes);
+  p.delta_s = (float*)(b + w.delta_s);
+  return p;
+}
+
+// ---- packed-layout index helpers (byte offsets inside one (batch, head) slab) ----
+// q_codes: query n (0..nQb*128), channel c
+__host__ __device__ inline size_t q_code_off(int n, int c, int d) {
+  const int tile = n >> 5, col = n & 31, s = c >> 5, half = (c >> 4) & 1, byte = c & 15;
+  return ((size_t)(tile * (d >> 5) + s) * 64 + col + 32 * half) * 16 + byte;
+}
+// k_codes: key n, channel c
+__host__ __device__ inline size_t k_code_off(int n, int c, int d) {
+  const int blk = n >> 6, kt = (n >> 5) & 1, kk = n & 31;
+  const int h = kk >> 4, g = (kk >> 2) & 3, r = kk & 3, rho = 8 * g + 4 * h + r;
+  const int s = c >> 5, half = (c >> 4) & 1, byte = c & 15;
+  return ((size_t)((blk * (d >> 5) + s) * 2 + kt) * 64 + rho + 32 * half) * 16 + byte;
+}
+// v_codes: key n, channel c
+__host__ __device__ inline size_t v_code_off(int n, int c, int d) {
+  const int blk = n >> 6, part = (n >> 5) & 1, h = (n >> 4) & 1, byte = n & 15;
+  const int ct = c >> 5, ch = c & 31;
+  return ((size_t)((blk * (d >> 5) + ct) * 2 + part) * 64 + ch + 32 * h) * 16 + byte;
+}
+
+// ---- 16-bit input helpers ----
+__device__ inline float bf16_to_f32(unsigned short u) { return __uint_as_float((unsigned)u << 16); }
+__device__ inline float fp16_to_f32(unsigned short u) {
+  return (float)__builtin_bit_cast(_Float16, u);
+}
+template <bool BF16> __device__ inline float load16(unsigned short u) {
+  if constexpr (BF16) return bf16_to_f32(u); else return fp16_to_f32(u);
+}
+__device__ inline unsigned short f32_to_bf16_rne(float x) {
+  unsigned u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40);  // NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+__device__ inline unsigned short f32_to_fp16_rne(float x) {
+  return __builtin_bit_cast(unsigned short, (_Float16)x);
+}
+template <bool BF16> __device__ inline unsigned short store16(float x) {
+  if constexpr (BF16) return f32_to_bf16_rne(x); else return f32_to_fp16_rne(x);
+}
+
+// launchers (defined in the .hip files)
+hipError_t launch_prologue(const Dims& D, const Ptrs& P, hipStream_t s);
+hipError_t launch_attention(const Dims& D, const Ptrs& P, hipStream_t s);
+hipError_t launch_unpack(const Dims& D, const Ptrs& P, const void* quant_out, hipStream_t s);
+hipError_t launch_debug_qk(const Dims& D, const Ptrs& P, int b, int h, int q_tile, int kv_block,
+                           int32_t* out, hipStream_t s);
+
+}  // namespace sage

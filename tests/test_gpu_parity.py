@@ -1,0 +1,170 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on seeded inputs that span several tiles, ragged tails, both modes, both head dims, causal
+masks and grouped KV heads.
+
+Bars: codes, scales, means and int32 score accumulators bit-equal; Delta-S equal up to the
+last FP32 bit of a float64-accumulated value; outputs within 2e-3 max-abs after dividing by
+the row's L-inf norm and cosine >= 0.9999 (the tolerance the benchmark spec states for this path)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import sage_oracle as so
+
+pytestmark = pytest.mark.gpu
+
+OUT_TOL = 2e-3
+COS_TOL = 0.9999
+
+
+def _half_ulp16(x, dtype):
+    """Half the spacing of the 16-bit output format at |x| (fp16: 10 mantissa bits, bf16: 7)."""
+    mant = 10 if dtype == "fp16" else 7
+    ax = np.maximum(np.abs(x).astype(np.float64), 2.0 ** -14 if dtype == "fp16" else 2.0 ** -126)
+    return 0.5 * np.exp2(np.floor(np.log2(ax)) - mant)
+
+
+def check_output(got16, ref32, dtype):
+    """The stated bar applies to the FP32 result; the kernel then rounds once to the 16-bit
+    output type, which can move an element by at most half a unit of that format.  So each
+    element must lie within OUT_TOL * ||ref row||_inf + half an output ulp of the oracle's
+    unrounded FP32 value, and the flattened cosine must reach COS_TOL."""
+    ref = ref32.astype(np.float64).reshape(-1, ref32.shape[-1])
+    got = got16.astype(np.float64).reshape(-1, ref32.shape[-1])
+    linf = np.abs(ref).max(axis=1, keepdims=True)
+    allowed = OUT_TOL * linf + _half_ulp16(ref, dtype)
+    excess = np.abs(got - ref) - allowed
+    worst = float((np.abs(got - ref) / np.where(linf > 0, linf, 1)).max())
+    cos = wl.cos_sim(got, ref)
+    print(f"  max-abs/row-Linf {worst:.3e} (bar {OUT_TOL:g} + half an output ulp)  cos {cos:.7f}", flush=True)
+    assert np.isfinite(got).all()
+    assert excess.max() <= 0, f"{(excess > 0).sum()} elements beyond tolerance, worst excess {excess.max():.3e}"
+    assert cos >= COS_TOL
+
+
+def _pa():
+    import paper_2411_10958_amd as pa
+    pa.load_library()
+    return pa
+
+
+def _spec(N, d, dtype="bf16", H=2, Hkv=2, B=1, causal=False, outliers=0, cfg=91):
+    return wl.WorkloadSpec(f"t{N}x{d}", B, H, Hkv, N, d, dtype, causal, 3.0, 1.5, outliers, 10.0, 1.0, cfg)
+
+
+def _gpu_inputs(spec, seed=0):
+    data = wl.make_inputs(spec, seed)
+    dev = torch.device("cuda:0")
+    return data, tuple(wl.to_torch(data[n], spec.dtype, dev) for n in "qkv")
+
+
+CASES = [
+    # N, d, dtype, H, Hkv, causal
+    (256, 64, "fp16", 2, 2, False),     # the tiny configuration
+    (256, 64, "fp16", 2, 2, True),
+    (250, 64, "fp16", 2, 2, False),     # ragged last tiles
+    (333, 128, "bf16", 2, 1, True),     # ragged + causal + grouped KV heads + d=128
+    (640, 128, "bf16", 4, 2, False),    # several Q blocks and 10 KV blocks
+    (1, 64, "bf16", 1, 1, True),        # degenerate: a single token
+    (17, 128, "fp16", 1, 1, False),     # shorter than one group-of-16 plus one
+]
+
+
+@pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("N,d,dtype,H,Hkv,causal", CASES)
+def test_prologue_bit_exact(N, d, dtype, H, Hkv, causal, mode):
+    pa = _pa()
+    spec = _spec(N, d, dtype, H, Hkv, causal=causal)
+    data, (q, k, v) = _gpu_inputs(spec)
+    print(f"case N={N} d={d} {dtype} H={H}/{Hkv} mode={mode}", flush=True)
+    got, args, ws = pa.sage_attn_quant(q, k, v, causal=causal, mode=mode)
+    torch.cuda.synchronize()
+    got = {n: t.cpu().numpy() for n, t in got.items()}
+    g = H // Hkv
+    for b in range(spec.B):
+        for h in range(H):
+            pro = so.quantize_head(data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g], mode=mode)
+            assert np.array_equal(got["q_codes"][b, h], pro["q_codes"]), "q codes"
+            assert np.array_equal(got["q_scale"][b, h], pro["q_scale"]), "q scales"
+            assert np.array_equal(got["k_codes"][b, h // g], pro["k_codes"]), "k codes"
+            assert np.array_equal(got["k_scale"][b, h // g], pro["k_scale"]), "k scales"
+            assert np.array_equal(got["v_codes"][b, h // g], pro["v_codes"]), "v codes"
+            assert np.array_equal(got["v_scale"][b, h // g], pro["v_scale"]), "v scales"
+            assert np.array_equal(got["k_mean"][b, h // g], pro["kbar"]), "k mean"
+            if mode == "int4_fp8":
+                assert np.array_equal(got["q_mean"][b, h], pro["qbar"]), "q block means"
+                D = pro["delta_s"]
+                diff = np.abs(got["delta_s"][b, h].astype(np.float64) - D.astype(np.float64))
+                # float64 accumulation in another order, one rounding to FP32: at most the last bit
+                assert np.all(diff <= np.spacing(np.abs(D)).astype(np.float64)), "delta S"
+                assert (diff > 0).mean() < 1e-3
+            # int32 score accumulators of every (q tile, kv block) through the MFMA path
+            nqb, nkb = (N + 127) // 128, (N + 63) // 64
+            for qt in range(nqb):
+                for kb in range(nkb):
+                    acc = pa.sage_attn_debug_qk(args, b, h, qt, kb).cpu().numpy()
+                    rows = slice(qt * 128, min(qt * 128 + 128, N))
+                    keys = slice(kb * 64, min(kb * 64 + 64, N))
+                    ref = so.int_scores(pro["q_codes"][rows], pro["k_codes"][keys])
+                    assert np.array_equal(acc[: ref.shape[0], : ref.shape[1]], ref), "int32 accumulators"
+                    assert not acc[ref.shape[0]:].any() and not acc[:, ref.shape[1]:].any()
+
+
+@pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("N,d,dtype,H,Hkv,causal", CASES)
+def test_attention_output_matches_oracle(N, d, dtype, H, Hkv, causal, mode):
+    pa = _pa()
+    spec = _spec(N, d, dtype, H, Hkv, causal=causal)
+    data, (q, k, v) = _gpu_inputs(spec)
+    print(f"case N={N} d={d} {dtype} H={H}/{Hkv} causal={causal} mode={mode}", flush=True)
+    out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode)
+    torch.cuda.synchronize()
+    got = wl.from_torch(out)
+    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32")
+    check_output(got, ref, dtype)
+    # accuracy against the unquantized definition is reported, not asserted tightly
+    g = H // Hkv
+    full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
+                     for h in range(H)])
+    print(f"  vs FP64 attention: cos {wl.cos_sim(got[0], full):.5f} relL1 {wl.rel_l1(got[0], full):.4f}", flush=True)
+    assert wl.cos_sim(got[0], full) > (0.9 if mode == "int4_fp8" else 0.99)
+
+
+def test_plain_signature_and_repeatability():
+    pa = _pa()
+    spec = _spec(384, 128, "bf16", 2, 2)
+    data, (q, k, v) = _gpu_inputs(spec)
+    out1 = torch.empty_like(q)
+    out2 = torch.full_like(q, 7.0)
+    pa.sage_attn_fwd(q, k, v, out1, causal=True, mode="int4_fp8")
+    pa.sage_attn_fwd(q, k, v, out2, causal=True, mode="int4_fp8")
+    torch.cuda.synchronize()
+    assert torch.equal(out1, out2)                       # deterministic
+    ref = pa.sage_attn_fwd_ex(q, k, v, causal=True, mode="int4_fp8")
+    torch.cuda.synchronize()
+    assert torch.equal(out1, ref)                        # both entry points agree
+    pa.sage_attn_release()
+
+
+def test_error_codes_from_the_boundary():
+    pa = _pa()
+    spec = _spec(128, 64, "bf16", 2, 2)
+    _, (q, k, v) = _gpu_inputs(spec)
+    a = pa.make_args(q, k, v, torch.empty_like(q))
+    lib = pa.load_library()
+    import ctypes
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -3          # no workspace
+    a.d = 96
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -2          # unsupported head dim
+    assert pa.sage_attn_workspace_bytes(a) == 0
+    a.d = 64; a.H_kv = 3
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -1          # H % H_kv != 0
+    a.H_kv = 2; a.q = 0
+    ws = torch.empty(1 << 22, dtype=torch.uint8, device="cuda")
+    a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel()
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -1          # null pointer
+    a.q = q.data_ptr(); a.workspace_bytes = 1024
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -3          # workspace too small
+    a.workspace_bytes = ws.numel(); a.mode = 5
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -2
