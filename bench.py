@@ -1,0 +1,150 @@
+"""Throughput of the quantized attention forward pass on one MI355X.
+
+A step is one pass of the whole hot path - smoothing / Delta-S / quantization prologue plus the
+fused attention kernel - over one batch of synthetic, outlier-bearing inputs already resident in
+HBM.  Prints ONE JSON line (see README/DESIGN for the fields): whole-path TOPS as `value`, the
+attention kernel's own roofline figure, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TOPS = 5000.0   # MI355X dense int8 / fp8 MFMA peak (both 5.0 POP/s)
+
+
+def cpu_baseline(spec, mode, budget_s=12.0, max_heads=32):
+    """The CPU oracle as it stands, timed on whole heads of the same workload (as many heads
+    as fit in about budget_s seconds)."""
+    import numpy as np
+    import workloads as wl
+    from oracle import sage_oracle as so
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    heads, ins, outs, dt = [], [], [], 0.0
+    for h in range(min(max_heads, spec.H)):
+        qkv = (wl.make_head(spec, "q", 0, h), wl.make_head(spec, "k", 0, h * spec.H_kv // spec.H),
+               wl.make_head(spec, "v", 0, h * spec.H_kv // spec.H))
+        t0 = time.perf_counter()
+        o = so.sage_attention_head(*qkv, causal=spec.causal, mode=mode, out_dtype="fp32")[0]
+        dt += time.perf_counter() - t0
+        heads.append((0, h)); ins.append(qkv); outs.append(o)
+        if dt > budget_s:
+            break
+    ops = 4.0 * len(heads) * float(spec.N) ** 2 * spec.d / (2 if spec.causal else 1)
+    return dict(value=ops / dt / 1e12, unit="TOPS", cores=threads, kind="oracle",
+                sample=f"{len(heads)} of {spec.B * spec.H} (batch, head) slices of {spec.name}, all query blocks, "
+                       f"{dt:.1f} s"), heads, ins, outs
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="prefill4k")
+    ap.add_argument("--mode", default="int4_fp8", choices=["int4_fp8", "int8_fp8"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2411_10958_amd as pa
+    import workloads as wl
+
+    pa.load_library()            # fails loudly when the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    spec = wl.CONFIGS[args.workload]
+    data = wl.make_inputs(spec, seed=0)
+    q, k, v = (wl.to_torch(data[n], spec.dtype, dev) for n in "qkv")
+    out = torch.empty_like(q)
+    a = pa.make_args(q, k, v, out, causal=spec.causal, mode=args.mode)
+    ws = torch.empty(pa.sage_attn_workspace_bytes(a), dtype=torch.uint8, device=dev)
+    a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel()
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        pa.sage_attn_prologue(a)
+        if events is not None:
+            events[1].record()
+        pa.sage_attn_core(a)
+        if events is not None:
+            events[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    ms_pro = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    ms_core = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    ops = wl.flops(spec)
+    tops = ops / (ms_step * 1e-3) / 1e12
+    core_tops = ops / (ms_core * 1e-3) / 1e12
+
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "attn_kernel_traffic.json")
+    if os.path.exists(tfile):
+        with open(tfile) as f:
+            traffic = json.load(f).get(f"{args.workload}/{args.mode}")
+
+    res = {
+        "metric": "quantized attention TOPS at d=128 (causal + non-causal), cos-sim vs FP32",
+        "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8+fp8" if args.mode == "int8_fp8" else "int4(in i8)+fp8", "data": "synthetic",
+        "config": {"workload": f"{spec.name}: B={spec.B} H={spec.H} H_kv={spec.H_kv} N={spec.N} d={spec.d} "
+                               f"{spec.dtype} causal={spec.causal}", "mode": args.mode,
+                   "ops_formula": "4*B*H*N^2*d" + ("/2" if spec.causal else "")},
+        "breakdown_ms": {"prologue": round(ms_pro, 4), "attention_kernel": round(ms_core, 4)},
+        "roofline": {"bound": "mfma", "kernel": "k_attn_fwd", "achieved": round(core_tops, 2), "peak": PEAK_TOPS,
+                     "unit": "TFLOP/s", "frac": round(core_tops / PEAK_TOPS, 4), "traffic": traffic},
+    }
+
+    # accuracy of what was just computed, on sampled heads (outside the timed region)
+    torch.cuda.synchronize()
+    if not args.no_cpu_baseline:
+        from oracle import sage_oracle as so
+        base, heads, ins, outs = cpu_baseline(spec, args.mode)
+        res["cpu_baseline"] = base
+        got = np.stack([wl.from_torch(out[b, h]) for b, h in heads])
+        ref = np.stack(outs)
+        rows = slice(0, spec.N, max(1, spec.N // 512))
+        full = np.stack([so.ref_attn_fp64(qh, kh, vh, spec.causal, rows=rows) for qh, kh, vh in ins])
+        # the oracle's FP32 output; the kernel rounds once more to the 16-bit output type
+        mant = 10 if spec.dtype == "fp16" else 7
+        half_ulp = 0.5 * np.exp2(np.floor(np.log2(np.maximum(np.abs(ref), 1e-30))) - mant)
+        linf = np.abs(ref).max(axis=-1, keepdims=True)
+        excess = (np.abs(got - ref) - half_ulp) / linf
+        res["accuracy"] = {"sample": f"{len(heads)} heads",
+                           "vs_oracle_max_abs_over_row_linf_beyond_output_rounding": float(max(excess.max(), 0.0)),
+                           "vs_oracle_cos": wl.cos_sim(got, ref),
+                           "vs_fp64_attention_cos": wl.cos_sim(got[:, rows], full),
+                           "vs_fp64_attention_rel_l1": wl.rel_l1(got[:, rows], full)}
+    else:
+        res["cpu_baseline"] = None
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

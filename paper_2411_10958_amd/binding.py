@@ -40,7 +40,8 @@ class sage_quant_out(ctypes.Structure):
 
 
 def lib_path():
-    return os.path.join(_PKG, "libsageattn.so")
+    """The in-tree library; SAGEATTN_LIB may name another build of the same sources."""
+    return os.environ.get("SAGEATTN_LIB") or os.path.join(_PKG, "libsageattn.so")
 
 
 def load_library():

@@ -23,10 +23,10 @@ def hipcc():
     return "hipcc"
 
 
-def build_library(verbose=True, extra_flags=()):
+def build_library(verbose=True, extra_flags=(), out=LIB):
     srcs = [os.path.join(PKG, "csrc", s) for s in SOURCES]
     cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"),
-           "-I", os.path.join(PKG, "csrc"), "-o", LIB, *srcs]
+           "-I", os.path.join(PKG, "csrc"), "-o", out, *srcs]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -36,7 +36,7 @@ def build_library(verbose=True, extra_flags=()):
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -28,19 +28,13 @@ struct AttnParams {
   float kappa;
 };
 
-// LDS stage: K^ block, V^ block, then 64 Delta-S floats and 4 key-group scales.
-template <int D> struct Stage {
-  static constexpr int K_CHUNKS = D * BKV / 16;        // 16-byte chunks
-  static constexpr int V_CHUNKS = D * BKV / 16;
-  static constexpr int X_CHUNKS = 32;                  // 16 chunks Delta-S + 1 chunk scales (+pad)
-  static constexpr int CHUNKS = K_CHUNKS + V_CHUNKS + X_CHUNKS;
-};
-
-// Score accumulators of one wavefront: 2 key tiles x (32 keys x 32 queries), int32.
-// lds_k: this stage's K^ chunks; qreg: the wavefront's Q^ B-operands (one per 32-channel step).
+// Score accumulators of one wavefront for one 64-key block: 2 key tiles x (32 keys x 32
+// queries), int32.  ka: the block's K^ chunks already in registers (chunk (s, kt) at ka[2s + kt]);
+// qreg: the wavefront's Q^ B-operands (one per 32-channel step).  Element acc[kt][v] belongs to
+// key 32*kt + 16*(lane/32) + v of the block and to query lane%32 of the wavefront.
 template <int D>
-__device__ inline void qk_tile(const v4i* __restrict__ lds_k, const v4i (&qreg)[D / 32], int lane,
-                               v16i (&acc)[2]) {
+__device__ __forceinline__ void qk_tile(const v4i (&ka)[2 * (D / 32)], const v4i (&qreg)[D / 32],
+                                        v16i (&acc)[2]) {
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
@@ -49,19 +43,142 @@ __device__ inline void qk_tile(const v4i* __restrict__ lds_k, const v4i (&qreg)[
 #pragma unroll
   for (int s = 0; s < D / 32; ++s) {
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-      const v4i a = lds_k[(s * 2 + kt) * 64 + lane];
-      acc[kt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qreg[s], acc[kt], 0, 0, 0);
-    }
+    for (int kt = 0; kt < 2; ++kt)
+      acc[kt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[s * 2 + kt], qreg[s], acc[kt], 0, 0, 0);
   }
 }
 
+// Per-wavefront running state of Algorithm 1's inner loop.
+template <int D> struct RowState {
+  v16f O[D / 32];   // cross-block FP32 accumulator; O[ct][v]: channel 32ct + 8(v/4) + 4(lane/32) + v%4
+  float m_run;      // running max of the base-2 scores of this lane's query
+  float l_run;      // this lane's share of the running sum of 448 * P~
+};
+
+// One block of Algorithm 1's inner loop for one wavefront: integer scores, dequantize +
+// Delta-S, online softmax, P~ -> FP8, R = P^ V^ (level 1), O = alpha O + R (level 2).
+// LDS operands are fetched in batches well ahead of the MFMAs that use them (all K^ chunks and
+// the Delta-S row first, all V^ chunks right after the score MFMAs), so each batch pays the LDS
+// latency once and the second batch lands while the softmax arithmetic runs.
+template <int D, bool INT4, bool CAUSAL, bool MASKED>
+__device__ __forceinline__ void process_block(RowState<D>& st, const v4i* __restrict__ lk,
+                                              const v4i (&qreg)[D / 32], const v4i* __restrict__ lv,
+                                              const float* __restrict__ lx, float dq, float kappa,
+                                              int lane, int key0, int query, int N) {
+  constexpr int CT = D / 32, NK = 2 * (D / 32);
+  const int half = lane >> 5;
+  v4i ka[NK];
+#pragma unroll
+  for (int i = 0; i < NK; ++i) ka[i] = lk[i * 64 + lane];
+  v4f dsr[2][4];
+  if constexpr (INT4) {
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      const v4f* dsv = reinterpret_cast<const v4f*>(lx + 32 * kt + 16 * half);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) dsr[kt][g] = dsv[g];
+    }
+  }
+  const float dk0 = lx[64 + half], dk1 = lx[66 + half];
+  __builtin_amdgcn_sched_barrier(0);
+  v16i acc[2];
+  qk_tile<D>(ka, qreg, acc);
+  __builtin_amdgcn_sched_barrier(0);
+  v4i va[2 * CT];
+#pragma unroll
+  for (int i = 0; i < 2 * CT; ++i) va[i] = lv[i * 64 + lane];
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- dequantize, add Delta-S (Algorithm 1, score line), in base 2; S overwrites acc ----
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+    const float c = __fmul_rn(__fmul_rn(dq, kt == 0 ? dk0 : dk1), kappa);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      if constexpr (INT4) {
+        const v4f d4 = dsr[kt][g];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          acc[kt][4 * g + r] = __float_as_int(__fmaf_rn((float)acc[kt][4 * g + r], c, d4[r]));
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          acc[kt][4 * g + r] = __float_as_int(__fmul_rn((float)acc[kt][4 * g + r], c));
+      }
+    }
+  }
+  if constexpr (MASKED) {   // causal diagonal and keys beyond N
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = key0 + 32 * kt + 16 * half + v;
+        if (key >= N || (CAUSAL && key > query)) acc[kt][v] = __float_as_int(-INFINITY);
+      }
+    }
+  }
+  // ---- online softmax (Eq. 1 / Algorithm 1) ----
+  float mx = fmaxf(__int_as_float(acc[0][0]), __int_as_float(acc[1][0]));
+#pragma unroll
+  for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(__int_as_float(acc[0][v]), __int_as_float(acc[1][v])));
+  {
+    // the other half of the wavefront holds the other 32 keys of the same query
+    const unsigned u = __float_as_uint(mx);
+    const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+  }
+  const float m_new = fmaxf(st.m_run, mx);
+  const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_new);   // 2^-inf = 0 on the first block
+  const float m_sub = m_new - LOG2_448;                           // folds the *448 of Sec. 3.3
+  st.m_run = m_new;
+  float ls = 0.0f;
+  v8i pb;
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      float e[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        e[r] = __builtin_amdgcn_exp2f(__int_as_float(acc[kt][4 * g + r]) - m_sub);   // = 448 * P~
+        ls += e[r];
+      }
+      int wd = 0;
+      wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[0], e[1], wd, false);
+      wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[2], e[3], wd, true);
+      pb[kt * 4 + g] = wd;
+    }
+  }
+  st.l_run = __fmaf_rn(alpha, st.l_run, ls);
+  // ---- level 1: R = P^ V^ over this block with a zero accumulator; level 2: O = alpha*O + R
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct) {
+    v8i a;
+    const v4i a0 = va[ct * 2 + 0];
+    const v4i a1 = va[ct * 2 + 1];
+    a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
+    a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
+    v16f R;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) R[v] = 0.0f;
+    R = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, R, 0, 0, 0, 0, 0, 0);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) st.O[ct][v] = __fmaf_rn(alpha, st.O[ct][v], R[v]);
+  }
+}
+
+#ifndef SAGE_WAVES_PER_SIMD
+#define SAGE_WAVES_PER_SIMD 2
+#endif
+
 template <int D, bool INT4, bool CAUSAL, bool BF16>
-__global__ void __launch_bounds__(256, 2) k_attn_fwd(const AttnParams p) {
-  constexpr int KS = D / 32;   // 32-channel steps of the score product
-  constexpr int CT = D / 32;   // 32-channel tiles of the output
-  using St = Stage<D>;
-  __shared__ v4i lds[2][St::CHUNKS];
+__global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const AttnParams p) {
+  constexpr int KS = D / 32;          // 32-channel steps of the score product
+  constexpr int CT = D / 32;          // 32-channel tiles of the output
+  constexpr int KC = D * BKV / 16;    // 16-byte chunks of one K^ (or V^) block
+  constexpr int CPT = KC / 256;       // chunks per thread per block copy (2 or 1)
+  __shared__ v4i lds_k[2][KC];
+  __shared__ v4i lds_v[2][KC];
+  __shared__ v4i lds_x[2][32];        // 64 Delta-S floats, then the block's 4 key-group scales
 
   // XCD-aware tile order: consecutive workgroup ids land on different XCDs (8 of them), so
   // give every XCD a contiguous range of tiles - tiles of one head then share one L2.
@@ -73,12 +190,12 @@ __global__ void __launch_bounds__(256, 2) k_attn_fwd(const AttnParams p) {
   const int b = bh / p.H, h = bh % p.H;
   const size_t bhkv = (size_t)b * p.Hkv + h / (p.H / p.Hkv);
 
-  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int t = threadIdx.x, lane = t & 63;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int n = lane & 31, half = lane >> 5;
   const int q_lo = qb * BQ + w * WQ;          // first query of this wavefront
   const int query = q_lo + n;
 
-  // ---- per-workgroup sources ----
   const v4i* gk = reinterpret_cast<const v4i*>(p.k_codes + bhkv * (size_t)p.nKb * BKV * D);
   const v4i* gv = reinterpret_cast<const v4i*>(p.v_codes + bhkv * (size_t)p.nKb * BKV * D);
   const v4i* gd = INT4 ? reinterpret_cast<const v4i*>(p.delta_s + ((size_t)bh * p.nQb + qb) * p.nKb * BKV) : nullptr;
@@ -87,31 +204,29 @@ __global__ void __launch_bounds__(256, 2) k_attn_fwd(const AttnParams p) {
   int nblk = p.nKb;
   if (CAUSAL) nblk = min(nblk, (qb * BQ + BQ - 1) / BKV + 1);
 
-  // global -> register staging of one block: K^ and V^ chunks, Delta-S row piece, key scales
-  constexpr int CPT = St::K_CHUNKS / 256;     // chunks per thread per operand (2 or 1)
-  v4i rk[CPT], rv[CPT], rx;
+  // Block copies are staged through registers: global loads are issued at the top of an
+  // iteration and written to the other LDS stage at its end, so their latency hides under the
+  // block's arithmetic.  The copy is the identity on 16-byte chunk indices.
+  v4i rk[CPT], rv[CPT], rx = {0, 0, 0, 0};
   auto fetch = [&](int j) {
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
-      rk[i] = gk[(size_t)j * St::K_CHUNKS + i * 256 + t];
-      rv[i] = gv[(size_t)j * St::V_CHUNKS + i * 256 + t];
+      rk[i] = gk[(size_t)j * KC + i * 256 + t];
+      rv[i] = gv[(size_t)j * KC + i * 256 + t];
     }
-    if (t < 16) {
-      if constexpr (INT4) rx = gd[j * 16 + t]; else rx = v4i{0, 0, 0, 0};
-    } else if (t == 16) {
-      rx = gs[j];
-    }
+    if (t < 16) { if constexpr (INT4) rx = gd[j * 16 + t]; }
+    else if (t == 16) rx = gs[j];
   };
-  auto stash = [&](int stage) {
+  auto stash = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
-      lds[stage][i * 256 + t] = rk[i];
-      lds[stage][St::K_CHUNKS + i * 256 + t] = rv[i];
+      lds_k[buf][i * 256 + t] = rk[i];
+      lds_v[buf][i * 256 + t] = rv[i];
     }
-    if (t <= 16) lds[stage][St::K_CHUNKS + St::V_CHUNKS + t] = rx;
+    if (t <= 16) lds_x[buf][t] = rx;
   };
 
-  // ---- this wavefront's Q^ operands and scale ----
+  // ---- this wavefront's Q^ operands (registers, for the whole kernel) and scale ----
   v4i qreg[KS];
   {
     const v4i* gq = reinterpret_cast<const v4i*>(p.q_codes + (size_t)bh * p.nQb * BQ * D);
@@ -121,118 +236,60 @@ __global__ void __launch_bounds__(256, 2) k_attn_fwd(const AttnParams p) {
   }
   const float dq = p.q_scale[((size_t)bh * p.nQb + qb) * (BQ / QGROUP) + (w * WQ + n) / QGROUP];
 
-  v16f O[CT];
+  RowState<D> st;
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) O[ct][v] = 0.0f;
+    for (int v = 0; v < 16; ++v) st.O[ct][v] = 0.0f;
   }
-  float m_run = -INFINITY;   // running row max of the base-2 scores
-  float l_run = 0.0f;        // this lane's share of the running row sum of 448 * P~
+  st.m_run = -INFINITY;
+  st.l_run = 0.0f;
 
   fetch(0);
   stash(0);
   __syncthreads();
 
-  for (int j = 0; j < nblk; ++j) {
-    const int stage = j & 1;
+  // The wavefront walks all nblk blocks of the workgroup (copies and barriers are shared), in
+  // three straight-line phases: blocks every lane sees in full, blocks that need the causal /
+  // tail mask, and (causal only) blocks past the wavefront's last query, where it only helps
+  // with the copies.
+  int n_plain = min(nblk, p.N / BKV);                          // blocks without padded keys
+  int n_act = nblk;                                            // blocks with any visible key
+  if (CAUSAL) {
+    n_plain = min(n_plain, (q_lo + 1) / BKV);                  // key0 + 63 <= q_lo
+    n_act = min(nblk, (q_lo + WQ - 1) / BKV + 1);              // key0 <= q_lo + 31
+  }
+  n_plain = __builtin_amdgcn_readfirstlane(n_plain);
+  n_act = __builtin_amdgcn_readfirstlane(n_act);
+  int j = 0;
+  for (; j < n_plain; ++j) {
     if (j + 1 < nblk) fetch(j + 1);
-
-    const int key0 = j * BKV;
-    // a wavefront whose queries all precede this block has nothing visible in it
-    const bool active = !CAUSAL || key0 <= q_lo + WQ - 1;
-    if (active) {
-      const v4i* lk = lds[stage];
-      const v4i* lv = lds[stage] + St::K_CHUNKS;
-      const float* lx = reinterpret_cast<const float*>(lds[stage] + St::K_CHUNKS + St::V_CHUNKS);
-
-      v16i acc[2];
-      qk_tile<D>(lk, qreg, lane, acc);
-
-      // ---- dequantize, add Delta-S (Algorithm 1, score line), in base 2 ----
-      float S[2][16];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        const float dk = lx[64 + 2 * kt + half];
-        const float c = __fmul_rn(__fmul_rn(dq, dk), p.kappa);
-        if constexpr (INT4) {
-          const v4f* dsv = reinterpret_cast<const v4f*>(lx + 32 * kt + 16 * half);
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const v4f d4 = dsv[g];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) S[kt][4 * g + r] = __fmaf_rn((float)acc[kt][4 * g + r], c, d4[r]);
-          }
-        } else {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) S[kt][v] = __fmul_rn((float)acc[kt][v], c);
-        }
-      }
-      // ---- masks: causal diagonal and keys beyond N ----
-      const bool need_mask = (CAUSAL && key0 + BKV - 1 > q_lo) || (key0 + BKV > p.N);
-      if (need_mask) {
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int key = key0 + 32 * kt + 16 * half + v;
-            if (key >= p.N || (CAUSAL && key > query)) S[kt][v] = -INFINITY;
-          }
-        }
-      }
-      // ---- online softmax (Eq. 1 / Algorithm 1) ----
-      float mx = S[0][0];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, S[kt][v]);
-      }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // 2^-inf = 0 on the first block
-      const float m_sub = m_new - LOG2_448;                          // folds the *448 of Sec. 3.3
-      m_run = m_new;
-      float ls = 0.0f;
-      v8i pb;
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float e[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            e[r] = __builtin_amdgcn_exp2f(S[kt][4 * g + r] - m_sub);   // = 448 * P~
-            ls += e[r];
-          }
-          int wd = 0;
-          wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[0], e[1], wd, false);
-          wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[2], e[3], wd, true);
-          pb[kt * 4 + g] = wd;
-        }
-      }
-      l_run = __fmaf_rn(alpha, l_run, ls);
-      // ---- level 1: R = P^ V^ over this block with a zero accumulator; level 2: O = alpha*O + R
-#pragma unroll
-      for (int ct = 0; ct < CT; ++ct) {
-        v8i a;
-        const v4i a0 = lv[(ct * 2 + 0) * 64 + lane];
-        const v4i a1 = lv[(ct * 2 + 1) * 64 + lane];
-        a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
-        a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
-        v16f R;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) R[v] = 0.0f;
-        R = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, R, 0, 0, 0, 0, 0, 0);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) O[ct][v] = __fmaf_rn(alpha, O[ct][v], R[v]);
-      }
-    }
-    if (j + 1 < nblk) stash(stage ^ 1);
+    process_block<D, INT4, CAUSAL, false>(st, lds_k[j & 1], qreg, lds_v[j & 1],
+                                          reinterpret_cast<const float*>(lds_x[j & 1]), dq, p.kappa, lane,
+                                          j * BKV, query, p.N);
+    if (j + 1 < nblk) stash((j + 1) & 1);
+    __syncthreads();
+  }
+  for (; j < n_act; ++j) {
+    if (j + 1 < nblk) fetch(j + 1);
+    process_block<D, INT4, CAUSAL, true>(st, lds_k[j & 1], qreg, lds_v[j & 1],
+                                         reinterpret_cast<const float*>(lds_x[j & 1]), dq, p.kappa, lane,
+                                         j * BKV, query, p.N);
+    if (j + 1 < nblk) stash((j + 1) & 1);
+    __syncthreads();
+  }
+  for (; j < nblk; ++j) {
+    if (j + 1 < nblk) { fetch(j + 1); stash((j + 1) & 1); }
     __syncthreads();
   }
 
   // ---- epilogue (Algorithm 1 last line): O / l / 448 * delta_V; l_run already carries the 448
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  float l_tot = st.l_run;
+  {
+    const unsigned u = __float_as_uint(l_tot);
+    const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+  }
   if (query < p.N) {
     unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) + ((size_t)bh * p.N + query) * D;
     const float* dv = p.v_scale + bhkv * D;
@@ -244,7 +301,7 @@ __global__ void __launch_bounds__(256, 2) k_attn_fwd(const AttnParams p) {
         const v4f sc = *reinterpret_cast<const v4f*>(dv + c0);
         unsigned short o4[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) o4[r] = store16<BF16>(__fmul_rn(__fdiv_rn(O[ct][4 * g + r], l_tot), sc[r]));
+        for (int r = 0; r < 4; ++r) o4[r] = store16<BF16>(__fmul_rn(__fdiv_rn(st.O[ct][4 * g + r], l_tot), sc[r]));
         *reinterpret_cast<uint2*>(orow + c0) =
             make_uint2((unsigned)o4[0] | ((unsigned)o4[1] << 16), (unsigned)o4[2] | ((unsigned)o4[3] << 16));
       }
@@ -262,12 +319,14 @@ __global__ void __launch_bounds__(256) k_debug_qk(const int8_t* __restrict__ q_c
   const v4i* gk = reinterpret_cast<const v4i*>(k_codes) + (size_t)kv_block * (D * BKV / 16);
   for (int i = t; i < D * BKV / 16; i += 256) lds[i] = gk[i];
   __syncthreads();
-  v4i qreg[D / 32];
+  v4i qreg[D / 32], ka[2 * (D / 32)];
   const v4i* gq = reinterpret_cast<const v4i*>(q_codes);
 #pragma unroll
   for (int s = 0; s < D / 32; ++s) qreg[s] = gq[(size_t)((q_tile * (BQ / WQ) + w) * (D / 32) + s) * 64 + lane];
+#pragma unroll
+  for (int i = 0; i < 2 * (D / 32); ++i) ka[i] = lds[i * 64 + lane];
   v16i acc[2];
-  qk_tile<D>(lds, qreg, lane, acc);
+  qk_tile<D>(ka, qreg, acc);
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll

@@ -24,7 +24,7 @@ class WorkloadSpec:
     causal: bool
     k_offset_std: float  # per-channel offset of K (shared by all tokens of a head)
     q_offset_std: float  # per-channel offset of Q
-    n_outlier_ch: int    # channels of Q and K scaled by outlier_gain
+    n_outlier_ch: int    # channels of Q and K whose per-channel offset is scaled by outlier_gain
     outlier_gain: float
     token_norm_max: float  # token-wise scale drawn log-uniformly from [1, token_norm_max]
     config_id: int
@@ -77,11 +77,14 @@ def _qk_like(spec, rng, offset_std):
     if spec.token_norm_max > 1.0:
         s = np.exp(rng.uniform(0.0, np.log(spec.token_norm_max), size=(N, 1))).astype(np.float32)
         x *= s
-    if offset_std > 0:
-        x += (offset_std * rng.standard_normal((1, d))).astype(np.float32)
+    off = (offset_std * rng.standard_normal((1, d))).astype(np.float32)
     if spec.n_outlier_ch > 0:
+        # channel-wise outliers are biases shared by all tokens (the structure the paper's
+        # smoothing removes): a few channels carry an offset outlier_gain times larger
         ch = rng.choice(d, size=spec.n_outlier_ch, replace=False)
-        x[:, ch] *= np.float32(spec.outlier_gain)
+        off[:, ch] *= np.float32(spec.outlier_gain)
+    if offset_std > 0:
+        x += off
     return x
 
 
