@@ -181,7 +181,7 @@ def quantize_v(V):
 
 # --------------------------------------------------------------------------- prologue
 def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SMOOTH,
-                  smooth_q_on=None, smooth_k_on=True, pv_exact=False):
+                  smooth_q_on=None, smooth_k_on=True, pv_exact=False, ds_blocks=None):
     """Everything Algorithm 1 computes before the inner loop, for one (batch, head).
 
     Q, K, V: [N, d] float32 holding exactly representable 16-bit values.
@@ -189,7 +189,9 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
     mode "int8_fp8": only K smoothed, INT8 range [-127, 127] (SageAttn2-8b, Table
     "Two kernel implementations").  An integer `mode` is used as qmax directly, smooth_*_on
     override the mode and pv_exact keeps P~ and V unquantized: all three exist only so the
-    pins can take the quantizers to their high-precision limit.
+    pins can take the quantizers to their high-precision limit.  ds_blocks, if given, lists
+    the smoothing blocks whose Delta-S rows are wanted (the other rows are left zero): sampling
+    support for sequences where the full [N/b_q, N] bias would not fit in host memory.
     """
     N, d = Q.shape
     if sm_scale is None:
@@ -204,7 +206,11 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
         kbar, gK = np.zeros(d, f32), np.asarray(K, f32)
     if smooth_q_on:
         qbar, gQ = smooth_q(Q, bq)
-        D = delta_s(qbar, gK, kappa)
+        if ds_blocks is None:
+            D = delta_s(qbar, gK, kappa)
+        else:
+            D = np.zeros((qbar.shape[0], N), f32)
+            D[list(ds_blocks)] = delta_s(qbar[list(ds_blocks)], gK, kappa)
     else:
         qbar, gQ, D = None, np.asarray(Q, f32), None
     gq, gk = group_map(gmap, N, "q"), group_map(gmap, N, "k")

@@ -29,22 +29,54 @@ struct AttnParams {
 };
 
 // Score accumulators of one wavefront for one 64-key block: 2 key tiles x (32 keys x 32
-// queries), int32.  ka: the block's K^ chunks already in registers (chunk (s, kt) at ka[2s + kt]);
-// qreg: the wavefront's Q^ B-operands (one per 32-channel step).  Element acc[kt][v] belongs to
-// key 32*kt + 16*(lane/32) + v of the block and to query lane%32 of the wavefront.
-template <int D>
+// queries).  ka: the block's K^ chunks already in registers (chunk (s, kt) at ka[2s + kt]); qreg:
+// the wavefront's Q^ B-operands (one per 32-channel step).  Element acc[kt][v] belongs to key
+// 32*kt + 16*(lane/32) + v of the block and to query lane%32 of the wavefront.
+// INT8 mode: v_mfma_i32_32x32x32_i8, int32 accumulators.  INT4 mode: the codes are E4M3 bytes and
+// two 32-channel steps feed one v_mfma_f32_32x32x64_f8f6f4 (both operands list their 64 channels
+// in the same order: the 16 of step 2s, then the 16 of step 2s+1, per lane half); the FP32
+// accumulators hold the exact integers.  Either way the result is returned as raw 32-bit lanes.
+template <int D, bool INT4>
 __device__ __forceinline__ void qk_tile(const v4i (&ka)[2 * (D / 32)], const v4i (&qreg)[D / 32],
                                         v16i (&acc)[2]) {
+  if constexpr (INT4) {
+    v16f accf[2];
 #pragma unroll
-  for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[kt][v] = 0;
-  }
+      for (int v = 0; v < 16; ++v) accf[kt][v] = 0.0f;
+    }
 #pragma unroll
-  for (int s = 0; s < D / 32; ++s) {
+    for (int s = 0; s < D / 64; ++s) {
+      v8i bq;
+      bq[0] = qreg[2 * s][0]; bq[1] = qreg[2 * s][1]; bq[2] = qreg[2 * s][2]; bq[3] = qreg[2 * s][3];
+      bq[4] = qreg[2 * s + 1][0]; bq[5] = qreg[2 * s + 1][1]; bq[6] = qreg[2 * s + 1][2]; bq[7] = qreg[2 * s + 1][3];
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-      acc[kt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[s * 2 + kt], qreg[s], acc[kt], 0, 0, 0);
+      for (int kt = 0; kt < 2; ++kt) {
+        const v4i a0 = ka[(2 * s) * 2 + kt], a1 = ka[(2 * s + 1) * 2 + kt];
+        v8i a;
+        a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
+        a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
+        accf[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, bq, accf[kt], 0, 0, 0, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[kt][v] = __float_as_int(accf[kt][v]);
+    }
+  } else {
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[kt][v] = 0;
+    }
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+        acc[kt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[s * 2 + kt], qreg[s], acc[kt], 0, 0, 0);
+    }
   }
 }
 
@@ -82,7 +114,7 @@ __device__ __forceinline__ void process_block(RowState<D>& st, const v4i* __rest
   const float dk0 = lx[64 + half], dk1 = lx[66 + half];
   __builtin_amdgcn_sched_barrier(0);
   v16i acc[2];
-  qk_tile<D>(ka, qreg, acc);
+  qk_tile<D, INT4>(ka, qreg, acc);
   __builtin_amdgcn_sched_barrier(0);
   v4i va[2 * CT];
 #pragma unroll
@@ -98,7 +130,7 @@ __device__ __forceinline__ void process_block(RowState<D>& st, const v4i* __rest
         const v4f d4 = dsr[kt][g];
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-          acc[kt][4 * g + r] = __float_as_int(__fmaf_rn((float)acc[kt][4 * g + r], c, d4[r]));
+          acc[kt][4 * g + r] = __float_as_int(__fmaf_rn(__int_as_float(acc[kt][4 * g + r]), c, d4[r]));
       } else {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
@@ -119,7 +151,8 @@ __device__ __forceinline__ void process_block(RowState<D>& st, const v4i* __rest
   // ---- online softmax (Eq. 1 / Algorithm 1) ----
   float mx = fmaxf(__int_as_float(acc[0][0]), __int_as_float(acc[1][0]));
 #pragma unroll
-  for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(__int_as_float(acc[0][v]), __int_as_float(acc[1][v])));
+  for (int v = 1; v < 16; ++v)   // one v_max3_f32 per step
+    mx = fmaxf(fmaxf(mx, __int_as_float(acc[0][v])), __int_as_float(acc[1][v]));
   {
     // the other half of the wavefront holds the other 32 keys of the same query
     const unsigned u = __float_as_uint(mx);
@@ -142,7 +175,7 @@ __device__ __forceinline__ void process_block(RowState<D>& st, const v4i* __rest
         e[r] = __builtin_amdgcn_exp2f(__int_as_float(acc[kt][4 * g + r]) - m_sub);   // = 448 * P~
         ls += e[r];
       }
-      int wd = 0;
+      int wd = __float_as_int(e[0]);   // any value: both halves are overwritten below
       wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[0], e[1], wd, false);
       wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[2], e[3], wd, true);
       pb[kt * 4 + g] = wd;
@@ -310,7 +343,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
 }
 
 // Integer score accumulators of one (128-query tile, 64-key block) through qk_tile.
-template <int D>
+template <int D, bool INT4>
 __global__ void __launch_bounds__(256) k_debug_qk(const int8_t* __restrict__ q_codes,
                                                   const int8_t* __restrict__ k_codes, int q_tile,
                                                   int kv_block, int32_t* __restrict__ out) {
@@ -326,11 +359,12 @@ __global__ void __launch_bounds__(256) k_debug_qk(const int8_t* __restrict__ q_c
 #pragma unroll
   for (int i = 0; i < 2 * (D / 32); ++i) ka[i] = lds[i * 64 + lane];
   v16i acc[2];
-  qk_tile<D>(ka, qreg, acc);
+  qk_tile<D, INT4>(ka, qreg, acc);
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) out[(w * WQ + n) * BKV + 32 * kt + 16 * half + v] = acc[kt][v];
+    for (int v = 0; v < 16; ++v)
+      out[(w * WQ + n) * BKV + 32 * kt + 16 * half + v] = INT4 ? (int)__int_as_float(acc[kt][v]) : acc[kt][v];
   }
 }
 
@@ -365,8 +399,13 @@ hipError_t launch_debug_qk(const Dims& D, const Ptrs& P, int b, int h, int q_til
   const size_t bhkv = (size_t)b * D.Hkv + h / (D.H / D.Hkv);
   const int8_t* qc = P.q_codes + bh * (size_t)D.nQb * BQ * D.d;
   const int8_t* kc = P.k_codes + bhkv * (size_t)D.nKb * BKV * D.d;
-  if (D.d == 128) k_debug_qk<128><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
-  else k_debug_qk<64><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
+  if (D.d == 128) {
+    if (D.int4) k_debug_qk<128, true><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
+    else k_debug_qk<128, false><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
+  } else {
+    if (D.int4) k_debug_qk<64, true><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
+    else k_debug_qk<64, false><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
+  }
   return hipGetLastError();
 }
 

@@ -35,6 +35,8 @@ struct Dims {
 //
 // Packed layouts (one "chunk" = 16 bytes = one lane's operand piece, 64 chunks = one
 // wavefront-wide ds_read_b128 / global load):
+//   (codes are two's-complement int8 bytes in the INT8 mode and E4M3 bytes of the same integers in
+//   the INT4 mode, see int4_code_to_e4m3 below)
 //   q_codes: [B*H][N_q32 tiles of 32 queries][d/32 k-steps][64 lanes] chunks.  Lane l of
 //            k-step s holds query 32*tile + l%32, channels 32*s + 16*(l/32) + 0..15
 //            (the B operand of v_mfma_i32_32x32x32_i8).
@@ -122,6 +124,22 @@ __host__ __device__ inline size_t v_code_off(int n, int c, int d) {
   const int blk = n >> 6, part = (n >> 5) & 1, h = (n >> 4) & 1, byte = n & 15;
   const int ct = c >> 5, ch = c & 31;
   return ((size_t)((blk * (d >> 5) + ct) * 2 + part) * 64 + ch + 32 * h) * 16 + byte;
+}
+
+// ---- INT4 codes travel as FP8 E4M3 bytes ----
+// Every integer in [-7, 7] is an E4M3 value (1, 2, 3 = 1.5*2, 4, 5 = 1.25*4, 6 = 1.5*4, 7 = 1.75*4),
+// products (<= 49) and their sums over d <= 128 channels (<= 6272) are exact in the FP32 accumulator
+// of v_mfma_f32_32x32x64_f8f6f4, so the score product of the INT4 mode runs on the FP8 matrix pipe
+// and yields the exact integer accumulators as floats - no int->float conversion afterwards.
+__host__ __device__ inline unsigned char int4_code_to_e4m3(int c) {
+  const unsigned long long tab = 0x4E4C4A4844403800ull;   // bytes for |c| = 0..7
+  const int a = c < 0 ? -c : c;
+  return (unsigned char)(((tab >> (8 * a)) & 0xffu) | (c < 0 ? 0x80u : 0u));
+}
+__host__ __device__ inline int e4m3_to_int4_code(unsigned char b) {
+  const int e = (b >> 3) & 15, m = b & 7;
+  const int a = e == 0 ? 0 : ((8 + m) << (e - 7)) >> 3;     // (1 + m/8) * 2^(e-7), e in 7..9 here
+  return (b & 0x80) ? -a : a;
 }
 
 // ---- 16-bit input helpers ----

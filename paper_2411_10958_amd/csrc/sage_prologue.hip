@@ -35,7 +35,11 @@ __device__ inline int quant_code(float x, float delta, int qmax) {
   return c > qmax ? qmax : (c < -qmax ? -qmax : c);
 }
 
-__device__ inline uint2 pack8(const int (&c)[8]) {
+template <bool AS_E4M3>
+__device__ inline uint2 pack8(const int (&cc)[8]) {
+  int c[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) c[e] = AS_E4M3 ? (int)int4_code_to_e4m3(cc[e]) : cc[e];
   uint2 o;
   o.x = (unsigned)(c[0] & 0xff) | ((unsigned)(c[1] & 0xff) << 8) | ((unsigned)(c[2] & 0xff) << 16) |
         ((unsigned)(c[3] & 0xff) << 24);
@@ -167,7 +171,7 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
       int c[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) c[e] = quant_code(x[i][e], delta, QMAX);
-      *reinterpret_cast<uint2*>(codes + q_code_off(n0 + rg * RPT + i, cg * 8, D)) = pack8(c);
+      *reinterpret_cast<uint2*>(codes + q_code_off(n0 + rg * RPT + i, cg * 8, D)) = pack8<INT4>(c);
     }
   }
 }
@@ -213,7 +217,7 @@ __global__ void __launch_bounds__(256) k_quant_k(const unsigned short* __restric
     int c[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) c[e] = quant_code(x[i][e], delta, QMAX);
-    *reinterpret_cast<uint2*>(codes + k_code_off(n0 + rg * RPT + i, cg * 8, D)) = pack8(c);
+    *reinterpret_cast<uint2*>(codes + k_code_off(n0 + rg * RPT + i, cg * 8, D)) = pack8<INT4>(c);
   }
 }
 
@@ -269,18 +273,22 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
 
 // ------------------------------------------------------------------------------------------
 // Delta-S (Sec. 3.1): D[i, t] = fl32(kappa * <q_bar_i, gamma(K)_t>), inner product in float64
-// so that the value does not depend on summation order.  One workgroup per 64 keys of one
-// (batch, query head); thread (key, lane-group) walks the query blocks four at a time.
+// so that the value does not depend on summation order.  A small GEMM per (batch, query head):
+// [nQb x d] . [d x N], run on the FP64 matrix pipe (v_mfma_f64_16x16x4f64).  One workgroup per
+// 64 keys; wavefront w owns keys 16w..16w+15 and keeps their gamma(K) (as float64 B operands)
+// in registers while it walks the query blocks 16 at a time.
+typedef double v4d __attribute__((ext_vector_type(4)));
+
 template <bool BF16, int D>
 __global__ void __launch_bounds__(256) k_delta_s(const unsigned short* __restrict__ K,
                                                  const float* __restrict__ k_mean,
                                                  const float* __restrict__ q_mean,
                                                  float* __restrict__ delta_s, int N, int nQb, int nKb,
                                                  int H, int Hkv, float kappa) {
-  constexpr int QROWS = 16;  // query-block means staged per pass
+  constexpr int QROWS = 16;  // query-block means per MFMA tile
   __shared__ float s_gk[BKV][D + 1];
-  __shared__ float s_q[QROWS][D];
-  const int t = threadIdx.x;
+  __shared__ float s_q[QROWS][D + 1];
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int kb = blockIdx.x;
   const size_t bh = blockIdx.y;
   const int b = (int)(bh / H), h = (int)(bh % H);
@@ -305,7 +313,12 @@ __global__ void __launch_bounds__(256) k_delta_s(const unsigned short* __restric
       for (int e = 0; e < 8; ++e) s_gk[r][cg * 8 + e] = x[e];
     }
   }
-  const int key = t & 63, sub = t >> 6;  // sub in 0..3 handles staged rows 4*sub .. 4*sub+3
+  __syncthreads();
+  // operand lane map of the 16x16x4 FP64 MFMA: lane l supplies A[l%16][l/16] and B[l/16][l%16]
+  const int r16 = lane & 15, k4 = lane >> 4;
+  double bk[D / 4];
+#pragma unroll
+  for (int cs = 0; cs < D / 4; ++cs) bk[cs] = (double)s_gk[16 * w + r16][4 * cs + k4];
   const double kap = (double)kappa;
   for (int i0 = 0; i0 < nQb; i0 += QROWS) {
     __syncthreads();
@@ -314,17 +327,15 @@ __global__ void __launch_bounds__(256) k_delta_s(const unsigned short* __restric
       s_q[r][c] = (i0 + r < nQb) ? q_mean[(bh * nQb + i0 + r) * D + c] : 0.0f;
     }
     __syncthreads();
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll 4
-    for (int c = 0; c < D; ++c) {
-      const double g = (double)s_gk[key][c];
+    v4d acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[j] = fma((double)s_q[4 * sub + j][c], g, acc[j]);
-    }
+    for (int cs = 0; cs < D / 4; ++cs)
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[r16][4 * cs + k4], bk[cs], acc, 0, 0, 0);
+    // result lane map: lane l, element v holds row 4*v + l/16, column l%16
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int i = i0 + 4 * sub + j;
-      if (i < nQb) delta_s[(bh * nQb + i) * (size_t)nKb * BKV + n0 + key] = (float)(kap * acc[j]);
+    for (int v = 0; v < 4; ++v) {
+      const int i = i0 + 4 * v + k4;
+      if (i < nQb) delta_s[(bh * nQb + i) * (size_t)nKb * BKV + n0 + 16 * w + r16] = (float)(kap * acc[v]);
     }
   }
 }
@@ -332,13 +343,15 @@ __global__ void __launch_bounds__(256) k_delta_s(const unsigned short* __restric
 // ------------------------------------------------------------------------------------------
 // Copies from the packed workspace to plain layouts (used only by sage_attn_quant).
 __global__ void k_unpack_codes(const int8_t* __restrict__ packed, int8_t* __restrict__ plain, int N,
-                               int d, size_t slab, int which) {
-  // grid: (ceil(N*d/256), heads); which: 0 = q, 1 = k, 2 = v
+                               int d, size_t slab, int which, int e4m3_ints) {
+  // grid: (ceil(N*d/256), heads); which: 0 = q, 1 = k, 2 = v; e4m3_ints: q/k bytes hold integers as E4M3
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (size_t)N * d) return;
   const int n = (int)(i / d), c = (int)(i % d);
   const size_t off = which == 0 ? q_code_off(n, c, d) : (which == 1 ? k_code_off(n, c, d) : v_code_off(n, c, d));
-  plain[(size_t)blockIdx.y * N * d + i] = packed[(size_t)blockIdx.y * slab + off];
+  int8_t b = packed[(size_t)blockIdx.y * slab + off];
+  if (e4m3_ints && which != 2) b = (int8_t)e4m3_to_int4_code((unsigned char)b);
+  plain[(size_t)blockIdx.y * N * d + i] = b;
 }
 
 __global__ void k_unpack_rows(const float* __restrict__ src, float* __restrict__ dst, int n_valid,
@@ -386,9 +399,9 @@ hipError_t launch_unpack(const Dims& D, const Ptrs& P, const void* quant_out, hi
       qo.q_codes, qo.k_codes, qo.v_codes, qo.q_scale, qo.k_scale, qo.v_scale, qo.k_mean, qo.q_mean, qo.delta_s};
   const int BH = D.B * D.H, BHkv = D.B * D.Hkv;
   const unsigned gx = (unsigned)(((size_t)D.N * D.d + 255) / 256);
-  if (o.qc) k_unpack_codes<<<dim3(gx, BH), 256, 0, s>>>(P.q_codes, o.qc, D.N, D.d, (size_t)D.nQb * BQ * D.d, 0);
-  if (o.kc) k_unpack_codes<<<dim3(gx, BHkv), 256, 0, s>>>(P.k_codes, o.kc, D.N, D.d, (size_t)D.nKb * BKV * D.d, 1);
-  if (o.vc) k_unpack_codes<<<dim3(gx, BHkv), 256, 0, s>>>((const int8_t*)P.v_codes, (int8_t*)o.vc, D.N, D.d, (size_t)D.nKb * BKV * D.d, 2);
+  if (o.qc) k_unpack_codes<<<dim3(gx, BH), 256, 0, s>>>(P.q_codes, o.qc, D.N, D.d, (size_t)D.nQb * BQ * D.d, 0, D.int4);
+  if (o.kc) k_unpack_codes<<<dim3(gx, BHkv), 256, 0, s>>>(P.k_codes, o.kc, D.N, D.d, (size_t)D.nKb * BKV * D.d, 1, D.int4);
+  if (o.vc) k_unpack_codes<<<dim3(gx, BHkv), 256, 0, s>>>((const int8_t*)P.v_codes, (int8_t*)o.vc, D.N, D.d, (size_t)D.nKb * BKV * D.d, 2, 0);
   const int nqg = (D.N + QGROUP - 1) / QGROUP, nkg = (D.N + KGROUP - 1) / KGROUP;
   if (o.qs) k_unpack_rows<<<dim3((nqg + 255) / 256, BH), 256, 0, s>>>(P.q_scale, o.qs, nqg, D.nQb * (BQ / QGROUP));
   if (o.ks) k_unpack_rows<<<dim3((nkg + 255) / 256, BHkv), 256, 0, s>>>(P.k_scale, o.ks, nkg, D.nKb * (BKV / KGROUP));

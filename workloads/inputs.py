@@ -8,7 +8,9 @@ exactly representable 16-bit values, laid out [B, H, N, d] (K, V: [B, H_kv, N, d
 Every (batch, head) slice is generated from its own seed, so a single head of a large
 configuration can be drawn without materialising the rest.
 """
+import os
 from dataclasses import dataclass, replace
+
 import numpy as np
 
 
@@ -54,10 +56,10 @@ def round_to_dtype(x, dtype):
     if dtype == "fp16":
         return x.astype(np.float16).astype(np.float32)
     if dtype == "bf16":
-        u = x.view(np.uint32).astype(np.uint64)
-        lsb = (u >> 16) & 1
-        u = (u + 0x7FFF + lsb) & 0xFFFF0000
-        return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+        u = x.view(np.uint32)
+        with np.errstate(over="ignore"):
+            u = (u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) & np.uint32(0xFFFF0000)
+        return u.view(np.float32).reshape(x.shape)   # finite inputs far from overflow: no wrap-around
     raise ValueError(dtype)
 
 
@@ -114,12 +116,20 @@ def make_inputs(spec, seed=0, heads=None):
     q = np.empty((spec.B, len(q_heads), spec.N, spec.d), np.float32)
     k = np.empty((spec.B, len(kv_heads), spec.N, spec.d), np.float32)
     v = np.empty_like(k)
-    for b in range(spec.B):
-        for i, h in enumerate(q_heads):
-            q[b, i] = make_head(spec, "q", b, h, seed)
-        for i, h in enumerate(kv_heads):
-            k[b, i] = make_head(spec, "k", b, h, seed)
-            v[b, i] = make_head(spec, "v", b, h, seed)
+    jobs = [(q, "q", b, i, h) for b in range(spec.B) for i, h in enumerate(q_heads)]
+    jobs += [(a, w, b, i, h) for a, w in ((k, "k"), (v, "v")) for b in range(spec.B) for i, h in enumerate(kv_heads)]
+
+    def fill(job):
+        arr, which, b, i, h = job
+        arr[b, i] = make_head(spec, which, b, h, seed)
+
+    if len(jobs) * spec.N * spec.d > (1 << 24):     # slices are independent and seeded one by one
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+            list(ex.map(fill, jobs))
+    else:
+        for job in jobs:
+            fill(job)
     return dict(q=q, k=k, v=v, q_heads=q_heads, kv_heads=kv_heads, spec=spec)
 
 
