@@ -87,39 +87,14 @@ template <int D> struct RowState {
   float l_run;      // this lane's share of the running sum of 448 * P~
 };
 
-// One block of Algorithm 1's inner loop for one wavefront: integer scores, dequantize +
-// Delta-S, online softmax, P~ -> FP8, R = P^ V^ (level 1), O = alpha O + R (level 2).
-// LDS operands are fetched in batches well ahead of the MFMAs that use them (all K^ chunks and
-// the Delta-S row first, all V^ chunks right after the score MFMAs), so each batch pays the LDS
-// latency once and the second batch lands while the softmax arithmetic runs.
+// Middle part of one block of Algorithm 1's inner loop for one wavefront: the raw scores in
+// `acc` are dequantized (+ Delta-S) in place, go through the online softmax and become the FP8
+// P~ operand `pb`.  Returns alpha = 2^(m_old - m_new).
 template <int D, bool INT4, bool CAUSAL, bool MASKED>
-__device__ __forceinline__ void process_block(RowState<D>& st, const v4i* __restrict__ lk,
-                                              const v4i (&qreg)[D / 32], const v4i* __restrict__ lv,
-                                              const float* __restrict__ lx, float dq, float kappa,
-                                              int lane, int key0, int query, int N) {
-  constexpr int CT = D / 32, NK = 2 * (D / 32);
+__device__ __forceinline__ float block_softmax(RowState<D>& st, v16i (&acc)[2], const v4f (&dsr)[2][4],
+                                               float dk0, float dk1, v8i& pb, float dq, float kappa,
+                                               int lane, int key0, int query, int N) {
   const int half = lane >> 5;
-  v4i ka[NK];
-#pragma unroll
-  for (int i = 0; i < NK; ++i) ka[i] = lk[i * 64 + lane];
-  v4f dsr[2][4];
-  if constexpr (INT4) {
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-      const v4f* dsv = reinterpret_cast<const v4f*>(lx + 32 * kt + 16 * half);
-#pragma unroll
-      for (int g = 0; g < 4; ++g) dsr[kt][g] = dsv[g];
-    }
-  }
-  const float dk0 = lx[64 + half], dk1 = lx[66 + half];
-  __builtin_amdgcn_sched_barrier(0);
-  v16i acc[2];
-  qk_tile<D, INT4>(ka, qreg, acc);
-  __builtin_amdgcn_sched_barrier(0);
-  v4i va[2 * CT];
-#pragma unroll
-  for (int i = 0; i < 2 * CT; ++i) va[i] = lv[i * 64 + lane];
-  __builtin_amdgcn_sched_barrier(0);
   // ---- dequantize, add Delta-S (Algorithm 1, score line), in base 2; S overwrites acc ----
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt) {
@@ -164,7 +139,6 @@ __device__ __forceinline__ void process_block(RowState<D>& st, const v4i* __rest
   const float m_sub = m_new - LOG2_448;                           // folds the *448 of Sec. 3.3
   st.m_run = m_new;
   float ls = 0.0f;
-  v8i pb;
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
@@ -182,9 +156,16 @@ __device__ __forceinline__ void process_block(RowState<D>& st, const v4i* __rest
     }
   }
   st.l_run = __fmaf_rn(alpha, st.l_run, ls);
-  // ---- level 1: R = P^ V^ over this block with a zero accumulator; level 2: O = alpha*O + R
+  return alpha;
+}
+
+// Second half: level 1, R = P^ V^ over this block with a zero accumulator (one K = 64 MFMA per
+// 32 output channels); level 2, O = alpha * O + R in FP32 (Sec. 3.4).
+template <int D>
+__device__ __forceinline__ void block_pv(RowState<D>& st, const v4i (&va)[2 * (D / 32)], const v8i& pb,
+                                         float alpha) {
 #pragma unroll
-  for (int ct = 0; ct < CT; ++ct) {
+  for (int ct = 0; ct < D / 32; ++ct) {
     v8i a;
     const v4i a0 = va[ct * 2 + 0];
     const v4i a1 = va[ct * 2 + 1];
@@ -278,14 +259,9 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   st.m_run = -INFINITY;
   st.l_run = 0.0f;
 
-  fetch(0);
-  stash(0);
-  __syncthreads();
-
-  // The wavefront walks all nblk blocks of the workgroup (copies and barriers are shared), in
-  // three straight-line phases: blocks every lane sees in full, blocks that need the causal /
-  // tail mask, and (causal only) blocks past the wavefront's last query, where it only helps
-  // with the copies.
+  // The wavefront walks all nblk blocks of the workgroup (copies and barriers are shared):
+  // blocks [0, n_act) hold keys visible to some of its queries, of which [0, n_plain) need no
+  // mask; past n_act (causal only) it just helps with the copies.
   int n_plain = min(nblk, p.N / BKV);                          // blocks without padded keys
   int n_act = nblk;                                            // blocks with any visible key
   if (CAUSAL) {
@@ -294,27 +270,74 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   }
   n_plain = __builtin_amdgcn_readfirstlane(n_plain);
   n_act = __builtin_amdgcn_readfirstlane(n_act);
+
+  // Software pipeline, one barrier per block.  At the top of iteration j the registers hold the
+  // K^ operands of block j (read from LDS during iteration j-1) and the global copy of block
+  // j+1 (loaded during iteration j-1); LDS stage j%2 holds block j.  The iteration
+  //   1. issues the score MFMAs of block j, then (while they run) reads block j's Delta-S,
+  //      scales and V^ operands, writes block j+1 into the other stage and starts the global
+  //      loads of block j+2,
+  //   2. runs dequantization + softmax of block j,
+  //   3. barrier: block j+1 is now visible and nobody needs K^_j / Delta-S_j any more,
+  //   4. starts the LDS reads of K^_{j+1} and runs P~V + the O update of block j under them.
+  // So no LDS or global latency sits between a barrier and the MFMAs that follow it.
+  v4i ka[2 * KS], va[2 * CT];
+  v4f dsr[2][4];
+  float dk0 = 0.0f, dk1 = 0.0f;
+  auto read_k = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 2 * KS; ++i) ka[i] = lds_k[buf][i * 64 + lane];
+  };
+  auto read_v = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 2 * CT; ++i) va[i] = lds_v[buf][i * 64 + lane];
+  };
+  auto read_x = [&](int buf) {
+    const float* lx = reinterpret_cast<const float*>(lds_x[buf]);
+    if constexpr (INT4) {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        const v4f* dsv = reinterpret_cast<const v4f*>(lx + 32 * kt + 16 * half);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) dsr[kt][g] = dsv[g];
+      }
+    }
+    dk0 = lx[64 + half];
+    dk1 = lx[66 + half];
+  };
+  fetch(0);
+  stash(0);
+  if (nblk > 1) fetch(1);
+  __syncthreads();
+  read_k(0);
+
+#define SAGE_ITER(MASKED_, ACTIVE_)                                                                  \
+  do {                                                                                               \
+    const int cur = j & 1;                                                                           \
+    v16i acc[2];                                                                                     \
+    if (ACTIVE_) {                                                                                   \
+      qk_tile<D, INT4>(ka, qreg, acc);                                                               \
+      __builtin_amdgcn_sched_barrier(0);                                                             \
+      read_x(cur);                                                                                   \
+      read_v(cur);                                                                                   \
+    }                                                                                                \
+    if (j + 1 < nblk) stash(cur ^ 1);                                                                \
+    if (j + 2 < nblk) fetch(j + 2);                                                                  \
+    __builtin_amdgcn_sched_barrier(0);                                                               \
+    v8i pb;                                                                                          \
+    float alpha = 1.0f;                                                                              \
+    if (ACTIVE_)                                                                                     \
+      alpha = block_softmax<D, INT4, CAUSAL, MASKED_>(st, acc, dsr, dk0, dk1, pb, dq, p.kappa, lane,  \
+                                                      j * BKV, query, p.N);                          \
+    __syncthreads();                                                                                 \
+    if (j + 1 < n_act) read_k(cur ^ 1);                                                              \
+    if (ACTIVE_) block_pv<D>(st, va, pb, alpha);                                                     \
+  } while (0)
   int j = 0;
-  for (; j < n_plain; ++j) {
-    if (j + 1 < nblk) fetch(j + 1);
-    process_block<D, INT4, CAUSAL, false>(st, lds_k[j & 1], qreg, lds_v[j & 1],
-                                          reinterpret_cast<const float*>(lds_x[j & 1]), dq, p.kappa, lane,
-                                          j * BKV, query, p.N);
-    if (j + 1 < nblk) stash((j + 1) & 1);
-    __syncthreads();
-  }
-  for (; j < n_act; ++j) {
-    if (j + 1 < nblk) fetch(j + 1);
-    process_block<D, INT4, CAUSAL, true>(st, lds_k[j & 1], qreg, lds_v[j & 1],
-                                         reinterpret_cast<const float*>(lds_x[j & 1]), dq, p.kappa, lane,
-                                         j * BKV, query, p.N);
-    if (j + 1 < nblk) stash((j + 1) & 1);
-    __syncthreads();
-  }
-  for (; j < nblk; ++j) {
-    if (j + 1 < nblk) { fetch(j + 1); stash((j + 1) & 1); }
-    __syncthreads();
-  }
+  for (; j < n_plain; ++j) SAGE_ITER(false, true);
+  for (; j < n_act; ++j) SAGE_ITER(true, true);
+  for (; j < nblk; ++j) SAGE_ITER(false, false);
+#undef SAGE_ITER
 
   // ---- epilogue (Algorithm 1 last line): O / l / 448 * delta_V; l_run already carries the 448
   float l_tot = st.l_run;
