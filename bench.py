@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--workload", default="prefill4k")
     ap.add_argument("--mode", default="int4_fp8", choices=["int4_fp8", "int8_fp8"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only; run with --gpus 1", file=sys.stderr)
@@ -86,6 +89,12 @@ def main():
         if events is not None:
             events[2].record()
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -102,11 +111,24 @@ def main():
     tops = ops / (ms_step * 1e-3) / 1e12
     core_tops = ops / (ms_core * 1e-3) / 1e12
 
+    # HBM bytes per launch of the attention kernel, from the committed rocprofv3 counter summary
     traffic = None
     tfile = os.path.join(ROOT, "profiles", "attn_kernel_traffic.json")
     if os.path.exists(tfile):
         with open(tfile) as f:
-            traffic = json.load(f).get(f"{args.workload}/{args.mode}")
+            t = json.load(f).get(f"{args.workload}/{args.mode}")
+        if t:
+            traffic = t["hbm_read_bytes"] + t["hbm_write_bytes"]
+    # algorithmic bytes of the same launch: codes of Q, K, V (1 B each), Delta-S rows the tiles read,
+    # scales, and the 16-bit output
+    BH, BHkv = spec.B * spec.H, spec.B * spec.H_kv
+    nqb = (spec.N + 127) // 128
+    ds_bytes = 0
+    if args.mode == "int4_fp8":
+        per_row = [min(spec.N, (i * 128 + 128 + 63) // 64 * 64) if spec.causal else spec.N for i in range(nqb)]
+        ds_bytes = 4 * BH * sum(per_row)
+    alg_bytes = (BH + 2 * BHkv) * spec.N * spec.d + ds_bytes + 4 * (BH * spec.N // 2 + BHkv * spec.N // 16) \
+        + 2 * BH * spec.N * spec.d
 
     res = {
         "metric": "quantized attention TOPS at d=128 (causal + non-causal), cos-sim vs FP32",
@@ -118,7 +140,8 @@ def main():
                    "ops_formula": "4*B*H*N^2*d" + ("/2" if spec.causal else "")},
         "breakdown_ms": {"prologue": round(ms_pro, 4), "attention_kernel": round(ms_core, 4)},
         "roofline": {"bound": "mfma", "kernel": "k_attn_fwd", "achieved": round(core_tops, 2), "peak": PEAK_TOPS,
-                     "unit": "TFLOP/s", "frac": round(core_tops / PEAK_TOPS, 4), "traffic": traffic},
+                     "unit": "TFLOP/s", "frac": round(core_tops / PEAK_TOPS, 4), "traffic": traffic,
+                     "algorithmic_bytes": alg_bytes, "ops_per_launch": ops},
     }
 
     # accuracy of what was just computed, on sampled heads (outside the timed region)

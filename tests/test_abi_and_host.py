@@ -1,0 +1,99 @@
+"""CPU-side checks of the C-ABI library: it loads without a GPU, exports every function that
+include/sage_attn.h declares, sizes workspaces consistently and rejects bad arguments on the
+host before anything is launched.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _lib():
+    import paper_2411_10958_amd as pa
+    if not os.path.exists(pa.lib_path()):
+        pytest.skip("libsageattn.so is not built (run __graft_entry__.build())")
+    return pa, pa.load_library()
+
+
+def _declared_functions():
+    with open(os.path.join(ROOT, "include", "sage_attn.h")) as f:
+        text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(sage_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    pa, lib = _lib()
+    names = _declared_functions()
+    assert {"sage_attn_fwd", "sage_attn_fwd_ex", "sage_attn_quant", "sage_attn_workspace_bytes",
+            "sage_attn_prologue", "sage_attn_core", "sage_attn_debug_qk", "sage_attn_release",
+            "sage_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in sage_attn.h but not exported"
+
+
+def test_binding_has_the_same_names():
+    pa, _ = _lib()
+    for n in _declared_functions():
+        assert hasattr(pa, n), f"binding lacks {n}"
+
+
+def _args(pa, **kw):
+    from paper_2411_10958_amd.binding import sage_attn_args
+    a = sage_attn_args()
+    a.B, a.H, a.H_kv, a.N, a.d, a.mode, a.dtype = 4, 32, 32, 4096, 128, 0, 1
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def test_workspace_size_formula():
+    pa, _ = _lib()
+    a = _args(pa)
+    n = pa.sage_attn_workspace_bytes(a)
+    BH, N, d = 128, 4096, 128
+    codes = 3 * BH * N * d
+    delta_s = BH * (N // 128) * N * 4
+    assert codes + delta_s <= n <= codes + delta_s + 16 * 1024 * 1024
+    a8 = _args(pa, mode=1)
+    assert pa.sage_attn_workspace_bytes(a8) < n - delta_s + 1024      # no Delta-S in the 8-bit variant
+    # ragged N rounds up to whole tiles; grouped KV heads shrink K/V storage
+    assert pa.sage_attn_workspace_bytes(_args(pa, N=4097)) > n
+    assert pa.sage_attn_workspace_bytes(_args(pa, H_kv=8)) < n
+    assert n % 256 == 0
+
+
+def test_argument_errors_are_found_on_the_host():
+    pa, lib = _lib()
+    bad = [dict(d=96), dict(d=256), dict(mode=2), dict(dtype=3)]
+    for kw in bad:
+        a = _args(pa, **kw)
+        assert pa.sage_attn_workspace_bytes(a) == 0
+        assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -2, kw
+    for kw in [dict(N=0), dict(B=-1), dict(H_kv=5)]:
+        a = _args(pa, **kw)
+        assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -1, kw
+    a = _args(pa)                      # valid shapes but null tensors
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -1
+    a.q = a.k = a.v = a.out = 4096     # non-null, but no workspace: rejected before any launch
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -3
+    assert lib.sage_attn_quant(ctypes.byref(a), None) == -1
+    assert lib.sage_attn_debug_qk(ctypes.byref(a), 0, 0, 0, 0, None) == -1
+    assert lib.sage_attn_fwd_ex(None) == -1
+    assert pa.sage_status_string(0) == "ok" and "workspace" in pa.sage_status_string(-3)
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    import paper_2411_10958_amd.binding as b
+    monkeypatch.setenv("SAGEATTN_LIB", str(tmp_path / "nope.so"))
+    monkeypatch.setattr(b, "_LIB", None)
+    with pytest.raises(FileNotFoundError):
+        b.load_library()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
