@@ -159,11 +159,22 @@ __device__ __forceinline__ float block_softmax(RowState<D>& st, v16i (&acc)[2], 
   return alpha;
 }
 
-// Second half: level 1, R = P^ V^ over this block with a zero accumulator (one K = 64 MFMA per
-// 32 output channels); level 2, O = alpha * O + R in FP32 (Sec. 3.4).
+// Second half: the two-level accumulation of Sec. 3.4 on gfx950.  One v_mfma_f32_32x32x64_f8f6f4 has
+// K = 64 = b_kv: the instruction sums the block's 64 FP8 products in its internal accumulator
+// (level 1, confined to this block) and then adds its C operand in full FP32 (level 2: the
+// cross-block accumulator O; measured - C passes through bit-exactly and C + product keeps FP32
+// precision).  So O is the C/D operand, pre-scaled by alpha = 2^(m_old - m_new) only when some
+// query of the wavefront actually moved its running max in this block.
 template <int D>
 __device__ __forceinline__ void block_pv(RowState<D>& st, const v4i (&va)[2 * (D / 32)], const v8i& pb,
                                          float alpha) {
+  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+    for (int ct = 0; ct < D / 32; ++ct) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) st.O[ct][v] = __fmul_rn(alpha, st.O[ct][v]);
+    }
+  }
 #pragma unroll
   for (int ct = 0; ct < D / 32; ++ct) {
     v8i a;
@@ -171,12 +182,7 @@ __device__ __forceinline__ void block_pv(RowState<D>& st, const v4i (&va)[2 * (D
     const v4i a1 = va[ct * 2 + 1];
     a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
     a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
-    v16f R;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) R[v] = 0.0f;
-    R = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, R, 0, 0, 0, 0, 0, 0);
-#pragma unroll
-    for (int v = 0; v < 16; ++v) st.O[ct][v] = __fmaf_rn(alpha, st.O[ct][v], R[v]);
+    st.O[ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, st.O[ct], 0, 0, 0, 0, 0, 0);
   }
 }
 

@@ -279,15 +279,16 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
 // in registers while it walks the query blocks 16 at a time.
 typedef double v4d __attribute__((ext_vector_type(4)));
 
+constexpr int DS_QROWS = 32;    // query-block means staged in LDS per pass: two 16-row MFMA tiles
+
 template <bool BF16, int D>
 __global__ void __launch_bounds__(256) k_delta_s(const unsigned short* __restrict__ K,
                                                  const float* __restrict__ k_mean,
                                                  const float* __restrict__ q_mean,
                                                  float* __restrict__ delta_s, int N, int nQb, int nKb,
                                                  int H, int Hkv, float kappa) {
-  constexpr int QROWS = 16;  // query-block means per MFMA tile
   __shared__ float s_gk[BKV][D + 1];
-  __shared__ float s_q[QROWS][D + 1];
+  __shared__ float s_q[DS_QROWS][D + 1];
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int kb = blockIdx.x;
   const size_t bh = blockIdx.y;
@@ -313,29 +314,40 @@ __global__ void __launch_bounds__(256) k_delta_s(const unsigned short* __restric
       for (int e = 0; e < 8; ++e) s_gk[r][cg * 8 + e] = x[e];
     }
   }
-  __syncthreads();
-  // operand lane map of the 16x16x4 FP64 MFMA: lane l supplies A[l%16][l/16] and B[l/16][l%16]
+  // operand lane map of the 16x16x4 FP64 MFMA: lane l supplies A[l%16][l/16] and B[l/16][l%16];
+  // result: lane l, element v holds row 4*v + l/16, column l%16
   const int r16 = lane & 15, k4 = lane >> 4;
-  double bk[D / 4];
-#pragma unroll
-  for (int cs = 0; cs < D / 4; ++cs) bk[cs] = (double)s_gk[16 * w + r16][4 * cs + k4];
   const double kap = (double)kappa;
-  for (int i0 = 0; i0 < nQb; i0 += QROWS) {
-    __syncthreads();
-    for (int idx = t; idx < QROWS * D; idx += 256) {
-      const int r = idx / D, c = idx % D;
-      s_q[r][c] = (i0 + r < nQb) ? q_mean[(bh * nQb + i0 + r) * D + c] : 0.0f;
+  bool have_b = false;
+  double bk[D / 4];
+  for (int i0 = 0; i0 < nQb; i0 += DS_QROWS) {
+    const int rows = min(DS_QROWS, nQb - i0);
+    if (i0 > 0) __syncthreads();
+    for (int idx = t; idx < ((rows + 15) & ~15) * (D / 4); idx += 256) {
+      const int r = idx / (D / 4), c4 = idx % (D / 4);
+      float4 q4 = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < rows) q4 = *reinterpret_cast<const float4*>(q_mean + (bh * nQb + i0 + r) * D + 4 * c4);
+      s_q[r][4 * c4 + 0] = q4.x; s_q[r][4 * c4 + 1] = q4.y; s_q[r][4 * c4 + 2] = q4.z; s_q[r][4 * c4 + 3] = q4.w;
     }
     __syncthreads();
-    v4d acc = {0.0, 0.0, 0.0, 0.0};
+    if (!have_b) {   // this wavefront's 16 keys as float64 B operands, kept for the whole kernel
 #pragma unroll
-    for (int cs = 0; cs < D / 4; ++cs)
-      acc = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[r16][4 * cs + k4], bk[cs], acc, 0, 0, 0);
-    // result lane map: lane l, element v holds row 4*v + l/16, column l%16
+      for (int cs = 0; cs < D / 4; ++cs) bk[cs] = (double)s_gk[16 * w + r16][4 * cs + k4];
+      have_b = true;
+    }
+    // two independent accumulator chains (rows 0..15 and 16..31 of the pass) keep the pipe busy
+    v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int cs = 0; cs < D / 4; ++cs) {
+      acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[r16][4 * cs + k4], bk[cs], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[16 + r16][4 * cs + k4], bk[cs], acc1, 0, 0, 0);
+    }
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int i = i0 + 4 * v + k4;
-      if (i < nQb) delta_s[(bh * nQb + i) * (size_t)nKb * BKV + n0 + 16 * w + r16] = (float)(kap * acc[v]);
+      float* dst = delta_s + (bh * nQb + i) * (size_t)nKb * BKV + n0 + 16 * w + r16;
+      if (i < nQb) dst[0] = (float)(kap * acc0[v]);
+      if (i + 16 < nQb) dst[(size_t)16 * nKb * BKV] = (float)(kap * acc1[v]);
     }
   }
 }
