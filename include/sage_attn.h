@@ -127,6 +127,16 @@ int sage_attn_quant(const sage_attn_args* args, const sage_quant_out* out);
 int sage_attn_debug_qk(const sage_attn_args* args, int b, int h, int q_tile, int kv_block,
                        int32_t* out_acc);
 
+/* Hardware check behind the accumulation design (the probe of Sec. 3.4, "FP32 MMA Buffer for FP22
+   Accumulator", run on gfx950): executes ONE v_mfma_f32_32x32x64_f8f6f4, D = A*B + C, the
+   instruction the P~V product uses (K = 64 = one accumulation block).
+     a_codes, b_codes: device, [64 lanes][32] E4M3 bytes; lane l of A holds row l%32, k = 32*(l/32) + byte;
+                       lane l of B holds column l%32, same k.
+     c_in, d_out:      device, [64 lanes][16] float; element v of lane l is row 8*(v/4) + 4*(l/32) + v%4,
+                       column l%32. */
+int sage_attn_debug_mfma_fp8(const uint8_t* a_codes, const uint8_t* b_codes, const float* c_in,
+                             float* d_out, void* stream);
+
 const char* sage_status_string(int status);
 
 #ifdef __cplusplus

@@ -66,6 +66,8 @@ def load_library():
         lib.sage_attn_quant.argtypes = [P(sage_attn_args), P(sage_quant_out)]
         lib.sage_attn_debug_qk.restype = ctypes.c_int
         lib.sage_attn_debug_qk.argtypes = [P(sage_attn_args)] + [ctypes.c_int] * 4 + [ctypes.c_void_p]
+        lib.sage_attn_debug_mfma_fp8.restype = ctypes.c_int
+        lib.sage_attn_debug_mfma_fp8.argtypes = [ctypes.c_void_p] * 5
         lib.sage_status_string.restype = ctypes.c_char_p
         lib.sage_status_string.argtypes = [ctypes.c_int]
         _LIB = lib
@@ -198,3 +200,12 @@ def sage_attn_debug_qk(args, b, h, q_tile, kv_block, device="cuda"):
     out = torch.empty((128, 64), dtype=torch.int32, device=device)
     _check(load_library().sage_attn_debug_qk(ctypes.byref(args), b, h, q_tile, kv_block, _ptr(out)), "sage_attn_debug_qk")
     return out
+
+
+def sage_attn_debug_mfma_fp8(a_codes, b_codes, c_in):
+    """One v_mfma_f32_32x32x64_f8f6f4: a_codes, b_codes uint8 [64, 32] (E4M3), c_in float32 [64, 16]."""
+    d = torch.empty_like(c_in)
+    s = torch.cuda.current_stream(c_in.device).cuda_stream
+    _check(load_library().sage_attn_debug_mfma_fp8(_ptr(a_codes), _ptr(b_codes), _ptr(c_in), _ptr(d), s),
+           "sage_attn_debug_mfma_fp8")
+    return d

@@ -143,6 +143,12 @@ int sage_attn_debug_qk(const sage_attn_args* args, int b, int h, int q_tile, int
   return hip_status(launch_debug_qk(D, P, b, h, q_tile, kv_block, out_acc, (hipStream_t)args->stream));
 }
 
+int sage_attn_debug_mfma_fp8(const uint8_t* a_codes, const uint8_t* b_codes, const float* c_in,
+                             float* d_out, void* stream) {
+  if (!a_codes || !b_codes || !c_in || !d_out) return SAGE_ERR_INVALID_ARG;
+  return hip_status(launch_debug_mfma_fp8(a_codes, b_codes, c_in, d_out, (hipStream_t)stream));
+}
+
 const char* sage_status_string(int status) {
   switch (status) {
     case SAGE_OK: return "ok";

@@ -397,6 +397,18 @@ __global__ void __launch_bounds__(256) k_debug_qk(const int8_t* __restrict__ q_c
   }
 }
 
+// One P~V-type MFMA on caller-provided operands (hardware check of the accumulation path).
+__global__ void __launch_bounds__(64) k_debug_mfma_fp8(const v8i* __restrict__ a, const v8i* __restrict__ b,
+                                                       const v16f* __restrict__ c, v16f* __restrict__ d) {
+  const int l = threadIdx.x;
+  d[l] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[l], b[l], c[l], 0, 0, 0, 0, 0, 0);
+}
+
+hipError_t launch_debug_mfma_fp8(const void* a, const void* b, const float* c, float* d, hipStream_t s) {
+  k_debug_mfma_fp8<<<1, 64, 0, s>>>((const v8i*)a, (const v8i*)b, (const v16f*)c, (v16f*)d);
+  return hipGetLastError();
+}
+
 template <int D, bool INT4, bool CAUSAL, bool BF16>
 static hipError_t launch_attention_t(const Dims& Dm, const Ptrs& P, hipStream_t s) {
   AttnParams p;

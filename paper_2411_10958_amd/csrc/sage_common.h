@@ -167,6 +167,7 @@ template <bool BF16> __device__ inline unsigned short store16(float x) {
 hipError_t launch_prologue(const Dims& D, const Ptrs& P, hipStream_t s);
 hipError_t launch_attention(const Dims& D, const Ptrs& P, hipStream_t s);
 hipError_t launch_unpack(const Dims& D, const Ptrs& P, const void* quant_out, hipStream_t s);
+hipError_t launch_debug_mfma_fp8(const void* a, const void* b, const float* c, float* d, hipStream_t s);
 hipError_t launch_debug_qk(const Dims& D, const Ptrs& P, int b, int h, int q_tile, int kv_block,
                            int32_t* out, hipStream_t s);
 
