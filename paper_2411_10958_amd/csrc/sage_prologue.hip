@@ -156,7 +156,10 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
       }
     }
   }
-  int8_t* codes = q_codes + bh * (size_t)nQb * BQ * D;
+  // codes go to LDS in the packed order of this 128-query slab (4 tiles x d/32 steps x 64 lanes
+  // chunks, contiguous in the workspace) and leave as coalesced 16-byte stores
+  __shared__ uint4 s_codes[BQ * D / 16];
+  uint8_t* img = reinterpret_cast<uint8_t*>(s_codes);
 #pragma unroll
   for (int p = 0; p < RPT / 2; ++p) {
     float mx = 0.0f;
@@ -171,9 +174,13 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
       int c[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) c[e] = quant_code(x[i][e], delta, QMAX);
-      *reinterpret_cast<uint2*>(codes + q_code_off(n0 + rg * RPT + i, cg * 8, D)) = pack8<INT4>(c);
+      *reinterpret_cast<uint2*>(img + q_code_off(rg * RPT + i, cg * 8, D)) = pack8<INT4>(c);
     }
   }
+  __syncthreads();
+  uint4* dst = reinterpret_cast<uint4*>(q_codes + (bh * nQb + qb) * (size_t)BQ * D);
+#pragma unroll
+  for (int i = t; i < BQ * D / 16; i += 256) dst[i] = s_codes[i];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -211,14 +218,19 @@ __global__ void __launch_bounds__(256) k_quant_k(const unsigned short* __restric
   mx = wave_max(mx);  // the wavefront's rows are keys 16*wave .. 16*wave+15 of the block
   const float delta = __fdiv_rn(mx, (float)QMAX);
   if ((t & 63) == 0) k_scale[(bh * nKb + kb) * (BKV / KGROUP) + (t >> 6)] = delta;
-  int8_t* codes = k_codes + bh * (size_t)nKb * BKV * D;
+  __shared__ uint4 s_codes[BKV * D / 16];   // the block's packed image, then coalesced 16-byte stores
+  uint8_t* img = reinterpret_cast<uint8_t*>(s_codes);
 #pragma unroll
   for (int i = 0; i < RPT; ++i) {
     int c[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) c[e] = quant_code(x[i][e], delta, QMAX);
-    *reinterpret_cast<uint2*>(codes + k_code_off(n0 + rg * RPT + i, cg * 8, D)) = pack8<INT4>(c);
+    *reinterpret_cast<uint2*>(img + k_code_off(rg * RPT + i, cg * 8, D)) = pack8<INT4>(c);
   }
+  __syncthreads();
+  uint4* dst = reinterpret_cast<uint4*>(k_codes + (bh * nKb + kb) * (size_t)BKV * D);
+#pragma unroll
+  for (int i = t; i < BKV * D / 16; i += 256) dst[i] = s_codes[i];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -295,6 +307,26 @@ __global__ void __launch_bounds__(256) k_delta_s(const unsigned short* __restric
   const int b = (int)(bh / H), h = (int)(bh % H);
   const size_t bhkv = (size_t)b * Hkv + h / (H / Hkv);
   const int n0 = kb * BKV;
+  // the first pass of block means is requested before the K tile so both round trips overlap
+  constexpr int QPT = DS_QROWS * (D / 4) / 256;   // float4 pieces per thread per pass
+  float4 qpre[QPT];
+  auto load_q = [&](int i0) {
+#pragma unroll
+    for (int k = 0; k < QPT; ++k) {
+      const int idx = t + k * 256, r = idx / (D / 4), c4 = idx % (D / 4);
+      qpre[k] = (i0 + r < nQb) ? *reinterpret_cast<const float4*>(q_mean + (bh * nQb + i0 + r) * D + 4 * c4)
+                               : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  auto store_q = [&]() {
+#pragma unroll
+    for (int k = 0; k < QPT; ++k) {
+      const int idx = t + k * 256, r = idx / (D / 4), c4 = idx % (D / 4);
+      s_q[r][4 * c4 + 0] = qpre[k].x; s_q[r][4 * c4 + 1] = qpre[k].y;
+      s_q[r][4 * c4 + 2] = qpre[k].z; s_q[r][4 * c4 + 3] = qpre[k].w;
+    }
+  };
+  load_q(0);
   {
     constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BKV / NRG;
     const int cg = t % NCG, rg = t / NCG;
@@ -321,15 +353,10 @@ __global__ void __launch_bounds__(256) k_delta_s(const unsigned short* __restric
   bool have_b = false;
   double bk[D / 4];
   for (int i0 = 0; i0 < nQb; i0 += DS_QROWS) {
-    const int rows = min(DS_QROWS, nQb - i0);
-    if (i0 > 0) __syncthreads();
-    for (int idx = t; idx < ((rows + 15) & ~15) * (D / 4); idx += 256) {
-      const int r = idx / (D / 4), c4 = idx % (D / 4);
-      float4 q4 = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (r < rows) q4 = *reinterpret_cast<const float4*>(q_mean + (bh * nQb + i0 + r) * D + 4 * c4);
-      s_q[r][4 * c4 + 0] = q4.x; s_q[r][4 * c4 + 1] = q4.y; s_q[r][4 * c4 + 2] = q4.z; s_q[r][4 * c4 + 3] = q4.w;
-    }
+    if (i0 > 0) __syncthreads();       // everyone is done with the previous pass's rows
+    store_q();
     __syncthreads();
+    if (i0 + DS_QROWS < nQb) load_q(i0 + DS_QROWS);   // next pass, in flight under the MFMAs
     if (!have_b) {   // this wavefront's 16 keys as float64 B operands, kept for the whole kernel
 #pragma unroll
       for (int cs = 0; cs < D / 4; ++cs) bk[cs] = (double)s_gk[16 * w + r16][4 * cs + k4];
