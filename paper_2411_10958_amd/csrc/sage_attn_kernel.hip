@@ -8,9 +8,9 @@
 // and row sum are therefore lane-local plus one exchange between the two lane halves, one
 // lane needs one delta_Q and one delta_K per tile (Sec. 3.2's per-thread principle on this
 // accumulator layout), and the FP8 P~ registers are directly the B operand of
-// O^T = V^^T P~^T (v_mfma_f32_32x32x64_f8f6f4, K = 64 = one accumulation block), which is
-// issued with a zero accumulator: R is the per-block FP32 buffer of Sec. 3.4 and is folded
-// into the running O with one FP32 fma per element.
+// O^T = V^^T P~^T (v_mfma_f32_32x32x64_f8f6f4, K = 64 = one accumulation block).  The
+// instruction sums the block's 64 products internally (level 1 of Sec. 3.4) and adds its C
+// operand - the running O - in full FP32 (level 2).
 #include "sage_common.h"
 
 namespace sage {

@@ -184,53 +184,141 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
 }
 
 // ------------------------------------------------------------------------------------------
-// K: smoothing by the token mean, 16-key-group quantization.  One workgroup per 64 keys;
-// a 16-key group is exactly one wavefront's rows.  (Algorithm 1: psi_K(K_j) after
-// K = K - mean(K).)
+// K: smoothing by the token mean, 16-key-group quantization and, in the int4 mode, Delta-S.
+// (Algorithm 1: psi_K(K_j) after K = K - mean(K); Sec. 3.1: Delta-S = q_bar_i . gamma(K)^T.)
+//
+// One workgroup per 64 keys of one (batch, KV head); wavefront w owns keys 16w..16w+15, which
+// is exactly one quantization group.  Lane l holds key 16w + l%16 and the D/4 consecutive
+// channels (D/4)*(l/16) .. +D/4-1, i.e. the wavefront reads 16 whole rows as one contiguous
+// piece.  That is also the B-operand shape of the 16x16x4 FP64 MFMA (lane l supplies
+// B[k = l/16][column l%16]) once contraction slot (step cs, k = l/16) is assigned channel
+// (D/4)*(l/16) + cs - any assignment is valid as long as the A operand uses the same one - so
+// the smoothed keys feed the Delta-S product straight from the registers they were quantized in.
+//
+// Delta-S: D[i, t] = fl32(kappa * <q_bar_i, gamma(K)_t>), inner product in float64 so that the
+// value does not depend on summation order: a small GEMM [nQb x d] . [d x 64] per query head
+// of the KV group, walked 32 query blocks at a time (two independent accumulator chains).
+// v_mfma_f64_16x16x4_f64 sustains about 70 TFLOP/s on the whole chip and, unlike the low-precision
+// matrix instructions, does not run concurrently with other vector work of the SIMD, so this
+// phase costs its own MFMA time (2*nQb*N*d flops per head) on top of the quantization.
+typedef double v4d __attribute__((ext_vector_type(4)));
+
+constexpr int DS_QROWS = 32;    // query-block means staged in LDS per pass: two 16-row MFMA tiles
+
 template <bool BF16, bool INT4, int D>
-__global__ void __launch_bounds__(256) k_quant_k(const unsigned short* __restrict__ K,
+__global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __restrict__ K,
                                                  const float* __restrict__ k_mean,
                                                  float* __restrict__ k_scale, int8_t* __restrict__ k_codes,
-                                                 int N, int nKb) {
-  constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BKV / NRG;  // 4 or 2 rows per thread
+                                                 const float* __restrict__ q_mean,
+                                                 float* __restrict__ delta_s, int N, int nKb, int nQb,
+                                                 int G, float kappa) {
+  constexpr int CPL = D / 4;                       // channels per lane (32 or 16)
   constexpr int QMAX = INT4 ? 7 : 127;
-  const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
+  // LDS row of staged block means: channel c sits at column c + 16*(c / 32) when D = 128, so the
+  // 32 lanes of a half-wavefront (16 rows x 2 channel groups) hit 32 different banks (odd stride)
+  constexpr int SQW = D + (D == 128 ? 48 : 0) + 1;
+  __shared__ uint4 s_codes[BKV * D / 16];          // the block's packed image
+  __shared__ float s_q[INT4 ? DS_QROWS : 1][SQW];
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int r16 = lane & 15, k4 = lane >> 4;
   const int kb = blockIdx.x;
-  const size_t bh = blockIdx.y;
+  const size_t bhkv = blockIdx.y;
   const int n0 = kb * BKV;
-  float mean[8];
+  const int r = 16 * w + r16, c0 = CPL * k4;
+
+  // Delta-S passes: (query head of the group, 32 query blocks); the first pass's block means are
+  // requested before the K rows so that both round trips overlap
+  constexpr int QPT = DS_QROWS * (D / 4) / 256;    // float4 pieces per thread per pass
+  const int npass_h = (nQb + DS_QROWS - 1) / DS_QROWS;
+  const int npass = INT4 ? G * npass_h : 0;
+  float4 qpre[QPT];
+  auto load_q = [&](int p) {
+    const size_t bh = bhkv * G + p / npass_h;
+    const int i0 = (p % npass_h) * DS_QROWS;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) mean[e] = k_mean[bh * D + cg * 8 + e];
-  float x[RPT][8];
-  float mx = 0.0f;
-#pragma unroll
-  for (int i = 0; i < RPT; ++i) {
-    const int n = n0 + rg * RPT + i;
-    if (n < N) {
-      load8<BF16>(K + (bh * N + n) * D + cg * 8, x[i]);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { x[i][e] = __fsub_rn(x[i][e], mean[e]); mx = fmaxf(mx, fabsf(x[i][e])); }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) x[i][e] = 0.0f;
+    for (int k = 0; k < QPT; ++k) {
+      const int idx = t + k * 256, rr = idx / (D / 4), c4 = idx % (D / 4);
+      qpre[k] = (i0 + rr < nQb) ? *reinterpret_cast<const float4*>(q_mean + (bh * nQb + i0 + rr) * D + 4 * c4)
+                                : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+  };
+  auto store_q = [&]() {
+#pragma unroll
+    for (int k = 0; k < QPT; ++k) {
+      const int idx = t + k * 256, rr = idx / (D / 4), c4 = idx % (D / 4);
+      const int col = 4 * c4 + (D == 128 ? 16 * (c4 >> 3) : 0);
+      s_q[rr][col + 0] = qpre[k].x; s_q[rr][col + 1] = qpre[k].y;
+      s_q[rr][col + 2] = qpre[k].z; s_q[rr][col + 3] = qpre[k].w;
+    }
+  };
+  if constexpr (INT4) load_q(0);
+
+  float x[CPL];
+  float mx = 0.0f;
+  if (n0 + r < N) {
+#pragma unroll
+    for (int p = 0; p < CPL / 8; ++p) {
+      float x8[8];
+      load8<BF16>(K + (bhkv * N + n0 + r) * D + c0 + 8 * p, x8);
+      const float4 m0 = *reinterpret_cast<const float4*>(k_mean + bhkv * D + c0 + 8 * p);
+      const float4 m1 = *reinterpret_cast<const float4*>(k_mean + bhkv * D + c0 + 8 * p + 4);
+      const float mean[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        x[8 * p + e] = __fsub_rn(x8[e], mean[e]);
+        mx = fmaxf(mx, fabsf(x[8 * p + e]));
+      }
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < CPL; ++e) x[e] = 0.0f;      // padded keys: codes 0, Delta-S 0
   }
-  mx = wave_max(mx);  // the wavefront's rows are keys 16*wave .. 16*wave+15 of the block
+  mx = wave_max(mx);
   const float delta = __fdiv_rn(mx, (float)QMAX);
-  if ((t & 63) == 0) k_scale[(bh * nKb + kb) * (BKV / KGROUP) + (t >> 6)] = delta;
-  __shared__ uint4 s_codes[BKV * D / 16];   // the block's packed image, then coalesced 16-byte stores
+  if (lane == 0) k_scale[(bhkv * nKb + kb) * (BKV / KGROUP) + w] = delta;
   uint8_t* img = reinterpret_cast<uint8_t*>(s_codes);
 #pragma unroll
-  for (int i = 0; i < RPT; ++i) {
+  for (int p = 0; p < CPL / 8; ++p) {
     int c[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) c[e] = quant_code(x[i][e], delta, QMAX);
-    *reinterpret_cast<uint2*>(img + k_code_off(rg * RPT + i, cg * 8, D)) = pack8<INT4>(c);
+    for (int e = 0; e < 8; ++e) c[e] = quant_code(x[8 * p + e], delta, QMAX);
+    *reinterpret_cast<uint2*>(img + k_code_off(r, c0 + 8 * p, D)) = pack8<INT4>(c);
   }
   __syncthreads();
-  uint4* dst = reinterpret_cast<uint4*>(k_codes + (bh * nKb + kb) * (size_t)BKV * D);
+  uint4* dst = reinterpret_cast<uint4*>(k_codes + (bhkv * nKb + kb) * (size_t)BKV * D);
 #pragma unroll
   for (int i = t; i < BKV * D / 16; i += 256) dst[i] = s_codes[i];
+
+  if constexpr (INT4) {
+    // FP64 MFMA lane map: lane l supplies A[l%16][l/16] and B[l/16][l%16]; result element v of
+    // lane l is row 4*v + l/16, column l%16
+    double bk[CPL];
+#pragma unroll
+    for (int cs = 0; cs < CPL; ++cs) bk[cs] = (double)x[cs];
+    const double kap = (double)kappa;
+    const int qcol = c0 + (D == 128 ? 16 * k4 : 0);
+    for (int p = 0; p < npass; ++p) {
+      if (p > 0) __syncthreads();                  // everyone is done with the previous pass's rows
+      store_q();
+      __syncthreads();
+      if (p + 1 < npass) load_q(p + 1);            // next pass, in flight under the MFMAs
+      v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int cs = 0; cs < CPL; ++cs) {
+        acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[r16][qcol + cs], bk[cs], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[16 + r16][qcol + cs], bk[cs], acc1, 0, 0, 0);
+      }
+      const size_t bh = bhkv * G + p / npass_h;
+      const int i0 = (p % npass_h) * DS_QROWS;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int i = i0 + 4 * v + k4;
+        float* out = delta_s + (bh * nQb + i) * (size_t)nKb * BKV + n0 + r;
+        if (i < nQb) out[0] = (float)(kap * acc0[v]);
+        if (i + 16 < nQb) out[(size_t)16 * nKb * BKV] = (float)(kap * acc1[v]);
+      }
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -284,102 +372,6 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
 }
 
 // ------------------------------------------------------------------------------------------
-// Delta-S (Sec. 3.1): D[i, t] = fl32(kappa * <q_bar_i, gamma(K)_t>), inner product in float64
-// so that the value does not depend on summation order.  A small GEMM per (batch, query head):
-// [nQb x d] . [d x N], run on the FP64 matrix pipe (v_mfma_f64_16x16x4f64).  One workgroup per
-// 64 keys; wavefront w owns keys 16w..16w+15 and keeps their gamma(K) (as float64 B operands)
-// in registers while it walks the query blocks 16 at a time.
-typedef double v4d __attribute__((ext_vector_type(4)));
-
-constexpr int DS_QROWS = 32;    // query-block means staged in LDS per pass: two 16-row MFMA tiles
-
-template <bool BF16, int D>
-__global__ void __launch_bounds__(256) k_delta_s(const unsigned short* __restrict__ K,
-                                                 const float* __restrict__ k_mean,
-                                                 const float* __restrict__ q_mean,
-                                                 float* __restrict__ delta_s, int N, int nQb, int nKb,
-                                                 int H, int Hkv, float kappa) {
-  __shared__ float s_gk[BKV][D + 1];
-  __shared__ float s_q[DS_QROWS][D + 1];
-  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-  const int kb = blockIdx.x;
-  const size_t bh = blockIdx.y;
-  const int b = (int)(bh / H), h = (int)(bh % H);
-  const size_t bhkv = (size_t)b * Hkv + h / (H / Hkv);
-  const int n0 = kb * BKV;
-  // the first pass of block means is requested before the K tile so both round trips overlap
-  constexpr int QPT = DS_QROWS * (D / 4) / 256;   // float4 pieces per thread per pass
-  float4 qpre[QPT];
-  auto load_q = [&](int i0) {
-#pragma unroll
-    for (int k = 0; k < QPT; ++k) {
-      const int idx = t + k * 256, r = idx / (D / 4), c4 = idx % (D / 4);
-      qpre[k] = (i0 + r < nQb) ? *reinterpret_cast<const float4*>(q_mean + (bh * nQb + i0 + r) * D + 4 * c4)
-                               : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-  };
-  auto store_q = [&]() {
-#pragma unroll
-    for (int k = 0; k < QPT; ++k) {
-      const int idx = t + k * 256, r = idx / (D / 4), c4 = idx % (D / 4);
-      s_q[r][4 * c4 + 0] = qpre[k].x; s_q[r][4 * c4 + 1] = qpre[k].y;
-      s_q[r][4 * c4 + 2] = qpre[k].z; s_q[r][4 * c4 + 3] = qpre[k].w;
-    }
-  };
-  load_q(0);
-  {
-    constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BKV / NRG;
-    const int cg = t % NCG, rg = t / NCG;
-#pragma unroll
-    for (int i = 0; i < RPT; ++i) {
-      const int r = rg * RPT + i;
-      float x[8];
-      if (n0 + r < N) {
-        load8<BF16>(K + (bhkv * N + n0 + r) * D + cg * 8, x);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = __fsub_rn(x[e], k_mean[bhkv * D + cg * 8 + e]);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = 0.0f;
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) s_gk[r][cg * 8 + e] = x[e];
-    }
-  }
-  // operand lane map of the 16x16x4 FP64 MFMA: lane l supplies A[l%16][l/16] and B[l/16][l%16];
-  // result: lane l, element v holds row 4*v + l/16, column l%16
-  const int r16 = lane & 15, k4 = lane >> 4;
-  const double kap = (double)kappa;
-  bool have_b = false;
-  double bk[D / 4];
-  for (int i0 = 0; i0 < nQb; i0 += DS_QROWS) {
-    if (i0 > 0) __syncthreads();       // everyone is done with the previous pass's rows
-    store_q();
-    __syncthreads();
-    if (i0 + DS_QROWS < nQb) load_q(i0 + DS_QROWS);   // next pass, in flight under the MFMAs
-    if (!have_b) {   // this wavefront's 16 keys as float64 B operands, kept for the whole kernel
-#pragma unroll
-      for (int cs = 0; cs < D / 4; ++cs) bk[cs] = (double)s_gk[16 * w + r16][4 * cs + k4];
-      have_b = true;
-    }
-    // two independent accumulator chains (rows 0..15 and 16..31 of the pass) keep the pipe busy
-    v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-    for (int cs = 0; cs < D / 4; ++cs) {
-      acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[r16][4 * cs + k4], bk[cs], acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[16 + r16][4 * cs + k4], bk[cs], acc1, 0, 0, 0);
-    }
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int i = i0 + 4 * v + k4;
-      float* dst = delta_s + (bh * nQb + i) * (size_t)nKb * BKV + n0 + 16 * w + r16;
-      if (i < nQb) dst[0] = (float)(kap * acc0[v]);
-      if (i + 16 < nQb) dst[(size_t)16 * nKb * BKV] = (float)(kap * acc1[v]);
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------
 // Copies from the packed workspace to plain layouts (used only by sage_attn_quant).
 __global__ void k_unpack_codes(const int8_t* __restrict__ packed, int8_t* __restrict__ plain, int N,
                                int d, size_t slab, int which, int e4m3_ints) {
@@ -412,11 +404,10 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
   k_col_stats<BF16, D><<<dim3((Dm.N + STAT_ROWS - 1) / STAT_ROWS, BHkv), 256, 0, s>>>(k, v, P.k_sum, P.v_max, Dm.N);
   k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_max, P.k_mean, P.v_scale, nstat, Dm.N);
   k_quant_q<BF16, INT4, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.nQb);
-  k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, Dm.N, Dm.nKb);
+  k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
+                                                              P.delta_s, Dm.N, Dm.nKb, Dm.nQb, Dm.H / Dm.Hkv,
+                                                              Dm.kappa);
   k_quant_v<BF16, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, P.v_codes, Dm.N, Dm.nKb);
-  if constexpr (INT4)
-    k_delta_s<BF16, D><<<dim3(Dm.nKb, BH), 256, 0, s>>>(k, P.k_mean, P.q_mean, P.delta_s, Dm.N, Dm.nQb,
-                                                        Dm.nKb, Dm.H, Dm.Hkv, Dm.kappa);
   return hipGetLastError();
 }
 
