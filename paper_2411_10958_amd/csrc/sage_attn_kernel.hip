@@ -190,15 +190,29 @@ __device__ __forceinline__ void block_pv(RowState<D>& st, const v4i (&va)[2 * (D
 #define SAGE_WAVES_PER_SIMD 2
 #endif
 
+// Global -> LDS copies without a register stop (the LDS-DMA form of the global load: lane l's
+// 16 or 4 bytes land at LDS byte m0 + 16*l or m0 + 4*l).  Issued from inline assembly so that
+// the wait for them is placed by hand - one vmcnt wait right before the barrier that publishes a
+// stage - instead of in front of every later LDS read.  gbase is wavefront-uniform.
+__device__ __forceinline__ void dma_b128(const void* gbase, unsigned voff, unsigned lds_byte) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_byte), "v"(voff), "s"(gbase) : "memory");
+}
+__device__ __forceinline__ void dma_b32(const void* gbase, unsigned voff, unsigned lds_byte) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+               :: "s"(lds_byte), "v"(voff), "s"(gbase) : "memory");
+}
+
 template <int D, bool INT4, bool CAUSAL, bool BF16>
 __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const AttnParams p) {
   constexpr int KS = D / 32;          // 32-channel steps of the score product
   constexpr int CT = D / 32;          // 32-channel tiles of the output
   constexpr int KC = D * BKV / 16;    // 16-byte chunks of one K^ (or V^) block
   constexpr int CPT = KC / 256;       // chunks per thread per block copy (2 or 1)
-  __shared__ v4i lds_k[2][KC];
-  __shared__ v4i lds_v[2][KC];
-  __shared__ v4i lds_x[2][32];        // 64 Delta-S floats, then the block's 4 key-group scales
+  constexpr int NST = 3;              // LDS stages: block j is read while j+1 and j+2 arrive
+  constexpr int XC = 32;              // chunks of the small part: 64 Delta-S floats, then 4 key-group scales
+  constexpr int STAGE = 2 * KC + XC;  // chunks per stage: K^, V^, small part
+  __shared__ v4i lds[NST][STAGE];
 
   // XCD-aware tile order: consecutive workgroup ids land on different XCDs (8 of them), so
   // give every XCD a contiguous range of tiles - tiles of one head then share one L2.
@@ -218,33 +232,35 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
 
   const v4i* gk = reinterpret_cast<const v4i*>(p.k_codes + bhkv * (size_t)p.nKb * BKV * D);
   const v4i* gv = reinterpret_cast<const v4i*>(p.v_codes + bhkv * (size_t)p.nKb * BKV * D);
-  const v4i* gd = INT4 ? reinterpret_cast<const v4i*>(p.delta_s + ((size_t)bh * p.nQb + qb) * p.nKb * BKV) : nullptr;
-  const v4i* gs = reinterpret_cast<const v4i*>(p.k_scale + bhkv * (size_t)p.nKb * 4);
+  const float* gd = INT4 ? p.delta_s + ((size_t)bh * p.nQb + qb) * p.nKb * BKV : nullptr;
+  const float* gs = p.k_scale + bhkv * (size_t)p.nKb * 4;
 
   int nblk = p.nKb;
   if (CAUSAL) nblk = min(nblk, (qb * BQ + BQ - 1) / BKV + 1);
 
-  // Block copies are staged through registers: global loads are issued at the top of an
-  // iteration and written to the other LDS stage at its end, so their latency hides under the
-  // block's arithmetic.  The copy is the identity on 16-byte chunk indices.
-  v4i rk[CPT], rv[CPT], rx = {0, 0, 0, 0};
-  auto fetch = [&](int j) {
+  // Block copies: every wavefront moves its quarter of the K^ and V^ chunks (the copy is the
+  // identity on chunk indices), wavefront 0 the block's Delta-S row, wavefront 1 the 4 scales.
+  const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)&lds[0][0];
+  auto issue = [&](int j, int st) {
+    const unsigned sb = lds0 + (unsigned)st * (STAGE * 16);
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
-      rk[i] = gk[(size_t)j * KC + i * 256 + t];
-      rv[i] = gv[(size_t)j * KC + i * 256 + t];
+      dma_b128(gk + (size_t)j * KC + i * 256, (unsigned)t * 16, sb + (unsigned)(i * 256 + 64 * w) * 16);
+      dma_b128(gv + (size_t)j * KC + i * 256, (unsigned)t * 16, sb + (unsigned)(KC + i * 256 + 64 * w) * 16);
     }
-    if (t < 16) { if constexpr (INT4) rx = gd[j * 16 + t]; }
-    else if (t == 16) rx = gs[j];
-  };
-  auto stash = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-      lds_k[buf][i * 256 + t] = rk[i];
-      lds_v[buf][i * 256 + t] = rv[i];
+    if (w == 0) {
+      if constexpr (INT4) dma_b32(gd + (size_t)j * BKV, (unsigned)lane * 4, sb + 2 * KC * 16);
+    } else if (w == 1) {
+      if (lane < 4) dma_b32(gs + (size_t)j * 4, (unsigned)lane * 4, sb + 2 * KC * 16 + 256);
     }
-    if (t <= 16) lds_x[buf][t] = rx;
   };
+  // Every wavefront issues at least 2*CPT copies per block, in block order, and loads complete in
+  // order: "at most 2*CPT outstanding" therefore means every block but the newest has landed.
+  auto wait_all_but_newest = [&]() {
+    if constexpr (CPT == 2) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)" ::: "memory");
+  };
+  auto wait_all = [&]() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); };
 
   // ---- this wavefront's Q^ operands (registers, for the whole kernel) and scale ----
   v4i qreg[KS];
@@ -277,29 +293,32 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   n_plain = __builtin_amdgcn_readfirstlane(n_plain);
   n_act = __builtin_amdgcn_readfirstlane(n_act);
 
-  // Software pipeline, one barrier per block.  At the top of iteration j the registers hold the
-  // K^ operands of block j (read from LDS during iteration j-1) and the global copy of block
-  // j+1 (loaded during iteration j-1); LDS stage j%2 holds block j.  The iteration
+  // Software pipeline, one barrier per block, three LDS stages.  At the top of iteration j the
+  // registers hold the K^ operands of block j (read from LDS during iteration j-1), stage j%3
+  // holds block j and the copy of block j+1 is in flight (issued during iteration j-1).  The
+  // iteration
   //   1. issues the score MFMAs of block j, then (while they run) reads block j's Delta-S,
-  //      scales and V^ operands, writes block j+1 into the other stage and starts the global
-  //      loads of block j+2,
+  //      scales and V^ operands and starts the copy of block j+2 into the stage that held block
+  //      j-1 (every wavefront passed iteration j-1's barrier with its reads of that block done),
   //   2. runs dequantization + softmax of block j,
-  //   3. barrier: block j+1 is now visible and nobody needs K^_j / Delta-S_j any more,
+  //   3. waits for its own share of block j+1 (issued a whole iteration ago) and meets the other
+  //      wavefronts at the barrier: block j+1 is now visible,
   //   4. starts the LDS reads of K^_{j+1} and runs P~V + the O update of block j under them.
-  // So no LDS or global latency sits between a barrier and the MFMAs that follow it.
+  // So no LDS or global latency sits between a barrier and the MFMAs that follow it, and a
+  // copy has about one and a half iterations to arrive.
   v4i ka[2 * KS], va[2 * CT];
   v4f dsr[2][4];
   float dk0 = 0.0f, dk1 = 0.0f;
-  auto read_k = [&](int buf) {
+  auto read_k = [&](int stg) {
 #pragma unroll
-    for (int i = 0; i < 2 * KS; ++i) ka[i] = lds_k[buf][i * 64 + lane];
+    for (int i = 0; i < 2 * KS; ++i) ka[i] = lds[stg][i * 64 + lane];
   };
-  auto read_v = [&](int buf) {
+  auto read_v = [&](int stg) {
 #pragma unroll
-    for (int i = 0; i < 2 * CT; ++i) va[i] = lds_v[buf][i * 64 + lane];
+    for (int i = 0; i < 2 * CT; ++i) va[i] = lds[stg][KC + i * 64 + lane];
   };
-  auto read_x = [&](int buf) {
-    const float* lx = reinterpret_cast<const float*>(lds_x[buf]);
+  auto read_x = [&](int stg) {
+    const float* lx = reinterpret_cast<const float*>(&lds[stg][2 * KC]);
     if constexpr (INT4) {
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt) {
@@ -311,15 +330,22 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     dk0 = lx[64 + half];
     dk1 = lx[66 + half];
   };
-  fetch(0);
-  stash(0);
-  if (nblk > 1) fetch(1);
+  // The compiler does not see the copies above, and it would otherwise leave its waits for the
+  // ordinary loads of Q^ and the scale inside the loop, where they would also wait for copies in
+  // flight: use those registers here so that the loads are complete before the first copy.
+#pragma unroll
+  for (int s = 0; s < KS; ++s) asm volatile("" :: "v"(qreg[s]));
+  asm volatile("" :: "v"(dq));
+  issue(0, 0);
+  if (nblk > 1) { issue(1, 1); wait_all_but_newest(); } else { wait_all(); }
   __syncthreads();
   read_k(0);
 
+  int cur = 0;   // stage of block j
 #define SAGE_ITER(MASKED_, ACTIVE_)                                                                  \
   do {                                                                                               \
-    const int cur = j & 1;                                                                           \
+    const int nx1 = cur == NST - 1 ? 0 : cur + 1;                                                    \
+    const int nx2 = nx1 == NST - 1 ? 0 : nx1 + 1;                                                    \
     v16i acc[2];                                                                                     \
     if (ACTIVE_) {                                                                                   \
       qk_tile<D, INT4>(ka, qreg, acc);                                                               \
@@ -327,17 +353,19 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
       read_x(cur);                                                                                   \
       read_v(cur);                                                                                   \
     }                                                                                                \
-    if (j + 1 < nblk) stash(cur ^ 1);                                                                \
-    if (j + 2 < nblk) fetch(j + 2);                                                                  \
+    const bool more = j + 2 < nblk;                                                                  \
+    if (more) issue(j + 2, nx2);                                                                     \
     __builtin_amdgcn_sched_barrier(0);                                                               \
     v8i pb;                                                                                          \
     float alpha = 1.0f;                                                                              \
     if (ACTIVE_)                                                                                     \
       alpha = block_softmax<D, INT4, CAUSAL, MASKED_>(st, acc, dsr, dk0, dk1, pb, dq, p.kappa, lane,  \
                                                       j * BKV, query, p.N);                          \
+    if (more) wait_all_but_newest(); else wait_all();                                                \
     __syncthreads();                                                                                 \
-    if (j + 1 < n_act) read_k(cur ^ 1);                                                              \
+    if (j + 1 < n_act) read_k(nx1);                                                                  \
     if (ACTIVE_) block_pv<D>(st, va, pb, alpha);                                                     \
+    cur = nx1;                                                                                       \
   } while (0)
   int j = 0;
   for (; j < n_plain; ++j) SAGE_ITER(false, true);
