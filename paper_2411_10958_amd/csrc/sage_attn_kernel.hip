@@ -36,48 +36,38 @@ struct AttnParams {
 // two 32-channel steps feed one v_mfma_f32_32x32x64_f8f6f4 (both operands list their 64 channels
 // in the same order: the 16 of step 2s, then the 16 of step 2s+1, per lane half); the FP32
 // accumulators hold the exact integers.  Either way the result is returned as raw 32-bit lanes.
-template <int D, bool INT4>
-__device__ __forceinline__ void qk_tile(const v4i (&ka)[2 * (D / 32)], const v4i (&qreg)[D / 32],
-                                        v16i (&acc)[2]) {
+template <int D, bool INT4, int KT>
+__device__ __forceinline__ void qk_half(const v4i (&ka)[2 * (D / 32)], const v4i (&qreg)[D / 32], v16i& acc) {
   if constexpr (INT4) {
-    v16f accf[2];
+    v16f accf;
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) accf[kt][v] = 0.0f;
-    }
+    for (int v = 0; v < 16; ++v) accf[v] = 0.0f;
 #pragma unroll
     for (int s = 0; s < D / 64; ++s) {
       v8i bq;
       bq[0] = qreg[2 * s][0]; bq[1] = qreg[2 * s][1]; bq[2] = qreg[2 * s][2]; bq[3] = qreg[2 * s][3];
       bq[4] = qreg[2 * s + 1][0]; bq[5] = qreg[2 * s + 1][1]; bq[6] = qreg[2 * s + 1][2]; bq[7] = qreg[2 * s + 1][3];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        const v4i a0 = ka[(2 * s) * 2 + kt], a1 = ka[(2 * s + 1) * 2 + kt];
-        v8i a;
-        a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
-        a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
-        accf[kt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, bq, accf[kt], 0, 0, 0, 0, 0, 0);
-      }
+      const v4i a0 = ka[(2 * s) * 2 + KT], a1 = ka[(2 * s + 1) * 2 + KT];
+      v8i a;
+      a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
+      a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
+      accf = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, bq, accf, 0, 0, 0, 0, 0, 0);
     }
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[kt][v] = __float_as_int(accf[kt][v]);
-    }
+    for (int v = 0; v < 16; ++v) acc[v] = __float_as_int(accf[v]);
   } else {
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int v = 0; v < 16; ++v) acc[v] = 0;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[kt][v] = 0;
-    }
-#pragma unroll
-    for (int s = 0; s < D / 32; ++s) {
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-        acc[kt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[s * 2 + kt], qreg[s], acc[kt], 0, 0, 0);
-    }
+    for (int s = 0; s < D / 32; ++s)
+      acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[s * 2 + KT], qreg[s], acc, 0, 0, 0);
   }
+}
+template <int D, bool INT4>
+__device__ __forceinline__ void qk_tile(const v4i (&ka)[2 * (D / 32)], const v4i (&qreg)[D / 32],
+                                        v16i (&acc)[2]) {
+  qk_half<D, INT4, 0>(ka, qreg, acc[0]);
+  qk_half<D, INT4, 1>(ka, qreg, acc[1]);
 }
 
 // Per-wavefront running state of Algorithm 1's inner loop.
@@ -87,13 +77,13 @@ template <int D> struct RowState {
   float l_run;      // this lane's share of the running sum of 448 * P~
 };
 
-// Middle part of one block of Algorithm 1's inner loop for one wavefront: the raw scores in
-// `acc` are dequantized (+ Delta-S) in place, go through the online softmax and become the FP8
-// P~ operand `pb`.  Returns alpha = 2^(m_old - m_new).
+// Middle part of one block of Algorithm 1's inner loop for one wavefront, in two steps.
+// softmax_max: the raw scores in `acc` are dequantized (+ Delta-S) in place and the running max is
+// updated; returns alpha = 2^(m_old - m_new) and, in m_sub, the exponent offset of this block.
 template <int D, bool INT4, bool CAUSAL, bool MASKED>
-__device__ __forceinline__ float block_softmax(RowState<D>& st, v16i (&acc)[2], const v4f (&dsr)[2][4],
-                                               float dk0, float dk1, v8i& pb, float dq, float kappa,
-                                               int lane, int key0, int query, int N) {
+__device__ __forceinline__ float softmax_max(RowState<D>& st, v16i (&acc)[2], const v4f (&dsr)[2][4],
+                                             float dk0, float dk1, float dq, float kappa, int lane,
+                                             int key0, int query, int N, float& m_sub) {
   const int half = lane >> 5;
   // ---- dequantize, add Delta-S (Algorithm 1, score line), in base 2; S overwrites acc ----
 #pragma unroll
@@ -123,7 +113,7 @@ __device__ __forceinline__ float block_softmax(RowState<D>& st, v16i (&acc)[2], 
       }
     }
   }
-  // ---- online softmax (Eq. 1 / Algorithm 1) ----
+  // ---- running max (Eq. 1 / Algorithm 1) ----
   float mx = fmaxf(__int_as_float(acc[0][0]), __int_as_float(acc[1][0]));
 #pragma unroll
   for (int v = 1; v < 16; ++v)   // one v_max3_f32 per step
@@ -136,27 +126,28 @@ __device__ __forceinline__ float block_softmax(RowState<D>& st, v16i (&acc)[2], 
   }
   const float m_new = fmaxf(st.m_run, mx);
   const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_new);   // 2^-inf = 0 on the first block
-  const float m_sub = m_new - LOG2_448;                           // folds the *448 of Sec. 3.3
+  m_sub = m_new - LOG2_448;                                       // folds the *448 of Sec. 3.3
   st.m_run = m_new;
-  float ls = 0.0f;
-#pragma unroll
-  for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      float e[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        e[r] = __builtin_amdgcn_exp2f(__int_as_float(acc[kt][4 * g + r]) - m_sub);   // = 448 * P~
-        ls += e[r];
-      }
-      int wd = __float_as_int(e[0]);   // any value: both halves are overwritten below
-      wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[0], e[1], wd, false);
-      wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[2], e[3], wd, true);
-      pb[kt * 4 + g] = wd;
-    }
-  }
-  st.l_run = __fmaf_rn(alpha, st.l_run, ls);
   return alpha;
+}
+
+// softmax_exp: key tile KT of the block: 448 * P~ = 2^(S - m_sub), its row-sum share added to ls, and
+// the FP8 codes written into words 4*KT .. 4*KT+3 of the P~ operand.
+template <int KT>
+__device__ __forceinline__ void softmax_exp(const v16i (&acc)[2], float m_sub, v8i& pb, float& ls) {
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    float e[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      e[r] = __builtin_amdgcn_exp2f(__int_as_float(acc[KT][4 * g + r]) - m_sub);
+      ls += e[r];
+    }
+    int wd = __float_as_int(e[0]);   // any value: both halves are overwritten below
+    wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[0], e[1], wd, false);
+    wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[2], e[3], wd, true);
+    pb[KT * 4 + g] = wd;
+  }
 }
 
 // Second half: the two-level accumulation of Sec. 3.4 on gfx950.  One v_mfma_f32_32x32x64_f8f6f4 has
@@ -166,8 +157,7 @@ __device__ __forceinline__ float block_softmax(RowState<D>& st, v16i (&acc)[2], 
 // precision).  So O is the C/D operand, pre-scaled by alpha = 2^(m_old - m_new) only when some
 // query of the wavefront actually moved its running max in this block.
 template <int D>
-__device__ __forceinline__ void block_pv(RowState<D>& st, const v4i (&va)[2 * (D / 32)], const v8i& pb,
-                                         float alpha) {
+__device__ __forceinline__ void block_rescale(RowState<D>& st, float alpha) {
   if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
     for (int ct = 0; ct < D / 32; ++ct) {
@@ -175,6 +165,9 @@ __device__ __forceinline__ void block_pv(RowState<D>& st, const v4i (&va)[2 * (D
       for (int v = 0; v < 16; ++v) st.O[ct][v] = __fmul_rn(alpha, st.O[ct][v]);
     }
   }
+}
+template <int D>
+__device__ __forceinline__ void block_pv(RowState<D>& st, const v4i (&va)[2 * (D / 32)], const v8i& pb) {
 #pragma unroll
   for (int ct = 0; ct < D / 32; ++ct) {
     v8i a;
@@ -293,19 +286,23 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   n_plain = __builtin_amdgcn_readfirstlane(n_plain);
   n_act = __builtin_amdgcn_readfirstlane(n_act);
 
-  // Software pipeline, one barrier per block, three LDS stages.  At the top of iteration j the
-  // registers hold the K^ operands of block j (read from LDS during iteration j-1), stage j%3
-  // holds block j and the copy of block j+1 is in flight (issued during iteration j-1).  The
-  // iteration
-  //   1. issues the score MFMAs of block j, then (while they run) reads block j's Delta-S,
-  //      scales and V^ operands and starts the copy of block j+2 into the stage that held block
-  //      j-1 (every wavefront passed iteration j-1's barrier with its reads of that block done),
-  //   2. runs dequantization + softmax of block j,
-  //   3. waits for its own share of block j+1 (issued a whole iteration ago) and meets the other
-  //      wavefronts at the barrier: block j+1 is now visible,
-  //   4. starts the LDS reads of K^_{j+1} and runs P~V + the O update of block j under them.
-  // So no LDS or global latency sits between a barrier and the MFMAs that follow it, and a
-  // copy has about one and a half iterations to arrive.
+  // Software pipeline, one barrier per block, three LDS stages; every MFMA is issued ahead of
+  // vector work that does not depend on it.  On entry to iteration j the raw scores of block j are
+  // in `acc` (their MFMAs were issued during iteration j-1), stage j%3 holds block j, the copy of
+  // block j+1 is in flight and the P~V MFMAs of block j-1 are still running.  The iteration
+  //   A.  reads block j's Delta-S row and scales from LDS, dequantizes the scores and updates the
+  //       running max (under P~V of block j-1),
+  //   B.  waits for its own share of block j+1 and meets the other wavefronts at the barrier:
+  //       block j+1 is visible, and nobody reads block j-1's stage any more,
+  //   C.  starts the LDS reads of K^_{j+1} and the copy of block j+2 into block j-1's stage,
+  //   D.  exponentials, row sum and FP8 codes of key tile 0 (covers the latency of C's reads),
+  //   E0. issues the score MFMAs of block j+1, key tile 0, into the registers D has just freed,
+  //   F.  starts the LDS reads of V^_j,
+  //   G.  exponentials, row sum and FP8 codes of key tile 1 (under E0's MFMAs),
+  //   E1. issues the score MFMAs of block j+1, key tile 1,
+  //   H.  rescales O if a running max moved and issues the P~V MFMAs of block j.
+  // Past the wavefront's last block C and E work on a stale stage (in bounds, results unused):
+  // unconditional, so that no register stays live for the sake of a path not taken.
   v4i ka[2 * KS], va[2 * CT];
   v4f dsr[2][4];
   float dk0 = 0.0f, dk1 = 0.0f;
@@ -340,31 +337,43 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   if (nblk > 1) { issue(1, 1); wait_all_but_newest(); } else { wait_all(); }
   __syncthreads();
   read_k(0);
+  v16i acc[2];
+  qk_tile<D, INT4>(ka, qreg, acc);    // block 0 holds a visible key for every query
 
   int cur = 0;   // stage of block j
 #define SAGE_ITER(MASKED_, ACTIVE_)                                                                  \
   do {                                                                                               \
     const int nx1 = cur == NST - 1 ? 0 : cur + 1;                                                    \
     const int nx2 = nx1 == NST - 1 ? 0 : nx1 + 1;                                                    \
-    v16i acc[2];                                                                                     \
-    if (ACTIVE_) {                                                                                   \
-      qk_tile<D, INT4>(ka, qreg, acc);                                                               \
-      __builtin_amdgcn_sched_barrier(0);                                                             \
-      read_x(cur);                                                                                   \
-      read_v(cur);                                                                                   \
-    }                                                                                                \
-    const bool more = j + 2 < nblk;                                                                  \
-    if (more) issue(j + 2, nx2);                                                                     \
-    __builtin_amdgcn_sched_barrier(0);                                                               \
-    v8i pb;                                                                                          \
-    float alpha = 1.0f;                                                                              \
+    float m_sub = 0.0f, alpha = 1.0f;                                                                \
+    if (ACTIVE_) read_x(cur);                                                                        \
     if (ACTIVE_)                                                                                     \
-      alpha = block_softmax<D, INT4, CAUSAL, MASKED_>(st, acc, dsr, dk0, dk1, pb, dq, p.kappa, lane,  \
-                                                      j * BKV, query, p.N);                          \
-    if (more) wait_all_but_newest(); else wait_all();                                                \
+      alpha = softmax_max<D, INT4, CAUSAL, MASKED_>(st, acc, dsr, dk0, dk1, dq, p.kappa, lane,       \
+                                                    j * BKV, query, p.N, m_sub);              /* A */ \
+    __builtin_amdgcn_sched_barrier(0);                                                               \
+    wait_all();                                                                               /* B */ \
     __syncthreads();                                                                                 \
-    if (j + 1 < n_act) read_k(nx1);                                                                  \
-    if (ACTIVE_) block_pv<D>(st, va, pb, alpha);                                                     \
+    if (ACTIVE_) read_k(nx1);                                                                 /* C */ \
+    if (j + 2 < nblk) issue(j + 2, nx2);                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                               \
+    if (ACTIVE_) {                                                                                   \
+      v8i pb;                                                                                        \
+      float ls = 0.0f;                                                                               \
+      softmax_exp<0>(acc, m_sub, pb, ls);                                                     /* D */ \
+      __builtin_amdgcn_sched_barrier(0);                                                             \
+      qk_half<D, INT4, 0>(ka, qreg, acc[0]);                                                  /* E0 */ \
+      __builtin_amdgcn_sched_barrier(0);                                                             \
+      read_v(cur);                                                                            /* F */ \
+      __builtin_amdgcn_sched_barrier(0);                                                             \
+      softmax_exp<1>(acc, m_sub, pb, ls);                                                     /* G */ \
+      st.l_run = __fmaf_rn(alpha, st.l_run, ls);                                                     \
+      __builtin_amdgcn_sched_barrier(0);                                                             \
+      qk_half<D, INT4, 1>(ka, qreg, acc[1]);                                                  /* E1 */ \
+      __builtin_amdgcn_sched_barrier(0);                                                             \
+      block_rescale<D>(st, alpha);                                                            /* H */ \
+      block_pv<D>(st, va, pb);                                                                       \
+      __builtin_amdgcn_sched_barrier(0);                                                             \
+    }                                                                                                \
     cur = nx1;                                                                                       \
   } while (0)
   int j = 0;
