@@ -36,38 +36,42 @@ struct AttnParams {
 // two 32-channel steps feed one v_mfma_f32_32x32x64_f8f6f4 (both operands list their 64 channels
 // in the same order: the 16 of step 2s, then the 16 of step 2s+1, per lane half); the FP32
 // accumulators hold the exact integers.  Either way the result is returned as raw 32-bit lanes.
-template <int D, bool INT4, int KT>
-__device__ __forceinline__ void qk_half(const v4i (&ka)[2 * (D / 32)], const v4i (&qreg)[D / 32], v16i& acc) {
+// The product is issued one MFMA ("step") at a time so that the steps can be spread between
+// pieces of vector work: step I works on key tile I % 2 and contraction piece I / 2 (64 channels
+// in the INT4 mode, 32 in the INT8 mode); the first piece of a tile starts from a zero accumulator.
+template <int D, bool INT4> constexpr int qk_steps() { return INT4 ? 2 * (D / 64) : 2 * (D / 32); }
+
+template <int D, bool INT4, int I>
+__device__ __forceinline__ void qk_step(const v4i (&ka)[2 * (D / 32)], const v4i (&qreg)[D / 32],
+                                        v16i (&acc)[2]) {
+  constexpr int KT = I & 1, S = I >> 1;
   if constexpr (INT4) {
-    v16f accf;
+    v8i bq, a;
+    bq[0] = qreg[2 * S][0]; bq[1] = qreg[2 * S][1]; bq[2] = qreg[2 * S][2]; bq[3] = qreg[2 * S][3];
+    bq[4] = qreg[2 * S + 1][0]; bq[5] = qreg[2 * S + 1][1]; bq[6] = qreg[2 * S + 1][2]; bq[7] = qreg[2 * S + 1][3];
+    const v4i a0 = ka[(2 * S) * 2 + KT], a1 = ka[(2 * S + 1) * 2 + KT];
+    a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
+    a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
+    v16f c;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) accf[v] = 0.0f;
+    for (int v = 0; v < 16; ++v) c[v] = S == 0 ? 0.0f : __int_as_float(acc[KT][v]);
+    c = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, bq, c, 0, 0, 0, 0, 0, 0);
 #pragma unroll
-    for (int s = 0; s < D / 64; ++s) {
-      v8i bq;
-      bq[0] = qreg[2 * s][0]; bq[1] = qreg[2 * s][1]; bq[2] = qreg[2 * s][2]; bq[3] = qreg[2 * s][3];
-      bq[4] = qreg[2 * s + 1][0]; bq[5] = qreg[2 * s + 1][1]; bq[6] = qreg[2 * s + 1][2]; bq[7] = qreg[2 * s + 1][3];
-      const v4i a0 = ka[(2 * s) * 2 + KT], a1 = ka[(2 * s + 1) * 2 + KT];
-      v8i a;
-      a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
-      a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
-      accf = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, bq, accf, 0, 0, 0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = __float_as_int(accf[v]);
+    for (int v = 0; v < 16; ++v) acc[KT][v] = __float_as_int(c[v]);
   } else {
+    v16i c;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0;
-#pragma unroll
-    for (int s = 0; s < D / 32; ++s)
-      acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[s * 2 + KT], qreg[s], acc, 0, 0, 0);
+    for (int v = 0; v < 16; ++v) c[v] = S == 0 ? 0 : acc[KT][v];
+    acc[KT] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[S * 2 + KT], qreg[S], c, 0, 0, 0);
   }
 }
-template <int D, bool INT4>
+template <int D, bool INT4, int I = 0>
 __device__ __forceinline__ void qk_tile(const v4i (&ka)[2 * (D / 32)], const v4i (&qreg)[D / 32],
                                         v16i (&acc)[2]) {
-  qk_half<D, INT4, 0>(ka, qreg, acc[0]);
-  qk_half<D, INT4, 1>(ka, qreg, acc[1]);
+  if constexpr (I < qk_steps<D, INT4>()) {
+    qk_step<D, INT4, I>(ka, qreg, acc);
+    qk_tile<D, INT4, I + 1>(ka, qreg, acc);
+  }
 }
 
 // Per-wavefront running state of Algorithm 1's inner loop.
@@ -77,43 +81,31 @@ template <int D> struct RowState {
   float l_run;      // this lane's share of the running sum of 448 * P~
 };
 
-// Middle part of one block of Algorithm 1's inner loop for one wavefront, in two steps.
-// softmax_max: the raw scores in `acc` are dequantized (+ Delta-S) in place and the running max is
-// updated; returns alpha = 2^(m_old - m_new) and, in m_sub, the exponent offset of this block.
-template <int D, bool INT4, bool CAUSAL, bool MASKED>
-__device__ __forceinline__ float softmax_max(RowState<D>& st, v16i (&acc)[2], const v4f (&dsr)[2][4],
-                                             float dk0, float dk1, float dq, float kappa, int lane,
-                                             int key0, int query, int N, float& m_sub) {
-  const int half = lane >> 5;
-  // ---- dequantize, add Delta-S (Algorithm 1, score line), in base 2; S overwrites acc ----
+// Middle part of one block of Algorithm 1's inner loop for one wavefront, cut into pieces of four
+// keys (one "group": registers 4G..4G+3 of key tile KT) so that MFMAs can be issued between them.
+//
+// dequant_group: the raw scores of the group are dequantized (+ Delta-S) into sc, in base 2
+// (Algorithm 1, score line); MASKED adds the causal diagonal and the keys beyond N.
+template <bool INT4, bool CAUSAL, bool MASKED, int KT, int G>
+__device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2], const v4f (&dsr)[2][4],
+                                              float c, int half, int key0, int query, int N) {
 #pragma unroll
-  for (int kt = 0; kt < 2; ++kt) {
-    const float c = __fmul_rn(__fmul_rn(dq, kt == 0 ? dk0 : dk1), kappa);
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      if constexpr (INT4) {
-        const v4f d4 = dsr[kt][g];
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          acc[kt][4 * g + r] = __float_as_int(__fmaf_rn(__int_as_float(acc[kt][4 * g + r]), c, d4[r]));
-      } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          acc[kt][4 * g + r] = __float_as_int(__fmul_rn((float)acc[kt][4 * g + r], c));
-      }
+  for (int r = 0; r < 4; ++r) {
+    float x;
+    if constexpr (INT4) x = __fmaf_rn(__int_as_float(raw[KT][4 * G + r]), c, dsr[KT][G][r]);
+    else x = __fmul_rn((float)raw[KT][4 * G + r], c);
+    if constexpr (MASKED) {
+      const int key = key0 + 32 * KT + 16 * half + 4 * G + r;
+      if (key >= N || (CAUSAL && key > query)) x = -INFINITY;
     }
+    sc[KT][4 * G + r] = __float_as_int(x);
   }
-  if constexpr (MASKED) {   // causal diagonal and keys beyond N
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = key0 + 32 * kt + 16 * half + v;
-        if (key >= N || (CAUSAL && key > query)) acc[kt][v] = __float_as_int(-INFINITY);
-      }
-    }
-  }
-  // ---- running max (Eq. 1 / Algorithm 1) ----
+}
+
+// update_max: running max over the block's 64 dequantized scores of this lane's query (Eq. 1 /
+// Algorithm 1); returns alpha = 2^(m_old - m_new) and, in m_sub, the exponent offset of the block.
+template <int D>
+__device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2], float& m_sub) {
   float mx = fmaxf(__int_as_float(acc[0][0]), __int_as_float(acc[1][0]));
 #pragma unroll
   for (int v = 1; v < 16; ++v)   // one v_max3_f32 per step
@@ -131,23 +123,20 @@ __device__ __forceinline__ float softmax_max(RowState<D>& st, v16i (&acc)[2], co
   return alpha;
 }
 
-// softmax_exp: key tile KT of the block: 448 * P~ = 2^(S - m_sub), its row-sum share added to ls, and
-// the FP8 codes written into words 4*KT .. 4*KT+3 of the P~ operand.
-template <int KT>
-__device__ __forceinline__ void softmax_exp(const v16i (&acc)[2], float m_sub, v8i& pb, float& ls) {
+// exp_group: 448 * P~ = 2^(S - m_sub) for the group, its row-sum share added to ls, its FP8 codes
+// written into word 4*KT + G of the P~ operand.
+template <int KT, int G>
+__device__ __forceinline__ void exp_group(const v16i (&acc)[2], float m_sub, v8i& pb, float& ls) {
+  float e[4];
 #pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    float e[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      e[r] = __builtin_amdgcn_exp2f(__int_as_float(acc[KT][4 * g + r]) - m_sub);
-      ls += e[r];
-    }
-    int wd = __float_as_int(e[0]);   // any value: both halves are overwritten below
-    wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[0], e[1], wd, false);
-    wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[2], e[3], wd, true);
-    pb[KT * 4 + g] = wd;
+  for (int r = 0; r < 4; ++r) {
+    e[r] = __builtin_amdgcn_exp2f(__int_as_float(acc[KT][4 * G + r]) - m_sub);
+    ls += e[r];
   }
+  int wd = __float_as_int(e[0]);   // any value: both halves are overwritten below
+  wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[0], e[1], wd, false);
+  wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[2], e[3], wd, true);
+  pb[KT * 4 + G] = wd;
 }
 
 // Second half: the two-level accumulation of Sec. 3.4 on gfx950.  One v_mfma_f32_32x32x64_f8f6f4 has
@@ -166,17 +155,14 @@ __device__ __forceinline__ void block_rescale(RowState<D>& st, float alpha) {
     }
   }
 }
-template <int D>
-__device__ __forceinline__ void block_pv(RowState<D>& st, const v4i (&va)[2 * (D / 32)], const v8i& pb) {
-#pragma unroll
-  for (int ct = 0; ct < D / 32; ++ct) {
-    v8i a;
-    const v4i a0 = va[ct * 2 + 0];
-    const v4i a1 = va[ct * 2 + 1];
-    a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
-    a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
-    st.O[ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, st.O[ct], 0, 0, 0, 0, 0, 0);
-  }
+template <int D, int CT>
+__device__ __forceinline__ void pv_step(RowState<D>& st, const v4i (&va)[2 * (D / 32)], const v8i& pb) {
+  v8i a;
+  const v4i a0 = va[CT * 2 + 0];
+  const v4i a1 = va[CT * 2 + 1];
+  a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
+  a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
+  st.O[CT] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, st.O[CT], 0, 0, 0, 0, 0, 0);
 }
 
 #ifndef SAGE_WAVES_PER_SIMD
@@ -286,22 +272,21 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   n_plain = __builtin_amdgcn_readfirstlane(n_plain);
   n_act = __builtin_amdgcn_readfirstlane(n_act);
 
-  // Software pipeline, one barrier per block, three LDS stages; every MFMA is issued ahead of
-  // vector work that does not depend on it.  On entry to iteration j the raw scores of block j are
-  // in `acc` (their MFMAs were issued during iteration j-1), stage j%3 holds block j, the copy of
-  // block j+1 is in flight and the P~V MFMAs of block j-1 are still running.  The iteration
-  //   A.  reads block j's Delta-S row and scales from LDS, dequantizes the scores and updates the
-  //       running max (under P~V of block j-1),
-  //   B.  waits for its own share of block j+1 and meets the other wavefronts at the barrier:
-  //       block j+1 is visible, and nobody reads block j-1's stage any more,
-  //   C.  starts the LDS reads of K^_{j+1} and the copy of block j+2 into block j-1's stage,
-  //   D.  exponentials, row sum and FP8 codes of key tile 0 (covers the latency of C's reads),
-  //   E0. issues the score MFMAs of block j+1, key tile 0, into the registers D has just freed,
-  //   F.  starts the LDS reads of V^_j,
-  //   G.  exponentials, row sum and FP8 codes of key tile 1 (under E0's MFMAs),
-  //   E1. issues the score MFMAs of block j+1, key tile 1,
-  //   H.  rescales O if a running max moved and issues the P~V MFMAs of block j.
-  // Past the wavefront's last block C and E work on a stale stage (in bounds, results unused):
+  // Software pipeline, one barrier per block, three LDS stages; every MFMA is issued between
+  // pieces of vector work that do not depend on it, one at a time (a burst of MFMAs would hold up
+  // the wavefront's own vector instructions behind it).  On entry to iteration j the dequantized
+  // scores of block j (`sc`), their alpha and exponent offset are in registers, stage j%3 holds
+  // block j and the copy of block j+1 is in flight.  The iteration
+  //   B. waits for its own share of block j+1 and meets the other wavefronts at the barrier:
+  //      block j+1 is visible, and nobody reads block j-1's stage any more,
+  //   C. starts the LDS reads of K^_{j+1} and the copy of block j+2 into block j-1's stage,
+  //   R. rescales O if a running max moved (covers the latency of C's reads),
+  //   X. exponentials, row sum and FP8 codes of block j, four keys at a time, with one score MFMA
+  //      of block j+1 issued in front of each piece; half way, the LDS reads of V^_j and of block
+  //      j+1's Delta-S row and scales are started,
+  //   Y. the P~V MFMAs of block j, each followed by a piece of block j+1's dequantization, then
+  //      block j+1's running-max update.
+  // Past the wavefront's last block C, X and Y work on a stale stage (in bounds, results unused):
   // unconditional, so that no register stays live for the sake of a path not taken.
   v4i ka[2 * KS], va[2 * CT];
   v4f dsr[2][4];
@@ -337,50 +322,88 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   if (nblk > 1) { issue(1, 1); wait_all_but_newest(); } else { wait_all(); }
   __syncthreads();
   read_k(0);
-  v16i acc[2];
-  qk_tile<D, INT4>(ka, qreg, acc);    // block 0 holds a visible key for every query
+  read_x(0);
+  v16i raw[2], sc[2];                 // raw scores being produced / dequantized scores of block j
+  qk_tile<D, INT4>(ka, qreg, raw);    // block 0 holds a visible key for every query
+  float alpha, m_sub;
+  constexpr int NQK = qk_steps<D, INT4>();
+  constexpr int GPC = 8 / CT;         // dequantization groups per P~V MFMA
+
+#define SAGE_DEQ(MASKED_, GI_, KEY0_)                                                                \
+  dequant_group<INT4, CAUSAL, MASKED_, (GI_) / 4, (GI_) % 4>(raw, sc, dsr, (GI_) / 4 == 0 ? c0 : c1, half, \
+                                                             KEY0_, query, p.N)
+#define SAGE_DEQ_ALL(MASKED_, KEY0_)                                                                 \
+  do {                                                                                               \
+    SAGE_DEQ(MASKED_, 0, KEY0_); SAGE_DEQ(MASKED_, 1, KEY0_); SAGE_DEQ(MASKED_, 2, KEY0_);           \
+    SAGE_DEQ(MASKED_, 3, KEY0_); SAGE_DEQ(MASKED_, 4, KEY0_); SAGE_DEQ(MASKED_, 5, KEY0_);           \
+    SAGE_DEQ(MASKED_, 6, KEY0_); SAGE_DEQ(MASKED_, 7, KEY0_);                                        \
+  } while (0)
+  {
+    const float c0 = __fmul_rn(__fmul_rn(dq, dk0), p.kappa), c1 = __fmul_rn(__fmul_rn(dq, dk1), p.kappa);
+    if (n_plain > 0) SAGE_DEQ_ALL(false, 0); else SAGE_DEQ_ALL(true, 0);
+    alpha = update_max<D>(st, sc, m_sub);
+  }
 
   int cur = 0;   // stage of block j
-#define SAGE_ITER(MASKED_, ACTIVE_)                                                                  \
+#define SAGE_X(GI_)                                                                                  \
+  do {                                                                                               \
+    if constexpr ((GI_) < NQK) qk_step<D, INT4, (GI_) < NQK ? (GI_) : 0>(ka, qreg, raw);             \
+    exp_group<(GI_) / 4, (GI_) % 4>(sc, m_sub, pb, ls);                                              \
+    __builtin_amdgcn_sched_barrier(0);                                                               \
+  } while (0)
+#define SAGE_Y(CT_, MASKED_)                                                                         \
+  do {                                                                                               \
+    if constexpr ((CT_) < CT) {                                                                      \
+      pv_step<D, (CT_) < CT ? (CT_) : 0>(st, va, pb);                                                \
+      SAGE_DEQ(MASKED_, (CT_) * GPC, (j + 1) * BKV);                                                 \
+      SAGE_DEQ(MASKED_, (CT_) * GPC + 1, (j + 1) * BKV);                                             \
+      if constexpr (GPC == 4) {                                                                      \
+        SAGE_DEQ(MASKED_, ((CT_) * GPC + 2) % 8, (j + 1) * BKV);                                     \
+        SAGE_DEQ(MASKED_, ((CT_) * GPC + 3) % 8, (j + 1) * BKV);                                     \
+      }                                                                                              \
+      __builtin_amdgcn_sched_barrier(0);                                                             \
+    }                                                                                                \
+  } while (0)
+#define SAGE_BODY(MASKED_NEXT_)                                                                      \
   do {                                                                                               \
     const int nx1 = cur == NST - 1 ? 0 : cur + 1;                                                    \
     const int nx2 = nx1 == NST - 1 ? 0 : nx1 + 1;                                                    \
-    float m_sub = 0.0f, alpha = 1.0f;                                                                \
-    if (ACTIVE_) read_x(cur);                                                                        \
-    if (ACTIVE_)                                                                                     \
-      alpha = softmax_max<D, INT4, CAUSAL, MASKED_>(st, acc, dsr, dk0, dk1, dq, p.kappa, lane,       \
-                                                    j * BKV, query, p.N, m_sub);              /* A */ \
-    __builtin_amdgcn_sched_barrier(0);                                                               \
     wait_all();                                                                               /* B */ \
     __syncthreads();                                                                                 \
-    if (ACTIVE_) read_k(nx1);                                                                 /* C */ \
+    read_k(nx1);                                                                              /* C */ \
     if (j + 2 < nblk) issue(j + 2, nx2);                                                             \
+    block_rescale<D>(st, alpha);                                                              /* R */ \
     __builtin_amdgcn_sched_barrier(0);                                                               \
-    if (ACTIVE_) {                                                                                   \
-      v8i pb;                                                                                        \
-      float ls = 0.0f;                                                                               \
-      softmax_exp<0>(acc, m_sub, pb, ls);                                                     /* D */ \
-      __builtin_amdgcn_sched_barrier(0);                                                             \
-      qk_half<D, INT4, 0>(ka, qreg, acc[0]);                                                  /* E0 */ \
-      __builtin_amdgcn_sched_barrier(0);                                                             \
-      read_v(cur);                                                                            /* F */ \
-      __builtin_amdgcn_sched_barrier(0);                                                             \
-      softmax_exp<1>(acc, m_sub, pb, ls);                                                     /* G */ \
-      st.l_run = __fmaf_rn(alpha, st.l_run, ls);                                                     \
-      __builtin_amdgcn_sched_barrier(0);                                                             \
-      qk_half<D, INT4, 1>(ka, qreg, acc[1]);                                                  /* E1 */ \
-      __builtin_amdgcn_sched_barrier(0);                                                             \
-      block_rescale<D>(st, alpha);                                                            /* H */ \
-      block_pv<D>(st, va, pb);                                                                       \
-      __builtin_amdgcn_sched_barrier(0);                                                             \
-    }                                                                                                \
+    v8i pb;                                                                                          \
+    float ls = 0.0f;                                                                                 \
+    SAGE_X(0); SAGE_X(1); SAGE_X(2); SAGE_X(3);                                               /* X */ \
+    read_v(cur);                                                                                     \
+    read_x(nx1);                                                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                               \
+    SAGE_X(4); SAGE_X(5); SAGE_X(6); SAGE_X(7);                                                      \
+    st.l_run = __fmaf_rn(alpha, st.l_run, ls);                                                       \
+    const float c0 = __fmul_rn(__fmul_rn(dq, dk0), p.kappa), c1 = __fmul_rn(__fmul_rn(dq, dk1), p.kappa); \
+    SAGE_Y(0, MASKED_NEXT_); SAGE_Y(1, MASKED_NEXT_); SAGE_Y(2, MASKED_NEXT_); SAGE_Y(3, MASKED_NEXT_); /* Y */ \
+    alpha = update_max<D>(st, sc, m_sub);                                                            \
     cur = nx1;                                                                                       \
   } while (0)
   int j = 0;
-  for (; j < n_plain; ++j) SAGE_ITER(false, true);
-  for (; j < n_act; ++j) SAGE_ITER(true, true);
-  for (; j < nblk; ++j) SAGE_ITER(false, false);
-#undef SAGE_ITER
+  for (; j + 1 < n_plain; ++j) SAGE_BODY(false);
+  for (; j < n_act; ++j) SAGE_BODY(true);
+  // causal only: blocks past this wavefront's last query - keep up the copies and the barriers
+  for (; j < nblk; ++j) {
+    const int nx1 = cur == NST - 1 ? 0 : cur + 1;
+    const int nx2 = nx1 == NST - 1 ? 0 : nx1 + 1;
+    wait_all();
+    __syncthreads();
+    if (j + 2 < nblk) issue(j + 2, nx2);
+    cur = nx1;
+  }
+#undef SAGE_BODY
+#undef SAGE_Y
+#undef SAGE_X
+#undef SAGE_DEQ_ALL
+#undef SAGE_DEQ
 
   // ---- epilogue (Algorithm 1 last line): O / l / 448 * delta_V; l_run already carries the 448
   float l_tot = st.l_run;
