@@ -181,7 +181,8 @@ def quantize_v(V):
 
 # --------------------------------------------------------------------------- prologue
 def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SMOOTH,
-                  smooth_q_on=None, smooth_k_on=True, pv_exact=False, ds_blocks=None):
+                  smooth_q_on=None, smooth_k_on=True, pv_exact=False, ds_blocks=None,
+                  smooth_v_on=False):
     """Everything Algorithm 1 computes before the inner loop, for one (batch, head).
 
     Q, K, V: [N, d] float32 holding exactly representable 16-bit values.
@@ -192,6 +193,9 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
     pins can take the quantizers to their high-precision limit.  ds_blocks, if given, lists
     the smoothing blocks whose Delta-S rows are wanted (the other rows are left zero): sampling
     support for sequences where the full [N/b_q, N] bias would not fit in host memory.
+    smooth_v_on: the optional technique at the end of Sec. 3.4 (Appendix "Smoothing V"): the
+    token mean of V is subtracted per channel before the FP8 quantization and added back to the
+    output (rows of the softmax sum to 1); the mean is kept in FP32.
     """
     N, d = Q.shape
     if sm_scale is None:
@@ -216,6 +220,11 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
     gq, gk = group_map(gmap, N, "q"), group_map(gmap, N, "k")
     dq, qc = quantize_groups(gQ, gq, qmax)
     dk, kc = quantize_groups(gK, gk, qmax)
+    if smooth_v_on:
+        vbar = token_mean(V)
+        V = (np.asarray(V, f32) - vbar[None, :]).astype(f32)
+    else:
+        vbar = None
     if pv_exact:
         dv, vc, vdec = np.ones(d, f32), None, np.asarray(V, f64)
     else:
@@ -223,7 +232,7 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
         vdec = e4m3_decode(vc)                            # [N, d] float64, exact
     return dict(N=N, d=d, kappa=kappa, qmax=qmax, kbar=kbar, qbar=qbar, delta_s=D,
                 q_codes=qc, q_scale=dq, q_groups=gq, k_codes=kc, k_scale=dk, k_groups=gk,
-                v_codes=vc, v_scale=dv, v_dec=vdec, pv_exact=pv_exact, bq=bq)
+                v_codes=vc, v_scale=dv, v_dec=vdec, pv_exact=pv_exact, bq=bq, vbar=vbar)
 
 
 # --------------------------------------------------------------------------- attention
@@ -282,6 +291,8 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
     out = (O / l[:, None]).astype(f32)
     out = (out / f32(E4M3_MAX)).astype(f32)
     out = (out * pro["v_scale"][None, :]).astype(f32)
+    if pro.get("vbar") is not None:                       # smooth V: O = O + mean(V)
+        out = (out + pro["vbar"][None, :]).astype(f32)
     res = _round_out(out, out_dtype)
     if return_state:
         return res, dict(m=m, l=l, O=O)

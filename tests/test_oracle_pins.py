@@ -295,6 +295,40 @@ def test_granularity_and_smoothing_orderings(facts):
     assert sm["qk"] > sm["k"] > sm["none"] and sm["qk"] > sm["q"] > sm["none"]
 
 
+# ---- optional smooth V (end of Sec. 3.4; Appendix "Smoothing V") ------------------------------
+@pytest.mark.parametrize("causal", [False, True])
+def test_smooth_v_is_result_neutral_and_added_back(causal):
+    q, k, v = _head(N=200, d=32, seed=4)
+    v = (v + np.linspace(-9, 9, 32, dtype=f32)[None, :]).astype(np.float16).astype(f32)   # channel biases
+    ref = so.ref_attn_fp64(q, k, v, causal=causal)
+    vm = v.astype(f64).mean(axis=0)
+    # rows of the softmax sum to 1, so P (V - vm) + vm = P V: plain float64 identity
+    shifted = so.ref_attn_fp64(q, k, (v.astype(f64) - vm), causal=causal) + vm
+    assert np.abs(shifted - ref).max() < 1e-12 * np.abs(ref).max()
+    # the oracle's path with quantizers at their high-precision limit keeps that identity
+    out, pro = so.sage_attention_head(q, k, v, causal=causal, mode=32767, out_dtype="fp32",
+                                      smooth_q_on=True, pv_exact=True, smooth_v_on=True)
+    assert np.array_equal(pro["vbar"], vm.astype(f32))
+    assert np.abs(out - ref).max() < 2e-3 * np.abs(ref).max()
+    assert wl.cos_sim(out, ref) > 1 - 1e-6
+
+
+def test_smooth_v_quantizes_the_centred_values_and_helps_with_channel_bias(facts):
+    q, k, v = _head(N=256, d=32, seed=5)
+    v = (v + np.float32(8.5)).astype(np.float16).astype(f32)        # the 8..9 bias quoted for CogVideoX
+    pro = so.quantize_head(q, k, v, smooth_v_on=True)
+    centred = (v - pro["vbar"][None, :]).astype(f32)
+    assert np.array_equal(pro["v_scale"], (np.abs(centred).max(axis=0) / f32(facts["e4m3_max"]["value"])).astype(f32))
+    dec = so.e4m3_decode(pro["v_codes"]) * pro["v_scale"].astype(f64)[None, :]
+    assert np.abs(dec - centred).max() <= np.abs(centred).max() * 2.0 ** -4 * 1.001
+    ref = so.ref_attn_fp64(q, k, v)
+    plain, _ = so.sage_attention_head(q, k, v, mode="int8_fp8", out_dtype="fp32")
+    smooth, _ = so.sage_attention_head(q, k, v, mode="int8_fp8", out_dtype="fp32", smooth_v_on=True)
+    # the paper's table for this technique reports a lower error with it (ordering only)
+    assert wl.rmse(smooth, ref) < 0.5 * wl.rmse(plain, ref)
+    assert wl.cos_sim(smooth, ref) >= wl.cos_sim(plain, ref)
+
+
 # ---- misc structure -------------------------------------------------------------------------
 def test_int8_mode_does_not_smooth_q():
     q, k, v = _head(N=128, d=16)
