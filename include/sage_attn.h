@@ -36,7 +36,7 @@ extern "C" {
 enum {
   SAGE_OK = 0,
   SAGE_ERR_INVALID_ARG = -1,  /* null pointer, non-positive size, H % H_kv != 0 */
-  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode or dtype */
+  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode, dtype or flag */
   SAGE_ERR_WORKSPACE = -3,    /* workspace missing or smaller than sage_attn_workspace_bytes() */
   SAGE_ERR_HIP = -4           /* a HIP call or launch failed (the HIP error is cleared) */
 };
@@ -45,6 +45,11 @@ enum {
    Both use FP8 E4M3 P~ and V (paper, table "Two kernel implementations"). */
 enum { SAGE_MODE_INT4_FP8 = 0, SAGE_MODE_INT8_FP8 = 1 };
 enum { SAGE_DT_FP16 = 0, SAGE_DT_BF16 = 1 };
+/* Optional techniques, or-ed into sage_attn_args.flags.
+   SAGE_FLAG_SMOOTH_V: the optional "smooth V" of Sec. 3.4 (last paragraph; Appendix "Smoothing V"):
+   the per-channel token mean of V is subtracted before the FP8 quantizer and added back, in FP32, to
+   the output (rows of the softmax sum to 1).  Costs one more pass over V in the preprocessing. */
+enum { SAGE_FLAG_SMOOTH_V = 1 };
 
 /* Numerical block sizes of Algorithm 1 as this library fixes them. */
 #define SAGE_BQ_SMOOTH 128 /* tokens per Q smoothing block (b_q) */
@@ -64,6 +69,7 @@ typedef struct sage_attn_args {
   float sm_scale;         /* <= 0 means 1/sqrt(d) */
   int mode;               /* SAGE_MODE_* */
   int dtype;              /* SAGE_DT_* : type of q, k, v and out */
+  int flags;              /* SAGE_FLAG_* or-ed together; 0 = the paper's default configuration */
   void* workspace;        /* device scratch of >= sage_attn_workspace_bytes(); 256-byte aligned */
   size_t workspace_bytes;
   void* stream;           /* hipStream_t, NULL = default stream */
@@ -102,7 +108,9 @@ void sage_attn_release(void);
      k_mean  [B,H_kv,d] f32       mean(K) over tokens (Eq. 2)
      q_mean  [B,H,ceil(N/128),d] f32   block means of Q (int4 mode only, else untouched)
      delta_s [B,H,ceil(N/128),N] f32   kappa * <q_mean_i, gamma(K)_t>, kappa = sm_scale*log2(e)
-                                       (int4 mode only, else untouched) */
+                                       (int4 mode only, else untouched)
+     v_mean  [B,H_kv,d] f32       mean(V) over tokens (SAGE_FLAG_SMOOTH_V only, else untouched); with
+                                  that flag v_codes and v_scale describe V - v_mean */
 typedef struct sage_quant_out {
   int8_t* q_codes;
   int8_t* k_codes;
@@ -113,6 +121,7 @@ typedef struct sage_quant_out {
   float* k_mean;
   float* q_mean;
   float* delta_s;
+  float* v_mean;
 } sage_quant_out;
 
 /* Runs the preprocessing of Algorithm 1 (as sage_attn_prologue) and then copies its results

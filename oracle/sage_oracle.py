@@ -326,7 +326,7 @@ def sage_attention_head(Q, K, V, causal=False, mode="int4_fp8", sm_scale=None, g
 
 
 def sage_attention(q, k, v, causal=False, mode="int4_fp8", sm_scale=None, gmap="g950",
-                   bq=BQ_SMOOTH, bkv=BKV_ACC, out_dtype="bf16"):
+                   bq=BQ_SMOOTH, bkv=BKV_ACC, out_dtype="bf16", **kw):
     """Batched form: q [B, H, N, d], k and v [B, H_kv, N, d]; query head h reads KV head
     h // (H / H_kv).  Returns [B, H, N, d] float32 (values rounded to out_dtype)."""
     B, H, N, d = q.shape
@@ -335,7 +335,7 @@ def sage_attention(q, k, v, causal=False, mode="int4_fp8", sm_scale=None, gmap="
     for b in range(B):
         for h in range(H):
             out[b, h], _ = sage_attention_head(q[b, h], k[b, h // g], v[b, h // g], causal, mode,
-                                               sm_scale, gmap, bq, bkv, out_dtype)
+                                               sm_scale, gmap, bq, bkv, out_dtype, **kw)
     return out
 
 

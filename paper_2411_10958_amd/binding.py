@@ -11,6 +11,7 @@ import torch
 
 SAGE_MODE_INT4_FP8, SAGE_MODE_INT8_FP8 = 0, 1
 SAGE_DT_FP16, SAGE_DT_BF16 = 0, 1
+SAGE_FLAG_SMOOTH_V = 1
 _MODES = {"int4_fp8": 0, "int8_fp8": 1, 0: 0, 1: 1}
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -29,14 +30,14 @@ class sage_attn_args(ctypes.Structure):
                 ("B", ctypes.c_int), ("H", ctypes.c_int), ("H_kv", ctypes.c_int),
                 ("N", ctypes.c_int), ("d", ctypes.c_int),
                 ("causal", ctypes.c_int), ("sm_scale", ctypes.c_float),
-                ("mode", ctypes.c_int), ("dtype", ctypes.c_int),
+                ("mode", ctypes.c_int), ("dtype", ctypes.c_int), ("flags", ctypes.c_int),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("stream", ctypes.c_void_p)]
 
 
 class sage_quant_out(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in ("q_codes", "k_codes", "v_codes", "q_scale", "k_scale",
-                                              "v_scale", "k_mean", "q_mean", "delta_s")]
+                                              "v_scale", "k_mean", "q_mean", "delta_s", "v_mean")]
 
 
 def lib_path():
@@ -95,7 +96,8 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
 
 
-def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None):
+def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
+              smooth_v=False):
     """Fills a sage_attn_args from torch tensors q [B,H,N,d], k/v [B,H_kv,N,d] (contiguous, on the
     GPU).  `workspace` is a uint8 GPU tensor (or None); `stream` a torch.cuda.Stream (None = the
     current one)."""
@@ -113,6 +115,7 @@ def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", wo
     a.q, a.k, a.v, a.out = q.data_ptr(), k.data_ptr(), v.data_ptr(), (out.data_ptr() if out is not None else 0)
     a.B, a.H, a.H_kv, a.N, a.d = B, H, k.shape[1], N, d
     a.causal, a.sm_scale, a.mode, a.dtype = int(bool(causal)), float(sm_scale), _MODES[mode], _dtype_code(q)
+    a.flags = SAGE_FLAG_SMOOTH_V if smooth_v else 0
     if workspace is not None:
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     else:
@@ -135,11 +138,12 @@ def _alloc_workspace(args, device):
     return ws
 
 
-def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None):
+def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
+                     smooth_v=False):
     """Whole forward pass.  Returns `out` (allocated if not given)."""
     if out is None:
         out = torch.empty_like(q)
-    a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream)
+    a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v)
     keep = _alloc_workspace(a, q.device) if workspace is None else workspace
     _check(load_library().sage_attn_fwd_ex(ctypes.byref(a)), "sage_attn_fwd_ex")
     del keep  # torch's caching allocator keeps the block alive for work already queued on this stream
@@ -166,9 +170,10 @@ def sage_attn_release():
     load_library().sage_attn_release()
 
 
-def sage_attn_quant(q, k, v, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, want=None):
+def sage_attn_quant(q, k, v, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, want=None,
+                    smooth_v=False):
     """Preprocessing only; returns (dict of torch tensors in plain layouts, args, workspace)."""
-    a = make_args(q, k, v, None, causal, sm_scale, mode, workspace)
+    a = make_args(q, k, v, None, causal, sm_scale, mode, workspace, smooth_v=smooth_v)
     ws = _alloc_workspace(a, q.device) if workspace is None else workspace
     B, H, N, d = q.shape
     Hkv = k.shape[1]
@@ -187,6 +192,8 @@ def sage_attn_quant(q, k, v, causal=False, sm_scale=0.0, mode="int4_fp8", worksp
     if int4:
         bufs["q_mean"] = torch.empty((B, H, nqb, d), dtype=torch.float32, device=dev)
         bufs["delta_s"] = torch.empty((B, H, nqb, N), dtype=torch.float32, device=dev)
+    if smooth_v:
+        bufs["v_mean"] = torch.empty((B, Hkv, d), dtype=torch.float32, device=dev)
     if want is not None:
         bufs = {n: t for n, t in bufs.items() if n in want}
     o = sage_quant_out()

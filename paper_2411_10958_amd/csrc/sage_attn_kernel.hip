@@ -22,6 +22,7 @@ struct AttnParams {
   const float* q_scale;
   const float* k_scale;
   const float* v_scale;
+  const float* v_mean;    // null, or the token mean of V to add back (smooth-V option)
   const float* delta_s;
   void* out;
   int H, Hkv, N, nQb, nKb, total_tiles;
@@ -405,7 +406,8 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
 #undef SAGE_DEQ_ALL
 #undef SAGE_DEQ
 
-  // ---- epilogue (Algorithm 1 last line): O / l / 448 * delta_V; l_run already carries the 448
+  // ---- epilogue (Algorithm 1 last line): O / l / 448 * delta_V (+ mean(V) with the smooth-V
+  // option, Sec. 3.4 last paragraph); l_run already carries the 448
   float l_tot = st.l_run;
   {
     const unsigned u = __float_as_uint(l_tot);
@@ -421,9 +423,15 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
       for (int g = 0; g < 4; ++g) {
         const int c0 = 32 * ct + 8 * g + 4 * half;
         const v4f sc = *reinterpret_cast<const v4f*>(dv + c0);
+        v4f vm = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (p.v_mean) vm = *reinterpret_cast<const v4f*>(p.v_mean + bhkv * D + c0);
         unsigned short o4[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) o4[r] = store16<BF16>(__fmul_rn(__fdiv_rn(st.O[ct][4 * g + r], l_tot), sc[r]));
+        for (int r = 0; r < 4; ++r) {
+          float o = __fmul_rn(__fdiv_rn(st.O[ct][4 * g + r], l_tot), sc[r]);
+          if (p.v_mean) o = __fadd_rn(o, vm[r]);
+          o4[r] = store16<BF16>(o);
+        }
         *reinterpret_cast<uint2*>(orow + c0) =
             make_uint2((unsigned)o4[0] | ((unsigned)o4[1] << 16), (unsigned)o4[2] | ((unsigned)o4[3] << 16));
       }
@@ -474,6 +482,7 @@ static hipError_t launch_attention_t(const Dims& Dm, const Ptrs& P, hipStream_t 
   AttnParams p;
   p.q_codes = P.q_codes; p.k_codes = P.k_codes; p.v_codes = P.v_codes;
   p.q_scale = P.q_scale; p.k_scale = P.k_scale; p.v_scale = P.v_scale; p.delta_s = P.delta_s;
+  p.v_mean = Dm.smooth_v ? P.v_mean : nullptr;
   p.out = P.out;
   p.H = Dm.H; p.Hkv = Dm.Hkv; p.N = Dm.N; p.nQb = Dm.nQb; p.nKb = Dm.nKb;
   p.total_tiles = Dm.B * Dm.H * Dm.nQb;

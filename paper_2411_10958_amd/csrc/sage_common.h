@@ -27,7 +27,7 @@ struct Dims {
   int B, H, Hkv, N, d;
   int nQb;     // ceil(N / 128) query blocks
   int nKb;     // ceil(N / 64) key blocks
-  int causal, int4, bf16;
+  int causal, int4, bf16, smooth_v;
   float kappa; // fl32(sm_scale * log2 e)
 };
 
@@ -50,8 +50,9 @@ struct Dims {
 //            which a lane's P~ registers come out of the score tiles).
 //   delta_s: [B*H][nQb][nKb*64] float, zero beyond N.
 //   q_scale: [B*H][nQb*64] float;  k_scale: [B*Hkv][nKb*4] float.
+//   v_sum, v_mean: [B*Hkv][d], only with the smooth-V option (otherwise zero-sized).
 struct Workspace {
-  size_t k_sum, v_max, k_mean, v_scale, q_mean, q_scale, k_scale, q_codes, k_codes, v_codes,
+  size_t k_sum, v_sum, v_max, k_mean, v_mean, v_scale, q_mean, q_scale, k_scale, q_codes, k_codes, v_codes,
       delta_s, total;
 };
 
@@ -63,8 +64,10 @@ inline Workspace make_workspace(const Dims& D) {
   auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
   const size_t BH = (size_t)D.B * D.H, BHkv = (size_t)D.B * D.Hkv;
   w.k_sum = take(BHkv * D.d * sizeof(double));
+  w.v_sum = take(D.smooth_v ? BHkv * D.d * sizeof(double) : 0);
   w.v_max = take(BHkv * D.d * sizeof(unsigned));
   w.k_mean = take(BHkv * D.d * sizeof(float));
+  w.v_mean = take(D.smooth_v ? BHkv * D.d * sizeof(float) : 0);
   w.v_scale = take(BHkv * D.d * sizeof(float));
   w.q_mean = take(BH * D.nQb * D.d * sizeof(float));
   w.q_scale = take(BH * D.nQb * (BQ / QGROUP) * sizeof(float));
@@ -80,9 +83,9 @@ inline Workspace make_workspace(const Dims& D) {
 struct Ptrs {
   const void *q, *k, *v;
   void* out;
-  double* k_sum;
+  double *k_sum, *v_sum;
   unsigned* v_max;
-  float *k_mean, *v_scale, *q_mean, *q_scale, *k_scale, *delta_s;
+  float *k_mean, *v_mean, *v_scale, *q_mean, *q_scale, *k_scale, *delta_s;
   int8_t *q_codes, *k_codes;
   uint8_t* v_codes;
 };
@@ -93,8 +96,10 @@ inline Ptrs make_ptrs(const void* q, const void* k, const void* v, void* out, vo
   Ptrs p;
   p.q = q; p.k = k; p.v = v; p.out = out;
   p.k_sum = (double*)(b + w.k_sum);
+  p.v_sum = (double*)(b + w.v_sum);
   p.v_max = (unsigned*)(b + w.v_max);
   p.k_mean = (float*)(b + w.k_mean);
+  p.v_mean = (float*)(b + w.v_mean);
   p.v_scale = (float*)(b + w.v_scale);
   p.q_mean = (float*)(b + w.q_mean);
   p.q_scale = (float*)(b + w.q_scale);

@@ -51,56 +51,110 @@ __device__ inline uint2 pack8(const int (&cc)[8]) {
 // ------------------------------------------------------------------------------------------
 // Column statistics: exact token sums of K (float64 accumulation of 16-bit values) and
 // per-channel max |V| (Algorithm 1, "Preprocessing": mean(K) and the scale of psi_V).
-__global__ void k_zero_stats(double* k_sum, unsigned* v_max, int n) {
+__global__ void k_zero_stats(double* k_sum, double* v_sum, unsigned* v_max, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) { k_sum[i] = 0.0; v_max[i] = 0u; }
+  if (i < n) {
+    k_sum[i] = 0.0;
+    v_max[i] = 0u;
+    if (v_sum) v_sum[i] = 0.0;     // smooth-V option only
+  }
 }
 
 constexpr int STAT_ROWS = 512;  // tokens per workgroup of k_col_stats
 
-template <bool BF16, int D>
+// With the smooth-V option the first pass takes the exact token sums of V instead of max|V| (the
+// maximum must be taken of the centred values, which needs the mean first: k_v_absmax below).
+template <bool BF16, int D, bool SMOOTH_V>
 __global__ void __launch_bounds__(256) k_col_stats(const unsigned short* __restrict__ K,
                                                    const unsigned short* __restrict__ V,
-                                                   double* __restrict__ k_sum,
+                                                   double* __restrict__ k_sum, double* __restrict__ v_sum,
                                                    unsigned* __restrict__ v_max, int N) {
   constexpr int NCG = D / 8, NRG = 256 / NCG;
   __shared__ double s_sum[NRG][D];
-  __shared__ float s_max[NRG][D];
+  __shared__ double s_vsum[SMOOTH_V ? NRG : 1][D];
+  __shared__ float s_max[SMOOTH_V ? 1 : NRG][D];
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
   const size_t head = (size_t)blockIdx.y * N * D;
   const int r0 = blockIdx.x * STAT_ROWS;
   const int r1 = min(r0 + STAT_ROWS, N);
-  double acc[8];
+  double acc[8], vacc[8];
   float mx[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { acc[e] = 0.0; mx[e] = 0.0f; }
+  for (int e = 0; e < 8; ++e) { acc[e] = 0.0; vacc[e] = 0.0; mx[e] = 0.0f; }
   for (int r = r0 + rg; r < r1; r += NRG) {
     float xk[8], xv[8];
     load8<BF16>(K + head + (size_t)r * D + cg * 8, xk);
     load8<BF16>(V + head + (size_t)r * D + cg * 8, xv);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { acc[e] += (double)xk[e]; mx[e] = fmaxf(mx[e], fabsf(xv[e])); }
+    for (int e = 0; e < 8; ++e) {
+      acc[e] += (double)xk[e];
+      if constexpr (SMOOTH_V) vacc[e] += (double)xv[e]; else mx[e] = fmaxf(mx[e], fabsf(xv[e]));
+    }
   }
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { s_sum[rg][cg * 8 + e] = acc[e]; s_max[rg][cg * 8 + e] = mx[e]; }
+  for (int e = 0; e < 8; ++e) {
+    s_sum[rg][cg * 8 + e] = acc[e];
+    if constexpr (SMOOTH_V) s_vsum[rg][cg * 8 + e] = vacc[e]; else s_max[rg][cg * 8 + e] = mx[e];
+  }
   __syncthreads();
   if (t < D) {
-    double s = 0.0;
+    double s = 0.0, sv = 0.0;
     float m = 0.0f;
-    for (int g = 0; g < NRG; ++g) { s += s_sum[g][t]; m = fmaxf(m, s_max[g][t]); }
+    for (int g = 0; g < NRG; ++g) {
+      s += s_sum[g][t];
+      if constexpr (SMOOTH_V) sv += s_vsum[g][t]; else m = fmaxf(m, s_max[g][t]);
+    }
     atomicAdd(&k_sum[(size_t)blockIdx.y * D + t], s);
-    atomicMax(&v_max[(size_t)blockIdx.y * D + t], __float_as_uint(m));  // m >= 0: uint order = float order
+    if constexpr (SMOOTH_V) atomicAdd(&v_sum[(size_t)blockIdx.y * D + t], sv);
+    else atomicMax(&v_max[(size_t)blockIdx.y * D + t], __float_as_uint(m));  // m >= 0: uint order = float order
   }
 }
 
-// k_mean = fl32(sum / N) (Eq. 2), delta_V = fl32(max|V| / 448) (Sec. 3.3)
-__global__ void k_finalize_stats(const double* __restrict__ k_sum, const unsigned* __restrict__ v_max,
-                                 float* __restrict__ k_mean, float* __restrict__ v_scale, int n, int N) {
+// Smooth-V option, second pass over V: per-channel max |fl32(V - mean(V))|.
+template <bool BF16, int D>
+__global__ void __launch_bounds__(256) k_v_absmax(const unsigned short* __restrict__ V,
+                                                  const float* __restrict__ v_mean,
+                                                  unsigned* __restrict__ v_max, int N) {
+  constexpr int NCG = D / 8, NRG = 256 / NCG;
+  __shared__ float s_max[NRG][D];
+  const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
+  const size_t head = (size_t)blockIdx.y * N * D;
+  const int r0 = blockIdx.x * STAT_ROWS;
+  const int r1 = min(r0 + STAT_ROWS, N);
+  float mean[8], mx[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { mean[e] = v_mean[(size_t)blockIdx.y * D + cg * 8 + e]; mx[e] = 0.0f; }
+  for (int r = r0 + rg; r < r1; r += NRG) {
+    float xv[8];
+    load8<BF16>(V + head + (size_t)r * D + cg * 8, xv);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) mx[e] = fmaxf(mx[e], fabsf(__fsub_rn(xv[e], mean[e])));
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s_max[rg][cg * 8 + e] = mx[e];
+  __syncthreads();
+  if (t < D) {
+    float m = 0.0f;
+    for (int g = 0; g < NRG; ++g) m = fmaxf(m, s_max[g][t]);
+    atomicMax(&v_max[(size_t)blockIdx.y * D + t], __float_as_uint(m));
+  }
+}
+
+// k_mean = fl32(sum / N) (Eq. 2), delta_V = fl32(max|V| / 448) (Sec. 3.3); with the smooth-V option
+// this call produces v_mean = fl32(sum / N) instead of delta_V, which k_finalize_vscale adds later.
+__global__ void k_finalize_stats(const double* __restrict__ k_sum, const double* __restrict__ v_sum,
+                                 const unsigned* __restrict__ v_max, float* __restrict__ k_mean,
+                                 float* __restrict__ v_mean, float* __restrict__ v_scale, int n, int N) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) {
     k_mean[i] = (float)(k_sum[i] / (double)N);
-    v_scale[i] = __fdiv_rn(__uint_as_float(v_max[i]), E4M3_MAX);
+    if (v_sum) v_mean[i] = (float)(v_sum[i] / (double)N);
+    else v_scale[i] = __fdiv_rn(__uint_as_float(v_max[i]), E4M3_MAX);
   }
+}
+__global__ void k_finalize_vscale(const unsigned* __restrict__ v_max, float* __restrict__ v_scale, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) v_scale[i] = __fdiv_rn(__uint_as_float(v_max[i]), E4M3_MAX);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -323,10 +377,12 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
 
 // ------------------------------------------------------------------------------------------
 // V: per-channel FP8 E4M3 codes, transposed into the A-operand order of the P~V product
-// (Sec. 3.3; Algorithm 1 "Preprocessing": (delta_V, V^) = psi_V(V)).
+// (Sec. 3.3; Algorithm 1 "Preprocessing": (delta_V, V^) = psi_V(V)).  v_mean is null, or the token
+// mean to subtract first (smooth-V option).
 template <bool BF16, int D>
 __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restrict__ V,
                                                  const float* __restrict__ v_scale,
+                                                 const float* __restrict__ v_mean,
                                                  uint8_t* __restrict__ v_codes, int N, int nKb) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BKV / NRG;
   __shared__ uint8_t tile[BKV][D + 16];
@@ -334,9 +390,12 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
   const int kb = blockIdx.x;
   const size_t bh = blockIdx.y;
   const int n0 = kb * BKV;
-  float sc[8];
+  float sc[8], mean[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) sc[e] = v_scale[bh * D + cg * 8 + e];
+  for (int e = 0; e < 8; ++e) {
+    sc[e] = v_scale[bh * D + cg * 8 + e];
+    mean[e] = v_mean ? v_mean[bh * D + cg * 8 + e] : 0.0f;
+  }
 #pragma unroll
   for (int i = 0; i < RPT; ++i) {
     const int r = rg * RPT + i;
@@ -344,7 +403,10 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
     if (n0 + r < N) {
       load8<BF16>(V + (bh * N + n0 + r) * D + cg * 8, x);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) x[e] = sc[e] > 0.0f ? __fdiv_rn(x[e], sc[e]) : 0.0f;
+      for (int e = 0; e < 8; ++e) {
+        if (v_mean) x[e] = __fsub_rn(x[e], mean[e]);
+        x[e] = sc[e] > 0.0f ? __fdiv_rn(x[e], sc[e]) : 0.0f;
+      }
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) x[e] = 0.0f;
@@ -400,14 +462,25 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
   const unsigned short* k = (const unsigned short*)P.k;
   const unsigned short* v = (const unsigned short*)P.v;
   const int nstat = BHkv * Dm.d;
-  k_zero_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_max, nstat);
-  k_col_stats<BF16, D><<<dim3((Dm.N + STAT_ROWS - 1) / STAT_ROWS, BHkv), 256, 0, s>>>(k, v, P.k_sum, P.v_max, Dm.N);
-  k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_max, P.k_mean, P.v_scale, nstat, Dm.N);
+  const dim3 gstat((Dm.N + STAT_ROWS - 1) / STAT_ROWS, BHkv);
+  const float* v_mean = Dm.smooth_v ? P.v_mean : nullptr;
+  k_zero_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, Dm.smooth_v ? P.v_sum : nullptr, P.v_max, nstat);
+  if (Dm.smooth_v) {
+    k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.N);
+    k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
+                                                        nstat, Dm.N);
+    k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.N);
+    k_finalize_vscale<<<(nstat + 255) / 256, 256, 0, s>>>(P.v_max, P.v_scale, nstat);
+  } else {
+    k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.N);
+    k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
+                                                        nstat, Dm.N);
+  }
   k_quant_q<BF16, INT4, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.nQb);
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
                                                               P.delta_s, Dm.N, Dm.nKb, Dm.nQb, Dm.H / Dm.Hkv,
                                                               Dm.kappa);
-  k_quant_v<BF16, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, P.v_codes, Dm.N, Dm.nKb);
+  k_quant_v<BF16, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.nKb);
   return hipGetLastError();
 }
 
@@ -425,8 +498,9 @@ hipError_t launch_prologue(const Dims& D, const Ptrs& P, hipStream_t s) {
 
 hipError_t launch_unpack(const Dims& D, const Ptrs& P, const void* quant_out, hipStream_t s) {
   const sage_quant_out& qo = *(const sage_quant_out*)quant_out;
-  struct { int8_t *qc, *kc; uint8_t* vc; float *qs, *ks, *vs, *km, *qm, *ds; } o = {
-      qo.q_codes, qo.k_codes, qo.v_codes, qo.q_scale, qo.k_scale, qo.v_scale, qo.k_mean, qo.q_mean, qo.delta_s};
+  struct { int8_t *qc, *kc; uint8_t* vc; float *qs, *ks, *vs, *km, *qm, *ds, *vm; } o = {
+      qo.q_codes, qo.k_codes, qo.v_codes, qo.q_scale, qo.k_scale, qo.v_scale, qo.k_mean, qo.q_mean, qo.delta_s,
+      qo.v_mean};
   const int BH = D.B * D.H, BHkv = D.B * D.Hkv;
   const unsigned gx = (unsigned)(((size_t)D.N * D.d + 255) / 256);
   if (o.qc) k_unpack_codes<<<dim3(gx, BH), 256, 0, s>>>(P.q_codes, o.qc, D.N, D.d, (size_t)D.nQb * BQ * D.d, 0, D.int4);
@@ -437,6 +511,7 @@ hipError_t launch_unpack(const Dims& D, const Ptrs& P, const void* quant_out, hi
   if (o.ks) k_unpack_rows<<<dim3((nkg + 255) / 256, BHkv), 256, 0, s>>>(P.k_scale, o.ks, nkg, D.nKb * (BKV / KGROUP));
   if (o.vs) k_unpack_rows<<<dim3(1, BHkv), 256, 0, s>>>(P.v_scale, o.vs, D.d, D.d);
   if (o.km) k_unpack_rows<<<dim3(1, BHkv), 256, 0, s>>>(P.k_mean, o.km, D.d, D.d);
+  if (o.vm && D.smooth_v) k_unpack_rows<<<dim3(1, BHkv), 256, 0, s>>>(P.v_mean, o.vm, D.d, D.d);
   if (D.int4) {
     if (o.qm) k_unpack_rows<<<dim3(1, BH * D.nQb), 256, 0, s>>>(P.q_mean, o.qm, D.d, D.d);
     if (o.ds) k_unpack_rows<<<dim3((D.N + 255) / 256, BH * D.nQb), 256, 0, s>>>(P.delta_s, o.ds, D.N, D.nKb * BKV);

@@ -62,11 +62,13 @@ def test_workspace_size_formula():
     assert pa.sage_attn_workspace_bytes(_args(pa, N=4097)) > n
     assert pa.sage_attn_workspace_bytes(_args(pa, H_kv=8)) < n
     assert n % 256 == 0
+    # the smooth-V option adds only the per-channel sums and means of V
+    assert 0 < pa.sage_attn_workspace_bytes(_args(pa, flags=1)) - n <= 128 * 128 * 12 + 1024
 
 
 def test_argument_errors_are_found_on_the_host():
     pa, lib = _lib()
-    bad = [dict(d=96), dict(d=256), dict(mode=2), dict(dtype=3)]
+    bad = [dict(d=96), dict(d=256), dict(mode=2), dict(dtype=3), dict(flags=2), dict(flags=-1)]
     for kw in bad:
         a = _args(pa, **kw)
         assert pa.sage_attn_workspace_bytes(a) == 0

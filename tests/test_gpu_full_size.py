@@ -88,3 +88,33 @@ def test_full_size_sampled_parity(name, mode):
             ref_rows.append(so.attention_rows(pro, rows, spec.causal, out_dtype="fp32"))
             got_rows.append(wl.from_torch(out[b, h, rows]))
         check_output(np.concatenate(got_rows), np.concatenate(ref_rows), spec.dtype)
+
+
+def test_full_size_smooth_v_sampled_parity():
+    """The optional smooth-V technique at the full size of the video-like workload with a channel
+    bias in V: preprocessing of V bit-exact on a whole head, outputs of sampled query blocks."""
+    pa = _pa()
+    spec = wl.CONFIGS["video17k_vbias"]
+    rng = np.random.default_rng(4321)
+    print("workload video17k_vbias, smooth V: generating inputs", flush=True)
+    data = wl.make_inputs(spec, seed=0)
+    dev = torch.device("cuda:0")
+    q, k, v = (wl.to_torch(data[n], spec.dtype, dev) for n in "qkv")
+    print("  running the HIP path", flush=True)
+    out = pa.sage_attn_fwd_ex(q, k, v, causal=spec.causal, mode="int4_fp8", smooth_v=True)
+    quant, args, ws = pa.sage_attn_quant(q, k, v, causal=spec.causal, mode="int4_fp8", smooth_v=True,
+                                         want=["v_codes", "v_scale", "v_mean"])
+    torch.cuda.synchronize()
+    b, h = 1, 20
+    blocks = _blocks(spec, 3, rng)
+    print(f"  oracle on (b={b}, h={h}), query blocks {blocks}", flush=True)
+    pro = so.quantize_head(data["q"][b, h], data["k"][b, h], data["v"][b, h], ds_blocks=blocks, smooth_v_on=True)
+    assert np.array_equal(quant["v_mean"][b, h].cpu().numpy(), pro["vbar"])
+    assert np.array_equal(quant["v_scale"][b, h].cpu().numpy(), pro["v_scale"])
+    assert np.array_equal(quant["v_codes"][b, h].cpu().numpy(), pro["v_codes"])
+    got_rows, ref_rows = [], []
+    for i in blocks:
+        rows = slice(i * 128, min(i * 128 + 128, spec.N))
+        ref_rows.append(so.attention_rows(pro, rows, spec.causal, out_dtype="fp32"))
+        got_rows.append(wl.from_torch(out[b, h, rows]))
+    check_output(np.concatenate(got_rows), np.concatenate(ref_rows), spec.dtype)

@@ -131,6 +131,48 @@ def test_attention_output_matches_oracle(N, d, dtype, H, Hkv, causal, mode):
     assert wl.cos_sim(got[0], full) > (0.9 if mode == "int4_fp8" else 0.99)
 
 
+# ---- optional smooth V (Sec. 3.4 last paragraph; Appendix "Smoothing V") ----------------------
+SMOOTH_V_CASES = [
+    (250, 64, "fp16", 2, 2, False),
+    (333, 128, "bf16", 2, 1, True),
+    (640, 128, "bf16", 4, 2, False),
+]
+
+
+@pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("N,d,dtype,H,Hkv,causal", SMOOTH_V_CASES)
+def test_smooth_v_matches_oracle(N, d, dtype, H, Hkv, causal, mode):
+    pa = _pa()
+    spec = _spec(N, d, dtype, H, Hkv, causal=causal).with_(v_bias=8.5)
+    data, (q, k, v) = _gpu_inputs(spec)
+    print(f"smooth-V case N={N} d={d} {dtype} H={H}/{Hkv} causal={causal} mode={mode}", flush=True)
+    got, args, ws = pa.sage_attn_quant(q, k, v, causal=causal, mode=mode, smooth_v=True,
+                                       want=("v_codes", "v_scale", "v_mean", "k_codes", "k_scale"))
+    torch.cuda.synchronize()
+    got = {n: t.cpu().numpy() for n, t in got.items()}
+    for b in range(spec.B):
+        for hk in range(Hkv):
+            pro = so.quantize_head(data["q"][b, hk * (H // Hkv)], data["k"][b, hk], data["v"][b, hk], mode=mode,
+                                   smooth_v_on=True)
+            assert np.array_equal(got["v_mean"][b, hk], pro["vbar"]), "v mean"
+            assert np.array_equal(got["v_scale"][b, hk], pro["v_scale"]), "v scales of the centred values"
+            assert np.array_equal(got["v_codes"][b, hk], pro["v_codes"]), "v codes of the centred values"
+            assert np.array_equal(got["k_codes"][b, hk], pro["k_codes"]), "k codes unaffected"
+    out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, smooth_v=True)
+    plain = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode)
+    torch.cuda.synchronize()
+    got_out, got_plain = wl.from_torch(out), wl.from_torch(plain)
+    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32",
+                            smooth_v_on=True)
+    check_output(got_out, ref, dtype)
+    g = H // Hkv
+    full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
+                     for h in range(H)])
+    e_s, e_p = wl.rmse(got_out[0], full), wl.rmse(got_plain[0], full)
+    print(f"  RMSE vs FP64 attention: smooth V {e_s:.4f}, plain {e_p:.4f}", flush=True)
+    assert e_s < e_p        # the ordering the paper's table for this technique reports
+
+
 def test_plain_signature_and_repeatability():
     pa = _pa()
     spec = _spec(384, 128, "bf16", 2, 2)

@@ -30,6 +30,7 @@ class WorkloadSpec:
     outlier_gain: float
     token_norm_max: float  # token-wise scale drawn log-uniformly from [1, token_norm_max]
     config_id: int
+    v_bias: float = 0.0  # per-channel bias of V: sign random per channel, magnitude in v_bias +- 0.5
 
     def with_(self, **kw):
         return replace(self, **kw)
@@ -45,6 +46,8 @@ CONFIGS = {
     "causal32k": WorkloadSpec("causal32k", 1, 32, 32, 32768, 128, "bf16", True, 3.0, 3.0, 4, 10.0, 1.0, 3),
     # video-diffusion-like: ragged N, d=64, token norms vary
     "video17k": WorkloadSpec("video17k", 2, 48, 48, 17776, 64, "bf16", False, 4.0, 4.0, 0, 1.0, 8.0, 4),
+    # the same with the channel-wise V bias quoted for a video model (Appendix "Smoothing V": 8 to 9)
+    "video17k_vbias": WorkloadSpec("video17k_vbias", 2, 48, 48, 17776, 64, "bf16", False, 4.0, 4.0, 0, 1.0, 8.0, 4, 8.5),
     # long-context causal prefill with grouped KV heads (4 query heads per KV head)
     "long128k": WorkloadSpec("long128k", 1, 32, 8, 131072, 128, "bf16", True, 3.0, 3.0, 0, 1.0, 1.0, 5),
 }
@@ -100,6 +103,9 @@ def make_head(spec, which, b, h, seed=0):
         x = _qk_like(spec, rng, spec.k_offset_std)
     else:
         x = rng.standard_normal((spec.N, spec.d), dtype=np.float32)
+        if spec.v_bias > 0:
+            sign = np.where(rng.random((1, spec.d)) < 0.5, -1.0, 1.0)
+            x += (sign * rng.uniform(spec.v_bias - 0.5, spec.v_bias + 0.5, size=(1, spec.d))).astype(np.float32)
     return _finish(x, spec.dtype)
 
 
