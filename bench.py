@@ -121,7 +121,8 @@ def main():
             t = json.load(f).get(f"{args.workload}/{args.mode}")
         if t:
             traffic = t["hbm_read_bytes"] + t["hbm_write_bytes"]
-    # algorithmic bytes of the same launch: codes of Q, K, V (1 B each), Delta-S rows the tiles read,
+    # algorithmic bytes of the same launch: codes of Q, K (1 B, or 6 bits in the INT4 mode) and V (1 B),
+    # Delta-S rows the tiles read,
     # scales, and the 16-bit output
     BH, BHkv = spec.B * spec.H, spec.B * spec.H_kv
     nqb = (spec.N + 127) // 128
@@ -129,8 +130,9 @@ def main():
     if args.mode == "int4_fp8":
         per_row = [min(spec.N, (i * 128 + 128 + 63) // 64 * 64) if spec.causal else spec.N for i in range(nqb)]
         ds_bytes = 4 * BH * sum(per_row)
-    alg_bytes = (BH + 2 * BHkv) * spec.N * spec.d + ds_bytes + 4 * (BH * spec.N // 2 + BHkv * spec.N // 16) \
-        + 2 * BH * spec.N * spec.d
+    qk_code_bytes = 0.75 if args.mode == "int4_fp8" else 1.0      # 6-bit codes in the INT4 mode
+    alg_bytes = int((BH + BHkv) * spec.N * spec.d * qk_code_bytes) + BHkv * spec.N * spec.d + ds_bytes \
+        + 4 * (BH * spec.N // 2 + BHkv * spec.N // 16) + 2 * BH * spec.N * spec.d
 
     res = {
         "metric": "quantized attention TOPS at d=128 (causal + non-causal), cos-sim vs FP32",

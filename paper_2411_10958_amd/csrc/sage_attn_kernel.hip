@@ -33,30 +33,31 @@ struct AttnParams {
 // queries).  ka: the block's K^ chunks already in registers (chunk (s, kt) at ka[2s + kt]); qreg:
 // the wavefront's Q^ B-operands (one per 32-channel step).  Element acc[kt][v] belongs to key
 // 32*kt + 16*(lane/32) + v of the block and to query lane%32 of the wavefront.
-// INT8 mode: v_mfma_i32_32x32x32_i8, int32 accumulators.  INT4 mode: the codes are E4M3 bytes and
-// two 32-channel steps feed one v_mfma_f32_32x32x64_f8f6f4 (both operands list their 64 channels
-// in the same order: the 16 of step 2s, then the 16 of step 2s+1, per lane half); the FP32
-// accumulators hold the exact integers.  Either way the result is returned as raw 32-bit lanes.
+// INT8 mode: v_mfma_i32_32x32x32_i8, int32 accumulators.  INT4 mode: the codes are 6-bit FP6 E2M3
+// values and feed v_mfma_f32_32x32x64_f8f6f4 in its FP6 operand format (twice the rate of the 8-bit
+// formats); the FP32 accumulators hold the exact integers.  Either way the result is returned as
+// raw 32-bit lanes.
 // The product is issued one MFMA ("step") at a time so that the steps can be spread between
 // pieces of vector work: step I works on key tile I % 2 and contraction piece I / 2 (64 channels
 // in the INT4 mode, 32 in the INT8 mode); the first piece of a tile starts from a zero accumulator.
-template <int D, bool INT4> constexpr int qk_steps() { return INT4 ? 2 * (D / 64) : 2 * (D / 32); }
+// Operand registers: INT8 mode one 16-byte chunk per (piece, tile); INT4 mode one FP6 payload (24
+// bytes in the low 6 dwords of an 8-dword operand) per (piece, tile).
+template <bool INT4> struct QkOperand { typedef v4i type; };
+template <> struct QkOperand<true> { typedef v8i type; };
+template <int D, bool INT4> constexpr int qk_pieces() { return INT4 ? D / 64 : D / 32; }
+template <int D, bool INT4> constexpr int qk_steps() { return 2 * qk_pieces<D, INT4>(); }
 
 template <int D, bool INT4, int I>
-__device__ __forceinline__ void qk_step(const v4i (&ka)[2 * (D / 32)], const v4i (&qreg)[D / 32],
+__device__ __forceinline__ void qk_step(const typename QkOperand<INT4>::type (&ka)[qk_steps<D, INT4>()],
+                                        const typename QkOperand<INT4>::type (&qreg)[qk_pieces<D, INT4>()],
                                         v16i (&acc)[2]) {
   constexpr int KT = I & 1, S = I >> 1;
   if constexpr (INT4) {
-    v8i bq, a;
-    bq[0] = qreg[2 * S][0]; bq[1] = qreg[2 * S][1]; bq[2] = qreg[2 * S][2]; bq[3] = qreg[2 * S][3];
-    bq[4] = qreg[2 * S + 1][0]; bq[5] = qreg[2 * S + 1][1]; bq[6] = qreg[2 * S + 1][2]; bq[7] = qreg[2 * S + 1][3];
-    const v4i a0 = ka[(2 * S) * 2 + KT], a1 = ka[(2 * S + 1) * 2 + KT];
-    a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
-    a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
     v16f c;
 #pragma unroll
     for (int v = 0; v < 16; ++v) c[v] = S == 0 ? 0.0f : __int_as_float(acc[KT][v]);
-    c = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, bq, c, 0, 0, 0, 0, 0, 0);
+    // operand format 2 = FP6 E2M3 for both A and B
+    c = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ka[S * 2 + KT], qreg[S], c, 2, 2, 0, 0, 0, 0);
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[KT][v] = __float_as_int(c[v]);
   } else {
@@ -67,11 +68,29 @@ __device__ __forceinline__ void qk_step(const v4i (&ka)[2 * (D / 32)], const v4i
   }
 }
 template <int D, bool INT4, int I = 0>
-__device__ __forceinline__ void qk_tile(const v4i (&ka)[2 * (D / 32)], const v4i (&qreg)[D / 32],
+__device__ __forceinline__ void qk_tile(const typename QkOperand<INT4>::type (&ka)[qk_steps<D, INT4>()],
+                                        const typename QkOperand<INT4>::type (&qreg)[qk_pieces<D, INT4>()],
                                         v16i (&acc)[2]) {
   if constexpr (I < qk_steps<D, INT4>()) {
     qk_step<D, INT4, I>(ka, qreg, acc);
     qk_tile<D, INT4, I + 1>(ka, qreg, acc);
+  }
+}
+
+// One (piece, tile) operand out of a packed K^ block or Q^ tile at `base` (LDS or global): INT8
+// mode chunk `op`*64 + lane; INT4 mode the lane's 16 bytes of op's first plane and 8 bytes of its
+// second plane.
+template <bool INT4, typename Ptr>
+__device__ __forceinline__ typename QkOperand<INT4>::type load_qk_operand(Ptr base, int op, int lane) {
+  if constexpr (INT4) {
+    const v4i lo = base[op * (OP6_BYTES / 16) + lane];
+    const uint2 hi = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(&base[op * (OP6_BYTES / 16) + 64]) + 8 * lane);
+    v8i r;
+    r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+    r[4] = (int)hi.x; r[5] = (int)hi.y; r[6] = 0; r[7] = 0;
+    return r;
+  } else {
+    return base[op * 64 + lane];
   }
 }
 
@@ -183,15 +202,21 @@ __device__ __forceinline__ void dma_b32(const void* gbase, unsigned voff, unsign
                :: "s"(lds_byte), "v"(voff), "s"(gbase) : "memory");
 }
 
+// An empty use of a register: the compiler must have the value complete (its load waited for) here.
+__device__ __forceinline__ void use_now(int x) { asm volatile("" :: "v"(x)); }
+__device__ __forceinline__ void use_now(float x) { asm volatile("" :: "v"(x)); }
+
 template <int D, bool INT4, bool CAUSAL, bool BF16>
 __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const AttnParams p) {
-  constexpr int KS = D / 32;          // 32-channel steps of the score product
   constexpr int CT = D / 32;          // 32-channel tiles of the output
-  constexpr int KC = D * BKV / 16;    // 16-byte chunks of one K^ (or V^) block
-  constexpr int CPT = KC / 256;       // chunks per thread per block copy (2 or 1)
+  constexpr int KC = D * BKV / 16;    // 16-byte chunks of one V^ block
+  constexpr int KCK = (int)(k_block_bytes(D, INT4) / 16);   // 16-byte chunks of one K^ block
+  constexpr int CPT = KC / 256;       // V^ chunks per thread per block copy (2 or 1)
+  constexpr int CPTK = (KCK + 255) / 256;   // K^ copy rounds (the last one may skip some wavefronts)
+  constexpr int MINC = KCK / 256 + CPT;     // copies every wavefront issues per block, at least
   constexpr int NST = 3;              // LDS stages: block j is read while j+1 and j+2 arrive
   constexpr int XC = 32;              // chunks of the small part: 64 Delta-S floats, then 4 key-group scales
-  constexpr int STAGE = 2 * KC + XC;  // chunks per stage: K^, V^, small part
+  constexpr int STAGE = KCK + KC + XC;   // chunks per stage: K^, V^, small part
   __shared__ v4i lds[NST][STAGE];
 
   // XCD-aware tile order: consecutive workgroup ids land on different XCDs (8 of them), so
@@ -210,7 +235,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   const int q_lo = qb * BQ + w * WQ;          // first query of this wavefront
   const int query = q_lo + n;
 
-  const v4i* gk = reinterpret_cast<const v4i*>(p.k_codes + bhkv * (size_t)p.nKb * BKV * D);
+  const v4i* gk = reinterpret_cast<const v4i*>(p.k_codes + bhkv * (size_t)p.nKb * k_block_bytes(D, INT4));
   const v4i* gv = reinterpret_cast<const v4i*>(p.v_codes + bhkv * (size_t)p.nKb * BKV * D);
   const float* gd = INT4 ? p.delta_s + ((size_t)bh * p.nQb + qb) * p.nKb * BKV : nullptr;
   const float* gs = p.k_scale + bhkv * (size_t)p.nKb * 4;
@@ -224,31 +249,39 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   auto issue = [&](int j, int st) {
     const unsigned sb = lds0 + (unsigned)st * (STAGE * 16);
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-      dma_b128(gk + (size_t)j * KC + i * 256, (unsigned)t * 16, sb + (unsigned)(i * 256 + 64 * w) * 16);
-      dma_b128(gv + (size_t)j * KC + i * 256, (unsigned)t * 16, sb + (unsigned)(KC + i * 256 + 64 * w) * 16);
+    for (int i = 0; i < CPTK; ++i) {
+      if (i * 256 + 64 * w < KCK)
+        dma_b128(gk + (size_t)j * KCK + i * 256, (unsigned)t * 16, sb + (unsigned)(i * 256 + 64 * w) * 16);
     }
+#pragma unroll
+    for (int i = 0; i < CPT; ++i)
+      dma_b128(gv + (size_t)j * KC + i * 256, (unsigned)t * 16, sb + (unsigned)(KCK + i * 256 + 64 * w) * 16);
     if (w == 0) {
-      if constexpr (INT4) dma_b32(gd + (size_t)j * BKV, (unsigned)lane * 4, sb + 2 * KC * 16);
+      if constexpr (INT4) dma_b32(gd + (size_t)j * BKV, (unsigned)lane * 4, sb + (KCK + KC) * 16);
     } else if (w == 1) {
-      if (lane < 4) dma_b32(gs + (size_t)j * 4, (unsigned)lane * 4, sb + 2 * KC * 16 + 256);
+      if (lane < 4) dma_b32(gs + (size_t)j * 4, (unsigned)lane * 4, sb + (KCK + KC) * 16 + 256);
     }
   };
-  // Every wavefront issues at least 2*CPT copies per block, in block order, and loads complete in
-  // order: "at most 2*CPT outstanding" therefore means every block but the newest has landed.
+  // Every wavefront issues at least MINC copies per block, in block order, and loads complete in
+  // order: "at most MINC outstanding" therefore means every block but the newest has landed.
   auto wait_all_but_newest = [&]() {
-    if constexpr (CPT == 2) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)" ::: "memory");
+    static_assert(MINC >= 1 && MINC <= 4, "copy count per block");
+    if constexpr (MINC == 4) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
+    else if constexpr (MINC == 3) asm volatile("s_waitcnt vmcnt(3) lgkmcnt(0)" ::: "memory");
+    else if constexpr (MINC == 2) asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)" ::: "memory");
   };
   auto wait_all = [&]() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); };
 
   // ---- this wavefront's Q^ operands (registers, for the whole kernel) and scale ----
-  v4i qreg[KS];
+  typedef typename QkOperand<INT4>::type qk_op;
+  constexpr int NP = qk_pieces<D, INT4>();
+  qk_op qreg[NP];
   {
-    const v4i* gq = reinterpret_cast<const v4i*>(p.q_codes + (size_t)bh * p.nQb * BQ * D);
-    const int qtile = qb * (BQ / WQ) + w;
+    const v4i* gq = reinterpret_cast<const v4i*>(p.q_codes + ((size_t)bh * p.nQb + qb) * q_slab_bytes(D, INT4)) +
+                    (size_t)w * (q_slab_bytes(D, INT4) / 16 / (BQ / WQ));
 #pragma unroll
-    for (int s = 0; s < KS; ++s) qreg[s] = gq[(size_t)(qtile * KS + s) * 64 + lane];
+    for (int s = 0; s < NP; ++s) qreg[s] = load_qk_operand<INT4>(gq, s, lane);
   }
   const float dq = p.q_scale[((size_t)bh * p.nQb + qb) * (BQ / QGROUP) + (w * WQ + n) / QGROUP];
 
@@ -289,19 +322,20 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   //      block j+1's running-max update.
   // Past the wavefront's last block C, X and Y work on a stale stage (in bounds, results unused):
   // unconditional, so that no register stays live for the sake of a path not taken.
-  v4i ka[2 * KS], va[2 * CT];
+  qk_op ka[2 * NP];
+  v4i va[2 * CT];
   v4f dsr[2][4];
   float dk0 = 0.0f, dk1 = 0.0f;
   auto read_k = [&](int stg) {
 #pragma unroll
-    for (int i = 0; i < 2 * KS; ++i) ka[i] = lds[stg][i * 64 + lane];
+    for (int i = 0; i < 2 * NP; ++i) ka[i] = load_qk_operand<INT4>(&lds[stg][0], i, lane);
   };
   auto read_v = [&](int stg) {
 #pragma unroll
-    for (int i = 0; i < 2 * CT; ++i) va[i] = lds[stg][KC + i * 64 + lane];
+    for (int i = 0; i < 2 * CT; ++i) va[i] = lds[stg][KCK + i * 64 + lane];
   };
   auto read_x = [&](int stg) {
-    const float* lx = reinterpret_cast<const float*>(&lds[stg][2 * KC]);
+    const float* lx = reinterpret_cast<const float*>(&lds[stg][KCK + KC]);
     if constexpr (INT4) {
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt) {
@@ -317,8 +351,11 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   // ordinary loads of Q^ and the scale inside the loop, where they would also wait for copies in
   // flight: use those registers here so that the loads are complete before the first copy.
 #pragma unroll
-  for (int s = 0; s < KS; ++s) asm volatile("" :: "v"(qreg[s]));
-  asm volatile("" :: "v"(dq));
+  for (int s = 0; s < NP; ++s) {
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(qk_op) / 4); ++i) use_now(qreg[s][i]);
+  }
+  use_now(dq);
   issue(0, 0);
   if (nblk > 1) { issue(1, 1); wait_all_but_newest(); } else { wait_all(); }
   __syncthreads();
@@ -444,17 +481,20 @@ template <int D, bool INT4>
 __global__ void __launch_bounds__(256) k_debug_qk(const int8_t* __restrict__ q_codes,
                                                   const int8_t* __restrict__ k_codes, int q_tile,
                                                   int kv_block, int32_t* __restrict__ out) {
-  __shared__ v4i lds[D * BKV / 16];
+  constexpr int KCK = (int)(k_block_bytes(D, INT4) / 16);
+  constexpr int NP = qk_pieces<D, INT4>();
+  __shared__ v4i lds[KCK];
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, n = lane & 31, half = lane >> 5;
-  const v4i* gk = reinterpret_cast<const v4i*>(k_codes) + (size_t)kv_block * (D * BKV / 16);
-  for (int i = t; i < D * BKV / 16; i += 256) lds[i] = gk[i];
+  const v4i* gk = reinterpret_cast<const v4i*>(k_codes) + (size_t)kv_block * KCK;
+  for (int i = t; i < KCK; i += 256) lds[i] = gk[i];
   __syncthreads();
-  v4i qreg[D / 32], ka[2 * (D / 32)];
-  const v4i* gq = reinterpret_cast<const v4i*>(q_codes);
+  typename QkOperand<INT4>::type qreg[NP], ka[2 * NP];
+  const v4i* gq = reinterpret_cast<const v4i*>(q_codes + (size_t)q_tile * q_slab_bytes(D, INT4)) +
+                  (size_t)w * (q_slab_bytes(D, INT4) / 16 / (BQ / WQ));
 #pragma unroll
-  for (int s = 0; s < D / 32; ++s) qreg[s] = gq[(size_t)((q_tile * (BQ / WQ) + w) * (D / 32) + s) * 64 + lane];
+  for (int s = 0; s < NP; ++s) qreg[s] = load_qk_operand<INT4>(gq, s, lane);
 #pragma unroll
-  for (int i = 0; i < 2 * (D / 32); ++i) ka[i] = lds[i * 64 + lane];
+  for (int i = 0; i < 2 * NP; ++i) ka[i] = load_qk_operand<INT4>(&lds[0], i, lane);
   v16i acc[2];
   qk_tile<D, INT4>(ka, qreg, acc);
 #pragma unroll
@@ -507,8 +547,8 @@ hipError_t launch_debug_qk(const Dims& D, const Ptrs& P, int b, int h, int q_til
                            int32_t* out, hipStream_t s) {
   const size_t bh = (size_t)b * D.H + h;
   const size_t bhkv = (size_t)b * D.Hkv + h / (D.H / D.Hkv);
-  const int8_t* qc = P.q_codes + bh * (size_t)D.nQb * BQ * D.d;
-  const int8_t* kc = P.k_codes + bhkv * (size_t)D.nKb * BKV * D.d;
+  const int8_t* qc = P.q_codes + bh * (size_t)D.nQb * q_slab_bytes(D.d, D.int4);
+  const int8_t* kc = P.k_codes + bhkv * (size_t)D.nKb * k_block_bytes(D.d, D.int4);
   if (D.d == 128) {
     if (D.int4) k_debug_qk<128, true><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
     else k_debug_qk<128, false><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);

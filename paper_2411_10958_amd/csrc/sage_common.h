@@ -35,8 +35,7 @@ struct Dims {
 //
 // Packed layouts (one "chunk" = 16 bytes = one lane's operand piece, 64 chunks = one
 // wavefront-wide ds_read_b128 / global load):
-//   (codes are two's-complement int8 bytes in the INT8 mode and E4M3 bytes of the same integers in
-//   the INT4 mode, see int4_code_to_e4m3 below)
+//  INT8 mode (two's-complement bytes):
 //   q_codes: [B*H][N_q32 tiles of 32 queries][d/32 k-steps][64 lanes] chunks.  Lane l of
 //            k-step s holds query 32*tile + l%32, channels 32*s + 16*(l/32) + 0..15
 //            (the B operand of v_mfma_i32_32x32x32_i8).
@@ -44,6 +43,14 @@ struct Dims {
 //            MFMA row rho = l%32 and channels 32*s + 16*(l/32) + 0..15, where row
 //            rho = 8g + 4h + r carries key 32*tile + 16h + 4g + r of the block, so that an
 //            accumulator lane (half h) ends up with 16 consecutive keys.
+//  INT4 mode (6-bit FP6 E2M3 codes of the same integers, see int4_code_to_e2m3 below): one
+//  operand of v_mfma_f32_32x32x64_f8f6f4 ("op") covers 32 rows x 64 channels; lane l supplies row
+//  l%32 and channels 32*(l/32) + e, element e at bit 6e of a 24-byte payload.  An op is stored
+//  as 1536 bytes: a plane of 64 x 16 bytes (payload bytes 0..15 of lanes 0..63) followed by a
+//  plane of 64 x 8 bytes (payload bytes 16..23), so that one ds_read_b128 and one ds_read_b64
+//  per lane fetch it without bank conflicts.
+//   q_codes: [B*H][N_q32 tiles][d/64 ops] x 1536 bytes (row = query 32*tile + l%32).
+//   k_codes: [B*Hkv][nKb blocks][d/64 ops][2 key tiles] x 1536 bytes (row rho as above).
 //   v_codes: [B*Hkv][nKb blocks][d/32 channel tiles][2 parts][64 lanes] chunks.  Lane l holds
 //            channel 32*ct + l%32 and the 16 keys 32*part + 16*(l/32) + 0..15 of the block
 //            (the A operand of v_mfma_f32_32x32x64_f8f6f4, key order matching the order in
@@ -57,6 +64,15 @@ struct Workspace {
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+constexpr int OP6_BYTES = 1536;   // one FP6 MFMA operand (32 rows x 64 channels x 6 bits)
+// bytes of the packed codes of one 128-query slab / one 64-key block
+__host__ __device__ constexpr size_t q_slab_bytes(int d, bool int4) {
+  return int4 ? (size_t)(BQ / 32) * (d / 64) * OP6_BYTES : (size_t)BQ * d;
+}
+__host__ __device__ constexpr size_t k_block_bytes(int d, bool int4) {
+  return int4 ? (size_t)(d / 64) * 2 * OP6_BYTES : (size_t)BKV * d;
+}
 
 inline Workspace make_workspace(const Dims& D) {
   Workspace w;
@@ -72,8 +88,8 @@ inline Workspace make_workspace(const Dims& D) {
   w.q_mean = take(BH * D.nQb * D.d * sizeof(float));
   w.q_scale = take(BH * D.nQb * (BQ / QGROUP) * sizeof(float));
   w.k_scale = take(BHkv * D.nKb * (BKV / KGROUP) * sizeof(float));
-  w.q_codes = take(BH * D.nQb * BQ * D.d);
-  w.k_codes = take(BHkv * D.nKb * BKV * D.d);
+  w.q_codes = take(BH * D.nQb * q_slab_bytes(D.d, D.int4));
+  w.k_codes = take(BHkv * D.nKb * k_block_bytes(D.d, D.int4));
   w.v_codes = take(BHkv * D.nKb * BKV * D.d);
   w.delta_s = take(D.int4 ? BH * D.nQb * D.nKb * BKV * sizeof(float) : 0);
   w.total = off;
@@ -131,20 +147,39 @@ __host__ __device__ inline size_t v_code_off(int n, int c, int d) {
   return ((size_t)((blk * (d >> 5) + ct) * 2 + part) * 64 + ch + 32 * h) * 16 + byte;
 }
 
-// ---- INT4 codes travel as FP8 E4M3 bytes ----
-// Every integer in [-7, 7] is an E4M3 value (1, 2, 3 = 1.5*2, 4, 5 = 1.25*4, 6 = 1.5*4, 7 = 1.75*4),
-// products (<= 49) and their sums over d <= 128 channels (<= 6272) are exact in the FP32 accumulator
-// of v_mfma_f32_32x32x64_f8f6f4, so the score product of the INT4 mode runs on the FP8 matrix pipe
-// and yields the exact integer accumulators as floats - no int->float conversion afterwards.
-__host__ __device__ inline unsigned char int4_code_to_e4m3(int c) {
-  const unsigned long long tab = 0x4E4C4A4844403800ull;   // bytes for |c| = 0..7
+// ---- INT4 codes travel as 6-bit FP6 E2M3 values ----
+// gfx950 has no 4-bit integer MFMA, but every integer in [-7, 7] is an E2M3 value (sign, 2 exponent
+// bits with bias 1, 3 mantissa bits: 1, 2, 3 = 1.5*2, 4, 5 = 1.25*4, 6 = 1.5*4, 7 = 1.75*4), products
+// (<= 49) and their sums over d <= 128 channels (<= 6272) are exact in the FP32 accumulator of
+// v_mfma_f32_32x32x64_f8f6f4, and the FP6 operand format runs at twice the rate of the 8-bit
+// formats: the gfx950 counterpart of "INT4 matmul is twice as fast as INT8".  The accumulators come
+// out as exact integers in float - no int->float conversion afterwards.
+__host__ __device__ inline unsigned int4_code_to_e2m3(int c) {
+  const unsigned long long tab = 0x1E1C1A1814100800ull;   // (exponent << 3 | mantissa) for |c| = 0..7
   const int a = c < 0 ? -c : c;
-  return (unsigned char)(((tab >> (8 * a)) & 0xffu) | (c < 0 ? 0x80u : 0u));
+  return (unsigned)((tab >> (8 * a)) & 0x1fu) | (c < 0 ? 0x20u : 0u);
 }
-__host__ __device__ inline int e4m3_to_int4_code(unsigned char b) {
-  const int e = (b >> 3) & 15, m = b & 7;
-  const int a = e == 0 ? 0 : ((8 + m) << (e - 7)) >> 3;     // (1 + m/8) * 2^(e-7), e in 7..9 here
-  return (b & 0x80) ? -a : a;
+__host__ __device__ inline int e2m3_to_int4_code(unsigned b) {
+  const int e = (b >> 3) & 3, m = b & 7;
+  const int a = e == 0 ? 0 : ((8 + m) << (e - 1)) >> 3;     // (1 + m/8) * 2^(e-1)
+  return (b & 0x20) ? -a : a;
+}
+// byte b (0..23) of lane_m's payload inside an op (16-byte plane, then 8-byte plane)
+__host__ __device__ inline int op6_byte(int lane_m, int b) {
+  return b < 16 ? lane_m * 16 + b : 1024 + lane_m * 8 + (b - 16);
+}
+// op base (bytes inside one (batch, head) slab), MFMA lane and element index of query / key n, channel c
+__host__ __device__ inline size_t q_op6(int n, int c, int d, int* lane_m, int* e) {
+  *lane_m = (n & 31) + 32 * ((c >> 5) & 1);
+  *e = c & 31;
+  return (size_t)((n >> 5) * (d >> 6) + (c >> 6)) * OP6_BYTES;
+}
+__host__ __device__ inline size_t k_op6(int n, int c, int d, int* lane_m, int* e) {
+  const int blk = n >> 6, kt = (n >> 5) & 1, kk = n & 31;
+  const int rho = 8 * ((kk >> 2) & 3) + 4 * (kk >> 4) + (kk & 3);
+  *lane_m = rho + 32 * ((c >> 5) & 1);
+  *e = c & 31;
+  return (size_t)((blk * (d >> 6) + (c >> 6)) * 2 + kt) * OP6_BYTES;
 }
 
 // ---- 16-bit input helpers ----

@@ -35,17 +35,28 @@ __device__ inline int quant_code(float x, float delta, int qmax) {
   return c > qmax ? qmax : (c < -qmax ? -qmax : c);
 }
 
-template <bool AS_E4M3>
-__device__ inline uint2 pack8(const int (&cc)[8]) {
-  int c[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) c[e] = AS_E4M3 ? (int)int4_code_to_e4m3(cc[e]) : cc[e];
+// eight int8 codes as two's-complement bytes
+__device__ inline uint2 pack8(const int (&c)[8]) {
   uint2 o;
   o.x = (unsigned)(c[0] & 0xff) | ((unsigned)(c[1] & 0xff) << 8) | ((unsigned)(c[2] & 0xff) << 16) |
         ((unsigned)(c[3] & 0xff) << 24);
   o.y = (unsigned)(c[4] & 0xff) | ((unsigned)(c[5] & 0xff) << 8) | ((unsigned)(c[6] & 0xff) << 16) |
         ((unsigned)(c[7] & 0xff) << 24);
   return o;
+}
+
+// N6 INT4 codes as consecutive 6-bit E2M3 fields (element e at bit 6e), N6 * 6 / 32 dwords
+template <int N6>
+__device__ inline void pack6(const int (&c)[N6], unsigned (&w)[N6 * 6 / 32]) {
+#pragma unroll
+  for (int i = 0; i < N6 * 6 / 32; ++i) w[i] = 0u;
+#pragma unroll
+  for (int e = 0; e < N6; ++e) {
+    const unsigned v = int4_code_to_e2m3(c[e]);
+    const int wi = (6 * e) >> 5, sh = (6 * e) & 31;
+    w[wi] |= v << sh;
+    if (sh > 26) w[wi + 1] |= v >> (32 - sh);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -210,8 +221,8 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
       }
     }
   }
-  // codes go to LDS in the packed order of this 128-query slab (4 tiles x d/32 steps x 64 lanes
-  // chunks, contiguous in the workspace) and leave as coalesced 16-byte stores
+  // codes go to LDS in the packed order of this 128-query slab (contiguous in the workspace) and
+  // leave as coalesced 16-byte stores
   __shared__ uint4 s_codes[BQ * D / 16];
   uint8_t* img = reinterpret_cast<uint8_t*>(s_codes);
 #pragma unroll
@@ -228,13 +239,29 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
       int c[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) c[e] = quant_code(x[i][e], delta, QMAX);
-      *reinterpret_cast<uint2*>(img + q_code_off(rg * RPT + i, cg * 8, D)) = pack8<INT4>(c);
+      if constexpr (INT4) {
+        // 8 codes = 48 bits = payload bytes 6*(cg%4) .. +5 of the row's lane: three 2-byte stores
+        int c16[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) c16[e] = e < 8 ? c[e] : 0;
+        unsigned w[3];
+        pack6<16>(c16, w);
+        int lane_m, e0;
+        const size_t op = q_op6(rg * RPT + i, cg * 8, D, &lane_m, &e0);
+        const int b0 = 6 * (e0 >> 3);
+        *reinterpret_cast<unsigned short*>(img + op + op6_byte(lane_m, b0)) = (unsigned short)(w[0] & 0xffffu);
+        *reinterpret_cast<unsigned short*>(img + op + op6_byte(lane_m, b0 + 2)) = (unsigned short)(w[0] >> 16);
+        *reinterpret_cast<unsigned short*>(img + op + op6_byte(lane_m, b0 + 4)) = (unsigned short)(w[1] & 0xffffu);
+      } else {
+        *reinterpret_cast<uint2*>(img + q_code_off(rg * RPT + i, cg * 8, D)) = pack8(c);
+      }
     }
   }
   __syncthreads();
-  uint4* dst = reinterpret_cast<uint4*>(q_codes + (bh * nQb + qb) * (size_t)BQ * D);
+  constexpr int SLAB16 = (int)(q_slab_bytes(D, INT4) / 16);
+  uint4* dst = reinterpret_cast<uint4*>(q_codes + (bh * nQb + qb) * q_slab_bytes(D, INT4));
 #pragma unroll
-  for (int i = t; i < BQ * D / 16; i += 256) dst[i] = s_codes[i];
+  for (int i = t; i < SLAB16; i += 256) dst[i] = s_codes[i];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -331,17 +358,34 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
   const float delta = __fdiv_rn(mx, (float)QMAX);
   if (lane == 0) k_scale[(bhkv * nKb + kb) * (BKV / KGROUP) + w] = delta;
   uint8_t* img = reinterpret_cast<uint8_t*>(s_codes);
+  if constexpr (INT4) {
+    // the lane's CPL codes are CPL*6/32 consecutive dwords of one MFMA lane's payload (all 6 of
+    // them when d = 128; dwords 0..2 or 3..5 when d = 64)
+    int c[CPL];
 #pragma unroll
-  for (int p = 0; p < CPL / 8; ++p) {
-    int c[8];
+    for (int e = 0; e < CPL; ++e) c[e] = quant_code(x[e], delta, QMAX);
+    unsigned w[CPL * 6 / 32];
+    pack6<CPL>(c, w);
+    int lane_m, e0;
+    const size_t op = k_op6(r, c0, D, &lane_m, &e0);
+    const int d0 = (6 * e0) >> 5;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) c[e] = quant_code(x[8 * p + e], delta, QMAX);
-    *reinterpret_cast<uint2*>(img + k_code_off(r, c0 + 8 * p, D)) = pack8<INT4>(c);
+    for (int i = 0; i < CPL * 6 / 32; ++i)
+      *reinterpret_cast<unsigned*>(img + op + op6_byte(lane_m, 4 * (d0 + i))) = w[i];
+  } else {
+#pragma unroll
+    for (int p = 0; p < CPL / 8; ++p) {
+      int c[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) c[e] = quant_code(x[8 * p + e], delta, QMAX);
+      *reinterpret_cast<uint2*>(img + k_code_off(r, c0 + 8 * p, D)) = pack8(c);
+    }
   }
   __syncthreads();
-  uint4* dst = reinterpret_cast<uint4*>(k_codes + (bhkv * nKb + kb) * (size_t)BKV * D);
+  constexpr int BLK16 = (int)(k_block_bytes(D, INT4) / 16);
+  uint4* dst = reinterpret_cast<uint4*>(k_codes + (bhkv * nKb + kb) * k_block_bytes(D, INT4));
 #pragma unroll
-  for (int i = t; i < BKV * D / 16; i += 256) dst[i] = s_codes[i];
+  for (int i = t; i < BLK16; i += 256) dst[i] = s_codes[i];
 
   if constexpr (INT4) {
     // FP64 MFMA lane map: lane l supplies A[l%16][l/16] and B[l/16][l%16]; result element v of
@@ -436,14 +480,24 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
 // ------------------------------------------------------------------------------------------
 // Copies from the packed workspace to plain layouts (used only by sage_attn_quant).
 __global__ void k_unpack_codes(const int8_t* __restrict__ packed, int8_t* __restrict__ plain, int N,
-                               int d, size_t slab, int which, int e4m3_ints) {
-  // grid: (ceil(N*d/256), heads); which: 0 = q, 1 = k, 2 = v; e4m3_ints: q/k bytes hold integers as E4M3
+                               int d, size_t slab, int which, int fp6) {
+  // grid: (ceil(N*d/256), heads); which: 0 = q, 1 = k, 2 = v; fp6: q/k hold 6-bit E2M3 codes
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (size_t)N * d) return;
   const int n = (int)(i / d), c = (int)(i % d);
-  const size_t off = which == 0 ? q_code_off(n, c, d) : (which == 1 ? k_code_off(n, c, d) : v_code_off(n, c, d));
-  int8_t b = packed[(size_t)blockIdx.y * slab + off];
-  if (e4m3_ints && which != 2) b = (int8_t)e4m3_to_int4_code((unsigned char)b);
+  const uint8_t* src = reinterpret_cast<const uint8_t*>(packed) + (size_t)blockIdx.y * slab;
+  int8_t b;
+  if (fp6 && which != 2) {
+    int lane_m, e;
+    const size_t op = which == 0 ? q_op6(n, c, d, &lane_m, &e) : k_op6(n, c, d, &lane_m, &e);
+    const int bit = 6 * e, by = bit >> 3;
+    unsigned v = src[op + op6_byte(lane_m, by)];
+    if (by + 1 < 24) v |= (unsigned)src[op + op6_byte(lane_m, by + 1)] << 8;
+    b = (int8_t)e2m3_to_int4_code((v >> (bit & 7)) & 63u);
+  } else {
+    const size_t off = which == 0 ? q_code_off(n, c, d) : (which == 1 ? k_code_off(n, c, d) : v_code_off(n, c, d));
+    b = (int8_t)src[off];
+  }
   plain[(size_t)blockIdx.y * N * d + i] = b;
 }
 
@@ -503,8 +557,8 @@ hipError_t launch_unpack(const Dims& D, const Ptrs& P, const void* quant_out, hi
       qo.v_mean};
   const int BH = D.B * D.H, BHkv = D.B * D.Hkv;
   const unsigned gx = (unsigned)(((size_t)D.N * D.d + 255) / 256);
-  if (o.qc) k_unpack_codes<<<dim3(gx, BH), 256, 0, s>>>(P.q_codes, o.qc, D.N, D.d, (size_t)D.nQb * BQ * D.d, 0, D.int4);
-  if (o.kc) k_unpack_codes<<<dim3(gx, BHkv), 256, 0, s>>>(P.k_codes, o.kc, D.N, D.d, (size_t)D.nKb * BKV * D.d, 1, D.int4);
+  if (o.qc) k_unpack_codes<<<dim3(gx, BH), 256, 0, s>>>(P.q_codes, o.qc, D.N, D.d, D.nQb * q_slab_bytes(D.d, D.int4), 0, D.int4);
+  if (o.kc) k_unpack_codes<<<dim3(gx, BHkv), 256, 0, s>>>(P.k_codes, o.kc, D.N, D.d, D.nKb * k_block_bytes(D.d, D.int4), 1, D.int4);
   if (o.vc) k_unpack_codes<<<dim3(gx, BHkv), 256, 0, s>>>((const int8_t*)P.v_codes, (int8_t*)o.vc, D.N, D.d, (size_t)D.nKb * BKV * D.d, 2, 0);
   const int nqg = (D.N + QGROUP - 1) / QGROUP, nkg = (D.N + KGROUP - 1) / KGROUP;
   if (o.qs) k_unpack_rows<<<dim3((nqg + 255) / 256, BH), 256, 0, s>>>(P.q_scale, o.qs, nqg, D.nQb * (BQ / QGROUP));
