@@ -105,7 +105,10 @@ template <int D> struct RowState {
 // keys (one "group": registers 4G..4G+3 of key tile KT) so that MFMAs can be issued between them.
 //
 // dequant_group: the raw scores of the group are dequantized (+ Delta-S) into sc, in base 2
-// (Algorithm 1, score line); MASKED adds the causal diagonal and the keys beyond N.
+// (Algorithm 1, score line); MASKED adds the causal diagonal and the keys beyond N.  In the INT8
+// mode there is no Delta-S and one positive factor c per key tile, so sc keeps the accumulators
+// as floats: the maximum commutes with the factor and the product is fused into the exponent's
+// argument (exp_group), one instruction less per score.
 template <bool INT4, bool CAUSAL, bool MASKED, int KT, int G>
 __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2], const v4f (&dsr)[2][4],
                                               float c, int half, int key0, int query, int N) {
@@ -113,7 +116,7 @@ __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2
   for (int r = 0; r < 4; ++r) {
     float x;
     if constexpr (INT4) x = __fmaf_rn(__int_as_float(raw[KT][4 * G + r]), c, dsr[KT][G][r]);
-    else x = __fmul_rn((float)raw[KT][4 * G + r], c);
+    else x = (float)raw[KT][4 * G + r];
     if constexpr (MASKED) {
       const int key = key0 + 32 * KT + 16 * half + 4 * G + r;
       if (key >= N || (CAUSAL && key > query)) x = -INFINITY;
@@ -124,12 +127,26 @@ __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2
 
 // update_max: running max over the block's 64 dequantized scores of this lane's query (Eq. 1 /
 // Algorithm 1); returns alpha = 2^(m_old - m_new) and, in m_sub, the exponent offset of the block.
-template <int D>
-__device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2], float& m_sub) {
-  float mx = fmaxf(__int_as_float(acc[0][0]), __int_as_float(acc[1][0]));
+template <int D, bool INT4>
+__device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2], float c0, float c1,
+                                            float& m_sub) {
+  float mx;
+  if constexpr (INT4) {
+    mx = fmaxf(__int_as_float(acc[0][0]), __int_as_float(acc[1][0]));
 #pragma unroll
-  for (int v = 1; v < 16; ++v)   // one v_max3_f32 per step
-    mx = fmaxf(fmaxf(mx, __int_as_float(acc[0][v])), __int_as_float(acc[1][v]));
+    for (int v = 1; v < 16; ++v)   // one v_max3_f32 per step
+      mx = fmaxf(fmaxf(mx, __int_as_float(acc[0][v])), __int_as_float(acc[1][v]));
+  } else {
+    // per key tile: max of the accumulators, then the tile's factor (c >= 0, so the order does not
+    // matter; a fully masked tile with c = 0 gives NaN, which fmaxf drops)
+    float m0 = __int_as_float(acc[0][0]), m1 = __int_as_float(acc[1][0]);
+#pragma unroll
+    for (int v = 1; v < 16; v += 2) {
+      m0 = fmaxf(fmaxf(m0, __int_as_float(acc[0][v])), __int_as_float(acc[0][(v + 1) & 15]));
+      m1 = fmaxf(fmaxf(m1, __int_as_float(acc[1][v])), __int_as_float(acc[1][(v + 1) & 15]));
+    }
+    mx = fmaxf(__fmul_rn(m0, c0), __fmul_rn(m1, c1));
+  }
   {
     // the other half of the wavefront holds the other 32 keys of the same query
     const unsigned u = __float_as_uint(mx);
@@ -143,14 +160,22 @@ __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2
   return alpha;
 }
 
-// exp_group: 448 * P~ = 2^(S - m_sub) for the group, its row-sum share added to ls, its FP8 codes
-// written into word 4*KT + G of the P~ operand.
-template <int KT, int G>
-__device__ __forceinline__ void exp_group(const v16i (&acc)[2], float m_sub, v8i& pb, float& ls) {
+// exp_group: 448 * P~ = 2^(S - m_sub) for the group (INT8 mode: S = sc * c, fused), its row-sum share
+// added to ls, its FP8 codes written into word 4*KT + G of the P~ operand.
+template <bool INT4, bool MASKED, int KT, int G>
+__device__ __forceinline__ void exp_group(const v16i (&acc)[2], float c, float m_sub, v8i& pb, float& ls) {
   float e[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
-    e[r] = __builtin_amdgcn_exp2f(__int_as_float(acc[KT][4 * G + r]) - m_sub);
+    const float x = __int_as_float(acc[KT][4 * G + r]);
+    float arg;
+    if constexpr (INT4) {
+      arg = x - m_sub;
+    } else {
+      arg = __fmaf_rn(x, c, -m_sub);
+      if constexpr (MASKED) arg = x == -INFINITY ? -INFINITY : arg;   // also when c = 0
+    }
+    e[r] = __builtin_amdgcn_exp2f(arg);
     ls += e[r];
   }
   int wd = __float_as_int(e[0]);   // any value: both halves are overwritten below
@@ -363,7 +388,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   read_x(0);
   v16i raw[2], sc[2];                 // raw scores being produced / dequantized scores of block j
   qk_tile<D, INT4>(ka, qreg, raw);    // block 0 holds a visible key for every query
-  float alpha, m_sub;
+  float alpha, m_sub, cj0, cj1;       // of block j; cj0, cj1: its dequantization factors per key tile
   constexpr int NQK = qk_steps<D, INT4>();
   constexpr int GPC = 8 / CT;         // dequantization groups per P~V MFMA
 
@@ -379,14 +404,15 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   {
     const float c0 = __fmul_rn(__fmul_rn(dq, dk0), p.kappa), c1 = __fmul_rn(__fmul_rn(dq, dk1), p.kappa);
     if (n_plain > 0) SAGE_DEQ_ALL(false, 0); else SAGE_DEQ_ALL(true, 0);
-    alpha = update_max<D>(st, sc, m_sub);
+    alpha = update_max<D, INT4>(st, sc, c0, c1, m_sub);
+    cj0 = c0; cj1 = c1;
   }
 
   int cur = 0;   // stage of block j
-#define SAGE_X(GI_)                                                                                  \
+#define SAGE_X(GI_, MASKED_)                                                                         \
   do {                                                                                               \
     if constexpr ((GI_) < NQK) qk_step<D, INT4, (GI_) < NQK ? (GI_) : 0>(ka, qreg, raw);             \
-    exp_group<(GI_) / 4, (GI_) % 4>(sc, m_sub, pb, ls);                                              \
+    exp_group<INT4, MASKED_, (GI_) / 4, (GI_) % 4>(sc, (GI_) / 4 == 0 ? cj0 : cj1, m_sub, pb, ls);   \
     __builtin_amdgcn_sched_barrier(0);                                                               \
   } while (0)
 #define SAGE_Y(CT_, MASKED_)                                                                         \
@@ -402,7 +428,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
       __builtin_amdgcn_sched_barrier(0);                                                             \
     }                                                                                                \
   } while (0)
-#define SAGE_BODY(MASKED_NEXT_)                                                                      \
+#define SAGE_BODY(MASKED_, MASKED_NEXT_)                                                                    \
   do {                                                                                               \
     const int nx1 = cur == NST - 1 ? 0 : cur + 1;                                                    \
     const int nx2 = nx1 == NST - 1 ? 0 : nx1 + 1;                                                    \
@@ -414,20 +440,22 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     __builtin_amdgcn_sched_barrier(0);                                                               \
     v8i pb;                                                                                          \
     float ls = 0.0f;                                                                                 \
-    SAGE_X(0); SAGE_X(1); SAGE_X(2); SAGE_X(3);                                               /* X */ \
+    SAGE_X(0, MASKED_); SAGE_X(1, MASKED_); SAGE_X(2, MASKED_); SAGE_X(3, MASKED_);           /* X */ \
     read_v(cur);                                                                                     \
     read_x(nx1);                                                                                     \
     __builtin_amdgcn_sched_barrier(0);                                                               \
-    SAGE_X(4); SAGE_X(5); SAGE_X(6); SAGE_X(7);                                                      \
+    SAGE_X(4, MASKED_); SAGE_X(5, MASKED_); SAGE_X(6, MASKED_); SAGE_X(7, MASKED_);                  \
     st.l_run = __fmaf_rn(alpha, st.l_run, ls);                                                       \
     const float c0 = __fmul_rn(__fmul_rn(dq, dk0), p.kappa), c1 = __fmul_rn(__fmul_rn(dq, dk1), p.kappa); \
     SAGE_Y(0, MASKED_NEXT_); SAGE_Y(1, MASKED_NEXT_); SAGE_Y(2, MASKED_NEXT_); SAGE_Y(3, MASKED_NEXT_); /* Y */ \
-    alpha = update_max<D>(st, sc, m_sub);                                                            \
+    alpha = update_max<D, INT4>(st, sc, c0, c1, m_sub);                                              \
+    cj0 = c0; cj1 = c1;                                                                              \
     cur = nx1;                                                                                       \
   } while (0)
   int j = 0;
-  for (; j + 1 < n_plain; ++j) SAGE_BODY(false);
-  for (; j < n_act; ++j) SAGE_BODY(true);
+  for (; j + 1 < n_plain; ++j) SAGE_BODY(false, false);
+  if (j < n_plain) { SAGE_BODY(false, true); ++j; }      // the last unmasked block, a masked (or no) successor
+  for (; j < n_act; ++j) SAGE_BODY(true, true);
   // causal only: blocks past this wavefront's last query - keep up the copies and the barriers
   for (; j < nblk; ++j) {
     const int nx1 = cur == NST - 1 ? 0 : cur + 1;
