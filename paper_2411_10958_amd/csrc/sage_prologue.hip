@@ -422,8 +422,8 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
 // ------------------------------------------------------------------------------------------
 // V: per-channel FP8 E4M3 codes, transposed into the A-operand order of the P~V product
 // (Sec. 3.3; Algorithm 1 "Preprocessing": (delta_V, V^) = psi_V(V)).  v_mean is null, or the token
-// mean to subtract first (smooth-V option).
-template <bool BF16, int D>
+// mean to subtract first (smooth-V option, SMOOTH_V).
+template <bool BF16, int D, bool SMOOTH_V>
 __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restrict__ V,
                                                  const float* __restrict__ v_scale,
                                                  const float* __restrict__ v_mean,
@@ -438,7 +438,7 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     sc[e] = v_scale[bh * D + cg * 8 + e];
-    mean[e] = v_mean ? v_mean[bh * D + cg * 8 + e] : 0.0f;
+    mean[e] = SMOOTH_V ? v_mean[bh * D + cg * 8 + e] : 0.0f;
   }
 #pragma unroll
   for (int i = 0; i < RPT; ++i) {
@@ -448,7 +448,7 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
       load8<BF16>(V + (bh * N + n0 + r) * D + cg * 8, x);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        if (v_mean) x[e] = __fsub_rn(x[e], mean[e]);
+        if constexpr (SMOOTH_V) x[e] = __fsub_rn(x[e], mean[e]);
         x[e] = sc[e] > 0.0f ? __fdiv_rn(x[e], sc[e]) : 0.0f;
       }
     } else {
@@ -534,7 +534,8 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
                                                               P.delta_s, Dm.N, Dm.nKb, Dm.nQb, Dm.H / Dm.Hkv,
                                                               Dm.kappa);
-  k_quant_v<BF16, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.nKb);
+  if (Dm.smooth_v) k_quant_v<BF16, D, true><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.nKb);
+  else k_quant_v<BF16, D, false><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.N, Dm.nKb);
   return hipGetLastError();
 }
 
