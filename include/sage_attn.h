@@ -36,7 +36,7 @@ extern "C" {
 enum {
   SAGE_OK = 0,
   SAGE_ERR_INVALID_ARG = -1,  /* null pointer, non-positive size, H % H_kv != 0 */
-  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode, dtype or flag */
+  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode, dtype, flag or group map */
   SAGE_ERR_WORKSPACE = -3,    /* workspace missing or smaller than sage_attn_workspace_bytes() */
   SAGE_ERR_HIP = -4           /* a HIP call or launch failed (the HIP error is cleared) */
 };
@@ -50,6 +50,12 @@ enum { SAGE_DT_FP16 = 0, SAGE_DT_BF16 = 1 };
    the per-channel token mean of V is subtracted before the FP8 quantizer and added back, in FP32, to
    the output (rows of the softmax sum to 1).  Costs one more pass over V in the preprocessing. */
 enum { SAGE_FLAG_SMOOTH_V = 1 };
+/* Quantization granularity of Q and K (Sec. 3.2; the ablation of the paper's granularity table).
+   SAGE_GROUPS_LANE: the default, the gfx950 counterpart of per-thread quantization (SAGE_Q_GROUP /
+   SAGE_K_GROUP below).  SAGE_GROUPS_BLOCK: one scale per 128-query block and per 64-key block
+   (per-block quantization, the granularity of SageAttention-1, Sec. 2.3); same kernels, same speed,
+   lower accuracy.  q_scale / k_scale keep their shapes (values repeat inside a block). */
+enum { SAGE_GROUPS_LANE = 0, SAGE_GROUPS_BLOCK = 1 };
 
 /* Numerical block sizes of Algorithm 1 as this library fixes them. */
 #define SAGE_BQ_SMOOTH 128 /* tokens per Q smoothing block (b_q) */
@@ -70,6 +76,7 @@ typedef struct sage_attn_args {
   int mode;               /* SAGE_MODE_* */
   int dtype;              /* SAGE_DT_* : type of q, k, v and out */
   int flags;              /* SAGE_FLAG_* or-ed together; 0 = the paper's default configuration */
+  int group_map;          /* SAGE_GROUPS_*; 0 = the default */
   void* workspace;        /* device scratch of >= sage_attn_workspace_bytes(); 256-byte aligned */
   size_t workspace_bytes;
   void* stream;           /* hipStream_t, NULL = default stream */

@@ -21,7 +21,12 @@ Precision rules (the readings this repository takes where the paper is silent):
     and 2**x replaces e**x, which leaves softmax unchanged;  the score of one (query, key)
     pair is the single FP32 rounding of  acc * c + D  with c = fl32(fl32(dQ*dK) * kappa)
     and D = fl32(kappa * <qbar_i, gamma(K)_t>)  (inner product in float64);
-  * l (the softmax denominator) sums the unquantized FP32 P~ as Algorithm 1 prints it;
+  * the FP8 code of P~ is decided on  E = 448 * P~  evaluated as one exponential,
+    E = fl32(2**fl32(S - m_sub)) with m_sub = fl32(m - fl32(log2 448))  (the static scale 1/448 of
+    Sec. 3.3 folded into the exponent: the same real number as exp(S - m) * 448, and the precision
+    in which the gfx950 kernel takes this decision); codes are E4M3(E), saturating at 448;
+  * l (the softmax denominator) sums the unquantized FP32 values as Algorithm 1 prints it (here
+    carried as 448 * l = sum of E, divided out at the end);
   * the per-block product R = P^ V^ is the exact sum of the FP8 products rounded once to
     FP32 (an ideal FP32 buffer), then O = fl32(fl32(alpha*O) + R).
 Parity pins for every function here live in tests/test_oracle_pins.py.
@@ -30,6 +35,7 @@ import numpy as np
 
 LOG2E_F32 = np.float32(1.4426950408889634)
 E4M3_MAX = 448.0
+LOG2_448_F32 = np.float32(np.log2(448.0))
 BQ_SMOOTH = 128   # tokens per Q smoothing block (Algorithm 1's b_q)
 BKV_ACC = 64      # keys per level-1 accumulation block (Algorithm 1's b_kv)
 
@@ -263,7 +269,7 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
     vdec = pro["v_dec"]
     nr = len(rows)
     m = np.full(nr, -np.inf, f32)
-    l = np.zeros(nr, f32)
+    l = np.zeros(nr, f32)                                 # 448 * (running sum of P~)
     O = np.zeros((nr, d), f32)
     last_key = int(rows[-1]) if causal else N - 1
     n_blocks = last_key // bkv + 1
@@ -279,17 +285,16 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
         if causal:
             S = np.where(ks[None, :] > rows[:, None], f32(-np.inf), S)
         m_new = np.maximum(m, S.max(axis=1))
+        m_sub = (m_new - LOG2_448_F32).astype(f32)
         with np.errstate(invalid="ignore"):
-            P = _exp2_f32((S - m_new[:, None]).astype(f32))
+            P448 = _exp2_f32((S - m_sub[:, None]).astype(f32))      # E = 448 * P~
             alpha = _exp2_f32((m - m_new).astype(f32))
-        l = ((alpha * l).astype(f32).astype(f64) + P.astype(f64).sum(axis=1)).astype(f32)
-        P448 = (P * f32(E4M3_MAX)).astype(f32)
+        l = ((alpha * l).astype(f32).astype(f64) + P448.astype(f64).sum(axis=1)).astype(f32)
         Phat = P448.astype(f64) if pro["pv_exact"] else e4m3_decode(e4m3_encode(P448))
         R = (Phat @ vdec[ks]).astype(f32)                 # exact block sum, one rounding
         O = ((alpha[:, None] * O).astype(f32) + R).astype(f32)
         m = m_new
-    out = (O / l[:, None]).astype(f32)
-    out = (out / f32(E4M3_MAX)).astype(f32)
+    out = (O / l[:, None]).astype(f32)                    # O and l both carry the factor 448
     out = (out * pro["v_scale"][None, :]).astype(f32)
     if pro.get("vbar") is not None:                       # smooth V: O = O + mean(V)
         out = (out + pro["vbar"][None, :]).astype(f32)

@@ -12,6 +12,8 @@ import torch
 SAGE_MODE_INT4_FP8, SAGE_MODE_INT8_FP8 = 0, 1
 SAGE_DT_FP16, SAGE_DT_BF16 = 0, 1
 SAGE_FLAG_SMOOTH_V = 1
+SAGE_GROUPS_LANE, SAGE_GROUPS_BLOCK = 0, 1
+_GROUPS = {"lane": 0, "block": 1, 0: 0, 1: 1}
 _MODES = {"int4_fp8": 0, "int8_fp8": 1, 0: 0, 1: 1}
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -30,7 +32,7 @@ class sage_attn_args(ctypes.Structure):
                 ("B", ctypes.c_int), ("H", ctypes.c_int), ("H_kv", ctypes.c_int),
                 ("N", ctypes.c_int), ("d", ctypes.c_int),
                 ("causal", ctypes.c_int), ("sm_scale", ctypes.c_float),
-                ("mode", ctypes.c_int), ("dtype", ctypes.c_int), ("flags", ctypes.c_int),
+                ("mode", ctypes.c_int), ("dtype", ctypes.c_int), ("flags", ctypes.c_int), ("group_map", ctypes.c_int),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("stream", ctypes.c_void_p)]
 
@@ -97,7 +99,7 @@ def _ptr(t):
 
 
 def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
-              smooth_v=False):
+              smooth_v=False, group_map="lane"):
     """Fills a sage_attn_args from torch tensors q [B,H,N,d], k/v [B,H_kv,N,d] (contiguous, on the
     GPU).  `workspace` is a uint8 GPU tensor (or None); `stream` a torch.cuda.Stream (None = the
     current one)."""
@@ -116,6 +118,7 @@ def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", wo
     a.B, a.H, a.H_kv, a.N, a.d = B, H, k.shape[1], N, d
     a.causal, a.sm_scale, a.mode, a.dtype = int(bool(causal)), float(sm_scale), _MODES[mode], _dtype_code(q)
     a.flags = SAGE_FLAG_SMOOTH_V if smooth_v else 0
+    a.group_map = _GROUPS[group_map]
     if workspace is not None:
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     else:
@@ -139,11 +142,11 @@ def _alloc_workspace(args, device):
 
 
 def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
-                     smooth_v=False):
+                     smooth_v=False, group_map="lane"):
     """Whole forward pass.  Returns `out` (allocated if not given)."""
     if out is None:
         out = torch.empty_like(q)
-    a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v)
+    a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v, group_map)
     keep = _alloc_workspace(a, q.device) if workspace is None else workspace
     _check(load_library().sage_attn_fwd_ex(ctypes.byref(a)), "sage_attn_fwd_ex")
     del keep  # torch's caching allocator keeps the block alive for work already queued on this stream
@@ -171,9 +174,9 @@ def sage_attn_release():
 
 
 def sage_attn_quant(q, k, v, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, want=None,
-                    smooth_v=False):
+                    smooth_v=False, group_map="lane"):
     """Preprocessing only; returns (dict of torch tensors in plain layouts, args, workspace)."""
-    a = make_args(q, k, v, None, causal, sm_scale, mode, workspace, smooth_v=smooth_v)
+    a = make_args(q, k, v, None, causal, sm_scale, mode, workspace, smooth_v=smooth_v, group_map=group_map)
     ws = _alloc_workspace(a, q.device) if workspace is None else workspace
     B, H, N, d = q.shape
     Hkv = k.shape[1]

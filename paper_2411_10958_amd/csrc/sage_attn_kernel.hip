@@ -87,7 +87,7 @@ __device__ __forceinline__ typename QkOperand<INT4>::type load_qk_operand(Ptr ba
     const uint2 hi = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(&base[op * (OP6_BYTES / 16) + 64]) + 8 * lane);
     v8i r;
     r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
-    r[4] = (int)hi.x; r[5] = (int)hi.y;     // dwords 6, 7 are not read in the FP6 operand format
+    r[4] = (int)hi.x; r[5] = (int)hi.y; r[6] = 0; r[7] = 0;
     return r;
   } else {
     return base[op * 64 + lane];

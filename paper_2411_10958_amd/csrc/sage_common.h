@@ -27,7 +27,7 @@ struct Dims {
   int B, H, Hkv, N, d;
   int nQb;     // ceil(N / 128) query blocks
   int nKb;     // ceil(N / 64) key blocks
-  int causal, int4, bf16, smooth_v;
+  int causal, int4, bf16, smooth_v, block_groups;
   float kappa; // fl32(sm_scale * log2 e)
 };
 

@@ -174,7 +174,8 @@ __global__ void k_finalize_vscale(const unsigned* __restrict__ v_max, float* __r
 template <bool BF16, bool INT4, int D>
 __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restrict__ Q,
                                                  float* __restrict__ q_mean, float* __restrict__ q_scale,
-                                                 int8_t* __restrict__ q_codes, int N, int nQb) {
+                                                 int8_t* __restrict__ q_codes, int N, int nQb,
+                                                 int block_groups) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;  // RPT rows per thread (8 or 4)
   constexpr int QMAX = INT4 ? 7 : 127;
   __shared__ double s_sum[NRG][D];
@@ -224,7 +225,20 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
   // codes go to LDS in the packed order of this 128-query slab (contiguous in the workspace) and
   // leave as coalesced 16-byte stores
   __shared__ uint4 s_codes[BQ * D / 16];
+  __shared__ float s_bmax[4];
   uint8_t* img = reinterpret_cast<uint8_t*>(s_codes);
+  float block_max = 0.0f;
+  if (block_groups) {       // per-block granularity: one scale for the whole 128-query block
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) block_max = fmaxf(block_max, fabsf(x[i][e]));
+    }
+    block_max = wave_max(block_max);
+    if ((t & 63) == 0) s_bmax[t >> 6] = block_max;
+    __syncthreads();
+    block_max = fmaxf(fmaxf(s_bmax[0], s_bmax[1]), fmaxf(s_bmax[2], s_bmax[3]));
+  }
 #pragma unroll
   for (int p = 0; p < RPT / 2; ++p) {
     float mx = 0.0f;
@@ -232,6 +246,7 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
     for (int e = 0; e < 8; ++e) mx = fmaxf(mx, fmaxf(fabsf(x[2 * p][e]), fabsf(x[2 * p + 1][e])));
 #pragma unroll
     for (int m = NCG / 2; m >= 1; m >>= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+    if (block_groups) mx = block_max;
     const float delta = __fdiv_rn(mx, (float)QMAX);
     if (cg == 0) q_scale[(bh * nQb + qb) * (BQ / QGROUP) + (rg * RPT) / 2 + p] = delta;
 #pragma unroll
@@ -292,7 +307,7 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
                                                  float* __restrict__ k_scale, int8_t* __restrict__ k_codes,
                                                  const float* __restrict__ q_mean,
                                                  float* __restrict__ delta_s, int N, int nKb, int nQb,
-                                                 int G, float kappa) {
+                                                 int G, float kappa, int block_groups) {
   constexpr int CPL = D / 4;                       // channels per lane (32 or 16)
   constexpr int QMAX = INT4 ? 7 : 127;
   // LDS row of staged block means: channel c sits at column c + 16*(c / 32) when D = 128, so the
@@ -355,6 +370,12 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
     for (int e = 0; e < CPL; ++e) x[e] = 0.0f;      // padded keys: codes 0, Delta-S 0
   }
   mx = wave_max(mx);
+  __shared__ float s_bmax[4];
+  if (block_groups) {       // per-block granularity: one scale for the whole 64-key block
+    if (lane == 0) s_bmax[w] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(s_bmax[0], s_bmax[1]), fmaxf(s_bmax[2], s_bmax[3]));
+  }
   const float delta = __fdiv_rn(mx, (float)QMAX);
   if (lane == 0) k_scale[(bhkv * nKb + kb) * (BKV / KGROUP) + w] = delta;
   uint8_t* img = reinterpret_cast<uint8_t*>(s_codes);
@@ -530,10 +551,11 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
                                                         nstat, Dm.N);
   }
-  k_quant_q<BF16, INT4, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.nQb);
+  k_quant_q<BF16, INT4, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.nQb,
+                                                        Dm.block_groups);
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
                                                               P.delta_s, Dm.N, Dm.nKb, Dm.nQb, Dm.H / Dm.Hkv,
-                                                              Dm.kappa);
+                                                              Dm.kappa, Dm.block_groups);
   if (Dm.smooth_v) k_quant_v<BF16, D, true><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.nKb);
   else k_quant_v<BF16, D, false><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.N, Dm.nKb);
   return hipGetLastError();

@@ -244,9 +244,26 @@ def test_online_state_matches_two_pass():
     m_ref = S.max(axis=1)
     shift = st["m"].astype(f64) - m_ref
     l_ref = np.exp2(S - m_ref[:, None]).sum(axis=1)
-    assert np.allclose(st["l"], l_ref, rtol=2e-3)
+    assert np.allclose(st["l"] / 448.0, l_ref, rtol=2e-3)      # the oracle carries 448 * l
     # the constant is the dropped bias b of Sec. 3.1 (times kappa): it varies per row only
     assert shift.shape == (128,)
+
+
+def test_static_p_scale_is_448():
+    # Sec. 3.3: P~ in [0, 1] is quantized with the static scale 1/448, i.e. the FP8 code is taken of
+    # 448 * P~.  With a single key P~ = 1: the carried denominator is 448 and the output is exactly the
+    # dequantized FP8 value of V; with two equal keys it is 896 and the average.
+    q = np.ones((1, 16), f32); k = np.ones((1, 16), f32)
+    v = np.linspace(-3, 3, 16, dtype=f32)[None, :].astype(np.float16).astype(f32)
+    pro = so.quantize_head(q, k, v, mode="int8_fp8")
+    out, st = so.attention_rows(pro, slice(0, 1), False, out_dtype="fp32", return_state=True)
+    assert abs(float(st["l"][0]) - 448.0) < 448.0 * 1e-6
+    dec = so.e4m3_decode(pro["v_codes"]) * pro["v_scale"].astype(f64)[None, :]
+    assert np.allclose(out, dec, rtol=1e-6, atol=0)
+    q2, k2, v2 = np.ones((2, 16), f32), np.ones((2, 16), f32), np.concatenate([v, v])
+    pro2 = so.quantize_head(q2, k2, v2, mode="int8_fp8")
+    _, st2 = so.attention_rows(pro2, slice(0, 2), False, out_dtype="fp32", return_state=True)
+    assert np.allclose(st2["l"], 896.0, rtol=1e-6)
 
 
 # ---- P6: the quantized pipeline approaches FP64 attention as bit-width grows -----------------
