@@ -255,3 +255,58 @@ def test_error_codes_from_the_boundary():
     assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -3          # workspace too small
     a.workspace_bytes = ws.numel(); a.mode = 5
     assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -2
+
+
+def test_side_stream_and_workspace_reuse():
+    """Work is enqueued on the stream the caller names; one workspace serves consecutive calls on
+    that stream (different shapes, the larger first), and the results equal the default-stream ones."""
+    pa = _pa()
+    big, small = _spec(640, 128, "bf16", 2, 2), _spec(250, 128, "bf16", 2, 2, causal=True)
+    _, (qb, kb, vb) = _gpu_inputs(big)
+    _, (qs, ks, vs) = _gpu_inputs(small, seed=1)
+    ref_b = pa.sage_attn_fwd_ex(qb, kb, vb)
+    ref_s = pa.sage_attn_fwd_ex(qs, ks, vs, causal=True)
+    torch.cuda.synchronize()
+    ws = torch.empty(pa.sage_attn_workspace_bytes(pa.make_args(qb, kb, vb)), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        out_b = pa.sage_attn_fwd_ex(qb, kb, vb, workspace=ws, stream=side)
+        out_s = pa.sage_attn_fwd_ex(qs, ks, vs, causal=True, workspace=ws, stream=side)
+        out_b2 = pa.sage_attn_fwd_ex(qb, kb, vb, workspace=ws, stream=side)
+    side.synchronize()
+    assert torch.equal(out_b, ref_b) and torch.equal(out_s, ref_s) and torch.equal(out_b2, ref_b)
+
+
+def test_graph_capture_and_replay():
+    """The whole forward pass (caller-provided workspace, no allocation, no host synchronisation)
+    can be captured into a HIP graph; every replay, with eager work and synchronisations in between
+    and with new input values in the captured buffers, equals the eager result."""
+    pa = _pa()
+    spec = _spec(333, 128, "bf16", 2, 1, causal=True)
+    _, (q, k, v) = _gpu_inputs(spec)
+    _, (q2, k2, v2) = _gpu_inputs(spec, seed=3)
+    eager1 = pa.sage_attn_fwd_ex(q, k, v, causal=True)
+    eager2 = pa.sage_attn_fwd_ex(q2, k2, v2, causal=True)
+    torch.cuda.synchronize()
+    qg, kg, vg = q.clone(), k.clone(), v.clone()
+    out = torch.zeros_like(q)
+    ws = torch.empty(pa.sage_attn_workspace_bytes(pa.make_args(qg, kg, vg)), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # one eager run on the capture stream first
+        pa.sage_attn_fwd_ex(qg, kg, vg, out=out, causal=True, workspace=ws, stream=side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        pa.sage_attn_fwd_ex(qg, kg, vg, out=out, causal=True, workspace=ws, stream=torch.cuda.current_stream())
+    for rep, (src, want) in enumerate([((q, k, v), eager1), ((q2, k2, v2), eager2), ((q, k, v), eager1)]):
+        for dst, s in zip((qg, kg, vg), src):
+            dst.copy_(s)
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {rep}"
+        _ = pa.sage_attn_fwd_ex(q2, k2, v2, causal=True)       # eager work between replays
+        torch.cuda.synchronize()
