@@ -115,7 +115,10 @@ void sage_attn_release(void);
      k_mean  [B,H_kv,d] f32       mean(K) over tokens (Eq. 2)
      q_mean  [B,H,ceil(N/128),d] f32   block means of Q (int4 mode only, else untouched)
      delta_s [B,H,ceil(N/128),N] f32   kappa * <q_mean_i, gamma(K)_t>, kappa = sm_scale*log2(e)
-                                       (int4 mode only, else untouched)
+                                       (int4 mode only, else untouched).  With causal = 1 the
+                                       entries no query can use are skipped in groups: row i is
+                                       defined for keys t < 4096 * (floor(i/32) + 1), the rest of the
+                                       row is left as it was
      v_mean  [B,H_kv,d] f32       mean(V) over tokens (SAGE_FLAG_SMOOTH_V only, else untouched); with
                                   that flag v_codes and v_scale describe V - v_mean */
 typedef struct sage_quant_out {

@@ -307,7 +307,7 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
                                                  float* __restrict__ k_scale, int8_t* __restrict__ k_codes,
                                                  const float* __restrict__ q_mean,
                                                  float* __restrict__ delta_s, int N, int nKb, int nQb,
-                                                 int G, float kappa, int block_groups) {
+                                                 int G, float kappa, int block_groups, int causal) {
   constexpr int CPL = D / 4;                       // channels per lane (32 or 16)
   constexpr int QMAX = INT4 ? 7 : 127;
   // LDS row of staged block means: channel c sits at column c + 16*(c / 32) when D = 128, so the
@@ -327,6 +327,10 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
   constexpr int QPT = DS_QROWS * (D / 4) / 256;    // float4 pieces per thread per pass
   const int npass_h = (nQb + DS_QROWS - 1) / DS_QROWS;
   const int npass = INT4 ? G * npass_h : 0;
+  // under a causal mask query block i sees this key block only if 128 i + 127 >= its first key:
+  // the passes of a head start with the one that holds block (first key) / 128
+  const int p_first = causal ? (kb * BKV / BQ) / DS_QROWS : 0;
+  auto next_pass = [&](int p) { return (p + 1) % npass_h >= p_first ? p + 1 : p + 1 + p_first; };
   float4 qpre[QPT];
   auto load_q = [&](int p) {
     const size_t bh = bhkv * G + p / npass_h;
@@ -347,7 +351,7 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
       s_q[rr][col + 2] = qpre[k].z; s_q[rr][col + 3] = qpre[k].w;
     }
   };
-  if constexpr (INT4) load_q(0);
+  if constexpr (INT4) load_q(p_first);
 
   float x[CPL];
   float mx = 0.0f;
@@ -416,11 +420,11 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
     for (int cs = 0; cs < CPL; ++cs) bk[cs] = (double)x[cs];
     const double kap = (double)kappa;
     const int qcol = c0 + (D == 128 ? 16 * k4 : 0);
-    for (int p = 0; p < npass; ++p) {
-      if (p > 0) __syncthreads();                  // everyone is done with the previous pass's rows
+    for (int p = p_first; p < npass; p = next_pass(p)) {
+      if (p > p_first) __syncthreads();            // everyone is done with the previous pass's rows
       store_q();
       __syncthreads();
-      if (p + 1 < npass) load_q(p + 1);            // next pass, in flight under the MFMAs
+      if (next_pass(p) < npass) load_q(next_pass(p));   // next pass, in flight under the MFMAs
       v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
       for (int cs = 0; cs < CPL; ++cs) {
@@ -555,7 +559,7 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
                                                         Dm.block_groups);
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
                                                               P.delta_s, Dm.N, Dm.nKb, Dm.nQb, Dm.H / Dm.Hkv,
-                                                              Dm.kappa, Dm.block_groups);
+                                                              Dm.kappa, Dm.block_groups, Dm.causal);
   if (Dm.smooth_v) k_quant_v<BF16, D, true><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.nKb);
   else k_quant_v<BF16, D, false><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.N, Dm.nKb);
   return hipGetLastError();

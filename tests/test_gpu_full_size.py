@@ -70,8 +70,12 @@ def test_full_size_sampled_parity(name, mode):
             assert np.array_equal(quant["q_mean"][b, h].cpu().numpy(), pro["qbar"])
             if "delta_s" in quant:
                 got_ds = quant["delta_s"][b, h][blocks].cpu().numpy().astype(np.float64)
-                ref_ds = pro["delta_s"][blocks]
-                assert np.all(np.abs(got_ds - ref_ds) <= np.spacing(np.abs(ref_ds)).astype(np.float64))
+                ref_ds = pro["delta_s"][blocks].astype(np.float64)
+                ok = np.abs(got_ds - ref_ds) <= np.spacing(np.abs(ref_ds))
+                if spec.causal:     # rows are computed up to the key a query block's group can see
+                    seen = np.arange(spec.N)[None, :] < 4096 * (np.asarray(blocks)[:, None] // 32 + 1)
+                    ok |= ~seen
+                assert np.all(ok)
         # int32 score accumulators of a few (query tile, key block) pairs through the MFMA path
         nkb = (spec.N + 63) // 64
         for qt in (blocks[0], blocks[-1]):
