@@ -191,7 +191,8 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
                   smooth_v_on=False):
     """Everything Algorithm 1 computes before the inner loop, for one (batch, head).
 
-    Q, K, V: [N, d] float32 holding exactly representable 16-bit values.
+    Q: [N, d], K and V: [N_kv, d] float32 holding exactly representable 16-bit values (N_kv = N in
+    Algorithm 1; other key lengths - cross attention, chunked prefill - change nothing in it).
     mode "int4_fp8": Q and K smoothed, INT4 range [-7, 7] (SageAttn2-4b);
     mode "int8_fp8": only K smoothed, INT8 range [-127, 127] (SageAttn2-8b, Table
     "Two kernel implementations").  An integer `mode` is used as qmax directly, smooth_*_on
@@ -204,6 +205,7 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
     output (rows of the softmax sum to 1); the mean is kept in FP32.
     """
     N, d = Q.shape
+    Nk = K.shape[0]
     if sm_scale is None:
         sm_scale = 1.0 / np.sqrt(d)
     qmax = {"int4_fp8": 7, "int8_fp8": 127}[mode] if isinstance(mode, str) else int(mode)
@@ -219,11 +221,11 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
         if ds_blocks is None:
             D = delta_s(qbar, gK, kappa)
         else:
-            D = np.zeros((qbar.shape[0], N), f32)
+            D = np.zeros((qbar.shape[0], Nk), f32)
             D[list(ds_blocks)] = delta_s(qbar[list(ds_blocks)], gK, kappa)
     else:
         qbar, gQ, D = None, np.asarray(Q, f32), None
-    gq, gk = group_map(gmap, N, "q"), group_map(gmap, N, "k")
+    gq, gk = group_map(gmap, N, "q"), group_map(gmap, Nk, "k")
     dq, qc = quantize_groups(gQ, gq, qmax)
     dk, kc = quantize_groups(gK, gk, qmax)
     if smooth_v_on:
@@ -236,7 +238,7 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
     else:
         dv, vc = quantize_v(V)
         vdec = e4m3_decode(vc)                            # [N, d] float64, exact
-    return dict(N=N, d=d, kappa=kappa, qmax=qmax, kbar=kbar, qbar=qbar, delta_s=D,
+    return dict(N=N, Nk=Nk, d=d, kappa=kappa, qmax=qmax, kbar=kbar, qbar=qbar, delta_s=D,
                 q_codes=qc, q_scale=dq, q_groups=gq, k_codes=kc, k_scale=dk, k_groups=gk,
                 v_codes=vc, v_scale=dv, v_dec=vdec, pv_exact=pv_exact, bq=bq, vbar=vbar)
 
@@ -258,9 +260,12 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
     """Inner loop + epilogue of Algorithm 1 for the query rows `rows` (a slice or index
     array inside ONE smoothing block) of a head prepared by `quantize_head`.
 
-    Returns the [len(rows), d] output rounded to the 16-bit type (as float32).
+    Returns the [len(rows), d] output rounded to the 16-bit type (as float32).  With N_kv != N
+    a causal mask is aligned to the last query and key: query r sees keys t <= r + (N_kv - N).
     """
-    N, d, kappa = pro["N"], pro["d"], pro["kappa"]
+    N, Nk, d, kappa = pro["N"], pro["Nk"], pro["d"], pro["kappa"]
+    coff = Nk - N
+    assert not causal or coff >= 0, "a causal mask needs N_kv >= N"
     rows = np.arange(N)[rows]
     blk = int(rows[0]) // pro["bq"]
     assert int(rows[-1]) // pro["bq"] == blk, "rows must lie in one smoothing block"
@@ -271,10 +276,10 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
     m = np.full(nr, -np.inf, f32)
     l = np.zeros(nr, f32)                                 # 448 * (running sum of P~)
     O = np.zeros((nr, d), f32)
-    last_key = int(rows[-1]) if causal else N - 1
+    last_key = int(rows[-1]) + coff if causal else Nk - 1
     n_blocks = last_key // bkv + 1
     for j in range(n_blocks):
-        ks = np.arange(j * bkv, min((j + 1) * bkv, N))
+        ks = np.arange(j * bkv, min((j + 1) * bkv, Nk))
         acc = int_scores(qc, pro["k_codes"][ks])
         dk = pro["k_scale"][pro["k_groups"][ks]]
         c = ((dq[:, None] * dk[None, :]).astype(f32) * kappa).astype(f32)
@@ -283,7 +288,7 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
             s = s + pro["delta_s"][blk, ks].astype(f64)[None, :]
         S = s.astype(f32)                                 # one rounding of acc*c + D
         if causal:
-            S = np.where(ks[None, :] > rows[:, None], f32(-np.inf), S)
+            S = np.where(ks[None, :] > rows[:, None] + coff, f32(-np.inf), S)
         m_new = np.maximum(m, S.max(axis=1))
         m_sub = (m_new - LOG2_448_F32).astype(f32)
         with np.errstate(invalid="ignore"):
@@ -347,15 +352,17 @@ def sage_attention(q, k, v, causal=False, mode="int4_fp8", sm_scale=None, gmap="
 # --------------------------------------------------------------------------- definition
 def ref_attn_fp64(Q, K, V, causal=False, sm_scale=None, rows=None):
     """softmax(Q K^T * sm_scale) V in float64 (Sec. 2.1, first formula), one head;
-    `rows` restricts the queries."""
+    `rows` restricts the queries.  K, V may have another length than Q; the causal mask is then
+    aligned to the last query and key."""
     Q, K, V = (np.asarray(x, f64) for x in (Q, K, V))
     N, d = Q.shape
+    Nk = K.shape[0]
     if sm_scale is None:
         sm_scale = 1.0 / np.sqrt(d)
     ridx = np.arange(N) if rows is None else np.arange(N)[rows]
     S = (Q[ridx] @ K.T) * sm_scale
     if causal:
-        S = np.where(np.arange(N)[None, :] > ridx[:, None], -np.inf, S)
+        S = np.where(np.arange(Nk)[None, :] > ridx[:, None] + (Nk - N), -np.inf, S)
     S = S - S.max(axis=1, keepdims=True)
     P = np.exp(S)
     return (P / P.sum(axis=1, keepdims=True)) @ V

@@ -346,6 +346,34 @@ def test_smooth_v_quantizes_the_centred_values_and_helps_with_channel_bias(facts
     assert wl.cos_sim(smooth, ref) >= wl.cos_sim(plain, ref)
 
 
+# ---- key length different from query length ------------------------------------------------------
+@pytest.mark.parametrize("causal", [False, True])
+def test_other_key_length(causal):
+    # the definition against a library routine with an explicit mask aligned to the last query and key,
+    # and the oracle's path with its quantizers at their high-precision limit against the definition
+    rng = np.random.default_rng(7)
+    Nq, Nk, d = 70, 203, 32
+    q = rng.standard_normal((Nq, d)).astype(np.float16).astype(f32)
+    k = (rng.standard_normal((Nk, d)) + 1.5).astype(np.float16).astype(f32)
+    v = rng.standard_normal((Nk, d)).astype(np.float16).astype(f32)
+    ref = so.ref_attn_fp64(q, k, v, causal=causal)
+    mask = None
+    if causal:
+        mask = torch.from_numpy(np.arange(Nk)[None, :] <= np.arange(Nq)[:, None] + (Nk - Nq))
+    lib = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q).double()[None], torch.from_numpy(k).double()[None], torch.from_numpy(v).double()[None],
+        attn_mask=mask).numpy()[0]
+    assert np.abs(ref - lib).max() < 1e-12
+    out, pro = so.sage_attention_head(q, k, v, causal=causal, mode=32767, out_dtype="fp32", smooth_q_on=True,
+                                      pv_exact=True)
+    assert pro["delta_s"].shape == (1, Nk) and pro["k_codes"].shape == (Nk, d) and pro["q_codes"].shape == (Nq, d)
+    assert np.abs(out - ref).max() < 2e-3 * np.abs(ref).max()
+    assert wl.cos_sim(out, ref) > 1 - 1e-6
+    if causal:      # the last query sees every key, the first one Nk - Nq + 1 of them
+        first = so.ref_attn_fp64(q[:1], k[: Nk - Nq + 1], v[: Nk - Nq + 1])
+        assert np.abs(ref[0] - first[0]).max() < 1e-12
+
+
 # ---- misc structure -------------------------------------------------------------------------
 def test_int8_mode_does_not_smooth_q():
     q, k, v = _head(N=128, d=16)
