@@ -11,8 +11,10 @@
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library never frees or
  *     keeps them.  q and out are contiguous [B, H, N, d]; k and v are contiguous
- *     [B, H_kv, N, d]; elements are 16-bit (fp16 or bf16, see dtype).  Query head h reads KV
- *     head h / (H / H_kv).  N_q = N_kv = N (prefill).
+ *     [B, H_kv, N_kv, d]; elements are 16-bit (fp16 or bf16, see dtype).  Query head h reads KV
+ *     head h / (H / H_kv).  N_kv = N unless sage_attn_args.N_kv says otherwise; a causal mask is
+ *     aligned to the last query and key (key t visible to query r iff t <= r + N_kv - N) and
+ *     needs N_kv >= N.
  *   - d is 64 or 128; mode and dtype take the enum values below; H must be a multiple of H_kv.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream)
  *     and the call returns without synchronising.  Kernels of one call are ordered on that
@@ -36,7 +38,7 @@ extern "C" {
 enum {
   SAGE_OK = 0,
   SAGE_ERR_INVALID_ARG = -1,  /* null pointer, non-positive size, H % H_kv != 0 */
-  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode, dtype, flag or group map */
+  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode, dtype, flag or group map, causal with N_kv < N */
   SAGE_ERR_WORKSPACE = -3,    /* workspace missing or smaller than sage_attn_workspace_bytes() */
   SAGE_ERR_HIP = -4           /* a HIP call or launch failed (the HIP error is cleared) */
 };
@@ -67,16 +69,17 @@ enum { SAGE_GROUPS_LANE = 0, SAGE_GROUPS_BLOCK = 1 };
 
 typedef struct sage_attn_args {
   const void* q;          /* device, [B, H, N, d] */
-  const void* k;          /* device, [B, H_kv, N, d] */
-  const void* v;          /* device, [B, H_kv, N, d] */
+  const void* k;          /* device, [B, H_kv, N_kv, d] */
+  const void* v;          /* device, [B, H_kv, N_kv, d] */
   void* out;              /* device, [B, H, N, d], written */
   int B, H, H_kv, N, d;
-  int causal;             /* 0: every key visible; 1: key t visible to query r iff t <= r */
+  int causal;             /* 0: every key visible; 1: key t visible to query r iff t <= r + N_kv - N */
   float sm_scale;         /* <= 0 means 1/sqrt(d) */
   int mode;               /* SAGE_MODE_* */
   int dtype;              /* SAGE_DT_* : type of q, k, v and out */
   int flags;              /* SAGE_FLAG_* or-ed together; 0 = the paper's default configuration */
   int group_map;          /* SAGE_GROUPS_*; 0 = the default */
+  int N_kv;               /* keys / values per head (cross attention, chunked prefill); 0 = N */
   void* workspace;        /* device scratch of >= sage_attn_workspace_bytes(); 256-byte aligned */
   size_t workspace_bytes;
   void* stream;           /* hipStream_t, NULL = default stream */
@@ -107,17 +110,17 @@ void sage_attn_release(void);
 /* Output of the preprocessing stage in plain ("logical") layouts, for checking it bit by bit.
    All pointers are device buffers the caller allocates; a NULL member is skipped.
      q_codes [B,H,N,d] int8       codes of gamma(Q) (int4 mode) or Q (int8 mode), Sec. 3.2
-     k_codes [B,H_kv,N,d] int8    codes of gamma(K)
-     v_codes [B,H_kv,N,d] uint8   E4M3 codes of V / delta_V, Sec. 3.3
+     k_codes [B,H_kv,N_kv,d] int8    codes of gamma(K)
+     v_codes [B,H_kv,N_kv,d] uint8   E4M3 codes of V / delta_V, Sec. 3.3
      q_scale [B,H,ceil(N/2)] f32  delta_Q per query group
-     k_scale [B,H_kv,ceil(N/16)] f32
+     k_scale [B,H_kv,ceil(N_kv/16)] f32
      v_scale [B,H_kv,d] f32       delta_V per channel
      k_mean  [B,H_kv,d] f32       mean(K) over tokens (Eq. 2)
      q_mean  [B,H,ceil(N/128),d] f32   block means of Q (int4 mode only, else untouched)
-     delta_s [B,H,ceil(N/128),N] f32   kappa * <q_mean_i, gamma(K)_t>, kappa = sm_scale*log2(e)
+     delta_s [B,H,ceil(N/128),N_kv] f32   kappa * <q_mean_i, gamma(K)_t>, kappa = sm_scale*log2(e)
                                        (int4 mode only, else untouched).  With causal = 1 the
                                        entries no query can use are skipped in groups: row i is
-                                       defined for keys t < 4096 * (floor(i/32) + 1), the rest of the
+                                       defined for keys t < 4096 * (floor(i/32) + 1) + N_kv - N, the rest of the
                                        row is left as it was
      v_mean  [B,H_kv,d] f32       mean(V) over tokens (SAGE_FLAG_SMOOTH_V only, else untouched); with
                                   that flag v_codes and v_scale describe V - v_mean */

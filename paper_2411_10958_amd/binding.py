@@ -32,7 +32,7 @@ class sage_attn_args(ctypes.Structure):
                 ("B", ctypes.c_int), ("H", ctypes.c_int), ("H_kv", ctypes.c_int),
                 ("N", ctypes.c_int), ("d", ctypes.c_int),
                 ("causal", ctypes.c_int), ("sm_scale", ctypes.c_float),
-                ("mode", ctypes.c_int), ("dtype", ctypes.c_int), ("flags", ctypes.c_int), ("group_map", ctypes.c_int),
+                ("mode", ctypes.c_int), ("dtype", ctypes.c_int), ("flags", ctypes.c_int), ("group_map", ctypes.c_int), ("N_kv", ctypes.c_int),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("stream", ctypes.c_void_p)]
 
@@ -109,7 +109,7 @@ def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", wo
     if k.shape != v.shape or k.dtype != q.dtype or v.dtype != q.dtype:
         raise ValueError("k and v must share shape; q, k, v must share dtype")
     B, H, N, d = q.shape
-    if k.shape[0] != B or k.shape[2] != N or k.shape[3] != d:
+    if k.shape[0] != B or k.shape[3] != d:
         raise ValueError("k/v shape does not match q")
     if out is not None and (out.shape != q.shape or out.dtype != q.dtype or not out.is_contiguous()):
         raise ValueError("out must look like q")
@@ -119,6 +119,7 @@ def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", wo
     a.causal, a.sm_scale, a.mode, a.dtype = int(bool(causal)), float(sm_scale), _MODES[mode], _dtype_code(q)
     a.flags = SAGE_FLAG_SMOOTH_V if smooth_v else 0
     a.group_map = _GROUPS[group_map]
+    a.N_kv = k.shape[2]
     if workspace is not None:
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     else:
@@ -148,8 +149,10 @@ def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_f
         out = torch.empty_like(q)
     a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v, group_map)
     keep = _alloc_workspace(a, q.device) if workspace is None else workspace
+    if workspace is None and stream is not None:
+        keep.record_stream(stream)   # allocated on the current stream, used on another one
     _check(load_library().sage_attn_fwd_ex(ctypes.byref(a)), "sage_attn_fwd_ex")
-    del keep  # torch's caching allocator keeps the block alive for work already queued on this stream
+    del keep  # torch's caching allocator keeps the block alive for work already queued on its streams
     return out
 
 
@@ -179,22 +182,22 @@ def sage_attn_quant(q, k, v, causal=False, sm_scale=0.0, mode="int4_fp8", worksp
     a = make_args(q, k, v, None, causal, sm_scale, mode, workspace, smooth_v=smooth_v, group_map=group_map)
     ws = _alloc_workspace(a, q.device) if workspace is None else workspace
     B, H, N, d = q.shape
-    Hkv = k.shape[1]
+    Hkv, Nk = k.shape[1], k.shape[2]
     dev = q.device
     int4 = _MODES[mode] == 0
     nqb = (N + 127) // 128
     bufs = dict(
         q_codes=torch.empty((B, H, N, d), dtype=torch.int8, device=dev),
-        k_codes=torch.empty((B, Hkv, N, d), dtype=torch.int8, device=dev),
-        v_codes=torch.empty((B, Hkv, N, d), dtype=torch.uint8, device=dev),
+        k_codes=torch.empty((B, Hkv, Nk, d), dtype=torch.int8, device=dev),
+        v_codes=torch.empty((B, Hkv, Nk, d), dtype=torch.uint8, device=dev),
         q_scale=torch.empty((B, H, (N + 1) // 2), dtype=torch.float32, device=dev),
-        k_scale=torch.empty((B, Hkv, (N + 15) // 16), dtype=torch.float32, device=dev),
+        k_scale=torch.empty((B, Hkv, (Nk + 15) // 16), dtype=torch.float32, device=dev),
         v_scale=torch.empty((B, Hkv, d), dtype=torch.float32, device=dev),
         k_mean=torch.empty((B, Hkv, d), dtype=torch.float32, device=dev),
     )
     if int4:
         bufs["q_mean"] = torch.empty((B, H, nqb, d), dtype=torch.float32, device=dev)
-        bufs["delta_s"] = torch.empty((B, H, nqb, N), dtype=torch.float32, device=dev)
+        bufs["delta_s"] = torch.empty((B, H, nqb, Nk), dtype=torch.float32, device=dev)
     if smooth_v:
         bufs["v_mean"] = torch.empty((B, Hkv, d), dtype=torch.float32, device=dev)
     if want is not None:

@@ -12,7 +12,9 @@ using namespace sage;
 int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if (!a) return SAGE_ERR_INVALID_ARG;
   if (a->B <= 0 || a->H <= 0 || a->H_kv <= 0 || a->N <= 0 || a->d <= 0) return SAGE_ERR_INVALID_ARG;
-  if (a->H % a->H_kv != 0) return SAGE_ERR_INVALID_ARG;
+  if (a->H % a->H_kv != 0 || a->N_kv < 0) return SAGE_ERR_INVALID_ARG;
+  const int Nk = a->N_kv > 0 ? a->N_kv : a->N;
+  if (a->causal && Nk < a->N) return SAGE_ERR_UNSUPPORTED;
   if (a->d != 64 && a->d != 128) return SAGE_ERR_UNSUPPORTED;
   if (a->mode != SAGE_MODE_INT4_FP8 && a->mode != SAGE_MODE_INT8_FP8) return SAGE_ERR_UNSUPPORTED;
   if (a->dtype != SAGE_DT_FP16 && a->dtype != SAGE_DT_BF16) return SAGE_ERR_UNSUPPORTED;
@@ -21,9 +23,10 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if (need_io && (!a->q || !a->k || !a->v || !a->out)) return SAGE_ERR_INVALID_ARG;
   // grid limits of the launches below (y dimension <= 65535, tile count fits an int)
   if ((long long)a->B * a->H > 65535) return SAGE_ERR_UNSUPPORTED;
-  const long long nQb = (a->N + BQ - 1) / BQ, nKb = (a->N + BKV - 1) / BKV;
+  const long long nQb = (a->N + BQ - 1) / BQ, nKb = (Nk + BKV - 1) / BKV;
   if ((long long)a->B * a->H * nQb > (1LL << 30)) return SAGE_ERR_UNSUPPORTED;
   D->B = a->B; D->H = a->H; D->Hkv = a->H_kv; D->N = a->N; D->d = a->d;
+  D->Nk = Nk; D->coff = Nk - a->N;
   D->nQb = (int)nQb; D->nKb = (int)nKb;
   D->causal = a->causal != 0;
   D->int4 = a->mode == SAGE_MODE_INT4_FP8;
@@ -91,7 +94,7 @@ int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B,
   sage_attn_args a;
   a.q = q; a.k = k; a.v = v; a.out = out;
   a.B = B; a.H = H; a.H_kv = H; a.N = N; a.d = d;
-  a.causal = causal; a.sm_scale = sm_scale; a.mode = mode; a.dtype = SAGE_DT_BF16; a.flags = 0; a.group_map = SAGE_GROUPS_LANE;
+  a.causal = causal; a.sm_scale = sm_scale; a.mode = mode; a.dtype = SAGE_DT_BF16; a.flags = 0; a.group_map = SAGE_GROUPS_LANE; a.N_kv = 0;
   a.workspace = nullptr; a.workspace_bytes = 0; a.stream = nullptr;
   const size_t need = sage_attn_workspace_bytes(&a);
   if (need == 0) {

@@ -25,7 +25,7 @@ struct AttnParams {
   const float* v_mean;    // null, or the token mean of V to add back (smooth-V option)
   const float* delta_s;
   void* out;
-  int H, Hkv, N, nQb, nKb, total_tiles;
+  int H, Hkv, N, Nk, coff, nQb, nKb, total_tiles;   // N queries, Nk keys; causal: key t <= query + coff
   float kappa;
 };
 
@@ -105,13 +105,14 @@ template <int D> struct RowState {
 // keys (one "group": registers 4G..4G+3 of key tile KT) so that MFMAs can be issued between them.
 //
 // dequant_group: the raw scores of the group are dequantized (+ Delta-S) into sc, in base 2
-// (Algorithm 1, score line); MASKED adds the causal diagonal and the keys beyond N.  In the INT8
+// (Algorithm 1, score line); MASKED adds the causal diagonal (keys past last_visible) and the
+// padded keys (n_keys and beyond).  In the INT8
 // mode there is no Delta-S and one positive factor c per key tile, so sc keeps the accumulators
 // as floats: the maximum commutes with the factor and the product is fused into the exponent's
 // argument (exp_group), one instruction less per score.
 template <bool INT4, bool CAUSAL, bool MASKED, int KT, int G>
 __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2], const v4f (&dsr)[2][4],
-                                              float c, int half, int key0, int query, int N) {
+                                              float c, int half, int key0, int last_visible, int n_keys) {
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     float x;
@@ -119,7 +120,7 @@ __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2
     else x = (float)raw[KT][4 * G + r];
     if constexpr (MASKED) {
       const int key = key0 + 32 * KT + 16 * half + 4 * G + r;
-      if (key >= N || (CAUSAL && key > query)) x = -INFINITY;
+      if (key >= n_keys || (CAUSAL && key > last_visible)) x = -INFINITY;
     }
     sc[KT][4 * G + r] = __float_as_int(x);
   }
@@ -266,7 +267,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   const float* gs = p.k_scale + bhkv * (size_t)p.nKb * 4;
 
   int nblk = p.nKb;
-  if (CAUSAL) nblk = min(nblk, (qb * BQ + BQ - 1) / BKV + 1);
+  if (CAUSAL) nblk = min(nblk, (qb * BQ + BQ - 1 + p.coff) / BKV + 1);
 
   // Block copies: every wavefront moves its quarter of the K^ and V^ chunks (the copy is the
   // identity on chunk indices), wavefront 0 the block's Delta-S row, wavefront 1 the 4 scales.
@@ -322,11 +323,11 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   // The wavefront walks all nblk blocks of the workgroup (copies and barriers are shared):
   // blocks [0, n_act) hold keys visible to some of its queries, of which [0, n_plain) need no
   // mask; past n_act (causal only) it just helps with the copies.
-  int n_plain = min(nblk, p.N / BKV);                          // blocks without padded keys
+  int n_plain = min(nblk, p.Nk / BKV);                         // blocks without padded keys
   int n_act = nblk;                                            // blocks with any visible key
   if (CAUSAL) {
-    n_plain = min(n_plain, (q_lo + 1) / BKV);                  // key0 + 63 <= q_lo
-    n_act = min(nblk, (q_lo + WQ - 1) / BKV + 1);              // key0 <= q_lo + 31
+    n_plain = min(n_plain, (q_lo + p.coff + 1) / BKV);         // key0 + 63 <= q_lo + coff
+    n_act = min(nblk, (q_lo + p.coff + WQ - 1) / BKV + 1);     // key0 <= q_lo + 31 + coff
   }
   n_plain = __builtin_amdgcn_readfirstlane(n_plain);
   n_act = __builtin_amdgcn_readfirstlane(n_act);
@@ -394,7 +395,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
 
 #define SAGE_DEQ(MASKED_, GI_, KEY0_)                                                                \
   dequant_group<INT4, CAUSAL, MASKED_, (GI_) / 4, (GI_) % 4>(raw, sc, dsr, (GI_) / 4 == 0 ? c0 : c1, half, \
-                                                             KEY0_, query, p.N)
+                                                             KEY0_, query + p.coff, p.Nk)
 #define SAGE_DEQ_ALL(MASKED_, KEY0_)                                                                 \
   do {                                                                                               \
     SAGE_DEQ(MASKED_, 0, KEY0_); SAGE_DEQ(MASKED_, 1, KEY0_); SAGE_DEQ(MASKED_, 2, KEY0_);           \
@@ -552,7 +553,7 @@ static hipError_t launch_attention_t(const Dims& Dm, const Ptrs& P, hipStream_t 
   p.q_scale = P.q_scale; p.k_scale = P.k_scale; p.v_scale = P.v_scale; p.delta_s = P.delta_s;
   p.v_mean = Dm.smooth_v ? P.v_mean : nullptr;
   p.out = P.out;
-  p.H = Dm.H; p.Hkv = Dm.Hkv; p.N = Dm.N; p.nQb = Dm.nQb; p.nKb = Dm.nKb;
+  p.H = Dm.H; p.Hkv = Dm.Hkv; p.N = Dm.N; p.Nk = Dm.Nk; p.coff = Dm.coff; p.nQb = Dm.nQb; p.nKb = Dm.nKb;
   p.total_tiles = Dm.B * Dm.H * Dm.nQb;
   p.kappa = Dm.kappa;
   const int grid = 8 * ((p.total_tiles + 7) / 8);

@@ -25,8 +25,10 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 struct Dims {
   int B, H, Hkv, N, d;
+  int Nk;      // keys / values per head (N unless the caller says otherwise)
+  int coff;    // Nk - N: the causal mask lets query r see keys t <= r + coff
   int nQb;     // ceil(N / 128) query blocks
-  int nKb;     // ceil(N / 64) key blocks
+  int nKb;     // ceil(Nk / 64) key blocks
   int causal, int4, bf16, smooth_v, block_groups;
   float kappa; // fl32(sm_scale * log2 e)
 };

@@ -307,7 +307,8 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
                                                  float* __restrict__ k_scale, int8_t* __restrict__ k_codes,
                                                  const float* __restrict__ q_mean,
                                                  float* __restrict__ delta_s, int N, int nKb, int nQb,
-                                                 int G, float kappa, int block_groups, int causal) {
+                                                 int G, float kappa, int block_groups, int causal,
+                                                 int coff) {
   constexpr int CPL = D / 4;                       // channels per lane (32 or 16)
   constexpr int QMAX = INT4 ? 7 : 127;
   // LDS row of staged block means: channel c sits at column c + 16*(c / 32) when D = 128, so the
@@ -327,9 +328,10 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
   constexpr int QPT = DS_QROWS * (D / 4) / 256;    // float4 pieces per thread per pass
   const int npass_h = (nQb + DS_QROWS - 1) / DS_QROWS;
   const int npass = INT4 ? G * npass_h : 0;
-  // under a causal mask query block i sees this key block only if 128 i + 127 >= its first key:
-  // the passes of a head start with the one that holds block (first key) / 128
-  const int p_first = causal ? (kb * BKV / BQ) / DS_QROWS : 0;
+  // under a causal mask (query r sees keys t <= r + coff) query block i sees this key block only
+  // if 128 i + 127 + coff >= its first key: the passes of a head start with the one that holds
+  // block (first key - coff) / 128
+  const int p_first = causal ? (max(kb * BKV - coff, 0) / BQ) / DS_QROWS : 0;
   auto next_pass = [&](int p) { return (p + 1) % npass_h >= p_first ? p + 1 : p + 1 + p_first; };
   float4 qpre[QPT];
   auto load_q = [&](int p) {
@@ -541,27 +543,27 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
   const unsigned short* k = (const unsigned short*)P.k;
   const unsigned short* v = (const unsigned short*)P.v;
   const int nstat = BHkv * Dm.d;
-  const dim3 gstat((Dm.N + STAT_ROWS - 1) / STAT_ROWS, BHkv);
+  const dim3 gstat((Dm.Nk + STAT_ROWS - 1) / STAT_ROWS, BHkv);
   const float* v_mean = Dm.smooth_v ? P.v_mean : nullptr;
   k_zero_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, Dm.smooth_v ? P.v_sum : nullptr, P.v_max, nstat);
   if (Dm.smooth_v) {
-    k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.N);
+    k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.Nk);
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
-                                                        nstat, Dm.N);
-    k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.N);
+                                                        nstat, Dm.Nk);
+    k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.Nk);
     k_finalize_vscale<<<(nstat + 255) / 256, 256, 0, s>>>(P.v_max, P.v_scale, nstat);
   } else {
-    k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.N);
+    k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.Nk);
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
-                                                        nstat, Dm.N);
+                                                        nstat, Dm.Nk);
   }
   k_quant_q<BF16, INT4, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.nQb,
                                                         Dm.block_groups);
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
-                                                              P.delta_s, Dm.N, Dm.nKb, Dm.nQb, Dm.H / Dm.Hkv,
-                                                              Dm.kappa, Dm.block_groups, Dm.causal);
-  if (Dm.smooth_v) k_quant_v<BF16, D, true><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.nKb);
-  else k_quant_v<BF16, D, false><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.N, Dm.nKb);
+                                                              P.delta_s, Dm.Nk, Dm.nKb, Dm.nQb, Dm.H / Dm.Hkv,
+                                                              Dm.kappa, Dm.block_groups, Dm.causal, Dm.coff);
+  if (Dm.smooth_v) k_quant_v<BF16, D, true><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.Nk, Dm.nKb);
+  else k_quant_v<BF16, D, false><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.Nk, Dm.nKb);
   return hipGetLastError();
 }
 
@@ -583,11 +585,11 @@ hipError_t launch_unpack(const Dims& D, const Ptrs& P, const void* quant_out, hi
       qo.q_codes, qo.k_codes, qo.v_codes, qo.q_scale, qo.k_scale, qo.v_scale, qo.k_mean, qo.q_mean, qo.delta_s,
       qo.v_mean};
   const int BH = D.B * D.H, BHkv = D.B * D.Hkv;
-  const unsigned gx = (unsigned)(((size_t)D.N * D.d + 255) / 256);
+  const unsigned gx = (unsigned)(((size_t)D.N * D.d + 255) / 256), gxk = (unsigned)(((size_t)D.Nk * D.d + 255) / 256);
   if (o.qc) k_unpack_codes<<<dim3(gx, BH), 256, 0, s>>>(P.q_codes, o.qc, D.N, D.d, D.nQb * q_slab_bytes(D.d, D.int4), 0, D.int4);
-  if (o.kc) k_unpack_codes<<<dim3(gx, BHkv), 256, 0, s>>>(P.k_codes, o.kc, D.N, D.d, D.nKb * k_block_bytes(D.d, D.int4), 1, D.int4);
-  if (o.vc) k_unpack_codes<<<dim3(gx, BHkv), 256, 0, s>>>((const int8_t*)P.v_codes, (int8_t*)o.vc, D.N, D.d, (size_t)D.nKb * BKV * D.d, 2, 0);
-  const int nqg = (D.N + QGROUP - 1) / QGROUP, nkg = (D.N + KGROUP - 1) / KGROUP;
+  if (o.kc) k_unpack_codes<<<dim3(gxk, BHkv), 256, 0, s>>>(P.k_codes, o.kc, D.Nk, D.d, D.nKb * k_block_bytes(D.d, D.int4), 1, D.int4);
+  if (o.vc) k_unpack_codes<<<dim3(gxk, BHkv), 256, 0, s>>>((const int8_t*)P.v_codes, (int8_t*)o.vc, D.Nk, D.d, (size_t)D.nKb * BKV * D.d, 2, 0);
+  const int nqg = (D.N + QGROUP - 1) / QGROUP, nkg = (D.Nk + KGROUP - 1) / KGROUP;
   if (o.qs) k_unpack_rows<<<dim3((nqg + 255) / 256, BH), 256, 0, s>>>(P.q_scale, o.qs, nqg, D.nQb * (BQ / QGROUP));
   if (o.ks) k_unpack_rows<<<dim3((nkg + 255) / 256, BHkv), 256, 0, s>>>(P.k_scale, o.ks, nkg, D.nKb * (BKV / KGROUP));
   if (o.vs) k_unpack_rows<<<dim3(1, BHkv), 256, 0, s>>>(P.v_scale, o.vs, D.d, D.d);
@@ -595,7 +597,7 @@ hipError_t launch_unpack(const Dims& D, const Ptrs& P, const void* quant_out, hi
   if (o.vm && D.smooth_v) k_unpack_rows<<<dim3(1, BHkv), 256, 0, s>>>(P.v_mean, o.vm, D.d, D.d);
   if (D.int4) {
     if (o.qm) k_unpack_rows<<<dim3(1, BH * D.nQb), 256, 0, s>>>(P.q_mean, o.qm, D.d, D.d);
-    if (o.ds) k_unpack_rows<<<dim3((D.N + 255) / 256, BH * D.nQb), 256, 0, s>>>(P.delta_s, o.ds, D.N, D.nKb * BKV);
+    if (o.ds) k_unpack_rows<<<dim3((D.Nk + 255) / 256, BH * D.nQb), 256, 0, s>>>(P.delta_s, o.ds, D.Nk, D.nKb * BKV);
   }
   return hipGetLastError();
 }

@@ -218,6 +218,48 @@ def test_per_block_groups_match_oracle(N, d, dtype, H, Hkv, causal, mode):
     assert e_f <= e_b * 1.02      # finer groups are not worse (the paper's granularity table)
 
 
+# ---- key length different from query length (cross attention, chunked prefill, decode) ---------
+CROSS_CASES = [
+    # N, N_kv, d, dtype, H, Hkv, causal
+    (200, 333, 128, "bf16", 2, 1, False),
+    (333, 70, 64, "fp16", 2, 2, False),       # fewer keys than queries
+    (130, 640, 128, "bf16", 2, 2, True),      # chunked prefill: the last 130 queries of 640 tokens
+    (1, 300, 128, "bf16", 4, 1, True),        # one decode step
+]
+
+
+@pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("N,Nk,d,dtype,H,Hkv,causal", CROSS_CASES)
+def test_other_key_length_matches_oracle(N, Nk, d, dtype, H, Hkv, causal, mode):
+    pa = _pa()
+    spec = _spec(N, d, dtype, H, Hkv, causal=causal).with_(N_kv=Nk)
+    data, (q, k, v) = _gpu_inputs(spec)
+    assert k.shape[2] == Nk and q.shape[2] == N
+    print(f"cross case N={N} N_kv={Nk} d={d} {dtype} H={H}/{Hkv} causal={causal} mode={mode}", flush=True)
+    got, args, ws = pa.sage_attn_quant(q, k, v, causal=causal, mode=mode)
+    out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode)
+    torch.cuda.synchronize()
+    got = {n: t.cpu().numpy() for n, t in got.items()}
+    g = H // Hkv
+    for h in range(H):
+        pro = so.quantize_head(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], mode=mode)
+        assert np.array_equal(got["q_codes"][0, h], pro["q_codes"]), "q codes"
+        assert np.array_equal(got["q_scale"][0, h], pro["q_scale"]), "q scales"
+        assert np.array_equal(got["k_codes"][0, h // g], pro["k_codes"]), "k codes"
+        assert np.array_equal(got["k_scale"][0, h // g], pro["k_scale"]), "k scales"
+        assert np.array_equal(got["v_codes"][0, h // g], pro["v_codes"]), "v codes"
+        assert np.array_equal(got["k_mean"][0, h // g], pro["kbar"]), "k mean"
+        if mode == "int4_fp8":
+            D = pro["delta_s"].astype(np.float64)
+            diff = np.abs(got["delta_s"][0, h].astype(np.float64) - D)
+            assert np.all(diff <= np.spacing(np.abs(D))), "delta S"
+    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32")
+    check_output(wl.from_torch(out), ref, dtype)
+    full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
+                     for h in range(H)])
+    assert wl.cos_sim(wl.from_torch(out)[0], full) > (0.9 if mode == "int4_fp8" else 0.99)
+
+
 def test_plain_signature_and_repeatability():
     pa = _pa()
     spec = _spec(384, 128, "bf16", 2, 2)
@@ -255,6 +297,10 @@ def test_error_codes_from_the_boundary():
     assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -3          # workspace too small
     a.workspace_bytes = ws.numel(); a.mode = 5
     assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -2
+    a.mode = 0; a.causal = 1; a.N_kv = a.N - 1
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -2          # causal mask with fewer keys than queries
+    a.N_kv = -3
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -1
 
 
 def test_side_stream_and_workspace_reuse():

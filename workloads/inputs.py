@@ -31,6 +31,11 @@ class WorkloadSpec:
     token_norm_max: float  # token-wise scale drawn log-uniformly from [1, token_norm_max]
     config_id: int
     v_bias: float = 0.0  # per-channel bias of V: sign random per channel, magnitude in v_bias +- 0.5
+    N_kv: int = 0        # keys / values per head; 0 = N
+
+    @property
+    def kv_len(self):
+        return self.N_kv or self.N
 
     def with_(self, **kw):
         return replace(self, **kw)
@@ -76,8 +81,8 @@ def _seed(spec, seed, kind, b, h):
     return np.random.SeedSequence([1000 * spec.config_id + seed, kind, b, h])
 
 
-def _qk_like(spec, rng, offset_std):
-    N, d = spec.N, spec.d
+def _qk_like(spec, rng, offset_std, N):
+    d = spec.d
     x = rng.standard_normal((N, d), dtype=np.float32)
     if spec.token_norm_max > 1.0:
         s = np.exp(rng.uniform(0.0, np.log(spec.token_norm_max), size=(N, 1))).astype(np.float32)
@@ -98,11 +103,11 @@ def make_head(spec, which, b, h, seed=0):
     kind = {"q": 0, "k": 1, "v": 2}[which]
     rng = np.random.default_rng(_seed(spec, seed, kind, b, h))
     if which == "q":
-        x = _qk_like(spec, rng, spec.q_offset_std)
+        x = _qk_like(spec, rng, spec.q_offset_std, spec.N)
     elif which == "k":
-        x = _qk_like(spec, rng, spec.k_offset_std)
+        x = _qk_like(spec, rng, spec.k_offset_std, spec.kv_len)
     else:
-        x = rng.standard_normal((spec.N, spec.d), dtype=np.float32)
+        x = rng.standard_normal((spec.kv_len, spec.d), dtype=np.float32)
         if spec.v_bias > 0:
             sign = np.where(rng.random((1, spec.d)) < 0.5, -1.0, 1.0)
             x += (sign * rng.uniform(spec.v_bias - 0.5, spec.v_bias + 0.5, size=(1, spec.d))).astype(np.float32)
@@ -120,7 +125,7 @@ def make_inputs(spec, seed=0, heads=None):
     q_heads = list(range(spec.H)) if heads is None else list(heads)
     kv_heads = sorted({h // g for h in q_heads})
     q = np.empty((spec.B, len(q_heads), spec.N, spec.d), np.float32)
-    k = np.empty((spec.B, len(kv_heads), spec.N, spec.d), np.float32)
+    k = np.empty((spec.B, len(kv_heads), spec.kv_len, spec.d), np.float32)
     v = np.empty_like(k)
     jobs = [(q, "q", b, i, h) for b in range(spec.B) for i, h in enumerate(q_heads)]
     jobs += [(a, w, b, i, h) for a, w in ((k, "k"), (v, "v")) for b in range(spec.B) for i, h in enumerate(kv_heads)]
@@ -140,9 +145,12 @@ def make_inputs(spec, seed=0, heads=None):
 
 
 def flops(spec):
-    """Operation count used for TOPS: 4*B*H*N^2*d, halved under a causal mask."""
-    ops = 4.0 * spec.B * spec.H * float(spec.N) ** 2 * spec.d
-    return ops / 2 if spec.causal else ops
+    """Operation count used for TOPS: 4*B*H*N*N_kv*d; under a causal mask the visible (query, key)
+    pairs, N*(2*N_kv - N)/2, i.e. half of N^2 when N_kv = N."""
+    pairs = float(spec.N) * spec.kv_len
+    if spec.causal:
+        pairs = float(spec.N) * (2.0 * spec.kv_len - spec.N) / 2.0
+    return 4.0 * spec.B * spec.H * pairs * spec.d
 
 
 def to_torch(x, dtype, device="cpu"):
