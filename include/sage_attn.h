@@ -10,7 +10,7 @@
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library never frees or
- *     keeps them.  q and out are contiguous [B, H, N, d]; k and v are contiguous
+ *     keeps them.  q and out are contiguous [B, H, N, d] (or [B, N, H, d], see layout); k and v are contiguous
  *     [B, H_kv, N_kv, d]; elements are 16-bit (fp16 or bf16, see dtype).  Query head h reads KV
  *     head h / (H / H_kv).  N_kv = N unless sage_attn_args.N_kv says otherwise; a causal mask is
  *     aligned to the last query and key (key t visible to query r iff t <= r + N_kv - N) and
@@ -38,7 +38,7 @@ extern "C" {
 enum {
   SAGE_OK = 0,
   SAGE_ERR_INVALID_ARG = -1,  /* null pointer, non-positive size, H % H_kv != 0 */
-  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode, dtype, flag or group map, causal with N_kv < N */
+  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode, dtype, flag, group map or layout, causal with N_kv < N */
   SAGE_ERR_WORKSPACE = -3,    /* workspace missing or smaller than sage_attn_workspace_bytes() */
   SAGE_ERR_HIP = -4           /* a HIP call or launch failed (the HIP error is cleared) */
 };
@@ -58,6 +58,9 @@ enum { SAGE_FLAG_SMOOTH_V = 1 };
    (per-block quantization, the granularity of SageAttention-1, Sec. 2.3); same kernels, same speed,
    lower accuracy.  q_scale / k_scale keep their shapes (values repeat inside a block). */
 enum { SAGE_GROUPS_LANE = 0, SAGE_GROUPS_BLOCK = 1 };
+/* Memory order of the four tensors (all contiguous): heads outside tokens, [B, H, N, d], or tokens
+   outside heads, [B, N, H, d] (k, v: H_kv and N_kv).  The workspace layouts do not depend on it. */
+enum { SAGE_LAYOUT_HND = 0, SAGE_LAYOUT_NHD = 1 };
 
 /* Numerical block sizes of Algorithm 1 as this library fixes them. */
 #define SAGE_BQ_SMOOTH 128 /* tokens per Q smoothing block (b_q) */
@@ -80,6 +83,7 @@ typedef struct sage_attn_args {
   int flags;              /* SAGE_FLAG_* or-ed together; 0 = the paper's default configuration */
   int group_map;          /* SAGE_GROUPS_*; 0 = the default */
   int N_kv;               /* keys / values per head (cross attention, chunked prefill); 0 = N */
+  int layout;             /* SAGE_LAYOUT_*: memory order of q, k, v and out; 0 = [B, H, N, d] */
   void* workspace;        /* device scratch of >= sage_attn_workspace_bytes(); 256-byte aligned */
   size_t workspace_bytes;
   void* stream;           /* hipStream_t, NULL = default stream */

@@ -14,6 +14,8 @@ SAGE_DT_FP16, SAGE_DT_BF16 = 0, 1
 SAGE_FLAG_SMOOTH_V = 1
 SAGE_GROUPS_LANE, SAGE_GROUPS_BLOCK = 0, 1
 _GROUPS = {"lane": 0, "block": 1, 0: 0, 1: 1}
+SAGE_LAYOUT_HND, SAGE_LAYOUT_NHD = 0, 1
+_LAYOUTS = {"HND": 0, "NHD": 1, 0: 0, 1: 1}
 _MODES = {"int4_fp8": 0, "int8_fp8": 1, 0: 0, 1: 1}
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -32,7 +34,7 @@ class sage_attn_args(ctypes.Structure):
                 ("B", ctypes.c_int), ("H", ctypes.c_int), ("H_kv", ctypes.c_int),
                 ("N", ctypes.c_int), ("d", ctypes.c_int),
                 ("causal", ctypes.c_int), ("sm_scale", ctypes.c_float),
-                ("mode", ctypes.c_int), ("dtype", ctypes.c_int), ("flags", ctypes.c_int), ("group_map", ctypes.c_int), ("N_kv", ctypes.c_int),
+                ("mode", ctypes.c_int), ("dtype", ctypes.c_int), ("flags", ctypes.c_int), ("group_map", ctypes.c_int), ("N_kv", ctypes.c_int), ("layout", ctypes.c_int),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("stream", ctypes.c_void_p)]
 
@@ -99,27 +101,30 @@ def _ptr(t):
 
 
 def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
-              smooth_v=False, group_map="lane"):
-    """Fills a sage_attn_args from torch tensors q [B,H,N,d], k/v [B,H_kv,N,d] (contiguous, on the
-    GPU).  `workspace` is a uint8 GPU tensor (or None); `stream` a torch.cuda.Stream (None = the
+              smooth_v=False, group_map="lane", layout="HND"):
+    """Fills a sage_attn_args from torch tensors q [B,H,N,d], k/v [B,H_kv,N_kv,d] (layout "HND") or
+    q [B,N,H,d], k/v [B,N_kv,H_kv,d] (layout "NHD"), contiguous, on the GPU.  `workspace` is a uint8 GPU tensor (or None); `stream` a torch.cuda.Stream (None = the
     current one)."""
     for name, t in (("q", q), ("k", k), ("v", v)):
         if not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
             raise ValueError(f"{name} must be a contiguous 4-D GPU tensor")
     if k.shape != v.shape or k.dtype != q.dtype or v.dtype != q.dtype:
         raise ValueError("k and v must share shape; q, k, v must share dtype")
-    B, H, N, d = q.shape
+    nhd = _LAYOUTS[layout] == SAGE_LAYOUT_NHD
+    B, H, N, d = (q.shape[0], q.shape[2], q.shape[1], q.shape[3]) if nhd else q.shape
+    Hkv, Nk = (k.shape[2], k.shape[1]) if nhd else (k.shape[1], k.shape[2])
     if k.shape[0] != B or k.shape[3] != d:
         raise ValueError("k/v shape does not match q")
     if out is not None and (out.shape != q.shape or out.dtype != q.dtype or not out.is_contiguous()):
         raise ValueError("out must look like q")
     a = sage_attn_args()
     a.q, a.k, a.v, a.out = q.data_ptr(), k.data_ptr(), v.data_ptr(), (out.data_ptr() if out is not None else 0)
-    a.B, a.H, a.H_kv, a.N, a.d = B, H, k.shape[1], N, d
+    a.B, a.H, a.H_kv, a.N, a.d = B, H, Hkv, N, d
     a.causal, a.sm_scale, a.mode, a.dtype = int(bool(causal)), float(sm_scale), _MODES[mode], _dtype_code(q)
     a.flags = SAGE_FLAG_SMOOTH_V if smooth_v else 0
     a.group_map = _GROUPS[group_map]
-    a.N_kv = k.shape[2]
+    a.N_kv = Nk
+    a.layout = _LAYOUTS[layout]
     if workspace is not None:
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     else:
@@ -143,11 +148,11 @@ def _alloc_workspace(args, device):
 
 
 def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
-                     smooth_v=False, group_map="lane"):
+                     smooth_v=False, group_map="lane", layout="HND"):
     """Whole forward pass.  Returns `out` (allocated if not given)."""
     if out is None:
         out = torch.empty_like(q)
-    a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v, group_map)
+    a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v, group_map, layout)
     keep = _alloc_workspace(a, q.device) if workspace is None else workspace
     if workspace is None and stream is not None:
         keep.record_stream(stream)   # allocated on the current stream, used on another one

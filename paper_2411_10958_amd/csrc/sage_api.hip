@@ -20,6 +20,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if (a->dtype != SAGE_DT_FP16 && a->dtype != SAGE_DT_BF16) return SAGE_ERR_UNSUPPORTED;
   if ((a->flags & ~SAGE_FLAG_SMOOTH_V) != 0) return SAGE_ERR_UNSUPPORTED;
   if (a->group_map != SAGE_GROUPS_LANE && a->group_map != SAGE_GROUPS_BLOCK) return SAGE_ERR_UNSUPPORTED;
+  if (a->layout != SAGE_LAYOUT_HND && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
   if (need_io && (!a->q || !a->k || !a->v || !a->out)) return SAGE_ERR_INVALID_ARG;
   // grid limits of the launches below (y dimension <= 65535, tile count fits an int)
   if ((long long)a->B * a->H > 65535) return SAGE_ERR_UNSUPPORTED;
@@ -33,6 +34,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   D->bf16 = a->dtype == SAGE_DT_BF16;
   D->smooth_v = (a->flags & SAGE_FLAG_SMOOTH_V) != 0;
   D->block_groups = a->group_map == SAGE_GROUPS_BLOCK;
+  D->nhd = a->layout == SAGE_LAYOUT_NHD;
   const float sm = a->sm_scale > 0.0f ? a->sm_scale : (float)(1.0 / std::sqrt((double)a->d));
   D->kappa = sm * LOG2E;   // one FP32 rounding of the product of two FP32 values
   return SAGE_OK;
@@ -94,7 +96,7 @@ int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B,
   sage_attn_args a;
   a.q = q; a.k = k; a.v = v; a.out = out;
   a.B = B; a.H = H; a.H_kv = H; a.N = N; a.d = d;
-  a.causal = causal; a.sm_scale = sm_scale; a.mode = mode; a.dtype = SAGE_DT_BF16; a.flags = 0; a.group_map = SAGE_GROUPS_LANE; a.N_kv = 0;
+  a.causal = causal; a.sm_scale = sm_scale; a.mode = mode; a.dtype = SAGE_DT_BF16; a.flags = 0; a.group_map = SAGE_GROUPS_LANE; a.N_kv = 0; a.layout = SAGE_LAYOUT_HND;
   a.workspace = nullptr; a.workspace_bytes = 0; a.stream = nullptr;
   const size_t need = sage_attn_workspace_bytes(&a);
   if (need == 0) {

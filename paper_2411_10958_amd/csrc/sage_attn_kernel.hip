@@ -26,6 +26,7 @@ struct AttnParams {
   const float* delta_s;
   void* out;
   int H, Hkv, N, Nk, coff, nQb, nKb, total_tiles;   // N queries, Nk keys; causal: key t <= query + coff
+  TensorMap om;           // where the rows of `out` start
   float kappa;
 };
 
@@ -481,7 +482,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
   }
   if (query < p.N) {
-    unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) + ((size_t)bh * p.N + query) * D;
+    unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) + row_offset(p.om, bh, query);
     const float* dv = p.v_scale + bhkv * D;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
@@ -553,7 +554,8 @@ static hipError_t launch_attention_t(const Dims& Dm, const Ptrs& P, hipStream_t 
   p.q_scale = P.q_scale; p.k_scale = P.k_scale; p.v_scale = P.v_scale; p.delta_s = P.delta_s;
   p.v_mean = Dm.smooth_v ? P.v_mean : nullptr;
   p.out = P.out;
-  p.H = Dm.H; p.Hkv = Dm.Hkv; p.N = Dm.N; p.Nk = Dm.Nk; p.coff = Dm.coff; p.nQb = Dm.nQb; p.nKb = Dm.nKb;
+  p.H = Dm.H; p.Hkv = Dm.Hkv; p.N = Dm.N; p.Nk = Dm.Nk; p.coff = Dm.coff; p.nQb = Dm.nQb;
+  p.om = make_tensor_map(Dm.nhd, Dm.H, Dm.N, Dm.d); p.nKb = Dm.nKb;
   p.total_tiles = Dm.B * Dm.H * Dm.nQb;
   p.kappa = Dm.kappa;
   const int grid = 8 * ((p.total_tiles + 7) / 8);

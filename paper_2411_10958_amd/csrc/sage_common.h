@@ -23,13 +23,29 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
+// Where row n of head (b, h) of a user tensor starts, in elements: b * sb + h * sh + n * sn.
+struct TensorMap {
+  long long sb, sh, sn;
+  int heads;
+};
+__host__ __device__ inline size_t row_offset(const TensorMap& m, size_t bh, int n) {
+  return (bh / m.heads) * (size_t)m.sb + (bh % m.heads) * (size_t)m.sh + (size_t)n * (size_t)m.sn;
+}
+inline TensorMap make_tensor_map(int nhd, int heads, int tokens, int d) {
+  TensorMap m;
+  m.heads = heads;
+  if (nhd) { m.sb = (long long)tokens * heads * d; m.sh = d; m.sn = (long long)heads * d; }
+  else     { m.sb = (long long)heads * tokens * d; m.sh = (long long)tokens * d; m.sn = d; }
+  return m;
+}
+
 struct Dims {
   int B, H, Hkv, N, d;
   int Nk;      // keys / values per head (N unless the caller says otherwise)
   int coff;    // Nk - N: the causal mask lets query r see keys t <= r + coff
   int nQb;     // ceil(N / 128) query blocks
   int nKb;     // ceil(Nk / 64) key blocks
-  int causal, int4, bf16, smooth_v, block_groups;
+  int causal, int4, bf16, smooth_v, block_groups, nhd;
   float kappa; // fl32(sm_scale * log2 e)
 };
 

@@ -79,13 +79,12 @@ template <bool BF16, int D, bool SMOOTH_V>
 __global__ void __launch_bounds__(256) k_col_stats(const unsigned short* __restrict__ K,
                                                    const unsigned short* __restrict__ V,
                                                    double* __restrict__ k_sum, double* __restrict__ v_sum,
-                                                   unsigned* __restrict__ v_max, int N) {
+                                                   unsigned* __restrict__ v_max, int N, TensorMap km) {
   constexpr int NCG = D / 8, NRG = 256 / NCG;
   __shared__ double s_sum[NRG][D];
   __shared__ double s_vsum[SMOOTH_V ? NRG : 1][D];
   __shared__ float s_max[SMOOTH_V ? 1 : NRG][D];
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
-  const size_t head = (size_t)blockIdx.y * N * D;
   const int r0 = blockIdx.x * STAT_ROWS;
   const int r1 = min(r0 + STAT_ROWS, N);
   double acc[8], vacc[8];
@@ -94,8 +93,9 @@ __global__ void __launch_bounds__(256) k_col_stats(const unsigned short* __restr
   for (int e = 0; e < 8; ++e) { acc[e] = 0.0; vacc[e] = 0.0; mx[e] = 0.0f; }
   for (int r = r0 + rg; r < r1; r += NRG) {
     float xk[8], xv[8];
-    load8<BF16>(K + head + (size_t)r * D + cg * 8, xk);
-    load8<BF16>(V + head + (size_t)r * D + cg * 8, xv);
+    const size_t row = row_offset(km, blockIdx.y, r) + cg * 8;
+    load8<BF16>(K + row, xk);
+    load8<BF16>(V + row, xv);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       acc[e] += (double)xk[e];
@@ -125,11 +125,10 @@ __global__ void __launch_bounds__(256) k_col_stats(const unsigned short* __restr
 template <bool BF16, int D>
 __global__ void __launch_bounds__(256) k_v_absmax(const unsigned short* __restrict__ V,
                                                   const float* __restrict__ v_mean,
-                                                  unsigned* __restrict__ v_max, int N) {
+                                                  unsigned* __restrict__ v_max, int N, TensorMap km) {
   constexpr int NCG = D / 8, NRG = 256 / NCG;
   __shared__ float s_max[NRG][D];
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
-  const size_t head = (size_t)blockIdx.y * N * D;
   const int r0 = blockIdx.x * STAT_ROWS;
   const int r1 = min(r0 + STAT_ROWS, N);
   float mean[8], mx[8];
@@ -137,7 +136,7 @@ __global__ void __launch_bounds__(256) k_v_absmax(const unsigned short* __restri
   for (int e = 0; e < 8; ++e) { mean[e] = v_mean[(size_t)blockIdx.y * D + cg * 8 + e]; mx[e] = 0.0f; }
   for (int r = r0 + rg; r < r1; r += NRG) {
     float xv[8];
-    load8<BF16>(V + head + (size_t)r * D + cg * 8, xv);
+    load8<BF16>(V + row_offset(km, blockIdx.y, r) + cg * 8, xv);
 #pragma unroll
     for (int e = 0; e < 8; ++e) mx[e] = fmaxf(mx[e], fabsf(__fsub_rn(xv[e], mean[e])));
   }
@@ -175,7 +174,7 @@ template <bool BF16, bool INT4, int D>
 __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restrict__ Q,
                                                  float* __restrict__ q_mean, float* __restrict__ q_scale,
                                                  int8_t* __restrict__ q_codes, int N, int nQb,
-                                                 int block_groups) {
+                                                 int block_groups, TensorMap qm) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;  // RPT rows per thread (8 or 4)
   constexpr int QMAX = INT4 ? 7 : 127;
   __shared__ double s_sum[NRG][D];
@@ -190,7 +189,7 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
   for (int i = 0; i < RPT; ++i) {
     const int r = rg * RPT + i;
     if (r < valid) {
-      load8<BF16>(Q + (bh * N + n0 + r) * D + cg * 8, x[i]);
+      load8<BF16>(Q + row_offset(qm, bh, n0 + r) + cg * 8, x[i]);
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) x[i][e] = 0.0f;
@@ -308,7 +307,7 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
                                                  const float* __restrict__ q_mean,
                                                  float* __restrict__ delta_s, int N, int nKb, int nQb,
                                                  int G, float kappa, int block_groups, int causal,
-                                                 int coff) {
+                                                 int coff, TensorMap km) {
   constexpr int CPL = D / 4;                       // channels per lane (32 or 16)
   constexpr int QMAX = INT4 ? 7 : 127;
   // LDS row of staged block means: channel c sits at column c + 16*(c / 32) when D = 128, so the
@@ -361,7 +360,7 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
 #pragma unroll
     for (int p = 0; p < CPL / 8; ++p) {
       float x8[8];
-      load8<BF16>(K + (bhkv * N + n0 + r) * D + c0 + 8 * p, x8);
+      load8<BF16>(K + row_offset(km, bhkv, n0 + r) + c0 + 8 * p, x8);
       const float4 m0 = *reinterpret_cast<const float4*>(k_mean + bhkv * D + c0 + 8 * p);
       const float4 m1 = *reinterpret_cast<const float4*>(k_mean + bhkv * D + c0 + 8 * p + 4);
       const float mean[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
@@ -454,7 +453,7 @@ template <bool BF16, int D, bool SMOOTH_V>
 __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restrict__ V,
                                                  const float* __restrict__ v_scale,
                                                  const float* __restrict__ v_mean,
-                                                 uint8_t* __restrict__ v_codes, int N, int nKb) {
+                                                 uint8_t* __restrict__ v_codes, int N, int nKb, TensorMap km) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BKV / NRG;
   __shared__ uint8_t tile[BKV][D + 16];
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
@@ -472,7 +471,7 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
     const int r = rg * RPT + i;
     float x[8];
     if (n0 + r < N) {
-      load8<BF16>(V + (bh * N + n0 + r) * D + cg * 8, x);
+      load8<BF16>(V + row_offset(km, bh, n0 + r) + cg * 8, x);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         if constexpr (SMOOTH_V) x[e] = __fsub_rn(x[e], mean[e]);
@@ -544,26 +543,27 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
   const unsigned short* v = (const unsigned short*)P.v;
   const int nstat = BHkv * Dm.d;
   const dim3 gstat((Dm.Nk + STAT_ROWS - 1) / STAT_ROWS, BHkv);
+  const TensorMap qm = make_tensor_map(Dm.nhd, Dm.H, Dm.N, Dm.d), km = make_tensor_map(Dm.nhd, Dm.Hkv, Dm.Nk, Dm.d);
   const float* v_mean = Dm.smooth_v ? P.v_mean : nullptr;
   k_zero_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, Dm.smooth_v ? P.v_sum : nullptr, P.v_max, nstat);
   if (Dm.smooth_v) {
-    k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.Nk);
+    k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.Nk, km);
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
                                                         nstat, Dm.Nk);
-    k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.Nk);
+    k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.Nk, km);
     k_finalize_vscale<<<(nstat + 255) / 256, 256, 0, s>>>(P.v_max, P.v_scale, nstat);
   } else {
-    k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.Nk);
+    k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.Nk, km);
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
                                                         nstat, Dm.Nk);
   }
   k_quant_q<BF16, INT4, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.nQb,
-                                                        Dm.block_groups);
+                                                        Dm.block_groups, qm);
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
                                                               P.delta_s, Dm.Nk, Dm.nKb, Dm.nQb, Dm.H / Dm.Hkv,
-                                                              Dm.kappa, Dm.block_groups, Dm.causal, Dm.coff);
-  if (Dm.smooth_v) k_quant_v<BF16, D, true><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.Nk, Dm.nKb);
-  else k_quant_v<BF16, D, false><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.Nk, Dm.nKb);
+                                                              Dm.kappa, Dm.block_groups, Dm.causal, Dm.coff, km);
+  if (Dm.smooth_v) k_quant_v<BF16, D, true><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.Nk, Dm.nKb, km);
+  else k_quant_v<BF16, D, false><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.Nk, Dm.nKb, km);
   return hipGetLastError();
 }
 

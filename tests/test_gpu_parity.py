@@ -260,6 +260,23 @@ def test_other_key_length_matches_oracle(N, Nk, d, dtype, H, Hkv, causal, mode):
     assert wl.cos_sim(wl.from_torch(out)[0], full) > (0.9 if mode == "int4_fp8" else 0.99)
 
 
+# ---- [B, N, H, d] memory order ------------------------------------------------------------------
+@pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("N,Nk,d,H,Hkv,causal", [(333, 333, 128, 4, 2, True), (200, 450, 64, 2, 2, False)])
+def test_nhd_layout_equals_hnd(N, Nk, d, H, Hkv, causal, mode):
+    """The same tensors handed over token-major give bit-identical results (the workspace layouts and
+    the arithmetic do not depend on the memory order of the inputs)."""
+    pa = _pa()
+    spec = _spec(N, d, "bf16", H, Hkv, B=2, causal=causal).with_(N_kv=Nk)
+    _, (q, k, v) = _gpu_inputs(spec)
+    ref = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode)
+    qn, kn, vn = (t.permute(0, 2, 1, 3).contiguous() for t in (q, k, v))
+    out = pa.sage_attn_fwd_ex(qn, kn, vn, causal=causal, mode=mode, layout="NHD")
+    torch.cuda.synchronize()
+    assert out.shape == qn.shape
+    assert torch.equal(out.permute(0, 2, 1, 3), ref)
+
+
 def test_plain_signature_and_repeatability():
     pa = _pa()
     spec = _spec(384, 128, "bf16", 2, 2)
