@@ -35,6 +35,66 @@ __device__ inline int quant_code(float x, float delta, int qmax) {
   return c > qmax ? qmax : (c < -qmax ? -qmax : c);
 }
 
+// The same psi without a division per element.  With r = 1/delta to within 1 ulp (the hardware
+// reciprocal), y = fl32(x * r) differs from the oracle's fl32(x / delta) by at most 2^-22 |y|, so
+// whenever y is further than tau = 2^-14 (|y| <= 127.5) or 2^-18 (|y| <= 7.5) from a half-integer the
+// two round to the same integer.  QuantScale holds r and the bound 0.5 - tau; the caller takes the
+// largest |y - rint(y)| of a group of elements and recomputes the group with quant_code when it
+// exceeds the bound (about one element in 2^13 resp. 2^17).  Scales outside [2^-100, 2^100]
+// always take the exact path (bound -1); delta == 0 gives r = 0 and codes 0.  No clamp is needed:
+// |x| <= the group maximum, and fl32(max / fl32(max / qmax)) rounds to qmax.
+struct QuantScale { float r, bound; };
+template <int QMAX>
+__device__ inline QuantScale quant_scale(float delta) {
+  QuantScale q;
+  const bool regular = delta >= 0x1p-100f && delta <= 0x1p100f;
+  q.r = regular ? __builtin_amdgcn_rcpf(delta) : 0.0f;
+  q.bound = (regular || delta == 0.0f) ? 0.5f - (QMAX > 7 ? 0x1p-14f : 0x1p-18f) : -1.0f;
+  return q;
+}
+// NE codes (as integer-valued floats) of x[0..NE) with one scale, handed to put(e, code)
+template <int NE, int QMAX, class Put>
+__device__ inline void quant_group(const float* x, float delta, const QuantScale& qs, Put&& put) {
+  float worst = 0.0f;
+#pragma unroll
+  for (int e = 0; e < NE; ++e) {
+    const float y = x[e] * qs.r;
+    const float c = rintf(y);
+    worst = fmaxf(worst, fabsf(y - c));
+    put(e, c);
+  }
+  if (!(worst <= qs.bound)) {
+#pragma unroll
+    for (int e = 0; e < NE; ++e) put(e, (float)quant_code(x[e], delta, QMAX));
+  }
+}
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned v6u __attribute__((ext_vector_type(6)));
+// 32 INT4 codes held as integer-valued floats (every integer of [-7, 7] is an E2M3 value) become
+// consecutive 6-bit E2M3 fields, element e at bit 6e: the conversion instruction takes the even
+// elements in its first operand and the odd ones in its second (scale 1.0), so the codes are
+// collected in that shape from the start
+struct Codes32 {
+  v16f ev, od;
+  __device__ inline void set(int e, float c) { if (e & 1) od[e >> 1] = c; else ev[e >> 1] = c; }
+  // The instruction writes its first result registers before it has read all of its inputs, and
+  // the compiler does not know: a result allocated on top of part of an input corrupts the codes.
+  // The empty asm statements make both operands opaque 16-register values and then need them and
+  // the result at the same time, which keeps the three register ranges apart.  (Vector operands
+  // of asm statements do not parse in the host pass, which never calls this.)
+  __device__ inline v6u pack() const {
+    v6u r = {0u, 0u, 0u, 0u, 0u, 0u};
+#if defined(__HIP_DEVICE_COMPILE__)
+    v16f a = ev, b = od;
+    asm volatile("" : "+v"(a), "+v"(b));
+    r = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(a, b, 1.0f);
+    asm volatile("" ::"v"(r), "v"(a), "v"(b));
+#endif
+    return r;
+  }
+};
+
 // eight int8 codes as two's-complement bytes
 __device__ inline uint2 pack8(const int (&c)[8]) {
   uint2 o;
@@ -384,26 +444,28 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
   const float delta = __fdiv_rn(mx, (float)QMAX);
   if (lane == 0) k_scale[(bhkv * nKb + kb) * (BKV / KGROUP) + w] = delta;
   uint8_t* img = reinterpret_cast<uint8_t*>(s_codes);
+  const QuantScale qs = quant_scale<QMAX>(delta);
   if constexpr (INT4) {
     // the lane's CPL codes are CPL*6/32 consecutive dwords of one MFMA lane's payload (all 6 of
     // them when d = 128; dwords 0..2 or 3..5 when d = 64)
-    int c[CPL];
+    Codes32 cd;
 #pragma unroll
-    for (int e = 0; e < CPL; ++e) c[e] = quant_code(x[e], delta, QMAX);
-    unsigned w[CPL * 6 / 32];
-    pack6<CPL>(c, w);
+    for (int e = 0; e < 16; ++e) { cd.ev[e] = 0.0f; cd.od[e] = 0.0f; }
+#pragma unroll
+    for (int g = 0; g < CPL / 8; ++g)
+      quant_group<8, QMAX>(x + 8 * g, delta, qs, [&](int e, float c) { cd.set(8 * g + e, c); });
+    const v6u pw = cd.pack();
     int lane_m, e0;
     const size_t op = k_op6(r, c0, D, &lane_m, &e0);
     const int d0 = (6 * e0) >> 5;
 #pragma unroll
     for (int i = 0; i < CPL * 6 / 32; ++i)
-      *reinterpret_cast<unsigned*>(img + op + op6_byte(lane_m, 4 * (d0 + i))) = w[i];
+      *reinterpret_cast<unsigned*>(img + op + op6_byte(lane_m, 4 * (d0 + i))) = pw[i];
   } else {
 #pragma unroll
     for (int p = 0; p < CPL / 8; ++p) {
       int c[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) c[e] = quant_code(x[8 * p + e], delta, QMAX);
+      quant_group<8, QMAX>(x + 8 * p, delta, qs, [&](int e, float cf) { c[e] = (int)cf; });
       *reinterpret_cast<uint2*>(img + k_code_off(r, c0 + 8 * p, D)) = pack8(c);
     }
   }
@@ -416,9 +478,9 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
   if constexpr (INT4) {
     // FP64 MFMA lane map: lane l supplies A[l%16][l/16] and B[l/16][l%16]; result element v of
     // lane l is row 4*v + l/16, column l%16
-    double bk[CPL];
-#pragma unroll
-    for (int cs = 0; cs < CPL; ++cs) bk[cs] = (double)x[cs];
+    // the smoothed keys stay in FP32 registers and are widened per use: CPL more conversions per
+    // pass (a few percent of the pass's MFMA time) instead of 2 CPL more live registers, which is
+    // what lets four workgroups share a CU
     const double kap = (double)kappa;
     const int qcol = c0 + (D == 128 ? 16 * k4 : 0);
     for (int p = p_first; p < npass; p = next_pass(p)) {
@@ -429,8 +491,10 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
       v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
       for (int cs = 0; cs < CPL; ++cs) {
-        acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[r16][qcol + cs], bk[cs], acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[16 + r16][qcol + cs], bk[cs], acc1, 0, 0, 0);
+        asm volatile("" : "+v"(x[cs]));              // keeps the widening inside the pass loop
+        const double bk = (double)x[cs];
+        acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[r16][qcol + cs], bk, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[16 + r16][qcol + cs], bk, acc1, 0, 0, 0);
       }
       const size_t bh = bhkv * G + p / npass_h;
       const int i0 = (p % npass_h) * DS_QROWS;
