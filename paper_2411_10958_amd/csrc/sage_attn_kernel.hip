@@ -482,7 +482,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
   }
   if (query < p.N) {
-    unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) + row_offset(p.om, bh, query);
+    unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) + row_offset(p.om, head_offset(p.om, (unsigned)bh), query);
     const float* dv = p.v_scale + bhkv * D;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {

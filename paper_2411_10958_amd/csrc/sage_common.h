@@ -28,8 +28,14 @@ struct TensorMap {
   long long sb, sh, sn;
   int heads;
 };
-__host__ __device__ inline size_t row_offset(const TensorMap& m, size_t bh, int n) {
-  return (bh / m.heads) * (size_t)m.sb + (bh % m.heads) * (size_t)m.sh + (size_t)n * (size_t)m.sn;
+// element offset of head bh = b * heads + h (taken once per kernel: it holds the only division),
+// and of token n within it
+__host__ __device__ inline size_t head_offset(const TensorMap& m, unsigned bh) {
+  const unsigned b = bh / (unsigned)m.heads, h = bh - b * (unsigned)m.heads;
+  return b * (size_t)m.sb + h * (size_t)m.sh;
+}
+__host__ __device__ inline size_t row_offset(const TensorMap& m, size_t head_base, int n) {
+  return head_base + (size_t)n * (size_t)m.sn;
 }
 inline TensorMap make_tensor_map(int nhd, int heads, int tokens, int d) {
   TensorMap m;

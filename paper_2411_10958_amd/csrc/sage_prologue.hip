@@ -21,6 +21,16 @@ __device__ inline void load8(const unsigned short* p, float (&x)[8]) {
   }
 }
 
+template <bool BF16>
+__device__ inline void unpack8(const uint4& raw, float* x) {
+  const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = load16<BF16>((unsigned short)(w[i] & 0xffffu));
+    x[2 * i + 1] = load16<BF16>((unsigned short)(w[i] >> 16));
+  }
+}
+
 __device__ inline float wave_max(float v) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
@@ -147,13 +157,14 @@ __global__ void __launch_bounds__(256) k_col_stats(const unsigned short* __restr
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
   const int r0 = blockIdx.x * STAT_ROWS;
   const int r1 = min(r0 + STAT_ROWS, N);
+  const size_t hbase = head_offset(km, blockIdx.y);
   double acc[8], vacc[8];
   float mx[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { acc[e] = 0.0; vacc[e] = 0.0; mx[e] = 0.0f; }
   for (int r = r0 + rg; r < r1; r += NRG) {
     float xk[8], xv[8];
-    const size_t row = row_offset(km, blockIdx.y, r) + cg * 8;
+    const size_t row = row_offset(km, hbase, r) + cg * 8;
     load8<BF16>(K + row, xk);
     load8<BF16>(V + row, xv);
 #pragma unroll
@@ -191,12 +202,13 @@ __global__ void __launch_bounds__(256) k_v_absmax(const unsigned short* __restri
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
   const int r0 = blockIdx.x * STAT_ROWS;
   const int r1 = min(r0 + STAT_ROWS, N);
+  const size_t hbase = head_offset(km, blockIdx.y);
   float mean[8], mx[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { mean[e] = v_mean[(size_t)blockIdx.y * D + cg * 8 + e]; mx[e] = 0.0f; }
   for (int r = r0 + rg; r < r1; r += NRG) {
     float xv[8];
-    load8<BF16>(V + row_offset(km, blockIdx.y, r) + cg * 8, xv);
+    load8<BF16>(V + row_offset(km, hbase, r) + cg * 8, xv);
 #pragma unroll
     for (int e = 0; e < 8; ++e) mx[e] = fmaxf(mx[e], fabsf(__fsub_rn(xv[e], mean[e])));
   }
@@ -244,12 +256,13 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
   const size_t bh = blockIdx.y;
   const int n0 = qb * BQ;
   const int valid = min(BQ, N - n0);
+  const size_t hbase = head_offset(qm, blockIdx.y);
   float x[RPT][8];
 #pragma unroll
   for (int i = 0; i < RPT; ++i) {
     const int r = rg * RPT + i;
     if (r < valid) {
-      load8<BF16>(Q + row_offset(qm, bh, n0 + r) + cg * 8, x[i]);
+      load8<BF16>(Q + row_offset(qm, hbase, n0 + r) + cg * 8, x[i]);
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) x[i][e] = 0.0f;
@@ -338,6 +351,126 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
   for (int i = t; i < SLAB16; i += 256) dst[i] = s_codes[i];
 }
 
+// The 4-bit variant of the same step.  Two thread-to-data maps, joined through LDS:
+//  - loading and the exact column sums of the block mean use the coalesced map of k_quant_q (a
+//    thread owns 8 channels of BQ*D/2048 rows), and the raw 16-bit rows are parked in LDS;
+//  - quantization uses the map the codes are consumed in: a thread owns D/4 consecutive channels
+//    of the two queries of one scale group, i.e. (half of) one MFMA lane's payload per query, so
+//    the group maximum is two lane exchanges away and the codes leave through one FP32->FP6
+//    conversion per query instead of per-element table look-ups and 6-bit shifts.
+// LDS rows are kept as 16-byte chunks with the chunk index XOR-ed by the row's group number, which
+// makes both maps conflict-free for d = 128.
+template <bool BF16, int D>
+__global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restrict__ Q,
+                                                  float* __restrict__ q_mean, float* __restrict__ q_scale,
+                                                  int8_t* __restrict__ q_codes, int N, int nQb,
+                                                  int block_groups, TensorMap qm) {
+  constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;   // load map: RPT rows x 8 channels
+  constexpr int CPL = D / 4, CPC = CPL / 8;                      // quantization map: 2 rows x CPL channels
+  constexpr int QMAX = 7;
+  constexpr int SLAB = (int)q_slab_bytes(D, true);
+  static_assert(SLAB <= (int)sizeof(double) * NRG * D, "the code image reuses the column-sum buffer");
+  __shared__ uint4 s_raw[BQ * NCG];
+  __shared__ double s_sum[NRG][D];
+  __shared__ __align__(16) float s_mean[D];
+  __shared__ float s_bmax[4];
+  const int t = threadIdx.x;
+  const int qb = blockIdx.x;
+  const size_t bh = blockIdx.y;
+  const int n0 = qb * BQ;
+  const int valid = min(BQ, N - n0);
+  const size_t hbase = head_offset(qm, blockIdx.y);
+  auto swz = [](int r) { return (r >> 1) & (D == 128 ? 3 : 1); };
+  {
+    const int cg = t % NCG, rg = t / NCG;
+    double cs[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cs[e] = 0.0;
+    uint4 raw[RPT];
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+      const int r = rg * RPT + i;
+      raw[i] = r < valid ? *reinterpret_cast<const uint4*>(Q + row_offset(qm, hbase, n0 + r) + cg * 8)
+                         : make_uint4(0u, 0u, 0u, 0u);                  // padded rows are zero
+    }
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+      const int r = rg * RPT + i;
+      s_raw[r * NCG + (cg ^ swz(r))] = raw[i];
+      float x8[8];
+      unpack8<BF16>(raw[i], x8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) cs[e] += (double)x8[e];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s_sum[rg][cg * 8 + e] = cs[e];
+  }
+  __syncthreads();
+  if (t < D) {
+    double sm = 0.0;
+    for (int g = 0; g < NRG; ++g) sm += s_sum[g][t];
+    const float m = (float)(sm / (double)valid);
+    s_mean[t] = m;
+    q_mean[(bh * nQb + qb) * D + t] = m;
+  }
+  __syncthreads();
+
+  const int pair = t >> 2, c4 = t & 3;
+  float x[2][CPL];
+  float mx = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = 2 * pair + i;
+#pragma unroll
+    for (int j = 0; j < CPC; ++j) {
+      unpack8<BF16>(s_raw[r * NCG + ((c4 * CPC + j) ^ swz(r))], &x[i][8 * j]);
+      if (r < valid) {
+        const float4 m0 = *reinterpret_cast<const float4*>(&s_mean[CPL * c4 + 8 * j]);
+        const float4 m1 = *reinterpret_cast<const float4*>(&s_mean[CPL * c4 + 8 * j + 4]);
+        const float mean[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          x[i][8 * j + e] = __fsub_rn(x[i][8 * j + e], mean[e]);
+          mx = fmaxf(mx, fabsf(x[i][8 * j + e]));
+        }
+      }
+    }
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+  mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+  if (block_groups) {       // per-block granularity: one scale for the whole 128-query block
+    const float bm = wave_max(mx);
+    if ((t & 63) == 0) s_bmax[t >> 6] = bm;
+    __syncthreads();
+    mx = fmaxf(fmaxf(s_bmax[0], s_bmax[1]), fmaxf(s_bmax[2], s_bmax[3]));
+  }
+  const float delta = __fdiv_rn(mx, (float)QMAX);
+  if (c4 == 0) q_scale[(bh * nQb + qb) * (BQ / QGROUP) + pair] = delta;
+  const QuantScale qs = quant_scale<QMAX>(delta);
+  uint8_t* img = reinterpret_cast<uint8_t*>(&s_sum[0][0]);   // everyone is past the column sums
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    Codes32 cd;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { cd.ev[e] = 0.0f; cd.od[e] = 0.0f; }
+#pragma unroll
+    for (int g = 0; g < CPC; ++g)
+      quant_group<8, QMAX>(&x[i][8 * g], delta, qs, [&](int e, float c) { cd.set(8 * g + e, c); });
+    const v6u pw = cd.pack();
+    int lane_m, e0;
+    const size_t op = q_op6(2 * pair + i, CPL * c4, D, &lane_m, &e0);
+    const int d0 = (6 * e0) >> 5;
+#pragma unroll
+    for (int k = 0; k < CPL * 6 / 32; ++k)
+      *reinterpret_cast<unsigned*>(img + op + op6_byte(lane_m, 4 * (d0 + k))) = pw[k];
+  }
+  __syncthreads();
+  uint4* dst = reinterpret_cast<uint4*>(q_codes + (bh * nQb + qb) * q_slab_bytes(D, true));
+  const uint4* src = reinterpret_cast<const uint4*>(img);
+#pragma unroll
+  for (int i = t; i < SLAB / 16; i += 256) dst[i] = src[i];
+}
+
 // ------------------------------------------------------------------------------------------
 // K: smoothing by the token mean, 16-key-group quantization and, in the int4 mode, Delta-S.
 // (Algorithm 1: psi_K(K_j) after K = K - mean(K); Sec. 3.1: Delta-S = q_bar_i . gamma(K)^T.)
@@ -416,11 +549,12 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
 
   float x[CPL];
   float mx = 0.0f;
+  const size_t hbase = head_offset(km, blockIdx.y);
   if (n0 + r < N) {
 #pragma unroll
     for (int p = 0; p < CPL / 8; ++p) {
       float x8[8];
-      load8<BF16>(K + row_offset(km, bhkv, n0 + r) + c0 + 8 * p, x8);
+      load8<BF16>(K + row_offset(km, hbase, n0 + r) + c0 + 8 * p, x8);
       const float4 m0 = *reinterpret_cast<const float4*>(k_mean + bhkv * D + c0 + 8 * p);
       const float4 m1 = *reinterpret_cast<const float4*>(k_mean + bhkv * D + c0 + 8 * p + 4);
       const float mean[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
@@ -524,22 +658,42 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
   const int kb = blockIdx.x;
   const size_t bh = blockIdx.y;
   const int n0 = kb * BKV;
-  float sc[8], mean[8];
+  const size_t hbase = head_offset(km, blockIdx.y);
+  // y = fl32(x * r) with r = 1/delta_V to within 1 ulp stands in for the oracle's fl32(x / delta_V):
+  // the two differ by at most 2^-22 |y| (4 units of y's last place), so they round to the same E4M3
+  // code unless y lies within that distance of the midpoint of two codes - for |y| >= 2^-6, where the
+  // codes carry 3 mantissa bits, unless the low 20 bits of y's significand are within 8 of 0x80000.
+  // Rows with such an element, with a |y| below 2^-6 (subnormal codes, fixed spacing) or with a scale
+  // outside [2^-100, 2^100] are recomputed with the exact quotient.
+  float sc[8], mean[8], rs[8];
+  bool regular = true;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     sc[e] = v_scale[bh * D + cg * 8 + e];
     mean[e] = SMOOTH_V ? v_mean[bh * D + cg * 8 + e] : 0.0f;
+    const bool ok = sc[e] >= 0x1p-100f && sc[e] <= 0x1p100f;
+    rs[e] = ok ? __builtin_amdgcn_rcpf(sc[e]) : 0.0f;
+    regular = regular && (ok || sc[e] == 0.0f);     // a zero scale means an all-zero channel: codes 0
   }
 #pragma unroll
   for (int i = 0; i < RPT; ++i) {
     const int r = rg * RPT + i;
     float x[8];
     if (n0 + r < N) {
-      load8<BF16>(V + row_offset(km, bh, n0 + r) + cg * 8, x);
+      load8<BF16>(V + row_offset(km, hbase, n0 + r) + cg * 8, x);
+      float xc[8], smallest = 1.0f;
+      unsigned nearest = 0xffffffffu;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        if constexpr (SMOOTH_V) x[e] = __fsub_rn(x[e], mean[e]);
-        x[e] = sc[e] > 0.0f ? __fdiv_rn(x[e], sc[e]) : 0.0f;
+        xc[e] = SMOOTH_V ? __fsub_rn(x[e], mean[e]) : x[e];
+        x[e] = xc[e] * rs[e];
+        smallest = fminf(smallest, fabsf(x[e]));
+        // distance of the low 20 significand bits from 0x80000, plus 8, in the top 20 bits
+        nearest = min(nearest, (__float_as_uint(x[e]) + (8u - 0x80000u)) << 12);
+      }
+      if (!regular || smallest < 0x1p-6f || nearest < (17u << 12)) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = sc[e] > 0.0f ? __fdiv_rn(xc[e], sc[e]) : 0.0f;
       }
     } else {
 #pragma unroll
@@ -621,8 +775,12 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
                                                         nstat, Dm.Nk);
   }
-  k_quant_q<BF16, INT4, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.nQb,
-                                                        Dm.block_groups, qm);
+  if constexpr (INT4)
+    k_quant_q4<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.nQb,
+                                                     Dm.block_groups, qm);
+  else
+    k_quant_q<BF16, false, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.nQb,
+                                                           Dm.block_groups, qm);
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
                                                               P.delta_s, Dm.Nk, Dm.nKb, Dm.nQb, Dm.H / Dm.Hkv,
                                                               Dm.kappa, Dm.block_groups, Dm.causal, Dm.coff, km);
