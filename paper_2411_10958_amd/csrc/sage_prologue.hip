@@ -141,7 +141,8 @@ __global__ void k_zero_stats(double* k_sum, double* v_sum, unsigned* v_max, int 
   }
 }
 
-constexpr int STAT_ROWS = 512;  // tokens per workgroup of k_col_stats
+constexpr int STAT_ROWS = 256;  // tokens per workgroup of k_col_stats
+constexpr int STAT_UNROLL = 4; // rows per thread in flight
 
 // With the smooth-V option the first pass takes the exact token sums of V instead of max|V| (the
 // maximum must be taken of the centred values, which needs the mean first: k_v_absmax below).
@@ -162,15 +163,31 @@ __global__ void __launch_bounds__(256) k_col_stats(const unsigned short* __restr
   float mx[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { acc[e] = 0.0; vacc[e] = 0.0; mx[e] = 0.0f; }
-  for (int r = r0 + rg; r < r1; r += NRG) {
-    float xk[8], xv[8];
-    const size_t row = row_offset(km, hbase, r) + cg * 8;
-    load8<BF16>(K + row, xk);
-    load8<BF16>(V + row, xv);
+  // STAT_UNROLL rows of K and of V are requested before the first is consumed: the pass is pure
+  // streaming, and the bytes in flight per CU are what sets its bandwidth (rows past the end read
+  // as zeros, which change neither a sum nor a maximum of magnitudes)
+  for (int r = r0 + rg; r < r1; r += STAT_UNROLL * NRG) {
+    uint4 rk[STAT_UNROLL], rv[STAT_UNROLL];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      acc[e] += (double)xk[e];
-      if constexpr (SMOOTH_V) vacc[e] += (double)xv[e]; else mx[e] = fmaxf(mx[e], fabsf(xv[e]));
+    for (int u = 0; u < STAT_UNROLL; ++u) {
+      const int rr = r + u * NRG;
+      rk[u] = rv[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (rr < r1) {
+        const size_t row = row_offset(km, hbase, rr) + cg * 8;
+        rk[u] = *reinterpret_cast<const uint4*>(K + row);
+        rv[u] = *reinterpret_cast<const uint4*>(V + row);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < STAT_UNROLL; ++u) {
+      float xk[8], xv[8];
+      unpack8<BF16>(rk[u], xk);
+      unpack8<BF16>(rv[u], xv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        acc[e] += (double)xk[e];
+        if constexpr (SMOOTH_V) vacc[e] += (double)xv[e]; else mx[e] = fmaxf(mx[e], fabsf(xv[e]));
+      }
     }
   }
 #pragma unroll
@@ -659,21 +676,11 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
   const size_t bh = blockIdx.y;
   const int n0 = kb * BKV;
   const size_t hbase = head_offset(km, blockIdx.y);
-  // y = fl32(x * r) with r = 1/delta_V to within 1 ulp stands in for the oracle's fl32(x / delta_V):
-  // the two differ by at most 2^-22 |y| (4 units of y's last place), so they round to the same E4M3
-  // code unless y lies within that distance of the midpoint of two codes - for |y| >= 2^-6, where the
-  // codes carry 3 mantissa bits, unless the low 20 bits of y's significand are within 8 of 0x80000.
-  // Rows with such an element, with a |y| below 2^-6 (subnormal codes, fixed spacing) or with a scale
-  // outside [2^-100, 2^100] are recomputed with the exact quotient.
-  float sc[8], mean[8], rs[8];
-  bool regular = true;
+  float sc[8], mean[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     sc[e] = v_scale[bh * D + cg * 8 + e];
     mean[e] = SMOOTH_V ? v_mean[bh * D + cg * 8 + e] : 0.0f;
-    const bool ok = sc[e] >= 0x1p-100f && sc[e] <= 0x1p100f;
-    rs[e] = ok ? __builtin_amdgcn_rcpf(sc[e]) : 0.0f;
-    regular = regular && (ok || sc[e] == 0.0f);     // a zero scale means an all-zero channel: codes 0
   }
 #pragma unroll
   for (int i = 0; i < RPT; ++i) {
@@ -681,19 +688,10 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
     float x[8];
     if (n0 + r < N) {
       load8<BF16>(V + row_offset(km, hbase, n0 + r) + cg * 8, x);
-      float xc[8], smallest = 1.0f;
-      unsigned nearest = 0xffffffffu;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        xc[e] = SMOOTH_V ? __fsub_rn(x[e], mean[e]) : x[e];
-        x[e] = xc[e] * rs[e];
-        smallest = fminf(smallest, fabsf(x[e]));
-        // distance of the low 20 significand bits from 0x80000, plus 8, in the top 20 bits
-        nearest = min(nearest, (__float_as_uint(x[e]) + (8u - 0x80000u)) << 12);
-      }
-      if (!regular || smallest < 0x1p-6f || nearest < (17u << 12)) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = sc[e] > 0.0f ? __fdiv_rn(xc[e], sc[e]) : 0.0f;
+        if constexpr (SMOOTH_V) x[e] = __fsub_rn(x[e], mean[e]);
+        x[e] = sc[e] > 0.0f ? __fdiv_rn(x[e], sc[e]) : 0.0f;
       }
     } else {
 #pragma unroll
