@@ -257,17 +257,15 @@ __global__ void k_finalize_vscale(const unsigned* __restrict__ v_max, float* __r
 }
 
 // ------------------------------------------------------------------------------------------
-// Q: block mean, smoothing (int4 mode), pair-group quantization.  One workgroup per 128
-// queries of one (batch, head)  (Algorithm 1: q_bar_i = mean(Q_i), psi_Q(Q_i - q_bar_i)).
-template <bool BF16, bool INT4, int D>
-__global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restrict__ Q,
-                                                 float* __restrict__ q_mean, float* __restrict__ q_scale,
-                                                 int8_t* __restrict__ q_codes, int N, int nQb,
-                                                 int block_groups, TensorMap qm) {
+// Q, 8-bit variant: pair-group quantization psi_Q(Q_i), no smoothing (the 8-bit kernel of the
+// paper's "two kernel implementations" leaves Q as it is).  One workgroup per 128 queries of one
+// (batch, head).
+template <bool BF16, int D>
+__global__ void __launch_bounds__(256) k_quant_q8(const unsigned short* __restrict__ Q,
+                                                  float* __restrict__ q_scale, int8_t* __restrict__ q_codes,
+                                                  int N, int nQb, int block_groups, TensorMap qm) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;  // RPT rows per thread (8 or 4)
-  constexpr int QMAX = INT4 ? 7 : 127;
-  __shared__ double s_sum[NRG][D];
-  __shared__ float s_mean[D];
+  constexpr int QMAX = 127;
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
   const int qb = blockIdx.x;
   const size_t bh = blockIdx.y;
@@ -283,32 +281,6 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) x[i][e] = 0.0f;
-    }
-  }
-  if constexpr (INT4) {
-    double cs[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      cs[e] = 0.0;
-#pragma unroll
-      for (int i = 0; i < RPT; ++i) cs[e] += (double)x[i][e];   // padded rows are zero
-      s_sum[rg][cg * 8 + e] = cs[e];
-    }
-    __syncthreads();
-    if (t < D) {
-      double s = 0.0;
-      for (int g = 0; g < NRG; ++g) s += s_sum[g][t];
-      const float m = (float)(s / (double)valid);
-      s_mean[t] = m;
-      q_mean[(bh * nQb + qb) * D + t] = m;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < RPT; ++i) {
-      if (rg * RPT + i < valid) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[i][e] = __fsub_rn(x[i][e], s_mean[cg * 8 + e]);
-      }
     }
   }
   // codes go to LDS in the packed order of this 128-query slab (contiguous in the workspace) and
@@ -338,37 +310,23 @@ __global__ void __launch_bounds__(256) k_quant_q(const unsigned short* __restric
     if (block_groups) mx = block_max;
     const float delta = __fdiv_rn(mx, (float)QMAX);
     if (cg == 0) q_scale[(bh * nQb + qb) * (BQ / QGROUP) + (rg * RPT) / 2 + p] = delta;
+    const QuantScale qs = quant_scale<QMAX>(delta);
 #pragma unroll
     for (int i = 2 * p; i < 2 * p + 2; ++i) {
       int c[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) c[e] = quant_code(x[i][e], delta, QMAX);
-      if constexpr (INT4) {
-        // 8 codes = 48 bits = payload bytes 6*(cg%4) .. +5 of the row's lane: three 2-byte stores
-        int c16[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) c16[e] = e < 8 ? c[e] : 0;
-        unsigned w[3];
-        pack6<16>(c16, w);
-        int lane_m, e0;
-        const size_t op = q_op6(rg * RPT + i, cg * 8, D, &lane_m, &e0);
-        const int b0 = 6 * (e0 >> 3);
-        *reinterpret_cast<unsigned short*>(img + op + op6_byte(lane_m, b0)) = (unsigned short)(w[0] & 0xffffu);
-        *reinterpret_cast<unsigned short*>(img + op + op6_byte(lane_m, b0 + 2)) = (unsigned short)(w[0] >> 16);
-        *reinterpret_cast<unsigned short*>(img + op + op6_byte(lane_m, b0 + 4)) = (unsigned short)(w[1] & 0xffffu);
-      } else {
-        *reinterpret_cast<uint2*>(img + q_code_off(rg * RPT + i, cg * 8, D)) = pack8(c);
-      }
+      quant_group<8, QMAX>(x[i], delta, qs, [&](int e, float cf) { c[e] = (int)cf; });
+      *reinterpret_cast<uint2*>(img + q_code_off(rg * RPT + i, cg * 8, D)) = pack8(c);
     }
   }
   __syncthreads();
-  constexpr int SLAB16 = (int)(q_slab_bytes(D, INT4) / 16);
-  uint4* dst = reinterpret_cast<uint4*>(q_codes + (bh * nQb + qb) * q_slab_bytes(D, INT4));
+  constexpr int SLAB16 = (int)(q_slab_bytes(D, false) / 16);
+  uint4* dst = reinterpret_cast<uint4*>(q_codes + (bh * nQb + qb) * q_slab_bytes(D, false));
 #pragma unroll
   for (int i = t; i < SLAB16; i += 256) dst[i] = s_codes[i];
 }
 
-// The 4-bit variant of the same step.  Two thread-to-data maps, joined through LDS:
+// Q, 4-bit variant: block mean, smoothing, pair-group quantization (Algorithm 1: q_bar_i =
+// mean(Q_i), psi_Q(Q_i - q_bar_i)).  Two thread-to-data maps, joined through LDS:
 //  - loading and the exact column sums of the block mean use the coalesced map of k_quant_q (a
 //    thread owns 8 channels of BQ*D/2048 rows), and the raw 16-bit rows are parked in LDS;
 //  - quantization uses the map the codes are consumed in: a thread owns D/4 consecutive channels
@@ -777,8 +735,7 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
     k_quant_q4<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.nQb,
                                                      Dm.block_groups, qm);
   else
-    k_quant_q<BF16, false, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.nQb,
-                                                           Dm.block_groups, qm);
+    k_quant_q8<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_scale, P.q_codes, Dm.N, Dm.nQb, Dm.block_groups, qm);
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
                                                               P.delta_s, Dm.Nk, Dm.nKb, Dm.nQb, Dm.H / Dm.Hkv,
                                                               Dm.kappa, Dm.block_groups, Dm.causal, Dm.coff, km);
