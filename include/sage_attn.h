@@ -15,6 +15,15 @@
  *     head h / (H / H_kv).  N_kv = N unless sage_attn_args.N_kv says otherwise; a causal mask is
  *     aligned to the last query and key (key t visible to query r iff t <= r + N_kv - N) and
  *     needs N_kv >= N.
+ *   - Variable-length batches: with cu_seqlens_q set, the B sequences are packed along the token
+ *     axis, q and out are [total_q, H, d], k and v [total_k, H_kv, d] (layout must be
+ *     SAGE_LAYOUT_NHD), sequence b owns query tokens cu_seqlens_q[b] .. cu_seqlens_q[b+1]-1 and
+ *     key tokens cu_seqlens_k[b] .. cu_seqlens_k[b+1]-1, and N / N_kv are the LONGEST query / key
+ *     length (they size the launch and the workspace; a longer sequence is cut to them).  Every
+ *     sequence is smoothed, quantized and attended on its own, exactly as a batch of one.  The
+ *     prefix sums live on the device and are not checked on the host: under a causal mask a
+ *     sequence with fewer keys than queries is masked as if aligned to the first query and key,
+ *     and a sequence without keys gets zeros.
  *   - d is 64 or 128; mode and dtype take the enum values below; H must be a multiple of H_kv.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream)
  *     and the call returns without synchronising.  Kernels of one call are ordered on that
@@ -38,7 +47,8 @@ extern "C" {
 enum {
   SAGE_OK = 0,
   SAGE_ERR_INVALID_ARG = -1,  /* null pointer, non-positive size, H % H_kv != 0 */
-  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode, dtype, flag, group map or layout, causal with N_kv < N */
+  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode, dtype, flag, group map or layout, causal with N_kv < N,
+                                 cu_seqlens without SAGE_LAYOUT_NHD, sage_attn_quant / sage_attn_debug_qk with cu_seqlens */
   SAGE_ERR_WORKSPACE = -3,    /* workspace missing or smaller than sage_attn_workspace_bytes() */
   SAGE_ERR_HIP = -4           /* a HIP call or launch failed (the HIP error is cleared) */
 };
@@ -87,6 +97,8 @@ typedef struct sage_attn_args {
   void* workspace;        /* device scratch of >= sage_attn_workspace_bytes(); 256-byte aligned */
   size_t workspace_bytes;
   void* stream;           /* hipStream_t, NULL = default stream */
+  const int* cu_seqlens_q; /* device, [B + 1] prefix sums of the query lengths, or NULL: fixed length N */
+  const int* cu_seqlens_k; /* device, [B + 1] prefix sums of the key lengths; NULL = cu_seqlens_q */
 } sage_attn_args;
 
 /* Bytes of device scratch one call needs for these shapes (codes, scales, means, Delta-S).

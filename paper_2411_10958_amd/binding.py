@@ -36,7 +36,8 @@ class sage_attn_args(ctypes.Structure):
                 ("causal", ctypes.c_int), ("sm_scale", ctypes.c_float),
                 ("mode", ctypes.c_int), ("dtype", ctypes.c_int), ("flags", ctypes.c_int), ("group_map", ctypes.c_int), ("N_kv", ctypes.c_int), ("layout", ctypes.c_int),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
-                ("stream", ctypes.c_void_p)]
+                ("stream", ctypes.c_void_p),
+                ("cu_seqlens_q", ctypes.c_void_p), ("cu_seqlens_k", ctypes.c_void_p)]
 
 
 class sage_quant_out(ctypes.Structure):
@@ -148,17 +149,53 @@ def _alloc_workspace(args, device):
 
 
 def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
-                     smooth_v=False, group_map="lane", layout="HND"):
-    """Whole forward pass.  Returns `out` (allocated if not given)."""
+                     smooth_v=False, group_map="lane", layout="HND", cu_seqlens_q=None, cu_seqlens_k=None,
+                     max_seqlen_q=None, max_seqlen_k=None):
+    """Whole forward pass.  Returns `out` (allocated if not given).  With cu_seqlens_q the batch is a packed
+    variable-length one (see make_varlen_args) and `layout` is ignored."""
     if out is None:
         out = torch.empty_like(q)
-    a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v, group_map, layout)
+    if cu_seqlens_q is not None:
+        a = make_varlen_args(q, k, v, out, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, max_seqlen_k, causal=causal,
+                             sm_scale=sm_scale, mode=mode, workspace=workspace, stream=stream, smooth_v=smooth_v,
+                             group_map=group_map)
+    else:
+        a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v, group_map, layout)
     keep = _alloc_workspace(a, q.device) if workspace is None else workspace
     if workspace is None and stream is not None:
         keep.record_stream(stream)   # allocated on the current stream, used on another one
     _check(load_library().sage_attn_fwd_ex(ctypes.byref(a)), "sage_attn_fwd_ex")
     del keep  # torch's caching allocator keeps the block alive for work already queued on its streams
     return out
+
+
+def make_varlen_args(q, k, v, out, cu_seqlens_q, cu_seqlens_k=None, max_seqlen_q=None, max_seqlen_k=None, **kw):
+    """sage_attn_args of a packed variable-length batch: q / out [total_q, H, d], k / v [total_k, H_kv, d],
+    cu_seqlens_* int32 GPU tensors [B + 1] (cu_seqlens_k None = the query one), max_seqlen_* the longest
+    sequence (taken from the prefix sums, with a device-to-host copy, when not given).  **kw as make_args."""
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        if not t.is_cuda or not t.is_contiguous() or t.dim() != 3:
+            raise ValueError(f"{name} must be a contiguous 3-D GPU tensor")
+    for name, t in (("cu_seqlens_q", cu_seqlens_q), ("cu_seqlens_k", cu_seqlens_k)):
+        if t is not None and (not t.is_cuda or t.dtype != torch.int32 or t.dim() != 1 or not t.is_contiguous()):
+            raise ValueError(f"{name} must be a contiguous 1-D int32 GPU tensor")
+    if cu_seqlens_k is not None and cu_seqlens_k.numel() != cu_seqlens_q.numel():
+        raise ValueError("cu_seqlens_q and cu_seqlens_k must have the same length")
+    B = cu_seqlens_q.numel() - 1
+    if B < 1:
+        raise ValueError("cu_seqlens_q must hold at least two entries")
+    if max_seqlen_q is None:
+        max_seqlen_q = int((cu_seqlens_q[1:] - cu_seqlens_q[:-1]).max().item())
+    if max_seqlen_k is None:
+        ck = cu_seqlens_k if cu_seqlens_k is not None else cu_seqlens_q
+        max_seqlen_k = int((ck[1:] - ck[:-1]).max().item())
+    # the struct is filled through [1, tokens, heads, d] views; B, N, N_kv are then set for the packed batch
+    a = make_args(q.unsqueeze(0), k.unsqueeze(0), v.unsqueeze(0), None if out is None else out.unsqueeze(0),
+                  layout="NHD", **kw)
+    a.B, a.N, a.N_kv = B, max(int(max_seqlen_q), 1), max(int(max_seqlen_k), 1)
+    a.cu_seqlens_q = cu_seqlens_q.data_ptr()
+    a.cu_seqlens_k = cu_seqlens_k.data_ptr() if cu_seqlens_k is not None else 0
+    return a
 
 
 def sage_attn_prologue(args):

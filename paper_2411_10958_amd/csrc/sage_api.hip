@@ -21,6 +21,8 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if ((a->flags & ~SAGE_FLAG_SMOOTH_V) != 0) return SAGE_ERR_UNSUPPORTED;
   if (a->group_map != SAGE_GROUPS_LANE && a->group_map != SAGE_GROUPS_BLOCK) return SAGE_ERR_UNSUPPORTED;
   if (a->layout != SAGE_LAYOUT_HND && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
+  if (a->cu_seqlens_k && !a->cu_seqlens_q) return SAGE_ERR_INVALID_ARG;
+  if (a->cu_seqlens_q && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
   if (need_io && (!a->q || !a->k || !a->v || !a->out)) return SAGE_ERR_INVALID_ARG;
   // grid limits of the launches below (y dimension <= 65535, tile count fits an int)
   if ((long long)a->B * a->H > 65535) return SAGE_ERR_UNSUPPORTED;
@@ -35,6 +37,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   D->smooth_v = (a->flags & SAGE_FLAG_SMOOTH_V) != 0;
   D->block_groups = a->group_map == SAGE_GROUPS_BLOCK;
   D->nhd = a->layout == SAGE_LAYOUT_NHD;
+  D->seq.cu_q = a->cu_seqlens_q; D->seq.cu_k = a->cu_seqlens_k;
   const float sm = a->sm_scale > 0.0f ? a->sm_scale : (float)(1.0 / std::sqrt((double)a->d));
   D->kappa = sm * LOG2E;   // one FP32 rounding of the product of two FP32 values
   return SAGE_OK;
@@ -97,6 +100,7 @@ int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B,
   a.q = q; a.k = k; a.v = v; a.out = out;
   a.B = B; a.H = H; a.H_kv = H; a.N = N; a.d = d;
   a.causal = causal; a.sm_scale = sm_scale; a.mode = mode; a.dtype = SAGE_DT_BF16; a.flags = 0; a.group_map = SAGE_GROUPS_LANE; a.N_kv = 0; a.layout = SAGE_LAYOUT_HND;
+  a.cu_seqlens_q = nullptr; a.cu_seqlens_k = nullptr;
   a.workspace = nullptr; a.workspace_bytes = 0; a.stream = nullptr;
   const size_t need = sage_attn_workspace_bytes(&a);
   if (need == 0) {
@@ -130,6 +134,7 @@ int sage_attn_quant(const sage_attn_args* args, const sage_quant_out* out) {
   int st = validate(args, &D, false);
   if (st != SAGE_OK) return st;
   if (!args->q || !args->k || !args->v) return SAGE_ERR_INVALID_ARG;
+  if (args->cu_seqlens_q) return SAGE_ERR_UNSUPPORTED;   // the plain copy-out layouts are fixed-length
   if ((long long)D.B * D.H * D.nQb > 65535) return SAGE_ERR_UNSUPPORTED;  // grid limit of the copy-out kernels
   const Workspace w = make_workspace(D);
   if ((st = check_workspace(args, w)) != SAGE_OK) return st;
@@ -143,6 +148,7 @@ int sage_attn_debug_qk(const sage_attn_args* args, int b, int h, int q_tile, int
   Dims D;
   int st = validate(args, &D, false);
   if (st != SAGE_OK) return st;
+  if (args->cu_seqlens_q) return SAGE_ERR_UNSUPPORTED;
   if (!out_acc || b < 0 || b >= D.B || h < 0 || h >= D.H || q_tile < 0 || q_tile >= D.nQb ||
       kv_block < 0 || kv_block >= D.nKb)
     return SAGE_ERR_INVALID_ARG;

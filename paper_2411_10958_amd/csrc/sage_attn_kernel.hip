@@ -28,6 +28,7 @@ struct AttnParams {
   int H, Hkv, N, Nk, coff, nQb, nKb, total_tiles;   // N queries, Nk keys; causal: key t <= query + coff
   TensorMap om;           // where the rows of `out` start
   float kappa;
+  SeqMap seq;             // variable-length batch: N, Nk, nQb, nKb describe the longest sequence
 };
 
 // Score accumulators of one wavefront for one 64-key block: 2 key tiles x (32 keys x 32
@@ -255,8 +256,22 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   const int qb = CAUSAL ? p.nQb - 1 - tile % p.nQb : tile % p.nQb;   // heavy tiles first
   const int b = bh / p.H, h = bh % p.H;
   const size_t bhkv = (size_t)b * p.Hkv + h / (p.H / p.Hkv);
+  // this sequence's lengths (the launch's N, Nk unless the batch is a variable-length one; slab
+  // strides below keep the block counts of the longest sequence)
+  const Seq sq = seq_of(p.seq, (unsigned)b, p.N, p.Nk);
+  if (qb * BQ >= sq.n) return;                 // a tile past the end of a shorter sequence
 
   const int t = threadIdx.x, lane = t & 63;
+  if (sq.nk == 0) {                            // no keys at all: the rows are defined as zeros
+    unsigned short* o = reinterpret_cast<unsigned short*>(p.out) + head_offset(p.om, (unsigned)bh);
+    for (int idx = t; idx < BQ * (D / 8); idx += 256) {
+      const int row = qb * BQ + idx / (D / 8);
+      if (row < sq.n)
+        *reinterpret_cast<uint4*>(o + row_offset(p.om, 0, (int)sq.q0 + row) + (idx % (D / 8)) * 8) =
+            make_uint4(0u, 0u, 0u, 0u);
+    }
+    return;
+  }
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int n = lane & 31, half = lane >> 5;
   const int q_lo = qb * BQ + w * WQ;          // first query of this wavefront
@@ -267,8 +282,8 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   const float* gd = INT4 ? p.delta_s + ((size_t)bh * p.nQb + qb) * p.nKb * BKV : nullptr;
   const float* gs = p.k_scale + bhkv * (size_t)p.nKb * 4;
 
-  int nblk = p.nKb;
-  if (CAUSAL) nblk = min(nblk, (qb * BQ + BQ - 1 + p.coff) / BKV + 1);
+  int nblk = (sq.nk + BKV - 1) / BKV;
+  if (CAUSAL) nblk = min(nblk, (qb * BQ + BQ - 1 + sq.coff) / BKV + 1);
 
   // Block copies: every wavefront moves its quarter of the K^ and V^ chunks (the copy is the
   // identity on chunk indices), wavefront 0 the block's Delta-S row, wavefront 1 the 4 scales.
@@ -324,11 +339,11 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   // The wavefront walks all nblk blocks of the workgroup (copies and barriers are shared):
   // blocks [0, n_act) hold keys visible to some of its queries, of which [0, n_plain) need no
   // mask; past n_act (causal only) it just helps with the copies.
-  int n_plain = min(nblk, p.Nk / BKV);                         // blocks without padded keys
+  int n_plain = min(nblk, sq.nk / BKV);                        // blocks without padded keys
   int n_act = nblk;                                            // blocks with any visible key
   if (CAUSAL) {
-    n_plain = min(n_plain, (q_lo + p.coff + 1) / BKV);         // key0 + 63 <= q_lo + coff
-    n_act = min(nblk, (q_lo + p.coff + WQ - 1) / BKV + 1);     // key0 <= q_lo + 31 + coff
+    n_plain = min(n_plain, (q_lo + sq.coff + 1) / BKV);        // key0 + 63 <= q_lo + coff
+    n_act = min(nblk, (q_lo + sq.coff + WQ - 1) / BKV + 1);    // key0 <= q_lo + 31 + coff
   }
   n_plain = __builtin_amdgcn_readfirstlane(n_plain);
   n_act = __builtin_amdgcn_readfirstlane(n_act);
@@ -396,7 +411,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
 
 #define SAGE_DEQ(MASKED_, GI_, KEY0_)                                                                \
   dequant_group<INT4, CAUSAL, MASKED_, (GI_) / 4, (GI_) % 4>(raw, sc, dsr, (GI_) / 4 == 0 ? c0 : c1, half, \
-                                                             KEY0_, query + p.coff, p.Nk)
+                                                             KEY0_, query + sq.coff, sq.nk)
 #define SAGE_DEQ_ALL(MASKED_, KEY0_)                                                                 \
   do {                                                                                               \
     SAGE_DEQ(MASKED_, 0, KEY0_); SAGE_DEQ(MASKED_, 1, KEY0_); SAGE_DEQ(MASKED_, 2, KEY0_);           \
@@ -481,8 +496,9 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
     l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
   }
-  if (query < p.N) {
-    unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) + row_offset(p.om, head_offset(p.om, (unsigned)bh), query);
+  if (query < sq.n) {
+    unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) +
+                           row_offset(p.om, head_offset(p.om, (unsigned)bh), (int)sq.q0 + query);
     const float* dv = p.v_scale + bhkv * D;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
@@ -555,7 +571,8 @@ static hipError_t launch_attention_t(const Dims& Dm, const Ptrs& P, hipStream_t 
   p.v_mean = Dm.smooth_v ? P.v_mean : nullptr;
   p.out = P.out;
   p.H = Dm.H; p.Hkv = Dm.Hkv; p.N = Dm.N; p.Nk = Dm.Nk; p.coff = Dm.coff; p.nQb = Dm.nQb;
-  p.om = make_tensor_map(Dm.nhd, Dm.H, Dm.N, Dm.d); p.nKb = Dm.nKb;
+  p.om = make_tensor_map(Dm.nhd, Dm.H, Dm.N, Dm.d, Dm.seq.cu_q != nullptr); p.nKb = Dm.nKb;
+  p.seq = Dm.seq;
   p.total_tiles = Dm.B * Dm.H * Dm.nQb;
   p.kappa = Dm.kappa;
   const int grid = 8 * ((p.total_tiles + 7) / 8);

@@ -34,12 +34,41 @@ __host__ __device__ inline size_t head_offset(const TensorMap& m, unsigned bh) {
   const unsigned b = bh / (unsigned)m.heads, h = bh - b * (unsigned)m.heads;
   return b * (size_t)m.sb + h * (size_t)m.sh;
 }
+
+// Variable-length batches: prefix sums of the sequence lengths (device pointers; both null for a
+// fixed-length batch).  seq_of() gives sequence b's lengths, cut to the launch's maxima so that no
+// index derived from them can leave the workspace slabs, its first tokens, and the causal offset
+// (never negative: a sequence with fewer keys than queries is masked from the first query and key).
+struct SeqMap { const int* cu_q; const int* cu_k; };
+struct Seq { int n, nk, coff; size_t q0, k0; };
+__device__ inline Seq seq_of(const SeqMap& sm, unsigned b, int N, int Nk) {
+  Seq s;
+  s.n = N; s.nk = Nk; s.q0 = 0; s.k0 = 0;
+  if (sm.cu_q) {
+    const int* ck = sm.cu_k ? sm.cu_k : sm.cu_q;
+    const int q0 = sm.cu_q[b], q1 = sm.cu_q[b + 1], k0 = ck[b], k1 = ck[b + 1];
+    s.n = min(max(q1 - q0, 0), N);
+    s.nk = min(max(k1 - k0, 0), Nk);
+    s.q0 = (size_t)max(q0, 0);
+    s.k0 = (size_t)max(k0, 0);
+  }
+  s.coff = max(s.nk - s.n, 0);
+  return s;
+}
+struct HeadPos { unsigned b; size_t base; };   // batch index and element offset of a head
+__host__ __device__ inline HeadPos head_pos(const TensorMap& m, unsigned bh) {
+  HeadPos p;
+  p.b = bh / (unsigned)m.heads;
+  p.base = p.b * (size_t)m.sb + (bh - p.b * (unsigned)m.heads) * (size_t)m.sh;
+  return p;
+}
 __host__ __device__ inline size_t row_offset(const TensorMap& m, size_t head_base, int n) {
   return head_base + (size_t)n * (size_t)m.sn;
 }
-inline TensorMap make_tensor_map(int nhd, int heads, int tokens, int d) {
+inline TensorMap make_tensor_map(int nhd, int heads, int tokens, int d, bool varlen = false) {
   TensorMap m;
   m.heads = heads;
+  if (varlen) { m.sb = 0; m.sh = d; m.sn = (long long)heads * d; return m; }   // packed [tokens, heads, d]
   if (nhd) { m.sb = (long long)tokens * heads * d; m.sh = d; m.sn = (long long)heads * d; }
   else     { m.sb = (long long)heads * tokens * d; m.sh = (long long)tokens * d; m.sn = d; }
   return m;
@@ -53,6 +82,7 @@ struct Dims {
   int nKb;     // ceil(Nk / 64) key blocks
   int causal, int4, bf16, smooth_v, block_groups, nhd;
   float kappa; // fl32(sm_scale * log2 e)
+  SeqMap seq;  // variable-length batch: N, Nk, nQb, nKb then describe the longest sequence
 };
 
 // Workspace map (all offsets multiples of 256 bytes).

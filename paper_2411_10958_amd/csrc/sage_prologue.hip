@@ -150,15 +150,18 @@ template <bool BF16, int D, bool SMOOTH_V>
 __global__ void __launch_bounds__(256) k_col_stats(const unsigned short* __restrict__ K,
                                                    const unsigned short* __restrict__ V,
                                                    double* __restrict__ k_sum, double* __restrict__ v_sum,
-                                                   unsigned* __restrict__ v_max, int N, TensorMap km) {
+                                                   unsigned* __restrict__ v_max, int Nq, int N, TensorMap km,
+                                                   SeqMap sm) {
   constexpr int NCG = D / 8, NRG = 256 / NCG;
   __shared__ double s_sum[NRG][D];
   __shared__ double s_vsum[SMOOTH_V ? NRG : 1][D];
   __shared__ float s_max[SMOOTH_V ? 1 : NRG][D];
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
+  const HeadPos hp = head_pos(km, blockIdx.y);
+  const Seq sq = seq_of(sm, hp.b, Nq, N);
   const int r0 = blockIdx.x * STAT_ROWS;
-  const int r1 = min(r0 + STAT_ROWS, N);
-  const size_t hbase = head_offset(km, blockIdx.y);
+  const int r1 = min(r0 + STAT_ROWS, sq.nk);
+  const size_t hbase = hp.base + sq.k0 * (size_t)km.sn;
   double acc[8], vacc[8];
   float mx[8];
 #pragma unroll
@@ -213,13 +216,16 @@ __global__ void __launch_bounds__(256) k_col_stats(const unsigned short* __restr
 template <bool BF16, int D>
 __global__ void __launch_bounds__(256) k_v_absmax(const unsigned short* __restrict__ V,
                                                   const float* __restrict__ v_mean,
-                                                  unsigned* __restrict__ v_max, int N, TensorMap km) {
+                                                  unsigned* __restrict__ v_max, int Nq, int N, TensorMap km,
+                                                  SeqMap sm) {
   constexpr int NCG = D / 8, NRG = 256 / NCG;
   __shared__ float s_max[NRG][D];
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
+  const HeadPos hp = head_pos(km, blockIdx.y);
+  const Seq sq = seq_of(sm, hp.b, Nq, N);
   const int r0 = blockIdx.x * STAT_ROWS;
-  const int r1 = min(r0 + STAT_ROWS, N);
-  const size_t hbase = head_offset(km, blockIdx.y);
+  const int r1 = min(r0 + STAT_ROWS, sq.nk);
+  const size_t hbase = hp.base + sq.k0 * (size_t)km.sn;
   float mean[8], mx[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { mean[e] = v_mean[(size_t)blockIdx.y * D + cg * 8 + e]; mx[e] = 0.0f; }
@@ -243,11 +249,13 @@ __global__ void __launch_bounds__(256) k_v_absmax(const unsigned short* __restri
 // this call produces v_mean = fl32(sum / N) instead of delta_V, which k_finalize_vscale adds later.
 __global__ void k_finalize_stats(const double* __restrict__ k_sum, const double* __restrict__ v_sum,
                                  const unsigned* __restrict__ v_max, float* __restrict__ k_mean,
-                                 float* __restrict__ v_mean, float* __restrict__ v_scale, int n, int N) {
+                                 float* __restrict__ v_mean, float* __restrict__ v_scale, int n, int Nq, int N,
+                                 int d, int Hkv, SeqMap sm) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) {
-    k_mean[i] = (float)(k_sum[i] / (double)N);
-    if (v_sum) v_mean[i] = (float)(v_sum[i] / (double)N);
+    const int nk = seq_of(sm, (unsigned)(i / d / Hkv), Nq, N).nk;      // this sequence's key count
+    k_mean[i] = nk > 0 ? (float)(k_sum[i] / (double)nk) : 0.0f;
+    if (v_sum) v_mean[i] = nk > 0 ? (float)(v_sum[i] / (double)nk) : 0.0f;
     else v_scale[i] = __fdiv_rn(__uint_as_float(v_max[i]), E4M3_MAX);
   }
 }
@@ -263,15 +271,19 @@ __global__ void k_finalize_vscale(const unsigned* __restrict__ v_max, float* __r
 template <bool BF16, int D>
 __global__ void __launch_bounds__(256) k_quant_q8(const unsigned short* __restrict__ Q,
                                                   float* __restrict__ q_scale, int8_t* __restrict__ q_codes,
-                                                  int N, int nQb, int block_groups, TensorMap qm) {
+                                                  int N, int Nk, int nQb, int block_groups, TensorMap qm,
+                                                  SeqMap sm) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;  // RPT rows per thread (8 or 4)
   constexpr int QMAX = 127;
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
   const int qb = blockIdx.x;
   const size_t bh = blockIdx.y;
   const int n0 = qb * BQ;
-  const int valid = min(BQ, N - n0);
-  const size_t hbase = head_offset(qm, blockIdx.y);
+  const HeadPos hp = head_pos(qm, blockIdx.y);
+  const Seq sq = seq_of(sm, hp.b, N, Nk);
+  const int valid = min(BQ, sq.n - n0);
+  if (valid <= 0) return;                     // a block past the end of a shorter sequence
+  const size_t hbase = hp.base + sq.q0 * (size_t)qm.sn;
   float x[RPT][8];
 #pragma unroll
   for (int i = 0; i < RPT; ++i) {
@@ -338,8 +350,8 @@ __global__ void __launch_bounds__(256) k_quant_q8(const unsigned short* __restri
 template <bool BF16, int D>
 __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restrict__ Q,
                                                   float* __restrict__ q_mean, float* __restrict__ q_scale,
-                                                  int8_t* __restrict__ q_codes, int N, int nQb,
-                                                  int block_groups, TensorMap qm) {
+                                                  int8_t* __restrict__ q_codes, int N, int Nk, int nQb,
+                                                  int block_groups, TensorMap qm, SeqMap sm) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;   // load map: RPT rows x 8 channels
   constexpr int CPL = D / 4, CPC = CPL / 8;                      // quantization map: 2 rows x CPL channels
   constexpr int QMAX = 7;
@@ -353,8 +365,11 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
   const int qb = blockIdx.x;
   const size_t bh = blockIdx.y;
   const int n0 = qb * BQ;
-  const int valid = min(BQ, N - n0);
-  const size_t hbase = head_offset(qm, blockIdx.y);
+  const HeadPos hp = head_pos(qm, blockIdx.y);
+  const Seq sq = seq_of(sm, hp.b, N, Nk);
+  const int valid = min(BQ, sq.n - n0);
+  if (valid <= 0) return;                     // a block past the end of a shorter sequence
+  const size_t hbase = hp.base + sq.q0 * (size_t)qm.sn;
   auto swz = [](int r) { return (r >> 1) & (D == 128 ? 3 : 1); };
   {
     const int cg = t % NCG, rg = t / NCG;
@@ -473,9 +488,9 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
                                                  const float* __restrict__ k_mean,
                                                  float* __restrict__ k_scale, int8_t* __restrict__ k_codes,
                                                  const float* __restrict__ q_mean,
-                                                 float* __restrict__ delta_s, int N, int nKb, int nQb,
-                                                 int G, float kappa, int block_groups, int causal,
-                                                 int coff, TensorMap km) {
+                                                 float* __restrict__ delta_s, int Nq, int Nmax, int nKb,
+                                                 int nQb, int G, float kappa, int block_groups, int causal,
+                                                 TensorMap km, SeqMap sm) {
   constexpr int CPL = D / 4;                       // channels per lane (32 or 16)
   constexpr int QMAX = INT4 ? 7 : 127;
   // LDS row of staged block means: channel c sits at column c + 16*(c / 32) when D = 128, so the
@@ -489,11 +504,18 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
   const size_t bhkv = blockIdx.y;
   const int n0 = kb * BKV;
   const int r = 16 * w + r16, c0 = CPL * k4;
+  // this sequence's key count N, query-block count nQs and causal offset (the slabs keep the
+  // strides nQb, nKb of the longest sequence)
+  const HeadPos hp = head_pos(km, blockIdx.y);
+  const Seq sq = seq_of(sm, hp.b, Nq, Nmax);
+  const int N = sq.nk, coff = sq.coff;
+  const int nQs = (sq.n + BQ - 1) / BQ;
+  if (n0 >= N) return;                             // a block past the end of a shorter sequence
 
   // Delta-S passes: (query head of the group, 32 query blocks); the first pass's block means are
   // requested before the K rows so that both round trips overlap
   constexpr int QPT = DS_QROWS * (D / 4) / 256;    // float4 pieces per thread per pass
-  const int npass_h = (nQb + DS_QROWS - 1) / DS_QROWS;
+  const int npass_h = max((nQs + DS_QROWS - 1) / DS_QROWS, 1);
   const int npass = INT4 ? G * npass_h : 0;
   // under a causal mask (query r sees keys t <= r + coff) query block i sees this key block only
   // if 128 i + 127 + coff >= its first key: the passes of a head start with the one that holds
@@ -507,7 +529,7 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
 #pragma unroll
     for (int k = 0; k < QPT; ++k) {
       const int idx = t + k * 256, rr = idx / (D / 4), c4 = idx % (D / 4);
-      qpre[k] = (i0 + rr < nQb) ? *reinterpret_cast<const float4*>(q_mean + (bh * nQb + i0 + rr) * D + 4 * c4)
+      qpre[k] = (i0 + rr < nQs) ? *reinterpret_cast<const float4*>(q_mean + (bh * nQb + i0 + rr) * D + 4 * c4)
                                 : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   };
@@ -524,7 +546,7 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
 
   float x[CPL];
   float mx = 0.0f;
-  const size_t hbase = head_offset(km, blockIdx.y);
+  const size_t hbase = hp.base + sq.k0 * (size_t)km.sn;
   if (n0 + r < N) {
 #pragma unroll
     for (int p = 0; p < CPL / 8; ++p) {
@@ -611,8 +633,8 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
       for (int v = 0; v < 4; ++v) {
         const int i = i0 + 4 * v + k4;
         float* out = delta_s + (bh * nQb + i) * (size_t)nKb * BKV + n0 + r;
-        if (i < nQb) out[0] = (float)(kap * acc0[v]);
-        if (i + 16 < nQb) out[(size_t)16 * nKb * BKV] = (float)(kap * acc1[v]);
+        if (i < nQs) out[0] = (float)(kap * acc0[v]);
+        if (i + 16 < nQs) out[(size_t)16 * nKb * BKV] = (float)(kap * acc1[v]);
       }
     }
   }
@@ -626,14 +648,19 @@ template <bool BF16, int D, bool SMOOTH_V>
 __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restrict__ V,
                                                  const float* __restrict__ v_scale,
                                                  const float* __restrict__ v_mean,
-                                                 uint8_t* __restrict__ v_codes, int N, int nKb, TensorMap km) {
+                                                 uint8_t* __restrict__ v_codes, int Nq, int Nmax, int nKb,
+                                                 TensorMap km, SeqMap sm) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BKV / NRG;
   __shared__ uint8_t tile[BKV][D + 16];
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
   const int kb = blockIdx.x;
   const size_t bh = blockIdx.y;
   const int n0 = kb * BKV;
-  const size_t hbase = head_offset(km, blockIdx.y);
+  const HeadPos hp = head_pos(km, blockIdx.y);
+  const Seq sq = seq_of(sm, hp.b, Nq, Nmax);
+  const int N = sq.nk;
+  if (n0 >= N) return;                             // a block past the end of a shorter sequence
+  const size_t hbase = hp.base + sq.k0 * (size_t)km.sn;
   float sc[8], mean[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -717,30 +744,37 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
   const unsigned short* v = (const unsigned short*)P.v;
   const int nstat = BHkv * Dm.d;
   const dim3 gstat((Dm.Nk + STAT_ROWS - 1) / STAT_ROWS, BHkv);
-  const TensorMap qm = make_tensor_map(Dm.nhd, Dm.H, Dm.N, Dm.d), km = make_tensor_map(Dm.nhd, Dm.Hkv, Dm.Nk, Dm.d);
+  const bool varlen = Dm.seq.cu_q != nullptr;
+  const TensorMap qm = make_tensor_map(Dm.nhd, Dm.H, Dm.N, Dm.d, varlen),
+                  km = make_tensor_map(Dm.nhd, Dm.Hkv, Dm.Nk, Dm.d, varlen);
+  const SeqMap sm = Dm.seq;
   const float* v_mean = Dm.smooth_v ? P.v_mean : nullptr;
   k_zero_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, Dm.smooth_v ? P.v_sum : nullptr, P.v_max, nstat);
   if (Dm.smooth_v) {
-    k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.Nk, km);
+    k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.N, Dm.Nk, km, sm);
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
-                                                        nstat, Dm.Nk);
-    k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.Nk, km);
+                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, sm);
+    k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.N, Dm.Nk, km, sm);
     k_finalize_vscale<<<(nstat + 255) / 256, 256, 0, s>>>(P.v_max, P.v_scale, nstat);
   } else {
-    k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.Nk, km);
+    k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.N, Dm.Nk, km, sm);
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
-                                                        nstat, Dm.Nk);
+                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, sm);
   }
   if constexpr (INT4)
-    k_quant_q4<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.nQb,
-                                                     Dm.block_groups, qm);
+    k_quant_q4<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
+                                                     Dm.block_groups, qm, sm);
   else
-    k_quant_q8<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_scale, P.q_codes, Dm.N, Dm.nQb, Dm.block_groups, qm);
+    k_quant_q8<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
+                                                     Dm.block_groups, qm, sm);
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
-                                                              P.delta_s, Dm.Nk, Dm.nKb, Dm.nQb, Dm.H / Dm.Hkv,
-                                                              Dm.kappa, Dm.block_groups, Dm.causal, Dm.coff, km);
-  if (Dm.smooth_v) k_quant_v<BF16, D, true><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.Nk, Dm.nKb, km);
-  else k_quant_v<BF16, D, false><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.Nk, Dm.nKb, km);
+                                                              P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
+                                                              Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.causal,
+                                                              km, sm);
+  if (Dm.smooth_v)
+    k_quant_v<BF16, D, true><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
+  else
+    k_quant_v<BF16, D, false><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
   return hipGetLastError();
 }
 

@@ -77,6 +77,12 @@ def test_argument_errors_are_found_on_the_host():
     for kw in [dict(N=0), dict(B=-1), dict(H_kv=5)]:
         a = _args(pa, **kw)
         assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -1, kw
+    a = _args(pa, cu_seqlens_q=4096)   # a packed variable-length batch needs the token-major layout
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -2
+    a = _args(pa, cu_seqlens_k=4096)   # key prefix sums without query prefix sums
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -1
+    a = _args(pa, cu_seqlens_q=4096, layout=1)
+    assert pa.sage_attn_workspace_bytes(a) == pa.sage_attn_workspace_bytes(_args(pa, layout=1))
     a = _args(pa)                      # valid shapes but null tensors
     assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -1
     a.q = a.k = a.v = a.out = 4096     # non-null, but no workspace: rejected before any launch

@@ -277,6 +277,65 @@ def test_nhd_layout_equals_hnd(N, Nk, d, H, Hkv, causal, mode):
     assert torch.equal(out.permute(0, 2, 1, 3), ref)
 
 
+# ---- packed variable-length batches ---------------------------------------------------------------
+def _packed_batch(lens_q, lens_k, d, dtype, H, Hkv, causal):
+    """Sequences of the given lengths, each drawn like a one-sequence workload, packed along the token
+    axis: q [total_q, H, d], k / v [total_k, H_kv, d] on the GPU, plus the per-sequence numpy arrays."""
+    seqs, qs, ks, vs = [], [], [], []
+    for i, (n, nk) in enumerate(zip(lens_q, lens_k)):
+        spec = _spec(max(n, 1), d, dtype, H, Hkv, causal=causal, cfg=120 + i).with_(N_kv=max(nk, 1))
+        data = wl.make_inputs(spec, seed=i)
+        qn, kn, vn = data["q"][0][:, :n], data["k"][0][:, :nk], data["v"][0][:, :nk]     # [heads, tokens, d]
+        seqs.append((qn, kn, vn))
+        qs.append(qn.transpose(1, 0, 2)); ks.append(kn.transpose(1, 0, 2)); vs.append(vn.transpose(1, 0, 2))
+    dev = torch.device("cuda:0")
+    pack = lambda parts: wl.to_torch(np.ascontiguousarray(np.concatenate(parts, axis=0)), dtype, dev)
+    cu = lambda lens: torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev)
+    return seqs, pack(qs), pack(ks), pack(vs), cu(lens_q), cu(lens_k)
+
+
+VARLEN_CASES = [
+    # lens_q, lens_k, d, dtype, H, Hkv, causal
+    ([200, 1, 333, 128], [200, 1, 333, 128], 128, "bf16", 4, 2, True),      # self attention, ragged, grouped KV heads
+    ([200, 1, 333, 128], [260, 5, 333, 640], 64, "fp16", 2, 2, True),       # more keys than queries per sequence
+    ([70, 300, 0, 129], [500, 64, 40, 1], 128, "bf16", 2, 1, False),        # cross lengths, a sequence without queries
+    ([50, 120], [0, 90], 64, "bf16", 2, 2, False),                          # a sequence without keys: zeros
+]
+
+
+@pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("lens_q,lens_k,d,dtype,H,Hkv,causal", VARLEN_CASES)
+def test_varlen_batch_equals_one_sequence_at_a_time(lens_q, lens_k, d, dtype, H, Hkv, causal, mode):
+    """Every sequence of a packed batch must come out exactly as when it is passed alone (same kernels,
+    same arithmetic: bit-identical), and one of them is checked against the oracle."""
+    pa = _pa()
+    seqs, q, k, v, cu_q, cu_k = _packed_batch(lens_q, lens_k, d, dtype, H, Hkv, causal)
+    print(f"varlen case q={lens_q} k={lens_k} d={d} {dtype} H={H}/{Hkv} causal={causal} mode={mode}", flush=True)
+    same = lens_q == lens_k
+    out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, cu_seqlens_q=cu_q, cu_seqlens_k=None if same else cu_k)
+    torch.cuda.synchronize()
+    assert out.shape == q.shape
+    oq, ok = np.concatenate([[0], np.cumsum(lens_q)]), np.concatenate([[0], np.cumsum(lens_k)])
+    checked = False
+    for b, (n, nk) in enumerate(zip(lens_q, lens_k)):
+        part = out[oq[b]:oq[b + 1]]
+        if n == 0:
+            continue
+        if nk == 0:
+            assert torch.count_nonzero(part) == 0
+            continue
+        alone = pa.sage_attn_fwd_ex(q[oq[b]:oq[b + 1]].unsqueeze(0).contiguous(), k[ok[b]:ok[b + 1]].unsqueeze(0).contiguous(),
+                                    v[ok[b]:ok[b + 1]].unsqueeze(0).contiguous(), causal=causal, mode=mode, layout="NHD")
+        torch.cuda.synchronize()
+        assert torch.equal(alone[0], part), f"sequence {b}"
+        if not checked and n >= 100:
+            qn, kn, vn = seqs[b]
+            ref = so.sage_attention(qn[None], kn[None], vn[None], causal=causal, mode=mode, out_dtype="fp32")
+            check_output(wl.from_torch(part).transpose(1, 0, 2), ref[0], dtype)
+            checked = True
+    assert checked
+
+
 def test_plain_signature_and_repeatability():
     pa = _pa()
     spec = _spec(384, 128, "bf16", 2, 2)
