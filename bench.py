@@ -53,8 +53,9 @@ def main():
     ap.add_argument("--workload", default="prefill4k")
     ap.add_argument("--mode", default="int4_fp8", choices=["int4_fp8", "int8_fp8"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--group-map", default="lane", choices=["lane", "block"],
-                    help="quantization granularity of Q and K: the default lane groups or one scale per block")
+    ap.add_argument("--group-map", default="lane", choices=["lane", "block", "fine", "token"],
+                    help="quantization granularity of Q and K: the default lane groups, one scale per block, "
+                         "per query and 4 keys, or per token")
     ap.add_argument("--smooth-v", action="store_true",
                     help="the optional smooth-V technique (one more pass over V in the prologue)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -134,8 +135,9 @@ def main():
         per_row = [min(spec.N, (i * 128 + 128 + 63) // 64 * 64) if spec.causal else spec.N for i in range(nqb)]
         ds_bytes = 4 * BH * sum(per_row)
     qk_code_bytes = 0.75 if args.mode == "int4_fp8" else 1.0      # 6-bit codes in the INT4 mode
+    qg, kg = {"lane": (2, 16), "block": (2, 16), "fine": (1, 4), "token": (1, 1)}[args.group_map]
     alg_bytes = int((BH + BHkv) * spec.N * spec.d * qk_code_bytes) + BHkv * spec.N * spec.d + ds_bytes \
-        + 4 * (BH * spec.N // 2 + BHkv * spec.N // 16) + 2 * BH * spec.N * spec.d
+        + 4 * (BH * spec.N // qg + BHkv * spec.N // kg) + 2 * BH * spec.N * spec.d
 
     res = {
         "metric": "quantized attention TOPS at d=128 (causal + non-causal), cos-sim vs FP32",
@@ -156,7 +158,8 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import sage_oracle as so
         base, heads, ins, outs = cpu_baseline(spec, args.mode, smooth_v=args.smooth_v,
-                                                gmap={"lane": "g950", "block": "per_block"}[args.group_map])
+                                                gmap={"lane": "g950", "block": "per_block", "fine": "fine",
+                                                      "token": "per_token"}[args.group_map])
         res["cpu_baseline"] = base
         got = np.stack([wl.from_torch(out[b, h]) for b, h in heads])
         ref = np.stack(outs)

@@ -66,8 +66,13 @@ enum { SAGE_FLAG_SMOOTH_V = 1 };
    SAGE_GROUPS_LANE: the default, the gfx950 counterpart of per-thread quantization (SAGE_Q_GROUP /
    SAGE_K_GROUP below).  SAGE_GROUPS_BLOCK: one scale per 128-query block and per 64-key block
    (per-block quantization, the granularity of SageAttention-1, Sec. 2.3); same kernels, same speed,
-   lower accuracy.  q_scale / k_scale keep their shapes (values repeat inside a block). */
-enum { SAGE_GROUPS_LANE = 0, SAGE_GROUPS_BLOCK = 1 };
+   lower accuracy.  q_scale / k_scale keep their shapes (values repeat inside a block).
+   SAGE_GROUPS_FINE: one scale per query and per run of 4 keys - the finest groups that still cost
+   one dequantization factor per accumulator quad on gfx950 (a lane of the score MFMA owns one query,
+   and its 16 accumulators are 4 runs of 4 consecutive keys): nearly free.  SAGE_GROUPS_TOKEN: one
+   scale per query and per key (per-token quantization, Sec. 3.2): a factor per score, not free.
+   Queries / keys per entry of q_scale / k_scale: 2 / 16 (LANE, BLOCK), 1 / 4 (FINE), 1 / 1 (TOKEN). */
+enum { SAGE_GROUPS_LANE = 0, SAGE_GROUPS_BLOCK = 1, SAGE_GROUPS_FINE = 2, SAGE_GROUPS_TOKEN = 3 };
 /* Memory order of the four tensors (all contiguous): heads outside tokens, [B, H, N, d], or tokens
    outside heads, [B, N, H, d] (k, v: H_kv and N_kv).  The workspace layouts do not depend on it. */
 enum { SAGE_LAYOUT_HND = 0, SAGE_LAYOUT_NHD = 1 };
@@ -128,8 +133,8 @@ void sage_attn_release(void);
      q_codes [B,H,N,d] int8       codes of gamma(Q) (int4 mode) or Q (int8 mode), Sec. 3.2
      k_codes [B,H_kv,N_kv,d] int8    codes of gamma(K)
      v_codes [B,H_kv,N_kv,d] uint8   E4M3 codes of V / delta_V, Sec. 3.3
-     q_scale [B,H,ceil(N/2)] f32  delta_Q per query group
-     k_scale [B,H_kv,ceil(N_kv/16)] f32
+     q_scale [B,H,ceil(N/2)] f32  delta_Q per query group ([B,H,N] with SAGE_GROUPS_FINE / _TOKEN)
+     k_scale [B,H_kv,ceil(N_kv/16)] f32   (ceil(N_kv/4) with SAGE_GROUPS_FINE, N_kv with SAGE_GROUPS_TOKEN)
      v_scale [B,H_kv,d] f32       delta_V per channel
      k_mean  [B,H_kv,d] f32       mean(K) over tokens (Eq. 2)
      q_mean  [B,H,ceil(N/128),d] f32   block means of Q (int4 mode only, else untouched)

@@ -98,6 +98,8 @@ def group_map(name, N, which):
              keys congruent to {2i, 2i+1} modulo 8.
     "per_token", "per_block" (128 queries / 64 keys), "per_tensor": the granularities the
              paper compares against (Sec. 2.2, Sec. 2.3, Sec. 3.2).
+    "fine":  every query on its own, keys in runs of 4: finer than "g950", still one scale per
+             accumulator quad of a gfx950 lane.
     """
     n = np.arange(N)
     if name == "g950":
@@ -106,6 +108,8 @@ def group_map(name, N, which):
         if which == "q":
             return (n // 32) * 8 + (n % 8)
         return (n // 64) * 4 + (n % 8) // 2
+    if name == "fine":
+        return n if which == "q" else n // 4
     if name == "per_token":
         return n
     if name == "per_block":

@@ -12,8 +12,9 @@ import torch
 SAGE_MODE_INT4_FP8, SAGE_MODE_INT8_FP8 = 0, 1
 SAGE_DT_FP16, SAGE_DT_BF16 = 0, 1
 SAGE_FLAG_SMOOTH_V = 1
-SAGE_GROUPS_LANE, SAGE_GROUPS_BLOCK = 0, 1
-_GROUPS = {"lane": 0, "block": 1, 0: 0, 1: 1}
+SAGE_GROUPS_LANE, SAGE_GROUPS_BLOCK, SAGE_GROUPS_FINE, SAGE_GROUPS_TOKEN = 0, 1, 2, 3
+_GROUPS = {"lane": 0, "block": 1, "fine": 2, "token": 3, 0: 0, 1: 1, 2: 2, 3: 3}
+_GROUP_SIZES = {0: (2, 16), 1: (2, 16), 2: (1, 4), 3: (1, 1)}     # queries, keys per stored scale
 SAGE_LAYOUT_HND, SAGE_LAYOUT_NHD = 0, 1
 _LAYOUTS = {"HND": 0, "NHD": 1, 0: 0, 1: 1}
 _MODES = {"int4_fp8": 0, "int8_fp8": 1, 0: 0, 1: 1}
@@ -228,12 +229,13 @@ def sage_attn_quant(q, k, v, causal=False, sm_scale=0.0, mode="int4_fp8", worksp
     dev = q.device
     int4 = _MODES[mode] == 0
     nqb = (N + 127) // 128
+    qg, kg = _GROUP_SIZES[_GROUPS[group_map]]
     bufs = dict(
         q_codes=torch.empty((B, H, N, d), dtype=torch.int8, device=dev),
         k_codes=torch.empty((B, Hkv, Nk, d), dtype=torch.int8, device=dev),
         v_codes=torch.empty((B, Hkv, Nk, d), dtype=torch.uint8, device=dev),
-        q_scale=torch.empty((B, H, (N + 1) // 2), dtype=torch.float32, device=dev),
-        k_scale=torch.empty((B, Hkv, (Nk + 15) // 16), dtype=torch.float32, device=dev),
+        q_scale=torch.empty((B, H, (N + qg - 1) // qg), dtype=torch.float32, device=dev),
+        k_scale=torch.empty((B, Hkv, (Nk + kg - 1) // kg), dtype=torch.float32, device=dev),
         v_scale=torch.empty((B, Hkv, d), dtype=torch.float32, device=dev),
         k_mean=torch.empty((B, Hkv, d), dtype=torch.float32, device=dev),
     )

@@ -103,6 +103,53 @@ template <int D> struct RowState {
   float l_run;      // this lane's share of the running sum of 448 * P~
 };
 
+// Quantization granularity of the keys as the kernel sees it (template parameter GM): a lane's 32
+// scores of a block are (key tile KT, quad G, R) = key 32 KT + 16 (lane / 32) + 4 G + R, so
+//   GM 0: one scale per run of 16 keys = one per key tile  (2 per lane and block; queries in pairs),
+//   GM 1: one scale per run of 4 keys  = one per quad      (8 per lane and block; every query its own),
+//   GM 2: one scale per key            = one per score     (32 per lane and block; every query its own).
+// KeyScales: the block's key scales this lane needs; Factors: c = fl32(fl32(delta_Q delta_K) kappa).
+template <int GM> struct KeyScales;
+template <> struct KeyScales<0> { float s[2]; };
+template <> struct KeyScales<1> { v4f s[2]; };
+template <> struct KeyScales<2> { v4f s[2][4]; };
+template <int GM> struct Factors;
+template <> struct Factors<0> {
+  float c[2];
+  __device__ __forceinline__ void set(float dq, float kappa, const KeyScales<0>& k) {
+    c[0] = __fmul_rn(__fmul_rn(dq, k.s[0]), kappa);
+    c[1] = __fmul_rn(__fmul_rn(dq, k.s[1]), kappa);
+  }
+  __device__ __forceinline__ float at(int kt, int, int) const { return c[kt]; }
+};
+template <> struct Factors<1> {
+  float c[2][4];
+  __device__ __forceinline__ void set(float dq, float kappa, const KeyScales<1>& k) {
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) c[kt][g] = __fmul_rn(__fmul_rn(dq, k.s[kt][g]), kappa);
+    }
+  }
+  __device__ __forceinline__ float at(int kt, int g, int) const { return c[kt][g]; }
+};
+template <> struct Factors<2> {
+  float c[2][4][4];
+  __device__ __forceinline__ void set(float dq, float kappa, const KeyScales<2>& k) {
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) c[kt][g][r] = __fmul_rn(__fmul_rn(dq, k.s[kt][g][r]), kappa);
+      }
+    }
+  }
+  __device__ __forceinline__ float at(int kt, int g, int r) const { return c[kt][g][r]; }
+};
+// The 8-bit mode fuses the factor into the exponent's argument when it is shared by at least a quad.
+template <bool INT4, int GM> constexpr bool fused_factor() { return !INT4 && GM != 2; }
+
 // Middle part of one block of Algorithm 1's inner loop for one wavefront, cut into pieces of four
 // keys (one "group": registers 4G..4G+3 of key tile KT) so that MFMAs can be issued between them.
 //
@@ -112,13 +159,15 @@ template <int D> struct RowState {
 // mode there is no Delta-S and one positive factor c per key tile, so sc keeps the accumulators
 // as floats: the maximum commutes with the factor and the product is fused into the exponent's
 // argument (exp_group), one instruction less per score.
-template <bool INT4, bool CAUSAL, bool MASKED, int KT, int G>
+template <bool INT4, bool CAUSAL, bool MASKED, int GM, int KT, int G>
 __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2], const v4f (&dsr)[2][4],
-                                              float c, int half, int key0, int last_visible, int n_keys) {
+                                              const Factors<GM>& fac, int half, int key0, int last_visible,
+                                              int n_keys) {
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     float x;
-    if constexpr (INT4) x = __fmaf_rn(__int_as_float(raw[KT][4 * G + r]), c, dsr[KT][G][r]);
+    if constexpr (INT4) x = __fmaf_rn(__int_as_float(raw[KT][4 * G + r]), fac.at(KT, G, r), dsr[KT][G][r]);
+    else if constexpr (!fused_factor<INT4, GM>()) x = __fmul_rn((float)raw[KT][4 * G + r], fac.at(KT, G, r));
     else x = (float)raw[KT][4 * G + r];
     if constexpr (MASKED) {
       const int key = key0 + 32 * KT + 16 * half + 4 * G + r;
@@ -130,16 +179,16 @@ __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2
 
 // update_max: running max over the block's 64 dequantized scores of this lane's query (Eq. 1 /
 // Algorithm 1); returns alpha = 2^(m_old - m_new) and, in m_sub, the exponent offset of the block.
-template <int D, bool INT4>
-__device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2], float c0, float c1,
+template <int D, bool INT4, int GM>
+__device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2], const Factors<GM>& fac,
                                             float& m_sub) {
   float mx;
-  if constexpr (INT4) {
+  if constexpr (!fused_factor<INT4, GM>()) {
     mx = fmaxf(__int_as_float(acc[0][0]), __int_as_float(acc[1][0]));
 #pragma unroll
     for (int v = 1; v < 16; ++v)   // one v_max3_f32 per step
       mx = fmaxf(fmaxf(mx, __int_as_float(acc[0][v])), __int_as_float(acc[1][v]));
-  } else {
+  } else if constexpr (GM == 0) {
     // per key tile: max of the accumulators, then the tile's factor (c >= 0, so the order does not
     // matter; a fully masked tile with c = 0 gives NaN, which fmaxf drops)
     float m0 = __int_as_float(acc[0][0]), m1 = __int_as_float(acc[1][0]);
@@ -148,7 +197,19 @@ __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2
       m0 = fmaxf(fmaxf(m0, __int_as_float(acc[0][v])), __int_as_float(acc[0][(v + 1) & 15]));
       m1 = fmaxf(fmaxf(m1, __int_as_float(acc[1][v])), __int_as_float(acc[1][(v + 1) & 15]));
     }
-    mx = fmaxf(__fmul_rn(m0, c0), __fmul_rn(m1, c1));
+    mx = fmaxf(__fmul_rn(m0, fac.at(0, 0, 0)), __fmul_rn(m1, fac.at(1, 0, 0)));
+  } else {
+    // the same per quad
+    mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float a = fmaxf(fmaxf(__int_as_float(acc[kt][4 * g]), __int_as_float(acc[kt][4 * g + 1])),
+                              fmaxf(__int_as_float(acc[kt][4 * g + 2]), __int_as_float(acc[kt][4 * g + 3])));
+        mx = fmaxf(mx, __fmul_rn(a, fac.at(kt, g, 0)));
+      }
+    }
   }
   {
     // the other half of the wavefront holds the other 32 keys of the same query
@@ -165,17 +226,18 @@ __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2
 
 // exp_group: 448 * P~ = 2^(S - m_sub) for the group (INT8 mode: S = sc * c, fused), its row-sum share
 // added to ls, its FP8 codes written into word 4*KT + G of the P~ operand.
-template <bool INT4, bool MASKED, int KT, int G>
-__device__ __forceinline__ void exp_group(const v16i (&acc)[2], float c, float m_sub, v8i& pb, float& ls) {
+template <bool INT4, bool MASKED, int GM, int KT, int G>
+__device__ __forceinline__ void exp_group(const v16i (&acc)[2], const Factors<GM>& fac, float m_sub, v8i& pb,
+                                          float& ls) {
   float e[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const float x = __int_as_float(acc[KT][4 * G + r]);
     float arg;
-    if constexpr (INT4) {
+    if constexpr (!fused_factor<INT4, GM>()) {
       arg = x - m_sub;
     } else {
-      arg = __fmaf_rn(x, c, -m_sub);
+      arg = __fmaf_rn(x, fac.at(KT, G, r), -m_sub);
       if constexpr (MASKED) arg = x == -INFINITY ? -INFINITY : arg;   // also when c = 0
     }
     e[r] = __builtin_amdgcn_exp2f(arg);
@@ -234,8 +296,10 @@ __device__ __forceinline__ void dma_b32(const void* gbase, unsigned voff, unsign
 __device__ __forceinline__ void use_now(int x) { asm volatile("" :: "v"(x)); }
 __device__ __forceinline__ void use_now(float x) { asm volatile("" :: "v"(x)); }
 
-template <int D, bool INT4, bool CAUSAL, bool BF16>
+template <int D, bool INT4, bool CAUSAL, bool BF16, int GM>
 __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const AttnParams p) {
+  constexpr int KSC = GM == 0 ? 4 : (GM == 1 ? 16 : 64);    // key scales per block
+  constexpr int QG = GM == 0 ? QGROUP : 1;                  // queries per scale
   constexpr int CT = D / 32;          // 32-channel tiles of the output
   constexpr int KC = D * BKV / 16;    // 16-byte chunks of one V^ block
   constexpr int KCK = (int)(k_block_bytes(D, INT4) / 16);   // 16-byte chunks of one K^ block
@@ -243,7 +307,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   constexpr int CPTK = (KCK + 255) / 256;   // K^ copy rounds (the last one may skip some wavefronts)
   constexpr int MINC = KCK / 256 + CPT;     // copies every wavefront issues per block, at least
   constexpr int NST = 3;              // LDS stages: block j is read while j+1 and j+2 arrive
-  constexpr int XC = 32;              // chunks of the small part: 64 Delta-S floats, then 4 key-group scales
+  constexpr int XC = 32;              // chunks of the small part: 64 Delta-S floats, then up to 64 key scales
   constexpr int STAGE = KCK + KC + XC;   // chunks per stage: K^, V^, small part
   __shared__ v4i lds[NST][STAGE];
 
@@ -280,7 +344,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   const v4i* gk = reinterpret_cast<const v4i*>(p.k_codes + bhkv * (size_t)p.nKb * k_block_bytes(D, INT4));
   const v4i* gv = reinterpret_cast<const v4i*>(p.v_codes + bhkv * (size_t)p.nKb * BKV * D);
   const float* gd = INT4 ? p.delta_s + ((size_t)bh * p.nQb + qb) * p.nKb * BKV : nullptr;
-  const float* gs = p.k_scale + bhkv * (size_t)p.nKb * 4;
+  const float* gs = p.k_scale + bhkv * (size_t)p.nKb * KSC;
 
   int nblk = (sq.nk + BKV - 1) / BKV;
   if (CAUSAL) nblk = min(nblk, (qb * BQ + BQ - 1 + sq.coff) / BKV + 1);
@@ -301,7 +365,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     if (w == 0) {
       if constexpr (INT4) dma_b32(gd + (size_t)j * BKV, (unsigned)lane * 4, sb + (KCK + KC) * 16);
     } else if (w == 1) {
-      if (lane < 4) dma_b32(gs + (size_t)j * 4, (unsigned)lane * 4, sb + (KCK + KC) * 16 + 256);
+      if (lane < KSC) dma_b32(gs + (size_t)j * KSC, (unsigned)lane * 4, sb + (KCK + KC) * 16 + 256);
     }
   };
   // Every wavefront issues at least MINC copies per block, in block order, and loads complete in
@@ -325,7 +389,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
 #pragma unroll
     for (int s = 0; s < NP; ++s) qreg[s] = load_qk_operand<INT4>(gq, s, lane);
   }
-  const float dq = p.q_scale[((size_t)bh * p.nQb + qb) * (BQ / QGROUP) + (w * WQ + n) / QGROUP];
+  const float dq = p.q_scale[((size_t)bh * p.nQb + qb) * (BQ / QG) + (w * WQ + n) / QG];
 
   RowState<D> st;
 #pragma unroll
@@ -367,7 +431,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   qk_op ka[2 * NP];
   v4i va[2 * CT];
   v4f dsr[2][4];
-  float dk0 = 0.0f, dk1 = 0.0f;
+  KeyScales<GM> ks;
   auto read_k = [&](int stg) {
 #pragma unroll
     for (int i = 0; i < 2 * NP; ++i) ka[i] = load_qk_operand<INT4>(&lds[stg][0], i, lane);
@@ -386,8 +450,20 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
         for (int g = 0; g < 4; ++g) dsr[kt][g] = dsv[g];
       }
     }
-    dk0 = lx[64 + half];
-    dk1 = lx[66 + half];
+    if constexpr (GM == 0) {
+      ks.s[0] = lx[64 + half];
+      ks.s[1] = lx[66 + half];
+    } else if constexpr (GM == 1) {
+      ks.s[0] = *reinterpret_cast<const v4f*>(lx + 64 + 4 * half);
+      ks.s[1] = *reinterpret_cast<const v4f*>(lx + 72 + 4 * half);
+    } else {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        const v4f* kv = reinterpret_cast<const v4f*>(lx + 64 + 32 * kt + 16 * half);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) ks.s[kt][g] = kv[g];
+      }
+    }
   };
   // The compiler does not see the copies above, and it would otherwise leave its waits for the
   // ordinary loads of Q^ and the scale inside the loop, where they would also wait for copies in
@@ -405,13 +481,14 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   read_x(0);
   v16i raw[2], sc[2];                 // raw scores being produced / dequantized scores of block j
   qk_tile<D, INT4>(ka, qreg, raw);    // block 0 holds a visible key for every query
-  float alpha, m_sub, cj0, cj1;       // of block j; cj0, cj1: its dequantization factors per key tile
+  float alpha, m_sub;                 // of block j
+  Factors<GM> fj;                     // block j's dequantization factors (used again by the fused exponent)
   constexpr int NQK = qk_steps<D, INT4>();
   constexpr int GPC = 8 / CT;         // dequantization groups per P~V MFMA
 
 #define SAGE_DEQ(MASKED_, GI_, KEY0_)                                                                \
-  dequant_group<INT4, CAUSAL, MASKED_, (GI_) / 4, (GI_) % 4>(raw, sc, dsr, (GI_) / 4 == 0 ? c0 : c1, half, \
-                                                             KEY0_, query + sq.coff, sq.nk)
+  dequant_group<INT4, CAUSAL, MASKED_, GM, (GI_) / 4, (GI_) % 4>(raw, sc, dsr, fn, half, KEY0_,          \
+                                                                 query + sq.coff, sq.nk)
 #define SAGE_DEQ_ALL(MASKED_, KEY0_)                                                                 \
   do {                                                                                               \
     SAGE_DEQ(MASKED_, 0, KEY0_); SAGE_DEQ(MASKED_, 1, KEY0_); SAGE_DEQ(MASKED_, 2, KEY0_);           \
@@ -419,17 +496,18 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     SAGE_DEQ(MASKED_, 6, KEY0_); SAGE_DEQ(MASKED_, 7, KEY0_);                                        \
   } while (0)
   {
-    const float c0 = __fmul_rn(__fmul_rn(dq, dk0), p.kappa), c1 = __fmul_rn(__fmul_rn(dq, dk1), p.kappa);
+    Factors<GM> fn;
+    fn.set(dq, p.kappa, ks);
     if (n_plain > 0) SAGE_DEQ_ALL(false, 0); else SAGE_DEQ_ALL(true, 0);
-    alpha = update_max<D, INT4>(st, sc, c0, c1, m_sub);
-    cj0 = c0; cj1 = c1;
+    alpha = update_max<D, INT4, GM>(st, sc, fn, m_sub);
+    fj = fn;
   }
 
   int cur = 0;   // stage of block j
 #define SAGE_X(GI_, MASKED_)                                                                         \
   do {                                                                                               \
     if constexpr ((GI_) < NQK) qk_step<D, INT4, (GI_) < NQK ? (GI_) : 0>(ka, qreg, raw);             \
-    exp_group<INT4, MASKED_, (GI_) / 4, (GI_) % 4>(sc, (GI_) / 4 == 0 ? cj0 : cj1, m_sub, pb, ls);   \
+    exp_group<INT4, MASKED_, GM, (GI_) / 4, (GI_) % 4>(sc, fj, m_sub, pb, ls);                       \
     __builtin_amdgcn_sched_barrier(0);                                                               \
   } while (0)
 #define SAGE_Y(CT_, MASKED_)                                                                         \
@@ -463,10 +541,11 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     __builtin_amdgcn_sched_barrier(0);                                                               \
     SAGE_X(4, MASKED_); SAGE_X(5, MASKED_); SAGE_X(6, MASKED_); SAGE_X(7, MASKED_);                  \
     st.l_run = __fmaf_rn(alpha, st.l_run, ls);                                                       \
-    const float c0 = __fmul_rn(__fmul_rn(dq, dk0), p.kappa), c1 = __fmul_rn(__fmul_rn(dq, dk1), p.kappa); \
+    Factors<GM> fn;                                                                                  \
+    fn.set(dq, p.kappa, ks);                                                                         \
     SAGE_Y(0, MASKED_NEXT_); SAGE_Y(1, MASKED_NEXT_); SAGE_Y(2, MASKED_NEXT_); SAGE_Y(3, MASKED_NEXT_); /* Y */ \
-    alpha = update_max<D, INT4>(st, sc, c0, c1, m_sub);                                              \
-    cj0 = c0; cj1 = c1;                                                                              \
+    alpha = update_max<D, INT4, GM>(st, sc, fn, m_sub);                                              \
+    fj = fn;                                                                                         \
     cur = nx1;                                                                                       \
   } while (0)
   int j = 0;
@@ -563,8 +642,8 @@ hipError_t launch_debug_mfma_fp8(const void* a, const void* b, const float* c, f
   return hipGetLastError();
 }
 
-template <int D, bool INT4, bool CAUSAL, bool BF16>
-static hipError_t launch_attention_t(const Dims& Dm, const Ptrs& P, hipStream_t s) {
+template <int D, bool INT4, bool CAUSAL, bool BF16, int GM>
+static hipError_t launch_attention_g(const Dims& Dm, const Ptrs& P, hipStream_t s) {
   AttnParams p;
   p.q_codes = P.q_codes; p.k_codes = P.k_codes; p.v_codes = P.v_codes;
   p.q_scale = P.q_scale; p.k_scale = P.k_scale; p.v_scale = P.v_scale; p.delta_s = P.delta_s;
@@ -576,8 +655,14 @@ static hipError_t launch_attention_t(const Dims& Dm, const Ptrs& P, hipStream_t 
   p.total_tiles = Dm.B * Dm.H * Dm.nQb;
   p.kappa = Dm.kappa;
   const int grid = 8 * ((p.total_tiles + 7) / 8);
-  k_attn_fwd<D, INT4, CAUSAL, BF16><<<grid, 256, 0, s>>>(p);
+  k_attn_fwd<D, INT4, CAUSAL, BF16, GM><<<grid, 256, 0, s>>>(p);
   return hipGetLastError();
+}
+template <int D, bool INT4, bool CAUSAL, bool BF16>
+static hipError_t launch_attention_t(const Dims& Dm, const Ptrs& P, hipStream_t s) {
+  if (Dm.kg == KGROUP) return launch_attention_g<D, INT4, CAUSAL, BF16, 0>(Dm, P, s);
+  if (Dm.kg == 4) return launch_attention_g<D, INT4, CAUSAL, BF16, 1>(Dm, P, s);
+  return launch_attention_g<D, INT4, CAUSAL, BF16, 2>(Dm, P, s);
 }
 
 hipError_t launch_attention(const Dims& D, const Ptrs& P, hipStream_t s) {

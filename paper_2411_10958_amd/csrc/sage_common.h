@@ -11,8 +11,8 @@ namespace sage {
 constexpr int BQ = 128;      // queries per workgroup tile = Q smoothing block (Algorithm 1, b_q)
 constexpr int BKV = 64;      // keys per block = level-1 accumulation block (b_kv)
 constexpr int WQ = 32;       // queries per wavefront (one 32x32 MFMA column tile)
-constexpr int QGROUP = 2;    // queries per quantization group
-constexpr int KGROUP = 16;   // keys per quantization group
+constexpr int QGROUP = 2;    // queries per quantization group (default group map)
+constexpr int KGROUP = 16;   // keys per quantization group (default group map)
 constexpr float E4M3_MAX = 448.0f;
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LOG2_448 = 8.807354922057604f;
@@ -81,6 +81,7 @@ struct Dims {
   int nQb;     // ceil(N / 128) query blocks
   int nKb;     // ceil(Nk / 64) key blocks
   int causal, int4, bf16, smooth_v, block_groups, nhd;
+  int qg, kg;  // queries / keys per stored scale: 2 / 16 (lane and block maps), 1 / 4 (fine), 1 / 1 (token)
   float kappa; // fl32(sm_scale * log2 e)
   SeqMap seq;  // variable-length batch: N, Nk, nQb, nKb then describe the longest sequence
 };
@@ -140,8 +141,8 @@ inline Workspace make_workspace(const Dims& D) {
   w.v_mean = take(D.smooth_v ? BHkv * D.d * sizeof(float) : 0);
   w.v_scale = take(BHkv * D.d * sizeof(float));
   w.q_mean = take(BH * D.nQb * D.d * sizeof(float));
-  w.q_scale = take(BH * D.nQb * (BQ / QGROUP) * sizeof(float));
-  w.k_scale = take(BHkv * D.nKb * (BKV / KGROUP) * sizeof(float));
+  w.q_scale = take(BH * D.nQb * (BQ / D.qg) * sizeof(float));
+  w.k_scale = take(BHkv * D.nKb * (BKV / D.kg) * sizeof(float));
   w.q_codes = take(BH * D.nQb * q_slab_bytes(D.d, D.int4));
   w.k_codes = take(BHkv * D.nKb * k_block_bytes(D.d, D.int4));
   w.v_codes = take(BHkv * D.nKb * BKV * D.d);

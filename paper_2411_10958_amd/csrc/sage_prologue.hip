@@ -271,8 +271,8 @@ __global__ void k_finalize_vscale(const unsigned* __restrict__ v_max, float* __r
 template <bool BF16, int D>
 __global__ void __launch_bounds__(256) k_quant_q8(const unsigned short* __restrict__ Q,
                                                   float* __restrict__ q_scale, int8_t* __restrict__ q_codes,
-                                                  int N, int Nk, int nQb, int block_groups, TensorMap qm,
-                                                  SeqMap sm) {
+                                                  int N, int Nk, int nQb, int block_groups, int qg,
+                                                  TensorMap qm, SeqMap sm) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;  // RPT rows per thread (8 or 4)
   constexpr int QMAX = 127;
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
@@ -314,17 +314,23 @@ __global__ void __launch_bounds__(256) k_quant_q8(const unsigned short* __restri
   }
 #pragma unroll
   for (int p = 0; p < RPT / 2; ++p) {
-    float mx = 0.0f;
+    float mxr[2];                       // per query; the pair shares the larger one unless qg == 1
 #pragma unroll
-    for (int e = 0; e < 8; ++e) mx = fmaxf(mx, fmaxf(fabsf(x[2 * p][e]), fabsf(x[2 * p + 1][e])));
+    for (int i = 0; i < 2; ++i) {
+      mxr[i] = 0.0f;
 #pragma unroll
-    for (int m = NCG / 2; m >= 1; m >>= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
-    if (block_groups) mx = block_max;
-    const float delta = __fdiv_rn(mx, (float)QMAX);
-    if (cg == 0) q_scale[(bh * nQb + qb) * (BQ / QGROUP) + (rg * RPT) / 2 + p] = delta;
-    const QuantScale qs = quant_scale<QMAX>(delta);
+      for (int e = 0; e < 8; ++e) mxr[i] = fmaxf(mxr[i], fabsf(x[2 * p + i][e]));
+#pragma unroll
+      for (int m = NCG / 2; m >= 1; m >>= 1) mxr[i] = fmaxf(mxr[i], __shfl_xor(mxr[i], m, 64));
+    }
+    if (qg == 2) mxr[0] = mxr[1] = fmaxf(mxr[0], mxr[1]);
+    if (block_groups) mxr[0] = mxr[1] = block_max;
 #pragma unroll
     for (int i = 2 * p; i < 2 * p + 2; ++i) {
+      const float delta = __fdiv_rn(mxr[i - 2 * p], (float)QMAX);
+      if (cg == 0 && (qg == 1 || i == 2 * p))
+        q_scale[(bh * nQb + qb) * (BQ >> (qg - 1)) + ((rg * RPT + i) >> (qg - 1))] = delta;   // qg is 1 or 2
+      const QuantScale qs = quant_scale<QMAX>(delta);
       int c[8];
       quant_group<8, QMAX>(x[i], delta, qs, [&](int e, float cf) { c[e] = (int)cf; });
       *reinterpret_cast<uint2*>(img + q_code_off(rg * RPT + i, cg * 8, D)) = pack8(c);
@@ -351,7 +357,7 @@ template <bool BF16, int D>
 __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restrict__ Q,
                                                   float* __restrict__ q_mean, float* __restrict__ q_scale,
                                                   int8_t* __restrict__ q_codes, int N, int Nk, int nQb,
-                                                  int block_groups, TensorMap qm, SeqMap sm) {
+                                                  int block_groups, int qg, TensorMap qm, SeqMap sm) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;   // load map: RPT rows x 8 channels
   constexpr int CPL = D / 4, CPC = CPL / 8;                      // quantization map: 2 rows x CPL channels
   constexpr int QMAX = 7;
@@ -407,7 +413,7 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
 
   const int pair = t >> 2, c4 = t & 3;
   float x[2][CPL];
-  float mx = 0.0f;
+  float mxr[2] = {0.0f, 0.0f};          // per query; the pair shares the larger one unless qg == 1
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int r = 2 * pair + i;
@@ -421,25 +427,27 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           x[i][8 * j + e] = __fsub_rn(x[i][8 * j + e], mean[e]);
-          mx = fmaxf(mx, fabsf(x[i][8 * j + e]));
+          mxr[i] = fmaxf(mxr[i], fabsf(x[i][8 * j + e]));
         }
       }
     }
+    mxr[i] = fmaxf(mxr[i], __shfl_xor(mxr[i], 1, 64));
+    mxr[i] = fmaxf(mxr[i], __shfl_xor(mxr[i], 2, 64));
   }
-  mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
-  mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+  if (qg == 2) mxr[0] = mxr[1] = fmaxf(mxr[0], mxr[1]);
   if (block_groups) {       // per-block granularity: one scale for the whole 128-query block
-    const float bm = wave_max(mx);
+    const float bm = wave_max(mxr[0]);
     if ((t & 63) == 0) s_bmax[t >> 6] = bm;
     __syncthreads();
-    mx = fmaxf(fmaxf(s_bmax[0], s_bmax[1]), fmaxf(s_bmax[2], s_bmax[3]));
+    mxr[0] = mxr[1] = fmaxf(fmaxf(s_bmax[0], s_bmax[1]), fmaxf(s_bmax[2], s_bmax[3]));
   }
-  const float delta = __fdiv_rn(mx, (float)QMAX);
-  if (c4 == 0) q_scale[(bh * nQb + qb) * (BQ / QGROUP) + pair] = delta;
-  const QuantScale qs = quant_scale<QMAX>(delta);
   uint8_t* img = reinterpret_cast<uint8_t*>(&s_sum[0][0]);   // everyone is past the column sums
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
+    const float delta = __fdiv_rn(mxr[i], (float)QMAX);
+    if (c4 == 0 && (qg == 1 || i == 0))   // qg is 1 or 2
+      q_scale[(bh * nQb + qb) * (BQ >> (qg - 1)) + ((2 * pair + i) >> (qg - 1))] = delta;
+    const QuantScale qs = quant_scale<QMAX>(delta);
     Codes32 cd;
 #pragma unroll
     for (int e = 0; e < 16; ++e) { cd.ev[e] = 0.0f; cd.od[e] = 0.0f; }
@@ -489,8 +497,8 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
                                                  float* __restrict__ k_scale, int8_t* __restrict__ k_codes,
                                                  const float* __restrict__ q_mean,
                                                  float* __restrict__ delta_s, int Nq, int Nmax, int nKb,
-                                                 int nQb, int G, float kappa, int block_groups, int causal,
-                                                 TensorMap km, SeqMap sm) {
+                                                 int nQb, int G, float kappa, int block_groups, int kg,
+                                                 int causal, TensorMap km, SeqMap sm) {
   constexpr int CPL = D / 4;                       // channels per lane (32 or 16)
   constexpr int QMAX = INT4 ? 7 : 127;
   // LDS row of staged block means: channel c sits at column c + 16*(c / 32) when D = 128, so the
@@ -565,7 +573,18 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
 #pragma unroll
     for (int e = 0; e < CPL; ++e) x[e] = 0.0f;      // padded keys: codes 0, Delta-S 0
   }
-  mx = wave_max(mx);
+  // lanes l, l^16, l^32, l^48 hold one key: its maximum first, then (unless every key has its own
+  // scale) the run of 4 keys, then (default) the wavefront's run of 16
+  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  if (kg >= 4) {
+    mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+  }
+  if (kg == 16) {
+    mx = fmaxf(mx, __shfl_xor(mx, 4, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 8, 64));
+  }
   __shared__ float s_bmax[4];
   if (block_groups) {       // per-block granularity: one scale for the whole 64-key block
     if (lane == 0) s_bmax[w] = mx;
@@ -573,7 +592,8 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
     mx = fmaxf(fmaxf(s_bmax[0], s_bmax[1]), fmaxf(s_bmax[2], s_bmax[3]));
   }
   const float delta = __fdiv_rn(mx, (float)QMAX);
-  if (lane == 0) k_scale[(bhkv * nKb + kb) * (BKV / KGROUP) + w] = delta;
+  const int ksh = kg == 16 ? 4 : (kg == 4 ? 2 : 0);
+  if (k4 == 0 && (r16 & (kg - 1)) == 0) k_scale[(bhkv * nKb + kb) * (BKV >> ksh) + ((16 * w + r16) >> ksh)] = delta;
   uint8_t* img = reinterpret_cast<uint8_t*>(s_codes);
   const QuantScale qs = quant_scale<QMAX>(delta);
   if constexpr (INT4) {
@@ -763,14 +783,14 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
   }
   if constexpr (INT4)
     k_quant_q4<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
-                                                     Dm.block_groups, qm, sm);
+                                                     Dm.block_groups, Dm.qg, qm, sm);
   else
     k_quant_q8<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
-                                                     Dm.block_groups, qm, sm);
+                                                     Dm.block_groups, Dm.qg, qm, sm);
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
                                                               P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
-                                                              Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.causal,
-                                                              km, sm);
+                                                              Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.kg,
+                                                              Dm.causal, km, sm);
   if (Dm.smooth_v)
     k_quant_v<BF16, D, true><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
   else
@@ -800,9 +820,9 @@ hipError_t launch_unpack(const Dims& D, const Ptrs& P, const void* quant_out, hi
   if (o.qc) k_unpack_codes<<<dim3(gx, BH), 256, 0, s>>>(P.q_codes, o.qc, D.N, D.d, D.nQb * q_slab_bytes(D.d, D.int4), 0, D.int4);
   if (o.kc) k_unpack_codes<<<dim3(gxk, BHkv), 256, 0, s>>>(P.k_codes, o.kc, D.Nk, D.d, D.nKb * k_block_bytes(D.d, D.int4), 1, D.int4);
   if (o.vc) k_unpack_codes<<<dim3(gxk, BHkv), 256, 0, s>>>((const int8_t*)P.v_codes, (int8_t*)o.vc, D.Nk, D.d, (size_t)D.nKb * BKV * D.d, 2, 0);
-  const int nqg = (D.N + QGROUP - 1) / QGROUP, nkg = (D.Nk + KGROUP - 1) / KGROUP;
-  if (o.qs) k_unpack_rows<<<dim3((nqg + 255) / 256, BH), 256, 0, s>>>(P.q_scale, o.qs, nqg, D.nQb * (BQ / QGROUP));
-  if (o.ks) k_unpack_rows<<<dim3((nkg + 255) / 256, BHkv), 256, 0, s>>>(P.k_scale, o.ks, nkg, D.nKb * (BKV / KGROUP));
+  const int nqg = (D.N + D.qg - 1) / D.qg, nkg = (D.Nk + D.kg - 1) / D.kg;
+  if (o.qs) k_unpack_rows<<<dim3((nqg + 255) / 256, BH), 256, 0, s>>>(P.q_scale, o.qs, nqg, D.nQb * (BQ / D.qg));
+  if (o.ks) k_unpack_rows<<<dim3((nkg + 255) / 256, BHkv), 256, 0, s>>>(P.k_scale, o.ks, nkg, D.nKb * (BKV / D.kg));
   if (o.vs) k_unpack_rows<<<dim3(1, BHkv), 256, 0, s>>>(P.v_scale, o.vs, D.d, D.d);
   if (o.km) k_unpack_rows<<<dim3(1, BHkv), 256, 0, s>>>(P.k_mean, o.km, D.d, D.d);
   if (o.vm && D.smooth_v) k_unpack_rows<<<dim3(1, BHkv), 256, 0, s>>>(P.v_mean, o.vm, D.d, D.d);

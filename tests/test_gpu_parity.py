@@ -218,6 +218,37 @@ def test_per_block_groups_match_oracle(N, d, dtype, H, Hkv, causal, mode):
     assert e_f <= e_b * 1.02      # finer groups are not worse (the paper's granularity table)
 
 
+# ---- finer granularities: every query its own scale, keys in runs of 4 ("fine") or one by one ("token") ----
+@pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("group_map,gmap", [("fine", "fine"), ("token", "per_token")])
+@pytest.mark.parametrize("N,d,dtype,H,Hkv,causal", [(333, 128, "bf16", 2, 1, True), (640, 64, "fp16", 2, 2, False)])
+def test_finer_groups_match_oracle(N, d, dtype, H, Hkv, causal, group_map, gmap, mode):
+    pa = _pa()
+    spec = _spec(N, d, dtype, H, Hkv, causal=causal, outliers=2)
+    data, (q, k, v) = _gpu_inputs(spec)
+    print(f"{group_map} case N={N} d={d} {dtype} H={H}/{Hkv} causal={causal} mode={mode}", flush=True)
+    got, args, ws = pa.sage_attn_quant(q, k, v, causal=causal, mode=mode, group_map=group_map,
+                                       want=("q_codes", "k_codes", "q_scale", "k_scale"))
+    out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, group_map=group_map)
+    lane = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode)
+    torch.cuda.synchronize()
+    got = {n: t.cpu().numpy() for n, t in got.items()}
+    g = H // Hkv
+    for h in range(H):
+        pro = so.quantize_head(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], mode=mode, gmap=gmap)
+        assert np.array_equal(got["q_codes"][0, h], pro["q_codes"]), "q codes"
+        assert np.array_equal(got["k_codes"][0, h // g], pro["k_codes"]), "k codes"
+        assert np.array_equal(got["q_scale"][0, h], pro["q_scale"]), "q scales"
+        assert np.array_equal(got["k_scale"][0, h // g], pro["k_scale"]), "k scales"
+    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32", gmap=gmap)
+    check_output(wl.from_torch(out), ref, dtype)
+    full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
+                     for h in range(H)])
+    e_f, e_l = wl.rel_l1(wl.from_torch(out)[0], full), wl.rel_l1(wl.from_torch(lane)[0], full)
+    print(f"  rel-L1 vs FP64 attention: {group_map} {e_f:.4f}, default groups {e_l:.4f}", flush=True)
+    assert e_f <= e_l * 1.02      # finer groups are not worse (the paper's granularity table)
+
+
 # ---- key length different from query length (cross attention, chunked prefill, decode) ---------
 CROSS_CASES = [
     # N, N_kv, d, dtype, H, Hkv, causal
