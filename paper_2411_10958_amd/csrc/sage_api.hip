@@ -29,7 +29,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   const long long nQb = (a->N + BQ - 1) / BQ, nKb = (Nk + BKV - 1) / BKV;
   if ((long long)a->B * a->H * nQb > (1LL << 30)) return SAGE_ERR_UNSUPPORTED;
   D->B = a->B; D->H = a->H; D->Hkv = a->H_kv; D->N = a->N; D->d = a->d;
-  D->Nk = Nk; D->coff = Nk - a->N;
+  D->Nk = Nk;
   D->nQb = (int)nQb; D->nKb = (int)nKb;
   D->causal = a->causal != 0;
   D->int4 = a->mode == SAGE_MODE_INT4_FP8;

@@ -25,7 +25,7 @@ struct AttnParams {
   const float* v_mean;    // null, or the token mean of V to add back (smooth-V option)
   const float* delta_s;
   void* out;
-  int H, Hkv, N, Nk, coff, nQb, nKb, total_tiles;   // N queries, Nk keys; causal: key t <= query + coff
+  int H, Hkv, N, Nk, nQb, nKb, total_tiles;   // N queries, Nk keys (of the longest sequence)
   TensorMap om;           // where the rows of `out` start
   float kappa;
   SeqMap seq;             // variable-length batch: N, Nk, nQb, nKb describe the longest sequence
@@ -649,7 +649,7 @@ static hipError_t launch_attention_g(const Dims& Dm, const Ptrs& P, hipStream_t 
   p.q_scale = P.q_scale; p.k_scale = P.k_scale; p.v_scale = P.v_scale; p.delta_s = P.delta_s;
   p.v_mean = Dm.smooth_v ? P.v_mean : nullptr;
   p.out = P.out;
-  p.H = Dm.H; p.Hkv = Dm.Hkv; p.N = Dm.N; p.Nk = Dm.Nk; p.coff = Dm.coff; p.nQb = Dm.nQb;
+  p.H = Dm.H; p.Hkv = Dm.Hkv; p.N = Dm.N; p.Nk = Dm.Nk; p.nQb = Dm.nQb;
   p.om = make_tensor_map(Dm.nhd, Dm.H, Dm.N, Dm.d, Dm.seq.cu_q != nullptr); p.nKb = Dm.nKb;
   p.seq = Dm.seq;
   p.total_tiles = Dm.B * Dm.H * Dm.nQb;

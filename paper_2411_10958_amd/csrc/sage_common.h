@@ -14,6 +14,7 @@ constexpr int WQ = 32;       // queries per wavefront (one 32x32 MFMA column til
 constexpr int QGROUP = 2;    // queries per quantization group (default group map)
 constexpr int KGROUP = 16;   // keys per quantization group (default group map)
 constexpr float E4M3_MAX = 448.0f;
+constexpr int STAT_ROWS = 256;  // tokens per workgroup of the column-statistics pass
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LOG2_448 = 8.807354922057604f;
 
@@ -77,7 +78,6 @@ inline TensorMap make_tensor_map(int nhd, int heads, int tokens, int d, bool var
 struct Dims {
   int B, H, Hkv, N, d;
   int Nk;      // keys / values per head (N unless the caller says otherwise)
-  int coff;    // Nk - N: the causal mask lets query r see keys t <= r + coff
   int nQb;     // ceil(N / 128) query blocks
   int nKb;     // ceil(Nk / 64) key blocks
   int causal, int4, bf16, smooth_v, block_groups, nhd;
@@ -111,8 +111,10 @@ struct Dims {
 //            (the A operand of v_mfma_f32_32x32x64_f8f6f4, key order matching the order in
 //            which a lane's P~ registers come out of the score tiles).
 //   delta_s: [B*H][nQb][nKb*64] float, zero beyond N.
-//   q_scale: [B*H][nQb*64] float;  k_scale: [B*Hkv][nKb*4] float.
-//   v_sum, v_mean: [B*Hkv][d], only with the smooth-V option (otherwise zero-sized).
+//   q_scale: [B*H][nQb*128/qg] float;  k_scale: [B*Hkv][nKb*64/kg] float (qg, kg: queries / keys per
+//            scale of the chosen group map).
+//   k_sum, v_max (and v_sum): [B*Hkv][ceil(Nk/STAT_ROWS)][d] partial results of the statistics pass;
+//   v_sum, v_mean only with the smooth-V option (otherwise zero-sized).
 struct Workspace {
   size_t k_sum, v_sum, v_max, k_mean, v_mean, v_scale, q_mean, q_scale, k_scale, q_codes, k_codes, v_codes,
       delta_s, total;
@@ -134,9 +136,10 @@ inline Workspace make_workspace(const Dims& D) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
   const size_t BH = (size_t)D.B * D.H, BHkv = (size_t)D.B * D.Hkv;
-  w.k_sum = take(BHkv * D.d * sizeof(double));
-  w.v_sum = take(D.smooth_v ? BHkv * D.d * sizeof(double) : 0);
-  w.v_max = take(BHkv * D.d * sizeof(unsigned));
+  const size_t nchunk = (size_t)(D.Nk + STAT_ROWS - 1) / STAT_ROWS;   // partial results of the statistics pass
+  w.k_sum = take(BHkv * nchunk * D.d * sizeof(double));
+  w.v_sum = take(D.smooth_v ? BHkv * nchunk * D.d * sizeof(double) : 0);
+  w.v_max = take(BHkv * nchunk * D.d * sizeof(unsigned));
   w.k_mean = take(BHkv * D.d * sizeof(float));
   w.v_mean = take(D.smooth_v ? BHkv * D.d * sizeof(float) : 0);
   w.v_scale = take(BHkv * D.d * sizeof(float));

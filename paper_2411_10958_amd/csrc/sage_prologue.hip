@@ -1,8 +1,11 @@
 // Preprocessing kernels of the quantized attention forward pass (paper Sec. 3.1-3.3 and the
 // "Preprocessing" line plus the first line of the outer loop of Algorithm 1): token means,
 // smoothing, Delta-S, group quantization of Q and K, per-channel FP8 quantization of V.
-// Everything here is bandwidth-bound; codes are written in the MFMA fragment order described
-// in sage_common.h so that the attention kernel can move them with plain 16-byte copies.
+// The passes stream Q, K and V once or twice each; after the loads it is the vector ALU work per
+// element (and, for Delta-S, the FP64 matrix pipe) that sets their speed, so the quantizers avoid
+// per-element divisions and per-element code packing.  Codes are written in the MFMA fragment
+// order described in sage_common.h so that the attention kernel can move them with plain 16-byte
+// copies.
 #include "sage_common.h"
 #include "sage_attn.h"
 
@@ -131,17 +134,9 @@ __device__ inline void pack6(const int (&c)[N6], unsigned (&w)[N6 * 6 / 32]) {
 
 // ------------------------------------------------------------------------------------------
 // Column statistics: exact token sums of K (float64 accumulation of 16-bit values) and
-// per-channel max |V| (Algorithm 1, "Preprocessing": mean(K) and the scale of psi_V).
-__global__ void k_zero_stats(double* k_sum, double* v_sum, unsigned* v_max, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) {
-    k_sum[i] = 0.0;
-    v_max[i] = 0u;
-    if (v_sum) v_sum[i] = 0.0;     // smooth-V option only
-  }
-}
-
-constexpr int STAT_ROWS = 256;  // tokens per workgroup of k_col_stats
+// per-channel max |V| (Algorithm 1, "Preprocessing": mean(K) and the scale of psi_V).  Every
+// workgroup writes the partial result of its STAT_ROWS tokens; the finalize kernels reduce the
+// partials of a head (no atomics, nothing to clear beforehand).
 constexpr int STAT_UNROLL = 4; // rows per thread in flight
 
 // With the smooth-V option the first pass takes the exact token sums of V instead of max|V| (the
@@ -206,9 +201,10 @@ __global__ void __launch_bounds__(256) k_col_stats(const unsigned short* __restr
       s += s_sum[g][t];
       if constexpr (SMOOTH_V) sv += s_vsum[g][t]; else m = fmaxf(m, s_max[g][t]);
     }
-    atomicAdd(&k_sum[(size_t)blockIdx.y * D + t], s);
-    if constexpr (SMOOTH_V) atomicAdd(&v_sum[(size_t)blockIdx.y * D + t], sv);
-    else atomicMax(&v_max[(size_t)blockIdx.y * D + t], __float_as_uint(m));  // m >= 0: uint order = float order
+    const size_t slot = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * D + t;
+    k_sum[slot] = s;
+    if constexpr (SMOOTH_V) v_sum[slot] = sv;
+    else v_max[slot] = __float_as_uint(m);
   }
 }
 
@@ -241,7 +237,7 @@ __global__ void __launch_bounds__(256) k_v_absmax(const unsigned short* __restri
   if (t < D) {
     float m = 0.0f;
     for (int g = 0; g < NRG; ++g) m = fmaxf(m, s_max[g][t]);
-    atomicMax(&v_max[(size_t)blockIdx.y * D + t], __float_as_uint(m));
+    v_max[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * D + t] = __float_as_uint(m);
   }
 }
 
@@ -250,18 +246,33 @@ __global__ void __launch_bounds__(256) k_v_absmax(const unsigned short* __restri
 __global__ void k_finalize_stats(const double* __restrict__ k_sum, const double* __restrict__ v_sum,
                                  const unsigned* __restrict__ v_max, float* __restrict__ k_mean,
                                  float* __restrict__ v_mean, float* __restrict__ v_scale, int n, int Nq, int N,
-                                 int d, int Hkv, SeqMap sm) {
+                                 int d, int Hkv, int nchunk, SeqMap sm) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) {
-    const int nk = seq_of(sm, (unsigned)(i / d / Hkv), Nq, N).nk;      // this sequence's key count
-    k_mean[i] = nk > 0 ? (float)(k_sum[i] / (double)nk) : 0.0f;
-    if (v_sum) v_mean[i] = nk > 0 ? (float)(v_sum[i] / (double)nk) : 0.0f;
-    else v_scale[i] = __fdiv_rn(__uint_as_float(v_max[i]), E4M3_MAX);
+    const int head = i / d, c = i - head * d;
+    const int nk = seq_of(sm, (unsigned)(head / Hkv), Nq, N).nk;      // this sequence's key count
+    const size_t p0 = (size_t)head * nchunk * d + c;
+    double ks = 0.0, vs = 0.0;
+    float vm = 0.0f;
+    for (int ch = 0; ch < nchunk; ++ch) {
+      ks += k_sum[p0 + (size_t)ch * d];
+      if (v_sum) vs += v_sum[p0 + (size_t)ch * d];
+      else vm = fmaxf(vm, __uint_as_float(v_max[p0 + (size_t)ch * d]));
+    }
+    k_mean[i] = nk > 0 ? (float)(ks / (double)nk) : 0.0f;
+    if (v_sum) v_mean[i] = nk > 0 ? (float)(vs / (double)nk) : 0.0f;
+    else v_scale[i] = __fdiv_rn(vm, E4M3_MAX);
   }
 }
-__global__ void k_finalize_vscale(const unsigned* __restrict__ v_max, float* __restrict__ v_scale, int n) {
+__global__ void k_finalize_vscale(const unsigned* __restrict__ v_max, float* __restrict__ v_scale, int n, int d,
+                                  int nchunk) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) v_scale[i] = __fdiv_rn(__uint_as_float(v_max[i]), E4M3_MAX);
+  if (i < n) {
+    const int head = i / d, c = i - head * d;
+    float vm = 0.0f;
+    for (int ch = 0; ch < nchunk; ++ch) vm = fmaxf(vm, __uint_as_float(v_max[((size_t)head * nchunk + ch) * d + c]));
+    v_scale[i] = __fdiv_rn(vm, E4M3_MAX);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -769,24 +780,26 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
                   km = make_tensor_map(Dm.nhd, Dm.Hkv, Dm.Nk, Dm.d, varlen);
   const SeqMap sm = Dm.seq;
   const float* v_mean = Dm.smooth_v ? P.v_mean : nullptr;
-  k_zero_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, Dm.smooth_v ? P.v_sum : nullptr, P.v_max, nstat);
-  if (Dm.smooth_v) {
-    k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.N, Dm.Nk, km, sm);
-    k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
-                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, sm);
-    k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.N, Dm.Nk, km, sm);
-    k_finalize_vscale<<<(nstat + 255) / 256, 256, 0, s>>>(P.v_max, P.v_scale, nstat);
-  } else {
-    k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.N, Dm.Nk, km, sm);
-    k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
-                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, sm);
-  }
+  // Q first: it depends on nothing, and with the statistics pass next to the K and V quantizers
+  // those re-read K and V while the chip's memory-side cache still holds most of them
   if constexpr (INT4)
     k_quant_q4<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
                                                      Dm.block_groups, Dm.qg, qm, sm);
   else
     k_quant_q8<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
                                                      Dm.block_groups, Dm.qg, qm, sm);
+  const int nchunk = (int)gstat.x;
+  if (Dm.smooth_v) {
+    k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.N, Dm.Nk, km, sm);
+    k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
+                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm);
+    k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.N, Dm.Nk, km, sm);
+    k_finalize_vscale<<<(nstat + 255) / 256, 256, 0, s>>>(P.v_max, P.v_scale, nstat, Dm.d, nchunk);
+  } else {
+    k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.N, Dm.Nk, km, sm);
+    k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
+                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm);
+  }
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
                                                               P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
                                                               Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.kg,
