@@ -48,8 +48,10 @@ def cpu_baseline(spec, mode, budget_s=12.0, max_heads=32, smooth_v=False, gmap="
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    # defaults: the chip needs some tens of milliseconds of back-to-back work before its clocks settle
+    # (5 warm-up steps of the 1 ms default workload measure 8 % low); 50 + 100 steps are 0.15 s of GPU time
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="prefill4k")
     ap.add_argument("--mode", default="int4_fp8", choices=["int4_fp8", "int8_fp8"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
