@@ -122,3 +122,76 @@ def test_full_size_smooth_v_sampled_parity():
         ref_rows.append(so.attention_rows(pro, rows, spec.causal, out_dtype="fp32"))
         got_rows.append(wl.from_torch(out[b, h, rows]))
     check_output(np.concatenate(got_rows), np.concatenate(ref_rows), spec.dtype)
+
+
+@pytest.mark.parametrize("group_map,gmap", [("fine", "fine"), ("token", "per_token")])
+def test_full_size_finer_groups_sampled_parity(group_map, gmap):
+    """The finer quantization granularities at the full size of the benchmark workload: codes and scales of a
+    whole head bit-exact, outputs of sampled query blocks."""
+    pa = _pa()
+    spec = wl.CONFIGS["prefill4k"]
+    rng = np.random.default_rng(99)
+    print(f"workload prefill4k, group map {group_map}: generating inputs", flush=True)
+    data = wl.make_inputs(spec, seed=0)
+    dev = torch.device("cuda:0")
+    q, k, v = (wl.to_torch(data[n], spec.dtype, dev) for n in "qkv")
+    print("  running the HIP path", flush=True)
+    out = pa.sage_attn_fwd_ex(q, k, v, causal=spec.causal, mode="int4_fp8", group_map=group_map)
+    quant, args, ws = pa.sage_attn_quant(q, k, v, causal=spec.causal, mode="int4_fp8", group_map=group_map,
+                                         want=["q_codes", "k_codes", "q_scale", "k_scale"])
+    torch.cuda.synchronize()
+    b, h = 2, 9
+    blocks = _blocks(spec, 3, rng)
+    print(f"  oracle on (b={b}, h={h}), query blocks {blocks}", flush=True)
+    pro = so.quantize_head(data["q"][b, h], data["k"][b, h], data["v"][b, h], ds_blocks=blocks, gmap=gmap)
+    for name in ("q_codes", "k_codes", "q_scale", "k_scale"):
+        assert np.array_equal(quant[name][b, h].cpu().numpy(), pro[name]), name
+    got_rows, ref_rows = [], []
+    for i in blocks:
+        rows = slice(i * 128, min(i * 128 + 128, spec.N))
+        ref_rows.append(so.attention_rows(pro, rows, spec.causal, out_dtype="fp32"))
+        got_rows.append(wl.from_torch(out[b, h, rows]))
+    check_output(np.concatenate(got_rows), np.concatenate(ref_rows), spec.dtype)
+
+
+def test_full_size_varlen_sampled_parity():
+    """A packed causal batch of five sequences of very different lengths (18 k tokens, 32 query heads on 8 KV
+    heads): every sequence bit-identical to a call on it alone, sampled query blocks of the longest one
+    against the oracle."""
+    pa = _pa()
+    lens = [4096, 1500, 8192, 333, 4200]
+    H, Hkv, d, dtype = 32, 8, 128, "bf16"
+    dev = torch.device("cuda:0")
+    print(f"packed batch {lens}: generating inputs", flush=True)
+    seqs = []
+    for i, n in enumerate(lens):
+        spec = wl.WorkloadSpec(f"seq{i}", 1, H, Hkv, n, d, dtype, True, 3.0, 3.0, 4, 10.0, 1.0, 200 + i)
+        seqs.append(wl.make_inputs(spec, seed=0))
+    pack = lambda name: wl.to_torch(np.ascontiguousarray(np.concatenate([s[name][0].transpose(1, 0, 2) for s in seqs])),
+                                    dtype, dev)
+    q, k, v = pack("q"), pack("k"), pack("v")
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev)
+    print("  running the HIP path", flush=True)
+    out = pa.sage_attn_fwd_ex(q, k, v, causal=True, mode="int4_fp8", cu_seqlens_q=cu, max_seqlen_q=max(lens),
+                              max_seqlen_k=max(lens))
+    torch.cuda.synchronize()
+    off = np.concatenate([[0], np.cumsum(lens)])
+    for i, n in enumerate(lens):
+        sl = slice(off[i], off[i + 1])
+        alone = pa.sage_attn_fwd_ex(q[sl].unsqueeze(0).contiguous(), k[sl].unsqueeze(0).contiguous(),
+                                    v[sl].unsqueeze(0).contiguous(), causal=True, mode="int4_fp8", layout="NHD")
+        torch.cuda.synchronize()
+        assert torch.equal(alone[0], out[sl]), f"sequence {i}"
+    i, h = 2, 13
+    rng = np.random.default_rng(7)
+    nqb = (lens[i] + 127) // 128
+    blocks = sorted({0, nqb // 2, nqb - 1} | set(int(x) for x in rng.choice(nqb, size=2, replace=False)))
+    print(f"  oracle on sequence {i}, head {h}, query blocks {blocks}", flush=True)
+    pro = so.quantize_head(seqs[i]["q"][0, h], seqs[i]["k"][0, h // (H // Hkv)], seqs[i]["v"][0, h // (H // Hkv)],
+                           ds_blocks=blocks)
+    got_rows, ref_rows = [], []
+    for bq in blocks:
+        rows = slice(bq * 128, min(bq * 128 + 128, lens[i]))
+        ref_rows.append(so.attention_rows(pro, rows, True, out_dtype="fp32"))
+        got_rows.append(wl.from_torch(out[off[i] + rows.start:off[i] + rows.stop, h]))
+    check_output(np.concatenate(got_rows), np.concatenate(ref_rows), dtype)
