@@ -242,7 +242,7 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
     else:
         dv, vc = quantize_v(V)
         vdec = e4m3_decode(vc)                            # [N, d] float64, exact
-    return dict(N=N, Nk=Nk, d=d, kappa=kappa, qmax=qmax, kbar=kbar, qbar=qbar, delta_s=D,
+    return dict(N=N, Nk=Nk, d=d, kappa=kappa, qmax=qmax, kbar=kbar, qbar=qbar, delta_s=D, Q=np.asarray(Q, f32),
                 q_codes=qc, q_scale=dq, q_groups=gq, k_codes=kc, k_scale=dk, k_groups=gk,
                 v_codes=vc, v_scale=dv, v_dec=vdec, pv_exact=pv_exact, bq=bq, vbar=vbar)
 
@@ -313,6 +313,21 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
     return res
 
 
+def row_lse(pro, rows, state):
+    """Natural-log-sum-exp of the scores sm_scale * <q_r, k_t> over the visible keys, as the quantized
+    path evaluates them: from the final running maximum m and sum l of Algorithm 1 (base 2, l carried
+    as 448 * l) plus the one row constant the smoothing of K drops from every score of a row
+    (Sec. 3.1: <q_r, mean(K)>, invisible to the softmax but part of the sum's scale):
+        lse_r = ln 2 * (m_r + log2(l_r / 448) + kappa * <q_r, mean(K)>),
+    evaluated in float64 from the FP32 state and rounded once to FP32.  This is what lets partial
+    results over disjoint key sets be merged (weights exp(lse_part - lse_total))."""
+    rows = np.arange(pro["N"])[rows]
+    m, l = state["m"].astype(f64), state["l"].astype(f64)
+    corr = f64(pro["kappa"]) * (pro["Q"][rows].astype(f64) @ pro["kbar"].astype(f64))
+    with np.errstate(divide="ignore"):
+        return (np.log(2.0) * (m + np.log2(l / E4M3_MAX) + corr)).astype(f32)
+
+
 def _round_out(x, dtype):
     if dtype == "fp16":
         return x.astype(np.float16).astype(f32)
@@ -326,16 +341,24 @@ def _round_out(x, dtype):
 
 
 def sage_attention_head(Q, K, V, causal=False, mode="int4_fp8", sm_scale=None, gmap="g950",
-                        bq=BQ_SMOOTH, bkv=BKV_ACC, out_dtype="bf16", q_blocks=None, **kw):
+                        bq=BQ_SMOOTH, bkv=BKV_ACC, out_dtype="bf16", q_blocks=None, want_lse=False, **kw):
     """Algorithm 1 for one (batch, head); `q_blocks` restricts the outer loop to some
-    smoothing blocks (rows of the others are left zero)."""
+    smoothing blocks (rows of the others are left zero).  With want_lse the prologue dict also
+    carries "lse" [N] (see row_lse)."""
     pro = quantize_head(Q, K, V, mode, sm_scale, gmap, bq, **kw)
     N, d = Q.shape
     out = np.zeros((N, d), f32)
+    lse = np.zeros(N, f32)
     nblk = (N + bq - 1) // bq
     for i in (range(nblk) if q_blocks is None else q_blocks):
         rows = slice(i * bq, min((i + 1) * bq, N))
-        out[rows] = attention_rows(pro, rows, causal, bkv, out_dtype)
+        if want_lse:
+            out[rows], st = attention_rows(pro, rows, causal, bkv, out_dtype, return_state=True)
+            lse[rows] = row_lse(pro, rows, st)
+        else:
+            out[rows] = attention_rows(pro, rows, causal, bkv, out_dtype)
+    if want_lse:
+        pro["lse"] = lse
     return out, pro
 
 
@@ -354,6 +377,22 @@ def sage_attention(q, k, v, causal=False, mode="int4_fp8", sm_scale=None, gmap="
 
 
 # --------------------------------------------------------------------------- definition
+def ref_lse_fp64(Q, K, causal=False, sm_scale=None, rows=None):
+    """ln sum_t exp(sm_scale * <q_r, k_t>) over the visible keys, float64, one head (the
+    normaliser of the softmax in Sec. 2.1, first formula)."""
+    Q, K = np.asarray(Q, f64), np.asarray(K, f64)
+    N, Nk = Q.shape[0], K.shape[0]
+    if sm_scale is None:
+        sm_scale = 1.0 / np.sqrt(Q.shape[1])
+    ridx = np.arange(N) if rows is None else np.arange(N)[rows]
+    S = (Q[ridx] @ K.T) * sm_scale
+    if causal:
+        S = np.where(np.arange(Nk)[None, :] > ridx[:, None] + (Nk - N), -np.inf, S)
+    mx = S.max(axis=1)
+    return mx + np.log(np.exp(S - mx[:, None]).sum(axis=1))
+
+
+
 def ref_attn_fp64(Q, K, V, causal=False, sm_scale=None, rows=None):
     """softmax(Q K^T * sm_scale) V in float64 (Sec. 2.1, first formula), one head;
     `rows` restricts the queries.  K, V may have another length than Q; the causal mask is then

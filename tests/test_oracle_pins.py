@@ -427,3 +427,46 @@ def test_output_rounding_matches_library_casts():
         lib = torch.from_numpy(x).to(td).float().numpy()
         assert np.array_equal(so._round_out(x, name), lib)
         assert np.array_equal(wl.round_to_dtype(x, name), lib)
+
+
+# ---- log-sum-exp of a row: the normaliser of Sec. 2.1 in the scale of the unsmoothed scores ----
+@pytest.mark.parametrize("causal", [False, True])
+def test_ref_lse_matches_library_logsumexp(causal):
+    q, k, _ = _head(N=90, d=16)
+    s = torch.from_numpy(q).double() @ torch.from_numpy(k).double().T / 4.0
+    if causal:
+        s = s.masked_fill(torch.ones(90, 90, dtype=torch.bool).triu(1), float("-inf"))
+    assert np.allclose(so.ref_lse_fp64(q, k, causal=causal), torch.logsumexp(s, dim=1).numpy(), rtol=1e-13, atol=1e-12)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("smooth_q_on", [False, True])
+def test_lse_approaches_the_definition_in_the_high_precision_limit(causal, smooth_q_on):
+    """With 16-bit codes the dequantized scores are the true ones to 1e-4, so m + log2 l plus the row
+    constant that smoothing K removed (Sec. 3.1) must reproduce ln sum exp(sm_scale q.k): a missing or
+    mis-signed constant, a missing log2(448) or a wrong base would be off by units."""
+    q, k, v = _head(N=300, d=32, seed=5, k_off=3.0, q_off=2.0)
+    _, pro = so.sage_attention_head(q, k, v, causal=causal, mode=32767, smooth_q_on=smooth_q_on, out_dtype="fp32",
+                                    want_lse=True)
+    ref = so.ref_lse_fp64(q, k, causal=causal)
+    assert np.abs(ref).max() > 5.0                      # the K offset makes the dropped constant large
+    assert np.abs(pro["lse"] - ref).max() < 2e-3
+    # and the quantized modes stay within their score error of it
+    for mode, tol in (("int8_fp8", 0.1), ("int4_fp8", 1.0)):
+        _, p2 = so.sage_attention_head(q, k, v, causal=causal, mode=mode, out_dtype="fp32", want_lse=True)
+        assert np.abs(p2["lse"] - ref).max() < tol
+
+
+def test_lse_merges_partial_results_over_disjoint_key_sets():
+    """out = sum_parts exp(lse_part - lse) out_part with lse = ln sum_parts exp(lse_part): the identity the
+    row statistic exists for, checked on the oracle's own outputs (each part smooths K with its own mean)."""
+    q, k, v = _head(N=256, d=32, seed=6)
+    full = so.ref_attn_fp64(q, k, v)
+    parts = [so.sage_attention_head(q, k[a:b], v[a:b], mode="int8_fp8", out_dtype="fp32", want_lse=True)
+             for a, b in ((0, 100), (100, 256))]
+    lse = np.stack([p[1]["lse"].astype(f64) for p in parts])
+    tot = np.log(np.exp(lse - lse.max(axis=0)).sum(axis=0)) + lse.max(axis=0)
+    merged = sum(np.exp(l - tot)[:, None] * p[0] for l, p in zip(lse, parts))
+    whole, _ = so.sage_attention_head(q, k, v, mode="int8_fp8", out_dtype="fp32")
+    assert wl.cos_sim(merged, full) > 0.998
+    assert wl.rel_l1(merged, full) < 1.5 * wl.rel_l1(whole, full) + 1e-3
