@@ -104,6 +104,13 @@ typedef struct sage_attn_args {
   void* stream;           /* hipStream_t, NULL = default stream */
   const int* cu_seqlens_q; /* device, [B + 1] prefix sums of the query lengths, or NULL: fixed length N */
   const int* cu_seqlens_k; /* device, [B + 1] prefix sums of the key lengths; NULL = cu_seqlens_q */
+  float* lse;             /* device, written if not NULL: [B, H, N] f32 (whatever the layout of q), or [H, total_q]
+                             for a variable-length batch.  Natural-log-sum-exp over the visible keys of
+                             sm_scale * <q_r, k_t> as the quantized path evaluates these scores: the final
+                             running maximum and sum of Algorithm 1 plus the row constant <q_r, mean(K)> that
+                             smoothing K removes from every score of a row (Sec. 3.1).  It is the weight needed
+                             to merge results computed over disjoint key sets: out = sum_i exp(lse_i - lse) out_i,
+                             lse = ln sum_i exp(lse_i).  -inf for a sequence without keys. */
 } sage_attn_args;
 
 /* Bytes of device scratch one call needs for these shapes (codes, scales, means, Delta-S).

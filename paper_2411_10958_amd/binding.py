@@ -38,7 +38,7 @@ class sage_attn_args(ctypes.Structure):
                 ("mode", ctypes.c_int), ("dtype", ctypes.c_int), ("flags", ctypes.c_int), ("group_map", ctypes.c_int), ("N_kv", ctypes.c_int), ("layout", ctypes.c_int),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("stream", ctypes.c_void_p),
-                ("cu_seqlens_q", ctypes.c_void_p), ("cu_seqlens_k", ctypes.c_void_p)]
+                ("cu_seqlens_q", ctypes.c_void_p), ("cu_seqlens_k", ctypes.c_void_p), ("lse", ctypes.c_void_p)]
 
 
 class sage_quant_out(ctypes.Structure):
@@ -151,9 +151,10 @@ def _alloc_workspace(args, device):
 
 def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
                      smooth_v=False, group_map="lane", layout="HND", cu_seqlens_q=None, cu_seqlens_k=None,
-                     max_seqlen_q=None, max_seqlen_k=None):
+                     max_seqlen_q=None, max_seqlen_k=None, return_lse=False):
     """Whole forward pass.  Returns `out` (allocated if not given).  With cu_seqlens_q the batch is a packed
-    variable-length one (see make_varlen_args) and `layout` is ignored."""
+    variable-length one (see make_varlen_args) and `layout` is ignored.  With return_lse the result is
+    (out, lse): lse float32 [B, H, N], or [H, total_q] for a variable-length batch."""
     if out is None:
         out = torch.empty_like(q)
     if cu_seqlens_q is not None:
@@ -162,12 +163,17 @@ def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_f
                              group_map=group_map)
     else:
         a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v, group_map, layout)
+    lse = None
+    if return_lse:
+        shape = (a.H, q.shape[0]) if cu_seqlens_q is not None else (a.B, a.H, a.N)
+        lse = torch.empty(shape, dtype=torch.float32, device=q.device)
+        a.lse = lse.data_ptr()
     keep = _alloc_workspace(a, q.device) if workspace is None else workspace
     if workspace is None and stream is not None:
         keep.record_stream(stream)   # allocated on the current stream, used on another one
     _check(load_library().sage_attn_fwd_ex(ctypes.byref(a)), "sage_attn_fwd_ex")
     del keep  # torch's caching allocator keeps the block alive for work already queued on its streams
-    return out
+    return (out, lse) if return_lse else out
 
 
 def make_varlen_args(q, k, v, out, cu_seqlens_q, cu_seqlens_k=None, max_seqlen_q=None, max_seqlen_k=None, **kw):

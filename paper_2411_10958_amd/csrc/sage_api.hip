@@ -40,6 +40,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   D->kg = a->group_map == SAGE_GROUPS_TOKEN ? 1 : (a->group_map == SAGE_GROUPS_FINE ? 4 : KGROUP);
   D->nhd = a->layout == SAGE_LAYOUT_NHD;
   D->seq.cu_q = a->cu_seqlens_q; D->seq.cu_k = a->cu_seqlens_k;
+  D->want_lse = a->lse != nullptr;
   const float sm = a->sm_scale > 0.0f ? a->sm_scale : (float)(1.0 / std::sqrt((double)a->d));
   D->kappa = sm * LOG2E;   // one FP32 rounding of the product of two FP32 values
   return SAGE_OK;
@@ -86,7 +87,8 @@ int sage_attn_core(const sage_attn_args* args) {
   if (st != SAGE_OK) return st;
   const Workspace w = make_workspace(D);
   if ((st = check_workspace(args, w)) != SAGE_OK) return st;
-  const Ptrs P = make_ptrs(args->q, args->k, args->v, args->out, args->workspace, w);
+  Ptrs P = make_ptrs(args->q, args->k, args->v, args->out, args->workspace, w);
+  P.lse = args->lse;
   return hip_status(launch_attention(D, P, (hipStream_t)args->stream));
 }
 
@@ -102,7 +104,7 @@ int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B,
   a.q = q; a.k = k; a.v = v; a.out = out;
   a.B = B; a.H = H; a.H_kv = H; a.N = N; a.d = d;
   a.causal = causal; a.sm_scale = sm_scale; a.mode = mode; a.dtype = SAGE_DT_BF16; a.flags = 0; a.group_map = SAGE_GROUPS_LANE; a.N_kv = 0; a.layout = SAGE_LAYOUT_HND;
-  a.cu_seqlens_q = nullptr; a.cu_seqlens_k = nullptr;
+  a.cu_seqlens_q = nullptr; a.cu_seqlens_k = nullptr; a.lse = nullptr;
   a.workspace = nullptr; a.workspace_bytes = 0; a.stream = nullptr;
   const size_t need = sage_attn_workspace_bytes(&a);
   if (need == 0) {

@@ -29,6 +29,9 @@ struct AttnParams {
   TensorMap om;           // where the rows of `out` start
   float kappa;
   SeqMap seq;             // variable-length batch: N, Nk, nQb, nKb describe the longest sequence
+  float* lse;             // null, or where the row log-sum-exp goes
+  const float* q_corr;    // kappa * <q_r, mean(K)> per query (read only with lse)
+  int B;
 };
 
 // Score accumulators of one wavefront for one 64-key block: 2 key tiles x (32 keys x 32
@@ -296,6 +299,13 @@ __device__ __forceinline__ void dma_b32(const void* gbase, unsigned voff, unsign
 __device__ __forceinline__ void use_now(int x) { asm volatile("" :: "v"(x)); }
 __device__ __forceinline__ void use_now(float x) { asm volatile("" :: "v"(x)); }
 
+// where query r of (batch b, head h) goes in the log-sum-exp output: [B, H, N], or [H, total_q] for a
+// variable-length batch
+__device__ __forceinline__ size_t lse_index(const AttnParams& p, const Seq& sq, int b, int h, int r) {
+  if (p.seq.cu_q) return (size_t)h * (size_t)p.seq.cu_q[p.B] + sq.q0 + r;
+  return ((size_t)b * p.H + h) * p.N + r;
+}
+
 template <int D, bool INT4, bool CAUSAL, bool BF16, int GM>
 __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const AttnParams p) {
   constexpr int KSC = GM == 0 ? 4 : (GM == 1 ? 16 : 64);    // key scales per block
@@ -334,6 +344,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
         *reinterpret_cast<uint4*>(o + row_offset(p.om, 0, (int)sq.q0 + row) + (idx % (D / 8)) * 8) =
             make_uint4(0u, 0u, 0u, 0u);
     }
+    if (p.lse && t < BQ && qb * BQ + t < sq.n) p.lse[lse_index(p, sq, b, h, qb * BQ + t)] = -INFINITY;
     return;
   }
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -504,6 +515,9 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   }
 
   int cur = 0;   // stage of block j
+  // exponent offset of the last block that was really processed (the running max minus log2 448): the
+  // pipeline's final update_max works on a stale stage and leaves st.m_run meaningless
+  float m_fin = -INFINITY;
 #define SAGE_X(GI_, MASKED_)                                                                         \
   do {                                                                                               \
     if constexpr ((GI_) < NQK) qk_step<D, INT4, (GI_) < NQK ? (GI_) : 0>(ka, qreg, raw);             \
@@ -541,6 +555,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     __builtin_amdgcn_sched_barrier(0);                                                               \
     SAGE_X(4, MASKED_); SAGE_X(5, MASKED_); SAGE_X(6, MASKED_); SAGE_X(7, MASKED_);                  \
     st.l_run = __fmaf_rn(alpha, st.l_run, ls);                                                       \
+    m_fin = m_sub;                                                                                   \
     Factors<GM> fn;                                                                                  \
     fn.set(dq, p.kappa, ks);                                                                         \
     SAGE_Y(0, MASKED_NEXT_); SAGE_Y(1, MASKED_NEXT_); SAGE_Y(2, MASKED_NEXT_); SAGE_Y(3, MASKED_NEXT_); /* Y */ \
@@ -574,6 +589,11 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     const unsigned u = __float_as_uint(l_tot);
     const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
     l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+  }
+  if (p.lse && half == 0 && query < sq.n) {
+    // ln sum_t exp(sm_scale <q, k_t>) = ln 2 * (m + log2(l) + the row constant smoothing K dropped); l_tot = 448 l
+    const float corr = p.q_corr[((size_t)bh * p.nQb + qb) * BQ + w * WQ + n];
+    p.lse[lse_index(p, sq, b, h, query)] = LN2 * ((m_fin + __builtin_amdgcn_logf(l_tot)) + corr);
   }
   if (query < sq.n) {
     unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) +
@@ -652,6 +672,7 @@ static hipError_t launch_attention_g(const Dims& Dm, const Ptrs& P, hipStream_t 
   p.H = Dm.H; p.Hkv = Dm.Hkv; p.N = Dm.N; p.Nk = Dm.Nk; p.nQb = Dm.nQb;
   p.om = make_tensor_map(Dm.nhd, Dm.H, Dm.N, Dm.d, Dm.seq.cu_q != nullptr); p.nKb = Dm.nKb;
   p.seq = Dm.seq;
+  p.lse = P.lse; p.q_corr = P.q_corr; p.B = Dm.B;
   p.total_tiles = Dm.B * Dm.H * Dm.nQb;
   p.kappa = Dm.kappa;
   const int grid = 8 * ((p.total_tiles + 7) / 8);

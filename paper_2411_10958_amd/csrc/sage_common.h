@@ -17,6 +17,7 @@ constexpr float E4M3_MAX = 448.0f;
 constexpr int STAT_ROWS = 256;  // tokens per workgroup of the column-statistics pass
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LOG2_448 = 8.807354922057604f;
+constexpr float LN2 = 0.6931471805599453f;
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
@@ -84,6 +85,7 @@ struct Dims {
   int qg, kg;  // queries / keys per stored scale: 2 / 16 (lane and block maps), 1 / 4 (fine), 1 / 1 (token)
   float kappa; // fl32(sm_scale * log2 e)
   SeqMap seq;  // variable-length batch: N, Nk, nQb, nKb then describe the longest sequence
+  int want_lse; // the caller asked for the row log-sum-exp
 };
 
 // Workspace map (all offsets multiples of 256 bytes).
@@ -116,8 +118,8 @@ struct Dims {
 //   k_sum, v_max (and v_sum): [B*Hkv][ceil(Nk/STAT_ROWS)][d] partial results of the statistics pass;
 //   v_sum, v_mean only with the smooth-V option (otherwise zero-sized).
 struct Workspace {
-  size_t k_sum, v_sum, v_max, k_mean, v_mean, v_scale, q_mean, q_scale, k_scale, q_codes, k_codes, v_codes,
-      delta_s, total;
+  size_t k_sum, v_sum, v_max, k_mean, v_mean, v_scale, q_mean, q_scale, k_scale, q_corr, q_codes, k_codes,
+      v_codes, delta_s, total;
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -146,6 +148,7 @@ inline Workspace make_workspace(const Dims& D) {
   w.q_mean = take(BH * D.nQb * D.d * sizeof(float));
   w.q_scale = take(BH * D.nQb * (BQ / D.qg) * sizeof(float));
   w.k_scale = take(BHkv * D.nKb * (BKV / D.kg) * sizeof(float));
+  w.q_corr = take(BH * D.nQb * BQ * sizeof(float));      // kappa * <q_r, mean(K)> per query (log-sum-exp output)
   w.q_codes = take(BH * D.nQb * q_slab_bytes(D.d, D.int4));
   w.k_codes = take(BHkv * D.nKb * k_block_bytes(D.d, D.int4));
   w.v_codes = take(BHkv * D.nKb * BKV * D.d);
@@ -159,7 +162,8 @@ struct Ptrs {
   void* out;
   double *k_sum, *v_sum;
   unsigned* v_max;
-  float *k_mean, *v_mean, *v_scale, *q_mean, *q_scale, *k_scale, *delta_s;
+  float *k_mean, *v_mean, *v_scale, *q_mean, *q_scale, *k_scale, *q_corr, *delta_s;
+  float* lse;
   int8_t *q_codes, *k_codes;
   uint8_t* v_codes;
 };
@@ -178,6 +182,8 @@ inline Ptrs make_ptrs(const void* q, const void* k, const void* v, void* out, vo
   p.q_mean = (float*)(b + w.q_mean);
   p.q_scale = (float*)(b + w.q_scale);
   p.k_scale = (float*)(b + w.k_scale);
+  p.q_corr = (float*)(b + w.q_corr);
+  p.lse = nullptr;
   p.q_codes = (int8_t*)(b + w.q_codes);
   p.k_codes = (int8_t*)(b + w.k_codes);
   p.v_codes = (uint8_t*)(b + w.v_codes);

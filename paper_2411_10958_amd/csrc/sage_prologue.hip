@@ -284,6 +284,28 @@ __global__ void k_finalize_vscale(const unsigned* __restrict__ v_max, float* __r
 }
 
 // ------------------------------------------------------------------------------------------
+// KV head of query head bh (G query heads per KV head)
+__device__ inline size_t kv_head(const TensorMap& qm, unsigned bh, int G) {
+  const unsigned b = bh / (unsigned)qm.heads, h = bh - b * (unsigned)qm.heads;
+  return (size_t)b * (qm.heads / G) + h / G;
+}
+// kappa * <q_r, mean(K)> for the rows of one thread group (the row constant that smoothing K drops
+// from the scores, Sec. 3.1; needed only for the log-sum-exp output): float64 products and sums,
+// one rounding.  x: this thread's 8 channels of RPT rows; NCG consecutive lanes share a row.
+template <int D, int NCG, int RPT>
+__device__ inline void row_constants(const float (&x)[RPT][8], float* out, int n_valid, const float* kbar8,
+                                     float kappa, int cg) {
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) {
+    double dot = 0.0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dot += (double)x[i][e] * (double)kbar8[e];
+#pragma unroll
+    for (int m = NCG / 2; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, 64);
+    if (cg == 0 && i < n_valid) out[i] = (float)((double)kappa * dot);
+  }
+}
+
 // Q, 8-bit variant: pair-group quantization psi_Q(Q_i), no smoothing (the 8-bit kernel of the
 // paper's "two kernel implementations" leaves Q as it is).  One workgroup per 128 queries of one
 // (batch, head).
@@ -291,7 +313,8 @@ template <bool BF16, int D>
 __global__ void __launch_bounds__(256) k_quant_q8(const unsigned short* __restrict__ Q,
                                                   float* __restrict__ q_scale, int8_t* __restrict__ q_codes,
                                                   int N, int Nk, int nQb, int block_groups, int qg,
-                                                  TensorMap qm, SeqMap sm) {
+                                                  TensorMap qm, SeqMap sm, float* __restrict__ q_corr,
+                                                  const float* __restrict__ k_mean, int G, float kappa) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;  // RPT rows per thread (8 or 4)
   constexpr int QMAX = 127;
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
@@ -314,6 +337,8 @@ __global__ void __launch_bounds__(256) k_quant_q8(const unsigned short* __restri
       for (int e = 0; e < 8; ++e) x[i][e] = 0.0f;
     }
   }
+  if (q_corr) row_constants<D, NCG, RPT>(x, q_corr + (bh * nQb + qb) * BQ + rg * RPT, valid - rg * RPT,
+                                         k_mean + kv_head(qm, blockIdx.y, G) * D + cg * 8, kappa, cg);
   // codes go to LDS in the packed order of this 128-query slab (contiguous in the workspace) and
   // leave as coalesced 16-byte stores
   __shared__ uint4 s_codes[BQ * D / 16];
@@ -376,7 +401,9 @@ template <bool BF16, int D>
 __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restrict__ Q,
                                                   float* __restrict__ q_mean, float* __restrict__ q_scale,
                                                   int8_t* __restrict__ q_codes, int N, int Nk, int nQb,
-                                                  int block_groups, int qg, TensorMap qm, SeqMap sm) {
+                                                  int block_groups, int qg, TensorMap qm, SeqMap sm,
+                                                  float* __restrict__ q_corr, const float* __restrict__ k_mean,
+                                                  int G, float kappa) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;   // load map: RPT rows x 8 channels
   constexpr int CPL = D / 4, CPC = CPL / 8;                      // quantization map: 2 rows x CPL channels
   constexpr int QMAX = 7;
@@ -433,12 +460,18 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
   const int pair = t >> 2, c4 = t & 3;
   float x[2][CPL];
   float mxr[2] = {0.0f, 0.0f};          // per query; the pair shares the larger one unless qg == 1
+  double dotk[2] = {0.0, 0.0};          // <q_r, mean(K)> over this thread's channels (log-sum-exp output only)
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int r = 2 * pair + i;
 #pragma unroll
     for (int j = 0; j < CPC; ++j) {
       unpack8<BF16>(s_raw[r * NCG + ((c4 * CPC + j) ^ swz(r))], &x[i][8 * j]);
+      if (q_corr) {
+        const float* kb = k_mean + kv_head(qm, blockIdx.y, G) * D + CPL * c4 + 8 * j;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dotk[i] += (double)x[i][8 * j + e] * (double)kb[e];
+      }
       if (r < valid) {
         const float4 m0 = *reinterpret_cast<const float4*>(&s_mean[CPL * c4 + 8 * j]);
         const float4 m1 = *reinterpret_cast<const float4*>(&s_mean[CPL * c4 + 8 * j + 4]);
@@ -452,6 +485,11 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
     }
     mxr[i] = fmaxf(mxr[i], __shfl_xor(mxr[i], 1, 64));
     mxr[i] = fmaxf(mxr[i], __shfl_xor(mxr[i], 2, 64));
+    if (q_corr) {
+      dotk[i] += __shfl_xor(dotk[i], 1, 64);
+      dotk[i] += __shfl_xor(dotk[i], 2, 64);
+      if (c4 == 0 && r < valid) q_corr[(bh * nQb + qb) * BQ + r] = (float)((double)kappa * dotk[i]);
+    }
   }
   if (qg == 2) mxr[0] = mxr[1] = fmaxf(mxr[0], mxr[1]);
   if (block_groups) {       // per-block granularity: one scale for the whole 128-query block
@@ -788,14 +826,21 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
                   km = make_tensor_map(Dm.nhd, Dm.Hkv, Dm.Nk, Dm.d, varlen);
   const SeqMap sm = Dm.seq;
   const float* v_mean = Dm.smooth_v ? P.v_mean : nullptr;
-  // Q first: it depends on nothing, and with the statistics pass next to the K and V quantizers
-  // those re-read K and V while the chip's memory-side cache still holds most of them
-  if constexpr (INT4)
-    k_quant_q4<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
-                                                     Dm.block_groups, Dm.qg, qm, sm);
-  else
-    k_quant_q8<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
-                                                     Dm.block_groups, Dm.qg, qm, sm);
+  // Q goes first: it depends on nothing, and with the statistics pass next to the K and V quantizers
+  // those re-read K and V while the chip's memory-side cache still holds most of them.  Only when
+  // the log-sum-exp output is wanted does Q wait for mean(K) (its row constants need it).
+  auto quant_q = [&]() {
+    float* corr = Dm.want_lse ? P.q_corr : nullptr;
+    if constexpr (INT4)
+      k_quant_q4<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
+                                                       Dm.block_groups, Dm.qg, qm, sm, corr, P.k_mean,
+                                                       Dm.H / Dm.Hkv, Dm.kappa);
+    else
+      k_quant_q8<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
+                                                       Dm.block_groups, Dm.qg, qm, sm, corr, P.k_mean,
+                                                       Dm.H / Dm.Hkv, Dm.kappa);
+  };
+  if (!Dm.want_lse) quant_q();
   const int nchunk = (int)gstat.x;
   if (Dm.smooth_v) {
     k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.N, Dm.Nk, km, sm);
@@ -808,6 +853,7 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
                                                         nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm);
   }
+  if (Dm.want_lse) quant_q();
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
                                                               P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
                                                               Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.kg,

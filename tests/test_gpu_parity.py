@@ -367,6 +367,82 @@ def test_varlen_batch_equals_one_sequence_at_a_time(lens_q, lens_k, d, dtype, H,
     assert checked
 
 
+# ---- row log-sum-exp (the weight for merging results over disjoint key sets) ---------------------
+LSE_CASES = [
+    # N, N_kv, d, dtype, H, Hkv, causal
+    (333, 333, 128, "bf16", 2, 1, True),
+    (640, 640, 64, "fp16", 2, 2, False),
+    (130, 500, 128, "bf16", 2, 2, True),
+]
+
+
+def _lse_close(got, ref):
+    # both sides round the same real number to FP32 after a few FP32 operations (running sum in another
+    # order, hardware log2 to 1 ulp): a few units of the last place of the largest term
+    tol = 1e-5 * np.maximum(1.0, np.abs(ref)) + 1e-5
+    assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= tol), \
+        f"worst {np.abs(got - ref).max():.3e}"
+
+
+@pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("N,Nk,d,dtype,H,Hkv,causal", LSE_CASES)
+def test_lse_matches_oracle(N, Nk, d, dtype, H, Hkv, causal, mode):
+    pa = _pa()
+    spec = _spec(N, d, dtype, H, Hkv, B=2, causal=causal).with_(N_kv=Nk)
+    data, (q, k, v) = _gpu_inputs(spec)
+    print(f"lse case N={N} N_kv={Nk} d={d} {dtype} H={H}/{Hkv} causal={causal} mode={mode}", flush=True)
+    plain = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode)
+    out, lse = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, return_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out, plain)                      # asking for it changes nothing else
+    assert lse.shape == (2, H, N)
+    g = H // Hkv
+    for b in range(2):
+        for h in range(H):
+            _, pro = so.sage_attention_head(data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g], causal=causal,
+                                            mode=mode, out_dtype="fp32", want_lse=True)
+            _lse_close(lse[b, h].cpu().numpy(), pro["lse"])
+    full = so.ref_lse_fp64(data["q"][1, 0], data["k"][1, 0], causal=causal)
+    assert np.abs(lse[1, 0].cpu().numpy() - full).max() < (1.0 if mode == "int4_fp8" else 0.1)
+
+
+def test_lse_of_a_packed_batch_and_merge_of_key_halves():
+    """[H, total_q] layout for a variable-length batch; and the use the statistic exists for: the keys of
+    every sequence split in two, both parts attended separately, merged with their lse."""
+    pa = _pa()
+    lens = [200, 77, 333]
+    seqs, q, k, v, cu_q, _ = _packed_batch(lens, lens, 128, "bf16", 4, 2, False)
+    out, lse = pa.sage_attn_fwd_ex(q, k, v, mode="int8_fp8", cu_seqlens_q=cu_q, return_lse=True)
+    torch.cuda.synchronize()
+    assert lse.shape == (4, sum(lens))
+    off = np.concatenate([[0], np.cumsum(lens)])
+    for b, n in enumerate(lens):
+        sl = slice(off[b], off[b + 1])
+        o1, l1 = pa.sage_attn_fwd_ex(q[sl].unsqueeze(0).contiguous(), k[sl].unsqueeze(0).contiguous(),
+                                     v[sl].unsqueeze(0).contiguous(), mode="int8_fp8", layout="NHD", return_lse=True)
+        torch.cuda.synchronize()
+        assert torch.equal(l1[0], lse[:, sl]) and torch.equal(o1[0], out[sl])
+        # two key halves of sequence b, merged
+        parts = []
+        for a0, a1 in ((0, n // 2), (n // 2, n)):
+            ks = k[off[b] + a0:off[b] + a1].unsqueeze(0).contiguous()
+            vs = v[off[b] + a0:off[b] + a1].unsqueeze(0).contiguous()
+            parts.append(pa.sage_attn_fwd_ex(q[sl].unsqueeze(0).contiguous(), ks, vs, mode="int8_fp8", layout="NHD",
+                                             return_lse=True))
+        torch.cuda.synchronize()
+        ls = torch.stack([p[1][0] for p in parts]).double()                # [2, H, n]
+        tot = torch.logsumexp(ls, dim=0)
+        merged = sum(torch.exp(l - tot).transpose(0, 1)[..., None] * p[0][0].double() for l, p in zip(ls, parts))
+        qn, kn, vn = seqs[b]
+        full = np.stack([so.ref_attn_fp64(qn[h], kn[h // 2], vn[h // 2]) for h in range(4)])   # [H, n, d]
+        got = merged.cpu().numpy().transpose(1, 0, 2)
+        whole = wl.from_torch(out[sl]).transpose(1, 0, 2)
+        assert wl.cos_sim(got, full) > 0.997
+        assert wl.rel_l1(got, full) < 1.5 * wl.rel_l1(whole, full) + 1e-3
+        lse_full = np.stack([so.ref_lse_fp64(qn[h], kn[h // 2]) for h in range(4)])
+        assert np.abs(tot.cpu().numpy() - lse_full).max() < 0.1
+
+
 def test_plain_signature_and_repeatability():
     pa = _pa()
     spec = _spec(384, 128, "bf16", 2, 2)
