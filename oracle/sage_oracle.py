@@ -85,6 +85,50 @@ def e4m3_encode(x):
     return code.astype(np.uint8)
 
 
+# --------------------------------------------------------------------------- FP8 E5M2
+# The other 8-bit float the paper weighs for P~ and V (Sec. 3.3 and the data-type table: E4M3 is
+# chosen because it is the more accurate one); kept as a variant so that the comparison can be made.
+E5M2_MAX = 57344.0
+LOG2_57344_F32 = np.float32(np.log2(57344.0))
+
+
+def e5m2_decode(codes):
+    """OCP FP8 E5M2 byte codes (IEEE-like: exponent field 31 is inf / NaN) -> float64."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    s = np.where(c & 0x80, -1.0, 1.0)
+    e = (c >> 2) & 0x1F
+    m = c & 0x3
+    sub = np.ldexp(m.astype(f64), -16)                     # exponent field 0: m * 2^-16
+    nor = np.ldexp(1.0 + m.astype(f64) / 4.0, e - 15)
+    v = np.where(e == 0, sub, nor)
+    v = np.where(e == 31, np.where(m == 0, np.inf, np.nan), v)
+    return s * v
+
+
+def e5m2_encode(x):
+    """Round-to-nearest-even, saturating (|x| > 57344 -> +-57344) encoder to E5M2 byte codes."""
+    x = np.asarray(x, dtype=f64)
+    sign = np.signbit(x)
+    a = np.minimum(np.abs(x), E5M2_MAX)
+    _, ex = np.frexp(a)
+    e_unb = np.maximum(ex - 1, -14)            # subnormals share the exponent -14
+    step = np.ldexp(1.0, e_unb - 2)            # 2 mantissa bits
+    v = np.minimum(np.rint(a / step) * step, E5M2_MAX)
+    _, ex2 = np.frexp(v)
+    e_unb2 = np.maximum(ex2 - 1, -14)
+    is_sub = v < 2.0 ** -14
+    mant = np.where(is_sub, np.rint(v * 2.0 ** 16), np.rint((v / np.ldexp(1.0, e_unb2) - 1.0) * 4.0))
+    efield = np.where(is_sub, 0, e_unb2 + 15)
+    code = (efield.astype(np.int64) << 2) | mant.astype(np.int64)
+    code = np.where(v == 0, 0, code)
+    code = code | np.where(sign, 0x80, 0)
+    return code.astype(np.uint8)
+
+
+_FP8 = {"e4m3": (E4M3_MAX, LOG2_448_F32, e4m3_encode, e4m3_decode),
+        "e5m2": (E5M2_MAX, LOG2_57344_F32, e5m2_encode, e5m2_decode)}
+
+
 # --------------------------------------------------------------------------- group maps
 def group_map(name, N, which):
     """Token -> quantization-group index, for `which` in {"q", "k"}.
@@ -178,21 +222,22 @@ def quantize_groups(X, groups, qmax):
     return delta, codes
 
 
-def quantize_v(V):
+def quantize_v(V, pv_fmt="e4m3"):
     """Per-channel FP8 quantization of V (Sec. 3.3; Algorithm 1 preprocessing):
-    delta_V[c] = max_n |V[n, c]| / 448, codes = E4M3(V / delta_V)."""
+    delta_V[c] = max_n |V[n, c]| / 448, codes = E4M3(V / delta_V)  (57344 and E5M2 for the variant)."""
+    fmax, _, enc, _ = _FP8[pv_fmt]
     V = np.asarray(V, f32)
-    delta = (np.abs(V).max(axis=0) / f32(E4M3_MAX)).astype(f32)
+    delta = (np.abs(V).max(axis=0) / f32(fmax)).astype(f32)
     with np.errstate(divide="ignore", invalid="ignore"):
         ratio = (V / delta[None, :]).astype(f32)
     ratio = np.where(delta[None, :] > 0, ratio, f32(0))
-    return delta, e4m3_encode(ratio)
+    return delta, enc(ratio)
 
 
 # --------------------------------------------------------------------------- prologue
 def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SMOOTH,
                   smooth_q_on=None, smooth_k_on=True, pv_exact=False, ds_blocks=None,
-                  smooth_v_on=False):
+                  smooth_v_on=False, pv_fmt="e4m3"):
     """Everything Algorithm 1 computes before the inner loop, for one (batch, head).
 
     Q: [N, d], K and V: [N_kv, d] float32 holding exactly representable 16-bit values (N_kv = N in
@@ -240,9 +285,10 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
     if pv_exact:
         dv, vc, vdec = np.ones(d, f32), None, np.asarray(V, f64)
     else:
-        dv, vc = quantize_v(V)
-        vdec = e4m3_decode(vc)                            # [N, d] float64, exact
+        dv, vc = quantize_v(V, pv_fmt)
+        vdec = _FP8[pv_fmt][3](vc)                        # [N, d] float64, exact
     return dict(N=N, Nk=Nk, d=d, kappa=kappa, qmax=qmax, kbar=kbar, qbar=qbar, delta_s=D, Q=np.asarray(Q, f32),
+                pv_fmt=pv_fmt,
                 q_codes=qc, q_scale=dq, q_groups=gq, k_codes=kc, k_scale=dk, k_groups=gk,
                 v_codes=vc, v_scale=dv, v_dec=vdec, pv_exact=pv_exact, bq=bq, vbar=vbar)
 
@@ -277,6 +323,7 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
     dq = pro["q_scale"][pro["q_groups"][rows]]
     vdec = pro["v_dec"]
     nr = len(rows)
+    fmax, log2_fmax, enc, dec = _FP8[pro["pv_fmt"]]       # static scale of P~: 1/448 (Sec. 3.3), or 1/57344
     m = np.full(nr, -np.inf, f32)
     l = np.zeros(nr, f32)                                 # 448 * (running sum of P~)
     O = np.zeros((nr, d), f32)
@@ -294,12 +341,12 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
         if causal:
             S = np.where(ks[None, :] > rows[:, None] + coff, f32(-np.inf), S)
         m_new = np.maximum(m, S.max(axis=1))
-        m_sub = (m_new - LOG2_448_F32).astype(f32)
+        m_sub = (m_new - log2_fmax).astype(f32)
         with np.errstate(invalid="ignore"):
             P448 = _exp2_f32((S - m_sub[:, None]).astype(f32))      # E = 448 * P~
             alpha = _exp2_f32((m - m_new).astype(f32))
         l = ((alpha * l).astype(f32).astype(f64) + P448.astype(f64).sum(axis=1)).astype(f32)
-        Phat = P448.astype(f64) if pro["pv_exact"] else e4m3_decode(e4m3_encode(P448))
+        Phat = P448.astype(f64) if pro["pv_exact"] else dec(enc(P448))
         R = (Phat @ vdec[ks]).astype(f32)                 # exact block sum, one rounding
         O = ((alpha[:, None] * O).astype(f32) + R).astype(f32)
         m = m_new
@@ -325,7 +372,7 @@ def row_lse(pro, rows, state):
     m, l = state["m"].astype(f64), state["l"].astype(f64)
     corr = f64(pro["kappa"]) * (pro["Q"][rows].astype(f64) @ pro["kbar"].astype(f64))
     with np.errstate(divide="ignore"):
-        return (np.log(2.0) * (m + np.log2(l / E4M3_MAX) + corr)).astype(f32)
+        return (np.log(2.0) * (m + np.log2(l / _FP8[pro["pv_fmt"]][0]) + corr)).astype(f32)
 
 
 def _round_out(x, dtype):

@@ -470,3 +470,30 @@ def test_lse_merges_partial_results_over_disjoint_key_sets():
     whole, _ = so.sage_attention_head(q, k, v, mode="int8_fp8", out_dtype="fp32")
     assert wl.cos_sim(merged, full) > 0.998
     assert wl.rel_l1(merged, full) < 1.5 * wl.rel_l1(whole, full) + 1e-3
+
+
+# ---- the E5M2 variant of the FP8 stage (Sec. 3.3 / the data-type table compare it with E4M3) ----
+def test_e5m2_codec_matches_library_cast_and_round_trips():
+    codes = np.arange(256, dtype=np.uint8)
+    lib = torch.from_numpy(codes).view(torch.float8_e5m2).to(torch.float64).numpy()
+    dec = so.e5m2_decode(codes)
+    assert np.array_equal(np.isnan(dec), np.isnan(lib)) and np.array_equal(dec[~np.isnan(dec)], lib[~np.isnan(lib)])
+    finite = np.isfinite(dec)
+    assert np.array_equal(so.e5m2_encode(dec[finite]), codes[finite])      # every finite code is a fixed point
+    rng = np.random.default_rng(3)
+    x = np.concatenate([rng.uniform(-57344, 57344, 4000), rng.normal(0, 1e-4, 2000), rng.normal(0, 3, 2000),
+                        [1.25 * 2.0 ** k for k in range(-16, 15)], [1.125, 1.375, 1.625, 1.875, 3.0e-5]]).astype(f32)
+    lib_codes = torch.from_numpy(x).to(torch.float8_e5m2).view(torch.uint8).numpy()
+    assert np.array_equal(so.e5m2_encode(x), lib_codes)          # round to nearest, ties to even, in range
+    assert so.e5m2_decode(so.e5m2_encode(np.array([1e9, -1e9]))).tolist() == [57344.0, -57344.0]   # saturating
+
+
+def test_e5m2_stage_is_less_accurate_than_e4m3():
+    """Two mantissa bits instead of three: the ordering of the paper's data-type comparison for P~V."""
+    q, k, v = _head(N=256, d=32, seed=2)
+    ref = so.ref_attn_fp64(q, k, v)
+    a, pa_ = so.sage_attention_head(q, k, v, mode="int8_fp8", out_dtype="fp32")
+    b, pb_ = so.sage_attention_head(q, k, v, mode="int8_fp8", out_dtype="fp32", pv_fmt="e5m2")
+    assert np.array_equal(pb_["v_scale"], (np.abs(v).max(axis=0) / f32(57344.0)).astype(f32))
+    assert wl.rel_l1(a, ref) < wl.rel_l1(b, ref) < 4 * wl.rel_l1(a, ref)
+    assert wl.cos_sim(b, ref) > 0.995
