@@ -18,7 +18,7 @@ if ROOT not in sys.path:
 PEAK_TOPS = 5000.0   # MI355X dense int8 / fp8 MFMA peak (both 5.0 POP/s)
 
 
-def cpu_baseline(spec, mode, budget_s=12.0, max_heads=32, smooth_v=False, gmap="g950"):
+def cpu_baseline(spec, mode, budget_s=12.0, max_heads=32, smooth_v=False, gmap="g950", pv_fmt="e4m3"):
     """The CPU oracle as it stands, timed on whole heads of the same workload (as many heads
     as fit in about budget_s seconds)."""
     import numpy as np
@@ -34,7 +34,8 @@ def cpu_baseline(spec, mode, budget_s=12.0, max_heads=32, smooth_v=False, gmap="
         qkv = (wl.make_head(spec, "q", 0, h), wl.make_head(spec, "k", 0, h * spec.H_kv // spec.H),
                wl.make_head(spec, "v", 0, h * spec.H_kv // spec.H))
         t0 = time.perf_counter()
-        o = so.sage_attention_head(*qkv, causal=spec.causal, mode=mode, out_dtype="fp32", smooth_v_on=smooth_v, gmap=gmap)[0]
+        o = so.sage_attention_head(*qkv, causal=spec.causal, mode=mode, out_dtype="fp32", smooth_v_on=smooth_v, gmap=gmap,
+                                   pv_fmt=pv_fmt)[0]
         dt += time.perf_counter() - t0
         heads.append((0, h)); ins.append(qkv); outs.append(o)
         if dt > budget_s:
@@ -58,6 +59,8 @@ def main():
     ap.add_argument("--group-map", default="lane", choices=["lane", "block", "fine", "token"],
                     help="quantization granularity of Q and K: the default lane groups, one scale per block, "
                          "per query and 4 keys, or per token")
+    ap.add_argument("--pv-format", default="e4m3", choices=["e4m3", "e5m2"],
+                    help="8-bit float format of P~ and V: the paper's E4M3, or E5M2 for the comparison")
     ap.add_argument("--smooth-v", action="store_true",
                     help="the optional smooth-V technique (one more pass over V in the prologue)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -83,7 +86,7 @@ def main():
     q, k, v = (wl.to_torch(data[n], spec.dtype, dev) for n in "qkv")
     out = torch.empty_like(q)
     a = pa.make_args(q, k, v, out, causal=spec.causal, mode=args.mode, smooth_v=args.smooth_v,
-                     group_map=args.group_map)
+                     group_map=args.group_map, pv_format=args.pv_format)
     ws = torch.empty(pa.sage_attn_workspace_bytes(a), dtype=torch.uint8, device=dev)
     a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel()
 
@@ -147,7 +150,7 @@ def main():
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8+fp8" if args.mode == "int8_fp8" else "int4+fp8", "data": "synthetic",
         "config": {"workload": f"{spec.name}: B={spec.B} H={spec.H} H_kv={spec.H_kv} N={spec.N} d={spec.d} "
-                               f"{spec.dtype} causal={spec.causal}", "mode": args.mode, "smooth_v": bool(args.smooth_v), "group_map": args.group_map,
+                               f"{spec.dtype} causal={spec.causal}", "mode": args.mode, "smooth_v": bool(args.smooth_v), "group_map": args.group_map, "pv_format": args.pv_format,
                    "ops_formula": "4*B*H*N^2*d" + ("/2" if spec.causal else "")},
         "breakdown_ms": {"prologue": round(ms_pro, 4), "attention_kernel": round(ms_core, 4)},
         "roofline": {"bound": "mfma", "kernel": "k_attn_fwd", "achieved": round(core_tops, 2), "peak": PEAK_TOPS,
@@ -161,7 +164,7 @@ def main():
         from oracle import sage_oracle as so
         base, heads, ins, outs = cpu_baseline(spec, args.mode, smooth_v=args.smooth_v,
                                                 gmap={"lane": "g950", "block": "per_block", "fine": "fine",
-                                                      "token": "per_token"}[args.group_map])
+                                                      "token": "per_token"}[args.group_map], pv_fmt=args.pv_format)
         res["cpu_baseline"] = base
         got = np.stack([wl.from_torch(out[b, h]) for b, h in heads])
         ref = np.stack(outs)

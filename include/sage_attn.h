@@ -73,6 +73,10 @@ enum { SAGE_FLAG_SMOOTH_V = 1 };
    scale per query and per key (per-token quantization, Sec. 3.2): a factor per score, not free.
    Queries / keys per entry of q_scale / k_scale: 2 / 16 (LANE, BLOCK), 1 / 4 (FINE), 1 / 1 (TOKEN). */
 enum { SAGE_GROUPS_LANE = 0, SAGE_GROUPS_BLOCK = 1, SAGE_GROUPS_FINE = 2, SAGE_GROUPS_TOKEN = 3 };
+/* 8-bit float format of P~ and V (Sec. 3.3; the paper's data-type comparison): E4M3 (the paper's choice,
+   static scale 1/448 for P~) or E5M2 (static scale 1/57344; one mantissa bit less, kept for the
+   comparison; only with SAGE_GROUPS_LANE / _BLOCK). */
+enum { SAGE_PV_E4M3 = 0, SAGE_PV_E5M2 = 1 };
 /* Memory order of the four tensors (all contiguous): heads outside tokens, [B, H, N, d], or tokens
    outside heads, [B, N, H, d] (k, v: H_kv and N_kv).  The workspace layouts do not depend on it. */
 enum { SAGE_LAYOUT_HND = 0, SAGE_LAYOUT_NHD = 1 };
@@ -111,6 +115,7 @@ typedef struct sage_attn_args {
                              smoothing K removes from every score of a row (Sec. 3.1).  It is the weight needed
                              to merge results computed over disjoint key sets: out = sum_i exp(lse_i - lse) out_i,
                              lse = ln sum_i exp(lse_i).  -inf for a sequence without keys. */
+  int pv_format;          /* SAGE_PV_*; 0 = E4M3 */
 } sage_attn_args;
 
 /* Bytes of device scratch one call needs for these shapes (codes, scales, means, Delta-S).
@@ -139,7 +144,7 @@ void sage_attn_release(void);
    All pointers are device buffers the caller allocates; a NULL member is skipped.
      q_codes [B,H,N,d] int8       codes of gamma(Q) (int4 mode) or Q (int8 mode), Sec. 3.2
      k_codes [B,H_kv,N_kv,d] int8    codes of gamma(K)
-     v_codes [B,H_kv,N_kv,d] uint8   E4M3 codes of V / delta_V, Sec. 3.3
+     v_codes [B,H_kv,N_kv,d] uint8   E4M3 (or E5M2, see pv_format) codes of V / delta_V, Sec. 3.3
      q_scale [B,H,ceil(N/2)] f32  delta_Q per query group ([B,H,N] with SAGE_GROUPS_FINE / _TOKEN)
      k_scale [B,H_kv,ceil(N_kv/16)] f32   (ceil(N_kv/4) with SAGE_GROUPS_FINE, N_kv with SAGE_GROUPS_TOKEN)
      v_scale [B,H_kv,d] f32       delta_V per channel

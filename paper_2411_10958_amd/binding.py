@@ -18,6 +18,8 @@ _GROUP_SIZES = {0: (2, 16), 1: (2, 16), 2: (1, 4), 3: (1, 1)}     # queries, key
 SAGE_LAYOUT_HND, SAGE_LAYOUT_NHD = 0, 1
 _LAYOUTS = {"HND": 0, "NHD": 1, 0: 0, 1: 1}
 _MODES = {"int4_fp8": 0, "int8_fp8": 1, 0: 0, 1: 1}
+SAGE_PV_E4M3, SAGE_PV_E5M2 = 0, 1
+_PV_FORMATS = {"e4m3": 0, "e5m2": 1, 0: 0, 1: 1}
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -38,7 +40,8 @@ class sage_attn_args(ctypes.Structure):
                 ("mode", ctypes.c_int), ("dtype", ctypes.c_int), ("flags", ctypes.c_int), ("group_map", ctypes.c_int), ("N_kv", ctypes.c_int), ("layout", ctypes.c_int),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("stream", ctypes.c_void_p),
-                ("cu_seqlens_q", ctypes.c_void_p), ("cu_seqlens_k", ctypes.c_void_p), ("lse", ctypes.c_void_p)]
+                ("cu_seqlens_q", ctypes.c_void_p), ("cu_seqlens_k", ctypes.c_void_p), ("lse", ctypes.c_void_p),
+                ("pv_format", ctypes.c_int)]
 
 
 class sage_quant_out(ctypes.Structure):
@@ -103,7 +106,7 @@ def _ptr(t):
 
 
 def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
-              smooth_v=False, group_map="lane", layout="HND"):
+              smooth_v=False, group_map="lane", layout="HND", pv_format="e4m3"):
     """Fills a sage_attn_args from torch tensors q [B,H,N,d], k/v [B,H_kv,N_kv,d] (layout "HND") or
     q [B,N,H,d], k/v [B,N_kv,H_kv,d] (layout "NHD"), contiguous, on the GPU.  `workspace` is a uint8 GPU tensor (or None); `stream` a torch.cuda.Stream (None = the
     current one)."""
@@ -127,6 +130,7 @@ def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", wo
     a.group_map = _GROUPS[group_map]
     a.N_kv = Nk
     a.layout = _LAYOUTS[layout]
+    a.pv_format = _PV_FORMATS[pv_format]
     if workspace is not None:
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     else:
@@ -151,7 +155,7 @@ def _alloc_workspace(args, device):
 
 def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
                      smooth_v=False, group_map="lane", layout="HND", cu_seqlens_q=None, cu_seqlens_k=None,
-                     max_seqlen_q=None, max_seqlen_k=None, return_lse=False):
+                     max_seqlen_q=None, max_seqlen_k=None, return_lse=False, pv_format="e4m3"):
     """Whole forward pass.  Returns `out` (allocated if not given).  With cu_seqlens_q the batch is a packed
     variable-length one (see make_varlen_args) and `layout` is ignored.  With return_lse the result is
     (out, lse): lse float32 [B, H, N], or [H, total_q] for a variable-length batch."""
@@ -160,9 +164,9 @@ def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_f
     if cu_seqlens_q is not None:
         a = make_varlen_args(q, k, v, out, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, max_seqlen_k, causal=causal,
                              sm_scale=sm_scale, mode=mode, workspace=workspace, stream=stream, smooth_v=smooth_v,
-                             group_map=group_map)
+                             group_map=group_map, pv_format=pv_format)
     else:
-        a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v, group_map, layout)
+        a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v, group_map, layout, pv_format)
     lse = None
     if return_lse:
         shape = (a.H, q.shape[0]) if cu_seqlens_q is not None else (a.B, a.H, a.N)
@@ -226,9 +230,10 @@ def sage_attn_release():
 
 
 def sage_attn_quant(q, k, v, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, want=None,
-                    smooth_v=False, group_map="lane"):
+                    smooth_v=False, group_map="lane", pv_format="e4m3"):
     """Preprocessing only; returns (dict of torch tensors in plain layouts, args, workspace)."""
-    a = make_args(q, k, v, None, causal, sm_scale, mode, workspace, smooth_v=smooth_v, group_map=group_map)
+    a = make_args(q, k, v, None, causal, sm_scale, mode, workspace, smooth_v=smooth_v, group_map=group_map,
+                  pv_format=pv_format)
     ws = _alloc_workspace(a, q.device) if workspace is None else workspace
     B, H, N, d = q.shape
     Hkv, Nk = k.shape[1], k.shape[2]

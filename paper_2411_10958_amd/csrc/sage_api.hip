@@ -21,6 +21,8 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if ((a->flags & ~SAGE_FLAG_SMOOTH_V) != 0) return SAGE_ERR_UNSUPPORTED;
   if (a->group_map < SAGE_GROUPS_LANE || a->group_map > SAGE_GROUPS_TOKEN) return SAGE_ERR_UNSUPPORTED;
   if (a->layout != SAGE_LAYOUT_HND && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
+  if (a->pv_format != SAGE_PV_E4M3 && a->pv_format != SAGE_PV_E5M2) return SAGE_ERR_UNSUPPORTED;
+  if (a->pv_format == SAGE_PV_E5M2 && a->group_map > SAGE_GROUPS_BLOCK) return SAGE_ERR_UNSUPPORTED;
   if (a->cu_seqlens_k && !a->cu_seqlens_q) return SAGE_ERR_INVALID_ARG;
   if (a->cu_seqlens_q && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
   if (need_io && (!a->q || !a->k || !a->v || !a->out)) return SAGE_ERR_INVALID_ARG;
@@ -41,6 +43,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   D->nhd = a->layout == SAGE_LAYOUT_NHD;
   D->seq.cu_q = a->cu_seqlens_q; D->seq.cu_k = a->cu_seqlens_k;
   D->want_lse = a->lse != nullptr;
+  D->e5m2 = a->pv_format == SAGE_PV_E5M2;
   const float sm = a->sm_scale > 0.0f ? a->sm_scale : (float)(1.0 / std::sqrt((double)a->d));
   D->kappa = sm * LOG2E;   // one FP32 rounding of the product of two FP32 values
   return SAGE_OK;
@@ -104,7 +107,7 @@ int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B,
   a.q = q; a.k = k; a.v = v; a.out = out;
   a.B = B; a.H = H; a.H_kv = H; a.N = N; a.d = d;
   a.causal = causal; a.sm_scale = sm_scale; a.mode = mode; a.dtype = SAGE_DT_BF16; a.flags = 0; a.group_map = SAGE_GROUPS_LANE; a.N_kv = 0; a.layout = SAGE_LAYOUT_HND;
-  a.cu_seqlens_q = nullptr; a.cu_seqlens_k = nullptr; a.lse = nullptr;
+  a.cu_seqlens_q = nullptr; a.cu_seqlens_k = nullptr; a.lse = nullptr; a.pv_format = SAGE_PV_E4M3;
   a.workspace = nullptr; a.workspace_bytes = 0; a.stream = nullptr;
   const size_t need = sage_attn_workspace_bytes(&a);
   if (need == 0) {

@@ -182,7 +182,7 @@ __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2
 
 // update_max: running max over the block's 64 dequantized scores of this lane's query (Eq. 1 /
 // Algorithm 1); returns alpha = 2^(m_old - m_new) and, in m_sub, the exponent offset of the block.
-template <int D, bool INT4, int GM>
+template <int D, bool INT4, int GM, bool E5M2>
 __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2], const Factors<GM>& fac,
                                             float& m_sub) {
   float mx;
@@ -222,14 +222,14 @@ __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2
   }
   const float m_new = fmaxf(st.m_run, mx);
   const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_new);   // 2^-inf = 0 on the first block
-  m_sub = m_new - LOG2_448;                                       // folds the *448 of Sec. 3.3
+  m_sub = m_new - (E5M2 ? LOG2_57344 : LOG2_448);                 // folds the *448 of Sec. 3.3
   st.m_run = m_new;
   return alpha;
 }
 
 // exp_group: 448 * P~ = 2^(S - m_sub) for the group (INT8 mode: S = sc * c, fused), its row-sum share
 // added to ls, its FP8 codes written into word 4*KT + G of the P~ operand.
-template <bool INT4, bool MASKED, int GM, int KT, int G>
+template <bool INT4, bool MASKED, int GM, bool E5M2, int KT, int G>
 __device__ __forceinline__ void exp_group(const v16i (&acc)[2], const Factors<GM>& fac, float m_sub, v8i& pb,
                                           float& ls) {
   float e[4];
@@ -247,8 +247,13 @@ __device__ __forceinline__ void exp_group(const v16i (&acc)[2], const Factors<GM
     ls += e[r];
   }
   int wd = __float_as_int(e[0]);   // any value: both halves are overwritten below
-  wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[0], e[1], wd, false);
-  wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[2], e[3], wd, true);
+  if constexpr (E5M2) {
+    wd = __builtin_amdgcn_cvt_pk_bf8_f32(e[0], e[1], wd, false);
+    wd = __builtin_amdgcn_cvt_pk_bf8_f32(e[2], e[3], wd, true);
+  } else {
+    wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[0], e[1], wd, false);
+    wd = __builtin_amdgcn_cvt_pk_fp8_f32(e[2], e[3], wd, true);
+  }
   pb[KT * 4 + G] = wd;
 }
 
@@ -268,14 +273,15 @@ __device__ __forceinline__ void block_rescale(RowState<D>& st, float alpha) {
     }
   }
 }
-template <int D, int CT>
+template <int D, int CT, bool E5M2>
 __device__ __forceinline__ void pv_step(RowState<D>& st, const v4i (&va)[2 * (D / 32)], const v8i& pb) {
   v8i a;
   const v4i a0 = va[CT * 2 + 0];
   const v4i a1 = va[CT * 2 + 1];
   a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
   a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
-  st.O[CT] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, st.O[CT], 0, 0, 0, 0, 0, 0);
+  // operand formats: 0 = E4M3, 1 = E5M2, for both V^ (A) and P^ (B)
+  st.O[CT] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, st.O[CT], E5M2 ? 1 : 0, E5M2 ? 1 : 0, 0, 0, 0, 0);
 }
 
 #ifndef SAGE_WAVES_PER_SIMD
@@ -306,7 +312,7 @@ __device__ __forceinline__ size_t lse_index(const AttnParams& p, const Seq& sq, 
   return ((size_t)b * p.H + h) * p.N + r;
 }
 
-template <int D, bool INT4, bool CAUSAL, bool BF16, int GM>
+template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, bool E5M2>
 __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const AttnParams p) {
   constexpr int KSC = GM == 0 ? 4 : (GM == 1 ? 16 : 64);    // key scales per block
   constexpr int QG = GM == 0 ? QGROUP : 1;                  // queries per scale
@@ -510,7 +516,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     Factors<GM> fn;
     fn.set(dq, p.kappa, ks);
     if (n_plain > 0) SAGE_DEQ_ALL(false, 0); else SAGE_DEQ_ALL(true, 0);
-    alpha = update_max<D, INT4, GM>(st, sc, fn, m_sub);
+    alpha = update_max<D, INT4, GM, E5M2>(st, sc, fn, m_sub);
     fj = fn;
   }
 
@@ -521,13 +527,13 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
 #define SAGE_X(GI_, MASKED_)                                                                         \
   do {                                                                                               \
     if constexpr ((GI_) < NQK) qk_step<D, INT4, (GI_) < NQK ? (GI_) : 0>(ka, qreg, raw);             \
-    exp_group<INT4, MASKED_, GM, (GI_) / 4, (GI_) % 4>(sc, fj, m_sub, pb, ls);                       \
+    exp_group<INT4, MASKED_, GM, E5M2, (GI_) / 4, (GI_) % 4>(sc, fj, m_sub, pb, ls);                 \
     __builtin_amdgcn_sched_barrier(0);                                                               \
   } while (0)
 #define SAGE_Y(CT_, MASKED_)                                                                         \
   do {                                                                                               \
     if constexpr ((CT_) < CT) {                                                                      \
-      pv_step<D, (CT_) < CT ? (CT_) : 0>(st, va, pb);                                                \
+      pv_step<D, (CT_) < CT ? (CT_) : 0, E5M2>(st, va, pb);                                          \
       SAGE_DEQ(MASKED_, (CT_) * GPC, (j + 1) * BKV);                                                 \
       SAGE_DEQ(MASKED_, (CT_) * GPC + 1, (j + 1) * BKV);                                             \
       if constexpr (GPC == 4) {                                                                      \
@@ -559,7 +565,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     Factors<GM> fn;                                                                                  \
     fn.set(dq, p.kappa, ks);                                                                         \
     SAGE_Y(0, MASKED_NEXT_); SAGE_Y(1, MASKED_NEXT_); SAGE_Y(2, MASKED_NEXT_); SAGE_Y(3, MASKED_NEXT_); /* Y */ \
-    alpha = update_max<D, INT4, GM>(st, sc, fn, m_sub);                                              \
+    alpha = update_max<D, INT4, GM, E5M2>(st, sc, fn, m_sub);                                              \
     fj = fn;                                                                                         \
     cur = nx1;                                                                                       \
   } while (0)
@@ -662,7 +668,7 @@ hipError_t launch_debug_mfma_fp8(const void* a, const void* b, const float* c, f
   return hipGetLastError();
 }
 
-template <int D, bool INT4, bool CAUSAL, bool BF16, int GM>
+template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, bool E5M2>
 static hipError_t launch_attention_g(const Dims& Dm, const Ptrs& P, hipStream_t s) {
   AttnParams p;
   p.q_codes = P.q_codes; p.k_codes = P.k_codes; p.v_codes = P.v_codes;
@@ -676,14 +682,15 @@ static hipError_t launch_attention_g(const Dims& Dm, const Ptrs& P, hipStream_t 
   p.total_tiles = Dm.B * Dm.H * Dm.nQb;
   p.kappa = Dm.kappa;
   const int grid = 8 * ((p.total_tiles + 7) / 8);
-  k_attn_fwd<D, INT4, CAUSAL, BF16, GM><<<grid, 256, 0, s>>>(p);
+  k_attn_fwd<D, INT4, CAUSAL, BF16, GM, E5M2><<<grid, 256, 0, s>>>(p);
   return hipGetLastError();
 }
 template <int D, bool INT4, bool CAUSAL, bool BF16>
 static hipError_t launch_attention_t(const Dims& Dm, const Ptrs& P, hipStream_t s) {
-  if (Dm.kg == KGROUP) return launch_attention_g<D, INT4, CAUSAL, BF16, 0>(Dm, P, s);
-  if (Dm.kg == 4) return launch_attention_g<D, INT4, CAUSAL, BF16, 1>(Dm, P, s);
-  return launch_attention_g<D, INT4, CAUSAL, BF16, 2>(Dm, P, s);
+  if (Dm.e5m2) return launch_attention_g<D, INT4, CAUSAL, BF16, 0, true>(Dm, P, s);   // default key groups only
+  if (Dm.kg == KGROUP) return launch_attention_g<D, INT4, CAUSAL, BF16, 0, false>(Dm, P, s);
+  if (Dm.kg == 4) return launch_attention_g<D, INT4, CAUSAL, BF16, 1, false>(Dm, P, s);
+  return launch_attention_g<D, INT4, CAUSAL, BF16, 2, false>(Dm, P, s);
 }
 
 hipError_t launch_attention(const Dims& D, const Ptrs& P, hipStream_t s) {

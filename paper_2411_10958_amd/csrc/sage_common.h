@@ -18,6 +18,8 @@ constexpr int STAT_ROWS = 256;  // tokens per workgroup of the column-statistics
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LOG2_448 = 8.807354922057604f;
 constexpr float LN2 = 0.6931471805599453f;
+constexpr float E5M2_MAX = 57344.0f;       // the E5M2 variant of the FP8 stage
+constexpr float LOG2_57344 = 15.807354922057604f;
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
@@ -86,6 +88,7 @@ struct Dims {
   float kappa; // fl32(sm_scale * log2 e)
   SeqMap seq;  // variable-length batch: N, Nk, nQb, nKb then describe the longest sequence
   int want_lse; // the caller asked for the row log-sum-exp
+  int e5m2;     // P~ and V in E5M2 instead of E4M3
 };
 
 // Workspace map (all offsets multiples of 256 bytes).

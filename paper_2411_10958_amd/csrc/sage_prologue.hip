@@ -254,7 +254,7 @@ __global__ void __launch_bounds__(256) k_v_absmax(const unsigned short* __restri
 __global__ void k_finalize_stats(const double* __restrict__ k_sum, const double* __restrict__ v_sum,
                                  const unsigned* __restrict__ v_max, float* __restrict__ k_mean,
                                  float* __restrict__ v_mean, float* __restrict__ v_scale, int n, int Nq, int N,
-                                 int d, int Hkv, int nchunk, SeqMap sm) {
+                                 int d, int Hkv, int nchunk, SeqMap sm, float code_max) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) {
     const int head = i / d, c = i - head * d;
@@ -269,17 +269,17 @@ __global__ void k_finalize_stats(const double* __restrict__ k_sum, const double*
     }
     k_mean[i] = nk > 0 ? (float)(ks / (double)nk) : 0.0f;
     if (v_sum) v_mean[i] = nk > 0 ? (float)(vs / (double)nk) : 0.0f;
-    else v_scale[i] = __fdiv_rn(vm, E4M3_MAX);
+    else v_scale[i] = __fdiv_rn(vm, code_max);
   }
 }
 __global__ void k_finalize_vscale(const unsigned* __restrict__ v_max, float* __restrict__ v_scale, int n, int d,
-                                  int nchunk) {
+                                  int nchunk, float code_max) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) {
     const int head = i / d, c = i - head * d;
     float vm = 0.0f;
     for (int ch = 0; ch < nchunk; ++ch) vm = fmaxf(vm, __uint_as_float(v_max[((size_t)head * nchunk + ch) * d + c]));
-    v_scale[i] = __fdiv_rn(vm, E4M3_MAX);
+    v_scale[i] = __fdiv_rn(vm, code_max);
   }
 }
 
@@ -721,7 +721,7 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
 // V: per-channel FP8 E4M3 codes, transposed into the A-operand order of the P~V product
 // (Sec. 3.3; Algorithm 1 "Preprocessing": (delta_V, V^) = psi_V(V)).  v_mean is null, or the token
 // mean to subtract first (smooth-V option, SMOOTH_V).
-template <bool BF16, int D, bool SMOOTH_V>
+template <bool BF16, int D, bool SMOOTH_V, bool E5M2>
 __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restrict__ V,
                                                  const float* __restrict__ v_scale,
                                                  const float* __restrict__ v_mean,
@@ -760,10 +760,17 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
       for (int e = 0; e < 8; ++e) x[e] = 0.0f;
     }
     int w0 = 0, w1 = 0;
-    w0 = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], w0, false);
-    w0 = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], w0, true);
-    w1 = __builtin_amdgcn_cvt_pk_fp8_f32(x[4], x[5], w1, false);
-    w1 = __builtin_amdgcn_cvt_pk_fp8_f32(x[6], x[7], w1, true);
+    if constexpr (E5M2) {
+      w0 = __builtin_amdgcn_cvt_pk_bf8_f32(x[0], x[1], w0, false);
+      w0 = __builtin_amdgcn_cvt_pk_bf8_f32(x[2], x[3], w0, true);
+      w1 = __builtin_amdgcn_cvt_pk_bf8_f32(x[4], x[5], w1, false);
+      w1 = __builtin_amdgcn_cvt_pk_bf8_f32(x[6], x[7], w1, true);
+    } else {
+      w0 = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], w0, false);
+      w0 = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], w0, true);
+      w1 = __builtin_amdgcn_cvt_pk_fp8_f32(x[4], x[5], w1, false);
+      w1 = __builtin_amdgcn_cvt_pk_fp8_f32(x[6], x[7], w1, true);
+    }
     *reinterpret_cast<uint2*>(&tile[r][cg * 8]) = make_uint2((unsigned)w0, (unsigned)w1);
   }
   __syncthreads();
@@ -842,26 +849,31 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
   };
   if (!Dm.want_lse) quant_q();
   const int nchunk = (int)gstat.x;
+  const float code_max = Dm.e5m2 ? E5M2_MAX : E4M3_MAX;
   if (Dm.smooth_v) {
     k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.N, Dm.Nk, km, sm);
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
-                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm);
+                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max);
     k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.N, Dm.Nk, km, sm);
-    k_finalize_vscale<<<(nstat + 255) / 256, 256, 0, s>>>(P.v_max, P.v_scale, nstat, Dm.d, nchunk);
+    k_finalize_vscale<<<(nstat + 255) / 256, 256, 0, s>>>(P.v_max, P.v_scale, nstat, Dm.d, nchunk, code_max);
   } else {
     k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.N, Dm.Nk, km, sm);
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
-                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm);
+                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max);
   }
   if (Dm.want_lse) quant_q();
   k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
                                                               P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
                                                               Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.kg,
                                                               Dm.causal, km, sm);
-  if (Dm.smooth_v)
-    k_quant_v<BF16, D, true><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
-  else
-    k_quant_v<BF16, D, false><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
+  const dim3 gv(Dm.nKb, BHkv);
+  if (Dm.smooth_v) {
+    if (Dm.e5m2) k_quant_v<BF16, D, true, true><<<gv, 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
+    else k_quant_v<BF16, D, true, false><<<gv, 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
+  } else {
+    if (Dm.e5m2) k_quant_v<BF16, D, false, true><<<gv, 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
+    else k_quant_v<BF16, D, false, false><<<gv, 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
+  }
   return hipGetLastError();
 }
 
