@@ -2,8 +2,8 @@
 
 A step is one pass of the whole hot path - smoothing / Delta-S / quantization prologue plus the
 fused attention kernel - over one batch of synthetic, outlier-bearing inputs already resident in
-HBM.  Prints ONE JSON line (see README/DESIGN for the fields): whole-path TOPS as `value`, the
-attention kernel's own roofline figure, and the CPU oracle timed on a bounded sample.
+HBM.  Prints ONE JSON line: whole-path TOPS as `value` (operations = 4*B*H*N*N_kv*d, halved under a
+causal mask), the attention kernel's own roofline figure, and the CPU oracle timed on a bounded sample.
 """
 import argparse
 import json
