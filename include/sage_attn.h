@@ -9,8 +9,8 @@
  * (Sec. 3.4); the whole loop is Algorithm 1.
  *
  * Conventions for every entry point
- *   - All tensor pointers are DEVICE pointers owned by the caller; the library never frees or
- *     keeps them.  q and out are contiguous [B, H, N, d] (or [B, N, H, d], see layout); k and v are contiguous
+ *   - All tensor pointers are DEVICE pointers owned by the caller, 16-byte aligned; the library never
+ *     frees or keeps them.  q and out are contiguous [B, H, N, d] (or [B, N, H, d], see layout); k and v are contiguous
  *     [B, H_kv, N_kv, d]; elements are 16-bit (fp16 or bf16, see dtype).  Query head h reads KV
  *     head h / (H / H_kv).  N_kv = N unless sage_attn_args.N_kv says otherwise; a causal mask is
  *     aligned to the last query and key (key t visible to query r iff t <= r + N_kv - N) and
@@ -46,7 +46,7 @@ extern "C" {
 
 enum {
   SAGE_OK = 0,
-  SAGE_ERR_INVALID_ARG = -1,  /* null pointer, non-positive size, H % H_kv != 0 */
+  SAGE_ERR_INVALID_ARG = -1,  /* null or misaligned pointer, non-positive size, H % H_kv != 0 */
   SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode, dtype, flag, group map or layout, causal with N_kv < N,
                                  cu_seqlens without SAGE_LAYOUT_NHD, sage_attn_quant / sage_attn_debug_qk with cu_seqlens */
   SAGE_ERR_WORKSPACE = -3,    /* workspace missing or smaller than sage_attn_workspace_bytes() */

@@ -26,6 +26,9 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if (a->cu_seqlens_k && !a->cu_seqlens_q) return SAGE_ERR_INVALID_ARG;
   if (a->cu_seqlens_q && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
   if (need_io && (!a->q || !a->k || !a->v || !a->out)) return SAGE_ERR_INVALID_ARG;
+  // the kernels move rows with 16-byte accesses (rows are multiples of 128 bytes, so the base decides)
+  if ((((uintptr_t)a->q | (uintptr_t)a->k | (uintptr_t)a->v | (uintptr_t)a->out) & 15u) != 0) return SAGE_ERR_INVALID_ARG;
+  if ((((uintptr_t)a->lse | (uintptr_t)a->cu_seqlens_q | (uintptr_t)a->cu_seqlens_k) & 3u) != 0) return SAGE_ERR_INVALID_ARG;
   // grid limits of the launches below (y dimension <= 65535, tile count fits an int)
   if ((long long)a->B * a->H > 65535) return SAGE_ERR_UNSUPPORTED;
   const long long nQb = (a->N + BQ - 1) / BQ, nKb = (Nk + BKV - 1) / BKV;

@@ -88,6 +88,9 @@ def test_argument_errors_are_found_on_the_host():
     assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -1
     a.q = a.k = a.v = a.out = 4096     # non-null, but no workspace: rejected before any launch
     assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -3
+    a.k = 4096 + 2                     # tensors must be 16-byte aligned
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -1
+    a.k = 4096
     assert lib.sage_attn_quant(ctypes.byref(a), None) == -1
     assert lib.sage_attn_debug_qk(ctypes.byref(a), 0, 0, 0, 0, None) == -1
     assert lib.sage_attn_fwd_ex(None) == -1
