@@ -56,7 +56,7 @@ def main():
     ap.add_argument("--workload", default="prefill4k")
     ap.add_argument("--mode", default="int4_fp8", choices=["int4_fp8", "int8_fp8"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--group-map", default="lane", choices=["lane", "block", "fine", "token"],
+    ap.add_argument("--group-map", default="lane", choices=["lane", "block", "fine", "token", "tensor"],
                     help="quantization granularity of Q and K: the default lane groups, one scale per block, "
                          "per query and 4 keys, or per token")
     ap.add_argument("--pv-format", default="e4m3", choices=["e4m3", "e5m2"],
@@ -143,7 +143,7 @@ def main():
         per_row = [min(spec.N, (i * 128 + 128 + 63) // 64 * 64) if spec.causal else spec.N for i in range(nqb)]
         ds_bytes = 4 * BH * sum(per_row)
     qk_code_bytes = 0.75 if args.mode == "int4_fp8" else 1.0      # 6-bit codes in the INT4 mode
-    qg, kg = {"lane": (2, 16), "block": (2, 16), "fine": (1, 4), "token": (1, 1)}[args.group_map]
+    qg, kg = {"lane": (2, 16), "block": (2, 16), "fine": (1, 4), "token": (1, 1), "tensor": (2, 16)}[args.group_map]
     alg_bytes = int((BH + BHkv) * spec.N * spec.d * qk_code_bytes) + BHkv * spec.N * spec.d + ds_bytes \
         + 4 * (BH * spec.N // qg + BHkv * spec.N // kg) + 2 * BH * spec.N * spec.d
 
@@ -167,7 +167,7 @@ def main():
         from oracle import sage_oracle as so
         base, heads, ins, outs = cpu_baseline(spec, args.mode, smooth_v=args.smooth_v,
                                                 gmap={"lane": "g950", "block": "per_block", "fine": "fine",
-                                                      "token": "per_token"}[args.group_map], pv_fmt=args.pv_format)
+                                                      "token": "per_token", "tensor": "per_tensor"}[args.group_map], pv_fmt=args.pv_format)
         res["cpu_baseline"] = base
         got = np.stack([wl.from_torch(out[b, h]) for b, h in heads])
         ref = np.stack(outs)

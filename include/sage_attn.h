@@ -71,11 +71,15 @@ enum { SAGE_FLAG_SMOOTH_V = 1 };
    one dequantization factor per accumulator quad on gfx950 (a lane of the score MFMA owns one query,
    and its 16 accumulators are 4 runs of 4 consecutive keys): nearly free.  SAGE_GROUPS_TOKEN: one
    scale per query and per key (per-token quantization, Sec. 3.2): a factor per score, not free.
-   Queries / keys per entry of q_scale / k_scale: 2 / 16 (LANE, BLOCK), 1 / 4 (FINE), 1 / 1 (TOKEN). */
-enum { SAGE_GROUPS_LANE = 0, SAGE_GROUPS_BLOCK = 1, SAGE_GROUPS_FINE = 2, SAGE_GROUPS_TOKEN = 3 };
+   SAGE_GROUPS_TENSOR: one scale for all queries and one for all keys of a (batch, head) (per-tensor
+   quantization, Sec. 2.2): the quantizers run twice (block maxima, then codes), the attention kernel is
+   that of LANE; the coarsest and least accurate map of the comparison.
+   Queries / keys per entry of q_scale / k_scale: 2 / 16 (LANE, BLOCK, TENSOR), 1 / 4 (FINE), 1 / 1 (TOKEN). */
+enum { SAGE_GROUPS_LANE = 0, SAGE_GROUPS_BLOCK = 1, SAGE_GROUPS_FINE = 2, SAGE_GROUPS_TOKEN = 3,
+       SAGE_GROUPS_TENSOR = 4 };
 /* 8-bit float format of P~ and V (Sec. 3.3; the paper's data-type comparison): E4M3 (the paper's choice,
    static scale 1/448 for P~) or E5M2 (static scale 1/57344; one mantissa bit less, kept for the
-   comparison; only with SAGE_GROUPS_LANE / _BLOCK). */
+   comparison; not with SAGE_GROUPS_FINE / _TOKEN). */
 enum { SAGE_PV_E4M3 = 0, SAGE_PV_E5M2 = 1 };
 /* Memory order of the four tensors (all contiguous): heads outside tokens, [B, H, N, d], or tokens
    outside heads, [B, N, H, d] (k, v: H_kv and N_kv).  The workspace layouts do not depend on it. */

@@ -12,9 +12,9 @@ import torch
 SAGE_MODE_INT4_FP8, SAGE_MODE_INT8_FP8 = 0, 1
 SAGE_DT_FP16, SAGE_DT_BF16 = 0, 1
 SAGE_FLAG_SMOOTH_V = 1
-SAGE_GROUPS_LANE, SAGE_GROUPS_BLOCK, SAGE_GROUPS_FINE, SAGE_GROUPS_TOKEN = 0, 1, 2, 3
-_GROUPS = {"lane": 0, "block": 1, "fine": 2, "token": 3, 0: 0, 1: 1, 2: 2, 3: 3}
-_GROUP_SIZES = {0: (2, 16), 1: (2, 16), 2: (1, 4), 3: (1, 1)}     # queries, keys per stored scale
+SAGE_GROUPS_LANE, SAGE_GROUPS_BLOCK, SAGE_GROUPS_FINE, SAGE_GROUPS_TOKEN, SAGE_GROUPS_TENSOR = 0, 1, 2, 3, 4
+_GROUPS = {"lane": 0, "block": 1, "fine": 2, "token": 3, "tensor": 4, 0: 0, 1: 1, 2: 2, 3: 3, 4: 4}
+_GROUP_SIZES = {0: (2, 16), 1: (2, 16), 2: (1, 4), 3: (1, 1), 4: (2, 16)}     # queries, keys per stored scale
 SAGE_LAYOUT_HND, SAGE_LAYOUT_NHD = 0, 1
 _LAYOUTS = {"HND": 0, "NHD": 1, 0: 0, 1: 1}
 _MODES = {"int4_fp8": 0, "int8_fp8": 1, 0: 0, 1: 1}

@@ -19,10 +19,11 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if (a->mode != SAGE_MODE_INT4_FP8 && a->mode != SAGE_MODE_INT8_FP8) return SAGE_ERR_UNSUPPORTED;
   if (a->dtype != SAGE_DT_FP16 && a->dtype != SAGE_DT_BF16) return SAGE_ERR_UNSUPPORTED;
   if ((a->flags & ~SAGE_FLAG_SMOOTH_V) != 0) return SAGE_ERR_UNSUPPORTED;
-  if (a->group_map < SAGE_GROUPS_LANE || a->group_map > SAGE_GROUPS_TOKEN) return SAGE_ERR_UNSUPPORTED;
+  if (a->group_map < SAGE_GROUPS_LANE || a->group_map > SAGE_GROUPS_TENSOR) return SAGE_ERR_UNSUPPORTED;
   if (a->layout != SAGE_LAYOUT_HND && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
   if (a->pv_format != SAGE_PV_E4M3 && a->pv_format != SAGE_PV_E5M2) return SAGE_ERR_UNSUPPORTED;
-  if (a->pv_format == SAGE_PV_E5M2 && a->group_map > SAGE_GROUPS_BLOCK) return SAGE_ERR_UNSUPPORTED;
+  if (a->pv_format == SAGE_PV_E5M2 && (a->group_map == SAGE_GROUPS_FINE || a->group_map == SAGE_GROUPS_TOKEN))
+    return SAGE_ERR_UNSUPPORTED;
   if (a->cu_seqlens_k && !a->cu_seqlens_q) return SAGE_ERR_INVALID_ARG;
   if (a->cu_seqlens_q && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
   if (need_io && (!a->q || !a->k || !a->v || !a->out)) return SAGE_ERR_INVALID_ARG;
@@ -40,8 +41,9 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   D->int4 = a->mode == SAGE_MODE_INT4_FP8;
   D->bf16 = a->dtype == SAGE_DT_BF16;
   D->smooth_v = (a->flags & SAGE_FLAG_SMOOTH_V) != 0;
-  D->block_groups = a->group_map == SAGE_GROUPS_BLOCK;
-  D->qg = a->group_map >= SAGE_GROUPS_FINE ? 1 : QGROUP;
+  D->tensor_groups = a->group_map == SAGE_GROUPS_TENSOR;
+  D->block_groups = a->group_map == SAGE_GROUPS_BLOCK || D->tensor_groups;
+  D->qg = (a->group_map == SAGE_GROUPS_FINE || a->group_map == SAGE_GROUPS_TOKEN) ? 1 : QGROUP;
   D->kg = a->group_map == SAGE_GROUPS_TOKEN ? 1 : (a->group_map == SAGE_GROUPS_FINE ? 4 : KGROUP);
   D->nhd = a->layout == SAGE_LAYOUT_NHD;
   D->seq.cu_q = a->cu_seqlens_q; D->seq.cu_k = a->cu_seqlens_k;

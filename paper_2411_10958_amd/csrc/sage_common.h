@@ -89,6 +89,7 @@ struct Dims {
   SeqMap seq;  // variable-length batch: N, Nk, nQb, nKb then describe the longest sequence
   int want_lse; // the caller asked for the row log-sum-exp
   int e5m2;     // P~ and V in E5M2 instead of E4M3
+  int tensor_groups;  // one scale per (batch, head) tensor of Q and of K (implies block_groups)
 };
 
 // Workspace map (all offsets multiples of 256 bytes).
@@ -121,8 +122,8 @@ struct Dims {
 //   k_sum, v_max (and v_sum): [B*Hkv][ceil(Nk/STAT_ROWS)][d] partial results of the statistics pass;
 //   v_sum, v_mean only with the smooth-V option (otherwise zero-sized).
 struct Workspace {
-  size_t k_sum, v_sum, v_max, k_mean, v_mean, v_scale, q_mean, q_scale, k_scale, q_corr, q_codes, k_codes,
-      v_codes, delta_s, total;
+  size_t k_sum, v_sum, v_max, k_mean, v_mean, v_scale, q_mean, q_scale, k_scale, q_corr, q_head_scale,
+      k_head_scale, q_codes, k_codes, v_codes, delta_s, total;
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -152,6 +153,8 @@ inline Workspace make_workspace(const Dims& D) {
   w.q_scale = take(BH * D.nQb * (BQ / D.qg) * sizeof(float));
   w.k_scale = take(BHkv * D.nKb * (BKV / D.kg) * sizeof(float));
   w.q_corr = take(BH * D.nQb * BQ * sizeof(float));      // kappa * <q_r, mean(K)> per query (log-sum-exp output)
+  w.q_head_scale = take(BH * sizeof(float));             // per-tensor granularity only
+  w.k_head_scale = take(BHkv * sizeof(float));
   w.q_codes = take(BH * D.nQb * q_slab_bytes(D.d, D.int4));
   w.k_codes = take(BHkv * D.nKb * k_block_bytes(D.d, D.int4));
   w.v_codes = take(BHkv * D.nKb * BKV * D.d);
@@ -165,7 +168,7 @@ struct Ptrs {
   void* out;
   double *k_sum, *v_sum;
   unsigned* v_max;
-  float *k_mean, *v_mean, *v_scale, *q_mean, *q_scale, *k_scale, *q_corr, *delta_s;
+  float *k_mean, *v_mean, *v_scale, *q_mean, *q_scale, *k_scale, *q_corr, *q_head_scale, *k_head_scale, *delta_s;
   float* lse;
   int8_t *q_codes, *k_codes;
   uint8_t* v_codes;
@@ -186,6 +189,8 @@ inline Ptrs make_ptrs(const void* q, const void* k, const void* v, void* out, vo
   p.q_scale = (float*)(b + w.q_scale);
   p.k_scale = (float*)(b + w.k_scale);
   p.q_corr = (float*)(b + w.q_corr);
+  p.q_head_scale = (float*)(b + w.q_head_scale);
+  p.k_head_scale = (float*)(b + w.k_head_scale);
   p.lse = nullptr;
   p.q_codes = (int8_t*)(b + w.q_codes);
   p.k_codes = (int8_t*)(b + w.k_codes);

@@ -314,7 +314,8 @@ __global__ void __launch_bounds__(256) k_quant_q8(const unsigned short* __restri
                                                   float* __restrict__ q_scale, int8_t* __restrict__ q_codes,
                                                   int N, int Nk, int nQb, int block_groups, int qg,
                                                   TensorMap qm, SeqMap sm, float* __restrict__ q_corr,
-                                                  const float* __restrict__ k_mean, int G, float kappa) {
+                                                  const float* __restrict__ k_mean, int G, float kappa,
+                                                  const float* __restrict__ head_scale, int stats_only) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;  // RPT rows per thread (8 or 4)
   constexpr int QMAX = 127;
   const int t = threadIdx.x, cg = t % NCG, rg = t / NCG;
@@ -371,15 +372,17 @@ __global__ void __launch_bounds__(256) k_quant_q8(const unsigned short* __restri
     if (block_groups) mxr[0] = mxr[1] = block_max;
 #pragma unroll
     for (int i = 2 * p; i < 2 * p + 2; ++i) {
-      const float delta = __fdiv_rn(mxr[i - 2 * p], (float)QMAX);
+      const float delta = head_scale ? head_scale[bh] : __fdiv_rn(mxr[i - 2 * p], (float)QMAX);
       if (cg == 0 && (qg == 1 || i == 2 * p))
         q_scale[(bh * nQb + qb) * (BQ >> (qg - 1)) + ((rg * RPT + i) >> (qg - 1))] = delta;   // qg is 1 or 2
+      if (stats_only) continue;          // per-tensor scales, first pass: only the block maxima are wanted
       const QuantScale qs = quant_scale<QMAX>(delta);
       int c[8];
       quant_group<8, QMAX>(x[i], delta, qs, [&](int e, float cf) { c[e] = (int)cf; });
       *reinterpret_cast<uint2*>(img + q_code_off(rg * RPT + i, cg * 8, D)) = pack8(c);
     }
   }
+  if (stats_only) return;
   __syncthreads();
   constexpr int SLAB16 = (int)(q_slab_bytes(D, false) / 16);
   uint4* dst = reinterpret_cast<uint4*>(q_codes + (bh * nQb + qb) * q_slab_bytes(D, false));
@@ -403,7 +406,8 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
                                                   int8_t* __restrict__ q_codes, int N, int Nk, int nQb,
                                                   int block_groups, int qg, TensorMap qm, SeqMap sm,
                                                   float* __restrict__ q_corr, const float* __restrict__ k_mean,
-                                                  int G, float kappa) {
+                                                  int G, float kappa, const float* __restrict__ head_scale,
+                                                  int stats_only) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;   // load map: RPT rows x 8 channels
   constexpr int CPL = D / 4, CPC = CPL / 8;                      // quantization map: 2 rows x CPL channels
   constexpr int QMAX = 7;
@@ -501,9 +505,10 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
   uint8_t* img = reinterpret_cast<uint8_t*>(&s_sum[0][0]);   // everyone is past the column sums
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    const float delta = __fdiv_rn(mxr[i], (float)QMAX);
+    const float delta = head_scale ? head_scale[bh] : __fdiv_rn(mxr[i], (float)QMAX);
     if (c4 == 0 && (qg == 1 || i == 0))   // qg is 1 or 2
       q_scale[(bh * nQb + qb) * (BQ >> (qg - 1)) + ((2 * pair + i) >> (qg - 1))] = delta;
+    if (stats_only) continue;            // per-tensor scales, first pass: only the block maxima are wanted
     const QuantScale qs = quant_scale<QMAX>(delta);
     Codes32 cd;
 #pragma unroll
@@ -519,6 +524,7 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
     for (int k = 0; k < CPL * 6 / 32; ++k)
       *reinterpret_cast<unsigned*>(img + op + op6_byte(lane_m, 4 * (d0 + k))) = pw[k];
   }
+  if (stats_only) return;
   __syncthreads();
   uint4* dst = reinterpret_cast<uint4*>(q_codes + (bh * nQb + qb) * q_slab_bytes(D, true));
   const uint4* src = reinterpret_cast<const uint4*>(img);
@@ -555,7 +561,8 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
                                                  const float* __restrict__ q_mean,
                                                  float* __restrict__ delta_s, int Nq, int Nmax, int nKb,
                                                  int nQb, int G, float kappa, int block_groups, int kg,
-                                                 int causal, TensorMap km, SeqMap sm) {
+                                                 int causal, TensorMap km, SeqMap sm,
+                                                 const float* __restrict__ head_scale, int stats_only) {
   constexpr int CPL = D / 4;                       // channels per lane (32 or 16)
   constexpr int QMAX = INT4 ? 7 : 127;
   // LDS row of staged block means: channel c sits at column c + 16*(c / 32) when D = 128, so the
@@ -648,9 +655,10 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
     __syncthreads();
     mx = fmaxf(fmaxf(s_bmax[0], s_bmax[1]), fmaxf(s_bmax[2], s_bmax[3]));
   }
-  const float delta = __fdiv_rn(mx, (float)QMAX);
+  const float delta = head_scale ? head_scale[bhkv] : __fdiv_rn(mx, (float)QMAX);
   const int ksh = kg == 16 ? 4 : (kg == 4 ? 2 : 0);
   if (k4 == 0 && (r16 & (kg - 1)) == 0) k_scale[(bhkv * nKb + kb) * (BKV >> ksh) + ((16 * w + r16) >> ksh)] = delta;
+  if (stats_only) return;                // per-tensor scales, first pass: only the block maxima are wanted
   uint8_t* img = reinterpret_cast<uint8_t*>(s_codes);
   const QuantScale qs = quant_scale<QMAX>(delta);
   if constexpr (INT4) {
@@ -789,6 +797,28 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
 }
 
 // ------------------------------------------------------------------------------------------
+// Per-tensor scales (the coarsest granularity of the paper's comparison, Sec. 2.2): the quantizers run
+// once in per-block mode just to leave every block's scale, this kernel takes the largest scale of a
+// head (delta = fl32(max / qmax) is monotone in the maximum, so the largest block scale is the
+// head's), and the quantizers run again with that scale.  One workgroup per head; `per_block` scale
+// entries per block, `stride` entries per head, blocks counted from the sequence's own length.
+__global__ void __launch_bounds__(256) k_head_scale(const float* __restrict__ scale, float* __restrict__ head_scale,
+                                                    int per_block, int stride, int tokens_per_block, int heads,
+                                                    int which_k, int Nq, int Nk, SeqMap sm) {
+  __shared__ float s_m[4];
+  const unsigned head = blockIdx.x;
+  const Seq sq = seq_of(sm, head / (unsigned)heads, Nq, Nk);
+  const int n = which_k ? sq.nk : sq.n;
+  const int entries = ((n + tokens_per_block - 1) / tokens_per_block) * per_block;
+  float m = 0.0f;
+  for (int i = threadIdx.x; i < entries; i += 256) m = fmaxf(m, scale[(size_t)head * stride + i]);
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0) s_m[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) head_scale[head] = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+}
+
+// ------------------------------------------------------------------------------------------
 // Copies from the packed workspace to plain layouts (used only by sage_attn_quant).
 __global__ void k_unpack_codes(const int8_t* __restrict__ packed, int8_t* __restrict__ plain, int N,
                                int d, size_t slab, int which, int fp6) {
@@ -836,16 +866,32 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
   // Q goes first: it depends on nothing, and with the statistics pass next to the K and V quantizers
   // those re-read K and V while the chip's memory-side cache still holds most of them.  Only when
   // the log-sum-exp output is wanted does Q wait for mean(K) (its row constants need it).
-  auto quant_q = [&]() {
-    float* corr = Dm.want_lse ? P.q_corr : nullptr;
+  auto quant_q_pass = [&](float* corr, const float* head_scale, int stats_only) {
     if constexpr (INT4)
       k_quant_q4<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
                                                        Dm.block_groups, Dm.qg, qm, sm, corr, P.k_mean,
-                                                       Dm.H / Dm.Hkv, Dm.kappa);
+                                                       Dm.H / Dm.Hkv, Dm.kappa, head_scale, stats_only);
     else
       k_quant_q8<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
                                                        Dm.block_groups, Dm.qg, qm, sm, corr, P.k_mean,
-                                                       Dm.H / Dm.Hkv, Dm.kappa);
+                                                       Dm.H / Dm.Hkv, Dm.kappa, head_scale, stats_only);
+  };
+  auto quant_q = [&]() {
+    float* corr = Dm.want_lse ? P.q_corr : nullptr;
+    if (Dm.tensor_groups) {     // block scales, their maximum per head, then the codes with that one scale
+      quant_q_pass(nullptr, nullptr, 1);
+      k_head_scale<<<BH, 256, 0, s>>>(P.q_scale, P.q_head_scale, BQ / Dm.qg, Dm.nQb * (BQ / Dm.qg), BQ, Dm.H, 0, Dm.N,
+                                     Dm.Nk, sm);
+      quant_q_pass(corr, P.q_head_scale, 0);
+    } else {
+      quant_q_pass(corr, nullptr, 0);
+    }
+  };
+  auto quant_k_pass = [&](const float* head_scale, int stats_only) {
+    k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
+                                                                P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
+                                                                Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.kg,
+                                                                Dm.causal, km, sm, head_scale, stats_only);
   };
   if (!Dm.want_lse) quant_q();
   const int nchunk = (int)gstat.x;
@@ -862,10 +908,14 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
                                                         nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max);
   }
   if (Dm.want_lse) quant_q();
-  k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
-                                                              P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
-                                                              Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.kg,
-                                                              Dm.causal, km, sm);
+  if (Dm.tensor_groups) {
+    quant_k_pass(nullptr, 1);
+    k_head_scale<<<BHkv, 256, 0, s>>>(P.k_scale, P.k_head_scale, BKV / Dm.kg, Dm.nKb * (BKV / Dm.kg), BKV, Dm.Hkv, 1,
+                                     Dm.N, Dm.Nk, sm);
+    quant_k_pass(P.k_head_scale, 0);
+  } else {
+    quant_k_pass(nullptr, 0);
+  }
   const dim3 gv(Dm.nKb, BHkv);
   if (Dm.smooth_v) {
     if (Dm.e5m2) k_quant_v<BF16, D, true, true><<<gv, 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);

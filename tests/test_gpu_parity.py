@@ -185,36 +185,37 @@ def test_smooth_v_matches_oracle(N, d, dtype, H, Hkv, causal, mode):
     assert e_s < e_p        # the ordering the paper's table for this technique reports
 
 
-# ---- per-block granularity (Sec. 2.3 / Sec. 3.2: the coarser grouping the paper compares with) ----
+# ---- per-block and per-tensor granularity (Sec. 2.2 / 2.3 / 3.2: the coarser groupings the paper compares with) ----
 @pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("group_map,gmap", [("block", "per_block"), ("tensor", "per_tensor")])
 @pytest.mark.parametrize("N,d,dtype,H,Hkv,causal", [(333, 128, "bf16", 2, 1, True), (640, 64, "fp16", 2, 2, False)])
-def test_per_block_groups_match_oracle(N, d, dtype, H, Hkv, causal, mode):
+def test_coarser_groups_match_oracle(N, d, dtype, H, Hkv, causal, group_map, gmap, mode):
     pa = _pa()
     spec = _spec(N, d, dtype, H, Hkv, causal=causal, outliers=2)
     data, (q, k, v) = _gpu_inputs(spec)
-    print(f"per-block case N={N} d={d} {dtype} H={H}/{Hkv} causal={causal} mode={mode}", flush=True)
-    got, args, ws = pa.sage_attn_quant(q, k, v, causal=causal, mode=mode, group_map="block",
+    print(f"{group_map} case N={N} d={d} {dtype} H={H}/{Hkv} causal={causal} mode={mode}", flush=True)
+    got, args, ws = pa.sage_attn_quant(q, k, v, causal=causal, mode=mode, group_map=group_map,
                                        want=("q_codes", "k_codes", "q_scale", "k_scale"))
-    out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, group_map="block")
+    out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, group_map=group_map)
     fine = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode)
     torch.cuda.synchronize()
     got = {n: t.cpu().numpy() for n, t in got.items()}
     g = H // Hkv
     for h in range(H):
         pro = so.quantize_head(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], mode=mode,
-                               gmap="per_block")
+                               gmap=gmap)
         assert np.array_equal(got["q_codes"][0, h], pro["q_codes"]), "q codes"
         assert np.array_equal(got["k_codes"][0, h // g], pro["k_codes"]), "k codes"
         # the library keeps its scale arrays' shapes: one entry per query pair / per 16 keys
         assert np.array_equal(got["q_scale"][0, h], pro["q_scale"][pro["q_groups"][::2]]), "q scales"
         assert np.array_equal(got["k_scale"][0, h // g], pro["k_scale"][pro["k_groups"][::16]]), "k scales"
     ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32",
-                            gmap="per_block")
+                            gmap=gmap)
     check_output(wl.from_torch(out), ref, dtype)
     full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
                      for h in range(H)])
     e_b, e_f = wl.rel_l1(wl.from_torch(out)[0], full), wl.rel_l1(wl.from_torch(fine)[0], full)
-    print(f"  rel-L1 vs FP64 attention: per-block {e_b:.4f}, default groups {e_f:.4f}", flush=True)
+    print(f"  rel-L1 vs FP64 attention: {group_map} {e_b:.4f}, default groups {e_f:.4f}", flush=True)
     assert e_f <= e_b * 1.02      # finer groups are not worse (the paper's granularity table)
 
 
