@@ -1,0 +1,106 @@
+"""Seeded sweep over combinations of the options of sage_attn_args on small shapes: every combination goes
+through the HIP path and is compared with the CPU oracle (same bars as tests/test_gpu_parity.py), so that
+interactions - a layout with a group map, smooth V with another key length, the log-sum-exp with a packed
+batch - are exercised and not only each option alone."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import sage_oracle as so
+from test_gpu_parity import check_output, _pa, _lse_close
+
+pytestmark = pytest.mark.gpu
+
+GMAPS = {"lane": "g950", "block": "per_block", "fine": "fine", "token": "per_token", "tensor": "per_tensor"}
+
+
+def _draw(rng):
+    d = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2]))
+    H = Hkv * int(rng.choice([1, 2, 4]))
+    causal = bool(rng.integers(2))
+    n = int(rng.choice([1, 17, 64, 100, 128, 129, 200, 257, 333, 450]))
+    nk = n if rng.random() < 0.5 else int(rng.choice([1, 63, 64, 65, 190, 300, 520]))
+    if causal and nk < n:
+        nk = n
+    group_map = str(rng.choice(list(GMAPS)))
+    pv = "e5m2" if (group_map in ("lane", "block", "tensor") and rng.random() < 0.3) else "e4m3"
+    return dict(d=d, H=H, Hkv=Hkv, causal=causal, n=n, nk=nk, group_map=group_map, pv=pv,
+                mode=str(rng.choice(["int4_fp8", "int8_fp8"])), dtype=str(rng.choice(["bf16", "fp16"])),
+                layout=str(rng.choice(["HND", "NHD"])), smooth_v=bool(rng.random() < 0.3), lse=bool(rng.random() < 0.5),
+                vbias=float(rng.choice([0.0, 4.0])))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_option_combination_matches_oracle(seed):
+    pa = _pa()
+    rng = np.random.default_rng(1000 + seed)
+    c = _draw(rng)
+    print(f"combination {seed}: {c}", flush=True)
+    spec = wl.WorkloadSpec("sweep", 2, c["H"], c["Hkv"], c["n"], c["d"], c["dtype"], c["causal"], 3.0, 1.5, 2, 10.0, 1.0,
+                           300 + seed, c["vbias"], c["nk"])
+    data = wl.make_inputs(spec, seed=seed)
+    dev = torch.device("cuda:0")
+    q, k, v = (wl.to_torch(data[x], c["dtype"], dev) for x in "qkv")
+    if c["layout"] == "NHD":
+        q, k, v = (t.permute(0, 2, 1, 3).contiguous() for t in (q, k, v))
+    res = pa.sage_attn_fwd_ex(q, k, v, causal=c["causal"], mode=c["mode"], smooth_v=c["smooth_v"], group_map=c["group_map"],
+                              layout=c["layout"], pv_format=c["pv"], return_lse=c["lse"])
+    torch.cuda.synchronize()
+    out, lse = res if c["lse"] else (res, None)
+    if c["layout"] == "NHD":
+        out = out.permute(0, 2, 1, 3)
+    g = c["H"] // c["Hkv"]
+    ref = np.empty((2, c["H"], c["n"], c["d"]), np.float32)
+    for b in range(2):
+        for h in range(c["H"]):
+            ref[b, h], pro = so.sage_attention_head(data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g],
+                                                    causal=c["causal"], mode=c["mode"], gmap=GMAPS[c["group_map"]],
+                                                    out_dtype="fp32", smooth_v_on=c["smooth_v"], pv_fmt=c["pv"],
+                                                    want_lse=c["lse"])
+            if c["lse"]:
+                _lse_close(lse[b, h].cpu().numpy(), pro["lse"])
+    check_output(wl.from_torch(out), ref, c["dtype"])
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_packed_batch_combination_matches_oracle(seed):
+    pa = _pa()
+    rng = np.random.default_rng(2000 + seed)
+    c = _draw(rng)
+    B = int(rng.integers(2, 5))
+    lens_q = [int(rng.choice([0, 1, 40, 128, 150, 300])) for _ in range(B)]
+    lens_q[int(rng.integers(B))] = 200                    # at least one sequence worth checking
+    lens_k = [n if (c["causal"] or rng.random() < 0.5) else int(rng.choice([1, 64, 90, 260])) for n in lens_q]
+    print(f"packed combination {seed}: {c} q={lens_q} k={lens_k}", flush=True)
+    dev = torch.device("cuda:0")
+    seqs, qs, ks, vs = [], [], [], []
+    for i, (n, nk) in enumerate(zip(lens_q, lens_k)):
+        spec = wl.WorkloadSpec("sweep", 1, c["H"], c["Hkv"], max(n, 1), c["d"], c["dtype"], c["causal"], 3.0, 1.5, 2, 10.0,
+                               1.0, 400 + 10 * seed + i, c["vbias"], max(nk, 1))
+        dd = wl.make_inputs(spec, seed=seed)
+        qn, kn, vn = dd["q"][0][:, :n], dd["k"][0][:, :nk], dd["v"][0][:, :nk]
+        seqs.append((qn, kn, vn))
+        qs.append(qn.transpose(1, 0, 2)); ks.append(kn.transpose(1, 0, 2)); vs.append(vn.transpose(1, 0, 2))
+    pack = lambda parts: wl.to_torch(np.ascontiguousarray(np.concatenate(parts, axis=0)), c["dtype"], dev)
+    cu = lambda lens: torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev)
+    q, k, v = pack(qs), pack(ks), pack(vs)
+    res = pa.sage_attn_fwd_ex(q, k, v, causal=c["causal"], mode=c["mode"], smooth_v=c["smooth_v"], group_map=c["group_map"],
+                              pv_format=c["pv"], return_lse=c["lse"], cu_seqlens_q=cu(lens_q), cu_seqlens_k=cu(lens_k))
+    torch.cuda.synchronize()
+    out, lse = res if c["lse"] else (res, None)
+    off = np.concatenate([[0], np.cumsum(lens_q)])
+    g = c["H"] // c["Hkv"]
+    for i, (n, nk) in enumerate(zip(lens_q, lens_k)):
+        if n == 0 or nk == 0:
+            continue
+        qn, kn, vn = seqs[i]
+        ref = np.empty((c["H"], n, c["d"]), np.float32)
+        for h in range(c["H"]):
+            ref[h], pro = so.sage_attention_head(qn[h], kn[h // g], vn[h // g], causal=c["causal"], mode=c["mode"],
+                                                 gmap=GMAPS[c["group_map"]], out_dtype="fp32", smooth_v_on=c["smooth_v"],
+                                                 pv_fmt=c["pv"], want_lse=c["lse"])
+            if c["lse"]:
+                _lse_close(lse[h, off[i]:off[i + 1]].cpu().numpy(), pro["lse"])
+        check_output(wl.from_torch(out[off[i]:off[i + 1]]).transpose(1, 0, 2), ref, c["dtype"])
