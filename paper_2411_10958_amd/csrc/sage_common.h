@@ -104,7 +104,7 @@ struct Dims {
 //            MFMA row rho = l%32 and channels 32*s + 16*(l/32) + 0..15, where row
 //            rho = 8g + 4h + r carries key 32*tile + 16h + 4g + r of the block, so that an
 //            accumulator lane (half h) ends up with 16 consecutive keys.
-//  INT4 mode (6-bit FP6 E2M3 codes of the same integers, see int4_code_to_e2m3 below): one
+//  INT4 mode (6-bit FP6 E2M3 codes of the same integers, see the FP6 note below): one
 //  operand of v_mfma_f32_32x32x64_f8f6f4 ("op") covers 32 rows x 64 channels; lane l supplies row
 //  l%32 and channels 32*(l/32) + e, element e at bit 6e of a 24-byte payload.  An op is stored
 //  as 1536 bytes: a plane of 64 x 16 bytes (payload bytes 0..15 of lanes 0..63) followed by a
@@ -226,11 +226,8 @@ __host__ __device__ inline size_t v_code_off(int n, int c, int d) {
 // v_mfma_f32_32x32x64_f8f6f4, and the FP6 operand format runs at twice the rate of the 8-bit
 // formats: the gfx950 counterpart of "INT4 matmul is twice as fast as INT8".  The accumulators come
 // out as exact integers in float - no int->float conversion afterwards.
-__host__ __device__ inline unsigned int4_code_to_e2m3(int c) {
-  const unsigned long long tab = 0x1E1C1A1814100800ull;   // (exponent << 3 | mantissa) for |c| = 0..7
-  const int a = c < 0 ? -c : c;
-  return (unsigned)((tab >> (8 * a)) & 0x1fu) | (c < 0 ? 0x20u : 0u);
-}
+// (The quantizers produce the fields with the hardware FP32 -> FP6 conversion; the decoder below serves
+// the copy-out of sage_attn_quant.)
 __host__ __device__ inline int e2m3_to_int4_code(unsigned b) {
   const int e = (b >> 3) & 3, m = b & 7;
   const int a = e == 0 ? 0 : ((8 + m) << (e - 1)) >> 3;     // (1 + m/8) * 2^(e-1)

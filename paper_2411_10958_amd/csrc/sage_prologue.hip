@@ -126,20 +126,6 @@ __device__ inline uint2 pack8(const int (&c)[8]) {
   return o;
 }
 
-// N6 INT4 codes as consecutive 6-bit E2M3 fields (element e at bit 6e), N6 * 6 / 32 dwords
-template <int N6>
-__device__ inline void pack6(const int (&c)[N6], unsigned (&w)[N6 * 6 / 32]) {
-#pragma unroll
-  for (int i = 0; i < N6 * 6 / 32; ++i) w[i] = 0u;
-#pragma unroll
-  for (int e = 0; e < N6; ++e) {
-    const unsigned v = int4_code_to_e2m3(c[e]);
-    const int wi = (6 * e) >> 5, sh = (6 * e) & 31;
-    w[wi] |= v << sh;
-    if (sh > 26) w[wi + 1] |= v >> (32 - sh);
-  }
-}
-
 // ------------------------------------------------------------------------------------------
 // Column statistics: exact token sums of K (float64 accumulation of 16-bit values) and
 // per-channel max |V| (Algorithm 1, "Preprocessing": mean(K) and the scale of psi_V).  Every
@@ -392,7 +378,7 @@ __global__ void __launch_bounds__(256) k_quant_q8(const unsigned short* __restri
 
 // Q, 4-bit variant: block mean, smoothing, pair-group quantization (Algorithm 1: q_bar_i =
 // mean(Q_i), psi_Q(Q_i - q_bar_i)).  Two thread-to-data maps, joined through LDS:
-//  - loading and the exact column sums of the block mean use the coalesced map of k_quant_q (a
+//  - loading and the exact column sums of the block mean use the coalesced map of k_quant_q8 (a
 //    thread owns 8 channels of BQ*D/2048 rows), and the raw 16-bit rows are parked in LDS;
 //  - quantization uses the map the codes are consumed in: a thread owns D/4 consecutive channels
 //    of the two queries of one scale group, i.e. (half of) one MFMA lane's payload per query, so
@@ -533,11 +519,12 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
 }
 
 // ------------------------------------------------------------------------------------------
-// K: smoothing by the token mean, 16-key-group quantization and, in the int4 mode, Delta-S.
+// K: smoothing by the token mean, group quantization (runs of 16 keys by default) and, in the int4
+// mode, Delta-S.
 // (Algorithm 1: psi_K(K_j) after K = K - mean(K); Sec. 3.1: Delta-S = q_bar_i . gamma(K)^T.)
 //
 // One workgroup per 64 keys of one (batch, KV head); wavefront w owns keys 16w..16w+15, which
-// is exactly one quantization group.  Lane l holds key 16w + l%16 and the D/4 consecutive
+// is exactly one default quantization group.  Lane l holds key 16w + l%16 and the D/4 consecutive
 // channels (D/4)*(l/16) .. +D/4-1, i.e. the wavefront reads 16 whole rows as one contiguous
 // piece.  That is also the B-operand shape of the 16x16x4 FP64 MFMA (lane l supplies
 // B[k = l/16][column l%16]) once contraction slot (step cs, k = l/16) is assigned channel
@@ -726,7 +713,8 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
 }
 
 // ------------------------------------------------------------------------------------------
-// V: per-channel FP8 E4M3 codes, transposed into the A-operand order of the P~V product
+// V: per-channel FP8 codes (E4M3, or E5M2 with the E5M2 template flag), transposed into the A-operand
+// order of the P~V product
 // (Sec. 3.3; Algorithm 1 "Preprocessing": (delta_V, V^) = psi_V(V)).  v_mean is null, or the token
 // mean to subtract first (smooth-V option, SMOOTH_V).
 template <bool BF16, int D, bool SMOOTH_V, bool E5M2>
