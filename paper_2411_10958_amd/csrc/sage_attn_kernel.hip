@@ -2,12 +2,13 @@
 // Algorithm 1.  One workgroup (4 wavefronts) owns one 128-query smoothing block of one
 // (batch, head); each wavefront owns 32 queries and walks the 64-key blocks.
 //
-// The score tile is computed transposed, S^T = K^ Q^^T, with v_mfma_i32_32x32x32_i8: rows are
+// The score tile is computed transposed, S^T = K^ Q^^T, with 32x32 MFMAs (v_mfma_i32_32x32x32_i8 in
+// the 8-bit mode, the FP6 operand format of v_mfma_f32_32x32x64_f8f6f4 in the 4-bit mode): rows are
 // keys, columns are queries, so a lane holds ONE query (column lane%32) and, thanks to the row
 // permutation baked into the packed K^ layout, 16 consecutive keys per 32-key tile.  Row max
 // and row sum are therefore lane-local plus one exchange between the two lane halves, one
 // lane needs one delta_Q and one delta_K per tile (Sec. 3.2's per-thread principle on this
-// accumulator layout), and the FP8 P~ registers are directly the B operand of
+// accumulator layout; finer key scales are a template option), and the FP8 P~ registers are directly the B operand of
 // O^T = V^^T P~^T (v_mfma_f32_32x32x64_f8f6f4, K = 64 = one accumulation block).  The
 // instruction sums the block's 64 products internally (level 1 of Sec. 3.4) and adds its C
 // operand - the running O - in full FP32 (level 2).
