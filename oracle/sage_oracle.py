@@ -125,8 +125,24 @@ def e5m2_encode(x):
     return code.astype(np.uint8)
 
 
+# INT8 for P~ and V, the third data type of the paper's comparison for the P~V product: P~ in [0, 1] with
+# the static scale 1/127, V per channel with max|V|/127, round-half-even, integer product.
+INT8_MAX = 127.0
+LOG2_127_F32 = np.float32(np.log2(127.0))
+
+
+def int8_encode(x):
+    return np.clip(np.rint(np.asarray(x, dtype=f64)), -INT8_MAX, INT8_MAX).astype(np.int8)
+
+
+def int8_decode(codes):
+    return np.asarray(codes, dtype=np.int8).astype(f64)
+
+
+# name -> (largest code magnitude, its log2 in FP32, encoder, decoder)
 _FP8 = {"e4m3": (E4M3_MAX, LOG2_448_F32, e4m3_encode, e4m3_decode),
-        "e5m2": (E5M2_MAX, LOG2_57344_F32, e5m2_encode, e5m2_decode)}
+        "e5m2": (E5M2_MAX, LOG2_57344_F32, e5m2_encode, e5m2_decode),
+        "int8": (INT8_MAX, LOG2_127_F32, int8_encode, int8_decode)}
 
 
 # --------------------------------------------------------------------------- group maps

@@ -497,3 +497,28 @@ def test_e5m2_stage_is_less_accurate_than_e4m3():
     assert np.array_equal(pb_["v_scale"], (np.abs(v).max(axis=0) / f32(57344.0)).astype(f32))
     assert wl.rel_l1(a, ref) < wl.rel_l1(b, ref) < 4 * wl.rel_l1(a, ref)
     assert wl.cos_sim(b, ref) > 0.995
+
+
+def test_int8_pv_variant_is_an_integer_product_with_static_scale_127():
+    """The INT8 choice for P~V of the paper's data-type comparison: V codes are the psi of Sec. 2.2 per channel
+    with qmax 127, P~ codes are rint(127 P~) (a row's largest P~ is 1 -> 127).  A uniform 7-bit grid loses the
+    many small P~ of a long row (below 1/254 they round to 0), a floating-point format does not: the INT8 error
+    grows with the sequence length and passes E4M3's, which is why the paper settles on E4M3 (Sec. 3.3)."""
+    errs = {}
+    for N in (256, 4096):
+        q, k, v = _head(N=N, d=32, seed=2)
+        ref = so.ref_attn_fp64(q, k, v)
+        a, _ = so.sage_attention_head(q, k, v, mode="int8_fp8", out_dtype="fp32")
+        b, pro = so.sage_attention_head(q, k, v, mode="int8_fp8", out_dtype="fp32", pv_fmt="int8")
+        errs[N] = (wl.rel_l1(a, ref), wl.rel_l1(b, ref))
+        if N == 256:
+            dv = (np.abs(v).max(axis=0) / f32(127.0)).astype(f32)
+            assert np.array_equal(pro["v_scale"], dv)
+            assert np.array_equal(pro["v_codes"],
+                                  np.clip(np.rint((v / dv[None, :]).astype(f32)), -127, 127).astype(np.int8))
+            assert np.abs(pro["v_codes"]).max() == 127
+            out, st = so.attention_rows(pro, slice(0, 128), False, out_dtype="fp32", return_state=True)
+            assert np.all(st["l"] >= 127.0 - 1e-3)      # the row maximum alone contributes 127 to 127 * l
+    assert errs[4096][1] > 1.5 * errs[256][1]           # INT8 degrades with the length ...
+    assert abs(errs[4096][0] - errs[256][0]) < 0.3 * errs[256][0]   # ... E4M3 does not
+    assert errs[4096][1] > errs[4096][0]
