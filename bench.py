@@ -59,8 +59,8 @@ def main():
     ap.add_argument("--group-map", default="lane", choices=["lane", "block", "fine", "token", "tensor"],
                     help="quantization granularity of Q and K: the default lane groups, one scale per block, "
                          "per query and 4 keys, or per token")
-    ap.add_argument("--pv-format", default="e4m3", choices=["e4m3", "e5m2"],
-                    help="8-bit float format of P~ and V: the paper's E4M3, or E5M2 for the comparison")
+    ap.add_argument("--pv-format", default="e4m3", choices=["e4m3", "e5m2", "int8"],
+                    help="8-bit data type of P~ and V: the paper's E4M3, or E5M2 / INT8 for the comparison")
     ap.add_argument("--smooth-v", action="store_true",
                     help="the optional smooth-V technique (one more pass over V in the prologue)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -151,7 +151,8 @@ def main():
         "metric": "quantized attention TOPS at d=128 (causal + non-causal), cos-sim vs FP32",
         "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8+fp8" if args.mode == "int8_fp8" else "int4+fp8", "data": "synthetic",
+        "dtype": ("int8" if args.mode == "int8_fp8" else "int4") + ("+int8" if args.pv_format == "int8" else "+fp8"),
+        "data": "synthetic",
         "config": {"workload": f"{spec.name}: B={spec.B} H={spec.H} H_kv={spec.H_kv} N={spec.N} d={spec.d} "
                                f"{spec.dtype} causal={spec.causal}", "mode": args.mode, "smooth_v": bool(args.smooth_v), "group_map": args.group_map, "pv_format": args.pv_format,
                    "ops_formula": "4*B*H*N^2*d" + ("/2" if spec.causal else "")},

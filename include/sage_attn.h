@@ -77,10 +77,12 @@ enum { SAGE_FLAG_SMOOTH_V = 1 };
    Queries / keys per entry of q_scale / k_scale: 2 / 16 (LANE, BLOCK, TENSOR), 1 / 4 (FINE), 1 / 1 (TOKEN). */
 enum { SAGE_GROUPS_LANE = 0, SAGE_GROUPS_BLOCK = 1, SAGE_GROUPS_FINE = 2, SAGE_GROUPS_TOKEN = 3,
        SAGE_GROUPS_TENSOR = 4 };
-/* 8-bit float format of P~ and V (Sec. 3.3; the paper's data-type comparison): E4M3 (the paper's choice,
-   static scale 1/448 for P~) or E5M2 (static scale 1/57344; one mantissa bit less, kept for the
-   comparison; not with SAGE_GROUPS_FINE / _TOKEN). */
-enum { SAGE_PV_E4M3 = 0, SAGE_PV_E5M2 = 1 };
+/* 8-bit data type of P~ and V (Sec. 3.3; the paper's data-type comparison): E4M3 (the paper's choice,
+   static scale 1/448 for P~), E5M2 (static scale 1/57344; one mantissa bit less) or INT8 (static scale
+   1/127, V per channel with max|V|/127, integer product converted and added to O in FP32 per block:
+   slower and, for long rows, less accurate).  The last two are kept for the comparison; not with
+   SAGE_GROUPS_FINE / _TOKEN. */
+enum { SAGE_PV_E4M3 = 0, SAGE_PV_E5M2 = 1, SAGE_PV_INT8 = 2 };
 /* Memory order of the four tensors (all contiguous): heads outside tokens, [B, H, N, d], or tokens
    outside heads, [B, N, H, d] (k, v: H_kv and N_kv).  The workspace layouts do not depend on it. */
 enum { SAGE_LAYOUT_HND = 0, SAGE_LAYOUT_NHD = 1 };
@@ -148,7 +150,7 @@ void sage_attn_release(void);
    All pointers are device buffers the caller allocates; a NULL member is skipped.
      q_codes [B,H,N,d] int8       codes of gamma(Q) (int4 mode) or Q (int8 mode), Sec. 3.2
      k_codes [B,H_kv,N_kv,d] int8    codes of gamma(K)
-     v_codes [B,H_kv,N_kv,d] uint8   E4M3 (or E5M2, see pv_format) codes of V / delta_V, Sec. 3.3
+     v_codes [B,H_kv,N_kv,d] uint8   E4M3 (or E5M2 / two's-complement INT8, see pv_format) codes of V / delta_V, Sec. 3.3
      q_scale [B,H,ceil(N/2)] f32  delta_Q per query group ([B,H,N] with SAGE_GROUPS_FINE / _TOKEN)
      k_scale [B,H_kv,ceil(N_kv/16)] f32   (ceil(N_kv/4) with SAGE_GROUPS_FINE, N_kv with SAGE_GROUPS_TOKEN)
      v_scale [B,H_kv,d] f32       delta_V per channel

@@ -18,8 +18,8 @@ _GROUP_SIZES = {0: (2, 16), 1: (2, 16), 2: (1, 4), 3: (1, 1), 4: (2, 16)}     # 
 SAGE_LAYOUT_HND, SAGE_LAYOUT_NHD = 0, 1
 _LAYOUTS = {"HND": 0, "NHD": 1, 0: 0, 1: 1}
 _MODES = {"int4_fp8": 0, "int8_fp8": 1, 0: 0, 1: 1}
-SAGE_PV_E4M3, SAGE_PV_E5M2 = 0, 1
-_PV_FORMATS = {"e4m3": 0, "e5m2": 1, 0: 0, 1: 1}
+SAGE_PV_E4M3, SAGE_PV_E5M2, SAGE_PV_INT8 = 0, 1, 2
+_PV_FORMATS = {"e4m3": 0, "e5m2": 1, "int8": 2, 0: 0, 1: 1, 2: 2}
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB = None

@@ -21,8 +21,8 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if ((a->flags & ~SAGE_FLAG_SMOOTH_V) != 0) return SAGE_ERR_UNSUPPORTED;
   if (a->group_map < SAGE_GROUPS_LANE || a->group_map > SAGE_GROUPS_TENSOR) return SAGE_ERR_UNSUPPORTED;
   if (a->layout != SAGE_LAYOUT_HND && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
-  if (a->pv_format != SAGE_PV_E4M3 && a->pv_format != SAGE_PV_E5M2) return SAGE_ERR_UNSUPPORTED;
-  if (a->pv_format == SAGE_PV_E5M2 && (a->group_map == SAGE_GROUPS_FINE || a->group_map == SAGE_GROUPS_TOKEN))
+  if (a->pv_format < SAGE_PV_E4M3 || a->pv_format > SAGE_PV_INT8) return SAGE_ERR_UNSUPPORTED;
+  if (a->pv_format != SAGE_PV_E4M3 && (a->group_map == SAGE_GROUPS_FINE || a->group_map == SAGE_GROUPS_TOKEN))
     return SAGE_ERR_UNSUPPORTED;
   if (a->cu_seqlens_k && !a->cu_seqlens_q) return SAGE_ERR_INVALID_ARG;
   if (a->cu_seqlens_q && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
@@ -48,7 +48,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   D->nhd = a->layout == SAGE_LAYOUT_NHD;
   D->seq.cu_q = a->cu_seqlens_q; D->seq.cu_k = a->cu_seqlens_k;
   D->want_lse = a->lse != nullptr;
-  D->e5m2 = a->pv_format == SAGE_PV_E5M2;
+  D->pvf = a->pv_format;        // SAGE_PV_* and PV_* share their values
   const float sm = a->sm_scale > 0.0f ? a->sm_scale : (float)(1.0 / std::sqrt((double)a->d));
   D->kappa = sm * LOG2E;   // one FP32 rounding of the product of two FP32 values
   return SAGE_OK;

@@ -183,7 +183,7 @@ __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2
 
 // update_max: running max over the block's 64 dequantized scores of this lane's query (Eq. 1 /
 // Algorithm 1); returns alpha = 2^(m_old - m_new) and, in m_sub, the exponent offset of the block.
-template <int D, bool INT4, int GM, bool E5M2>
+template <int D, bool INT4, int GM, int PVF>
 __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2], const Factors<GM>& fac,
                                             float& m_sub) {
   float mx;
@@ -223,14 +223,15 @@ __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2
   }
   const float m_new = fmaxf(st.m_run, mx);
   const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_new);   // 2^-inf = 0 on the first block
-  m_sub = m_new - (E5M2 ? LOG2_57344 : LOG2_448);                 // folds the *448 of Sec. 3.3
+  // folds the static scale of P~ (Sec. 3.3: *448; *57344 or *127 for the other data types) into the exponent
+  m_sub = m_new - (PVF == PV_INT8 ? LOG2_127 : (PVF == PV_E5M2 ? LOG2_57344 : LOG2_448));
   st.m_run = m_new;
   return alpha;
 }
 
 // exp_group: 448 * P~ = 2^(S - m_sub) for the group (INT8 mode: S = sc * c, fused), its row-sum share
 // added to ls, its FP8 codes written into word 4*KT + G of the P~ operand.
-template <bool INT4, bool MASKED, int GM, bool E5M2, int KT, int G>
+template <bool INT4, bool MASKED, int GM, int PVF, int KT, int G>
 __device__ __forceinline__ void exp_group(const v16i (&acc)[2], const Factors<GM>& fac, float m_sub, v8i& pb,
                                           float& ls) {
   float e[4];
@@ -248,7 +249,11 @@ __device__ __forceinline__ void exp_group(const v16i (&acc)[2], const Factors<GM
     ls += e[r];
   }
   int wd = __float_as_int(e[0]);   // any value: both halves are overwritten below
-  if constexpr (E5M2) {
+  if constexpr (PVF == PV_INT8) {
+    // rint(127 P~) in [0, 127] as bytes (the conversion is exact on the rounded values)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) wd = (int)__builtin_amdgcn_cvt_pk_u8_f32(rintf(e[r]), (unsigned)r, (unsigned)wd);
+  } else if constexpr (PVF == PV_E5M2) {
     wd = __builtin_amdgcn_cvt_pk_bf8_f32(e[0], e[1], wd, false);
     wd = __builtin_amdgcn_cvt_pk_bf8_f32(e[2], e[3], wd, true);
   } else {
@@ -274,15 +279,30 @@ __device__ __forceinline__ void block_rescale(RowState<D>& st, float alpha) {
     }
   }
 }
-template <int D, int CT, bool E5M2>
+// With INT8 codes the block's product is an integer matrix product (two K = 32 instructions) into a
+// fresh int32 accumulator - level 1 of Sec. 3.4 as the paper describes it - which is then converted and
+// added to O in FP32 (level 2): 32 more vector instructions per channel tile and block.
+template <int D, int CT, int PVF>
 __device__ __forceinline__ void pv_step(RowState<D>& st, const v4i (&va)[2 * (D / 32)], const v8i& pb) {
+  if constexpr (PVF == PV_INT8) {
+    const v4i p0 = {pb[0], pb[1], pb[2], pb[3]}, p1 = {pb[4], pb[5], pb[6], pb[7]};
+    v16i r;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) r[v] = 0;
+    r = __builtin_amdgcn_mfma_i32_32x32x32_i8(va[CT * 2 + 0], p0, r, 0, 0, 0);
+    r = __builtin_amdgcn_mfma_i32_32x32x32_i8(va[CT * 2 + 1], p1, r, 0, 0, 0);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) st.O[CT][v] = __fadd_rn(st.O[CT][v], (float)r[v]);
+    return;
+  }
   v8i a;
   const v4i a0 = va[CT * 2 + 0];
   const v4i a1 = va[CT * 2 + 1];
   a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
   a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
   // operand formats: 0 = E4M3, 1 = E5M2, for both V^ (A) and P^ (B)
-  st.O[CT] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, st.O[CT], E5M2 ? 1 : 0, E5M2 ? 1 : 0, 0, 0, 0, 0);
+  constexpr int FMT = PVF == PV_E5M2 ? 1 : 0;
+  st.O[CT] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, st.O[CT], FMT, FMT, 0, 0, 0, 0);
 }
 
 #ifndef SAGE_WAVES_PER_SIMD
@@ -313,7 +333,7 @@ __device__ __forceinline__ size_t lse_index(const AttnParams& p, const Seq& sq, 
   return ((size_t)b * p.H + h) * p.N + r;
 }
 
-template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, bool E5M2>
+template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, int PVF>
 __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const AttnParams p) {
   constexpr int KSC = GM == 0 ? 4 : (GM == 1 ? 16 : 64);    // key scales per block
   constexpr int QG = GM == 0 ? QGROUP : 1;                  // queries per scale
@@ -517,7 +537,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     Factors<GM> fn;
     fn.set(dq, p.kappa, ks);
     if (n_plain > 0) SAGE_DEQ_ALL(false, 0); else SAGE_DEQ_ALL(true, 0);
-    alpha = update_max<D, INT4, GM, E5M2>(st, sc, fn, m_sub);
+    alpha = update_max<D, INT4, GM, PVF>(st, sc, fn, m_sub);
     fj = fn;
   }
 
@@ -528,13 +548,13 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
 #define SAGE_X(GI_, MASKED_)                                                                         \
   do {                                                                                               \
     if constexpr ((GI_) < NQK) qk_step<D, INT4, (GI_) < NQK ? (GI_) : 0>(ka, qreg, raw);             \
-    exp_group<INT4, MASKED_, GM, E5M2, (GI_) / 4, (GI_) % 4>(sc, fj, m_sub, pb, ls);                 \
+    exp_group<INT4, MASKED_, GM, PVF, (GI_) / 4, (GI_) % 4>(sc, fj, m_sub, pb, ls);                  \
     __builtin_amdgcn_sched_barrier(0);                                                               \
   } while (0)
 #define SAGE_Y(CT_, MASKED_)                                                                         \
   do {                                                                                               \
     if constexpr ((CT_) < CT) {                                                                      \
-      pv_step<D, (CT_) < CT ? (CT_) : 0, E5M2>(st, va, pb);                                          \
+      pv_step<D, (CT_) < CT ? (CT_) : 0, PVF>(st, va, pb);                                           \
       SAGE_DEQ(MASKED_, (CT_) * GPC, (j + 1) * BKV);                                                 \
       SAGE_DEQ(MASKED_, (CT_) * GPC + 1, (j + 1) * BKV);                                             \
       if constexpr (GPC == 4) {                                                                      \
@@ -566,7 +586,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     Factors<GM> fn;                                                                                  \
     fn.set(dq, p.kappa, ks);                                                                         \
     SAGE_Y(0, MASKED_NEXT_); SAGE_Y(1, MASKED_NEXT_); SAGE_Y(2, MASKED_NEXT_); SAGE_Y(3, MASKED_NEXT_); /* Y */ \
-    alpha = update_max<D, INT4, GM, E5M2>(st, sc, fn, m_sub);                                              \
+    alpha = update_max<D, INT4, GM, PVF>(st, sc, fn, m_sub);                                              \
     fj = fn;                                                                                         \
     cur = nx1;                                                                                       \
   } while (0)
@@ -669,7 +689,7 @@ hipError_t launch_debug_mfma_fp8(const void* a, const void* b, const float* c, f
   return hipGetLastError();
 }
 
-template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, bool E5M2>
+template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, int PVF>
 static hipError_t launch_attention_g(const Dims& Dm, const Ptrs& P, hipStream_t s) {
   AttnParams p;
   p.q_codes = P.q_codes; p.k_codes = P.k_codes; p.v_codes = P.v_codes;
@@ -683,15 +703,17 @@ static hipError_t launch_attention_g(const Dims& Dm, const Ptrs& P, hipStream_t 
   p.total_tiles = Dm.B * Dm.H * Dm.nQb;
   p.kappa = Dm.kappa;
   const int grid = 8 * ((p.total_tiles + 7) / 8);
-  k_attn_fwd<D, INT4, CAUSAL, BF16, GM, E5M2><<<grid, 256, 0, s>>>(p);
+  k_attn_fwd<D, INT4, CAUSAL, BF16, GM, PVF><<<grid, 256, 0, s>>>(p);
   return hipGetLastError();
 }
 template <int D, bool INT4, bool CAUSAL, bool BF16>
 static hipError_t launch_attention_t(const Dims& Dm, const Ptrs& P, hipStream_t s) {
-  if (Dm.e5m2) return launch_attention_g<D, INT4, CAUSAL, BF16, 0, true>(Dm, P, s);   // default key groups only
-  if (Dm.kg == KGROUP) return launch_attention_g<D, INT4, CAUSAL, BF16, 0, false>(Dm, P, s);
-  if (Dm.kg == 4) return launch_attention_g<D, INT4, CAUSAL, BF16, 1, false>(Dm, P, s);
-  return launch_attention_g<D, INT4, CAUSAL, BF16, 2, false>(Dm, P, s);
+  // the other data types of P~V come with the default key groups only
+  if (Dm.pvf == PV_E5M2) return launch_attention_g<D, INT4, CAUSAL, BF16, 0, PV_E5M2>(Dm, P, s);
+  if (Dm.pvf == PV_INT8) return launch_attention_g<D, INT4, CAUSAL, BF16, 0, PV_INT8>(Dm, P, s);
+  if (Dm.kg == KGROUP) return launch_attention_g<D, INT4, CAUSAL, BF16, 0, PV_E4M3>(Dm, P, s);
+  if (Dm.kg == 4) return launch_attention_g<D, INT4, CAUSAL, BF16, 1, PV_E4M3>(Dm, P, s);
+  return launch_attention_g<D, INT4, CAUSAL, BF16, 2, PV_E4M3>(Dm, P, s);
 }
 
 hipError_t launch_attention(const Dims& D, const Ptrs& P, hipStream_t s) {

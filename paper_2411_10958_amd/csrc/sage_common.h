@@ -20,6 +20,9 @@ constexpr float LOG2_448 = 8.807354922057604f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float E5M2_MAX = 57344.0f;       // the E5M2 variant of the FP8 stage
 constexpr float LOG2_57344 = 15.807354922057604f;
+constexpr float INT8_PV_MAX = 127.0f;      // the INT8 variant of the P~V stage
+constexpr float LOG2_127 = 6.988684686772166f;
+enum { PV_E4M3 = 0, PV_E5M2 = 1, PV_INT8 = 2 };
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
@@ -88,7 +91,7 @@ struct Dims {
   float kappa; // fl32(sm_scale * log2 e)
   SeqMap seq;  // variable-length batch: N, Nk, nQb, nKb then describe the longest sequence
   int want_lse; // the caller asked for the row log-sum-exp
-  int e5m2;     // P~ and V in E5M2 instead of E4M3
+  int pvf;      // data type of P~ and V: PV_E4M3, PV_E5M2 or PV_INT8
   int tensor_groups;  // one scale per (batch, head) tensor of Q and of K (implies block_groups)
 };
 

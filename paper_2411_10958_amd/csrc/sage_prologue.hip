@@ -717,7 +717,7 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
 // order of the P~V product
 // (Sec. 3.3; Algorithm 1 "Preprocessing": (delta_V, V^) = psi_V(V)).  v_mean is null, or the token
 // mean to subtract first (smooth-V option, SMOOTH_V).
-template <bool BF16, int D, bool SMOOTH_V, bool E5M2>
+template <bool BF16, int D, bool SMOOTH_V, int PVF>
 __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restrict__ V,
                                                  const float* __restrict__ v_scale,
                                                  const float* __restrict__ v_mean,
@@ -756,7 +756,14 @@ __global__ void __launch_bounds__(256) k_quant_v(const unsigned short* __restric
       for (int e = 0; e < 8; ++e) x[e] = 0.0f;
     }
     int w0 = 0, w1 = 0;
-    if constexpr (E5M2) {
+    if constexpr (PVF == PV_INT8) {
+      // psi of Sec. 2.2 with qmax 127: |x / delta_V| <= 127 (1 + 2^-23), round-half-even, two's-complement bytes
+      int c[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) c[e] = (int)rintf(x[e]);
+      const uint2 pk = pack8(c);
+      w0 = (int)pk.x; w1 = (int)pk.y;
+    } else if constexpr (PVF == PV_E5M2) {
       w0 = __builtin_amdgcn_cvt_pk_bf8_f32(x[0], x[1], w0, false);
       w0 = __builtin_amdgcn_cvt_pk_bf8_f32(x[2], x[3], w0, true);
       w1 = __builtin_amdgcn_cvt_pk_bf8_f32(x[4], x[5], w1, false);
@@ -883,7 +890,7 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
   };
   if (!Dm.want_lse) quant_q();
   const int nchunk = (int)gstat.x;
-  const float code_max = Dm.e5m2 ? E5M2_MAX : E4M3_MAX;
+  const float code_max = Dm.pvf == PV_INT8 ? INT8_PV_MAX : (Dm.pvf == PV_E5M2 ? E5M2_MAX : E4M3_MAX);
   if (Dm.smooth_v) {
     k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.N, Dm.Nk, km, sm);
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
@@ -905,13 +912,17 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
     quant_k_pass(nullptr, 0);
   }
   const dim3 gv(Dm.nKb, BHkv);
+#define SAGE_QV(SV, PF, VM) k_quant_v<BF16, D, SV, PF><<<gv, 256, 0, s>>>(v, P.v_scale, VM, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm)
   if (Dm.smooth_v) {
-    if (Dm.e5m2) k_quant_v<BF16, D, true, true><<<gv, 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
-    else k_quant_v<BF16, D, true, false><<<gv, 256, 0, s>>>(v, P.v_scale, v_mean, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
+    if (Dm.pvf == PV_INT8) SAGE_QV(true, PV_INT8, v_mean);
+    else if (Dm.pvf == PV_E5M2) SAGE_QV(true, PV_E5M2, v_mean);
+    else SAGE_QV(true, PV_E4M3, v_mean);
   } else {
-    if (Dm.e5m2) k_quant_v<BF16, D, false, true><<<gv, 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
-    else k_quant_v<BF16, D, false, false><<<gv, 256, 0, s>>>(v, P.v_scale, nullptr, P.v_codes, Dm.N, Dm.Nk, Dm.nKb, km, sm);
+    if (Dm.pvf == PV_INT8) SAGE_QV(false, PV_INT8, nullptr);
+    else if (Dm.pvf == PV_E5M2) SAGE_QV(false, PV_E5M2, nullptr);
+    else SAGE_QV(false, PV_E4M3, nullptr);
   }
+#undef SAGE_QV
   return hipGetLastError();
 }
 

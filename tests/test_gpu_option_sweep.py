@@ -25,7 +25,7 @@ def _draw(rng):
     if causal and nk < n:
         nk = n
     group_map = str(rng.choice(list(GMAPS)))
-    pv = "e5m2" if (group_map in ("lane", "block", "tensor") and rng.random() < 0.3) else "e4m3"
+    pv = str(rng.choice(["e5m2", "int8"])) if (group_map in ("lane", "block", "tensor") and rng.random() < 0.4) else "e4m3"
     return dict(d=d, H=H, Hkv=Hkv, causal=causal, n=n, nk=nk, group_map=group_map, pv=pv,
                 mode=str(rng.choice(["int4_fp8", "int8_fp8"])), dtype=str(rng.choice(["bf16", "fp16"])),
                 layout=str(rng.choice(["HND", "NHD"])), smooth_v=bool(rng.random() < 0.3), lse=bool(rng.random() < 0.5),

@@ -250,26 +250,27 @@ def test_finer_groups_match_oracle(N, d, dtype, H, Hkv, causal, group_map, gmap,
     assert e_f <= e_l * 1.02      # finer groups are not worse (the paper's granularity table)
 
 
-# ---- E5M2 instead of E4M3 for P~ and V (the other format of the paper's data-type comparison) ----
+# ---- E5M2 or INT8 instead of E4M3 for P~ and V (the other data types of the paper's comparison) ----
 @pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("pv", ["e5m2", "int8"])
 @pytest.mark.parametrize("N,d,dtype,H,Hkv,causal", [(333, 128, "bf16", 2, 1, True), (640, 64, "fp16", 2, 2, False)])
-def test_e5m2_variant_matches_oracle(N, d, dtype, H, Hkv, causal, mode):
+def test_other_pv_data_types_match_oracle(N, d, dtype, H, Hkv, causal, pv, mode):
     pa = _pa()
     spec = _spec(N, d, dtype, H, Hkv, causal=causal)
     data, (q, k, v) = _gpu_inputs(spec)
-    print(f"e5m2 case N={N} d={d} {dtype} H={H}/{Hkv} causal={causal} mode={mode}", flush=True)
-    got, args, ws = pa.sage_attn_quant(q, k, v, causal=causal, mode=mode, pv_format="e5m2", want=("v_codes", "v_scale"))
-    out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, pv_format="e5m2")
+    print(f"{pv} case N={N} d={d} {dtype} H={H}/{Hkv} causal={causal} mode={mode}", flush=True)
+    got, args, ws = pa.sage_attn_quant(q, k, v, causal=causal, mode=mode, pv_format=pv, want=("v_codes", "v_scale"))
+    out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, pv_format=pv)
     e4 = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode)
     torch.cuda.synchronize()
     g = H // Hkv
     for h in range(Hkv):
-        pro = so.quantize_head(data["q"][0, h * g], data["k"][0, h], data["v"][0, h], mode=mode, pv_fmt="e5m2")
+        pro = so.quantize_head(data["q"][0, h * g], data["k"][0, h], data["v"][0, h], mode=mode, pv_fmt=pv)
         assert np.array_equal(got["v_scale"][0, h].cpu().numpy(), pro["v_scale"]), "v scales"
-        assert np.array_equal(got["v_codes"][0, h].cpu().numpy(), pro["v_codes"]), "v codes"
-    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32", pv_fmt="e5m2")
+        assert np.array_equal(got["v_codes"][0, h].cpu().numpy(), pro["v_codes"].view(np.uint8)), "v codes"
+    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32", pv_fmt=pv)
     check_output(wl.from_torch(out), ref, dtype)
-    if mode == "int8_fp8":     # where the FP8 stage dominates the error, E4M3 is the better format (Sec. 3.3)
+    if mode == "int8_fp8" and pv == "e5m2":   # where the FP8 stage dominates the error, E4M3 is the better format (Sec. 3.3)
         full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
                          for h in range(H)])
         assert wl.rel_l1(wl.from_torch(e4)[0], full) < wl.rel_l1(wl.from_torch(out)[0], full)
