@@ -201,7 +201,9 @@ __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2
       m0 = fmaxf(fmaxf(m0, __int_as_float(acc[0][v])), __int_as_float(acc[0][(v + 1) & 15]));
       m1 = fmaxf(fmaxf(m1, __int_as_float(acc[1][v])), __int_as_float(acc[1][(v + 1) & 15]));
     }
-    mx = fmaxf(__fmul_rn(m0, fac.at(0, 0, 0)), __fmul_rn(m1, fac.at(1, 0, 0)));
+    // |c|: the pipeline's last update works on a stale, fully masked block whose scales are arbitrary
+    // bits; -inf * |c| is -inf or NaN (dropped) whatever they are, so the running max stays intact
+    mx = fmaxf(__fmul_rn(m0, fabsf(fac.at(0, 0, 0))), __fmul_rn(m1, fabsf(fac.at(1, 0, 0))));
   } else {
     // the same per quad
     mx = -INFINITY;
@@ -211,7 +213,7 @@ __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2
       for (int g = 0; g < 4; ++g) {
         const float a = fmaxf(fmaxf(__int_as_float(acc[kt][4 * g]), __int_as_float(acc[kt][4 * g + 1])),
                               fmaxf(__int_as_float(acc[kt][4 * g + 2]), __int_as_float(acc[kt][4 * g + 3])));
-        mx = fmaxf(mx, __fmul_rn(a, fac.at(kt, g, 0)));
+        mx = fmaxf(mx, __fmul_rn(a, fabsf(fac.at(kt, g, 0))));
       }
     }
   }
@@ -542,9 +544,6 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   }
 
   int cur = 0;   // stage of block j
-  // exponent offset of the last block that was really processed (the running max minus log2 448): the
-  // pipeline's final update_max works on a stale stage and leaves st.m_run meaningless
-  float m_fin = -INFINITY;
 #define SAGE_X(GI_, MASKED_)                                                                         \
   do {                                                                                               \
     if constexpr ((GI_) < NQK) qk_step<D, INT4, (GI_) < NQK ? (GI_) : 0>(ka, qreg, raw);             \
@@ -582,7 +581,6 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     __builtin_amdgcn_sched_barrier(0);                                                               \
     SAGE_X(4, MASKED_); SAGE_X(5, MASKED_); SAGE_X(6, MASKED_); SAGE_X(7, MASKED_);                  \
     st.l_run = __fmaf_rn(alpha, st.l_run, ls);                                                       \
-    m_fin = m_sub;                                                                                   \
     Factors<GM> fn;                                                                                  \
     fn.set(dq, p.kappa, ks);                                                                         \
     SAGE_Y(0, MASKED_NEXT_); SAGE_Y(1, MASKED_NEXT_); SAGE_Y(2, MASKED_NEXT_); SAGE_Y(3, MASKED_NEXT_); /* Y */ \
@@ -620,7 +618,10 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   if (p.lse && half == 0 && query < sq.n) {
     // ln sum_t exp(sm_scale <q, k_t>) = ln 2 * (m + log2(l) + the row constant smoothing K dropped); l_tot = 448 l
     const float corr = p.q_corr[((size_t)bh * p.nQb + qb) * BQ + w * WQ + n];
-    p.lse[lse_index(p, sq, b, h, query)] = LN2 * ((m_fin + __builtin_amdgcn_logf(l_tot)) + corr);
+    // st.m_run survived the pipeline's last update: that one saw a fully masked (stale) block
+    constexpr float LOG2_SCALE = PVF == PV_INT8 ? LOG2_127 : (PVF == PV_E5M2 ? LOG2_57344 : LOG2_448);
+    p.lse[lse_index(p, sq, b, h, query)] =
+        LN2 * (((st.m_run - LOG2_SCALE) + __builtin_amdgcn_logf(l_tot)) + corr);
   }
   if (query < sq.n) {
     unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) +
