@@ -654,15 +654,13 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
         const v4f sc = *reinterpret_cast<const v4f*>(dv + c0);
         v4f vm = {0.0f, 0.0f, 0.0f, 0.0f};
         if (p.v_mean) vm = *reinterpret_cast<const v4f*>(p.v_mean + bhkv * D + c0);
-        unsigned short o4[4];
+        float o4[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          float o = __fmul_rn(__fmul_rn(st.O[ct][4 * g + r], inv_l), sc[r]);
-          if (p.v_mean) o = __fadd_rn(o, vm[r]);
-          o4[r] = store16<BF16>(o);
+          o4[r] = __fmul_rn(__fmul_rn(st.O[ct][4 * g + r], inv_l), sc[r]);
+          if (p.v_mean) o4[r] = __fadd_rn(o4[r], vm[r]);
         }
-        *reinterpret_cast<uint2*>(orow + c0) =
-            make_uint2((unsigned)o4[0] | ((unsigned)o4[1] << 16), (unsigned)o4[2] | ((unsigned)o4[3] << 16));
+        *reinterpret_cast<uint2*>(orow + c0) = make_uint2(pack16x2<BF16>(o4[0], o4[1]), pack16x2<BF16>(o4[2], o4[3]));
       }
     }
   }

@@ -274,6 +274,19 @@ __device__ inline unsigned short f32_to_fp16_rne(float x) {
 template <bool BF16> __device__ inline unsigned short store16(float x) {
   if constexpr (BF16) return f32_to_bf16_rne(x); else return f32_to_fp16_rne(x);
 }
+// two values rounded (nearest even) to the 16-bit type and packed, a in the low half: the hardware's
+// packed conversions (v_cvt_pk_bf16_f32 on gfx950)
+template <bool BF16> __device__ inline unsigned pack16x2(float a, float b) {
+  typedef float v2f_ __attribute__((ext_vector_type(2)));
+  const v2f_ x = {a, b};
+  if constexpr (BF16) {
+    typedef __bf16 v2b_ __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(x, v2b_));
+  } else {
+    typedef _Float16 v2h_ __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(x, v2h_));
+  }
+}
 
 // launchers (defined in the .hip files)
 hipError_t launch_prologue(const Dims& D, const Ptrs& P, hipStream_t s);
