@@ -18,7 +18,8 @@ if ROOT not in sys.path:
 PEAK_TOPS = 5000.0   # MI355X dense int8 / fp8 MFMA peak (both 5.0 POP/s)
 
 
-def cpu_baseline(spec, mode, budget_s=12.0, max_heads=32, smooth_v=False, gmap="g950", pv_fmt="e4m3"):
+def cpu_baseline(spec, mode, budget_s=12.0, max_heads=32, smooth_v=False, gmap="g950", pv_fmt="e4m3",
+                 smooth_k=True, smooth_q=True):
     """The CPU oracle as it stands, timed on whole heads of the same workload (as many heads
     as fit in about budget_s seconds)."""
     import numpy as np
@@ -35,7 +36,8 @@ def cpu_baseline(spec, mode, budget_s=12.0, max_heads=32, smooth_v=False, gmap="
                wl.make_head(spec, "v", 0, h * spec.H_kv // spec.H))
         t0 = time.perf_counter()
         o = so.sage_attention_head(*qkv, causal=spec.causal, mode=mode, out_dtype="fp32", smooth_v_on=smooth_v, gmap=gmap,
-                                   pv_fmt=pv_fmt)[0]
+                                   pv_fmt=pv_fmt, smooth_k_on=smooth_k,
+                                   smooth_q_on=smooth_q and mode == "int4_fp8")[0]
         dt += time.perf_counter() - t0
         heads.append((0, h)); ins.append(qkv); outs.append(o)
         if dt > budget_s:
@@ -63,6 +65,9 @@ def main():
                     help="8-bit data type of P~ and V: the paper's E4M3, or E5M2 / INT8 for the comparison")
     ap.add_argument("--smooth-v", action="store_true",
                     help="the optional smooth-V technique (one more pass over V in the prologue)")
+    ap.add_argument("--no-smooth-k", action="store_true", help="smoothing ablation: K is quantized as it is")
+    ap.add_argument("--no-smooth-q", action="store_true",
+                    help="smoothing ablation: Q is quantized as it is (4-bit mode; the 8-bit mode never smooths Q)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -86,7 +91,8 @@ def main():
     q, k, v = (wl.to_torch(data[n], spec.dtype, dev) for n in "qkv")
     out = torch.empty_like(q)
     a = pa.make_args(q, k, v, out, causal=spec.causal, mode=args.mode, smooth_v=args.smooth_v,
-                     group_map=args.group_map, pv_format=args.pv_format)
+                     group_map=args.group_map, pv_format=args.pv_format, smooth_k=not args.no_smooth_k,
+                     smooth_q=not args.no_smooth_q)
     ws = torch.empty(pa.sage_attn_workspace_bytes(a), dtype=torch.uint8, device=dev)
     a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel()
 
@@ -154,7 +160,9 @@ def main():
         "dtype": ("int8" if args.mode == "int8_fp8" else "int4") + ("+int8" if args.pv_format == "int8" else "+fp8"),
         "data": "synthetic",
         "config": {"workload": f"{spec.name}: B={spec.B} H={spec.H} H_kv={spec.H_kv} N={spec.N} d={spec.d} "
-                               f"{spec.dtype} causal={spec.causal}", "mode": args.mode, "smooth_v": bool(args.smooth_v), "group_map": args.group_map, "pv_format": args.pv_format,
+                               f"{spec.dtype} causal={spec.causal}", "mode": args.mode, "smooth_v": bool(args.smooth_v),
+                   "smooth_k": not args.no_smooth_k, "smooth_q": not args.no_smooth_q and args.mode == "int4_fp8",
+                   "group_map": args.group_map, "pv_format": args.pv_format,
                    "ops_formula": "4*B*H*N^2*d" + ("/2" if spec.causal else "")},
         "breakdown_ms": {"prologue": round(ms_pro, 4), "attention_kernel": round(ms_core, 4)},
         "roofline": {"bound": "mfma", "kernel": "k_attn_fwd", "achieved": round(core_tops, 2), "peak": PEAK_TOPS,
@@ -168,7 +176,8 @@ def main():
         from oracle import sage_oracle as so
         base, heads, ins, outs = cpu_baseline(spec, args.mode, smooth_v=args.smooth_v,
                                                 gmap={"lane": "g950", "block": "per_block", "fine": "fine",
-                                                      "token": "per_token", "tensor": "per_tensor"}[args.group_map], pv_fmt=args.pv_format)
+                                                      "token": "per_token", "tensor": "per_tensor"}[args.group_map], pv_fmt=args.pv_format,
+                                                smooth_k=not args.no_smooth_k, smooth_q=not args.no_smooth_q)
         res["cpu_baseline"] = base
         got = np.stack([wl.from_torch(out[b, h]) for b, h in heads])
         ref = np.stack(outs)

@@ -60,8 +60,13 @@ enum { SAGE_DT_FP16 = 0, SAGE_DT_BF16 = 1 };
 /* Optional techniques, or-ed into sage_attn_args.flags.
    SAGE_FLAG_SMOOTH_V: the optional "smooth V" of Sec. 3.4 (last paragraph; Appendix "Smoothing V"):
    the per-channel token mean of V is subtracted before the FP8 quantizer and added back, in FP32, to
-   the output (rows of the softmax sum to 1).  Costs one more pass over V in the preprocessing. */
-enum { SAGE_FLAG_SMOOTH_V = 1 };
+   the output (rows of the softmax sum to 1).  Costs one more pass over V in the preprocessing.
+   SAGE_FLAG_NO_SMOOTH_K / SAGE_FLAG_NO_SMOOTH_Q switch off the smoothing of K (Eq. 2) or of Q (Sec. 3.1)
+   for the rows "none" and "only K" of the paper's smoothing ablation: the corresponding mean is taken
+   as zero (k_mean, q_mean and, without Q smoothing, delta_s hold zeros; no Delta-S product is computed).
+   They change accuracy only, not the kernels.  The 8-bit mode never smooths Q, so NO_SMOOTH_Q changes
+   nothing there. */
+enum { SAGE_FLAG_SMOOTH_V = 1, SAGE_FLAG_NO_SMOOTH_K = 2, SAGE_FLAG_NO_SMOOTH_Q = 4 };
 /* Quantization granularity of Q and K (Sec. 3.2; the ablation of the paper's granularity table).
    SAGE_GROUPS_LANE: the default, the gfx950 counterpart of per-thread quantization (SAGE_Q_GROUP /
    SAGE_K_GROUP below).  SAGE_GROUPS_BLOCK: one scale per 128-query block and per 64-key block

@@ -240,7 +240,7 @@ __global__ void __launch_bounds__(256) k_v_absmax(const unsigned short* __restri
 __global__ void k_finalize_stats(const double* __restrict__ k_sum, const double* __restrict__ v_sum,
                                  const unsigned* __restrict__ v_max, float* __restrict__ k_mean,
                                  float* __restrict__ v_mean, float* __restrict__ v_scale, int n, int Nq, int N,
-                                 int d, int Hkv, int nchunk, SeqMap sm, float code_max) {
+                                 int d, int Hkv, int nchunk, SeqMap sm, float code_max, int smooth_k) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) {
     const int head = i / d, c = i - head * d;
@@ -253,7 +253,7 @@ __global__ void k_finalize_stats(const double* __restrict__ k_sum, const double*
       if (v_sum) vs += v_sum[p0 + (size_t)ch * d];
       else vm = fmaxf(vm, __uint_as_float(v_max[p0 + (size_t)ch * d]));
     }
-    k_mean[i] = nk > 0 ? (float)(ks / (double)nk) : 0.0f;
+    k_mean[i] = nk > 0 && smooth_k ? (float)(ks / (double)nk) : 0.0f;   // smoothing of K off: mean 0
     if (v_sum) v_mean[i] = nk > 0 ? (float)(vs / (double)nk) : 0.0f;
     else v_scale[i] = __fdiv_rn(vm, code_max);
   }
@@ -393,7 +393,7 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
                                                   int block_groups, int qg, TensorMap qm, SeqMap sm,
                                                   float* __restrict__ q_corr, const float* __restrict__ k_mean,
                                                   int G, float kappa, const float* __restrict__ head_scale,
-                                                  int stats_only) {
+                                                  int stats_only, int smooth_q) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;   // load map: RPT rows x 8 channels
   constexpr int CPL = D / 4, CPC = CPL / 8;                      // quantization map: 2 rows x CPL channels
   constexpr int QMAX = 7;
@@ -441,7 +441,7 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
   if (t < D) {
     double sm = 0.0;
     for (int g = 0; g < NRG; ++g) sm += s_sum[g][t];
-    const float m = (float)(sm / (double)valid);
+    const float m = smooth_q ? (float)(sm / (double)valid) : 0.0f;   // smoothing of Q off: mean 0
     s_mean[t] = m;
     q_mean[(bh * nQb + qb) * D + t] = m;
   }
@@ -549,7 +549,8 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
                                                  float* __restrict__ delta_s, int Nq, int Nmax, int nKb,
                                                  int nQb, int G, float kappa, int block_groups, int kg,
                                                  int causal, TensorMap km, SeqMap sm,
-                                                 const float* __restrict__ head_scale, int stats_only) {
+                                                 const float* __restrict__ head_scale, int stats_only,
+                                                 int zero_ds) {
   constexpr int CPL = D / 4;                       // channels per lane (32 or 16)
   constexpr int QMAX = INT4 ? 7 : 127;
   // LDS row of staged block means: channel c sits at column c + 16*(c / 32) when D = 128, so the
@@ -692,12 +693,14 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
       __syncthreads();
       if (next_pass(p) < npass) load_q(next_pass(p));   // next pass, in flight under the MFMAs
       v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+      if (!zero_ds) {      // (Q not smoothed: the block means are zero and so is Delta-S)
 #pragma unroll
-      for (int cs = 0; cs < CPL; ++cs) {
-        asm volatile("" : "+v"(x[cs]));              // keeps the widening inside the pass loop
-        const double bk = (double)x[cs];
-        acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[r16][qcol + cs], bk, acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[16 + r16][qcol + cs], bk, acc1, 0, 0, 0);
+        for (int cs = 0; cs < CPL; ++cs) {
+          asm volatile("" : "+v"(x[cs]));            // keeps the widening inside the pass loop
+          const double bk = (double)x[cs];
+          acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[r16][qcol + cs], bk, acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[16 + r16][qcol + cs], bk, acc1, 0, 0, 0);
+        }
       }
       const size_t bh = bhkv * G + p / npass_h;
       const int i0 = (p % npass_h) * DS_QROWS;
@@ -865,7 +868,7 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
     if constexpr (INT4)
       k_quant_q4<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
                                                        Dm.block_groups, Dm.qg, qm, sm, corr, P.k_mean,
-                                                       Dm.H / Dm.Hkv, Dm.kappa, head_scale, stats_only);
+                                                       Dm.H / Dm.Hkv, Dm.kappa, head_scale, stats_only, Dm.smooth_q);
     else
       k_quant_q8<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
                                                        Dm.block_groups, Dm.qg, qm, sm, corr, P.k_mean,
@@ -886,7 +889,7 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
     k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
                                                                 P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
                                                                 Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.kg,
-                                                                Dm.causal, km, sm, head_scale, stats_only);
+                                                                Dm.causal, km, sm, head_scale, stats_only, !Dm.smooth_q);
   };
   if (!Dm.want_lse) quant_q();
   const int nchunk = (int)gstat.x;
@@ -894,13 +897,13 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
   if (Dm.smooth_v) {
     k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.N, Dm.Nk, km, sm);
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
-                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max);
+                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max, Dm.smooth_k);
     k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.N, Dm.Nk, km, sm);
     k_finalize_vscale<<<(nstat + 255) / 256, 256, 0, s>>>(P.v_max, P.v_scale, nstat, Dm.d, nchunk, code_max);
   } else {
     k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.N, Dm.Nk, km, sm);
     k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
-                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max);
+                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max, Dm.smooth_k);
   }
   if (Dm.want_lse) quant_q();
   if (Dm.tensor_groups) {

@@ -185,6 +185,46 @@ def test_smooth_v_matches_oracle(N, d, dtype, H, Hkv, causal, mode):
     assert e_s < e_p        # the ordering the paper's table for this technique reports
 
 
+# ---- smoothing ablation (Sec. 3.1, Eq. 2; the paper's table of smoothing variants: none / only K / Q and K) ----
+@pytest.mark.parametrize("smooth_k,smooth_q", [(False, False), (True, False), (False, True)])
+@pytest.mark.parametrize("N,d,dtype,H,Hkv,causal", [(300, 64, "fp16", 2, 2, False), (448, 128, "bf16", 4, 2, True)])
+def test_smoothing_switched_off_matches_oracle(N, d, dtype, H, Hkv, causal, smooth_k, smooth_q):
+    pa = _pa()
+    spec = _spec(N, d, dtype, H, Hkv, causal=causal)
+    data, (q, k, v) = _gpu_inputs(spec)
+    print(f"smoothing ablation N={N} d={d} {dtype} H={H}/{Hkv} causal={causal} K={smooth_k} Q={smooth_q}", flush=True)
+    got, args, ws = pa.sage_attn_quant(q, k, v, causal=causal, smooth_k=smooth_k, smooth_q=smooth_q)
+    torch.cuda.synchronize()
+    got = {n: t.cpu().numpy() for n, t in got.items()}
+    g = H // Hkv
+    for b in range(spec.B):
+        for h in range(H):
+            pro = so.quantize_head(data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g],
+                                   smooth_q_on=smooth_q, smooth_k_on=smooth_k)
+            assert np.array_equal(got["q_codes"][b, h], pro["q_codes"]), "q codes"
+            assert np.array_equal(got["q_scale"][b, h], pro["q_scale"]), "q scales"
+            assert np.array_equal(got["k_codes"][b, h // g], pro["k_codes"]), "k codes"
+            assert np.array_equal(got["k_scale"][b, h // g], pro["k_scale"]), "k scales"
+            assert np.array_equal(got["k_mean"][b, h // g], pro["kbar"]), "k mean (zeros without K smoothing)"
+            if smooth_q:
+                assert np.array_equal(got["q_mean"][b, h], pro["qbar"]), "q block means"
+                D = pro["delta_s"].astype(np.float64)
+                diff = np.abs(got["delta_s"][b, h].astype(np.float64) - D)
+                assert np.all(diff <= np.spacing(np.abs(D))), "delta S"
+            else:
+                assert not got["q_mean"][b, h].any() and not got["delta_s"][b, h].any(), "no Q smoothing: zeros"
+    out, lse = pa.sage_attn_fwd_ex(q, k, v, causal=causal, smooth_k=smooth_k, smooth_q=smooth_q, return_lse=True)
+    torch.cuda.synchronize()
+    ref = np.empty((spec.B, H, N, d), np.float32)
+    for b in range(spec.B):
+        for h in range(H):
+            ref[b, h], pro = so.sage_attention_head(data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g],
+                                                    causal=causal, out_dtype="fp32", want_lse=True,
+                                                    smooth_q_on=smooth_q, smooth_k_on=smooth_k)
+            _lse_close(lse[b, h].cpu().numpy(), pro["lse"])
+    check_output(wl.from_torch(out), ref, dtype)
+
+
 # ---- per-block and per-tensor granularity (Sec. 2.2 / 2.3 / 3.2: the coarser groupings the paper compares with) ----
 @pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
 @pytest.mark.parametrize("group_map,gmap", [("block", "per_block"), ("tensor", "per_tensor")])
