@@ -26,10 +26,18 @@ def _draw(rng):
         nk = n
     group_map = str(rng.choice(list(GMAPS)))
     pv = str(rng.choice(["e5m2", "int8"])) if (group_map in ("lane", "block", "tensor") and rng.random() < 0.4) else "e4m3"
-    return dict(d=d, H=H, Hkv=Hkv, causal=causal, n=n, nk=nk, group_map=group_map, pv=pv,
-                mode=str(rng.choice(["int4_fp8", "int8_fp8"])), dtype=str(rng.choice(["bf16", "fp16"])),
-                layout=str(rng.choice(["HND", "NHD"])), smooth_v=bool(rng.random() < 0.3), lse=bool(rng.random() < 0.5),
-                vbias=float(rng.choice([0.0, 4.0])))
+    c = dict(d=d, H=H, Hkv=Hkv, causal=causal, n=n, nk=nk, group_map=group_map, pv=pv,
+             mode=str(rng.choice(["int4_fp8", "int8_fp8"])), dtype=str(rng.choice(["bf16", "fp16"])),
+             layout=str(rng.choice(["HND", "NHD"])), smooth_v=bool(rng.random() < 0.3), lse=bool(rng.random() < 0.5),
+             vbias=float(rng.choice([0.0, 4.0])))
+    # the smoothing switches are drawn last so that the earlier draws of a seed stay what they were
+    c["smooth_k"] = bool(rng.random() >= 0.25)
+    c["smooth_q"] = bool(rng.random() >= 0.25)
+    return c
+
+
+def _oracle_smoothing(c):
+    return dict(smooth_k_on=c["smooth_k"], smooth_q_on=c["smooth_q"] and c["mode"] == "int4_fp8")
 
 
 @pytest.mark.parametrize("seed", range(24))
@@ -46,7 +54,8 @@ def test_option_combination_matches_oracle(seed):
     if c["layout"] == "NHD":
         q, k, v = (t.permute(0, 2, 1, 3).contiguous() for t in (q, k, v))
     res = pa.sage_attn_fwd_ex(q, k, v, causal=c["causal"], mode=c["mode"], smooth_v=c["smooth_v"], group_map=c["group_map"],
-                              layout=c["layout"], pv_format=c["pv"], return_lse=c["lse"])
+                              layout=c["layout"], pv_format=c["pv"], return_lse=c["lse"], smooth_k=c["smooth_k"],
+                              smooth_q=c["smooth_q"])
     torch.cuda.synchronize()
     out, lse = res if c["lse"] else (res, None)
     if c["layout"] == "NHD":
@@ -58,7 +67,7 @@ def test_option_combination_matches_oracle(seed):
             ref[b, h], pro = so.sage_attention_head(data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g],
                                                     causal=c["causal"], mode=c["mode"], gmap=GMAPS[c["group_map"]],
                                                     out_dtype="fp32", smooth_v_on=c["smooth_v"], pv_fmt=c["pv"],
-                                                    want_lse=c["lse"])
+                                                    want_lse=c["lse"], **_oracle_smoothing(c))
             if c["lse"]:
                 _lse_close(lse[b, h].cpu().numpy(), pro["lse"])
     check_output(wl.from_torch(out), ref, c["dtype"])
@@ -87,7 +96,8 @@ def test_packed_batch_combination_matches_oracle(seed):
     cu = lambda lens: torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev)
     q, k, v = pack(qs), pack(ks), pack(vs)
     res = pa.sage_attn_fwd_ex(q, k, v, causal=c["causal"], mode=c["mode"], smooth_v=c["smooth_v"], group_map=c["group_map"],
-                              pv_format=c["pv"], return_lse=c["lse"], cu_seqlens_q=cu(lens_q), cu_seqlens_k=cu(lens_k))
+                              pv_format=c["pv"], return_lse=c["lse"], cu_seqlens_q=cu(lens_q), cu_seqlens_k=cu(lens_k),
+                              smooth_k=c["smooth_k"], smooth_q=c["smooth_q"])
     torch.cuda.synchronize()
     out, lse = res if c["lse"] else (res, None)
     off = np.concatenate([[0], np.cumsum(lens_q)])
@@ -100,7 +110,7 @@ def test_packed_batch_combination_matches_oracle(seed):
         for h in range(c["H"]):
             ref[h], pro = so.sage_attention_head(qn[h], kn[h // g], vn[h // g], causal=c["causal"], mode=c["mode"],
                                                  gmap=GMAPS[c["group_map"]], out_dtype="fp32", smooth_v_on=c["smooth_v"],
-                                                 pv_fmt=c["pv"], want_lse=c["lse"])
+                                                 pv_fmt=c["pv"], want_lse=c["lse"], **_oracle_smoothing(c))
             if c["lse"]:
                 _lse_close(lse[h, off[i]:off[i + 1]].cpu().numpy(), pro["lse"])
         check_output(wl.from_torch(out[off[i]:off[i + 1]]).transpose(1, 0, 2), ref, c["dtype"])
