@@ -105,7 +105,7 @@ typedef struct sage_attn_args {
   const void* k;          /* device, [B, H_kv, N_kv, d] */
   const void* v;          /* device, [B, H_kv, N_kv, d] */
   void* out;              /* device, [B, H, N, d], written */
-  int B, H, H_kv, N, d;
+  int B, H, H_kv, N, d;   /* d = 64 or 128; H a multiple of H_kv; N and N_kv <= 2^24; B * H <= 65535 */
   int causal;             /* 0: every key visible; 1: key t visible to query r iff t <= r + N_kv - N */
   float sm_scale;         /* <= 0 means 1/sqrt(d) */
   int mode;               /* SAGE_MODE_* */
@@ -146,7 +146,8 @@ int sage_attn_core(const sage_attn_args* args);
 
 /* Convenience form named by the problem statement (Sec. 2.1: O = softmax(QK^T/sqrt(d))V):
    bf16 tensors, H_kv = H, default stream, and a workspace the library allocates lazily with
-   hipMalloc, grows when needed and keeps until sage_attn_release().  Not thread-safe. */
+   hipMalloc on the current device, grows when needed (or when the current device changed) and keeps until
+   sage_attn_release().  Not thread-safe. */
 int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int H, int N,
                   int d, int causal, float sm_scale, int mode);
 void sage_attn_release(void);

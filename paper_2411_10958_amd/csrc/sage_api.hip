@@ -13,6 +13,8 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if (!a) return SAGE_ERR_INVALID_ARG;
   if (a->B <= 0 || a->H <= 0 || a->H_kv <= 0 || a->N <= 0 || a->d <= 0) return SAGE_ERR_INVALID_ARG;
   if (a->H % a->H_kv != 0 || a->N_kv < 0) return SAGE_ERR_INVALID_ARG;
+  // token indices and their tile arithmetic stay in 32-bit integers inside the kernels
+  if (a->N > MAX_TOKENS || a->N_kv > MAX_TOKENS) return SAGE_ERR_UNSUPPORTED;
   const int Nk = a->N_kv > 0 ? a->N_kv : a->N;
   if (a->causal && Nk < a->N) return SAGE_ERR_UNSUPPORTED;
   if (a->d != 64 && a->d != 128) return SAGE_ERR_UNSUPPORTED;
@@ -70,6 +72,20 @@ int hip_status(hipError_t e) {
 
 void* g_ws = nullptr;      // workspace of the convenience entry point
 size_t g_ws_bytes = 0;
+int g_ws_device = -1;      // the device it was allocated on
+
+// Frees the convenience workspace on the device that owns it (after that device's work is done).
+hipError_t release_ws() {
+  if (!g_ws) return hipSuccess;
+  int cur = -1;
+  hipError_t e = hipGetDevice(&cur);
+  if (e == hipSuccess && cur != g_ws_device) e = hipSetDevice(g_ws_device);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e == hipSuccess) e = hipFree(g_ws);
+  if (cur >= 0 && cur != g_ws_device) (void)hipSetDevice(cur);
+  g_ws = nullptr; g_ws_bytes = 0; g_ws_device = -1;
+  return e;
+}
 
 }  // namespace
 
@@ -121,26 +137,19 @@ int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B,
     Dims D;
     return validate(&a, &D, true);
   }
-  if (need > g_ws_bytes) {
-    if (g_ws) {
-      if (hipDeviceSynchronize() != hipSuccess) return hip_status(hipErrorUnknown);
-      (void)hipFree(g_ws);
-      g_ws = nullptr; g_ws_bytes = 0;
-    }
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return hip_status(hipErrorUnknown);
+  if (need > g_ws_bytes || dev != g_ws_device) {     // grow, or follow the caller to another device
+    if (release_ws() != hipSuccess) return hip_status(hipErrorUnknown);
     if (hipMalloc(&g_ws, need) != hipSuccess) { g_ws = nullptr; return hip_status(hipErrorOutOfMemory); }
     g_ws_bytes = need;
+    g_ws_device = dev;
   }
   a.workspace = g_ws; a.workspace_bytes = g_ws_bytes;
   return sage_attn_fwd_ex(&a);
 }
 
-void sage_attn_release(void) {
-  if (g_ws) {
-    (void)hipDeviceSynchronize();
-    (void)hipFree(g_ws);
-    g_ws = nullptr; g_ws_bytes = 0;
-  }
-}
+void sage_attn_release(void) { (void)release_ws(); }
 
 int sage_attn_quant(const sage_attn_args* args, const sage_quant_out* out) {
   if (!out) return SAGE_ERR_INVALID_ARG;

@@ -14,6 +14,7 @@ constexpr int WQ = 32;       // queries per wavefront (one 32x32 MFMA column til
 constexpr int QGROUP = 2;    // queries per quantization group (default group map)
 constexpr int KGROUP = 16;   // keys per quantization group (default group map)
 constexpr float E4M3_MAX = 448.0f;
+constexpr int MAX_TOKENS = 1 << 24;   // per sequence; keeps token and tile arithmetic inside 32-bit integers
 constexpr int STAT_ROWS = 256;  // tokens per workgroup of the column-statistics pass
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LOG2_448 = 8.807354922057604f;
@@ -262,18 +263,6 @@ __device__ inline float fp16_to_f32(unsigned short u) {
 }
 template <bool BF16> __device__ inline float load16(unsigned short u) {
   if constexpr (BF16) return bf16_to_f32(u); else return fp16_to_f32(u);
-}
-__device__ inline unsigned short f32_to_bf16_rne(float x) {
-  unsigned u = __float_as_uint(x);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40);  // NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (unsigned short)(u >> 16);
-}
-__device__ inline unsigned short f32_to_fp16_rne(float x) {
-  return __builtin_bit_cast(unsigned short, (_Float16)x);
-}
-template <bool BF16> __device__ inline unsigned short store16(float x) {
-  if constexpr (BF16) return f32_to_bf16_rne(x); else return f32_to_fp16_rne(x);
 }
 // two values rounded (nearest even) to the 16-bit type and packed, a in the low half: the hardware's
 // packed conversions (v_cvt_pk_bf16_f32 on gfx950)

@@ -71,12 +71,13 @@ def test_workspace_size_formula():
 
 def test_argument_errors_are_found_on_the_host():
     pa, lib = _lib()
-    bad = [dict(d=96), dict(d=256), dict(mode=2), dict(dtype=3), dict(flags=8), dict(flags=-1), dict(group_map=5), dict(group_map=-1), dict(layout=2), dict(pv_format=3),
+    bad = [dict(d=96), dict(d=256), dict(mode=2), dict(dtype=3), dict(flags=8), dict(flags=-1), dict(N=(1 << 24) + 1), dict(N_kv=(1 << 24) + 1), dict(group_map=5), dict(group_map=-1), dict(layout=2), dict(pv_format=3),
            dict(pv_format=1, group_map=2)]
     for kw in bad:
         a = _args(pa, **kw)
         assert pa.sage_attn_workspace_bytes(a) == 0
         assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -2, kw
+    assert pa.sage_attn_workspace_bytes(_args(pa, B=600, H=128, H_kv=128)) == 0      # B * H beyond the grid limit
     for kw in [dict(N=0), dict(B=-1), dict(H_kv=5)]:
         a = _args(pa, **kw)
         assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -1, kw
