@@ -484,8 +484,25 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   v4f dsr[2][4];
   KeyScales<GM> ks;
   auto read_k = [&](int stg) {
+    if constexpr (INT4) {
+      // The 8-byte tail of every FP6 operand is read by hand: left to itself the compiler pairs the tails
+      // of two operands into one two-address read and then moves the halves of its result next to their
+      // operands' first four registers, two vector instructions per operand in a loop that is bound by
+      // them.  The tail goes out before the operand's 16-byte read, which the compiler does see and
+      // waits for: LDS reads return in order, so that wait covers the tail too.
+      const unsigned tail0 = lds0 + (unsigned)stg * (STAGE * 16) + 1024u + 8u * (unsigned)lane;
 #pragma unroll
-    for (int i = 0; i < 2 * NP; ++i) ka[i] = load_qk_operand<INT4>(&lds[stg][0], i, lane);
+      for (int i = 0; i < 2 * NP; ++i) {
+        v2i hi;
+        asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(hi) : "v"(tail0), "n"(i * OP6_BYTES) : "memory");
+        const v4i lo = lds[stg][i * (OP6_BYTES / 16) + lane];
+        ka[i][0] = lo[0]; ka[i][1] = lo[1]; ka[i][2] = lo[2]; ka[i][3] = lo[3];
+        ka[i][4] = hi[0]; ka[i][5] = hi[1]; ka[i][6] = 0; ka[i][7] = 0;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2 * NP; ++i) ka[i] = load_qk_operand<INT4>(&lds[stg][0], i, lane);
+    }
   };
   auto read_v = [&](int stg) {
 #pragma unroll

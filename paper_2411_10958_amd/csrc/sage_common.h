@@ -25,6 +25,7 @@ constexpr float INT8_PV_MAX = 127.0f;      // the INT8 variant of the P~V stage
 constexpr float LOG2_127 = 6.988684686772166f;
 enum { PV_E4M3 = 0, PV_E5M2 = 1, PV_INT8 = 2 };
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
