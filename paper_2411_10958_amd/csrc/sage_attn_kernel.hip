@@ -349,6 +349,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   constexpr int XC = 32;              // chunks of the small part: 64 Delta-S floats, then up to 64 key scales
   constexpr int STAGE = KCK + KC + XC;   // chunks per stage: K^, V^, small part
   __shared__ v4i lds[NST][STAGE];
+  __shared__ __align__(16) float s_vs[2][D];   // delta_V and (smooth-V option) mean(V) of this KV head, for the epilogue
 
   // XCD-aware tile order: consecutive workgroup ids land on different XCDs (8 of them), so
   // give every XCD a contiguous range of tiles - tiles of one head then share one L2.
@@ -425,6 +426,19 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   // "at most n outstanding" still covers the load it means).  Under a causal mask, where many tiles are
   // short, the same order measured 1 % slower at N = 8192 and 16384, so there the copies follow the loads.
   constexpr bool COPIES_FIRST = !CAUSAL;
+  // The epilogue's per-channel constants travel to LDS now (wavefronts 2 and 3, one copy per 64 channels):
+  // read from global memory at the end of the tile, their round trip was idle time of the workgroup's share
+  // of the CU.  These copies are older than every block copy, so the wait counts below still hold.
+  {
+    const unsigned vs0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)&s_vs[0][0];
+    if (w == 2) {
+#pragma unroll
+      for (int i = 0; i < D / 64; ++i) dma_b32(p.v_scale + bhkv * D + 64 * i, (unsigned)lane * 4, vs0 + 256u * i);
+    } else if (w == 3 && p.v_mean) {
+#pragma unroll
+      for (int i = 0; i < D / 64; ++i) dma_b32(p.v_mean + bhkv * D + 64 * i, (unsigned)lane * 4, vs0 + 4u * D + 256u * i);
+    }
+  }
   if constexpr (COPIES_FIRST) {
     issue(0, 0);
     if (nblk > 1) issue(1, 1);
@@ -662,15 +676,14 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   if (query < sq.n) {
     unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) +
                            row_offset(p.om, head_offset(p.om, (unsigned)bh), (int)sq.q0 + query);
-    const float* dv = p.v_scale + bhkv * D;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int c0 = 32 * ct + 8 * g + 4 * half;
-        const v4f sc = *reinterpret_cast<const v4f*>(dv + c0);
+        const v4f sc = *reinterpret_cast<const v4f*>(&s_vs[0][c0]);
         v4f vm = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (p.v_mean) vm = *reinterpret_cast<const v4f*>(p.v_mean + bhkv * D + c0);
+        if (p.v_mean) vm = *reinterpret_cast<const v4f*>(&s_vs[1][c0]);
         float o4[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
