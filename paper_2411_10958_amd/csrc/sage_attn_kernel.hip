@@ -455,6 +455,9 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     for (int s = 0; s < NP; ++s) qreg[s] = load_qk_operand<INT4>(gq, s, lane);
   }
   const float dq = p.q_scale[((size_t)bh * p.nQb + qb) * (BQ / QG) + (w * WQ + n) / QG];
+  // the row constant of the log-sum-exp output, fetched now so that the epilogue does not wait for it
+  float lse_corr = 0.0f;
+  if (p.lse) lse_corr = p.q_corr[((size_t)bh * p.nQb + qb) * BQ + w * WQ + n];
 
   RowState<D> st;
 #pragma unroll
@@ -556,6 +559,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     for (int i = 0; i < (int)(sizeof(qk_op) / 4); ++i) use_now(qreg[s][i]);
   }
   use_now(dq);
+  use_now(lse_corr);
   if constexpr (COPIES_FIRST) {
     wait_all();
   } else {
@@ -663,11 +667,10 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   }
   if (p.lse && half == 0 && query < sq.n) {
     // ln sum_t exp(sm_scale <q, k_t>) = ln 2 * (m + log2(l) + the row constant smoothing K dropped); l_tot = 448 l
-    const float corr = p.q_corr[((size_t)bh * p.nQb + qb) * BQ + w * WQ + n];
     // st.m_run survived the pipeline's last update: that one saw a fully masked (stale) block
     constexpr float LOG2_SCALE = PVF == PV_INT8 ? LOG2_127 : (PVF == PV_E5M2 ? LOG2_57344 : LOG2_448);
     p.lse[lse_index(p, sq, b, h, query)] =
-        LN2 * (((st.m_run - LOG2_SCALE) + __builtin_amdgcn_logf(l_tot)) + corr);
+        LN2 * (((st.m_run - LOG2_SCALE) + __builtin_amdgcn_logf(l_tot)) + lse_corr);
   }
   // One correctly rounded reciprocal per row instead of a division per element (64 of them were 4 % of
   // a tile of 64 blocks): O * fl32(1/l) is within one unit of the last FP32 place of fl32(O / l), far
