@@ -170,7 +170,15 @@ __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     float x;
-    if constexpr (INT4) x = __fmaf_rn(__int_as_float(raw[KT][4 * G + r]), fac.at(KT, G, r), dsr[KT][G][r]);
+    if constexpr (INT4) {
+      // the three-address form by hand: left to choose, the compiler takes the two-address form (result in
+      // the register of Delta-S) for a few of these and then moves the results into place
+#if defined(__HIP_DEVICE_COMPILE__)
+      asm("v_fma_f32 %0, %1, %2, %3" : "=v"(x) : "v"(__int_as_float(raw[KT][4 * G + r])), "v"(fac.at(KT, G, r)), "v"(dsr[KT][G][r]));
+#else
+      x = 0.0f;
+#endif
+    }
     else if constexpr (!fused_factor<INT4, GM>()) x = __fmul_rn((float)raw[KT][4 * G + r], fac.at(KT, G, r));
     else x = (float)raw[KT][4 * G + r];
     if constexpr (MASKED) {
