@@ -39,5 +39,25 @@ def build_library(verbose=True, extra_flags=(), out=LIB):
     return out
 
 
+ABI_SMOKE_SRC = os.path.join(ROOT, "tests", "abi_c", "abi_smoke.c")
+ABI_SMOKE_BIN = os.path.join(ROOT, "tests", "abi_c", "abi_smoke")
+
+
+def build_abi_smoke(verbose=True):
+    """Compiles tests/abi_c/abi_smoke.c, a plain-C caller of the library (host compiler, no HIP device code)."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O2", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+           "-I", os.path.join(ROOT, "include"), "-o", ABI_SMOKE_BIN, ABI_SMOKE_SRC,
+           "-L", PKG, "-l:libsageattn.so", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN/../../paper_2411_10958_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("gcc failed:\n" + res.stdout)
+    return ABI_SMOKE_BIN
+
+
 if __name__ == "__main__":
     build_library(extra_flags=sys.argv[1:])
+    build_abi_smoke()
