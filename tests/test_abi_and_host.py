@@ -113,3 +113,13 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/sage_attn.h is a C header: a C11 compiler takes it with no HIP or C++ in sight."""
+    import subprocess
+    src = tmp_path / "t.c"
+    src.write_text('#include "sage_attn.h"\nint main(void) { sage_attn_args a; (void)a; return sizeof(sage_quant_out) > 0 ? 0 : 1; }\n')
+    res = subprocess.run(["gcc", "-std=c11", "-Wall", "-Werror", "-pedantic", "-fsyntax-only", "-I", os.path.join(ROOT, "include"),
+                          str(src)], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout
