@@ -68,6 +68,9 @@ def main():
     ap.add_argument("--no-smooth-k", action="store_true", help="smoothing ablation: K is quantized as it is")
     ap.add_argument("--no-smooth-q", action="store_true",
                     help="smoothing ablation: Q is quantized as it is (4-bit mode; the 8-bit mode never smooths Q)")
+    ap.add_argument("--fp32-delta-s", action="store_true",
+                    help="Delta-S accumulated in FP32 instead of FP64 (SAGE_FLAG_FP32_DELTA_S): faster preprocessing, "
+                         "Delta-S approximate instead of correctly rounded")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -92,7 +95,7 @@ def main():
     out = torch.empty_like(q)
     a = pa.make_args(q, k, v, out, causal=spec.causal, mode=args.mode, smooth_v=args.smooth_v,
                      group_map=args.group_map, pv_format=args.pv_format, smooth_k=not args.no_smooth_k,
-                     smooth_q=not args.no_smooth_q)
+                     smooth_q=not args.no_smooth_q, fp32_delta_s=args.fp32_delta_s)
     ws = torch.empty(pa.sage_attn_workspace_bytes(a), dtype=torch.uint8, device=dev)
     a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel()
 
@@ -162,6 +165,7 @@ def main():
         "config": {"workload": f"{spec.name}: B={spec.B} H={spec.H} H_kv={spec.H_kv} N={spec.N} d={spec.d} "
                                f"{spec.dtype} causal={spec.causal}", "mode": args.mode, "smooth_v": bool(args.smooth_v),
                    "smooth_k": not args.no_smooth_k, "smooth_q": not args.no_smooth_q and args.mode == "int4_fp8",
+                   "fp32_delta_s": bool(args.fp32_delta_s),
                    "group_map": args.group_map, "pv_format": args.pv_format,
                    "ops_formula": "4*B*H*N^2*d" + ("/2" if spec.causal else "")},
         "breakdown_ms": {"prologue": round(ms_pro, 4), "attention_kernel": round(ms_core, 4)},

@@ -65,8 +65,14 @@ enum { SAGE_DT_FP16 = 0, SAGE_DT_BF16 = 1 };
    for the rows "none" and "only K" of the paper's smoothing ablation: the corresponding mean is taken
    as zero (k_mean, q_mean and, without Q smoothing, delta_s hold zeros; no Delta-S product is computed).
    They change accuracy only, not the kernels.  The 8-bit mode never smooths Q, so NO_SMOOTH_Q changes
-   nothing there. */
-enum { SAGE_FLAG_SMOOTH_V = 1, SAGE_FLAG_NO_SMOOTH_K = 2, SAGE_FLAG_NO_SMOOTH_Q = 4 };
+   nothing there.
+   SAGE_FLAG_FP32_DELTA_S: Delta-S (Sec. 3.1) accumulated in FP32 on the matrix unit instead of FP64.  The
+   preprocessing gets faster (the FP64 product is a quarter of it at N = 4096 and most of it at long
+   sequences); Delta-S is then within (d + 2) 2^-24 kappa sum_c |q_bar_c gamma(K)_c| of the exact value
+   instead of correctly rounded.  That is far below the quantization noise of the method, but it moves
+   the last bits of the scores, so once in about 10^5 scores the FP8 code of P~ comes out one step away
+   from what the exact Delta-S gives.  Off by default; ignored by the 8-bit mode. */
+enum { SAGE_FLAG_SMOOTH_V = 1, SAGE_FLAG_NO_SMOOTH_K = 2, SAGE_FLAG_NO_SMOOTH_Q = 4, SAGE_FLAG_FP32_DELTA_S = 8 };
 /* Quantization granularity of Q and K (Sec. 3.2; the ablation of the paper's granularity table).
    SAGE_GROUPS_LANE: the default, the gfx950 counterpart of per-thread quantization (SAGE_Q_GROUP /
    SAGE_K_GROUP below).  SAGE_GROUPS_BLOCK: one scale per 128-query block and per 64-key block

@@ -20,7 +20,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if (a->d != 64 && a->d != 128) return SAGE_ERR_UNSUPPORTED;
   if (a->mode != SAGE_MODE_INT4_FP8 && a->mode != SAGE_MODE_INT8_FP8) return SAGE_ERR_UNSUPPORTED;
   if (a->dtype != SAGE_DT_FP16 && a->dtype != SAGE_DT_BF16) return SAGE_ERR_UNSUPPORTED;
-  if ((a->flags & ~(SAGE_FLAG_SMOOTH_V | SAGE_FLAG_NO_SMOOTH_K | SAGE_FLAG_NO_SMOOTH_Q)) != 0) return SAGE_ERR_UNSUPPORTED;
+  if ((a->flags & ~(SAGE_FLAG_SMOOTH_V | SAGE_FLAG_NO_SMOOTH_K | SAGE_FLAG_NO_SMOOTH_Q | SAGE_FLAG_FP32_DELTA_S)) != 0) return SAGE_ERR_UNSUPPORTED;
   if (a->group_map < SAGE_GROUPS_LANE || a->group_map > SAGE_GROUPS_TENSOR) return SAGE_ERR_UNSUPPORTED;
   if (a->layout != SAGE_LAYOUT_HND && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
   if (a->pv_format < SAGE_PV_E4M3 || a->pv_format > SAGE_PV_INT8) return SAGE_ERR_UNSUPPORTED;
@@ -45,6 +45,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   D->smooth_v = (a->flags & SAGE_FLAG_SMOOTH_V) != 0;
   D->smooth_k = (a->flags & SAGE_FLAG_NO_SMOOTH_K) == 0;
   D->smooth_q = (a->flags & SAGE_FLAG_NO_SMOOTH_Q) == 0;
+  D->ds32 = (a->flags & SAGE_FLAG_FP32_DELTA_S) != 0;
   D->tensor_groups = a->group_map == SAGE_GROUPS_TENSOR;
   D->block_groups = a->group_map == SAGE_GROUPS_BLOCK || D->tensor_groups;
   D->qg = (a->group_map == SAGE_GROUPS_FINE || a->group_map == SAGE_GROUPS_TOKEN) ? 1 : QGROUP;

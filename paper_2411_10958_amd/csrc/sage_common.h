@@ -90,6 +90,7 @@ struct Dims {
   int nKb;     // ceil(Nk / 64) key blocks
   int causal, int4, bf16, smooth_v, block_groups, nhd;
   int smooth_k, smooth_q;   // 0: that mean is taken as zero (the paper's smoothing ablation)
+  int ds32;                 // Delta-S accumulated in FP32 instead of FP64 (faster, approximate)
   int qg, kg;  // queries / keys per stored scale: 2 / 16 (lane and block maps), 1 / 4 (fine), 1 / 1 (token)
   float kappa; // fl32(sm_scale * log2 e)
   SeqMap seq;  // variable-length batch: N, Nk, nQb, nKb then describe the longest sequence

@@ -541,7 +541,7 @@ typedef double v4d __attribute__((ext_vector_type(4)));
 
 constexpr int DS_QROWS = 32;    // query-block means staged in LDS per pass: two 16-row MFMA tiles
 
-template <bool BF16, bool INT4, int D>
+template <bool BF16, bool INT4, int D, bool DS32 = false>
 __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __restrict__ K,
                                                  const float* __restrict__ k_mean,
                                                  float* __restrict__ k_scale, int8_t* __restrict__ k_codes,
@@ -692,24 +692,47 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
       store_q();
       __syncthreads();
       if (next_pass(p) < npass) load_q(next_pass(p));   // next pass, in flight under the MFMAs
-      v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
-      if (!zero_ds) {      // (Q not smoothed: the block means are zero and so is Delta-S)
-#pragma unroll
-        for (int cs = 0; cs < CPL; ++cs) {
-          asm volatile("" : "+v"(x[cs]));            // keeps the widening inside the pass loop
-          const double bk = (double)x[cs];
-          acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[r16][qcol + cs], bk, acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[16 + r16][qcol + cs], bk, acc1, 0, 0, 0);
-        }
-      }
       const size_t bh = bhkv * G + p / npass_h;
       const int i0 = (p % npass_h) * DS_QROWS;
+      if constexpr (DS32) {
+        // Faster, approximate form (an option of the boundary): the same product on the FP32 form of the
+        // instruction (result element v of lane l is row 4*(l/16) + v, column l%16).  FP32 accumulation:
+        // within (d + 2) 2^-24 kappa sum_c |q_bar_c gamma(K)_c| of the exact value, about half a unit of 2^-24 of
+        // that magnitude on average.  It runs at twice the rate and under the vector work of the workgroups
+        // that share the CU, so the product costs next to nothing on top of the quantization.
+        v4f acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (!zero_ds) {
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int i = i0 + 4 * v + k4;
-        float* out = delta_s + (bh * nQb + i) * (size_t)nKb * BKV + n0 + r;
-        if (i < nQs) out[0] = (float)(kap * acc0[v]);
-        if (i + 16 < nQs) out[(size_t)16 * nKb * BKV] = (float)(kap * acc1[v]);
+          for (int cs = 0; cs < CPL; ++cs) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(s_q[r16][qcol + cs], x[cs], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(s_q[16 + r16][qcol + cs], x[cs], acc1, 0, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int i = i0 + 4 * k4 + v;
+          float* out = delta_s + (bh * nQb + i) * (size_t)nKb * BKV + n0 + r;
+          if (i < nQs) out[0] = __fmul_rn(kappa, acc0[v]);
+          if (i + 16 < nQs) out[(size_t)16 * nKb * BKV] = __fmul_rn(kappa, acc1[v]);
+        }
+      } else {
+        v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+        if (!zero_ds) {      // (Q not smoothed: the block means are zero and so is Delta-S)
+#pragma unroll
+          for (int cs = 0; cs < CPL; ++cs) {
+            asm volatile("" : "+v"(x[cs]));            // keeps the widening inside the pass loop
+            const double bk = (double)x[cs];
+            acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[r16][qcol + cs], bk, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[16 + r16][qcol + cs], bk, acc1, 0, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int i = i0 + 4 * v + k4;
+          float* out = delta_s + (bh * nQb + i) * (size_t)nKb * BKV + n0 + r;
+          if (i < nQs) out[0] = (float)(kap * acc0[v]);
+          if (i + 16 < nQs) out[(size_t)16 * nKb * BKV] = (float)(kap * acc1[v]);
+        }
       }
     }
   }
@@ -886,10 +909,16 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
     }
   };
   auto quant_k_pass = [&](const float* head_scale, int stats_only) {
-    k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
-                                                                P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
-                                                                Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.kg,
-                                                                Dm.causal, km, sm, head_scale, stats_only, !Dm.smooth_q);
+    if (INT4 && Dm.ds32)     // (the last template argument is written INT4 so that the 8-bit build has no FP32 Delta-S copy)
+      k_quant_k<BF16, INT4, D, INT4><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
+                                                                      P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
+                                                                      Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.kg,
+                                                                      Dm.causal, km, sm, head_scale, stats_only, !Dm.smooth_q);
+    else
+      k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
+                                                                  P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
+                                                                  Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.kg,
+                                                                  Dm.causal, km, sm, head_scale, stats_only, !Dm.smooth_q);
   };
   if (!Dm.want_lse) quant_q();
   const int nchunk = (int)gstat.x;

@@ -225,6 +225,62 @@ def test_smoothing_switched_off_matches_oracle(N, d, dtype, H, Hkv, causal, smoo
     check_output(wl.from_torch(out), ref, dtype)
 
 
+# ---- Delta-S accumulated in FP32 (an option of the boundary: faster preprocessing, approximate Delta-S) ----
+def _delta_s_within_fp32_bound(got, pro, K, seen=None):
+    """The kernel's FP32-accumulated Delta-S against the oracle's (float64 inner product, one rounding): the
+    textbook bound of an FP32 dot product of d terms, |error| <= (d + 2) 2^-24 kappa sum_c |q_bar_c| |gamma(K)_c|
+    (+ the oracle's own final rounding), and - independent roundings largely cancel - a mean error below two
+    units of 2^-24 of that magnitude, which a lost operand bit (16-bit operands, say) would exceed."""
+    D = pro["delta_s"].astype(np.float64)
+    gK = (np.asarray(K, np.float32) - pro["kbar"][None, :]).astype(np.float32)
+    mag = float(pro["kappa"]) * (np.abs(pro["qbar"]).astype(np.float64) @ np.abs(gK).astype(np.float64).T)
+    diff = np.abs(np.asarray(got, np.float64) - D)
+    if seen is not None:
+        diff = np.where(seen, diff, 0.0)
+    u, d = 2.0 ** -24, gK.shape[1]
+    assert np.all(diff <= (d + 2) * u * mag + np.spacing(np.abs(D))), "delta S beyond the FP32 dot-product bound"
+    assert diff.mean() <= 2 * u * max(mag.mean(), 1e-30), "delta S: mean error too large for FP32 operands"
+
+
+@pytest.mark.parametrize("N,d,dtype,H,Hkv,causal", [(640, 128, "bf16", 4, 2, False), (300, 64, "fp16", 2, 2, True)])
+def test_fp32_delta_s_option(N, d, dtype, H, Hkv, causal):
+    pa = _pa()
+    spec = _spec(N, d, dtype, H, Hkv, causal=causal, outliers=2)
+    data, (q, k, v) = _gpu_inputs(spec)
+    print(f"FP32 Delta-S N={N} d={d} {dtype} H={H}/{Hkv} causal={causal}", flush=True)
+    got, args, ws = pa.sage_attn_quant(q, k, v, causal=causal, fp32_delta_s=True)
+    torch.cuda.synchronize()
+    got = {n: t.cpu().numpy() for n, t in got.items()}
+    g = H // Hkv
+    for b in range(spec.B):
+        for h in range(H):
+            pro = so.quantize_head(data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g])
+            # everything else of the preprocessing is untouched by the option
+            assert np.array_equal(got["q_codes"][b, h], pro["q_codes"]) and np.array_equal(got["k_codes"][b, h // g], pro["k_codes"])
+            assert np.array_equal(got["q_mean"][b, h], pro["qbar"]) and np.array_equal(got["k_scale"][b, h // g], pro["k_scale"])
+            _delta_s_within_fp32_bound(got["delta_s"][b, h], pro, data["k"][b, h // g])
+    out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, fp32_delta_s=True)
+    exact = pa.sage_attn_fwd_ex(q, k, v, causal=causal)
+    torch.cuda.synchronize()
+    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, out_dtype="fp32")
+    # Same bar as the default path, except that more rows may carry a P~ code one FP8 step away from the oracle's
+    # (the scores differ in their last bits): up to one row in 200 instead of one in 1000, each still within one
+    # FP8 step of the largest output magnitude.
+    got16 = wl.from_torch(out).astype(np.float64).reshape(-1, d)
+    r = ref.astype(np.float64).reshape(-1, d)
+    linf = np.abs(r).max(axis=1, keepdims=True)
+    excess = np.abs(got16 - r) - (OUT_TOL * linf + _half_ulp16(r, dtype))
+    bad = np.nonzero(excess.max(axis=1) > 0)[0]
+    print(f"  rows beyond the bar {len(bad)} of {len(r)}; cos {wl.cos_sim(got16, r):.7f}", flush=True)
+    assert np.isfinite(got16).all() and wl.cos_sim(got16, r) >= COS_TOL
+    assert len(bad) <= max(1, len(r) // 200)
+    if len(bad):
+        assert np.abs(got16 - r)[bad].max() <= 0.125 * np.abs(r).max() + _half_ulp16(r, dtype).max()
+    # and against the default path the outputs agree to the same bar
+    d2 = np.abs(got16 - wl.from_torch(exact).astype(np.float64).reshape(-1, d))
+    assert (d2.max(axis=1) > 2 * OUT_TOL * linf[:, 0] + 2 * _half_ulp16(r, dtype).max(axis=1)).mean() <= 0.005
+
+
 # ---- per-block and per-tensor granularity (Sec. 2.2 / 2.3 / 3.2: the coarser groupings the paper compares with) ----
 @pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
 @pytest.mark.parametrize("group_map,gmap", [("block", "per_block"), ("tensor", "per_tensor")])
