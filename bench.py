@@ -85,6 +85,10 @@ def main():
     ap.add_argument("--fp32-delta-s", action="store_true",
                     help="Delta-S accumulated in FP32 instead of FP64 (SAGE_FLAG_FP32_DELTA_S): faster preprocessing, "
                          "Delta-S approximate instead of correctly rounded")
+    ap.add_argument("--given-kv-stats", action="store_true",
+                    help="mean(K) and delta_V are computed once, outside the timed region, and supplied to every step "
+                         "(k_mean_in / v_scale_in: what a producer of K and V would hand over); the statistics pass is "
+                         "then not part of the step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -107,7 +111,8 @@ def main():
     data = wl.make_inputs(spec, seed=0)
     q, k, v = (wl.to_torch(data[n], spec.dtype, dev) for n in "qkv")
     out = torch.empty_like(q)
-    a = pa.make_args(q, k, v, out, causal=spec.causal, mode=args.mode, smooth_v=args.smooth_v,
+    kv_stats = pa.sage_attn_kv_stats(k, v, pv_format=args.pv_format) if args.given_kv_stats else None
+    a = pa.make_args(q, k, v, out, causal=spec.causal, mode=args.mode, smooth_v=args.smooth_v, kv_stats=kv_stats,
                      group_map=args.group_map, pv_format=args.pv_format, smooth_k=not args.no_smooth_k,
                      smooth_q=not args.no_smooth_q, fp32_delta_s=args.fp32_delta_s)
     ws = torch.empty(pa.sage_attn_workspace_bytes(a), dtype=torch.uint8, device=dev)
@@ -179,7 +184,7 @@ def main():
         "config": {"workload": f"{spec.name}: B={spec.B} H={spec.H} H_kv={spec.H_kv} N={spec.N} d={spec.d} "
                                f"{spec.dtype} causal={spec.causal}", "mode": args.mode, "smooth_v": bool(args.smooth_v),
                    "smooth_k": not args.no_smooth_k, "smooth_q": not args.no_smooth_q and args.mode == "int4_fp8",
-                   "fp32_delta_s": bool(args.fp32_delta_s),
+                   "fp32_delta_s": bool(args.fp32_delta_s), "given_kv_stats": bool(args.given_kv_stats),
                    "group_map": args.group_map, "pv_format": args.pv_format,
                    "ops_formula": "4*B*H*N^2*d" + ("/2" if spec.causal else "")},
         "breakdown_ms": {"prologue": round(ms_pro, 4), "attention_kernel": round(ms_core, 4)},

@@ -133,6 +133,14 @@ typedef struct sage_attn_args {
                              to merge results computed over disjoint key sets: out = sum_i exp(lse_i - lse) out_i,
                              lse = ln sum_i exp(lse_i).  -inf for a sequence without keys. */
   int pv_format;          /* SAGE_PV_*; 0 = E4M3 */
+  const float* k_mean_in;  /* device, [B, H_kv, d] f32, or NULL.  With k_mean_in and v_scale_in the statistics pass over K
+                              and V is skipped (K and V are then read once by the preprocessing instead of twice): the
+                              producer of K and V - a projection or rotary-embedding kernel, or the keeper of a KV cache -
+                              supplies them.  k_mean_in[c] = fl32(sum over the N_kv tokens of K[., c] / N_kv), the sum
+                              exact (Eq. 2); 16-byte aligned.  Both or neither; not with SAGE_FLAG_SMOOTH_V or
+                              SAGE_FLAG_NO_SMOOTH_K.  sage_attn_kv_stats computes exactly these two arrays. */
+  const float* v_scale_in; /* device, [B, H_kv, d] f32, or NULL: fl32(max over tokens |V[., c]| / 448) (Sec. 3.3; / 57344 for
+                              SAGE_PV_E5M2, / 127 for SAGE_PV_INT8) */
 } sage_attn_args;
 
 /* Bytes of device scratch one call needs for these shapes (codes, scales, means, Delta-S).
@@ -187,6 +195,11 @@ typedef struct sage_quant_out {
   float* delta_s;
   float* v_mean;
 } sage_quant_out;
+
+/* The statistics pass of the preprocessing alone (Algorithm 1, "Preprocessing": mean(K) and the scale of
+   psi_V): writes k_mean_out and v_scale_out, device [B, H_kv, d] f32 each, in the form k_mean_in / v_scale_in
+   take.  Reads k and v only (q and out may be NULL); needs the workspace of sage_attn_workspace_bytes(args). */
+int sage_attn_kv_stats(const sage_attn_args* args, float* k_mean_out, float* v_scale_out);
 
 /* Runs the preprocessing of Algorithm 1 (as sage_attn_prologue) and then copies its results
    out of the kernel-private packed workspace layout into `out`. */

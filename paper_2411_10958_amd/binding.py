@@ -44,7 +44,8 @@ class sage_attn_args(ctypes.Structure):
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("stream", ctypes.c_void_p),
                 ("cu_seqlens_q", ctypes.c_void_p), ("cu_seqlens_k", ctypes.c_void_p), ("lse", ctypes.c_void_p),
-                ("pv_format", ctypes.c_int)]
+                ("pv_format", ctypes.c_int),
+                ("k_mean_in", ctypes.c_void_p), ("v_scale_in", ctypes.c_void_p)]
 
 
 class sage_quant_out(ctypes.Structure):
@@ -75,6 +76,8 @@ def load_library():
         lib.sage_attn_fwd.restype = ctypes.c_int
         lib.sage_attn_fwd.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 5 + [ctypes.c_float, ctypes.c_int]
         lib.sage_attn_release.restype = None
+        lib.sage_attn_kv_stats.restype = ctypes.c_int
+        lib.sage_attn_kv_stats.argtypes = [P(sage_attn_args), ctypes.c_void_p, ctypes.c_void_p]
         lib.sage_attn_quant.restype = ctypes.c_int
         lib.sage_attn_quant.argtypes = [P(sage_attn_args), P(sage_quant_out)]
         lib.sage_attn_debug_qk.restype = ctypes.c_int
@@ -110,7 +113,7 @@ def _ptr(t):
 
 def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
               smooth_v=False, group_map="lane", layout="HND", pv_format="e4m3", smooth_k=True, smooth_q=True,
-              fp32_delta_s=False):
+              fp32_delta_s=False, kv_stats=None):
     """Fills a sage_attn_args from torch tensors q [B,H,N,d], k/v [B,H_kv,N_kv,d] (layout "HND") or
     q [B,N,H,d], k/v [B,N_kv,H_kv,d] (layout "NHD"), contiguous, on the GPU.  `workspace` is a uint8 GPU tensor (or None); `stream` a torch.cuda.Stream (None = the
     current one)."""
@@ -136,6 +139,14 @@ def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", wo
     a.N_kv = Nk
     a.layout = _LAYOUTS[layout]
     a.pv_format = _PV_FORMATS[pv_format]
+    if kv_stats is not None:       # (k_mean, v_scale) float32 GPU tensors [B, H_kv, d], e.g. from sage_attn_kv_stats
+        km, vs = kv_stats
+        for name, t in (("k_mean", km), ("v_scale", vs)):
+            # (the first extent is the batch size, or the number of sequences of a packed batch)
+            if not t.is_cuda or t.dtype != torch.float32 or not t.is_contiguous() or t.dim() != 3 or \
+                    tuple(t.shape[1:]) != (Hkv, d):
+                raise ValueError(f"kv_stats: {name} must be a contiguous float32 GPU tensor of shape [B, H_kv, d]")
+        a.k_mean_in, a.v_scale_in = km.data_ptr(), vs.data_ptr()
     if workspace is not None:
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     else:
@@ -161,7 +172,7 @@ def _alloc_workspace(args, device):
 def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
                      smooth_v=False, group_map="lane", layout="HND", cu_seqlens_q=None, cu_seqlens_k=None,
                      max_seqlen_q=None, max_seqlen_k=None, return_lse=False, pv_format="e4m3", smooth_k=True,
-                     smooth_q=True, fp32_delta_s=False):
+                     smooth_q=True, fp32_delta_s=False, kv_stats=None):
     """Whole forward pass.  Returns `out` (allocated if not given).  With cu_seqlens_q the batch is a packed
     variable-length one (see make_varlen_args) and `layout` is ignored.  With return_lse the result is
     (out, lse): lse float32 [B, H, N], or [H, total_q] for a variable-length batch."""
@@ -171,10 +182,10 @@ def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_f
         a = make_varlen_args(q, k, v, out, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, max_seqlen_k, causal=causal,
                              sm_scale=sm_scale, mode=mode, workspace=workspace, stream=stream, smooth_v=smooth_v,
                              group_map=group_map, pv_format=pv_format, smooth_k=smooth_k, smooth_q=smooth_q,
-                             fp32_delta_s=fp32_delta_s)
+                             fp32_delta_s=fp32_delta_s, kv_stats=kv_stats)
     else:
         a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v, group_map, layout, pv_format,
-                      smooth_k, smooth_q, fp32_delta_s)
+                      smooth_k, smooth_q, fp32_delta_s, kv_stats)
     lse = None
     if return_lse:
         shape = (a.H, q.shape[0]) if cu_seqlens_q is not None else (a.B, a.H, a.N)
@@ -233,16 +244,37 @@ def sage_attn_fwd(q, k, v, out, causal=False, sm_scale=0.0, mode="int4_fp8"):
     return out
 
 
+def sage_attn_kv_stats(k, v, layout="HND", pv_format="e4m3", cu_seqlens_k=None, max_seqlen_k=None, workspace=None,
+                       stream=None):
+    """mean(K) and delta_V alone (the statistics pass of the preprocessing): returns (k_mean, v_scale), float32
+    [B, H_kv, d] each, in the form the `kv_stats` argument of the other calls takes.  With cu_seqlens_k, k and v are
+    packed [total_k, H_kv, d] tensors and B is the number of sequences."""
+    if cu_seqlens_k is not None:
+        a = make_varlen_args(k, k, v, None, cu_seqlens_k, cu_seqlens_k, max_seqlen_k, max_seqlen_k, workspace=workspace,
+                             stream=stream, pv_format=pv_format)
+    else:
+        a = make_args(k, k, v, None, workspace=workspace, stream=stream, layout=layout, pv_format=pv_format)
+    keep = _alloc_workspace(a, k.device) if workspace is None else workspace
+    km = torch.empty((a.B, a.H_kv, a.d), dtype=torch.float32, device=k.device)
+    vs = torch.empty_like(km)
+    st = load_library().sage_attn_kv_stats(ctypes.byref(a), ctypes.c_void_p(km.data_ptr()), ctypes.c_void_p(vs.data_ptr()))
+    if st != 0:
+        raise SageError(st, "sage_attn_kv_stats")
+    del keep
+    return km, vs
+
+
 def sage_attn_release():
     load_library().sage_attn_release()
 
 
 def sage_attn_quant(q, k, v, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, want=None,
                     smooth_v=False, group_map="lane", pv_format="e4m3", smooth_k=True, smooth_q=True,
-                    fp32_delta_s=False):
+                    fp32_delta_s=False, kv_stats=None):
     """Preprocessing only; returns (dict of torch tensors in plain layouts, args, workspace)."""
     a = make_args(q, k, v, None, causal, sm_scale, mode, workspace, smooth_v=smooth_v, group_map=group_map,
-                  pv_format=pv_format, smooth_k=smooth_k, smooth_q=smooth_q, fp32_delta_s=fp32_delta_s)
+                  pv_format=pv_format, smooth_k=smooth_k, smooth_q=smooth_q, fp32_delta_s=fp32_delta_s,
+                  kv_stats=kv_stats)
     ws = _alloc_workspace(a, q.device) if workspace is None else workspace
     B, H, N, d = q.shape
     Hkv, Nk = k.shape[1], k.shape[2]

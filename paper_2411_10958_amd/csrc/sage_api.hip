@@ -29,6 +29,11 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if (a->cu_seqlens_k && !a->cu_seqlens_q) return SAGE_ERR_INVALID_ARG;
   if (a->cu_seqlens_q && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
   if (need_io && (!a->q || !a->k || !a->v || !a->out)) return SAGE_ERR_INVALID_ARG;
+  // statistics supplied by the producer of K and V: both arrays or neither, and only where mean(K) and
+  // delta_V are all the statistics pass would have produced
+  if ((a->k_mean_in != nullptr) != (a->v_scale_in != nullptr)) return SAGE_ERR_INVALID_ARG;
+  if (a->k_mean_in && (a->flags & (SAGE_FLAG_SMOOTH_V | SAGE_FLAG_NO_SMOOTH_K)) != 0) return SAGE_ERR_UNSUPPORTED;
+  if ((((uintptr_t)a->k_mean_in | (uintptr_t)a->v_scale_in) & 15u) != 0) return SAGE_ERR_INVALID_ARG;
   // the kernels move rows with 16-byte accesses (rows are multiples of 128 bytes, so the base decides)
   if ((((uintptr_t)a->q | (uintptr_t)a->k | (uintptr_t)a->v | (uintptr_t)a->out) & 15u) != 0) return SAGE_ERR_INVALID_ARG;
   if ((((uintptr_t)a->lse | (uintptr_t)a->cu_seqlens_q | (uintptr_t)a->cu_seqlens_k) & 3u) != 0) return SAGE_ERR_INVALID_ARG;
@@ -46,6 +51,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   D->smooth_k = (a->flags & SAGE_FLAG_NO_SMOOTH_K) == 0;
   D->smooth_q = (a->flags & SAGE_FLAG_NO_SMOOTH_Q) == 0;
   D->ds32 = (a->flags & SAGE_FLAG_FP32_DELTA_S) != 0;
+  D->stats_given = a->k_mean_in != nullptr;
   D->tensor_groups = a->group_map == SAGE_GROUPS_TENSOR;
   D->block_groups = a->group_map == SAGE_GROUPS_BLOCK || D->tensor_groups;
   D->qg = (a->group_map == SAGE_GROUPS_FINE || a->group_map == SAGE_GROUPS_TOKEN) ? 1 : QGROUP;
@@ -63,6 +69,17 @@ int check_workspace(const sage_attn_args* a, const Workspace& w) {
   if (!a->workspace || a->workspace_bytes < w.total) return SAGE_ERR_WORKSPACE;
   if (((uintptr_t)a->workspace & 255u) != 0) return SAGE_ERR_WORKSPACE;
   return SAGE_OK;
+}
+
+// Workspace pointers for `a`; mean(K) and delta_V point at the caller's arrays when it supplies them (the kernels
+// only read them then).
+Ptrs ptrs_for(const sage_attn_args* a, const Workspace& w) {
+  Ptrs P = make_ptrs(a->q, a->k, a->v, a->out, a->workspace, w);
+  if (a->k_mean_in) {
+    P.k_mean = const_cast<float*>(a->k_mean_in);
+    P.v_scale = const_cast<float*>(a->v_scale_in);
+  }
+  return P;
 }
 
 int hip_status(hipError_t e) {
@@ -104,7 +121,7 @@ int sage_attn_prologue(const sage_attn_args* args) {
   if (st != SAGE_OK) return st;
   const Workspace w = make_workspace(D);
   if ((st = check_workspace(args, w)) != SAGE_OK) return st;
-  const Ptrs P = make_ptrs(args->q, args->k, args->v, args->out, args->workspace, w);
+  const Ptrs P = ptrs_for(args, w);
   return hip_status(launch_prologue(D, P, (hipStream_t)args->stream));
 }
 
@@ -114,7 +131,7 @@ int sage_attn_core(const sage_attn_args* args) {
   if (st != SAGE_OK) return st;
   const Workspace w = make_workspace(D);
   if ((st = check_workspace(args, w)) != SAGE_OK) return st;
-  Ptrs P = make_ptrs(args->q, args->k, args->v, args->out, args->workspace, w);
+  Ptrs P = ptrs_for(args, w);
   P.lse = args->lse;
   return hip_status(launch_attention(D, P, (hipStream_t)args->stream));
 }
@@ -132,6 +149,7 @@ int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B,
   a.B = B; a.H = H; a.H_kv = H; a.N = N; a.d = d;
   a.causal = causal; a.sm_scale = sm_scale; a.mode = mode; a.dtype = SAGE_DT_BF16; a.flags = 0; a.group_map = SAGE_GROUPS_LANE; a.N_kv = 0; a.layout = SAGE_LAYOUT_HND;
   a.cu_seqlens_q = nullptr; a.cu_seqlens_k = nullptr; a.lse = nullptr; a.pv_format = SAGE_PV_E4M3;
+  a.k_mean_in = nullptr; a.v_scale_in = nullptr;
   a.workspace = nullptr; a.workspace_bytes = 0; a.stream = nullptr;
   const size_t need = sage_attn_workspace_bytes(&a);
   if (need == 0) {
@@ -152,6 +170,22 @@ int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B,
 
 void sage_attn_release(void) { (void)release_ws(); }
 
+int sage_attn_kv_stats(const sage_attn_args* args, float* k_mean_out, float* v_scale_out) {
+  if (!k_mean_out || !v_scale_out) return SAGE_ERR_INVALID_ARG;
+  if ((((uintptr_t)k_mean_out | (uintptr_t)v_scale_out) & 15u) != 0) return SAGE_ERR_INVALID_ARG;
+  Dims D;
+  int st = validate(args, &D, false);
+  if (st != SAGE_OK) return st;
+  if (!args->k || !args->v) return SAGE_ERR_INVALID_ARG;
+  if (args->k_mean_in || (args->flags & (SAGE_FLAG_SMOOTH_V | SAGE_FLAG_NO_SMOOTH_K)) != 0) return SAGE_ERR_UNSUPPORTED;
+  const Workspace w = make_workspace(D);
+  if ((st = check_workspace(args, w)) != SAGE_OK) return st;
+  Ptrs P = make_ptrs(args->q, args->k, args->v, args->out, args->workspace, w);
+  P.k_mean = k_mean_out;
+  P.v_scale = v_scale_out;
+  return hip_status(launch_kv_stats(D, P, (hipStream_t)args->stream));
+}
+
 int sage_attn_quant(const sage_attn_args* args, const sage_quant_out* out) {
   if (!out) return SAGE_ERR_INVALID_ARG;
   Dims D;
@@ -162,7 +196,7 @@ int sage_attn_quant(const sage_attn_args* args, const sage_quant_out* out) {
   if ((long long)D.B * D.H * D.nQb > 65535) return SAGE_ERR_UNSUPPORTED;  // grid limit of the copy-out kernels
   const Workspace w = make_workspace(D);
   if ((st = check_workspace(args, w)) != SAGE_OK) return st;
-  const Ptrs P = make_ptrs(args->q, args->k, args->v, args->out, args->workspace, w);
+  const Ptrs P = ptrs_for(args, w);
   if ((st = hip_status(launch_prologue(D, P, (hipStream_t)args->stream))) != SAGE_OK) return st;
   return hip_status(launch_unpack(D, P, out, (hipStream_t)args->stream));
 }
@@ -178,7 +212,7 @@ int sage_attn_debug_qk(const sage_attn_args* args, int b, int h, int q_tile, int
     return SAGE_ERR_INVALID_ARG;
   const Workspace w = make_workspace(D);
   if ((st = check_workspace(args, w)) != SAGE_OK) return st;
-  const Ptrs P = make_ptrs(args->q, args->k, args->v, args->out, args->workspace, w);
+  const Ptrs P = ptrs_for(args, w);
   return hip_status(launch_debug_qk(D, P, b, h, q_tile, kv_block, out_acc, (hipStream_t)args->stream));
 }
 

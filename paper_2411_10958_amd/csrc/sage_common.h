@@ -91,6 +91,7 @@ struct Dims {
   int causal, int4, bf16, smooth_v, block_groups, nhd;
   int smooth_k, smooth_q;   // 0: that mean is taken as zero (the paper's smoothing ablation)
   int ds32;                 // Delta-S accumulated in FP32 instead of FP64 (faster, approximate)
+  int stats_given;          // mean(K) and delta_V come from the caller: no statistics pass
   int qg, kg;  // queries / keys per stored scale: 2 / 16 (lane and block maps), 1 / 4 (fine), 1 / 1 (token)
   float kappa; // fl32(sm_scale * log2 e)
   SeqMap seq;  // variable-length batch: N, Nk, nQb, nKb then describe the longest sequence
@@ -282,6 +283,7 @@ template <bool BF16> __device__ inline unsigned pack16x2(float a, float b) {
 
 // launchers (defined in the .hip files)
 hipError_t launch_prologue(const Dims& D, const Ptrs& P, hipStream_t s);
+hipError_t launch_kv_stats(const Dims& D, const Ptrs& P, hipStream_t s);   // writes P.k_mean, P.v_scale
 hipError_t launch_attention(const Dims& D, const Ptrs& P, hipStream_t s);
 hipError_t launch_unpack(const Dims& D, const Ptrs& P, const void* quant_out, hipStream_t s);
 hipError_t launch_debug_mfma_fp8(const void* a, const void* b, const float* c, float* d, hipStream_t s);

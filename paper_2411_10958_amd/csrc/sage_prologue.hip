@@ -871,14 +871,37 @@ __global__ void k_unpack_rows(const float* __restrict__ src, float* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------
+// The statistics pass: mean(K) and delta_V (and mean(V) with the smooth-V option) into P.k_mean, P.v_scale, P.v_mean.
+template <bool BF16, int D>
+static void launch_stats_t(const Dims& Dm, const Ptrs& P, hipStream_t s) {
+  const int BHkv = Dm.B * Dm.Hkv;
+  const unsigned short* k = (const unsigned short*)P.k;
+  const unsigned short* v = (const unsigned short*)P.v;
+  const int nstat = BHkv * Dm.d;
+  const dim3 gstat((Dm.Nk + STAT_ROWS - 1) / STAT_ROWS, BHkv);
+  const TensorMap km = make_tensor_map(Dm.nhd, Dm.Hkv, Dm.Nk, Dm.d, Dm.seq.cu_q != nullptr);
+  const SeqMap sm = Dm.seq;
+  const int nchunk = (int)gstat.x;
+  const float code_max = Dm.pvf == PV_INT8 ? INT8_PV_MAX : (Dm.pvf == PV_E5M2 ? E5M2_MAX : E4M3_MAX);
+  if (Dm.smooth_v) {
+    k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.N, Dm.Nk, km, sm);
+    k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
+                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max, Dm.smooth_k);
+    k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.N, Dm.Nk, km, sm);
+    k_finalize_vscale<<<(nstat + 255) / 256, 256, 0, s>>>(P.v_max, P.v_scale, nstat, Dm.d, nchunk, code_max);
+  } else {
+    k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.N, Dm.Nk, km, sm);
+    k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
+                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max, Dm.smooth_k);
+  }
+}
+
 template <bool BF16, bool INT4, int D>
 static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s) {
   const int BH = Dm.B * Dm.H, BHkv = Dm.B * Dm.Hkv;
   const unsigned short* q = (const unsigned short*)P.q;
   const unsigned short* k = (const unsigned short*)P.k;
   const unsigned short* v = (const unsigned short*)P.v;
-  const int nstat = BHkv * Dm.d;
-  const dim3 gstat((Dm.Nk + STAT_ROWS - 1) / STAT_ROWS, BHkv);
   const bool varlen = Dm.seq.cu_q != nullptr;
   const TensorMap qm = make_tensor_map(Dm.nhd, Dm.H, Dm.N, Dm.d, varlen),
                   km = make_tensor_map(Dm.nhd, Dm.Hkv, Dm.Nk, Dm.d, varlen);
@@ -921,19 +944,7 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
                                                                   Dm.causal, km, sm, head_scale, stats_only, !Dm.smooth_q);
   };
   if (!Dm.want_lse) quant_q();
-  const int nchunk = (int)gstat.x;
-  const float code_max = Dm.pvf == PV_INT8 ? INT8_PV_MAX : (Dm.pvf == PV_E5M2 ? E5M2_MAX : E4M3_MAX);
-  if (Dm.smooth_v) {
-    k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.N, Dm.Nk, km, sm);
-    k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
-                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max, Dm.smooth_k);
-    k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.N, Dm.Nk, km, sm);
-    k_finalize_vscale<<<(nstat + 255) / 256, 256, 0, s>>>(P.v_max, P.v_scale, nstat, Dm.d, nchunk, code_max);
-  } else {
-    k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.N, Dm.Nk, km, sm);
-    k_finalize_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
-                                                        nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max, Dm.smooth_k);
-  }
+  if (!Dm.stats_given) launch_stats_t<BF16, D>(Dm, P, s);     // else P.k_mean and P.v_scale are the caller's arrays
   if (Dm.want_lse) quant_q();
   if (Dm.tensor_groups) {
     quant_k_pass(nullptr, 1);
@@ -968,6 +979,12 @@ hipError_t launch_prologue(const Dims& D, const Ptrs& P, hipStream_t s) {
     else        { if (D.int4) SAGE_PRO(false, true, 64); else SAGE_PRO(false, false, 64); }
   }
 #undef SAGE_PRO
+}
+
+hipError_t launch_kv_stats(const Dims& D, const Ptrs& P, hipStream_t s) {
+  if (D.d == 128) { if (D.bf16) launch_stats_t<true, 128>(D, P, s); else launch_stats_t<false, 128>(D, P, s); }
+  else            { if (D.bf16) launch_stats_t<true, 64>(D, P, s); else launch_stats_t<false, 64>(D, P, s); }
+  return hipGetLastError();
 }
 
 hipError_t launch_unpack(const Dims& D, const Ptrs& P, const void* quant_out, hipStream_t s) {

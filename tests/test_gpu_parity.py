@@ -5,6 +5,8 @@ masks and grouped KV heads.
 Bars: codes, scales, means and int32 score accumulators bit-equal; Delta-S equal up to the
 last FP32 bit of a float64-accumulated value; outputs within 2e-3 max-abs after dividing by
 the row's L-inf norm and cosine >= 0.9999 (the tolerance the benchmark spec states for this path)."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -279,6 +281,67 @@ def test_fp32_delta_s_option(N, d, dtype, H, Hkv, causal):
     # and against the default path the outputs agree to the same bar
     d2 = np.abs(got16 - wl.from_torch(exact).astype(np.float64).reshape(-1, d))
     assert (d2.max(axis=1) > 2 * OUT_TOL * linf[:, 0] + 2 * _half_ulp16(r, dtype).max(axis=1)).mean() <= 0.005
+
+
+# ---- statistics of K and V supplied by the caller (the producer of K and V, or the keeper of a KV cache) ----
+@pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("N,Nk,d,dtype,H,Hkv,causal,pv", [(300, 300, 128, "bf16", 4, 2, True, "e4m3"),
+                                                       (200, 450, 64, "fp16", 2, 2, False, "e5m2")])
+def test_supplied_kv_statistics(N, Nk, d, dtype, H, Hkv, causal, pv, mode):
+    pa = _pa()
+    spec = _spec(N, d, dtype, H, Hkv, B=2, causal=causal).with_(N_kv=Nk)
+    data, (q, k, v) = _gpu_inputs(spec)
+    print(f"supplied statistics N={N} N_kv={Nk} d={d} {dtype} H={H}/{Hkv} causal={causal} {pv} mode={mode}", flush=True)
+    km, vs = pa.sage_attn_kv_stats(k, v, pv_format=pv)
+    torch.cuda.synchronize()
+    for b in range(2):
+        for hk in range(Hkv):
+            pro = so.quantize_head(data["q"][b, hk * (H // Hkv)], data["k"][b, hk], data["v"][b, hk], mode=mode, pv_fmt=pv)
+            assert np.array_equal(km[b, hk].cpu().numpy(), pro["kbar"]), "mean(K)"
+            assert np.array_equal(vs[b, hk].cpu().numpy(), pro["v_scale"]), "delta_V"
+    plain, lse0 = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, pv_format=pv, return_lse=True)
+    out, lse1 = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, pv_format=pv, return_lse=True, kv_stats=(km, vs))
+    torch.cuda.synchronize()
+    assert torch.equal(out, plain) and torch.equal(lse0, lse1)      # the same path minus the statistics pass
+    # the arrays are read, not copied: other values give another result
+    out2 = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, pv_format=pv, kv_stats=(km + 0.25, vs))
+    torch.cuda.synchronize()
+    assert not torch.equal(out2, plain)
+    # one array without the other, or together with an option that needs more statistics
+    a = pa.make_args(q, k, v, torch.empty_like(q), causal=causal, mode=mode, pv_format=pv, kv_stats=(km, vs))
+    ws = torch.empty(pa.sage_attn_workspace_bytes(a), dtype=torch.uint8, device=q.device)
+    a.workspace, a.workspace_bytes = ws.data_ptr(), ws.numel()
+    lib = pa.load_library()
+    a.v_scale_in = 0
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -1
+    a.v_scale_in = vs.data_ptr()
+    a.flags = 1
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == -2
+    a.flags = 0
+    assert lib.sage_attn_fwd_ex(ctypes.byref(a)) == 0
+    torch.cuda.synchronize()
+
+
+def test_supplied_kv_statistics_of_a_packed_batch():
+    pa = _pa()
+    lens_q, lens_k, H, Hkv, d = [70, 200, 129], [300, 64, 129], 4, 2, 128
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(5)
+    tq, tk = sum(lens_q), sum(lens_k)
+    q = torch.tensor(rng.standard_normal((tq, H, d)), dtype=torch.bfloat16, device=dev)
+    k = torch.tensor(rng.standard_normal((tk, Hkv, d)) + 2.0, dtype=torch.bfloat16, device=dev)
+    v = torch.tensor(rng.standard_normal((tk, Hkv, d)), dtype=torch.bfloat16, device=dev)
+    cu = lambda lens: torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev)
+    cu_q, cu_k = cu(lens_q), cu(lens_k)
+    km, vs = pa.sage_attn_kv_stats(k, v, cu_seqlens_k=cu_k, max_seqlen_k=max(lens_k))
+    assert km.shape == (3, Hkv, d)
+    plain = pa.sage_attn_fwd_ex(q, k, v, cu_seqlens_q=cu_q, cu_seqlens_k=cu_k)
+    out = pa.sage_attn_fwd_ex(q, k, v, cu_seqlens_q=cu_q, cu_seqlens_k=cu_k, kv_stats=(km, vs))
+    torch.cuda.synchronize()
+    assert torch.equal(out, plain)
+    # sequence 1's mean is that of its own 64 keys
+    ref = k[300:364, 1].float().double().sum(dim=0) / 64
+    assert torch.equal(km[1, 1].cpu(), ref.float().cpu())
 
 
 # ---- per-block and per-tensor granularity (Sec. 2.2 / 2.3 / 3.2: the coarser groupings the paper compares with) ----
