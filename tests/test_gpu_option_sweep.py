@@ -33,6 +33,8 @@ def _draw(rng):
     # the smoothing switches are drawn last so that the earlier draws of a seed stay what they were
     c["smooth_k"] = bool(rng.random() >= 0.25)
     c["smooth_q"] = bool(rng.random() >= 0.25)
+    # statistics of K and V handed over by the caller (only where mean(K) and delta_V are all that pass produces)
+    c["kv_stats"] = bool(rng.random() < 0.4) and c["smooth_k"] and not c["smooth_v"]
     return c
 
 
@@ -53,9 +55,10 @@ def test_option_combination_matches_oracle(seed):
     q, k, v = (wl.to_torch(data[x], c["dtype"], dev) for x in "qkv")
     if c["layout"] == "NHD":
         q, k, v = (t.permute(0, 2, 1, 3).contiguous() for t in (q, k, v))
+    stats = pa.sage_attn_kv_stats(k, v, layout=c["layout"], pv_format=c["pv"]) if c["kv_stats"] else None
     res = pa.sage_attn_fwd_ex(q, k, v, causal=c["causal"], mode=c["mode"], smooth_v=c["smooth_v"], group_map=c["group_map"],
                               layout=c["layout"], pv_format=c["pv"], return_lse=c["lse"], smooth_k=c["smooth_k"],
-                              smooth_q=c["smooth_q"])
+                              smooth_q=c["smooth_q"], kv_stats=stats)
     torch.cuda.synchronize()
     out, lse = res if c["lse"] else (res, None)
     if c["layout"] == "NHD":
@@ -95,9 +98,11 @@ def test_packed_batch_combination_matches_oracle(seed):
     pack = lambda parts: wl.to_torch(np.ascontiguousarray(np.concatenate(parts, axis=0)), c["dtype"], dev)
     cu = lambda lens: torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev)
     q, k, v = pack(qs), pack(ks), pack(vs)
+    stats = pa.sage_attn_kv_stats(k, v, pv_format=c["pv"], cu_seqlens_k=cu(lens_k), max_seqlen_k=max(max(lens_k), 1)) \
+        if c["kv_stats"] else None
     res = pa.sage_attn_fwd_ex(q, k, v, causal=c["causal"], mode=c["mode"], smooth_v=c["smooth_v"], group_map=c["group_map"],
                               pv_format=c["pv"], return_lse=c["lse"], cu_seqlens_q=cu(lens_q), cu_seqlens_k=cu(lens_k),
-                              smooth_k=c["smooth_k"], smooth_q=c["smooth_q"])
+                              smooth_k=c["smooth_k"], smooth_q=c["smooth_q"], kv_stats=stats)
     torch.cuda.synchronize()
     out, lse = res if c["lse"] else (res, None)
     off = np.concatenate([[0], np.cumsum(lens_q)])
