@@ -290,6 +290,9 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
             D[list(ds_blocks)] = delta_s(qbar[list(ds_blocks)], gK, kappa)
     else:
         qbar, gQ, D = None, np.asarray(Q, f32), None
+    # The 4-bit variant's score line always carries the Delta-S addend (zeros when Q is left unsmoothed for the
+    # smoothing ablation); the 8-bit variant's has none (table "Two kernel implementations").
+    ds_step = bool(smooth_q_on) or mode == "int4_fp8"
     gq, gk = group_map(gmap, N, "q"), group_map(gmap, Nk, "k")
     dq, qc = quantize_groups(gQ, gq, qmax)
     dk, kc = quantize_groups(gK, gk, qmax)
@@ -305,7 +308,7 @@ def quantize_head(Q, K, V, mode="int4_fp8", sm_scale=None, gmap="g950", bq=BQ_SM
         vdec = _FP8[pv_fmt][3](vc)                        # [N, d] float64, exact
     return dict(N=N, Nk=Nk, d=d, kappa=kappa, qmax=qmax, kbar=kbar, qbar=qbar, delta_s=D, Q=np.asarray(Q, f32),
                 pv_fmt=pv_fmt,
-                q_codes=qc, q_scale=dq, q_groups=gq, k_codes=kc, k_scale=dk, k_groups=gk,
+                ds_step=ds_step, q_codes=qc, q_scale=dq, q_groups=gq, k_codes=kc, k_scale=dk, k_groups=gk,
                 v_codes=vc, v_scale=dv, v_dec=vdec, pv_exact=pv_exact, bq=bq, vbar=vbar)
 
 
@@ -359,7 +362,13 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
         m_new = np.maximum(m, S.max(axis=1))
         m_sub = (m_new - log2_fmax).astype(f32)
         with np.errstate(invalid="ignore"):
-            P448 = _exp2_f32((S - m_sub[:, None]).astype(f32))      # E = 448 * P~
+            if pro["ds_step"]:
+                arg = (S - m_sub[:, None]).astype(f32)    # the rounded score, then the subtraction
+            else:
+                # no Delta-S addend: dequantization and subtraction are one fused multiply-add, acc*c - m with one
+                # rounding (the running maximum itself is that of the rounded products, as above)
+                arg = np.where(np.isneginf(S), f32(-np.inf), (s - m_sub[:, None].astype(f64)).astype(f32))
+            P448 = _exp2_f32(arg)                         # E = 448 * P~
             alpha = _exp2_f32((m - m_new).astype(f32))
         l = ((alpha * l).astype(f32).astype(f64) + P448.astype(f64).sum(axis=1)).astype(f32)
         Phat = P448.astype(f64) if pro["pv_exact"] else dec(enc(P448))

@@ -151,8 +151,11 @@ template <> struct Factors<2> {
   }
   __device__ __forceinline__ float at(int kt, int g, int r) const { return c[kt][g][r]; }
 };
-// The 8-bit mode fuses the factor into the exponent's argument when it is shared by at least a quad.
-template <bool INT4, int GM> constexpr bool fused_factor() { return !INT4 && GM != 2; }
+// The 8-bit mode has no Delta-S in its score line: the dequantization product is fused into the exponent's
+// argument, 2^(fma(acc, c, -m)), one rounding, whatever the granularity of the key scales (with a scale per key
+// nothing is saved - the maximum needs the products anyway - but the value that decides the FP8 code of P~ is
+// formed the same way for every group map).
+template <bool INT4, int GM> constexpr bool fused_factor() { return !INT4; }
 
 // Middle part of one block of Algorithm 1's inner loop for one wavefront, cut into pieces of four
 // keys (one "group": registers 4G..4G+3 of key tile KT) so that MFMAs can be issued between them.
@@ -179,8 +182,7 @@ __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2
       x = 0.0f;
 #endif
     }
-    else if constexpr (!fused_factor<INT4, GM>()) x = __fmul_rn((float)raw[KT][4 * G + r], fac.at(KT, G, r));
-    else x = (float)raw[KT][4 * G + r];
+    else x = (float)raw[KT][4 * G + r];       // 8-bit mode: the factor is applied inside the exponent's argument
     if constexpr (MASKED) {
       const int key = key0 + 32 * KT + 16 * half + 4 * G + r;
       if (key >= n_keys || (CAUSAL && key > last_visible)) x = -INFINITY;
@@ -212,7 +214,7 @@ __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2
     // |c|: the pipeline's last update works on a stale, fully masked block whose scales are arbitrary
     // bits; -inf * |c| is -inf or NaN (dropped) whatever they are, so the running max stays intact
     mx = fmaxf(__fmul_rn(m0, fabsf(fac.at(0, 0, 0))), __fmul_rn(m1, fabsf(fac.at(1, 0, 0))));
-  } else {
+  } else if constexpr (GM == 1) {
     // the same per quad
     mx = -INFINITY;
 #pragma unroll
@@ -223,6 +225,16 @@ __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2
                               fmaxf(__int_as_float(acc[kt][4 * g + 2]), __int_as_float(acc[kt][4 * g + 3])));
         mx = fmaxf(mx, __fmul_rn(a, fabsf(fac.at(kt, g, 0))));
       }
+    }
+  } else {
+    // a scale per key: the maximum of the products themselves (a masked score is -inf whatever its factor)
+    mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int v = 0; v < 16; v += 2)
+        mx = fmaxf(fmaxf(mx, __fmul_rn(__int_as_float(acc[kt][v]), fabsf(fac.at(kt, v / 4, v % 4)))),
+                   __fmul_rn(__int_as_float(acc[kt][v + 1]), fabsf(fac.at(kt, (v + 1) / 4, (v + 1) % 4))));
     }
   }
   {
@@ -533,16 +545,20 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
 #pragma unroll
     for (int i = 0; i < 2 * CT; ++i) va[i] = lds[stg][KCK + i * 64 + lane];
   };
-  auto read_x = [&](int stg) {
+  // With a scale per key in the 8-bit mode the block's 32 factors stay live through the exponentials (they are
+  // fused into the exponent's argument), so the next block's 32 key scales are fetched after them, not half way.
+  constexpr bool LATE_SCALES = GM == 2 && !INT4;
+  auto read_x = [&](int stg, bool ds_part = true, bool scale_part = true) {
     const float* lx = reinterpret_cast<const float*>(&lds[stg][KCK + KC]);
     if constexpr (INT4) {
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
+      for (int kt = 0; ds_part && kt < 2; ++kt) {
         const v4f* dsv = reinterpret_cast<const v4f*>(lx + 32 * kt + 16 * half);
 #pragma unroll
         for (int g = 0; g < 4; ++g) dsr[kt][g] = dsv[g];
       }
     }
+    if (!scale_part) return;
     if constexpr (GM == 0) {
       ks.s[0] = lx[64 + half];
       ks.s[1] = lx[66 + half];
@@ -635,9 +651,10 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     float ls = 0.0f;                                                                                 \
     SAGE_X(0, MASKED_); SAGE_X(1, MASKED_); SAGE_X(2, MASKED_); SAGE_X(3, MASKED_);           /* X */ \
     read_v(cur);                                                                                     \
-    read_x(nx1);                                                                                     \
+    read_x(nx1, true, !LATE_SCALES);                                                                 \
     __builtin_amdgcn_sched_barrier(0);                                                               \
     SAGE_X(4, MASKED_); SAGE_X(5, MASKED_); SAGE_X(6, MASKED_); SAGE_X(7, MASKED_);                  \
+    if constexpr (LATE_SCALES) read_x(nx1, false, true);                                             \
     st.l_run = __fmaf_rn(alpha, st.l_run, ls);                                                       \
     Factors<GM> fn;                                                                                  \
     fn.set(dq, p.kappa, ks);                                                                         \
