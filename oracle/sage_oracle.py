@@ -344,6 +344,7 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
     nr = len(rows)
     fmax, log2_fmax, enc, dec = _FP8[pro["pv_fmt"]]       # static scale of P~: 1/448 (Sec. 3.3), or 1/57344
     m = np.full(nr, -np.inf, f32)
+    e = np.full(nr, -np.inf, f32)                         # exponent offset of the running sums: E = 2^(S - e)
     l = np.zeros(nr, f32)                                 # 448 * (running sum of P~)
     O = np.zeros((nr, d), f32)
     last_key = int(rows[-1]) + coff if causal else Nk - 1
@@ -360,7 +361,14 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
         if causal:
             S = np.where(ks[None, :] > rows[:, None] + coff, f32(-np.inf), S)
         m_new = np.maximum(m, S.max(axis=1))
-        m_sub = (m_new - log2_fmax).astype(f32)
+        # Exponent offset: the static scale of P~ is folded into the exponent, E = fmax * P~ = 2^(S - e) with
+        # e = m - log2(fmax).  Rounded to nearest, e could come out below m - log2(fmax) and the row's largest E above
+        # fmax - for scores beyond 2^19 far enough to overflow the 8-bit format.  So the maximum is first nudged
+        # upward by |m| 2^-22 (two to four units of its last place, one fused multiply-add): then E <= fmax whatever
+        # the roundings, at the price of a P~ scale 2^-22 |m| ln 2 below 1, which cancels in O / l.
+        with np.errstate(invalid="ignore"):
+            t = np.where(np.isfinite(m_new), (np.abs(m_new).astype(f64) * 2.0 ** -22 + m_new.astype(f64)).astype(f32), m_new)
+        m_sub = (t - log2_fmax).astype(f32)
         with np.errstate(invalid="ignore"):
             if pro["ds_step"]:
                 arg = (S - m_sub[:, None]).astype(f32)    # the rounded score, then the subtraction
@@ -369,35 +377,36 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
                 # rounding (the running maximum itself is that of the rounded products, as above)
                 arg = np.where(np.isneginf(S), f32(-np.inf), (s - m_sub[:, None].astype(f64)).astype(f32))
             P448 = _exp2_f32(arg)                         # E = 448 * P~
-            alpha = _exp2_f32((m - m_new).astype(f32))
+            alpha = _exp2_f32((e - m_sub).astype(f32))   # rescales what was summed under the previous offset
         l = ((alpha * l).astype(f32).astype(f64) + P448.astype(f64).sum(axis=1)).astype(f32)
         Phat = P448.astype(f64) if pro["pv_exact"] else dec(enc(P448))
         R = (Phat @ vdec[ks]).astype(f32)                 # exact block sum, one rounding
         O = ((alpha[:, None] * O).astype(f32) + R).astype(f32)
-        m = m_new
+        m, e = m_new, m_sub
     out = (O / l[:, None]).astype(f32)                    # O and l both carry the factor 448
     out = (out * pro["v_scale"][None, :]).astype(f32)
     if pro.get("vbar") is not None:                       # smooth V: O = O + mean(V)
         out = (out + pro["vbar"][None, :]).astype(f32)
     res = _round_out(out, out_dtype)
     if return_state:
-        return res, dict(m=m, l=l, O=O)
+        return res, dict(m=m, e=e, l=l, O=O)
     return res
 
 
 def row_lse(pro, rows, state):
     """Natural-log-sum-exp of the scores sm_scale * <q_r, k_t> over the visible keys, as the quantized
-    path evaluates them: from the final running maximum m and sum l of Algorithm 1 (base 2, l carried
-    as 448 * l) plus the one row constant the smoothing of K drops from every score of a row
-    (Sec. 3.1: <q_r, mean(K)>, invisible to the softmax but part of the sum's scale):
-        lse_r = ln 2 * (m_r + log2(l_r / 448) + kappa * <q_r, mean(K)>),
+    path evaluates them: from the final exponent offset e (the running maximum of Algorithm 1 minus
+    log2 448, see attention_rows) and the sum l carried under it (base 2: sum_t 2^S_t = l * 2^e) plus the
+    one row constant the smoothing of K drops from every score of a row (Sec. 3.1: <q_r, mean(K)>,
+    invisible to the softmax but part of the sum's scale):
+        lse_r = ln 2 * (e_r + log2(l_r) + kappa * <q_r, mean(K)>),
     evaluated in float64 from the FP32 state and rounded once to FP32.  This is what lets partial
     results over disjoint key sets be merged (weights exp(lse_part - lse_total))."""
     rows = np.arange(pro["N"])[rows]
-    m, l = state["m"].astype(f64), state["l"].astype(f64)
+    e, l = state["e"].astype(f64), state["l"].astype(f64)
     corr = f64(pro["kappa"]) * (pro["Q"][rows].astype(f64) @ pro["kbar"].astype(f64))
     with np.errstate(divide="ignore"):
-        return (np.log(2.0) * (m + np.log2(l / _FP8[pro["pv_fmt"]][0]) + corr)).astype(f32)
+        return (np.log(2.0) * (e + np.log2(l) + corr)).astype(f32)
 
 
 def _round_out(x, dtype):

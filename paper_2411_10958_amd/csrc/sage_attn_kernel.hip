@@ -192,7 +192,8 @@ __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2
 }
 
 // update_max: running max over the block's 64 dequantized scores of this lane's query (Eq. 1 /
-// Algorithm 1); returns alpha = 2^(m_old - m_new) and, in m_sub, the exponent offset of the block.
+// Algorithm 1); takes the previous block's exponent offset in m_sub and returns the new one there, and
+// alpha = 2^(old offset - new offset).
 template <int D, bool INT4, int GM, int PVF>
 __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2], const Factors<GM>& fac,
                                             float& m_sub) {
@@ -244,9 +245,17 @@ __device__ __forceinline__ float update_max(RowState<D>& st, const v16i (&acc)[2
     mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
   }
   const float m_new = fmaxf(st.m_run, mx);
-  const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_new);   // 2^-inf = 0 on the first block
-  // folds the static scale of P~ (Sec. 3.3: *448; *57344 or *127 for the other data types) into the exponent
-  m_sub = m_new - (PVF == PV_INT8 ? LOG2_127 : (PVF == PV_E5M2 ? LOG2_57344 : LOG2_448));
+  // The static scale of P~ (Sec. 3.3: *448; *57344 or *127 for the other data types) is folded into the exponent:
+  // E = scale * P~ = 2^(S - e), e = m - log2(scale).  Rounded to nearest, e could come out below m - log2(scale) and
+  // the row's largest E above the scale - for scores beyond 2^19 far enough to overflow the 8-bit format, whose
+  // conversion then gives NaN.  So m is first nudged upward by |m| 2^-22 (two to four units of its last place):
+  // E <= scale whatever the roundings; the factor 2^-(2^-22 |m|) on P~ cancels in O / l.  The previous sums are
+  // rescaled by the power of two of the offsets' difference (2^-inf = 0 on the first block), so O and l stay
+  // sums under the current offset exactly.
+  const float e_new = __fmaf_rn(fabsf(m_new), 0x1p-22f, m_new) -
+                      (PVF == PV_INT8 ? LOG2_127 : (PVF == PV_E5M2 ? LOG2_57344 : LOG2_448));
+  const float alpha = __builtin_amdgcn_exp2f(m_sub - e_new);      // m_sub: the offset of the previous block
+  m_sub = e_new;
   st.m_run = m_new;
   return alpha;
 }
@@ -272,9 +281,12 @@ __device__ __forceinline__ void exp_group(const v16i (&acc)[2], const Factors<GM
   }
   int wd = __float_as_int(e[0]);   // any value: both halves are overwritten below
   if constexpr (PVF == PV_INT8) {
-    // rint(127 P~) in [0, 127] as bytes (the conversion is exact on the rounded values)
+    // rint(127 P~) clipped to [0, 127] as bytes (the conversion is exact on the rounded values).  The clip
+    // matters: for scores beyond 2^16 the rounding of m - log2(127) lets the row's largest term come out as
+    // 127 * 2^(half an ulp of m) > 127.5, and a byte of 128 would be read as -128 by the integer MFMA.
 #pragma unroll
-    for (int r = 0; r < 4; ++r) wd = (int)__builtin_amdgcn_cvt_pk_u8_f32(rintf(e[r]), (unsigned)r, (unsigned)wd);
+    for (int r = 0; r < 4; ++r)
+      wd = (int)__builtin_amdgcn_cvt_pk_u8_f32(rintf(fminf(e[r], INT8_PV_MAX)), (unsigned)r, (unsigned)wd);
   } else if constexpr (PVF == PV_E5M2) {
     wd = __builtin_amdgcn_cvt_pk_bf8_f32(e[0], e[1], wd, false);
     wd = __builtin_amdgcn_cvt_pk_bf8_f32(e[2], e[3], wd, true);
@@ -595,7 +607,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   read_x(0);
   v16i raw[2], sc[2];                 // raw scores being produced / dequantized scores of block j
   qk_tile<D, INT4>(ka, qreg, raw);    // block 0 holds a visible key for every query
-  float alpha, m_sub;                 // of block j
+  float alpha, m_sub = -INFINITY;     // of block j (m_sub: nothing summed yet)
   Factors<GM> fj;                     // block j's dequantization factors (used again by the fused exponent)
   constexpr int NQK = qk_steps<D, INT4>();
   constexpr int GPC = 8 / CT;         // dequantization groups per P~V MFMA
@@ -691,11 +703,11 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
   }
   if (p.lse && half == 0 && query < sq.n) {
-    // ln sum_t exp(sm_scale <q, k_t>) = ln 2 * (m + log2(l) + the row constant smoothing K dropped); l_tot = 448 l
-    // st.m_run survived the pipeline's last update: that one saw a fully masked (stale) block
-    constexpr float LOG2_SCALE = PVF == PV_INT8 ? LOG2_127 : (PVF == PV_E5M2 ? LOG2_57344 : LOG2_448);
+    // ln sum_t exp(sm_scale <q, k_t>) = ln 2 * (e + log2(l) + the row constant smoothing K dropped): l_tot is the
+    // sum of 2^(S - e) under the final exponent offset e = m_sub, which survived the pipeline's last update
+    // (that one saw a fully masked, stale block and left the running max where it was)
     p.lse[lse_index(p, sq, b, h, query)] =
-        LN2 * (((st.m_run - LOG2_SCALE) + __builtin_amdgcn_logf(l_tot)) + lse_corr);
+        LN2 * ((m_sub + __builtin_amdgcn_logf(l_tot)) + lse_corr);
   }
   // One correctly rounded reciprocal per row instead of a division per element (64 of them were 4 % of
   // a tile of 64 blocks): O * fl32(1/l) is within one unit of the last FP32 place of fl32(O / l), far

@@ -11,6 +11,7 @@ import torch
 import workloads as wl
 from oracle import sage_oracle as so
 from test_gpu_parity import check_output, _pa, _lse_close
+from test_gpu_prologue_fuzz import _awkward
 
 pytestmark = pytest.mark.gpu
 
@@ -37,7 +38,21 @@ def _draw(rng):
     c["smooth_q"] = bool(rng.random() >= 0.25)
     # statistics of K and V handed over by the caller (only where mean(K) and delta_V are all that pass produces)
     c["kv_stats"] = bool(rng.random() < 0.4) and c["smooth_k"] and not c["smooth_v"]
+    # inputs with awkward values (heads scaled by powers of two, all-zero tokens, channels and heads, ties, heavy
+    # tails) instead of the workload generator's
+    c["awkward"] = bool(rng.random() < 0.3)
     return c
+
+
+def _inputs(c, seed, cfg, n=None, nk=None, B=2):
+    n, nk = (c["n"] if n is None else n), (c["nk"] if nk is None else nk)
+    if c["awkward"]:
+        r = np.random.default_rng(9000 + 17 * seed + cfg)
+        mk = lambda heads, tokens, lim: np.stack([_awkward(r, (heads, tokens, c["d"]), c["dtype"], lim) for _ in range(B)])
+        return dict(q=mk(c["H"], n, 8), k=mk(c["Hkv"], nk, 8), v=mk(c["Hkv"], nk, 4))
+    spec = wl.WorkloadSpec("sweep", B, c["H"], c["Hkv"], n, c["d"], c["dtype"], c["causal"], 3.0, 1.5, 2, 10.0, 1.0,
+                           cfg, c["vbias"], nk)
+    return wl.make_inputs(spec, seed=seed)
 
 
 def _oracle_smoothing(c):
@@ -54,9 +69,7 @@ def test_option_combination_matches_oracle(seed):
     rng = np.random.default_rng(1000 + seed)
     c = _draw(rng)
     print(f"combination {seed}: {c}", flush=True)
-    spec = wl.WorkloadSpec("sweep", 2, c["H"], c["Hkv"], c["n"], c["d"], c["dtype"], c["causal"], 3.0, 1.5, 2, 10.0, 1.0,
-                           300 + seed, c["vbias"], c["nk"])
-    data = wl.make_inputs(spec, seed=seed)
+    data = _inputs(c, seed, 300 + seed)
     dev = torch.device("cuda:0")
     q, k, v = (wl.to_torch(data[x], c["dtype"], dev) for x in "qkv")
     if c["layout"] == "NHD":
@@ -78,7 +91,7 @@ def test_option_combination_matches_oracle(seed):
                                                     out_dtype="fp32", smooth_v_on=c["smooth_v"], pv_fmt=c["pv"],
                                                     want_lse=c["lse"], **_oracle_smoothing(c))
             if c["lse"]:
-                _lse_close(lse[b, h].cpu().numpy(), pro["lse"])
+                _lse_close(lse[b, h].cpu().numpy(), pro["lse"], pro)
     check_output(wl.from_torch(out), ref, c["dtype"])
 
 
@@ -95,9 +108,7 @@ def test_packed_batch_combination_matches_oracle(seed):
     dev = torch.device("cuda:0")
     seqs, qs, ks, vs = [], [], [], []
     for i, (n, nk) in enumerate(zip(lens_q, lens_k)):
-        spec = wl.WorkloadSpec("sweep", 1, c["H"], c["Hkv"], max(n, 1), c["d"], c["dtype"], c["causal"], 3.0, 1.5, 2, 10.0,
-                               1.0, 400 + 10 * seed + i, c["vbias"], max(nk, 1))
-        dd = wl.make_inputs(spec, seed=seed)
+        dd = _inputs(c, seed, 400 + 10 * seed + i, max(n, 1), max(nk, 1), B=1)
         qn, kn, vn = dd["q"][0][:, :n], dd["k"][0][:, :nk], dd["v"][0][:, :nk]
         seqs.append((qn, kn, vn))
         qs.append(qn.transpose(1, 0, 2)); ks.append(kn.transpose(1, 0, 2)); vs.append(vn.transpose(1, 0, 2))
@@ -123,5 +134,5 @@ def test_packed_batch_combination_matches_oracle(seed):
                                                  gmap=GMAPS[c["group_map"]], out_dtype="fp32", smooth_v_on=c["smooth_v"],
                                                  pv_fmt=c["pv"], want_lse=c["lse"], **_oracle_smoothing(c))
             if c["lse"]:
-                _lse_close(lse[h, off[i]:off[i + 1]].cpu().numpy(), pro["lse"])
+                _lse_close(lse[h, off[i]:off[i + 1]].cpu().numpy(), pro["lse"], pro)
         check_output(wl.from_torch(out[off[i]:off[i + 1]]).transpose(1, 0, 2), ref, c["dtype"])

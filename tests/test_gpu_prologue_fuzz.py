@@ -24,8 +24,8 @@ def _round16(x, dtype):
     return t.to(torch.float32).numpy()
 
 
-def _awkward(rng, shape, dtype):
-    """[H, n, d] float32 values exactly representable in the 16-bit type."""
+def _awkward(rng, shape, dtype, lim=None):
+    """[H, n, d] float32 values exactly representable in the 16-bit type; heads scaled by 2^e, |e| <= lim."""
     H, n, d = shape
     kind = rng.integers(4)
     if kind == 0:                                   # few distinct values: many exact ties x / delta = k + 1/2
@@ -36,7 +36,8 @@ def _awkward(rng, shape, dtype):
         x = (rng.standard_normal(shape) * np.exp(2.0 * rng.standard_normal(shape))).astype(np.float32)
     else:                                           # small integers (products and sums exact everywhere)
         x = rng.integers(-7, 8, size=shape).astype(np.float32)
-    lim = 14 if dtype == "fp16" else 30             # keep fp16 inside its range
+    if lim is None:
+        lim = 14 if dtype == "fp16" else 30         # keep fp16 inside its range
     x = x * np.exp2(rng.integers(-lim, lim // 2 + 1, size=(H, 1, 1))).astype(np.float32)
     if rng.random() < 0.5:
         x[:, rng.integers(n)] = 0.0                 # an all-zero token
