@@ -49,7 +49,8 @@ def _inputs(c, seed, cfg, n=None, nk=None, B=2):
     if c["awkward"]:
         r = np.random.default_rng(9000 + 17 * seed + cfg)
         mk = lambda heads, tokens, lim: np.stack([_awkward(r, (heads, tokens, c["d"]), c["dtype"], lim) for _ in range(B)])
-        return dict(q=mk(c["H"], n, 8), k=mk(c["Hkv"], nk, 8), v=mk(c["Hkv"], nk, 4))
+        lim = int(os.environ.get("SAGE_SWEEP_LIM", "8"))     # heads of Q and K scaled by up to 2^lim either way
+        return dict(q=mk(c["H"], n, lim), k=mk(c["Hkv"], nk, lim), v=mk(c["Hkv"], nk, 4))
     spec = wl.WorkloadSpec("sweep", B, c["H"], c["Hkv"], n, c["d"], c["dtype"], c["causal"], 3.0, 1.5, 2, 10.0, 1.0,
                            cfg, c["vbias"], nk)
     return wl.make_inputs(spec, seed=seed)
