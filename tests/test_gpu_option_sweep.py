@@ -23,8 +23,9 @@ def _draw(rng):
     Hkv = int(rng.choice([1, 2]))
     H = Hkv * int(rng.choice([1, 2, 4]))
     causal = bool(rng.integers(2))
-    n = int(rng.choice([1, 17, 64, 100, 128, 129, 200, 257, 333, 450]))
-    nk = n if rng.random() < 0.5 else int(rng.choice([1, 63, 64, 65, 190, 300, 520]))
+    long_run = bool(os.environ.get("SAGE_SWEEP_LONG"))       # one-off runs on longer sequences (slower oracle)
+    n = int(rng.choice([513, 700, 1111, 2048] if long_run else [1, 17, 64, 100, 128, 129, 200, 257, 333, 450]))
+    nk = n if rng.random() < 0.5 else int(rng.choice([640, 1500, 2500, 3100] if long_run else [1, 63, 64, 65, 190, 300, 520]))
     if causal and nk < n:
         nk = n
     group_map = str(rng.choice(list(GMAPS)))
