@@ -241,7 +241,8 @@ def _delta_s_within_fp32_bound(got, pro, K, seen=None):
         diff = np.where(seen, diff, 0.0)
     u, d = 2.0 ** -24, gK.shape[1]
     assert np.all(diff <= (d + 2) * u * mag + np.spacing(np.abs(D))), "delta S beyond the FP32 dot-product bound"
-    assert diff.mean() <= 2 * u * max(mag.mean(), 1e-30), "delta S: mean error too large for FP32 operands"
+    if diff.size >= 4096:       # a statement about many independent roundings
+        assert diff.mean() <= 2 * u * max(mag.mean(), 1e-30), "delta S: mean error too large for FP32 operands"
 
 
 @pytest.mark.parametrize("N,d,dtype,H,Hkv,causal", [(640, 128, "bf16", 4, 2, False), (300, 64, "fp16", 2, 2, True)])
