@@ -101,3 +101,9 @@ def test_preprocessing_fuzz(seed):
             assert np.all(diff <= np.spacing(np.abs(D))), "delta S"
         elif int4:
             assert not got["delta_s"][0, h].any() and not got["q_mean"][0, h].any()
+        # the integer score accumulators of one random (128-query tile, 64-key block) through the kernel's MFMA code
+        qt, kb = int(rng.integers((n + 127) // 128)), int(rng.integers((nk + 63) // 64))
+        acc = pa.sage_attn_debug_qk(args, 0, h, qt, kb).cpu().numpy()
+        ref = so.int_scores(pro["q_codes"][qt * 128:qt * 128 + 128], pro["k_codes"][kb * 64:kb * 64 + 64])
+        assert np.array_equal(acc[: ref.shape[0], : ref.shape[1]], ref), "int32 accumulators"
+        assert not acc[ref.shape[0]:].any() and not acc[:, ref.shape[1]:].any()
