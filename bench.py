@@ -155,8 +155,10 @@ def main():
 
     # HBM bytes per launch of the attention kernel, from the committed rocprofv3 counter summary
     traffic = None
-    tfile = os.path.join(ROOT, "profiles", "attn_kernel_traffic.json")
-    if os.path.exists(tfile):
+    tfile = os.path.join(ROOT, "profiles", "attn_kernel_traffic.txt")      # JSON text, one record per workload / mode
+    default_options = (args.group_map == "lane" and args.pv_format == "e4m3" and not args.smooth_v and not args.no_smooth_k
+                       and not args.no_smooth_q and not args.fp32_delta_s)
+    if os.path.exists(tfile) and default_options:         # the counters were collected with the default options
         with open(tfile) as f:
             t = json.load(f).get(f"{args.workload}/{args.mode}")
         if t:
