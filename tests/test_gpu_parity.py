@@ -42,7 +42,9 @@ def check_output(got16, ref32, dtype):
     ref = ref32.astype(np.float64).reshape(-1, ref32.shape[-1])
     got = got16.astype(np.float64).reshape(-1, ref32.shape[-1])
     linf = np.abs(ref).max(axis=1, keepdims=True)
-    allowed = OUT_TOL * linf + _half_ulp16(ref, dtype)
+    # (+ the smallest normal FP32 number: results in the subnormal range are flushed by some of the hardware's
+    # conversions and are not compared more finely than that)
+    allowed = OUT_TOL * linf + _half_ulp16(ref, dtype) + 2.0 ** -126
     excess = np.abs(got - ref) - allowed
     worst = float((np.abs(got - ref) / np.where(linf > 0, linf, 1)).max())
     cos = wl.cos_sim(got, ref)
