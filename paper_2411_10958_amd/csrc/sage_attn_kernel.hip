@@ -50,8 +50,10 @@ struct AttnParams {
 // bytes in the low 6 dwords of an 8-dword operand) per (piece, tile).
 template <bool INT4> struct QkOperand { typedef v4i type; };
 template <> struct QkOperand<true> { typedef v8i type; };
+template <bool INT4> using qk_operand_t = typename QkOperand<INT4>::type;
 template <int D, bool INT4> constexpr int qk_pieces() { return INT4 ? D / 64 : D / 32; }
 template <int D, bool INT4> constexpr int qk_steps() { return 2 * qk_pieces<D, INT4>(); }
+template <int D, bool INT4> struct KBlockRegs { typedef qk_operand_t<INT4> type[2 * (INT4 ? D / 64 : D / 32)]; };
 
 template <int D, bool INT4, int I>
 __device__ __forceinline__ void qk_step(const typename QkOperand<INT4>::type (&ka)[qk_steps<D, INT4>()],
@@ -97,6 +99,23 @@ __device__ __forceinline__ typename QkOperand<INT4>::type load_qk_operand(Ptr ba
     return r;
   } else {
     return base[op * 64 + lane];
+  }
+}
+
+// The K^ operands of one block out of LDS (blk: the block's packed image).
+// INT4 mode: an operand is a 16-byte read plus an 8-byte read (its "tail").  Left free, the compiler pairs the
+// tails of two operands into one two-address read and then moves the halves of its result next to their
+// operands' first four registers, two vector instructions per operand in a loop that is bound by them.  The
+// empty statement after every operand is a fence for memory accesses: reads cannot be merged across it, so
+// every tail stays a read of its own that lands where its operand wants it, while the compiler still knows
+// about every read and waits for it before the first use.
+template <int D, bool INT4, typename Ptr>
+__device__ __forceinline__ void read_k_block(Ptr blk, int lane, typename KBlockRegs<D, INT4>::type& ka) {
+  constexpr int NS = qk_steps<D, INT4>();
+#pragma unroll
+  for (int i = 0; i < NS; ++i) {
+    ka[i] = load_qk_operand<INT4>(blk, i, lane);
+    if constexpr (INT4) asm volatile("" ::: "memory");
   }
 }
 
@@ -348,12 +367,14 @@ __device__ __forceinline__ void pv_step(RowState<D>& st, const v4i (&va)[2 * (D 
 // the wait for them is placed by hand - one vmcnt wait right before the barrier that publishes a
 // stage - instead of in front of every later LDS read.  gbase is wavefront-uniform.
 __device__ __forceinline__ void dma_b128(const void* gbase, unsigned voff, unsigned lds_byte) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_byte), "v"(voff), "s"(gbase) : "memory");
+  unsigned m0_after;    // M0 is declared as a result, so the compiler knows the statement overwrites it
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
+               : "={m0}"(m0_after) : "s"(lds_byte), "v"(voff), "s"(gbase) : "memory");
 }
 __device__ __forceinline__ void dma_b32(const void* gbase, unsigned voff, unsigned lds_byte) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-               :: "s"(lds_byte), "v"(voff), "s"(gbase) : "memory");
+  unsigned m0_after;
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3"
+               : "={m0}"(m0_after) : "s"(lds_byte), "v"(voff), "s"(gbase) : "memory");
 }
 
 // An empty use of a register: the compiler must have the value complete (its load waited for) here.
@@ -533,25 +554,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   v4f dsr[2][4];
   KeyScales<GM> ks;
   auto read_k = [&](int stg) {
-    if constexpr (INT4) {
-      // The 8-byte tail of every FP6 operand is read by hand: left to itself the compiler pairs the tails
-      // of two operands into one two-address read and then moves the halves of its result next to their
-      // operands' first four registers, two vector instructions per operand in a loop that is bound by
-      // them.  The tail goes out before the operand's 16-byte read, which the compiler does see and
-      // waits for: LDS reads return in order, so that wait covers the tail too.
-      const unsigned tail0 = lds0 + (unsigned)stg * (STAGE * 16) + 1024u + 8u * (unsigned)lane;
-#pragma unroll
-      for (int i = 0; i < 2 * NP; ++i) {
-        v2i hi;
-        asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(hi) : "v"(tail0), "n"(i * OP6_BYTES) : "memory");
-        const v4i lo = lds[stg][i * (OP6_BYTES / 16) + lane];
-        ka[i][0] = lo[0]; ka[i][1] = lo[1]; ka[i][2] = lo[2]; ka[i][3] = lo[3];
-        ka[i][4] = hi[0]; ka[i][5] = hi[1]; ka[i][6] = 0; ka[i][7] = 0;
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 2 * NP; ++i) ka[i] = load_qk_operand<INT4>(&lds[stg][0], i, lane);
-    }
+    read_k_block<D, INT4>(&lds[stg][0], lane, ka);
   };
   auto read_v = [&](int stg) {
 #pragma unroll
@@ -753,8 +756,8 @@ __global__ void __launch_bounds__(256) k_debug_qk(const int8_t* __restrict__ q_c
                   (size_t)w * (q_slab_bytes(D, INT4) / 16 / (BQ / WQ));
 #pragma unroll
   for (int s = 0; s < NP; ++s) qreg[s] = load_qk_operand<INT4>(gq, s, lane);
-#pragma unroll
-  for (int i = 0; i < 2 * NP; ++i) ka[i] = load_qk_operand<INT4>(&lds[0], i, lane);
+  // the block's operands come out of LDS through the attention kernel's own fetch code
+  read_k_block<D, INT4>(&lds[0], lane, ka);
   v16i acc[2];
   qk_tile<D, INT4>(ka, qreg, acc);
 #pragma unroll
