@@ -166,6 +166,19 @@ int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B,
                   int d, int causal, float sm_scale, int mode);
 void sage_attn_release(void);
 
+/* For callers that cannot allocate device memory or have it allocated on their behalf: code running under HIP
+   graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same forward pass as
+   sage_attn_fwd_ex, with the workspace taken from a fixed array of SAGE_STATIC_WORKSPACE_BYTES that is part of
+   the library's device image (every GPU the library is used on holds its own copy from the first call on it
+   until the process ends): the call makes no hipMalloc / hipFree and no other allocating call, and ignores
+   args->workspace / workspace_bytes.  q, k, v, out (and lse, cu_seqlens_*, k_mean_in, v_scale_in) are the
+   caller's, as everywhere.  Shapes whose sage_attn_workspace_bytes() exceeds SAGE_STATIC_WORKSPACE_BYTES are
+   refused with SAGE_ERR_WORKSPACE before anything is launched; more than 64 devices: SAGE_ERR_UNSUPPORTED.
+   All calls on one GPU share that GPU's array: calls that overlap there (two streams, two threads) race, and
+   the caller must order them; nothing in it has to be cleared between calls. */
+#define SAGE_STATIC_WORKSPACE_BYTES (64u << 20)
+int sage_attn_fwd_static(const sage_attn_args* args);
+
 /* Output of the preprocessing stage in plain ("logical") layouts, for checking it bit by bit.
    All pointers are device buffers the caller allocates; a NULL member is skipped.
      q_codes [B,H,N,d] int8       codes of gamma(Q) (int4 mode) or Q (int8 mode), Sec. 3.2

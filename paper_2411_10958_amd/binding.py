@@ -70,7 +70,7 @@ def load_library():
         P = ctypes.POINTER
         lib.sage_attn_workspace_bytes.restype = ctypes.c_size_t
         lib.sage_attn_workspace_bytes.argtypes = [P(sage_attn_args)]
-        for name in ("sage_attn_fwd_ex", "sage_attn_prologue", "sage_attn_core"):
+        for name in ("sage_attn_fwd_ex", "sage_attn_prologue", "sage_attn_core", "sage_attn_fwd_static"):
             getattr(lib, name).restype = ctypes.c_int
             getattr(lib, name).argtypes = [P(sage_attn_args)]
         lib.sage_attn_fwd.restype = ctypes.c_int
@@ -197,6 +197,14 @@ def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_f
     _check(load_library().sage_attn_fwd_ex(ctypes.byref(a)), "sage_attn_fwd_ex")
     del keep  # torch's caching allocator keeps the block alive for work already queued on its streams
     return (out, lse) if return_lse else out
+
+
+def sage_attn_fwd_static(q, k, v, out, causal=False, sm_scale=0.0, mode="int4_fp8", stream=None, **kw):
+    """The forward pass on the library's built-in workspace (no allocation anywhere: `out` is the caller's).
+    **kw as make_args."""
+    a = make_args(q, k, v, out, causal, sm_scale, mode, None, stream, **kw)
+    _check(load_library().sage_attn_fwd_static(ctypes.byref(a)), "sage_attn_fwd_static")
+    return out
 
 
 def make_varlen_args(q, k, v, out, cu_seqlens_q, cu_seqlens_k=None, max_seqlen_q=None, max_seqlen_k=None, **kw):

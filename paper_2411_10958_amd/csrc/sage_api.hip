@@ -88,6 +88,14 @@ int hip_status(hipError_t e) {
   return SAGE_ERR_HIP;
 }
 
+// Workspace of sage_attn_fwd_static: device memory that exists from the moment the library is loaded on a GPU, so
+// the call itself allocates nothing.  Every GPU holds its own copy of the array at its own address; in host code the
+// array's name is only a handle for hipGetSymbolAddress, the address kernels can use is what that call returns, taken
+// once per device (with that device current) and kept in g_static_ws.
+static __device__ __align__(256) unsigned char scratch[SAGE_STATIC_WORKSPACE_BYTES];
+constexpr int MAX_DEVICES = 64;
+void* g_static_ws[MAX_DEVICES] = {};
+
 void* g_ws = nullptr;      // workspace of the convenience entry point
 size_t g_ws_bytes = 0;
 int g_ws_device = -1;      // the device it was allocated on
@@ -169,6 +177,31 @@ int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B,
 }
 
 void sage_attn_release(void) { (void)release_ws(); }
+
+int sage_attn_fwd_static(const sage_attn_args* args) {
+  Dims D;
+  int st = validate(args, &D, true);
+  if (st != SAGE_OK) return st;
+  const Workspace w = make_workspace(D);
+  if (w.total > (size_t)SAGE_STATIC_WORKSPACE_BYTES) return SAGE_ERR_WORKSPACE;   // beyond the built-in workspace
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return hip_status(hipErrorUnknown);
+  if (dev < 0 || dev >= MAX_DEVICES) return SAGE_ERR_UNSUPPORTED;
+  if (!g_static_ws[dev]) {                  // first call on this device: where does its copy of the array live?
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return hip_status(hipErrorUnknown);
+    g_static_ws[dev] = ptr;
+  }
+  // Nothing in the workspace has to start at zero (every kernel writes what a later one reads), so the contents
+  // the previous call left behind need no clearing.
+  sage_attn_args a = *args;
+  a.workspace = g_static_ws[dev];
+  a.workspace_bytes = (size_t)SAGE_STATIC_WORKSPACE_BYTES;
+  Ptrs P = ptrs_for(&a, w);
+  if ((st = hip_status(launch_prologue(D, P, (hipStream_t)a.stream))) != SAGE_OK) return st;
+  P.lse = a.lse;
+  return hip_status(launch_attention(D, P, (hipStream_t)a.stream));
+}
 
 int sage_attn_kv_stats(const sage_attn_args* args, float* k_mean_out, float* v_scale_out) {
   if (!k_mean_out || !v_scale_out) return SAGE_ERR_INVALID_ARG;
