@@ -21,12 +21,11 @@ Precision rules (the readings this repository takes where the paper is silent):
     and 2**x replaces e**x, which leaves softmax unchanged;  the score of one (query, key)
     pair is the single FP32 rounding of  acc * c + D  with c = fl32(fl32(dQ*dK) * kappa)
     and D = fl32(kappa * <qbar_i, gamma(K)_t>)  (inner product in float64);
-  * the FP8 code of P~ is decided on  E = 448 * P~  evaluated as one exponential,
-    E = fl32(2**fl32(S - m_sub)) with m_sub = fl32(m - fl32(log2 448))  (the static scale 1/448 of
-    Sec. 3.3 folded into the exponent: the same real number as exp(S - m) * 448, and the precision
-    in which the gfx950 kernel takes this decision); codes are E4M3(E), saturating at 448;
-  * l (the softmax denominator) sums the unquantized FP32 values as Algorithm 1 prints it (here
-    carried as 448 * l = sum of E, divided out at the end);
+  * the inner loop is evaluated in the order Algorithm 1 prints it, one FP32 rounding per line:
+    P~ = fl32(2**fl32(S - m)), l = fl32(fl32(alpha * l) + rowsum(P~)) on the unquantized P~, then
+    P^ = E4M3(fl32(P~ * 448)), saturating at 448 (`attention_rows`, the oracle of record);
+    `attention_rows_kernel_order` is a second, separately named form with the roundings where the
+    gfx950 kernel has them (static scale folded into the exponent), pinned against the first;
   * the per-block product R = P^ V^ is the exact sum of the FP8 products rounded once to
     FP32 (an ideal FP32 buffer), then O = fl32(fl32(alpha*O) + R).
 Parity pins for every function here live in tests/test_oracle_pins.py.
@@ -325,80 +324,180 @@ def int_scores(q_codes, k_codes):
     return np.rint(q_codes.astype(f64) @ k_codes.astype(f64).T).astype(np.int64)
 
 
-def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_state=False):
-    """Inner loop + epilogue of Algorithm 1 for the query rows `rows` (a slice or index
-    array inside ONE smoothing block) of a head prepared by `quantize_head`.
-
-    Returns the [len(rows), d] output rounded to the 16-bit type (as float32).  With N_kv != N
-    a causal mask is aligned to the last query and key: query r sees keys t <= r + (N_kv - N).
-    """
-    N, Nk, d, kappa = pro["N"], pro["Nk"], pro["d"], pro["kappa"]
+def _row_setup(pro, rows, causal, bkv):
+    """What both forms of the inner loop share before their first block: the rows' codes and scales, the
+    smoothing block they lie in, and the number of key blocks they walk."""
+    N, Nk = pro["N"], pro["Nk"]
     coff = Nk - N
     assert not causal or coff >= 0, "a causal mask needs N_kv >= N"
     rows = np.arange(N)[rows]
     blk = int(rows[0]) // pro["bq"]
     assert int(rows[-1]) // pro["bq"] == blk, "rows must lie in one smoothing block"
-    qc = pro["q_codes"][rows]
-    dq = pro["q_scale"][pro["q_groups"][rows]]
-    vdec = pro["v_dec"]
-    nr = len(rows)
-    fmax, log2_fmax, enc, dec = _FP8[pro["pv_fmt"]]       # static scale of P~: 1/448 (Sec. 3.3), or 1/57344
-    m = np.full(nr, -np.inf, f32)
-    e = np.full(nr, -np.inf, f32)                         # exponent offset of the running sums: E = 2^(S - e)
-    l = np.zeros(nr, f32)                                 # 448 * (running sum of P~)
-    O = np.zeros((nr, d), f32)
     last_key = int(rows[-1]) + coff if causal else Nk - 1
-    n_blocks = last_key // bkv + 1
-    for j in range(n_blocks):
-        ks = np.arange(j * bkv, min((j + 1) * bkv, Nk))
-        acc = int_scores(qc, pro["k_codes"][ks])
-        dk = pro["k_scale"][pro["k_groups"][ks]]
-        c = ((dq[:, None] * dk[None, :]).astype(f32) * kappa).astype(f32)
-        s = acc.astype(f64) * c.astype(f64)
-        if pro["delta_s"] is not None:
-            s = s + pro["delta_s"][blk, ks].astype(f64)[None, :]
-        S = s.astype(f32)                                 # one rounding of acc*c + D
-        if causal:
-            S = np.where(ks[None, :] > rows[:, None] + coff, f32(-np.inf), S)
-        m_new = np.maximum(m, S.max(axis=1))
-        # Exponent offset: the static scale of P~ is folded into the exponent, E = fmax * P~ = 2^(S - e) with
-        # e = m - log2(fmax).  Rounded to nearest, e could come out below m - log2(fmax) and the row's largest E above
-        # fmax - for scores beyond 2^19 far enough to overflow the 8-bit format.  So the maximum is first nudged
-        # upward by |m| 2^-22 (two to four units of its last place, one fused multiply-add): then E <= fmax whatever
-        # the roundings, at the price of a P~ scale 2^-22 |m| ln 2 below 1, which cancels in O / l.
-        with np.errstate(invalid="ignore"):
-            t = np.where(np.isfinite(m_new), (np.abs(m_new).astype(f64) * 2.0 ** -22 + m_new.astype(f64)).astype(f32), m_new)
-        m_sub = (t - log2_fmax).astype(f32)
-        with np.errstate(invalid="ignore"):
-            if pro["ds_step"]:
-                arg = (S - m_sub[:, None]).astype(f32)    # the rounded score, then the subtraction
-            else:
-                # no Delta-S addend: dequantization and subtraction are one fused multiply-add, acc*c - m with one
-                # rounding (the running maximum itself is that of the rounded products, as above)
-                arg = np.where(np.isneginf(S), f32(-np.inf), (s - m_sub[:, None].astype(f64)).astype(f32))
-            P448 = _exp2_f32(arg)                         # E = 448 * P~
-            alpha = _exp2_f32((e - m_sub).astype(f32))   # rescales what was summed under the previous offset
-        l = ((alpha * l).astype(f32).astype(f64) + P448.astype(f64).sum(axis=1)).astype(f32)
-        Phat = P448.astype(f64) if pro["pv_exact"] else dec(enc(P448))
-        R = (Phat @ vdec[ks]).astype(f32)                 # exact block sum, one rounding
-        O = ((alpha[:, None] * O).astype(f32) + R).astype(f32)
-        m, e = m_new, m_sub
-    out = (O / l[:, None]).astype(f32)                    # O and l both carry the factor 448
+    return rows, blk, coff, last_key // bkv + 1
+
+
+def _block_scores(pro, rows, blk, coff, causal, j, bkv):
+    """Score line of Algorithm 1 for key block j: S = psi^-1(Qhat Khat^T) + Delta-S, in base 2.
+    Returns (ks, s, S): the block's key indices, the unrounded float64 value acc * c (+ D) and its single
+    FP32 rounding with masked positions at -inf."""
+    ks = np.arange(j * bkv, min((j + 1) * bkv, pro["Nk"]))
+    acc = int_scores(pro["q_codes"][rows], pro["k_codes"][ks])
+    dq = pro["q_scale"][pro["q_groups"][rows]]
+    dk = pro["k_scale"][pro["k_groups"][ks]]
+    c = ((dq[:, None] * dk[None, :]).astype(f32) * pro["kappa"]).astype(f32)
+    s = acc.astype(f64) * c.astype(f64)
+    if pro["delta_s"] is not None:
+        s = s + pro["delta_s"][blk, ks].astype(f64)[None, :]
+    S = s.astype(f32)                                     # one rounding of acc*c + D
+    if causal:
+        S = np.where(ks[None, :] > rows[:, None] + coff, f32(-np.inf), S)
+    return ks, s, S
+
+
+def _epilogue(pro, O, l, fmax, out_dtype):
+    """Last line of Algorithm 1: O / l / 448 * delta_V (+ mean(V) with the smooth-V option), rounded to the
+    output type.  fmax is the static scale still to be divided out (1 when l already carries it)."""
+    out = (O / l[:, None]).astype(f32)
+    if fmax != 1.0:
+        out = (out / f32(fmax)).astype(f32)
     out = (out * pro["v_scale"][None, :]).astype(f32)
     if pro.get("vbar") is not None:                       # smooth V: O = O + mean(V)
         out = (out + pro["vbar"][None, :]).astype(f32)
-    res = _round_out(out, out_dtype)
+    return _round_out(out, out_dtype)
+
+
+def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_state=False, p_codes=None,
+                   return_codes=False):
+    """THE ORACLE OF RECORD for the inner loop + epilogue of Algorithm 1, evaluated in the order the
+    algorithm prints its lines, every line rounded once to FP32:
+
+        S    = psi^-1(Matmul(Qhat_i, Khat_j^T)) + Delta-S_ij            (one rounding of acc * c + D)
+        m_ij = max(m_i,j-1, rowmax(S))
+        P~   = exp(S - m_ij)                                           (base 2: kappa carries log2 e)
+        l_ij = exp(m_i,j-1 - m_ij) * l_i,j-1 + rowsum(P~)              (the unquantized P~)
+        P^   = (P~ * 448).to(FP8 E4M3)                                 (Sec. 3.3 static scale)
+        O_ij = diag(exp(m_i,j-1 - m_ij)) O_i,j-1 + Matmul(P^, V^_j)    (Sec. 3.4: block product exact,
+                                                                        rounded once; then the FP32 sum)
+        O_i  = diag(l)^-1 O / 448 * delta_V
+
+    for the query rows `rows` (a slice or index array inside ONE smoothing block) of a head prepared by
+    `quantize_head`.  Returns the [len(rows), d] output rounded to out_dtype (as float32).  With N_kv != N
+    a causal mask is aligned to the last query and key: query r sees keys t <= r + (N_kv - N).
+
+    p_codes: optional uint8 / int8 array [len(rows), n_blocks * bkv]: 8-bit codes to use for P^ INSTEAD of
+    the ones this function would compute (everything else - m, P~, l - as printed).  It exists so that a test
+    can show that a deviating result is explained by nothing but the codes of P^ (a floating-point value
+    decides an integer there).  return_codes: also return the codes of P^ that were used, same shape.
+    """
+    rows, blk, coff, n_blocks = _row_setup(pro, rows, causal, bkv)
+    d = pro["d"]
+    vdec = pro["v_dec"]
+    nr = len(rows)
+    fmax, _, enc, dec = _FP8[pro["pv_fmt"]]               # static scale of P~: 1/448 (Sec. 3.3)
+    m = np.full(nr, -np.inf, f32)
+    l = np.zeros(nr, f32)
+    O = np.zeros((nr, d), f32)
+    codes = np.zeros((nr, n_blocks * bkv), np.uint8)
+    for j in range(n_blocks):
+        ks, _, S = _block_scores(pro, rows, blk, coff, causal, j, bkv)
+        m_new = np.maximum(m, S.max(axis=1))
+        with np.errstate(invalid="ignore"):
+            P = _exp2_f32((S - m_new[:, None]).astype(f32))
+            alpha = _exp2_f32((m - m_new).astype(f32))
+        l = ((alpha * l).astype(f32).astype(f64) + P.astype(f64).sum(axis=1)).astype(f32)
+        if pro["pv_exact"]:
+            Phat = (P * f32(fmax)).astype(f32).astype(f64)
+        else:
+            if p_codes is None:
+                cj = enc((P * f32(fmax)).astype(f32)).view(np.uint8)
+            else:
+                cj = np.asarray(p_codes)[:, j * bkv: j * bkv + len(ks)].view(np.uint8)
+            codes[:, j * bkv: j * bkv + len(ks)] = cj
+            Phat = dec(cj.view(np.int8) if pro["pv_fmt"] == "int8" else cj)
+        R = (Phat @ vdec[ks]).astype(f32)                 # exact block sum, one rounding
+        O = ((alpha[:, None] * O).astype(f32) + R).astype(f32)
+        m = m_new
+    res = _epilogue(pro, O, l, fmax, out_dtype)
+    ret = (res,)
     if return_state:
-        return res, dict(m=m, e=e, l=l, O=O)
-    return res
+        ret += (dict(m=m, e=m, l=l, O=O),)                # e: the exponent offset l is summed under (here m itself)
+    if return_codes:
+        ret += (codes,)
+    return ret if len(ret) > 1 else res
+
+
+def attention_rows_kernel_order(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_state=False,
+                                return_codes=False, return_e=False):
+    """NOT the oracle of record: the same inner loop with the FP32 roundings placed where the gfx950 kernel
+    places them.  Mathematically it is Algorithm 1 line for line; it differs from `attention_rows` in three
+    rounding decisions, each of which tests/test_oracle_pins.py compares with the printed form:
+
+      * the static scale 448 of P~ (Sec. 3.3) is folded into the exponent: E = 448 P~ = 2^(S - e) with the
+        offset e = fl32(m' - fl32(log2 448)), one exponential and no multiplication; l and O are carried as
+        sums of E (448 l, 448 O), so the epilogue divides O by l only;
+      * before the subtraction m is nudged upward, m' = fl32(m + 2^-22 |m|) (one fused multiply-add), so that the
+        row's largest E stays <= 448 whatever way e rounds - P~ is thereby scaled by 2^-(2^-22 |m|), which
+        cancels in O / l - and the running sums are rescaled by 2^(e_old - e_new);
+      * the 8-bit variant (no Delta-S addend in its score line) forms the exponent's argument acc * c - e with
+        one rounding (a fused multiply-add) while the running maximum is that of the rounded products.
+
+    The GPU tests compare the kernel with this function at a tolerance that only leaves room for the
+    hardware's exponential, summation order and reciprocal, and with `attention_rows` at the stated bar.
+    return_e: also return the unrounded-to-8-bit values E [len(rows), n_blocks * bkv] (float32).
+    """
+    rows, blk, coff, n_blocks = _row_setup(pro, rows, causal, bkv)
+    d = pro["d"]
+    vdec = pro["v_dec"]
+    nr = len(rows)
+    fmax, log2_fmax, enc, dec = _FP8[pro["pv_fmt"]]
+    m = np.full(nr, -np.inf, f32)
+    e = np.full(nr, -np.inf, f32)                         # exponent offset of the running sums: E = 2^(S - e)
+    l = np.zeros(nr, f32)                                 # fmax * (running sum of P~)
+    O = np.zeros((nr, d), f32)
+    codes = np.zeros((nr, n_blocks * bkv), np.uint8)
+    Eall = np.zeros((nr, n_blocks * bkv), f32)
+    for j in range(n_blocks):
+        ks, s, S = _block_scores(pro, rows, blk, coff, causal, j, bkv)
+        m_new = np.maximum(m, S.max(axis=1))
+        with np.errstate(invalid="ignore"):
+            t = np.where(np.isfinite(m_new), (np.abs(m_new).astype(f64) * 2.0 ** -22 + m_new.astype(f64)).astype(f32), m_new)
+        e_new = (t - log2_fmax).astype(f32)
+        with np.errstate(invalid="ignore"):
+            if pro["ds_step"]:
+                arg = (S - e_new[:, None]).astype(f32)    # the rounded score, then the subtraction
+            else:
+                arg = np.where(np.isneginf(S), f32(-np.inf), (s - e_new[:, None].astype(f64)).astype(f32))
+            E = _exp2_f32(arg)                            # E = fmax * P~
+            alpha = _exp2_f32((e - e_new).astype(f32))    # rescales what was summed under the previous offset
+        l = ((alpha * l).astype(f32).astype(f64) + E.astype(f64).sum(axis=1)).astype(f32)
+        if pro["pv_exact"]:
+            Phat = E.astype(f64)
+        else:
+            cj = enc(E).view(np.uint8)
+            codes[:, j * bkv: j * bkv + len(ks)] = cj
+            Phat = dec(cj.view(np.int8) if pro["pv_fmt"] == "int8" else cj)
+        Eall[:, j * bkv: j * bkv + len(ks)] = E
+        R = (Phat @ vdec[ks]).astype(f32)
+        O = ((alpha[:, None] * O).astype(f32) + R).astype(f32)
+        m, e = m_new, e_new
+    res = _epilogue(pro, O, l, 1.0, out_dtype)            # O and l both carry the factor fmax
+    ret = (res,)
+    if return_state:
+        ret += (dict(m=m, e=e, l=l, O=O),)
+    if return_codes:
+        ret += (codes,)
+    if return_e:
+        ret += (Eall,)
+    return ret if len(ret) > 1 else res
 
 
 def row_lse(pro, rows, state):
     """Natural-log-sum-exp of the scores sm_scale * <q_r, k_t> over the visible keys, as the quantized
-    path evaluates them: from the final exponent offset e (the running maximum of Algorithm 1 minus
-    log2 448, see attention_rows) and the sum l carried under it (base 2: sum_t 2^S_t = l * 2^e) plus the
-    one row constant the smoothing of K drops from every score of a row (Sec. 3.1: <q_r, mean(K)>,
-    invisible to the softmax but part of the sum's scale):
+    path evaluates them: from the final exponent offset e the sum l is carried under (the running maximum of
+    Algorithm 1 in `attention_rows`; the maximum minus log2 448 in `attention_rows_kernel_order`), in base 2
+    sum_t 2^S_t = l * 2^e, plus the one row constant the smoothing of K drops from every score of a row
+    (Sec. 3.1: <q_r, mean(K)>, invisible to the softmax but part of the sum's scale):
         lse_r = ln 2 * (e_r + log2(l_r) + kappa * <q_r, mean(K)>),
     evaluated in float64 from the FP32 state and rounded once to FP32.  This is what lets partial
     results over disjoint key sets be merged (weights exp(lse_part - lse_total))."""
@@ -421,11 +520,17 @@ def _round_out(x, dtype):
     raise ValueError(dtype)
 
 
+FORMS = {"printed": attention_rows, "kernel": attention_rows_kernel_order}
+
+
 def sage_attention_head(Q, K, V, causal=False, mode="int4_fp8", sm_scale=None, gmap="g950",
-                        bq=BQ_SMOOTH, bkv=BKV_ACC, out_dtype="bf16", q_blocks=None, want_lse=False, **kw):
+                        bq=BQ_SMOOTH, bkv=BKV_ACC, out_dtype="bf16", q_blocks=None, want_lse=False,
+                        form="printed", **kw):
     """Algorithm 1 for one (batch, head); `q_blocks` restricts the outer loop to some
     smoothing blocks (rows of the others are left zero).  With want_lse the prologue dict also
-    carries "lse" [N] (see row_lse)."""
+    carries "lse" [N] (see row_lse).  form: "printed" (`attention_rows`, the oracle of record) or "kernel"
+    (`attention_rows_kernel_order`)."""
+    attention_rows = FORMS[form]
     pro = quantize_head(Q, K, V, mode, sm_scale, gmap, bq, **kw)
     N, d = Q.shape
     out = np.zeros((N, d), f32)
@@ -444,7 +549,7 @@ def sage_attention_head(Q, K, V, causal=False, mode="int4_fp8", sm_scale=None, g
 
 
 def sage_attention(q, k, v, causal=False, mode="int4_fp8", sm_scale=None, gmap="g950",
-                   bq=BQ_SMOOTH, bkv=BKV_ACC, out_dtype="bf16", **kw):
+                   bq=BQ_SMOOTH, bkv=BKV_ACC, out_dtype="bf16", form="printed", **kw):
     """Batched form: q [B, H, N, d], k and v [B, H_kv, N, d]; query head h reads KV head
     h // (H / H_kv).  Returns [B, H, N, d] float32 (values rounded to out_dtype)."""
     B, H, N, d = q.shape
@@ -453,7 +558,7 @@ def sage_attention(q, k, v, causal=False, mode="int4_fp8", sm_scale=None, gmap="
     for b in range(B):
         for h in range(H):
             out[b, h], _ = sage_attention_head(q[b, h], k[b, h // g], v[b, h // g], causal, mode,
-                                               sm_scale, gmap, bq, bkv, out_dtype, **kw)
+                                               sm_scale, gmap, bq, bkv, out_dtype, form=form, **kw)
     return out
 
 

@@ -9,7 +9,8 @@ import torch
 
 import workloads as wl
 from oracle import sage_oracle as so
-from test_gpu_parity import check_output, _pa
+from oracle import parity
+from test_gpu_parity import _pa
 
 pytestmark = pytest.mark.gpu
 
@@ -84,12 +85,11 @@ def test_full_size_sampled_parity(name, mode):
                 ref = so.int_scores(pro["q_codes"][rows], pro["k_codes"][keys])
                 assert np.array_equal(acc[: ref.shape[0], : ref.shape[1]], ref)
         # outputs of the sampled query blocks
-        got_rows, ref_rows = [], []
+        chk = parity.OutputCheck(spec.dtype, f"(b={b}, h={h}) ")
         for i in blocks:
             rows = slice(i * 128, min(i * 128 + 128, spec.N))
-            ref_rows.append(so.attention_rows(pro, rows, spec.causal, out_dtype="fp32"))
-            got_rows.append(wl.from_torch(out[b, h, rows]))
-        check_output(np.concatenate(got_rows), np.concatenate(ref_rows), spec.dtype)
+            chk.add(wl.from_torch(out[b, h, rows]), pro, rows, spec.causal)
+        chk.finish()
 
 
 def test_full_size_smooth_v_sampled_parity():
@@ -114,12 +114,11 @@ def test_full_size_smooth_v_sampled_parity():
     assert np.array_equal(quant["v_mean"][b, h].cpu().numpy(), pro["vbar"])
     assert np.array_equal(quant["v_scale"][b, h].cpu().numpy(), pro["v_scale"])
     assert np.array_equal(quant["v_codes"][b, h].cpu().numpy(), pro["v_codes"])
-    got_rows, ref_rows = [], []
+    chk = parity.OutputCheck(spec.dtype)
     for i in blocks:
         rows = slice(i * 128, min(i * 128 + 128, spec.N))
-        ref_rows.append(so.attention_rows(pro, rows, spec.causal, out_dtype="fp32"))
-        got_rows.append(wl.from_torch(out[b, h, rows]))
-    check_output(np.concatenate(got_rows), np.concatenate(ref_rows), spec.dtype)
+        chk.add(wl.from_torch(out[b, h, rows]), pro, rows, spec.causal)
+    chk.finish()
 
 
 @pytest.mark.parametrize("group_map,gmap", [("fine", "fine"), ("token", "per_token")])
@@ -144,12 +143,11 @@ def test_full_size_finer_groups_sampled_parity(group_map, gmap):
     pro = so.quantize_head(data["q"][b, h], data["k"][b, h], data["v"][b, h], ds_blocks=blocks, gmap=gmap)
     for name in ("q_codes", "k_codes", "q_scale", "k_scale"):
         assert np.array_equal(quant[name][b, h].cpu().numpy(), pro[name]), name
-    got_rows, ref_rows = [], []
+    chk = parity.OutputCheck(spec.dtype)
     for i in blocks:
         rows = slice(i * 128, min(i * 128 + 128, spec.N))
-        ref_rows.append(so.attention_rows(pro, rows, spec.causal, out_dtype="fp32"))
-        got_rows.append(wl.from_torch(out[b, h, rows]))
-    check_output(np.concatenate(got_rows), np.concatenate(ref_rows), spec.dtype)
+        chk.add(wl.from_torch(out[b, h, rows]), pro, rows, spec.causal)
+    chk.finish()
 
 
 def test_full_size_varlen_sampled_parity():
@@ -187,9 +185,8 @@ def test_full_size_varlen_sampled_parity():
     print(f"  oracle on sequence {i}, head {h}, query blocks {blocks}", flush=True)
     pro = so.quantize_head(seqs[i]["q"][0, h], seqs[i]["k"][0, h // (H // Hkv)], seqs[i]["v"][0, h // (H // Hkv)],
                            ds_blocks=blocks)
-    got_rows, ref_rows = [], []
+    chk = parity.OutputCheck(dtype)
     for bq in blocks:
         rows = slice(bq * 128, min(bq * 128 + 128, lens[i]))
-        ref_rows.append(so.attention_rows(pro, rows, True, out_dtype="fp32"))
-        got_rows.append(wl.from_torch(out[off[i] + rows.start:off[i] + rows.stop, h]))
-    check_output(np.concatenate(got_rows), np.concatenate(ref_rows), dtype)
+        chk.add(wl.from_torch(out[off[i] + rows.start:off[i] + rows.stop, h]), pro, rows, True)
+    chk.finish()

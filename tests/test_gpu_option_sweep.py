@@ -10,7 +10,8 @@ import torch
 
 import workloads as wl
 from oracle import sage_oracle as so
-from test_gpu_parity import check_output, _pa, _lse_close
+from oracle import parity
+from test_gpu_parity import _pa, _lse_close
 from test_gpu_prologue_fuzz import _awkward
 
 pytestmark = pytest.mark.gpu
@@ -65,7 +66,13 @@ def _oracle_smoothing(c):
 N_SEEDS = int(os.environ.get("SAGE_SWEEP_SEEDS", "48"))
 
 
-@pytest.mark.parametrize("seed", range(N_SEEDS))
+# Seeds kept as fixed regression cases whatever SAGE_SWEEP_SEEDS says.  7631: the dominant key of some rows has
+# an all-zero V row, so the whole output row lies below the smallest normal FP32 number, where the hardware
+# exponential's flush of subnormal results shows (the absolute floor of oracle/parity.py).
+REGRESSION_SEEDS = [7631]
+
+
+@pytest.mark.parametrize("seed", list(range(N_SEEDS)) + [s for s in REGRESSION_SEEDS if s >= N_SEEDS])
 def test_option_combination_matches_oracle(seed):
     pa = _pa()
     rng = np.random.default_rng(1000 + seed)
@@ -84,17 +91,12 @@ def test_option_combination_matches_oracle(seed):
     out, lse = res if c["lse"] else (res, None)
     if c["layout"] == "NHD":
         out = out.permute(0, 2, 1, 3)
-    g = c["H"] // c["Hkv"]
-    ref = np.empty((2, c["H"], c["n"], c["d"]), np.float32)
-    for b in range(2):
-        for h in range(c["H"]):
-            ref[b, h], pro = so.sage_attention_head(data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g],
-                                                    causal=c["causal"], mode=c["mode"], gmap=GMAPS[c["group_map"]],
-                                                    out_dtype="fp32", smooth_v_on=c["smooth_v"], pv_fmt=c["pv"],
-                                                    want_lse=c["lse"], **_oracle_smoothing(c))
-            if c["lse"]:
-                _lse_close(lse[b, h].cpu().numpy(), pro["lse"], pro)
-    check_output(wl.from_torch(out), ref, c["dtype"])
+    pros = parity.check_heads(wl.from_torch(out), data, c["causal"], c["mode"], c["dtype"], want_lse=c["lse"],
+                              gmap=GMAPS[c["group_map"]], smooth_v_on=c["smooth_v"], pv_fmt=c["pv"], **_oracle_smoothing(c))
+    if c["lse"]:
+        for b in range(2):
+            for h in range(c["H"]):
+                _lse_close(lse[b, h].cpu().numpy(), pros[b][h]["lse"], pros[b][h])
 
 
 @pytest.mark.parametrize("seed", range(max(6, N_SEEDS // 4)))
@@ -130,11 +132,10 @@ def test_packed_batch_combination_matches_oracle(seed):
         if n == 0 or nk == 0:
             continue
         qn, kn, vn = seqs[i]
-        ref = np.empty((c["H"], n, c["d"]), np.float32)
-        for h in range(c["H"]):
-            ref[h], pro = so.sage_attention_head(qn[h], kn[h // g], vn[h // g], causal=c["causal"], mode=c["mode"],
-                                                 gmap=GMAPS[c["group_map"]], out_dtype="fp32", smooth_v_on=c["smooth_v"],
-                                                 pv_fmt=c["pv"], want_lse=c["lse"], **_oracle_smoothing(c))
-            if c["lse"]:
-                _lse_close(lse[h, off[i]:off[i + 1]].cpu().numpy(), pro["lse"], pro)
-        check_output(wl.from_torch(out[off[i]:off[i + 1]]).transpose(1, 0, 2), ref, c["dtype"])
+        pros = parity.check_heads(wl.from_torch(out[off[i]:off[i + 1]]).transpose(1, 0, 2)[None],
+                                  dict(q=qn[None], k=kn[None], v=vn[None]), c["causal"], c["mode"], c["dtype"],
+                                  want_lse=c["lse"], gmap=GMAPS[c["group_map"]], smooth_v_on=c["smooth_v"], pv_fmt=c["pv"],
+                                  **_oracle_smoothing(c))
+        if c["lse"]:
+            for h in range(c["H"]):
+                _lse_close(lse[h, off[i]:off[i + 1]].cpu().numpy(), pros[0][h]["lse"], pros[0][h])

@@ -4,7 +4,8 @@ masks and grouped KV heads.
 
 Bars: codes, scales, means and int32 score accumulators bit-equal; Delta-S equal up to the
 last FP32 bit of a float64-accumulated value; outputs within 2e-3 max-abs after dividing by
-the row's L-inf norm and cosine >= 0.9999 (the tolerance the benchmark spec states for this path)."""
+the row's L-inf norm and cosine >= 0.9999 against Algorithm 1 evaluated as printed, within 5e-4 against
+its kernel-order form, every row beyond either bar explained by one-step codes of P~ (oracle/parity.py)."""
 import ctypes
 
 import numpy as np
@@ -12,51 +13,13 @@ import pytest
 import torch
 
 import workloads as wl
+from oracle import parity
 from oracle import sage_oracle as so
 
 pytestmark = pytest.mark.gpu
 
-OUT_TOL = 2e-3
-COS_TOL = 0.9999
-
-
-def _half_ulp16(x, dtype):
-    """Half the spacing of the 16-bit output format at |x| (fp16: 10 mantissa bits, bf16: 7)."""
-    mant = 10 if dtype == "fp16" else 7
-    ax = np.maximum(np.abs(x).astype(np.float64), 2.0 ** -14 if dtype == "fp16" else 2.0 ** -126)
-    return 0.5 * np.exp2(np.floor(np.log2(ax)) - mant)
-
-
-def check_output(got16, ref32, dtype):
-    """The stated bar applies to the FP32 result; the kernel then rounds once to the 16-bit
-    output type, which can move an element by at most half a unit of that format.  So each
-    element must lie within OUT_TOL * ||ref row||_inf + half an output ulp of the oracle's
-    unrounded FP32 value, and the flattened cosine must reach COS_TOL.
-
-    One exception is allowed for, because a floating-point value decides an integer here: both
-    sides take the FP8 code of 448 * P~ in the same FP32 arithmetic, but the hardware exponential
-    is accurate to 1 ulp, not correctly rounded, so about one P~ in 10^6 lands on the other side of
-    an E4M3 rounding boundary and its code differs by one step (at most 1/8 of that one term).  A
-    row that carries such a term with a large softmax weight misses the bar; at most one row in a
-    thousand may do so, and then by no more than one FP8 step of the largest output magnitude."""
-    ref = ref32.astype(np.float64).reshape(-1, ref32.shape[-1])
-    got = got16.astype(np.float64).reshape(-1, ref32.shape[-1])
-    linf = np.abs(ref).max(axis=1, keepdims=True)
-    # (+ the smallest normal FP32 number: results in the subnormal range are flushed by some of the hardware's
-    # conversions and are not compared more finely than that)
-    allowed = OUT_TOL * linf + _half_ulp16(ref, dtype) + 2.0 ** -126
-    excess = np.abs(got - ref) - allowed
-    worst = float((np.abs(got - ref) / np.where(linf > 0, linf, 1)).max())
-    cos = wl.cos_sim(got, ref)
-    bad_rows = np.nonzero(excess.max(axis=1) > 0)[0]
-    print(f"  max-abs/row-Linf {worst:.3e} (bar {OUT_TOL:g} + half an output ulp)  cos {cos:.7f}  "
-          f"rows beyond the bar {len(bad_rows)} of {len(ref)}", flush=True)
-    assert np.isfinite(got).all()
-    assert len(bad_rows) <= len(ref) // 1000, \
-        f"{len(bad_rows)} rows beyond tolerance, worst excess {excess.max():.3e}"
-    if len(bad_rows):
-        assert np.abs(got - ref)[bad_rows].max() <= 0.125 * np.abs(ref).max() + _half_ulp16(ref, dtype).max()
-    assert cos >= COS_TOL
+OUT_TOL, COS_TOL = parity.OUT_TOL, parity.COS_TOL
+_half_ulp16 = parity.half_ulp16
 
 
 def _pa():
@@ -137,8 +100,7 @@ def test_attention_output_matches_oracle(N, d, dtype, H, Hkv, causal, mode):
     out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode)
     torch.cuda.synchronize()
     got = wl.from_torch(out)
-    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32")
-    check_output(got, ref, dtype)
+    parity.check_heads(got, data, causal, mode, dtype)
     # accuracy against the unquantized definition is reported, not asserted tightly
     g = H // Hkv
     full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
@@ -178,9 +140,7 @@ def test_smooth_v_matches_oracle(N, d, dtype, H, Hkv, causal, mode):
     plain = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode)
     torch.cuda.synchronize()
     got_out, got_plain = wl.from_torch(out), wl.from_torch(plain)
-    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32",
-                            smooth_v_on=True)
-    check_output(got_out, ref, dtype)
+    parity.check_heads(got_out, data, causal, mode, dtype, smooth_v_on=True)
     g = H // Hkv
     full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
                      for h in range(H)])
@@ -219,14 +179,11 @@ def test_smoothing_switched_off_matches_oracle(N, d, dtype, H, Hkv, causal, smoo
                 assert not got["q_mean"][b, h].any() and not got["delta_s"][b, h].any(), "no Q smoothing: zeros"
     out, lse = pa.sage_attn_fwd_ex(q, k, v, causal=causal, smooth_k=smooth_k, smooth_q=smooth_q, return_lse=True)
     torch.cuda.synchronize()
-    ref = np.empty((spec.B, H, N, d), np.float32)
+    pros = parity.check_heads(wl.from_torch(out), data, causal, "int4_fp8", dtype, want_lse=True,
+                              smooth_q_on=smooth_q, smooth_k_on=smooth_k)
     for b in range(spec.B):
         for h in range(H):
-            ref[b, h], pro = so.sage_attention_head(data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g],
-                                                    causal=causal, out_dtype="fp32", want_lse=True,
-                                                    smooth_q_on=smooth_q, smooth_k_on=smooth_k)
-            _lse_close(lse[b, h].cpu().numpy(), pro["lse"], pro)
-    check_output(wl.from_torch(out), ref, dtype)
+            _lse_close(lse[b, h].cpu().numpy(), pros[b][h]["lse"], pros[b][h])
 
 
 # ---- Delta-S accumulated in FP32 (an option of the boundary: faster preprocessing, approximate Delta-S) ----
@@ -267,22 +224,30 @@ def test_fp32_delta_s_option(N, d, dtype, H, Hkv, causal):
     out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, fp32_delta_s=True)
     exact = pa.sage_attn_fwd_ex(q, k, v, causal=causal)
     torch.cuda.synchronize()
-    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, out_dtype="fp32")
-    # Same bar as the default path, except that more rows may carry a P~ code one FP8 step away from the oracle's
-    # (the scores differ in their last bits): up to one row in 200 instead of one in 1000, each still within one
-    # FP8 step of the largest output magnitude.
-    got16 = wl.from_torch(out).astype(np.float64).reshape(-1, d)
-    r = ref.astype(np.float64).reshape(-1, d)
+    # Same bars as the default path.  The scores now differ from the oracle's in their last bits, so more codes of
+    # P~ can come out one step away; the ones that can are those whose value lies within the FP32 dot-product bound of
+    # Delta-S (times ln 2: a difference in the base-2 score is that relative difference in 2^score) of a rounding
+    # boundary, and a row beyond a bar must be explained by moving one or two of exactly those.
+    u = 2.0 ** -24
+
+    def ds_width(pro, r):
+        gK = (pro_k[id(pro)] - pro["kbar"][None, :]).astype(np.float32)
+        mag = float(pro["kappa"]) * (np.abs(pro["qbar"][r // 128]).astype(np.float64) @ np.abs(gK).astype(np.float64).T)
+        return np.log(2.0) * ((d + 2) * u * mag + np.spacing(np.abs(pro["delta_s"][r // 128]).astype(np.float64)))
+
+    pro_k = {}
+    chk = parity.OutputCheck(dtype, "FP32 Delta-S: ", near=ds_width)
+    got16 = wl.from_torch(out)
+    for b in range(spec.B):
+        for h in range(H):
+            pro = so.quantize_head(data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g])
+            pro_k[id(pro)] = data["k"][b, h // g]
+            chk.add_head(got16[b, h], pro, causal)
+    chk.finish()
+    # and against the default path the outputs agree to the same bar, but for the rows with such a code
+    r = wl.from_torch(exact).astype(np.float64).reshape(-1, d)
     linf = np.abs(r).max(axis=1, keepdims=True)
-    excess = np.abs(got16 - r) - (OUT_TOL * linf + _half_ulp16(r, dtype))
-    bad = np.nonzero(excess.max(axis=1) > 0)[0]
-    print(f"  rows beyond the bar {len(bad)} of {len(r)}; cos {wl.cos_sim(got16, r):.7f}", flush=True)
-    assert np.isfinite(got16).all() and wl.cos_sim(got16, r) >= COS_TOL
-    assert len(bad) <= max(1, len(r) // 200)
-    if len(bad):
-        assert np.abs(got16 - r)[bad].max() <= 0.125 * np.abs(r).max() + _half_ulp16(r, dtype).max()
-    # and against the default path the outputs agree to the same bar
-    d2 = np.abs(got16 - wl.from_torch(exact).astype(np.float64).reshape(-1, d))
+    d2 = np.abs(got16.astype(np.float64).reshape(-1, d) - r)
     assert (d2.max(axis=1) > 2 * OUT_TOL * linf[:, 0] + 2 * _half_ulp16(r, dtype).max(axis=1)).mean() <= 0.005
 
 
@@ -371,9 +336,7 @@ def test_coarser_groups_match_oracle(N, d, dtype, H, Hkv, causal, group_map, gma
         # the library keeps its scale arrays' shapes: one entry per query pair / per 16 keys
         assert np.array_equal(got["q_scale"][0, h], pro["q_scale"][pro["q_groups"][::2]]), "q scales"
         assert np.array_equal(got["k_scale"][0, h // g], pro["k_scale"][pro["k_groups"][::16]]), "k scales"
-    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32",
-                            gmap=gmap)
-    check_output(wl.from_torch(out), ref, dtype)
+    parity.check_heads(wl.from_torch(out), data, causal, mode, dtype, gmap=gmap)
     full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
                      for h in range(H)])
     e_b, e_f = wl.rel_l1(wl.from_torch(out)[0], full), wl.rel_l1(wl.from_torch(fine)[0], full)
@@ -403,8 +366,7 @@ def test_finer_groups_match_oracle(N, d, dtype, H, Hkv, causal, group_map, gmap,
         assert np.array_equal(got["k_codes"][0, h // g], pro["k_codes"]), "k codes"
         assert np.array_equal(got["q_scale"][0, h], pro["q_scale"]), "q scales"
         assert np.array_equal(got["k_scale"][0, h // g], pro["k_scale"]), "k scales"
-    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32", gmap=gmap)
-    check_output(wl.from_torch(out), ref, dtype)
+    parity.check_heads(wl.from_torch(out), data, causal, mode, dtype, gmap=gmap)
     full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
                      for h in range(H)])
     e_f, e_l = wl.rel_l1(wl.from_torch(out)[0], full), wl.rel_l1(wl.from_torch(lane)[0], full)
@@ -430,8 +392,7 @@ def test_other_pv_data_types_match_oracle(N, d, dtype, H, Hkv, causal, pv, mode)
         pro = so.quantize_head(data["q"][0, h * g], data["k"][0, h], data["v"][0, h], mode=mode, pv_fmt=pv)
         assert np.array_equal(got["v_scale"][0, h].cpu().numpy(), pro["v_scale"]), "v scales"
         assert np.array_equal(got["v_codes"][0, h].cpu().numpy(), pro["v_codes"].view(np.uint8)), "v codes"
-    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32", pv_fmt=pv)
-    check_output(wl.from_torch(out), ref, dtype)
+    parity.check_heads(wl.from_torch(out), data, causal, mode, dtype, pv_fmt=pv)
     if mode == "int8_fp8" and pv == "e5m2":   # where the FP8 stage dominates the error, E4M3 is the better format (Sec. 3.3)
         full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
                          for h in range(H)])
@@ -473,8 +434,7 @@ def test_other_key_length_matches_oracle(N, Nk, d, dtype, H, Hkv, causal, mode):
             D = pro["delta_s"].astype(np.float64)
             diff = np.abs(got["delta_s"][0, h].astype(np.float64) - D)
             assert np.all(diff <= np.spacing(np.abs(D))), "delta S"
-    ref = so.sage_attention(data["q"], data["k"], data["v"], causal=causal, mode=mode, out_dtype="fp32")
-    check_output(wl.from_torch(out), ref, dtype)
+    parity.check_heads(wl.from_torch(out), data, causal, mode, dtype)
     full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
                      for h in range(H)])
     assert wl.cos_sim(wl.from_torch(out)[0], full) > (0.9 if mode == "int4_fp8" else 0.99)
@@ -550,8 +510,8 @@ def test_varlen_batch_equals_one_sequence_at_a_time(lens_q, lens_k, d, dtype, H,
         assert torch.equal(alone[0], part), f"sequence {b}"
         if not checked and n >= 100:
             qn, kn, vn = seqs[b]
-            ref = so.sage_attention(qn[None], kn[None], vn[None], causal=causal, mode=mode, out_dtype="fp32")
-            check_output(wl.from_torch(part).transpose(1, 0, 2), ref[0], dtype)
+            parity.check_heads(wl.from_torch(part).transpose(1, 0, 2)[None], dict(q=qn[None], k=kn[None], v=vn[None]),
+                               causal, mode, dtype)
             checked = True
     assert checked
 
@@ -592,12 +552,10 @@ def test_lse_matches_oracle(N, Nk, d, dtype, H, Hkv, causal, mode):
     torch.cuda.synchronize()
     assert torch.equal(out, plain)                      # asking for it changes nothing else
     assert lse.shape == (2, H, N)
-    g = H // Hkv
+    pros = parity.check_heads(wl.from_torch(out), data, causal, mode, dtype, want_lse=True)
     for b in range(2):
         for h in range(H):
-            _, pro = so.sage_attention_head(data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g], causal=causal,
-                                            mode=mode, out_dtype="fp32", want_lse=True)
-            _lse_close(lse[b, h].cpu().numpy(), pro["lse"], pro)
+            _lse_close(lse[b, h].cpu().numpy(), pros[b][h]["lse"], pros[b][h])
     full = so.ref_lse_fp64(data["q"][1, 0], data["k"][1, 0], causal=causal)
     assert np.abs(lse[1, 0].cpu().numpy() - full).max() < (1.0 if mode == "int4_fp8" else 0.1)
 

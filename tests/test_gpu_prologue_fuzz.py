@@ -19,33 +19,7 @@ N_SEEDS = int(os.environ.get("SAGE_FUZZ_SEEDS", "32"))
 GMAPS = {"lane": "g950", "block": "per_block", "fine": "fine", "token": "per_token", "tensor": "per_tensor"}
 
 
-def _round16(x, dtype):
-    t = torch.tensor(x, dtype=torch.float32).to(torch.float16 if dtype == "fp16" else torch.bfloat16)
-    return t.to(torch.float32).numpy()
-
-
-def _awkward(rng, shape, dtype, lim=None):
-    """[H, n, d] float32 values exactly representable in the 16-bit type; heads scaled by 2^e, |e| <= lim."""
-    H, n, d = shape
-    kind = rng.integers(4)
-    if kind == 0:                                   # few distinct values: many exact ties x / delta = k + 1/2
-        x = rng.integers(-15, 16, size=shape).astype(np.float32) * 0.5
-    elif kind == 1:                                 # ordinary noise with channel offsets
-        x = rng.standard_normal(shape).astype(np.float32) + 3.0 * rng.standard_normal((H, 1, d)).astype(np.float32)
-    elif kind == 2:                                 # heavy tails
-        x = (rng.standard_normal(shape) * np.exp(2.0 * rng.standard_normal(shape))).astype(np.float32)
-    else:                                           # small integers (products and sums exact everywhere)
-        x = rng.integers(-7, 8, size=shape).astype(np.float32)
-    if lim is None:
-        lim = 14 if dtype == "fp16" else 30         # keep fp16 inside its range
-    x = x * np.exp2(rng.integers(-lim, lim // 2 + 1, size=(H, 1, 1))).astype(np.float32)
-    if rng.random() < 0.5:
-        x[:, rng.integers(n)] = 0.0                 # an all-zero token
-    if rng.random() < 0.5:
-        x[:, :, rng.integers(d)] = 0.0              # an all-zero channel
-    if rng.random() < 0.2:
-        x[rng.integers(H)] = 0.0                    # an all-zero head
-    return _round16(np.clip(x, -6e4, 6e4) if dtype == "fp16" else x, dtype)
+_awkward = wl.awkward_values       # seeded generator of awkward inputs (shared with the CPU pins)
 
 
 @pytest.mark.parametrize("seed", range(N_SEEDS))

@@ -235,35 +235,42 @@ def test_block_sizes_do_not_change_the_mathematics():
         assert np.abs(out - ref).max() < 2e-3 * np.abs(ref).max()
 
 
-def test_online_state_matches_two_pass():
+@pytest.mark.parametrize("form", ["printed", "kernel"])
+def test_online_state_matches_two_pass(form):
     q, k, v = _head(N=192, d=16, k_off=1.0)
     pro = so.quantize_head(q, k, v, mode=32767, smooth_q_on=True, pv_exact=True)
-    _, st = so.attention_rows(pro, slice(0, 128), False, out_dtype="fp32", return_state=True)
+    _, st = so.FORMS[form](pro, slice(0, 128), False, out_dtype="fp32", return_state=True)
+    carried = 448.0 if form == "kernel" else 1.0       # the kernel-order form carries 448 * l
     S = (q[:128].astype(f64) @ (k.astype(f64) - pro["kbar"].astype(f64)).T) / np.sqrt(16) * np.log2(np.e)
     # m is the row max of the base-2 scores up to a row constant: compare differences
     m_ref = S.max(axis=1)
     shift = st["m"].astype(f64) - m_ref
     l_ref = np.exp2(S - m_ref[:, None]).sum(axis=1)
-    assert np.allclose(st["l"] / 448.0, l_ref, rtol=2e-3)      # the oracle carries 448 * l
+    assert np.allclose(st["l"] / carried, l_ref, rtol=2e-3)
     # the constant is the dropped bias b of Sec. 3.1 (times kappa): it varies per row only
     assert shift.shape == (128,)
 
 
-def test_static_p_scale_is_448():
+@pytest.mark.parametrize("form", ["printed", "kernel"])
+def test_static_p_scale_is_448(form):
     # Sec. 3.3: P~ in [0, 1] is quantized with the static scale 1/448, i.e. the FP8 code is taken of
-    # 448 * P~.  With a single key P~ = 1: the carried denominator is 448 and the output is exactly the
-    # dequantized FP8 value of V; with two equal keys it is 896 and the average.
+    # 448 * P~.  With a single key P~ = 1: its code is that of 448, the denominator is 1 (448 in the form that
+    # carries 448 * l) and the output is exactly the dequantized FP8 value of V; with two equal keys the
+    # denominator doubles and the output is the average.
+    attention_rows = so.FORMS[form]
+    carried = 448.0 if form == "kernel" else 1.0
     q = np.ones((1, 16), f32); k = np.ones((1, 16), f32)
     v = np.linspace(-3, 3, 16, dtype=f32)[None, :].astype(np.float16).astype(f32)
     pro = so.quantize_head(q, k, v, mode="int8_fp8")
-    out, st = so.attention_rows(pro, slice(0, 1), False, out_dtype="fp32", return_state=True)
-    assert abs(float(st["l"][0]) - 448.0) < 448.0 * 1e-6
+    out, st, codes = attention_rows(pro, slice(0, 1), False, out_dtype="fp32", return_state=True, return_codes=True)
+    assert abs(float(st["l"][0]) - carried) < carried * 1e-6
+    assert codes[0, 0] == so.e4m3_encode(448.0) and not codes[0, 1:].any()
     dec = so.e4m3_decode(pro["v_codes"]) * pro["v_scale"].astype(f64)[None, :]
     assert np.allclose(out, dec, rtol=1e-6, atol=0)
     q2, k2, v2 = np.ones((2, 16), f32), np.ones((2, 16), f32), np.concatenate([v, v])
     pro2 = so.quantize_head(q2, k2, v2, mode="int8_fp8")
-    _, st2 = so.attention_rows(pro2, slice(0, 2), False, out_dtype="fp32", return_state=True)
-    assert np.allclose(st2["l"], 896.0, rtol=1e-6)
+    _, st2 = attention_rows(pro2, slice(0, 2), False, out_dtype="fp32", return_state=True)
+    assert np.allclose(st2["l"], 2 * carried, rtol=1e-6)
 
 
 # ---- P6: the quantized pipeline approaches FP64 attention as bit-width grows -----------------
@@ -517,8 +524,12 @@ def test_int8_pv_variant_is_an_integer_product_with_static_scale_127():
             assert np.array_equal(pro["v_codes"],
                                   np.clip(np.rint((v / dv[None, :]).astype(f32)), -127, 127).astype(np.int8))
             assert np.abs(pro["v_codes"]).max() == 127
-            out, st = so.attention_rows(pro, slice(0, 128), False, out_dtype="fp32", return_state=True)
-            assert np.all(st["l"] >= 127.0 - 1e-3)      # the row maximum alone contributes 127 to 127 * l
+            out, st, codes = so.attention_rows(pro, slice(0, 128), False, out_dtype="fp32", return_state=True,
+                                               return_codes=True)
+            assert np.all(st["l"] >= 1.0)                # the row maximum alone contributes 1 to l ...
+            assert np.all(codes.view(np.int8).max(axis=1) == 127)    # ... and its code is 127
+            _, stk = so.attention_rows_kernel_order(pro, slice(0, 128), False, out_dtype="fp32", return_state=True)
+            assert np.all(stk["l"] >= 127.0 - 1e-3)     # the form that carries 127 * l
     assert errs[4096][1] > 1.5 * errs[256][1]           # INT8 degrades with the length ...
     assert abs(errs[4096][0] - errs[256][0]) < 0.3 * errs[256][0]   # ... E4M3 does not
     assert errs[4096][1] > errs[4096][0]

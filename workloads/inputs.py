@@ -144,6 +144,34 @@ def make_inputs(spec, seed=0, heads=None):
     return dict(q=q, k=k, v=v, q_heads=q_heads, kv_heads=kv_heads, spec=spec)
 
 
+def awkward_values(rng, shape, dtype, lim=None):
+    """[H, n, d] float32 values exactly representable in the 16-bit type, chosen to be awkward for a quantized
+    attention path rather than typical: one of four kinds per call (few distinct values, so that many quotients
+    x / delta are exact rounding ties; ordinary noise with channel offsets; heavy tails; small integers), every
+    head scaled by its own power of two 2^e with -lim <= e <= lim/2, and, with some probability, an all-zero
+    token, an all-zero channel and an all-zero head.  `rng` is a numpy Generator (the caller seeds it)."""
+    H, n, d = shape
+    kind = rng.integers(4)
+    if kind == 0:
+        x = rng.integers(-15, 16, size=shape).astype(np.float32) * 0.5
+    elif kind == 1:
+        x = rng.standard_normal(shape).astype(np.float32) + 3.0 * rng.standard_normal((H, 1, d)).astype(np.float32)
+    elif kind == 2:
+        x = (rng.standard_normal(shape) * np.exp(2.0 * rng.standard_normal(shape))).astype(np.float32)
+    else:
+        x = rng.integers(-7, 8, size=shape).astype(np.float32)
+    if lim is None:
+        lim = 14 if dtype == "fp16" else 30         # keep fp16 inside its range
+    x = x * np.exp2(rng.integers(-lim, lim // 2 + 1, size=(H, 1, 1))).astype(np.float32)
+    if rng.random() < 0.5:
+        x[:, rng.integers(n)] = 0.0
+    if rng.random() < 0.5:
+        x[:, :, rng.integers(d)] = 0.0
+    if rng.random() < 0.2:
+        x[rng.integers(H)] = 0.0
+    return round_to_dtype(np.clip(x, -6e4, 6e4) if dtype == "fp16" else x, dtype)
+
+
 def flops(spec):
     """Operation count used for TOPS: 4*B*H*N*N_kv*d; under a causal mask the visible (query, key)
     pairs, N*(2*N_kv - N)/2, i.e. half of N^2 when N_kv = N."""
