@@ -186,19 +186,17 @@ template <bool INT4, int GM> constexpr bool fused_factor() { return !INT4; }
 // as floats: the maximum commutes with the factor and the product is fused into the exponent's
 // argument (exp_group), one instruction less per score.
 template <bool INT4, bool CAUSAL, bool MASKED, int GM, int KT, int G>
-__device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2], const v4f (&dsr)[2][4],
-                                              const Factors<GM>& fac, int half, int key0, int last_visible,
-                                              int n_keys) {
+__device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2], const Factors<GM>& fac, int half,
+                                              int key0, int last_visible, int n_keys) {
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     float x;
     if constexpr (INT4) {
-      // the three-address form by hand: left to choose, the compiler takes the two-address form (result in
-      // the register of Delta-S) for a few of these and then moves the results into place
+      // On entry sc holds the block's Delta-S values (read from LDS straight into these registers): the score is
+      // one multiply-add in place, in the two-operand encoding, which issues faster than the three-operand one.
+      x = __int_as_float(sc[KT][4 * G + r]);
 #if defined(__HIP_DEVICE_COMPILE__)
-      asm("v_fma_f32 %0, %1, %2, %3" : "=v"(x) : "v"(__int_as_float(raw[KT][4 * G + r])), "v"(fac.at(KT, G, r)), "v"(dsr[KT][G][r]));
-#else
-      x = 0.0f;
+      asm("v_fmac_f32 %0, %1, %2" : "+v"(x) : "v"(__int_as_float(raw[KT][4 * G + r])), "v"(fac.at(KT, G, r)));
 #endif
     }
     else x = (float)raw[KT][4 * G + r];       // 8-bit mode: the factor is applied inside the exponent's argument
@@ -406,11 +404,26 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
 
   // XCD-aware tile order: consecutive workgroup ids land on different XCDs (8 of them), so
   // give every XCD a contiguous range of tiles - tiles of one head then share one L2.
+  // Under a causal mask a tile's work grows with its position, and workgroups start in index order: when an XCD's
+  // range holds whole heads, its tiles are issued heaviest first ACROSS those heads (all their last tiles, then all
+  // their last but one, ...) instead of head by head, where the heavy tiles of the last head would start late and
+  // finish long after the rest (measured at N = 8192, where a range is four heads of 64 tiles: 13 % of the kernel's
+  // time; 1.5 % at N = 16384).  Longer sequences keep the head-by-head order: the imbalance shrinks with the tile
+  // count while four interleaved heads no longer share an XCD's L2 (N = 32768: 1.5 % slower interleaved).
   const int per_xcd = (p.total_tiles + 7) / 8;
-  const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  const int in_xcd = blockIdx.x / 8;
+  int tile = (blockIdx.x % 8) * per_xcd + in_xcd;
+  int bh, qb;
+  if (CAUSAL && p.nQb <= 128 && per_xcd % p.nQb == 0) {
+    const int heads_here = per_xcd / p.nQb;
+    bh = (blockIdx.x % 8) * heads_here + in_xcd % heads_here;
+    qb = p.nQb - 1 - in_xcd / heads_here;
+    tile = bh * p.nQb;      // (only compared with the tile count below)
+  } else {
+    bh = tile / p.nQb;
+    qb = CAUSAL ? p.nQb - 1 - tile % p.nQb : tile % p.nQb;   // heavy tiles first
+  }
   if (tile >= p.total_tiles) return;
-  const int bh = tile / p.nQb;
-  const int qb = CAUSAL ? p.nQb - 1 - tile % p.nQb : tile % p.nQb;   // heavy tiles first
   const int b = bh / p.H, h = bh % p.H;
   const size_t bhkv = (size_t)b * p.Hkv + h / (p.H / p.Hkv);
   // this sequence's lengths (the launch's N, Nk unless the batch is a variable-length one; slab
@@ -543,16 +556,17 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   //   C. starts the LDS reads of K^_{j+1} and the copy of block j+2 into block j-1's stage,
   //   R. rescales O if a running max moved (covers the latency of C's reads),
   //   X. exponentials, row sum and FP8 codes of block j, four keys at a time, with one score MFMA
-  //      of block j+1 issued in front of each piece; half way, the LDS reads of V^_j and of block
-  //      j+1's Delta-S row and scales are started,
+  //      of block j+1 issued in front of each piece; half way, the LDS reads of V^_j, of block j+1's scales
+  //      and of the first key tile's half of its Delta-S row are started - the latter straight into the score
+  //      registers that half of the exponentials has just finished with; the other half follows at the end,
   //   Y. the P~V MFMAs of block j, each followed by a piece of block j+1's dequantization, then
   //      block j+1's running-max update.
   // Past the wavefront's last block C, X and Y work on a stale stage (in bounds, results unused):
   // unconditional, so that no register stays live for the sake of a path not taken.
   qk_op ka[2 * NP];
   v4i va[2 * CT];
-  v4f dsr[2][4];
   KeyScales<GM> ks;
+  v16i raw[2], sc[2];                 // raw scores being produced / dequantized scores of block j
   auto read_k = [&](int stg) {
     read_k_block<D, INT4>(&lds[stg][0], lane, ka);
   };
@@ -563,17 +577,21 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   // With a scale per key in the 8-bit mode the block's 32 factors stay live through the exponentials (they are
   // fused into the exponent's argument), so the next block's 32 key scales are fetched after them, not half way.
   constexpr bool LATE_SCALES = GM == 2 && !INT4;
-  auto read_x = [&](int stg, bool ds_part = true, bool scale_part = true) {
-    const float* lx = reinterpret_cast<const float*>(&lds[stg][KCK + KC]);
+  // Delta-S of key tile kt of the block in stage stg, into the registers the tile's scores will be formed in
+  // (they are free once the previous block's exponentials of that tile are done)
+  auto read_ds = [&](int stg, int kt) {
     if constexpr (INT4) {
+      const v4f* dsv = reinterpret_cast<const v4f*>(reinterpret_cast<const float*>(&lds[stg][KCK + KC]) + 32 * kt + 16 * half);
 #pragma unroll
-      for (int kt = 0; ds_part && kt < 2; ++kt) {
-        const v4f* dsv = reinterpret_cast<const v4f*>(lx + 32 * kt + 16 * half);
+      for (int g = 0; g < 4; ++g) {
+        const v4f t4 = dsv[g];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) dsr[kt][g] = dsv[g];
+        for (int r = 0; r < 4; ++r) sc[kt][4 * g + r] = __float_as_int(t4[r]);
       }
     }
-    if (!scale_part) return;
+  };
+  auto read_scales = [&](int stg) {
+    const float* lx = reinterpret_cast<const float*>(&lds[stg][KCK + KC]);
     if constexpr (GM == 0) {
       ks.s[0] = lx[64 + half];
       ks.s[1] = lx[66 + half];
@@ -607,8 +625,9 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   }
   __syncthreads();
   read_k(0);
-  read_x(0);
-  v16i raw[2], sc[2];                 // raw scores being produced / dequantized scores of block j
+  read_ds(0, 0);
+  read_ds(0, 1);
+  read_scales(0);
   qk_tile<D, INT4>(ka, qreg, raw);    // block 0 holds a visible key for every query
   float alpha, m_sub = -INFINITY;     // of block j (m_sub: nothing summed yet)
   Factors<GM> fj;                     // block j's dequantization factors (used again by the fused exponent)
@@ -616,7 +635,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   constexpr int GPC = 8 / CT;         // dequantization groups per P~V MFMA
 
 #define SAGE_DEQ(MASKED_, GI_, KEY0_)                                                                \
-  dequant_group<INT4, CAUSAL, MASKED_, GM, (GI_) / 4, (GI_) % 4>(raw, sc, dsr, fn, half, KEY0_,          \
+  dequant_group<INT4, CAUSAL, MASKED_, GM, (GI_) / 4, (GI_) % 4>(raw, sc, fn, half, KEY0_,               \
                                                                  query + sq.coff, sq.nk)
 #define SAGE_DEQ_ALL(MASKED_, KEY0_)                                                                 \
   do {                                                                                               \
@@ -666,10 +685,12 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     float ls = 0.0f;                                                                                 \
     SAGE_X(0, MASKED_); SAGE_X(1, MASKED_); SAGE_X(2, MASKED_); SAGE_X(3, MASKED_);           /* X */ \
     read_v(cur);                                                                                     \
-    read_x(nx1, true, !LATE_SCALES);                                                                 \
+    read_ds(nx1, 0);                                                                                 \
+    if constexpr (!LATE_SCALES) read_scales(nx1);                                                    \
     __builtin_amdgcn_sched_barrier(0);                                                               \
     SAGE_X(4, MASKED_); SAGE_X(5, MASKED_); SAGE_X(6, MASKED_); SAGE_X(7, MASKED_);                  \
-    if constexpr (LATE_SCALES) read_x(nx1, false, true);                                             \
+    read_ds(nx1, 1);                                                                                 \
+    if constexpr (LATE_SCALES) read_scales(nx1);                                                     \
     st.l_run = __fmaf_rn(alpha, st.l_run, ls);                                                       \
     Factors<GM> fn;                                                                                  \
     fn.set(dq, p.kappa, ks);                                                                         \
