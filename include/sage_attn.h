@@ -24,7 +24,7 @@
  *     prefix sums live on the device and are not checked on the host: under a causal mask a
  *     sequence with fewer keys than queries is masked as if aligned to the first query and key,
  *     and a sequence without keys gets zeros.
- *   - d is 64 or 128; mode and dtype take the enum values below; H must be a multiple of H_kv.
+ *   - d is 64, 128 or 256; mode and dtype take the enum values below; H must be a multiple of H_kv.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream)
  *     and the call returns without synchronising.  Kernels of one call are ordered on that
  *     stream; two calls that share a workspace must be ordered by the caller.
@@ -47,7 +47,7 @@ extern "C" {
 enum {
   SAGE_OK = 0,
   SAGE_ERR_INVALID_ARG = -1,  /* null or misaligned pointer, non-positive size, H % H_kv != 0 */
-  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, unknown mode, dtype, flag, group map or layout, causal with N_kv < N,
+  SAGE_ERR_UNSUPPORTED = -2,  /* d not in {64,128,256}, unknown mode, dtype, flag, group map or layout, causal with N_kv < N,
                                  cu_seqlens without SAGE_LAYOUT_NHD, sage_attn_quant / sage_attn_debug_qk with cu_seqlens */
   SAGE_ERR_WORKSPACE = -3,    /* workspace missing or smaller than sage_attn_workspace_bytes() */
   SAGE_ERR_HIP = -4           /* a HIP call or launch failed (the HIP error is cleared) */
@@ -111,7 +111,7 @@ typedef struct sage_attn_args {
   const void* k;          /* device, [B, H_kv, N_kv, d] */
   const void* v;          /* device, [B, H_kv, N_kv, d] */
   void* out;              /* device, [B, H, N, d], written */
-  int B, H, H_kv, N, d;   /* d = 64 or 128; H a multiple of H_kv; N and N_kv <= 2^24; B * H <= 65535 */
+  int B, H, H_kv, N, d;   /* d = 64, 128 or 256; H a multiple of H_kv; N and N_kv <= 2^24; B * H <= 65535 */
   int causal;             /* 0: every key visible; 1: key t visible to query r iff t <= r + N_kv - N */
   float sm_scale;         /* <= 0 means 1/sqrt(d) */
   int mode;               /* SAGE_MODE_* */

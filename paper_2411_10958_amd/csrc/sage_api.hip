@@ -17,7 +17,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if (a->N > MAX_TOKENS || a->N_kv > MAX_TOKENS) return SAGE_ERR_UNSUPPORTED;
   const int Nk = a->N_kv > 0 ? a->N_kv : a->N;
   if (a->causal && Nk < a->N) return SAGE_ERR_UNSUPPORTED;
-  if (a->d != 64 && a->d != 128) return SAGE_ERR_UNSUPPORTED;
+  if (a->d != 64 && a->d != 128 && a->d != 256) return SAGE_ERR_UNSUPPORTED;
   if (a->mode != SAGE_MODE_INT4_FP8 && a->mode != SAGE_MODE_INT8_FP8) return SAGE_ERR_UNSUPPORTED;
   if (a->dtype != SAGE_DT_FP16 && a->dtype != SAGE_DT_BF16) return SAGE_ERR_UNSUPPORTED;
   if ((a->flags & ~(SAGE_FLAG_SMOOTH_V | SAGE_FLAG_NO_SMOOTH_K | SAGE_FLAG_NO_SMOOTH_Q | SAGE_FLAG_FP32_DELTA_S)) != 0) return SAGE_ERR_UNSUPPORTED;

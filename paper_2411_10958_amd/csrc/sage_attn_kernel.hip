@@ -386,8 +386,11 @@ __device__ __forceinline__ size_t lse_index(const AttnParams& p, const Seq& sq, 
   return ((size_t)b * p.H + h) * p.N + r;
 }
 
+// d = 256: the cross-block accumulator O alone is 128 registers per lane, so a workgroup takes a CU's whole register
+// file (one wavefront per SIMD, 512 registers each: the accumulators of the matrix instructions live in the second
+// half) and its three LDS stages are 88 KB.
 template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, int PVF>
-__global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const AttnParams p) {
+__global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_attn_fwd(const AttnParams p) {
   constexpr int KSC = GM == 0 ? 4 : (GM == 1 ? 16 : 64);    // key scales per block
   constexpr int QG = GM == 0 ? QGROUP : 1;                  // queries per scale
   constexpr int CT = D / 32;          // 32-channel tiles of the output
@@ -478,11 +481,8 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   // Every wavefront issues at least MINC copies per block, in block order, and loads complete in
   // order: "at most MINC outstanding" therefore means every block but the newest has landed.
   auto wait_all_but_newest = [&]() {
-    static_assert(MINC >= 1 && MINC <= 4, "copy count per block");
-    if constexpr (MINC == 4) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
-    else if constexpr (MINC == 3) asm volatile("s_waitcnt vmcnt(3) lgkmcnt(0)" ::: "memory");
-    else if constexpr (MINC == 2) asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)" ::: "memory");
+    static_assert(MINC >= 1 && MINC <= 8, "copy count per block");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(MINC) : "memory");
   };
   auto wait_all = [&]() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); };
 
@@ -632,7 +632,9 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   float alpha, m_sub = -INFINITY;     // of block j (m_sub: nothing summed yet)
   Factors<GM> fj;                     // block j's dequantization factors (used again by the fused exponent)
   constexpr int NQK = qk_steps<D, INT4>();
-  constexpr int GPC = 8 / CT;         // dequantization groups per P~V MFMA
+  constexpr int QPX = NQK > 8 ? 2 : 1;   // score MFMAs issued in front of each of the 8 pieces of the exponentials
+  static_assert(NQK <= 16, "score MFMAs per block");
+  constexpr int GPC = CT >= 8 ? 1 : 8 / CT;   // dequantization groups per P~V MFMA
 
 #define SAGE_DEQ(MASKED_, GI_, KEY0_)                                                                \
   dequant_group<INT4, CAUSAL, MASKED_, GM, (GI_) / 4, (GI_) % 4>(raw, sc, fn, half, KEY0_,               \
@@ -654,7 +656,12 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   int cur = 0;   // stage of block j
 #define SAGE_X(GI_, MASKED_)                                                                         \
   do {                                                                                               \
-    if constexpr ((GI_) < NQK) qk_step<D, INT4, (GI_) < NQK ? (GI_) : 0>(ka, qreg, raw);             \
+    if constexpr (QPX == 2) {                                                                        \
+      qk_step<D, INT4, 2 * (GI_) < NQK ? 2 * (GI_) : 0>(ka, qreg, raw);                               \
+      qk_step<D, INT4, 2 * (GI_) + 1 < NQK ? 2 * (GI_) + 1 : 0>(ka, qreg, raw);                       \
+    } else if constexpr ((GI_) < NQK) {                                                              \
+      qk_step<D, INT4, (GI_) < NQK ? (GI_) : 0>(ka, qreg, raw);                                      \
+    }                                                                                                \
     exp_group<INT4, MASKED_, GM, PVF, (GI_) / 4, (GI_) % 4>(sc, fj, m_sub, pb, ls);                  \
     __builtin_amdgcn_sched_barrier(0);                                                               \
   } while (0)
@@ -662,8 +669,8 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
   do {                                                                                               \
     if constexpr ((CT_) < CT) {                                                                      \
       pv_step<D, (CT_) < CT ? (CT_) : 0, PVF>(st, va, pb);                                           \
-      SAGE_DEQ(MASKED_, (CT_) * GPC, (j + 1) * BKV);                                                 \
-      SAGE_DEQ(MASKED_, (CT_) * GPC + 1, (j + 1) * BKV);                                             \
+      SAGE_DEQ(MASKED_, ((CT_) * GPC) % 8, (j + 1) * BKV);                                           \
+      if constexpr (GPC >= 2) SAGE_DEQ(MASKED_, ((CT_) * GPC + 1) % 8, (j + 1) * BKV);               \
       if constexpr (GPC == 4) {                                                                      \
         SAGE_DEQ(MASKED_, ((CT_) * GPC + 2) % 8, (j + 1) * BKV);                                     \
         SAGE_DEQ(MASKED_, ((CT_) * GPC + 3) % 8, (j + 1) * BKV);                                     \
@@ -695,6 +702,7 @@ __global__ void __launch_bounds__(256, SAGE_WAVES_PER_SIMD) k_attn_fwd(const Att
     Factors<GM> fn;                                                                                  \
     fn.set(dq, p.kappa, ks);                                                                         \
     SAGE_Y(0, MASKED_NEXT_); SAGE_Y(1, MASKED_NEXT_); SAGE_Y(2, MASKED_NEXT_); SAGE_Y(3, MASKED_NEXT_); /* Y */ \
+    SAGE_Y(4, MASKED_NEXT_); SAGE_Y(5, MASKED_NEXT_); SAGE_Y(6, MASKED_NEXT_); SAGE_Y(7, MASKED_NEXT_);         \
     alpha = update_max<D, INT4, GM, PVF>(st, sc, fn, m_sub);                                              \
     fj = fn;                                                                                         \
     cur = nx1;                                                                                       \
@@ -832,8 +840,9 @@ hipError_t launch_attention(const Dims& D, const Ptrs& P, hipStream_t s) {
 #define SAGE_ATT(DD, I4, CA, BF) return launch_attention_t<DD, I4, CA, BF>(D, P, s)
 #define SAGE_ATT_BF(DD, I4, CA) do { if (D.bf16) SAGE_ATT(DD, I4, CA, true); else SAGE_ATT(DD, I4, CA, false); } while (0)
 #define SAGE_ATT_CA(DD, I4) do { if (D.causal) SAGE_ATT_BF(DD, I4, true); else SAGE_ATT_BF(DD, I4, false); } while (0)
-  if (D.d == 128) { if (D.int4) SAGE_ATT_CA(128, true); else SAGE_ATT_CA(128, false); }
-  else            { if (D.int4) SAGE_ATT_CA(64, true); else SAGE_ATT_CA(64, false); }
+  if (D.d == 256)      { if (D.int4) SAGE_ATT_CA(256, true); else SAGE_ATT_CA(256, false); }
+  else if (D.d == 128) { if (D.int4) SAGE_ATT_CA(128, true); else SAGE_ATT_CA(128, false); }
+  else                 { if (D.int4) SAGE_ATT_CA(64, true); else SAGE_ATT_CA(64, false); }
 #undef SAGE_ATT_CA
 #undef SAGE_ATT_BF
 #undef SAGE_ATT
@@ -845,7 +854,10 @@ hipError_t launch_debug_qk(const Dims& D, const Ptrs& P, int b, int h, int q_til
   const size_t bhkv = (size_t)b * D.Hkv + h / (D.H / D.Hkv);
   const int8_t* qc = P.q_codes + bh * (size_t)D.nQb * q_slab_bytes(D.d, D.int4);
   const int8_t* kc = P.k_codes + bhkv * (size_t)D.nKb * k_block_bytes(D.d, D.int4);
-  if (D.d == 128) {
+  if (D.d == 256) {
+    if (D.int4) k_debug_qk<256, true><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
+    else k_debug_qk<256, false><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
+  } else if (D.d == 128) {
     if (D.int4) k_debug_qk<128, true><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
     else k_debug_qk<128, false><<<1, 256, 0, s>>>(qc, kc, q_tile, kv_block, out);
   } else {

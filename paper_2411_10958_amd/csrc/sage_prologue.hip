@@ -398,9 +398,11 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
   constexpr int CPL = D / 4, CPC = CPL / 8;                      // quantization map: 2 rows x CPL channels
   constexpr int QMAX = 7;
   constexpr int SLAB = (int)q_slab_bytes(D, true);
-  static_assert(SLAB <= (int)sizeof(double) * NRG * D, "the code image reuses the column-sum buffer");
+  constexpr int SUMS = (int)sizeof(double) * NRG * D;
   __shared__ uint4 s_raw[BQ * NCG];
-  __shared__ double s_sum[NRG][D];
+  // the column sums, and later (everyone past them) the packed code image of the slab
+  __shared__ __align__(16) unsigned char s_buf[SLAB > SUMS ? SLAB : SUMS];
+  double (*s_sum)[D] = reinterpret_cast<double (*)[D]>(s_buf);
   __shared__ __align__(16) float s_mean[D];
   __shared__ float s_bmax[4];
   const int t = threadIdx.x;
@@ -412,7 +414,7 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
   const int valid = min(BQ, sq.n - n0);
   if (valid <= 0) return;                     // a block past the end of a shorter sequence
   const size_t hbase = hp.base + sq.q0 * (size_t)qm.sn;
-  auto swz = [](int r) { return (r >> 1) & (D == 128 ? 3 : 1); };
+  auto swz = [](int r) { return (r >> 1) & (D >= 128 ? 3 : 1); };
   {
     const int cg = t % NCG, rg = t / NCG;
     double cs[8];
@@ -488,7 +490,10 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
     __syncthreads();
     mxr[0] = mxr[1] = fmaxf(fmaxf(s_bmax[0], s_bmax[1]), fmaxf(s_bmax[2], s_bmax[3]));
   }
-  uint8_t* img = reinterpret_cast<uint8_t*>(&s_sum[0][0]);   // everyone is past the column sums
+  uint8_t* img = s_buf;                  // everyone is past the column sums
+  // the thread's CPL channels of a query are one MFMA lane payload of 32 codes (d = 128), half of one (d = 64) or
+  // two of them (d = 256: both lane halves of one operand)
+  constexpr int NPL = CPL > 32 ? CPL / 32 : 1, CPP = CPL / NPL;     // payloads per query and thread, codes in each
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const float delta = head_scale ? head_scale[bh] : __fdiv_rn(mxr[i], (float)QMAX);
@@ -496,19 +501,22 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
       q_scale[(bh * nQb + qb) * (BQ >> (qg - 1)) + ((2 * pair + i) >> (qg - 1))] = delta;
     if (stats_only) continue;            // per-tensor scales, first pass: only the block maxima are wanted
     const QuantScale qs = quant_scale<QMAX>(delta);
-    Codes32 cd;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) { cd.ev[e] = 0.0f; cd.od[e] = 0.0f; }
+    for (int pl = 0; pl < NPL; ++pl) {
+      Codes32 cd;
 #pragma unroll
-    for (int g = 0; g < CPC; ++g)
-      quant_group<8, QMAX>(&x[i][8 * g], delta, qs, [&](int e, float c) { cd.set(8 * g + e, c); });
-    const v6u pw = cd.pack();
-    int lane_m, e0;
-    const size_t op = q_op6(2 * pair + i, CPL * c4, D, &lane_m, &e0);
-    const int d0 = (6 * e0) >> 5;
+      for (int e = 0; e < 16; ++e) { cd.ev[e] = 0.0f; cd.od[e] = 0.0f; }
 #pragma unroll
-    for (int k = 0; k < CPL * 6 / 32; ++k)
-      *reinterpret_cast<unsigned*>(img + op + op6_byte(lane_m, 4 * (d0 + k))) = pw[k];
+      for (int g = 0; g < CPP / 8; ++g)
+        quant_group<8, QMAX>(&x[i][CPP * pl + 8 * g], delta, qs, [&](int e, float c) { cd.set(8 * g + e, c); });
+      const v6u pw = cd.pack();
+      int lane_m, e0;
+      const size_t op = q_op6(2 * pair + i, CPL * c4 + CPP * pl, D, &lane_m, &e0);
+      const int d0 = (6 * e0) >> 5;
+#pragma unroll
+      for (int k = 0; k < CPP * 6 / 32; ++k)
+        *reinterpret_cast<unsigned*>(img + op + op6_byte(lane_m, 4 * (d0 + k))) = pw[k];
+    }
   }
   if (stats_only) return;
   __syncthreads();
@@ -542,7 +550,7 @@ typedef double v4d __attribute__((ext_vector_type(4)));
 constexpr int DS_QROWS = 32;    // query-block means staged in LDS per pass: two 16-row MFMA tiles
 
 template <bool BF16, bool INT4, int D, bool DS32 = false>
-__global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __restrict__ K,
+__global__ void __launch_bounds__(256, D == 256 ? 2 : 4) k_quant_k(const unsigned short* __restrict__ K,
                                                  const float* __restrict__ k_mean,
                                                  float* __restrict__ k_scale, int8_t* __restrict__ k_codes,
                                                  const float* __restrict__ q_mean,
@@ -555,7 +563,8 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
   constexpr int QMAX = INT4 ? 7 : 127;
   // LDS row of staged block means: channel c sits at column c + 16*(c / 32) when D = 128, so the
   // 32 lanes of a half-wavefront (16 rows x 2 channel groups) hit 32 different banks (odd stride)
-  constexpr int SQW = D + (D == 128 ? 48 : 0) + 1;
+  constexpr int SQW = D + (D >= 128 ? 48 : 0) + 1;
+  constexpr int PADSH = D == 256 ? 6 : 5;          // 16 columns of padding after every 32 (d = 128) / 64 (d = 256) channels
   __shared__ uint4 s_codes[BKV * D / 16];          // the block's packed image
   __shared__ float s_q[INT4 ? DS_QROWS : 1][SQW];
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
@@ -597,7 +606,7 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
 #pragma unroll
     for (int k = 0; k < QPT; ++k) {
       const int idx = t + k * 256, rr = idx / (D / 4), c4 = idx % (D / 4);
-      const int col = 4 * c4 + (D == 128 ? 16 * (c4 >> 3) : 0);
+      const int col = 4 * c4 + (D >= 128 ? 16 * ((4 * c4) >> PADSH) : 0);
       s_q[rr][col + 0] = qpre[k].x; s_q[rr][col + 1] = qpre[k].y;
       s_q[rr][col + 2] = qpre[k].z; s_q[rr][col + 3] = qpre[k].w;
     }
@@ -651,20 +660,24 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
   const QuantScale qs = quant_scale<QMAX>(delta);
   if constexpr (INT4) {
     // the lane's CPL codes are CPL*6/32 consecutive dwords of one MFMA lane's payload (all 6 of
-    // them when d = 128; dwords 0..2 or 3..5 when d = 64)
-    Codes32 cd;
+    // them when d = 128; dwords 0..2 or 3..5 when d = 64), or two whole payloads (d = 256)
+    constexpr int NPL = CPL > 32 ? CPL / 32 : 1, CPP = CPL / NPL;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) { cd.ev[e] = 0.0f; cd.od[e] = 0.0f; }
+    for (int pl = 0; pl < NPL; ++pl) {
+      Codes32 cd;
 #pragma unroll
-    for (int g = 0; g < CPL / 8; ++g)
-      quant_group<8, QMAX>(x + 8 * g, delta, qs, [&](int e, float c) { cd.set(8 * g + e, c); });
-    const v6u pw = cd.pack();
-    int lane_m, e0;
-    const size_t op = k_op6(r, c0, D, &lane_m, &e0);
-    const int d0 = (6 * e0) >> 5;
+      for (int e = 0; e < 16; ++e) { cd.ev[e] = 0.0f; cd.od[e] = 0.0f; }
 #pragma unroll
-    for (int i = 0; i < CPL * 6 / 32; ++i)
-      *reinterpret_cast<unsigned*>(img + op + op6_byte(lane_m, 4 * (d0 + i))) = pw[i];
+      for (int g = 0; g < CPP / 8; ++g)
+        quant_group<8, QMAX>(x + CPP * pl + 8 * g, delta, qs, [&](int e, float c) { cd.set(8 * g + e, c); });
+      const v6u pw = cd.pack();
+      int lane_m, e0;
+      const size_t op = k_op6(r, c0 + CPP * pl, D, &lane_m, &e0);
+      const int d0 = (6 * e0) >> 5;
+#pragma unroll
+      for (int i = 0; i < CPP * 6 / 32; ++i)
+        *reinterpret_cast<unsigned*>(img + op + op6_byte(lane_m, 4 * (d0 + i))) = pw[i];
+    }
   } else {
 #pragma unroll
     for (int p = 0; p < CPL / 8; ++p) {
@@ -686,7 +699,7 @@ __global__ void __launch_bounds__(256, 4) k_quant_k(const unsigned short* __rest
     // pass (a few percent of the pass's MFMA time) instead of 2 CPL more live registers, which is
     // what lets four workgroups share a CU
     const double kap = (double)kappa;
-    const int qcol = c0 + (D == 128 ? 16 * k4 : 0);
+    const int qcol = c0 + (D >= 128 ? 16 * k4 : 0);
     for (int p = p_first; p < npass; p = next_pass(p)) {
       if (p > p_first) __syncthreads();            // everyone is done with the previous pass's rows
       store_q();
@@ -971,7 +984,10 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
 
 hipError_t launch_prologue(const Dims& D, const Ptrs& P, hipStream_t s) {
 #define SAGE_PRO(BF, I4, DD) return launch_prologue_t<BF, I4, DD>(D, P, s)
-  if (D.d == 128) {
+  if (D.d == 256) {
+    if (D.bf16) { if (D.int4) SAGE_PRO(true, true, 256); else SAGE_PRO(true, false, 256); }
+    else        { if (D.int4) SAGE_PRO(false, true, 256); else SAGE_PRO(false, false, 256); }
+  } else if (D.d == 128) {
     if (D.bf16) { if (D.int4) SAGE_PRO(true, true, 128); else SAGE_PRO(true, false, 128); }
     else        { if (D.int4) SAGE_PRO(false, true, 128); else SAGE_PRO(false, false, 128); }
   } else {
@@ -982,8 +998,9 @@ hipError_t launch_prologue(const Dims& D, const Ptrs& P, hipStream_t s) {
 }
 
 hipError_t launch_kv_stats(const Dims& D, const Ptrs& P, hipStream_t s) {
-  if (D.d == 128) { if (D.bf16) launch_stats_t<true, 128>(D, P, s); else launch_stats_t<false, 128>(D, P, s); }
-  else            { if (D.bf16) launch_stats_t<true, 64>(D, P, s); else launch_stats_t<false, 64>(D, P, s); }
+  if (D.d == 256)      { if (D.bf16) launch_stats_t<true, 256>(D, P, s); else launch_stats_t<false, 256>(D, P, s); }
+  else if (D.d == 128) { if (D.bf16) launch_stats_t<true, 128>(D, P, s); else launch_stats_t<false, 128>(D, P, s); }
+  else                 { if (D.bf16) launch_stats_t<true, 64>(D, P, s); else launch_stats_t<false, 64>(D, P, s); }
   return hipGetLastError();
 }
 

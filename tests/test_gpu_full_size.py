@@ -22,6 +22,7 @@ PLAN = {
     "causal32k": ([(0, 30), (0, 7)], 4),
     "video17k": ([(0, 0), (1, 47), (1, 20)], 6),
     "long128k": ([(0, 2), (0, 29), (0, 12)], 3),
+    "causal8k_d256": ([(0, 3), (0, 15)], 5),
 }
 
 

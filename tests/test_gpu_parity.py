@@ -47,6 +47,8 @@ CASES = [
     (640, 128, "bf16", 4, 2, False),    # several Q blocks and 10 KV blocks
     (1, 64, "bf16", 1, 1, True),        # degenerate: a single token
     (17, 128, "fp16", 1, 1, False),     # shorter than one group-of-16 plus one
+    (300, 256, "bf16", 2, 1, True),     # head dimension 256: ragged + causal + grouped KV heads
+    (256, 256, "fp16", 2, 2, False),
 ]
 
 
