@@ -73,6 +73,7 @@ def cpu_baseline(spec, mode, n_heads, oracle_kw):
     the sample scaled accordingly.  Must run before this process touches the GPU (it forks)."""
     import multiprocessing as mp
     import numpy as np
+    import workloads as wl
     cores = max(1, min(int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1), os.cpu_count() or 1, 16))
     nqb = (spec.N + 127) // 128
     blocks, rows = None, None
@@ -88,7 +89,7 @@ def cpu_baseline(spec, mode, n_heads, oracle_kw):
         each = pool.map(_oracle_job, jobs, chunksize=1)
         wall = time.perf_counter() - t0
     if rows is None:
-        ops_head = 4.0 * float(spec.N) * spec.kv_len * spec.d / (2 if spec.causal else 1)
+        ops_head = wl.flops(spec) / (spec.B * spec.H)
     else:       # keys a sampled row sees: all of them, or (causal) those up to itself
         seen = (rows + 1 + (spec.kv_len - spec.N)).astype(np.float64) if spec.causal else np.full(len(rows), float(spec.kv_len))
         ops_head = 4.0 * float(seen.sum()) * spec.d
@@ -244,6 +245,7 @@ def main():
 
     peak_mix = mix_peak(args.mode, args.pv_format)
     alu = alu_ceiling_tops(spec.d)
+    splits = pa.sage_attn_kv_splits(a)
     res = {
         "metric": "quantized attention TOPS at d=128 (causal + non-causal), cos-sim vs FP32",
         "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -255,7 +257,7 @@ def main():
                                f"{spec.dtype} causal={spec.causal}", "mode": args.mode, "smooth_v": bool(args.smooth_v),
                    "smooth_k": not args.no_smooth_k, "smooth_q": not args.no_smooth_q and args.mode == "int4_fp8",
                    "fp32_delta_s": bool(args.fp32_delta_s), "given_kv_stats": bool(args.given_kv_stats),
-                   "group_map": args.group_map, "pv_format": args.pv_format,
+                   "group_map": args.group_map, "pv_format": args.pv_format, "kv_splits": splits,
                    "ops_formula": "4*B*H*N^2*d" + ("/2" if spec.causal else "")},
         "breakdown_ms": {"prologue": round(ms_pro, 4), "attention_kernel": round(ms_core, 4)},
         # The attention kernel is a dense contraction whose vector work (the softmax between its two products) takes
@@ -272,6 +274,16 @@ def main():
                                                            "command; quoted, not measured in this run)" if traffic else None,
                      "algorithmic_bytes": alg_bytes, "ops_per_launch": ops},
     }
+
+    if spec.N <= 128 and spec.kv_len >= 64 * spec.N:
+        # decode-shaped: a few queries per sequence against a long cache.  The attention kernel then reads every code of
+        # K and V once per KV head (query heads of a group find them in the caches) and does next to no arithmetic per
+        # byte: its bound is HBM bandwidth, and its figure is bytes per second.
+        kv_bytes = int(BHkv * spec.kv_len * spec.d * (qk_code_bytes + 1.0)) + ds_bytes + 4 * BHkv * spec.kv_len // kg
+        res["roofline"] = {"bound": "hbm", "kernel": "k_attn_fwd (key range split) + k_merge_splits",
+                           "achieved": round(kv_bytes / (ms_core * 1e-3) / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
+                           "frac": round(kv_bytes / (ms_core * 1e-3) / 1e9 / 8000.0, 4), "traffic": None,
+                           "algorithmic_bytes": kv_bytes, "ops_per_launch": ops}
 
     # accuracy of what was just computed, on sampled heads (outside the timed region): the comparison the GPU tests make
     torch.cuda.synchronize()
@@ -291,7 +303,7 @@ def main():
             qh, kh, vh = data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g]
             pro = so.quantize_head(qh, kh, vh, mode=args.mode, ds_blocks=blocks, **oracle_kw)
             got = wl.from_torch(out[b, h])
-            chk.add_head(got, pro, spec.causal, blocks=blocks)
+            chk.add_head(got, pro, spec.causal, blocks=blocks, splits=splits)
             got_rows.append(got[rows[sub]])
             full_rows.append(so.ref_attn_fp64(qh, kh, vh, spec.causal, rows=rows[sub]))
         import contextlib

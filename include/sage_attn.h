@@ -20,7 +20,8 @@
  *     SAGE_LAYOUT_NHD), sequence b owns query tokens cu_seqlens_q[b] .. cu_seqlens_q[b+1]-1 and
  *     key tokens cu_seqlens_k[b] .. cu_seqlens_k[b+1]-1, and N / N_kv are the LONGEST query / key
  *     length (they size the launch and the workspace; a longer sequence is cut to them).  Every
- *     sequence is smoothed, quantized and attended on its own, exactly as a batch of one.  The
+ *     sequence is smoothed, quantized and attended on its own, exactly as a batch of one (bit for bit when
+ *     kv_splits is the same in both calls: left to the library it depends on the call's tile count).  The
  *     prefix sums live on the device and are not checked on the host: under a causal mask a
  *     sequence with fewer keys than queries is masked as if aligned to the first query and key,
  *     and a sequence without keys gets zeros.
@@ -141,11 +142,29 @@ typedef struct sage_attn_args {
                               SAGE_FLAG_NO_SMOOTH_K.  sage_attn_kv_stats computes exactly these two arrays. */
   const float* v_scale_in; /* device, [B, H_kv, d] f32, or NULL: fl32(max over tokens |V[., c]| / 448) (Sec. 3.3; / 57344 for
                               SAGE_PV_E5M2, / 127 for SAGE_PV_INT8) */
+  int kv_splits;           /* Workgroups per 128-query tile in the attention kernel, each walking its own chunk of the key
+                              blocks and leaving (m, l, O) under its own running maximum; a second kernel merges the
+                              chunks by the rule that combines consecutive blocks in Eq. 1 (Sec. 2.1).  For calls with
+                              few query tiles and many keys - a decode step, a short chunk of queries against a long
+                              cache - where one workgroup per tile would leave most of the chip idle.  0: the library
+                              decides (it splits when there are fewer than 256 tiles; sage_attn_kv_splits tells);
+                              1: never; 2..64: this many (cut to one chunk per 8 key blocks at most).  Default groups
+                              (SAGE_GROUPS_LANE, _BLOCK, _TENSOR) and SAGE_PV_E4M3 only, else 1.
+                              Chunks of a tile: with nblk its key blocks (those up to its last query's last visible key
+                              under a causal mask), n_vis the leading ones in which its FIRST query sees a key (all of
+                              them without a mask) and C = ceil(n_vis / S), chunk s covers blocks [s C, (s + 1) C), the
+                              last non-empty one runs on to nblk.  The result is Algorithm 1 on every chunk, merged; it
+                              differs from the unsplit result where the 8-bit codes of P~ depend on the running
+                              maximum, not beyond the accuracy of either. */
 } sage_attn_args;
 
-/* Bytes of device scratch one call needs for these shapes (codes, scales, means, Delta-S).
-   Depends only on B, H, H_kv, N, d, mode.  Returns 0 if those are invalid. */
+/* Bytes of device scratch one call needs for these shapes (codes, scales, means, Delta-S, partial results of a
+   split key range).  Depends on the shapes, mode, options and kv_splits, not on pointers.  Returns 0 if those are invalid. */
 size_t sage_attn_workspace_bytes(const sage_attn_args* args);
+
+/* The number of key chunks per query tile sage_attn_fwd_ex / sage_attn_core will use for these arguments (see
+   kv_splits); 0 if the arguments are invalid. */
+int sage_attn_kv_splits(const sage_attn_args* args);
 
 /* The whole forward pass of Algorithm 1: preprocessing (smoothing, Delta-S, quantization;
    Sec. 3.1-3.3) followed by the fused attention kernel (inner loop and epilogue). */

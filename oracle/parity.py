@@ -100,12 +100,31 @@ class OutputCheck:
         self.dot = self.gg = self.rr = 0.0
         self.unexplained = []
 
+    @staticmethod
+    def _eval(form, pro, rows, causal, bkv, chunks, p_codes=None):
+        """Either form of the oracle on `rows`, the key range walked in one piece or in `chunks` merged by
+        `merge_key_chunks`.  Returns (FP32 output, state, codes, E or None)."""
+        fn = so.FORMS[form]
+        extra = dict(return_e=True) if form == "kernel" else dict(p_codes=p_codes)
+        if chunks is None:
+            r = fn(pro, rows, causal, bkv, "fp32", return_state=True, return_codes=True, **extra)
+            return r if form == "kernel" else r + (None,)
+        parts = [fn(pro, rows, causal, bkv, "fp32", return_state=True, return_codes=True, blocks=c, **extra) for c in chunks]
+        out, st = so.merge_key_chunks(pro, [p[1] for p in parts], form, "fp32")
+        codes = parts[0][2].copy()
+        E = parts[0][3].copy() if form == "kernel" else None
+        for c, p in zip(chunks[1:], parts[1:]):              # every chunk filled its own columns
+            codes[:, c[0] * bkv:] = p[2][:, c[0] * bkv:]
+            if E is not None:
+                E[:, c[0] * bkv:] = p[3][:, c[0] * bkv:]
+        return out, st, codes, E
+
     # ---- one block of rows inside one smoothing block of one head
-    def add(self, got16, pro, rows, causal, bkv=so.BKV_ACC):
+    def add(self, got16, pro, rows, causal, bkv=so.BKV_ACC, chunks=None):
+        """chunks: the key chunks [(j0, j1), ...] the kernel split this tile's key range into (None: one piece)."""
         got = np.asarray(got16, np.float64)
-        ref_p, st_p, codes_p = so.attention_rows(pro, rows, causal, bkv, "fp32", return_state=True, return_codes=True)
-        ref_k, st_k, codes_k, E_k = so.attention_rows_kernel_order(pro, rows, causal, bkv, "fp32", return_state=True,
-                                                                  return_codes=True, return_e=True)
+        ref_p, st_p, codes_p, _ = self._eval("printed", pro, rows, causal, bkv, chunks)
+        ref_k, st_k, codes_k, E_k = self._eval("kernel", pro, rows, causal, bkv, chunks)
         assert np.isfinite(got).all(), f"{self.label}: non-finite output"
         ref_p64, ref_k64 = ref_p.astype(np.float64), ref_k.astype(np.float64)
         m = st_p["m"]
@@ -132,11 +151,11 @@ class OutputCheck:
         for i in np.nonzero(bad_a | bad_b)[0]:
             why = "unquantized P~: no codes to explain a difference with" if pv_exact else \
                 self._explain(got[i], pro, int(ridx[i]), causal, bkv, codes_p[i], codes_k[i], E_k[i], float(m[i]),
-                              beyond_b=bool(bad_b[i]))
+                              beyond_b=bool(bad_b[i]), chunks=chunks)
             if why is not None:
                 self.unexplained.append(f"row {int(ridx[i])}: {why} (excess A {ex_a[i]:.3e}, B {ex_b[i]:.3e})")
 
-    def _explain(self, got, pro, r, causal, bkv, cp, ck, Ek, m, beyond_b):
+    def _explain(self, got, pro, r, causal, bkv, cp, ck, Ek, m, beyond_b, chunks=None):
         """None if the row is explained, else the reason it is not."""
         step = ck.view(np.int8).astype(int) - cp.view(np.int8).astype(int) if pro["pv_fmt"] == "int8" \
             else ck.astype(int) - cp.astype(int)
@@ -145,7 +164,7 @@ class OutputCheck:
         mm = np.array([m], np.float32)
 
         def agrees(codes, tol):
-            sub = so.attention_rows(pro, np.array([r]), causal, bkv, "fp32", p_codes=codes[None, :]).astype(np.float64)
+            sub = self._eval("printed", pro, np.array([r]), causal, bkv, chunks, p_codes=codes[None, :])[0].astype(np.float64)
             return bool((np.abs(got[None, :] - sub) <= _allowed(sub, tol, mm, self.dtype, pro.get("vbar"))).all())
 
         if not beyond_b:
@@ -169,12 +188,14 @@ class OutputCheck:
         return f"no one or two of the {len(cand)} near-boundary codes account for it"
 
     # ---- conveniences
-    def add_head(self, got_head, pro, causal, blocks=None, bkv=so.BKV_ACC):
-        """got_head: [N, d] of one (batch, head); blocks: smoothing blocks to compare (default all)."""
+    def add_head(self, got_head, pro, causal, blocks=None, bkv=so.BKV_ACC, splits=1):
+        """got_head: [N, d] of one (batch, head); blocks: smoothing blocks to compare (default all); splits: key
+        chunks per query tile the kernel used (sage_attn_kv_splits)."""
         N, bq = pro["N"], pro["bq"]
         for i in (range((N + bq - 1) // bq) if blocks is None else blocks):
             rows = slice(i * bq, min((i + 1) * bq, N))
-            self.add(got_head[rows], pro, rows, causal, bkv)
+            chunks = so.key_chunks(pro, i * bq, i * bq + bq - 1, causal, splits, bkv) if splits > 1 else None
+            self.add(got_head[rows], pro, rows, causal, bkv, chunks)
 
     def finish(self):
         cos = self.dot / np.sqrt(self.gg * self.rr) if self.gg > 0 and self.rr > 0 else 1.0
@@ -188,7 +209,7 @@ class OutputCheck:
         return cos
 
 
-def check_heads(got, data, causal, mode, dtype, label="", want_lse=False, **oracle_kw):
+def check_heads(got, data, causal, mode, dtype, label="", want_lse=False, splits=1, **oracle_kw):
     """got: [B, H, N, d] (float32 values of the 16-bit outputs); data: dict with q [B, H, N, d], k, v [B, H_kv, N_kv, d].
     Every head goes through `quantize_head(**oracle_kw)` and every smoothing block through OutputCheck.  Returns
     the per-head oracle records, pros[b][h] (with "lse" of the printed form when want_lse)."""
@@ -200,13 +221,14 @@ def check_heads(got, data, causal, mode, dtype, label="", want_lse=False, **orac
         pros.append([])
         for h in range(H):
             pro = so.quantize_head(data["q"][b, h], data["k"][b, h // g], data["v"][b, h // g], mode=mode, **oracle_kw)
-            chk.add_head(got[b, h], pro, causal)
+            chk.add_head(got[b, h], pro, causal, splits=splits)
             if want_lse:
                 N, bq = pro["N"], pro["bq"]
                 lse = np.zeros(N, np.float32)
                 for i in range((N + bq - 1) // bq):
                     rows = slice(i * bq, min((i + 1) * bq, N))
-                    _, st = so.attention_rows(pro, rows, causal, out_dtype="fp32", return_state=True)
+                    chunks = so.key_chunks(pro, i * bq, i * bq + bq - 1, causal, splits) if splits > 1 else None
+                    st = OutputCheck._eval("printed", pro, rows, causal, so.BKV_ACC, chunks)[1]
                     lse[rows] = so.row_lse(pro, rows, st)
                 pro["lse"] = lse
             pros[-1].append(pro)

@@ -368,7 +368,7 @@ def _epilogue(pro, O, l, fmax, out_dtype):
 
 
 def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_state=False, p_codes=None,
-                   return_codes=False):
+                   return_codes=False, blocks=None):
     """THE ORACLE OF RECORD for the inner loop + epilogue of Algorithm 1, evaluated in the order the
     algorithm prints its lines, every line rounded once to FP32:
 
@@ -385,6 +385,8 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
     `quantize_head`.  Returns the [len(rows), d] output rounded to out_dtype (as float32).  With N_kv != N
     a causal mask is aligned to the last query and key: query r sees keys t <= r + (N_kv - N).
 
+    blocks: optional (j0, j1): walk only the key blocks j0 <= j < j1 (a chunk of a split key range; the state
+    returned is then that chunk's, see `merge_key_chunks`).
     p_codes: optional uint8 / int8 array [len(rows), n_blocks * bkv]: 8-bit codes to use for P^ INSTEAD of
     the ones this function would compute (everything else - m, P~, l - as printed).  It exists so that a test
     can show that a deviating result is explained by nothing but the codes of P^ (a floating-point value
@@ -399,7 +401,7 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
     l = np.zeros(nr, f32)
     O = np.zeros((nr, d), f32)
     codes = np.zeros((nr, n_blocks * bkv), np.uint8)
-    for j in range(n_blocks):
+    for j in range(n_blocks) if blocks is None else range(blocks[0], min(blocks[1], n_blocks)):
         ks, _, S = _block_scores(pro, rows, blk, coff, causal, j, bkv)
         m_new = np.maximum(m, S.max(axis=1))
         with np.errstate(invalid="ignore"):
@@ -428,7 +430,7 @@ def attention_rows(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_stat
 
 
 def attention_rows_kernel_order(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16", return_state=False,
-                                return_codes=False, return_e=False):
+                                return_codes=False, return_e=False, blocks=None):
     """NOT the oracle of record: the same inner loop with the FP32 roundings placed where the gfx950 kernel
     places them.  Mathematically it is Algorithm 1 line for line; it differs from `attention_rows` in three
     rounding decisions, each of which tests/test_oracle_pins.py compares with the printed form:
@@ -457,7 +459,7 @@ def attention_rows_kernel_order(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16"
     O = np.zeros((nr, d), f32)
     codes = np.zeros((nr, n_blocks * bkv), np.uint8)
     Eall = np.zeros((nr, n_blocks * bkv), f32)
-    for j in range(n_blocks):
+    for j in range(n_blocks) if blocks is None else range(blocks[0], min(blocks[1], n_blocks)):
         ks, s, S = _block_scores(pro, rows, blk, coff, causal, j, bkv)
         m_new = np.maximum(m, S.max(axis=1))
         with np.errstate(invalid="ignore"):
@@ -490,6 +492,42 @@ def attention_rows_kernel_order(pro, rows, causal, bkv=BKV_ACC, out_dtype="bf16"
     if return_e:
         ret += (Eall,)
     return ret if len(ret) > 1 else res
+
+
+def key_chunks(pro, first_row, last_row, causal, splits, bkv=BKV_ACC):
+    """The chunks [(j0, j1), ...] into which the key blocks of a query tile (rows first_row .. last_row) are split
+    for `splits` workgroups: every chunk must start with a block in which every query of the tile sees a key,
+    so the n_vis leading blocks visible to the tile's first query are divided evenly, C = ceil(n_vis / splits)
+    each, and the last non-empty chunk runs on to the tile's last block."""
+    coff = pro["Nk"] - pro["N"]
+    nblk = (pro["Nk"] + bkv - 1) // bkv
+    n_vis = nblk
+    if causal:
+        nblk = min(nblk, (last_row + coff) // bkv + 1)
+        n_vis = min(nblk, (first_row + coff) // bkv + 1)
+    C = (n_vis + splits - 1) // splits
+    used = (n_vis + C - 1) // C
+    return [(s * C, nblk if s + 1 >= used else (s + 1) * C) for s in range(used)]
+
+
+def merge_key_chunks(pro, states, form, out_dtype="bf16"):
+    """Online softmax over disjoint key sets (Sec. 2.1, Eq. 1 applied to chunks instead of consecutive blocks):
+    each state holds a chunk's final (e, l, O) - the sums l = sum 2^(S - e) and O under the chunk's own exponent
+    offset e.  Under the largest offset e* the sums add up with weights 2^(e_s - e*); then Algorithm 1's last
+    line.  Evaluated in float64 from the FP32 states, one rounding to FP32 before the output cast.
+    Returns (output rows, merged state)."""
+    e = np.stack([st["e"].astype(f64) for st in states])              # [S, rows]
+    e_max = e.max(axis=0)
+    with np.errstate(invalid="ignore"):
+        w = np.where(np.isneginf(e), 0.0, np.exp2(e - e_max[None, :]))
+    l = sum(w[s] * st["l"].astype(f64) for s, st in enumerate(states))
+    O = sum(w[s][:, None] * st["O"].astype(f64) for s, st in enumerate(states))
+    fmax = 1.0 if form == "kernel" else _FP8[pro["pv_fmt"]][0]        # the kernel-order sums carry the static scale
+    out = (O / l[:, None] / fmax * pro["v_scale"].astype(f64)[None, :]).astype(f32)
+    if pro.get("vbar") is not None:
+        out = (out.astype(f64) + pro["vbar"].astype(f64)[None, :]).astype(f32)
+    return _round_out(out, out_dtype), dict(m=np.max(np.stack([st["m"] for st in states]), axis=0), e=e_max.astype(f32),
+                                            l=l.astype(f32), O=O.astype(f32))
 
 
 def row_lse(pro, rows, state):

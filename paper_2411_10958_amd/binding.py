@@ -45,7 +45,7 @@ class sage_attn_args(ctypes.Structure):
                 ("stream", ctypes.c_void_p),
                 ("cu_seqlens_q", ctypes.c_void_p), ("cu_seqlens_k", ctypes.c_void_p), ("lse", ctypes.c_void_p),
                 ("pv_format", ctypes.c_int),
-                ("k_mean_in", ctypes.c_void_p), ("v_scale_in", ctypes.c_void_p)]
+                ("k_mean_in", ctypes.c_void_p), ("v_scale_in", ctypes.c_void_p), ("kv_splits", ctypes.c_int)]
 
 
 class sage_quant_out(ctypes.Structure):
@@ -75,6 +75,8 @@ def load_library():
             getattr(lib, name).argtypes = [P(sage_attn_args)]
         lib.sage_attn_fwd.restype = ctypes.c_int
         lib.sage_attn_fwd.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 5 + [ctypes.c_float, ctypes.c_int]
+        lib.sage_attn_kv_splits.restype = ctypes.c_int
+        lib.sage_attn_kv_splits.argtypes = [P(sage_attn_args)]
         lib.sage_attn_release.restype = None
         lib.sage_attn_kv_stats.restype = ctypes.c_int
         lib.sage_attn_kv_stats.argtypes = [P(sage_attn_args), ctypes.c_void_p, ctypes.c_void_p]
@@ -113,7 +115,7 @@ def _ptr(t):
 
 def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
               smooth_v=False, group_map="lane", layout="HND", pv_format="e4m3", smooth_k=True, smooth_q=True,
-              fp32_delta_s=False, kv_stats=None):
+              fp32_delta_s=False, kv_stats=None, kv_splits=0):
     """Fills a sage_attn_args from torch tensors q [B,H,N,d], k/v [B,H_kv,N_kv,d] (layout "HND") or
     q [B,N,H,d], k/v [B,N_kv,H_kv,d] (layout "NHD"), contiguous, on the GPU.  `workspace` is a uint8 GPU tensor (or None); `stream` a torch.cuda.Stream (None = the
     current one)."""
@@ -139,6 +141,7 @@ def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", wo
     a.N_kv = Nk
     a.layout = _LAYOUTS[layout]
     a.pv_format = _PV_FORMATS[pv_format]
+    a.kv_splits = int(kv_splits)
     if kv_stats is not None:       # (k_mean, v_scale) float32 GPU tensors [B, H_kv, d], e.g. from sage_attn_kv_stats
         km, vs = kv_stats
         for name, t in (("k_mean", km), ("v_scale", vs)):
@@ -160,6 +163,11 @@ def sage_attn_workspace_bytes(args):
     return int(load_library().sage_attn_workspace_bytes(ctypes.byref(args)))
 
 
+def sage_attn_kv_splits(args):
+    """Key chunks per query tile the attention kernel will use for these arguments."""
+    return int(load_library().sage_attn_kv_splits(ctypes.byref(args)))
+
+
 def _alloc_workspace(args, device):
     need = sage_attn_workspace_bytes(args)
     if need == 0:
@@ -172,7 +180,7 @@ def _alloc_workspace(args, device):
 def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
                      smooth_v=False, group_map="lane", layout="HND", cu_seqlens_q=None, cu_seqlens_k=None,
                      max_seqlen_q=None, max_seqlen_k=None, return_lse=False, pv_format="e4m3", smooth_k=True,
-                     smooth_q=True, fp32_delta_s=False, kv_stats=None):
+                     smooth_q=True, fp32_delta_s=False, kv_stats=None, kv_splits=0):
     """Whole forward pass.  Returns `out` (allocated if not given).  With cu_seqlens_q the batch is a packed
     variable-length one (see make_varlen_args) and `layout` is ignored.  With return_lse the result is
     (out, lse): lse float32 [B, H, N], or [H, total_q] for a variable-length batch."""
@@ -182,10 +190,10 @@ def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_f
         a = make_varlen_args(q, k, v, out, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, max_seqlen_k, causal=causal,
                              sm_scale=sm_scale, mode=mode, workspace=workspace, stream=stream, smooth_v=smooth_v,
                              group_map=group_map, pv_format=pv_format, smooth_k=smooth_k, smooth_q=smooth_q,
-                             fp32_delta_s=fp32_delta_s, kv_stats=kv_stats)
+                             fp32_delta_s=fp32_delta_s, kv_stats=kv_stats, kv_splits=kv_splits)
     else:
         a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v, group_map, layout, pv_format,
-                      smooth_k, smooth_q, fp32_delta_s, kv_stats)
+                      smooth_k, smooth_q, fp32_delta_s, kv_stats, kv_splits)
     lse = None
     if return_lse:
         shape = (a.H, q.shape[0]) if cu_seqlens_q is not None else (a.B, a.H, a.N)

@@ -60,6 +60,16 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   D->seq.cu_q = a->cu_seqlens_q; D->seq.cu_k = a->cu_seqlens_k;
   D->want_lse = a->lse != nullptr;
   D->pvf = a->pv_format;        // SAGE_PV_* and PV_* share their values
+  // key range split (kv_splits): only where few tiles would leave the chip idle, at least 8 key blocks per chunk
+  if (a->kv_splits < 0 || a->kv_splits > 64) return SAGE_ERR_INVALID_ARG;
+  D->splits = 1;
+  if (D->kg == KGROUP && D->pvf == PV_E4M3 && a->kv_splits != 1) {
+    const long long tiles = (long long)a->B * a->H * nQb;
+    long long S = a->kv_splits > 1 ? a->kv_splits : (tiles < 256 ? (512 + tiles - 1) / tiles : 1);
+    if (S > nKb / 8) S = nKb / 8;
+    if (S > 64) S = 64;
+    if (S >= 2) D->splits = (int)S;
+  }
   const float sm = a->sm_scale > 0.0f ? a->sm_scale : (float)(1.0 / std::sqrt((double)a->d));
   D->kappa = sm * LOG2E;   // one FP32 rounding of the product of two FP32 values
   return SAGE_OK;
@@ -123,6 +133,12 @@ size_t sage_attn_workspace_bytes(const sage_attn_args* args) {
   return make_workspace(D).total;
 }
 
+int sage_attn_kv_splits(const sage_attn_args* args) {
+  Dims D;
+  if (validate(args, &D, false) != SAGE_OK) return 0;
+  return D.splits;
+}
+
 int sage_attn_prologue(const sage_attn_args* args) {
   Dims D;
   int st = validate(args, &D, true);
@@ -157,7 +173,7 @@ int sage_attn_fwd(const void* q, const void* k, const void* v, void* out, int B,
   a.B = B; a.H = H; a.H_kv = H; a.N = N; a.d = d;
   a.causal = causal; a.sm_scale = sm_scale; a.mode = mode; a.dtype = SAGE_DT_BF16; a.flags = 0; a.group_map = SAGE_GROUPS_LANE; a.N_kv = 0; a.layout = SAGE_LAYOUT_HND;
   a.cu_seqlens_q = nullptr; a.cu_seqlens_k = nullptr; a.lse = nullptr; a.pv_format = SAGE_PV_E4M3;
-  a.k_mean_in = nullptr; a.v_scale_in = nullptr;
+  a.k_mean_in = nullptr; a.v_scale_in = nullptr; a.kv_splits = 0;
   a.workspace = nullptr; a.workspace_bytes = 0; a.stream = nullptr;
   const size_t need = sage_attn_workspace_bytes(&a);
   if (need == 0) {

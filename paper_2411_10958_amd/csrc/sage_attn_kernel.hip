@@ -33,7 +33,27 @@ struct AttnParams {
   float* lse;             // null, or where the row log-sum-exp goes
   const float* q_corr;    // kappa * <q_r, mean(K)> per query (read only with lse)
   int B;
+  // key range split over several workgroups per tile (few tiles, many keys): partial results, merged by k_merge_splits
+  int splits;             // workgroups per tile (1: no split)
+  float* part_o;          // [tile * splits + s][128 rows][d]: unnormalized O under the chunk's own exponent offset
+  float* part_el;         // [tile * splits + s][128 rows][2]: that offset e and the sum l under it
 };
+
+// Split of a tile's key blocks [0, nblk) into chunks, one workgroup each (Sec. 2.1, Eq. 1: the running maximum / sum /
+// output of disjoint key sets combine by the same rule that combines consecutive blocks).  Every chunk must start
+// with a block in which every query of the tile sees a key, so the chunks divide the first n_vis blocks - those
+// with a key visible to the tile's first query - evenly, C = ceil(n_vis / S) blocks each, and the last non-empty
+// chunk runs on to nblk; chunks s >= ceil(n_vis / C) are empty.
+struct KeyChunk { int j0, j1; };
+__host__ __device__ inline KeyChunk key_chunk(int s, int S, int nblk, int n_vis) {
+  const int C = (n_vis + S - 1) / S;
+  const int used = C > 0 ? (n_vis + C - 1) / C : 0;
+  KeyChunk k;
+  k.j0 = s * C;
+  k.j1 = s + 1 >= used ? nblk : (s + 1) * C;
+  if (s >= used) { k.j0 = k.j1 = 0; }
+  return k;
+}
 
 // Score accumulators of one wavefront for one 64-key block: 2 key tiles x (32 keys x 32
 // queries).  ka: the block's K^ chunks already in registers (chunk (s, kt) at ka[2s + kt]); qreg:
@@ -389,7 +409,7 @@ __device__ __forceinline__ size_t lse_index(const AttnParams& p, const Seq& sq, 
 // d = 256: the cross-block accumulator O alone is 128 registers per lane, so a workgroup takes a CU's whole register
 // file (one wavefront per SIMD, 512 registers each: the accumulators of the matrix instructions live in the second
 // half) and its three LDS stages are 88 KB.
-template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, int PVF>
+template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, int PVF, bool SPLIT = false>
 __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_attn_fwd(const AttnParams p) {
   constexpr int KSC = GM == 0 ? 4 : (GM == 1 ? 16 : 64);    // key scales per block
   constexpr int QG = GM == 0 ? QGROUP : 1;                  // queries per scale
@@ -413,11 +433,15 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
   // finish long after the rest (measured at N = 8192, where a range is four heads of 64 tiles: 13 % of the kernel's
   // time; 1.5 % at N = 16384).  Longer sequences keep the head-by-head order: the imbalance shrinks with the tile
   // count while four interleaved heads no longer share an XCD's L2 (N = 32768: 1.5 % slower interleaved).
-  const int per_xcd = (p.total_tiles + 7) / 8;
+  const int n_wg = SPLIT ? p.total_tiles * p.splits : p.total_tiles;
+  const int per_xcd = (n_wg + 7) / 8;
   const int in_xcd = blockIdx.x / 8;
   int tile = (blockIdx.x % 8) * per_xcd + in_xcd;
+  if (tile >= n_wg) return;
+  int split = 0;
+  if constexpr (SPLIT) { split = tile % p.splits; tile /= p.splits; }
   int bh, qb;
-  if (CAUSAL && p.nQb <= 128 && per_xcd % p.nQb == 0) {
+  if (!SPLIT && CAUSAL && p.nQb <= 128 && per_xcd % p.nQb == 0) {
     const int heads_here = per_xcd / p.nQb;
     bh = (blockIdx.x % 8) * heads_here + in_xcd % heads_here;
     qb = p.nQb - 1 - in_xcd / heads_here;
@@ -436,6 +460,7 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
 
   const int t = threadIdx.x, lane = t & 63;
   if (sq.nk == 0) {                            // no keys at all: the rows are defined as zeros
+    if (SPLIT && split != 0) return;           // (written once; the merge kernel leaves such a tile alone)
     unsigned short* o = reinterpret_cast<unsigned short*>(p.out) + head_offset(p.om, (unsigned)bh);
     for (int idx = t; idx < BQ * (D / 8); idx += 256) {
       const int row = qb * BQ + idx / (D / 8);
@@ -458,6 +483,20 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
 
   int nblk = (sq.nk + BKV - 1) / BKV;
   if (CAUSAL) nblk = min(nblk, (qb * BQ + BQ - 1 + sq.coff) / BKV + 1);
+  int j_begin = 0;                             // this workgroup's key blocks: [j_begin, nblk)
+  if constexpr (SPLIT) {
+    const int n_vis = CAUSAL ? min(nblk, (qb * BQ + sq.coff) / BKV + 1) : nblk;
+    const KeyChunk kc = key_chunk(split, p.splits, nblk, n_vis);
+    j_begin = kc.j0;
+    nblk = kc.j1;
+    if (j_begin >= nblk) {                     // an empty chunk: offset -inf, sum 0 (the merge skips it)
+      if (t < BQ) {
+        float* el = p.part_el + ((size_t)((bh * p.nQb + qb) * p.splits + split) * BQ + t) * 2;
+        el[0] = -INFINITY; el[1] = 0.0f;
+      }
+      return;
+    }
+  }
 
   // Block copies: every wavefront moves its quarter of the K^ and V^ chunks (the copy is the
   // identity on chunk indices), wavefront 0 the block's Delta-S row, wavefront 1 the 4 scales.
@@ -506,8 +545,8 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
     }
   }
   if constexpr (COPIES_FIRST) {
-    issue(0, 0);
-    if (nblk > 1) issue(1, 1);
+    issue(j_begin, 0);
+    if (j_begin + 1 < nblk) issue(j_begin + 1, 1);
   }
 
   // ---- this wavefront's Q^ operands (registers, for the whole kernel) and scale ----
@@ -545,6 +584,12 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
   }
   n_plain = __builtin_amdgcn_readfirstlane(n_plain);
   n_act = __builtin_amdgcn_readfirstlane(n_act);
+
+  // Keys from here on are masked like the padding past the sequence's end.  For a chunk of a split key range that
+  // is the chunk's end: the pipeline always forms the scores of one block past the last (from a stale stage), and
+  // its running-max update must see them masked, or the exponent offset handed to the merge would not be the one
+  // the sums were taken under.
+  const int n_keys_end = SPLIT ? min(sq.nk, nblk * BKV) : sq.nk;
 
   // Software pipeline, one barrier per block, three LDS stages; every MFMA is issued between
   // pieces of vector work that do not depend on it, one at a time (a burst of MFMAs would hold up
@@ -620,15 +665,15 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
   if constexpr (COPIES_FIRST) {
     wait_all();
   } else {
-    issue(0, 0);
-    if (nblk > 1) { issue(1, 1); wait_all_but_newest(); } else { wait_all(); }
+    issue(j_begin, 0);
+    if (j_begin + 1 < nblk) { issue(j_begin + 1, 1); wait_all_but_newest(); } else { wait_all(); }
   }
   __syncthreads();
   read_k(0);
   read_ds(0, 0);
   read_ds(0, 1);
   read_scales(0);
-  qk_tile<D, INT4>(ka, qreg, raw);    // block 0 holds a visible key for every query
+  qk_tile<D, INT4>(ka, qreg, raw);    // the first block holds a visible key for every query
   float alpha, m_sub = -INFINITY;     // of block j (m_sub: nothing summed yet)
   Factors<GM> fj;                     // block j's dequantization factors (used again by the fused exponent)
   constexpr int NQK = qk_steps<D, INT4>();
@@ -638,7 +683,7 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
 
 #define SAGE_DEQ(MASKED_, GI_, KEY0_)                                                                \
   dequant_group<INT4, CAUSAL, MASKED_, GM, (GI_) / 4, (GI_) % 4>(raw, sc, fn, half, KEY0_,               \
-                                                                 query + sq.coff, sq.nk)
+                                                                 query + sq.coff, n_keys_end)
 #define SAGE_DEQ_ALL(MASKED_, KEY0_)                                                                 \
   do {                                                                                               \
     SAGE_DEQ(MASKED_, 0, KEY0_); SAGE_DEQ(MASKED_, 1, KEY0_); SAGE_DEQ(MASKED_, 2, KEY0_);           \
@@ -648,7 +693,7 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
   {
     Factors<GM> fn;
     fn.set(dq, p.kappa, ks);
-    if (n_plain > 0) SAGE_DEQ_ALL(false, 0); else SAGE_DEQ_ALL(true, 0);
+    if (j_begin < n_plain) SAGE_DEQ_ALL(false, j_begin * BKV); else SAGE_DEQ_ALL(true, j_begin * BKV);
     alpha = update_max<D, INT4, GM, PVF>(st, sc, fn, m_sub);
     fj = fn;
   }
@@ -707,7 +752,7 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
     fj = fn;                                                                                         \
     cur = nx1;                                                                                       \
   } while (0)
-  int j = 0;
+  int j = j_begin;
   for (; j + 1 < n_plain; ++j) SAGE_BODY(false, false);
   if (j < n_plain) { SAGE_BODY(false, true); ++j; }      // the last unmasked block, a masked (or no) successor
   for (; j < n_act; ++j) SAGE_BODY(true, true);
@@ -733,6 +778,22 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
     const unsigned u = __float_as_uint(l_tot);
     const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
     l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+  }
+  if constexpr (SPLIT) {
+    // a chunk of the keys: the sums stay under the chunk's own exponent offset and go to the merge kernel as they are
+    const size_t prow = (size_t)((bh * p.nQb + qb) * p.splits + split) * BQ + w * WQ + n;
+    if (query < sq.n) {
+      if (half == 0) { p.part_el[prow * 2] = m_sub; p.part_el[prow * 2 + 1] = l_tot; }
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const v4f o4 = {st.O[ct][4 * g], st.O[ct][4 * g + 1], st.O[ct][4 * g + 2], st.O[ct][4 * g + 3]};
+          *reinterpret_cast<v4f*>(p.part_o + prow * D + 32 * ct + 8 * g + 4 * half) = o4;
+        }
+      }
+    }
+    return;
   }
   if (p.lse && half == 0 && query < sq.n) {
     // ln sum_t exp(sm_scale <q, k_t>) = ln 2 * (e + log2(l) + the row constant smoothing K dropped): l_tot is the
@@ -765,6 +826,61 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
         *reinterpret_cast<uint2*>(orow + c0) = make_uint2(pack16x2<BF16>(o4[0], o4[1]), pack16x2<BF16>(o4[2], o4[3]));
       }
     }
+  }
+}
+
+// Merge of the partial results of a tile's key chunks (Eq. 1 applied to disjoint key sets): under the largest of
+// the chunks' exponent offsets e* the sums add up with weights 2^(e_s - e*); then the epilogue of Algorithm 1.
+// One workgroup per tile, two threads per query row (half of the channels each).
+template <int D, bool BF16>
+__global__ void __launch_bounds__(256) k_merge_splits(const AttnParams p) {
+  const int tile = blockIdx.x;
+  const int bh = tile / p.nQb, qb = tile % p.nQb;
+  const int b = bh / p.H, h = bh % p.H;
+  const size_t bhkv = (size_t)b * p.Hkv + h / (p.H / p.Hkv);
+  const Seq sq = seq_of(p.seq, (unsigned)b, p.N, p.Nk);
+  if (qb * BQ >= sq.n || sq.nk == 0) return;   // (a sequence without keys was written by the attention kernel)
+  const int t = threadIdx.x, r = t >> 1, c_lo = (t & 1) * (D / 2);
+  const int query = qb * BQ + r;
+  if (query >= sq.n) return;
+  const size_t row0 = (size_t)tile * p.splits * BQ + r;       // this row in chunk 0; chunk s is s * BQ rows further
+  float e_max = -INFINITY;
+  for (int s = 0; s < p.splits; ++s) e_max = fmaxf(e_max, p.part_el[(row0 + (size_t)s * BQ) * 2]);
+  float l = 0.0f;
+  float acc[D / 2];
+#pragma unroll
+  for (int c = 0; c < D / 2; ++c) acc[c] = 0.0f;
+  for (int s = 0; s < p.splits; ++s) {
+    const size_t row = row0 + (size_t)s * BQ;
+    const float e = p.part_el[row * 2];
+    if (e == -INFINITY) continue;              // an empty chunk
+    const float wgt = __builtin_amdgcn_exp2f(e - e_max);
+    l = __fmaf_rn(wgt, p.part_el[row * 2 + 1], l);
+    const v4f* o = reinterpret_cast<const v4f*>(p.part_o + row * D + c_lo);
+#pragma unroll
+    for (int c = 0; c < D / 8; ++c) {
+      const v4f o4 = o[c];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc[4 * c + k] = __fmaf_rn(wgt, o4[k], acc[4 * c + k]);
+    }
+  }
+  if (p.lse && (t & 1) == 0)
+    p.lse[lse_index(p, sq, b, h, query)] =
+        LN2 * ((e_max + __builtin_amdgcn_logf(l)) + p.q_corr[((size_t)bh * p.nQb + qb) * BQ + r]);
+  const float inv_l = __fdiv_rn(1.0f, l);
+  unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) +
+                         row_offset(p.om, head_offset(p.om, (unsigned)bh), (int)sq.q0 + query) + c_lo;
+  const float* vs = p.v_scale + bhkv * D + c_lo;
+  const float* vm = p.v_mean ? p.v_mean + bhkv * D + c_lo : nullptr;
+#pragma unroll
+  for (int c = 0; c < D / 2; c += 4) {
+    float o4[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      o4[k] = __fmul_rn(__fmul_rn(acc[c + k], inv_l), vs[c + k]);
+      if (vm) o4[k] = __fadd_rn(o4[k], vm[c + k]);
+    }
+    *reinterpret_cast<uint2*>(orow + c) = make_uint2(pack16x2<BF16>(o4[0], o4[1]), pack16x2<BF16>(o4[2], o4[3]));
   }
 }
 
@@ -822,6 +938,15 @@ static hipError_t launch_attention_g(const Dims& Dm, const Ptrs& P, hipStream_t 
   p.lse = P.lse; p.q_corr = P.q_corr; p.B = Dm.B;
   p.total_tiles = Dm.B * Dm.H * Dm.nQb;
   p.kappa = Dm.kappa;
+  p.splits = Dm.splits; p.part_o = P.part_o; p.part_el = P.part_el;
+  if constexpr (GM == 0 && PVF == PV_E4M3) {        // (the key split comes with the default groups and data type)
+    if (Dm.splits > 1) {
+      const int grid = 8 * ((p.total_tiles * Dm.splits + 7) / 8);
+      k_attn_fwd<D, INT4, CAUSAL, BF16, GM, PVF, true><<<grid, 256, 0, s>>>(p);
+      k_merge_splits<D, BF16><<<p.total_tiles, 256, 0, s>>>(p);
+      return hipGetLastError();
+    }
+  }
   const int grid = 8 * ((p.total_tiles + 7) / 8);
   k_attn_fwd<D, INT4, CAUSAL, BF16, GM, PVF><<<grid, 256, 0, s>>>(p);
   return hipGetLastError();

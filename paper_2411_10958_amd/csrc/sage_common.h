@@ -98,6 +98,7 @@ struct Dims {
   int want_lse; // the caller asked for the row log-sum-exp
   int pvf;      // data type of P~ and V: PV_E4M3, PV_E5M2 or PV_INT8
   int tensor_groups;  // one scale per (batch, head) tensor of Q and of K (implies block_groups)
+  int splits;         // workgroups per query tile in the attention kernel (key range split; 1 = none)
 };
 
 // Workspace map (all offsets multiples of 256 bytes).
@@ -131,7 +132,7 @@ struct Dims {
 //   v_sum, v_mean only with the smooth-V option (otherwise zero-sized).
 struct Workspace {
   size_t k_sum, v_sum, v_max, k_mean, v_mean, v_scale, q_mean, q_scale, k_scale, q_corr, q_head_scale,
-      k_head_scale, q_codes, k_codes, v_codes, delta_s, total;
+      k_head_scale, q_codes, k_codes, v_codes, delta_s, part_o, part_el, total;
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -167,6 +168,9 @@ inline Workspace make_workspace(const Dims& D) {
   w.k_codes = take(BHkv * D.nKb * k_block_bytes(D.d, D.int4));
   w.v_codes = take(BHkv * D.nKb * BKV * D.d);
   w.delta_s = take(D.int4 ? BH * D.nQb * D.nKb * BKV * sizeof(float) : 0);
+  // partial results of a split key range: per (tile, chunk) 128 rows of d floats, and (offset, sum) per row
+  w.part_o = take(D.splits > 1 ? BH * D.nQb * D.splits * BQ * D.d * sizeof(float) : 0);
+  w.part_el = take(D.splits > 1 ? BH * D.nQb * D.splits * BQ * 2 * sizeof(float) : 0);
   w.total = off;
   return w;
 }
@@ -177,6 +181,7 @@ struct Ptrs {
   double *k_sum, *v_sum;
   unsigned* v_max;
   float *k_mean, *v_mean, *v_scale, *q_mean, *q_scale, *k_scale, *q_corr, *q_head_scale, *k_head_scale, *delta_s;
+  float *part_o, *part_el;
   float* lse;
   int8_t *q_codes, *k_codes;
   uint8_t* v_codes;
@@ -204,6 +209,8 @@ inline Ptrs make_ptrs(const void* q, const void* k, const void* v, void* out, vo
   p.k_codes = (int8_t*)(b + w.k_codes);
   p.v_codes = (uint8_t*)(b + w.v_codes);
   p.delta_s = (float*)(b + w.delta_s);
+  p.part_o = (float*)(b + w.part_o);
+  p.part_el = (float*)(b + w.part_el);
   return p;
 }
 

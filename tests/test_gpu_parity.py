@@ -442,6 +442,60 @@ def test_other_key_length_matches_oracle(N, Nk, d, dtype, H, Hkv, causal, mode):
     assert wl.cos_sim(wl.from_torch(out)[0], full) > (0.9 if mode == "int4_fp8" else 0.99)
 
 
+# ---- key range of a tile split over several workgroups (decode steps, few queries against a long cache) ----------
+SPLIT_CASES = [
+    # N, N_kv, d, dtype, H, Hkv, causal, kv_splits (0: the library decides)
+    (1, 1500, 128, "bf16", 4, 1, True, 0),        # one decode step
+    (32, 2000, 128, "bf16", 2, 2, True, 4),       # a short chunk of queries at the end of a cache
+    (130, 1100, 64, "fp16", 2, 1, False, 3),      # two query tiles, the second one ragged
+    (7, 1700, 256, "bf16", 2, 2, True, 0),
+    (200, 1030, 128, "bf16", 1, 1, True, 5),      # chunks of different lengths per tile, a diagonal inside the last one
+]
+
+
+@pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("N,Nk,d,dtype,H,Hkv,causal,kv_splits", SPLIT_CASES)
+def test_split_key_range_matches_oracle(N, Nk, d, dtype, H, Hkv, causal, kv_splits, mode):
+    """Every chunk is Algorithm 1 on its key blocks; the merge is Eq. 1's rule for disjoint key sets.  The oracle walks
+    the same chunks (oracle.key_chunks mirrors the documented rule) and merges them in float64."""
+    pa = _pa()
+    spec = _spec(N, d, dtype, H, Hkv, B=2, causal=causal).with_(N_kv=Nk)
+    data, (q, k, v) = _gpu_inputs(spec)
+    S = pa.sage_attn_kv_splits(pa.make_args(q, k, v, causal=causal, mode=mode, kv_splits=kv_splits))
+    print(f"split case N={N} N_kv={Nk} d={d} {dtype} H={H}/{Hkv} causal={causal} mode={mode}: {S} chunks per tile", flush=True)
+    assert S > 1 and (kv_splits == 0 or S == min(kv_splits, ((Nk + 63) // 64) // 8))     # at least 8 key blocks per chunk
+    out, lse = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, kv_splits=kv_splits, return_lse=True)
+    whole = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, kv_splits=1)
+    torch.cuda.synchronize()
+    pros = parity.check_heads(wl.from_torch(out), data, causal, mode, dtype, want_lse=True, splits=S)
+    for b in range(2):
+        for h in range(H):
+            _lse_close(lse[b, h].cpu().numpy(), pros[b][h]["lse"], pros[b][h])
+    # the unsplit path is checked against the unsplit oracle, and both approximate the same attention
+    parity.check_heads(wl.from_torch(whole), data, causal, mode, dtype)
+    g = H // Hkv
+    full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal) for h in range(H)])
+    e_split, e_whole = wl.rel_l1(wl.from_torch(out)[0], full), wl.rel_l1(wl.from_torch(whole)[0], full)
+    print(f"  rel-L1 vs FP64 attention: split {e_split:.4f}, one piece {e_whole:.4f}", flush=True)
+    assert e_split < 1.3 * e_whole + 1e-3
+
+
+def test_split_key_range_is_refused_where_it_does_not_apply():
+    pa = _pa()
+    spec = _spec(16, 128, "bf16", 2, 2).with_(N_kv=2048)
+    _, (q, k, v) = _gpu_inputs(spec)
+    assert pa.sage_attn_kv_splits(pa.make_args(q, k, v)) > 1                        # few tiles, many keys: split
+    assert pa.sage_attn_kv_splits(pa.make_args(q, k, v, kv_splits=1)) == 1          # switched off
+    assert pa.sage_attn_kv_splits(pa.make_args(q, k, v, group_map="fine")) == 1     # default groups only
+    assert pa.sage_attn_kv_splits(pa.make_args(q, k, v, pv_format="e5m2")) == 1
+    a = pa.make_args(q, k, v, torch.empty_like(q), kv_splits=65)
+    assert pa.sage_attn_workspace_bytes(a) == 0
+    big = _spec(4096, 128, "bf16", 8, 8)                                             # 256 tiles: no split (shapes only)
+    a = pa.make_args(q, k, v)
+    a.N, a.N_kv, a.H, a.H_kv = 4096, 4096, 8, 8
+    assert pa.sage_attn_kv_splits(a) == 1
+
+
 # ---- [B, N, H, d] memory order ------------------------------------------------------------------
 @pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
 @pytest.mark.parametrize("N,Nk,d,H,Hkv,causal", [(333, 333, 128, 4, 2, True), (200, 450, 64, 2, 2, False)])

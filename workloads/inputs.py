@@ -51,6 +51,8 @@ CONFIGS = {
     "causal32k": WorkloadSpec("causal32k", 1, 32, 32, 32768, 128, "bf16", True, 3.0, 3.0, 4, 10.0, 1.0, 3),
     # the causal 8k case with 256-wide heads (half the heads: the same operation count per head as two 128-wide ones)
     "causal8k_d256": WorkloadSpec("causal8k_d256", 1, 16, 16, 8192, 256, "bf16", True, 3.0, 3.0, 4, 10.0, 1.0, 6),
+    # one decode step: a single new query per sequence against a 32k-token cache, grouped KV heads
+    "decode32k": WorkloadSpec("decode32k", 4, 32, 8, 1, 128, "bf16", True, 3.0, 3.0, 4, 10.0, 1.0, 7, 0.0, 32768),
     # video-diffusion-like: ragged N, d=64, token norms vary
     "video17k": WorkloadSpec("video17k", 2, 48, 48, 17776, 64, "bf16", False, 4.0, 4.0, 0, 1.0, 8.0, 4),
     # the same with the channel-wise V bias quoted for a video model (Appendix "Smoothing V": 8 to 9)
