@@ -58,6 +58,23 @@ def build_abi_smoke(verbose=True):
     return ABI_SMOKE_BIN
 
 
+PROBE_SRC = os.path.join(PKG, "csrc", "probe_valu_issue.hip")
+PROBE_BIN = os.path.join(PKG, "probe_valu_issue")
+
+
+def build_probe(verbose=True):
+    """Compiles csrc/probe_valu_issue.hip, the stand-alone hardware probe the vector-ALU ceiling quoted by bench.py
+    comes from (profiles/valu_issue_probe.txt holds its output)."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wno-unused-command-line-argument", "-o", PROBE_BIN, PROBE_SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    return PROBE_BIN
+
+
 if __name__ == "__main__":
     build_library(extra_flags=sys.argv[1:])
     build_abi_smoke()
+    build_probe()

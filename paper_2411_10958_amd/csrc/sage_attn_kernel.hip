@@ -213,11 +213,10 @@ __device__ __forceinline__ void dequant_group(const v16i (&raw)[2], v16i (&sc)[2
     float x;
     if constexpr (INT4) {
       // On entry sc holds the block's Delta-S values (read from LDS straight into these registers): the score is
-      // one multiply-add in place, in the two-operand encoding, which issues faster than the three-operand one.
-      x = __int_as_float(sc[KT][4 * G + r]);
-#if defined(__HIP_DEVICE_COMPILE__)
-      asm("v_fmac_f32 %0, %1, %2" : "+v"(x) : "v"(__int_as_float(raw[KT][4 * G + r])), "v"(fac.at(KT, G, r)));
-#endif
+      // one fused multiply-add in place (the two-operand encoding, which issues faster than the three-operand
+      // one).  Written as an ordinary expression, not as inline assembly: the compiler must see that it reads the
+      // accumulators of a matrix instruction, or it cannot keep the wait states that read needs.
+      x = __builtin_fmaf(__int_as_float(raw[KT][4 * G + r]), fac.at(KT, G, r), __int_as_float(sc[KT][4 * G + r]));
     }
     else x = (float)raw[KT][4 * G + r];       // 8-bit mode: the factor is applied inside the exponent's argument
     if constexpr (MASKED) {
@@ -376,9 +375,23 @@ __device__ __forceinline__ void pv_step(RowState<D>& st, const v4i (&va)[2 * (D 
   st.O[CT] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, st.O[CT], FMT, FMT, 0, 0, 0, 0);
 }
 
-#ifndef SAGE_WAVES_PER_SIMD
-#define SAGE_WAVES_PER_SIMD 2
+// Wavefronts per SIMD the attention kernel is built for, by variant.  d = 128 with the default key groups: 3 (168
+// registers: one block's scores live at a time, no software pipeline inside a wavefront - the other two wavefronts
+// of the SIMD fill its waits; measured 8 - 9 % faster than 2 wavefronts with the score product of the next block
+// pipelined into the exponentials of the current one).  The variants that hold more per-block state (a key scale
+// per quad or per key, the INT8 P~V product) would spill at 168 registers and keep the pipelined form at 2.
+// d = 64: half the accumulator, one more wavefront.  d = 256: 1 (the accumulator alone is 128 registers).
+#ifndef SAGE_OCC_D128
+#define SAGE_OCC_D128 3
 #endif
+#ifndef SAGE_OCC_D64
+#define SAGE_OCC_D64 4
+#endif
+template <int D, int GM, int PVF> constexpr int attn_occupancy() {
+  if (D == 256) return 1;
+  if (D == 128) return (GM == 0 && PVF != PV_INT8) ? SAGE_OCC_D128 : 2;
+  return GM == 0 && PVF != PV_INT8 ? SAGE_OCC_D64 : (SAGE_OCC_D64 >= 3 ? 3 : 2);
+}
 
 // Global -> LDS copies without a register stop (the LDS-DMA form of the global load: lane l's
 // 16 or 4 bytes land at LDS byte m0 + 16*l or m0 + 4*l).  Issued from inline assembly so that
@@ -410,7 +423,8 @@ __device__ __forceinline__ size_t lse_index(const AttnParams& p, const Seq& sq, 
 // file (one wavefront per SIMD, 512 registers each: the accumulators of the matrix instructions live in the second
 // half) and its three LDS stages are 88 KB.
 template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, int PVF, bool SPLIT = false>
-__global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_attn_fwd(const AttnParams p) {
+__global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fwd(const AttnParams p) {
+  constexpr bool OCC3 = attn_occupancy<D, GM, PVF>() >= 3;     // the form without a software pipeline
   constexpr int KSC = GM == 0 ? 4 : (GM == 1 ? 16 : 64);    // key scales per block
   constexpr int QG = GM == 0 ? QGROUP : 1;                  // queries per scale
   constexpr int CT = D / 32;          // 32-channel tiles of the output
@@ -663,17 +677,11 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
   use_now(dq);
   use_now(lse_corr);
   if constexpr (COPIES_FIRST) {
-    wait_all();
+    if constexpr (!OCC3) wait_all();
   } else {
     issue(j_begin, 0);
-    if (j_begin + 1 < nblk) { issue(j_begin + 1, 1); wait_all_but_newest(); } else { wait_all(); }
+    if (j_begin + 1 < nblk) { issue(j_begin + 1, 1); if constexpr (!OCC3) wait_all_but_newest(); } else { if constexpr (!OCC3) wait_all(); }
   }
-  __syncthreads();
-  read_k(0);
-  read_ds(0, 0);
-  read_ds(0, 1);
-  read_scales(0);
-  qk_tile<D, INT4>(ka, qreg, raw);    // the first block holds a visible key for every query
   float alpha, m_sub = -INFINITY;     // of block j (m_sub: nothing summed yet)
   Factors<GM> fj;                     // block j's dequantization factors (used again by the fused exponent)
   constexpr int NQK = qk_steps<D, INT4>();
@@ -690,7 +698,13 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
     SAGE_DEQ(MASKED_, 3, KEY0_); SAGE_DEQ(MASKED_, 4, KEY0_); SAGE_DEQ(MASKED_, 5, KEY0_);           \
     SAGE_DEQ(MASKED_, 6, KEY0_); SAGE_DEQ(MASKED_, 7, KEY0_);                                        \
   } while (0)
-  {
+  if constexpr (!OCC3) {
+    __syncthreads();
+    read_k(0);
+    read_ds(0, 0);
+    read_ds(0, 1);
+    read_scales(0);
+    qk_tile<D, INT4>(ka, qreg, raw);    // the first block holds a visible key for every query
     Factors<GM> fn;
     fn.set(dq, p.kappa, ks);
     if (j_begin < n_plain) SAGE_DEQ_ALL(false, j_begin * BKV); else SAGE_DEQ_ALL(true, j_begin * BKV);
@@ -752,10 +766,46 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
     fj = fn;                                                                                         \
     cur = nx1;                                                                                       \
   } while (0)
+  // Variant for three wavefronts per SIMD (168 registers): no software pipeline inside a wavefront - block j's score
+  // product, softmax piece and P~V product run one after the other, and the two other wavefronts of the SIMD fill
+  // the waits - so only one block's scores are live at a time.
+#define SAGE_E3(GI_, MASKED_) exp_group<INT4, MASKED_, GM, PVF, (GI_) / 4, (GI_) % 4>(sc, fn, m_sub, pb, ls)
+#define SAGE_P3(CT_) do { if constexpr ((CT_) < CT) pv_step<D, (CT_) < CT ? (CT_) : 0, PVF>(st, va, pb); } while (0)
+#define SAGE_BODY3(MASKED_)                                                                          \
+  do {                                                                                               \
+    const int nx1 = cur == NST - 1 ? 0 : cur + 1;                                                    \
+    const int nx2 = nx1 == NST - 1 ? 0 : nx1 + 1;                                                    \
+    wait_all();                                                                                      \
+    __syncthreads();                                                                                 \
+    if (j + 2 < nblk) issue(j + 2, nx2);                                                             \
+    read_k(cur);                                                                                     \
+    read_ds(cur, 0);                                                                                 \
+    read_ds(cur, 1);                                                                                 \
+    read_scales(cur);                                                                                \
+    qk_tile<D, INT4>(ka, qreg, raw);                                                                 \
+    Factors<GM> fn;                                                                                  \
+    fn.set(dq, p.kappa, ks);                                                                         \
+    SAGE_DEQ_ALL(MASKED_, j * BKV);                                                                  \
+    alpha = update_max<D, INT4, GM, PVF>(st, sc, fn, m_sub);                                         \
+    block_rescale<D>(st, alpha);                                                                     \
+    v8i pb;                                                                                          \
+    float ls = 0.0f;                                                                                 \
+    SAGE_E3(0, MASKED_); SAGE_E3(1, MASKED_); SAGE_E3(2, MASKED_); SAGE_E3(3, MASKED_);              \
+    read_v(cur);                                                                                     \
+    SAGE_E3(4, MASKED_); SAGE_E3(5, MASKED_); SAGE_E3(6, MASKED_); SAGE_E3(7, MASKED_);              \
+    st.l_run = __fmaf_rn(alpha, st.l_run, ls);                                                       \
+    SAGE_P3(0); SAGE_P3(1); SAGE_P3(2); SAGE_P3(3); SAGE_P3(4); SAGE_P3(5); SAGE_P3(6); SAGE_P3(7);  \
+    cur = nx1;                                                                                       \
+  } while (0)
   int j = j_begin;
-  for (; j + 1 < n_plain; ++j) SAGE_BODY(false, false);
-  if (j < n_plain) { SAGE_BODY(false, true); ++j; }      // the last unmasked block, a masked (or no) successor
-  for (; j < n_act; ++j) SAGE_BODY(true, true);
+  if constexpr (OCC3) {
+    for (; j < n_plain; ++j) SAGE_BODY3(false);
+    for (; j < n_act; ++j) SAGE_BODY3(true);
+  } else {
+    for (; j + 1 < n_plain; ++j) SAGE_BODY(false, false);
+    if (j < n_plain) { SAGE_BODY(false, true); ++j; }      // the last unmasked block, a masked (or no) successor
+    for (; j < n_act; ++j) SAGE_BODY(true, true);
+  }
   // causal only: blocks past this wavefront's last query - keep up the copies and the barriers
   for (; j < nblk; ++j) {
     const int nx1 = cur == NST - 1 ? 0 : cur + 1;
@@ -765,6 +815,9 @@ __global__ void __launch_bounds__(256, D == 256 ? 1 : SAGE_WAVES_PER_SIMD) k_att
     if (j + 2 < nblk) issue(j + 2, nx2);
     cur = nx1;
   }
+#undef SAGE_BODY3
+#undef SAGE_P3
+#undef SAGE_E3
 #undef SAGE_BODY
 #undef SAGE_Y
 #undef SAGE_X
