@@ -380,15 +380,20 @@ __device__ __forceinline__ void pv_step(RowState<D>& st, const v4i (&va)[2 * (D 
 // of the SIMD fill its waits; measured 8 - 9 % faster than 2 wavefronts with the score product of the next block
 // pipelined into the exponentials of the current one).  The variants that hold more per-block state (a key scale
 // per quad or per key, the INT8 P~V product) would spill at 168 registers and keep the pipelined form at 2.
-// d = 64: half the accumulator, one more wavefront.  d = 256: 1 (the accumulator alone is 128 registers).
+// d = 64: half the accumulator, one more wavefront.  d = 256: 2 (the accumulator alone is 128 registers; 254 in all,
+// two LDS stages of 29 KB so that two workgroups fit a CU; 2140 TOPS on the causal 8k case against 1254 for the
+// pipelined form at one wavefront per SIMD, whose accumulators had to live in the second half of the register file).
 #ifndef SAGE_OCC_D128
 #define SAGE_OCC_D128 3
 #endif
 #ifndef SAGE_OCC_D64
 #define SAGE_OCC_D64 4
 #endif
+#ifndef SAGE_OCC_D256
+#define SAGE_OCC_D256 2
+#endif
 template <int D, int GM, int PVF> constexpr int attn_occupancy() {
-  if (D == 256) return 1;
+  if (D == 256) return SAGE_OCC_D256;
   if (D == 128) return (GM == 0 && PVF != PV_INT8) ? SAGE_OCC_D128 : 2;
   return GM == 0 && PVF != PV_INT8 ? SAGE_OCC_D64 : (SAGE_OCC_D64 >= 3 ? 3 : 2);
 }
@@ -419,12 +424,9 @@ __device__ __forceinline__ size_t lse_index(const AttnParams& p, const Seq& sq, 
   return ((size_t)b * p.H + h) * p.N + r;
 }
 
-// d = 256: the cross-block accumulator O alone is 128 registers per lane, so a workgroup takes a CU's whole register
-// file (one wavefront per SIMD, 512 registers each: the accumulators of the matrix instructions live in the second
-// half) and its three LDS stages are 88 KB.
 template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, int PVF, bool SPLIT = false>
 __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fwd(const AttnParams p) {
-  constexpr bool OCC3 = attn_occupancy<D, GM, PVF>() >= 3;     // the form without a software pipeline
+  constexpr bool OCC3 = attn_occupancy<D, GM, PVF>() >= (D == 256 ? 2 : 3);     // the form without a software pipeline
   constexpr int KSC = GM == 0 ? 4 : (GM == 1 ? 16 : 64);    // key scales per block
   constexpr int QG = GM == 0 ? QGROUP : 1;                  // queries per scale
   constexpr int CT = D / 32;          // 32-channel tiles of the output
@@ -433,7 +435,10 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   constexpr int CPT = KC / 256;       // V^ chunks per thread per block copy (2 or 1)
   constexpr int CPTK = (KCK + 255) / 256;   // K^ copy rounds (the last one may skip some wavefronts)
   constexpr int MINC = KCK / 256 + CPT;     // copies every wavefront issues per block, at least
-  constexpr int NST = 3;              // LDS stages: block j is read while j+1 and j+2 arrive
+  // LDS stages: block j is read while j+1 and j+2 arrive (d = 256 without the software pipeline: two stages of
+  // 29 KB, so that two workgroups fit a CU)
+  constexpr int NST = (D == 256 && attn_occupancy<D, GM, PVF>() >= 2) ? 2 : 3;
+  constexpr int PD = NST - 1;         // copies run this many blocks ahead
   constexpr int XC = 32;              // chunks of the small part: 64 Delta-S floats, then up to 64 key scales
   constexpr int STAGE = KCK + KC + XC;   // chunks per stage: K^, V^, small part
   __shared__ v4i lds[NST][STAGE];
@@ -560,7 +565,7 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   }
   if constexpr (COPIES_FIRST) {
     issue(j_begin, 0);
-    if (j_begin + 1 < nblk) issue(j_begin + 1, 1);
+    if (PD > 1 && j_begin + 1 < nblk) issue(j_begin + 1, 1);
   }
 
   // ---- this wavefront's Q^ operands (registers, for the whole kernel) and scale ----
@@ -680,7 +685,7 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
     if constexpr (!OCC3) wait_all();
   } else {
     issue(j_begin, 0);
-    if (j_begin + 1 < nblk) { issue(j_begin + 1, 1); if constexpr (!OCC3) wait_all_but_newest(); } else { if constexpr (!OCC3) wait_all(); }
+    if (PD > 1 && j_begin + 1 < nblk) { issue(j_begin + 1, 1); if constexpr (!OCC3) wait_all_but_newest(); } else { if constexpr (!OCC3) wait_all(); }
   }
   float alpha, m_sub = -INFINITY;     // of block j (m_sub: nothing summed yet)
   Factors<GM> fj;                     // block j's dequantization factors (used again by the fused exponent)
@@ -774,10 +779,10 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
 #define SAGE_BODY3(MASKED_)                                                                          \
   do {                                                                                               \
     const int nx1 = cur == NST - 1 ? 0 : cur + 1;                                                    \
-    const int nx2 = nx1 == NST - 1 ? 0 : nx1 + 1;                                                    \
+    const int nxp = PD == 1 ? nx1 : (nx1 == NST - 1 ? 0 : nx1 + 1);      /* stage of block j + PD */  \
     wait_all();                                                                                      \
     __syncthreads();                                                                                 \
-    if (j + 2 < nblk) issue(j + 2, nx2);                                                             \
+    if (j + PD < nblk) issue(j + PD, nxp);                                                           \
     read_k(cur);                                                                                     \
     read_ds(cur, 0);                                                                                 \
     read_ds(cur, 1);                                                                                 \
@@ -809,10 +814,10 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   // causal only: blocks past this wavefront's last query - keep up the copies and the barriers
   for (; j < nblk; ++j) {
     const int nx1 = cur == NST - 1 ? 0 : cur + 1;
-    const int nx2 = nx1 == NST - 1 ? 0 : nx1 + 1;
+    const int nxp = PD == 1 ? nx1 : (nx1 == NST - 1 ? 0 : nx1 + 1);
     wait_all();
     __syncthreads();
-    if (j + 2 < nblk) issue(j + 2, nx2);
+    if (j + PD < nblk) issue(j + PD, nxp);
     cur = nx1;
   }
 #undef SAGE_BODY3
