@@ -233,6 +233,18 @@ typedef struct sage_quant_out {
    take.  Reads k and v only (q and out may be NULL); needs the workspace of sage_attn_workspace_bytes(args). */
 int sage_attn_kv_stats(const sage_attn_args* args, float* k_mean_out, float* v_scale_out);
 
+/* The same statistics kept as running state of a K / V that grows (a KV cache): args->k, args->v hold only the NEW
+   tokens, [B, H_kv, N_kv, d] (N_kv = the chunk's length; q, out may be NULL), n_before is the number of tokens already
+   accumulated (0: the state is initialised from this chunk).  k_sum_state [B, H_kv, d] f64 (exact column sums of
+   K, Eq. 2) and v_absmax_state [B, H_kv, d] f32 (column maxima of |V|, Sec. 3.3) are read and updated; k_mean_out and
+   v_scale_out, [B, H_kv, d] f32, receive mean(K) and delta_V of all n_before + N_kv tokens in the form k_mean_in /
+   v_scale_in take.  The sums are exact, so any split into chunks gives bit for bit what sage_attn_kv_stats gives on
+   the whole.  With it the keeper of a cache reads old keys and values once per attention call (in the quantizers)
+   instead of twice.  Fixed-length batches only; not with SAGE_FLAG_SMOOTH_V / SAGE_FLAG_NO_SMOOTH_K; needs the
+   workspace of sage_attn_workspace_bytes(args); n_before + N_kv <= 2^24. */
+int sage_attn_kv_stats_update(const sage_attn_args* args, double* k_sum_state, float* v_absmax_state, long long n_before,
+                              float* k_mean_out, float* v_scale_out);
+
 /* Runs the preprocessing of Algorithm 1 (as sage_attn_prologue) and then copies its results
    out of the kernel-private packed workspace layout into `out`. */
 int sage_attn_quant(const sage_attn_args* args, const sage_quant_out* out);

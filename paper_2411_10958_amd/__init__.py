@@ -7,7 +7,7 @@ PyTorch is used only to own device memory and streams.
 from .binding import (make_varlen_args, SAGE_MODE_INT4_FP8, SAGE_MODE_INT8_FP8, SAGE_DT_FP16, SAGE_DT_BF16,
                       SageError, lib_path, load_library, sage_attn_workspace_bytes, sage_attn_kv_splits,
                       sage_attn_fwd_ex, sage_attn_prologue, sage_attn_core, sage_attn_fwd, sage_attn_fwd_static,
-                      sage_attn_release, sage_attn_quant, sage_attn_kv_stats, sage_attn_debug_qk, sage_attn_debug_mfma_fp8, sage_status_string,
+                      sage_attn_release, sage_attn_quant, sage_attn_kv_stats, sage_attn_kv_stats_update, sage_attn_debug_qk, sage_attn_debug_mfma_fp8, sage_status_string,
                       make_args)
 
 __all__ = [n for n in dir() if n.startswith(("sage_", "SAGE_", "Sage"))] + ["lib_path", "load_library", "make_args", "make_varlen_args"]

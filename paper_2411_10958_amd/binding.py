@@ -80,6 +80,9 @@ def load_library():
         lib.sage_attn_release.restype = None
         lib.sage_attn_kv_stats.restype = ctypes.c_int
         lib.sage_attn_kv_stats.argtypes = [P(sage_attn_args), ctypes.c_void_p, ctypes.c_void_p]
+        lib.sage_attn_kv_stats_update.restype = ctypes.c_int
+        lib.sage_attn_kv_stats_update.argtypes = [P(sage_attn_args), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_longlong,
+                                                  ctypes.c_void_p, ctypes.c_void_p]
         lib.sage_attn_quant.restype = ctypes.c_int
         lib.sage_attn_quant.argtypes = [P(sage_attn_args), P(sage_quant_out)]
         lib.sage_attn_debug_qk.restype = ctypes.c_int
@@ -278,6 +281,30 @@ def sage_attn_kv_stats(k, v, layout="HND", pv_format="e4m3", cu_seqlens_k=None, 
         raise SageError(st, "sage_attn_kv_stats")
     del keep
     return km, vs
+
+
+def sage_attn_kv_stats_update(k_new, v_new, state, layout="HND", pv_format="e4m3", workspace=None, stream=None):
+    """Running statistics of a growing K / V.  k_new, v_new: the new tokens [B, H_kv, n_new, d]; state: None for the
+    first chunk, else what the previous call returned.  Returns (k_mean, v_scale, state): the statistics of everything
+    accumulated so far (as `kv_stats` takes them) and the updated state (k_sum float64, v_absmax float32, token count)."""
+    a = make_args(k_new, k_new, v_new, None, workspace=workspace, stream=stream, layout=layout, pv_format=pv_format)
+    keep = _alloc_workspace(a, k_new.device) if workspace is None else workspace
+    shape = (a.B, a.H_kv, a.d)
+    if state is None:
+        ks = torch.empty(shape, dtype=torch.float64, device=k_new.device)
+        vm = torch.empty(shape, dtype=torch.float32, device=k_new.device)
+        n_before = 0
+    else:
+        ks, vm, n_before = state
+    km = torch.empty(shape, dtype=torch.float32, device=k_new.device)
+    vs = torch.empty_like(km)
+    st = load_library().sage_attn_kv_stats_update(ctypes.byref(a), ctypes.c_void_p(ks.data_ptr()), ctypes.c_void_p(vm.data_ptr()),
+                                                  ctypes.c_longlong(n_before), ctypes.c_void_p(km.data_ptr()),
+                                                  ctypes.c_void_p(vs.data_ptr()))
+    if st != 0:
+        raise SageError(st, "sage_attn_kv_stats_update")
+    del keep
+    return km, vs, (ks, vm, n_before + a.N_kv)
 
 
 def sage_attn_release():

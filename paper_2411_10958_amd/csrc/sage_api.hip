@@ -235,6 +235,27 @@ int sage_attn_kv_stats(const sage_attn_args* args, float* k_mean_out, float* v_s
   return hip_status(launch_kv_stats(D, P, (hipStream_t)args->stream));
 }
 
+int sage_attn_kv_stats_update(const sage_attn_args* args, double* k_sum_state, float* v_absmax_state, long long n_before,
+                              float* k_mean_out, float* v_scale_out) {
+  if (!k_sum_state || !v_absmax_state || !k_mean_out || !v_scale_out || n_before < 0) return SAGE_ERR_INVALID_ARG;
+  if ((((uintptr_t)k_mean_out | (uintptr_t)v_scale_out | (uintptr_t)v_absmax_state) & 15u) != 0 || ((uintptr_t)k_sum_state & 7u) != 0)
+    return SAGE_ERR_INVALID_ARG;
+  Dims D;
+  int st = validate(args, &D, false);
+  if (st != SAGE_OK) return st;
+  if (!args->k || !args->v) return SAGE_ERR_INVALID_ARG;
+  if (args->cu_seqlens_q || args->k_mean_in || (args->flags & (SAGE_FLAG_SMOOTH_V | SAGE_FLAG_NO_SMOOTH_K)) != 0)
+    return SAGE_ERR_UNSUPPORTED;
+  if (n_before + (long long)D.Nk > MAX_TOKENS) return SAGE_ERR_UNSUPPORTED;
+  const Workspace w = make_workspace(D);
+  if ((st = check_workspace(args, w)) != SAGE_OK) return st;
+  Ptrs P = make_ptrs(args->q, args->k, args->v, args->out, args->workspace, w);
+  P.k_mean = k_mean_out;
+  P.v_scale = v_scale_out;
+  return hip_status(launch_kv_stats_update(D, P, k_sum_state, v_absmax_state, n_before == 0, n_before + (long long)D.Nk,
+                                           (hipStream_t)args->stream));
+}
+
 int sage_attn_quant(const sage_attn_args* args, const sage_quant_out* out) {
   if (!out) return SAGE_ERR_INVALID_ARG;
   Dims D;

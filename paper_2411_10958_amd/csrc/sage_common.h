@@ -291,6 +291,8 @@ template <bool BF16> __device__ inline unsigned pack16x2(float a, float b) {
 // launchers (defined in the .hip files)
 hipError_t launch_prologue(const Dims& D, const Ptrs& P, hipStream_t s);
 hipError_t launch_kv_stats(const Dims& D, const Ptrs& P, hipStream_t s);   // writes P.k_mean, P.v_scale
+hipError_t launch_kv_stats_update(const Dims& D, const Ptrs& P, double* state_sum, float* state_max, int fresh,
+                                  long long n_total, hipStream_t s);
 hipError_t launch_attention(const Dims& D, const Ptrs& P, hipStream_t s);
 hipError_t launch_unpack(const Dims& D, const Ptrs& P, const void* quant_out, hipStream_t s);
 hipError_t launch_debug_mfma_fp8(const void* a, const void* b, const float* c, float* d, hipStream_t s);

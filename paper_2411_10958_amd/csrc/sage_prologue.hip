@@ -258,6 +258,31 @@ __global__ void k_finalize_stats(const double* __restrict__ k_sum, const double*
     else v_scale[i] = __fdiv_rn(vm, code_max);
   }
 }
+// Running statistics of a growing K / V (a KV cache that is appended to): the exact column sums of K and the column
+// maxima of |V| are kept as state, a new chunk's partial results are added to them, and mean(K), delta_V of the whole
+// are written.  Float64 sums of 16-bit values are exact, so the state after any sequence of chunks equals the one
+// pass over everything, bit for bit.  fresh != 0: the state is initialised from this chunk.
+__global__ void k_accumulate_stats(const double* __restrict__ k_sum, const unsigned* __restrict__ v_max,
+                                   double* __restrict__ state_sum, float* __restrict__ state_max,
+                                   float* __restrict__ k_mean, float* __restrict__ v_scale, int n, int d, int nchunk,
+                                   int fresh, long long n_total, float code_max) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    const int head = i / d, c = i - head * d;
+    const size_t p0 = (size_t)head * nchunk * d + c;
+    double ks = fresh ? 0.0 : state_sum[i];
+    float vm = fresh ? 0.0f : state_max[i];
+    for (int ch = 0; ch < nchunk; ++ch) {
+      ks += k_sum[p0 + (size_t)ch * d];
+      vm = fmaxf(vm, __uint_as_float(v_max[p0 + (size_t)ch * d]));
+    }
+    state_sum[i] = ks;
+    state_max[i] = vm;
+    k_mean[i] = n_total > 0 ? (float)(ks / (double)n_total) : 0.0f;
+    v_scale[i] = __fdiv_rn(vm, code_max);
+  }
+}
+
 __global__ void k_finalize_vscale(const unsigned* __restrict__ v_max, float* __restrict__ v_scale, int n, int d,
                                   int nchunk, float code_max) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1001,6 +1026,29 @@ hipError_t launch_kv_stats(const Dims& D, const Ptrs& P, hipStream_t s) {
   if (D.d == 256)      { if (D.bf16) launch_stats_t<true, 256>(D, P, s); else launch_stats_t<false, 256>(D, P, s); }
   else if (D.d == 128) { if (D.bf16) launch_stats_t<true, 128>(D, P, s); else launch_stats_t<false, 128>(D, P, s); }
   else                 { if (D.bf16) launch_stats_t<true, 64>(D, P, s); else launch_stats_t<false, 64>(D, P, s); }
+  return hipGetLastError();
+}
+
+template <bool BF16, int D>
+static void launch_stats_update_t(const Dims& Dm, const Ptrs& P, double* state_sum, float* state_max, int fresh,
+                                  long long n_total, hipStream_t s) {
+  const int BHkv = Dm.B * Dm.Hkv, nstat = BHkv * Dm.d;
+  const dim3 gstat((Dm.Nk + STAT_ROWS - 1) / STAT_ROWS, BHkv);
+  const TensorMap km = make_tensor_map(Dm.nhd, Dm.Hkv, Dm.Nk, Dm.d, false);
+  const float code_max = Dm.pvf == PV_INT8 ? INT8_PV_MAX : (Dm.pvf == PV_E5M2 ? E5M2_MAX : E4M3_MAX);
+  k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>((const unsigned short*)P.k, (const unsigned short*)P.v, P.k_sum, nullptr,
+                                                    P.v_max, Dm.N, Dm.Nk, km, Dm.seq);
+  k_accumulate_stats<<<(nstat + 255) / 256, 256, 0, s>>>(P.k_sum, P.v_max, state_sum, state_max, P.k_mean, P.v_scale, nstat,
+                                                         Dm.d, (int)gstat.x, fresh, n_total, code_max);
+}
+
+hipError_t launch_kv_stats_update(const Dims& D, const Ptrs& P, double* state_sum, float* state_max, int fresh,
+                                  long long n_total, hipStream_t s) {
+#define SAGE_SU(BF, DD) launch_stats_update_t<BF, DD>(D, P, state_sum, state_max, fresh, n_total, s)
+  if (D.d == 256)      { if (D.bf16) SAGE_SU(true, 256); else SAGE_SU(false, 256); }
+  else if (D.d == 128) { if (D.bf16) SAGE_SU(true, 128); else SAGE_SU(false, 128); }
+  else                 { if (D.bf16) SAGE_SU(true, 64); else SAGE_SU(false, 64); }
+#undef SAGE_SU
   return hipGetLastError();
 }
 

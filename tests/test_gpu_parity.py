@@ -292,6 +292,37 @@ def test_supplied_kv_statistics(N, Nk, d, dtype, H, Hkv, causal, pv, mode):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("d,dtype,pv", [(128, "bf16", "e4m3"), (64, "fp16", "e5m2"), (256, "bf16", "e4m3")])
+def test_running_kv_statistics_of_a_growing_cache(d, dtype, pv):
+    """Statistics kept as running state while K and V grow chunk by chunk: after every chunk mean(K) and delta_V equal
+    the oracle's on the prefix, bit for bit, and at the end the one-pass statistics; attention with them equals the
+    plain call."""
+    pa = _pa()
+    N, Nk, H, Hkv = 40, 1501, 4, 2
+    spec = _spec(N, d, dtype, H, Hkv, B=2, causal=True).with_(N_kv=Nk)
+    data, (q, k, v) = _gpu_inputs(spec)
+    state, n = None, 0
+    for n_new in (700, 800, 1):
+        km, vs, state = pa.sage_attn_kv_stats_update(k[:, :, n:n + n_new].contiguous(), v[:, :, n:n + n_new].contiguous(),
+                                                     state, pv_format=pv)
+        n += n_new
+        torch.cuda.synchronize()
+        assert state[2] == n
+        for b in range(2):
+            for hk in range(Hkv):
+                kbar = so.token_mean(data["k"][b, hk][:n])
+                dv = so.quantize_v(data["v"][b, hk][:n], pv)[0]
+                assert np.array_equal(km[b, hk].cpu().numpy(), kbar), f"mean(K) of the first {n} tokens"
+                assert np.array_equal(vs[b, hk].cpu().numpy(), dv), f"delta_V of the first {n} tokens"
+    km1, vs1 = pa.sage_attn_kv_stats(k, v, pv_format=pv)
+    torch.cuda.synchronize()
+    assert torch.equal(km, km1) and torch.equal(vs, vs1)
+    plain = pa.sage_attn_fwd_ex(q, k, v, causal=True, pv_format=pv)
+    out = pa.sage_attn_fwd_ex(q, k, v, causal=True, pv_format=pv, kv_stats=(km, vs))
+    torch.cuda.synchronize()
+    assert torch.equal(out, plain)
+
+
 def test_supplied_kv_statistics_of_a_packed_batch():
     pa = _pa()
     lens_q, lens_k, H, Hkv, d = [70, 200, 129], [300, 64, 129], 4, 2, 128
