@@ -32,12 +32,13 @@ def mix_peak(mode, pv_format="e4m3"):
 
 # Vector-ALU ceiling of Algorithm 1's inner loop on this chip: per score the loop needs, per lane, one multiply-add
 # (dequantization + Delta-S), half a three-input maximum, one subtraction, one exponential, one addition (row sum)
-# and half a packed FP8 conversion.  Issued back to back by the two wavefronts that share a SIMD - in that mix,
-# nothing else running - these ten instructions per two scores take VALU_CYCLES_PER_2_SCORES cycles of the SIMD
-# (measured with a working probe; the instruction classes alone: add / sub / mul 3.1, fma 3.7, max3 5.2, exp 8.7,
-# packed FP8 conversion 8.7 cycles per wavefront instruction at two wavefronts per SIMD).  A wavefront instruction
-# covers 64 lanes, so one SIMD finishes 128 scores per that many cycles; a score is 4 d operations.
-VALU_CYCLES_PER_2_SCORES = 61.3
+# and half a packed FP8 conversion.  Issued back to back in that mix, nothing else running, these ten instructions
+# per two scores take 69.3 / 52.5 / 48.7 cycles of a SIMD with 2 / 3 / 4 wavefronts resident (measured by
+# paper_2411_10958_amd/csrc/probe_valu_issue.hip, summary under profiles/; the classes alone at 4 wavefronts: add /
+# sub / mul / fma 2.6 to 2.9, max3 4.5, exp 8.4, packed FP8 conversion 8.4 cycles per wavefront instruction).  The
+# ceiling takes the best of them.  A wavefront instruction covers 64 lanes, so one SIMD finishes 128 scores per that
+# many cycles; a score is 4 d operations.
+VALU_CYCLES_PER_2_SCORES = 48.7
 N_SIMD = 1024
 CLOCK_GHZ = 2.4
 

@@ -77,7 +77,7 @@ int main() {
   CK(hipMalloc(&g_ticks, 256 * sizeof(long long)));
   printf("core cycles per wavefront instruction issued by one SIMD (median of 256 workgroups, one per CU)\n");
   printf("%-32s %10s %10s %10s %10s\n", "wavefronts per SIMD:", "1", "2", "3", "4");
-  double mix2 = 0;
+  double mix[4] = {0, 0, 0, 0};
   for (int kind = 0; kind < NKIND; ++kind) {
     double c[4];
     for (int w = 1; w <= 4; ++w) {
@@ -94,10 +94,13 @@ int main() {
         default: c[w - 1] = cycles<MIX>(threads); break;
       }
     }
-    if (kind == MIX) mix2 = c[1];
+    if (kind == MIX) for (int w = 0; w < 4; ++w) mix[w] = c[w];
     printf("%-32s %10.2f %10.2f %10.2f %10.2f\n", NAMES[kind], c[0], c[1], c[2], c[3]);
   }
-  printf("softmax mix at 2 wavefronts per SIMD: %.1f cycles per 2 scores of 64 lanes -> ceiling of the loop's vector work at "
-         "d = 128, 1024 SIMDs, 2.4 GHz: %.0f TOP/s\n", 10.0 * mix2, 1024 * 2.4e9 * 128.0 / (10.0 * mix2) * 512.0 / 1e12);
+  printf("ceiling of the loop's vector work (a wavefront instruction covers 64 lanes; 4 d operations per score; 1024 SIMDs, "
+         "2.4 GHz):\n");
+  for (int w = 1; w < 4; ++w)
+    printf("  %d wavefronts per SIMD: %.1f cycles per 2 scores of 64 lanes -> %.0f TOP/s at d = 128\n", w + 1, 10.0 * mix[w],
+           1024 * 2.4e9 * 128.0 / (10.0 * mix[w]) * 512.0 / 1e12);
   return 0;
 }

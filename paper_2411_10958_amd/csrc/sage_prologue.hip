@@ -248,7 +248,8 @@ __global__ void k_finalize_stats(const double* __restrict__ k_sum, const double*
     const size_t p0 = (size_t)head * nchunk * d + c;
     double ks = 0.0, vs = 0.0;
     float vm = 0.0f;
-    for (int ch = 0; ch < nchunk; ++ch) {
+#pragma unroll 8
+    for (int ch = 0; ch < nchunk; ++ch) {      // (unrolled so that the loads of eight chunks are in flight together)
       ks += k_sum[p0 + (size_t)ch * d];
       if (v_sum) vs += v_sum[p0 + (size_t)ch * d];
       else vm = fmaxf(vm, __uint_as_float(v_max[p0 + (size_t)ch * d]));
@@ -272,6 +273,7 @@ __global__ void k_accumulate_stats(const double* __restrict__ k_sum, const unsig
     const size_t p0 = (size_t)head * nchunk * d + c;
     double ks = fresh ? 0.0 : state_sum[i];
     float vm = fresh ? 0.0f : state_max[i];
+#pragma unroll 8
     for (int ch = 0; ch < nchunk; ++ch) {
       ks += k_sum[p0 + (size_t)ch * d];
       vm = fmaxf(vm, __uint_as_float(v_max[p0 + (size_t)ch * d]));
@@ -609,22 +611,39 @@ __global__ void __launch_bounds__(256, D == 256 ? 2 : 4) k_quant_k(const unsigne
   // Delta-S passes: (query head of the group, 32 query blocks); the first pass's block means are
   // requested before the K rows so that both round trips overlap
   constexpr int QPT = DS_QROWS * (D / 4) / 256;    // float4 pieces per thread per pass
-  const int npass_h = max((nQs + DS_QROWS - 1) / DS_QROWS, 1);
-  const int npass = INT4 ? G * npass_h : 0;
+  // A sequence with fewer than 32 query blocks (a decode step, a short chunk against a long cache) would leave most
+  // rows of a pass empty: there the rows of all the query heads of the group are numbered through, head-major,
+  // and share passes ("flat").  Which pass a row sits in changes nothing in its value.
+  const bool flat = nQs < DS_QROWS;
+  const int npass_h = flat ? 1 : (nQs + DS_QROWS - 1) / DS_QROWS;
+  const int nrow = flat ? G * max(nQs, 0) : 0;
+  const int npass = INT4 ? (flat ? (nrow + DS_QROWS - 1) / DS_QROWS : G * npass_h) : 0;
   // under a causal mask (query r sees keys t <= r + coff) query block i sees this key block only
   // if 128 i + 127 + coff >= its first key: the passes of a head start with the one that holds
   // block (first key - coff) / 128
-  const int p_first = causal ? (max(kb * BKV - coff, 0) / BQ) / DS_QROWS : 0;
+  const int p_first = causal && !flat ? (max(kb * BKV - coff, 0) / BQ) / DS_QROWS : 0;
   auto next_pass = [&](int p) { return (p + 1) % npass_h >= p_first ? p + 1 : p + 1 + p_first; };
+  // row rr of pass p: query head (as a row of the [B H] axis) and query block; false for an empty row
+  auto pass_row = [&](int p, int rr, size_t* bh, int* i) {
+    if (flat) {
+      const int R = p * DS_QROWS + rr, g = R / max(nQs, 1);
+      *bh = bhkv * G + g;
+      *i = R - g * nQs;
+      return R < nrow;
+    }
+    *bh = bhkv * G + p / npass_h;
+    *i = (p % npass_h) * DS_QROWS + rr;
+    return *i < nQs;
+  };
   float4 qpre[QPT];
   auto load_q = [&](int p) {
-    const size_t bh = bhkv * G + p / npass_h;
-    const int i0 = (p % npass_h) * DS_QROWS;
 #pragma unroll
     for (int k = 0; k < QPT; ++k) {
       const int idx = t + k * 256, rr = idx / (D / 4), c4 = idx % (D / 4);
-      qpre[k] = (i0 + rr < nQs) ? *reinterpret_cast<const float4*>(q_mean + (bh * nQb + i0 + rr) * D + 4 * c4)
-                                : make_float4(0.f, 0.f, 0.f, 0.f);
+      size_t bh;
+      int i;
+      qpre[k] = pass_row(p, rr, &bh, &i) ? *reinterpret_cast<const float4*>(q_mean + (bh * nQb + i) * D + 4 * c4)
+                                         : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   };
   auto store_q = [&]() {
@@ -730,8 +749,13 @@ __global__ void __launch_bounds__(256, D == 256 ? 2 : 4) k_quant_k(const unsigne
       store_q();
       __syncthreads();
       if (next_pass(p) < npass) load_q(next_pass(p));   // next pass, in flight under the MFMAs
-      const size_t bh = bhkv * G + p / npass_h;
-      const int i0 = (p % npass_h) * DS_QROWS;
+      // rows 16..31 of the pass all empty (a short last pass): their chain of matrix instructions is left out
+      const bool upper = flat ? p * DS_QROWS + 16 < nrow : (p % npass_h) * DS_QROWS + 16 < nQs;
+      auto put = [&](int rr, float val) {
+        size_t bh;
+        int i;
+        if (pass_row(p, rr, &bh, &i)) delta_s[(bh * nQb + i) * (size_t)nKb * BKV + n0 + r] = val;
+      };
       if constexpr (DS32) {
         // Faster, approximate form (an option of the boundary): the same product on the FP32 form of the
         // instruction (result element v of lane l is row 4*(l/16) + v, column l%16).  FP32 accumulation:
@@ -743,15 +767,13 @@ __global__ void __launch_bounds__(256, D == 256 ? 2 : 4) k_quant_k(const unsigne
 #pragma unroll
           for (int cs = 0; cs < CPL; ++cs) {
             acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(s_q[r16][qcol + cs], x[cs], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(s_q[16 + r16][qcol + cs], x[cs], acc1, 0, 0, 0);
+            if (upper) acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(s_q[16 + r16][qcol + cs], x[cs], acc1, 0, 0, 0);
           }
         }
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          const int i = i0 + 4 * k4 + v;
-          float* out = delta_s + (bh * nQb + i) * (size_t)nKb * BKV + n0 + r;
-          if (i < nQs) out[0] = __fmul_rn(kappa, acc0[v]);
-          if (i + 16 < nQs) out[(size_t)16 * nKb * BKV] = __fmul_rn(kappa, acc1[v]);
+          put(4 * k4 + v, __fmul_rn(kappa, acc0[v]));
+          if (upper) put(16 + 4 * k4 + v, __fmul_rn(kappa, acc1[v]));
         }
       } else {
         v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
@@ -761,15 +783,13 @@ __global__ void __launch_bounds__(256, D == 256 ? 2 : 4) k_quant_k(const unsigne
             asm volatile("" : "+v"(x[cs]));            // keeps the widening inside the pass loop
             const double bk = (double)x[cs];
             acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[r16][qcol + cs], bk, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[16 + r16][qcol + cs], bk, acc1, 0, 0, 0);
+            if (upper) acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)s_q[16 + r16][qcol + cs], bk, acc1, 0, 0, 0);
           }
         }
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          const int i = i0 + 4 * v + k4;
-          float* out = delta_s + (bh * nQb + i) * (size_t)nKb * BKV + n0 + r;
-          if (i < nQs) out[0] = (float)(kap * acc0[v]);
-          if (i + 16 < nQs) out[(size_t)16 * nKb * BKV] = (float)(kap * acc1[v]);
+          put(4 * v + k4, (float)(kap * acc0[v]));
+          if (upper) put(16 + 4 * v + k4, (float)(kap * acc1[v]));
         }
       }
     }

@@ -49,6 +49,8 @@ CASES = [
     (17, 128, "fp16", 1, 1, False),     # shorter than one group-of-16 plus one
     (300, 256, "bf16", 2, 1, True),     # head dimension 256: ragged + causal + grouped KV heads
     (256, 256, "fp16", 2, 2, False),
+    (1300, 128, "bf16", 8, 2, True),    # 11 query blocks x 4 heads of a KV group: the Delta-S rows of the group share passes
+    (2100, 64, "fp16", 4, 2, False),    # 17 x 2 rows: a second pass with two rows
 ]
 
 
@@ -102,7 +104,9 @@ def test_attention_output_matches_oracle(N, d, dtype, H, Hkv, causal, mode):
     out = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode)
     torch.cuda.synchronize()
     got = wl.from_torch(out)
-    parity.check_heads(got, data, causal, mode, dtype)
+    # (few tiles and many keys: the library splits the key range by itself, and says so)
+    splits = pa.sage_attn_kv_splits(pa.make_args(q, k, v, causal=causal, mode=mode))
+    parity.check_heads(got, data, causal, mode, dtype, splits=splits)
     # accuracy against the unquantized definition is reported, not asserted tightly
     g = H // Hkv
     full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
