@@ -108,11 +108,13 @@ def main():
     ap.add_argument("--preroll-ms", type=float, default=60.0,
                     help="untimed back-to-back steps for at least this long before the warm-up steps: the chip needs some "
                          "tens of milliseconds of work before its clocks settle (5 steps of 1 ms measure 8 %% low)")
-    ap.add_argument("--workload", default="prefill4k")
+    ap.add_argument("--workload", default="prefill4k",
+                    help="a configuration of workloads/inputs.py, or an ad-hoc shape such as b4h32n8192d128c "
+                         "(batch, heads, tokens, head dimension, c = causal / f = full)")
     ap.add_argument("--mode", default="int4_fp8", choices=["int4_fp8", "int8_fp8"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the causal N >= 8192 sweep")
-    ap.add_argument("--sweep", default="causal8k,causal16k,causal32k", help="workloads of the sweep (both modes each)")
+    ap.add_argument("--sweep", default="causal8k,causal16k,causal32k", help="workloads of the sweep (both modes each; names as for --workload)")
     ap.add_argument("--cpu-heads", type=int, default=32, help="(batch, head) slices of the CPU-baseline sample")
     ap.add_argument("--group-map", default="lane", choices=list(GMAPS),
                     help="quantization granularity of Q and K: the default lane groups, one scale per block, "
@@ -141,7 +143,7 @@ def main():
 
     import numpy as np
     import workloads as wl
-    spec = wl.CONFIGS[args.workload]
+    spec = wl.spec_of(args.workload)
     oracle_kw = dict(smooth_v_on=args.smooth_v, gmap=GMAPS[args.group_map], pv_fmt=args.pv_format,
                      smooth_k_on=not args.no_smooth_k, smooth_q_on=not args.no_smooth_q and args.mode == "int4_fp8")
     # The CPU leg runs first: its worker processes are forked, which must not happen once this process holds a GPU.
@@ -332,7 +334,7 @@ def main():
         torch.cuda.empty_cache()
         sweep = []
         for name in [s for s in args.sweep.split(",") if s]:
-            sp = wl.CONFIGS[name]
+            sp = wl.spec_of(name)
             d_in = None
             for mode in ("int4_fp8", "int8_fp8"):
                 d_in, a2, keep2 = prepare(sp, mode, False) if d_in is None else (d_in,) + _reuse(pa, torch, sp, mode, keep2)

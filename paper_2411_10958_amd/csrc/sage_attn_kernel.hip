@@ -446,26 +446,37 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
 
   // XCD-aware tile order: consecutive workgroup ids land on different XCDs (8 of them), so
   // give every XCD a contiguous range of tiles - tiles of one head then share one L2.
-  // Under a causal mask a tile's work grows with its position, and workgroups start in index order: when an XCD's
-  // range holds whole heads, its tiles are issued heaviest first ACROSS those heads (all their last tiles, then all
-  // their last but one, ...) instead of head by head, where the heavy tiles of the last head would start late and
-  // finish long after the rest (measured at N = 8192, where a range is four heads of 64 tiles: 13 % of the kernel's
-  // time; 1.5 % at N = 16384).  Longer sequences keep the head-by-head order: the imbalance shrinks with the tile
-  // count while four interleaved heads no longer share an XCD's L2 (N = 32768: 1.5 % slower interleaved).
+  // Under a causal mask a tile's work grows with its position, and workgroups start in index order.  There the
+  // heads are taken in groups of 32 and a group's tiles are issued heaviest first ACROSS its heads (all their last
+  // tiles, then all their last but one, ...), workgroup i taking the i-th tile of that list: every XCD then gets
+  // every eighth tile of each weight - an equal share of the work whatever the head count - and, with 32 heads in a
+  // group, the tiles of the same four heads.  Head by head the heavy tiles of an XCD's last head would start late
+  // and finish long after the rest (13 % of the kernel's time at N = 8192, 1.5 % at N = 16384), and contiguous
+  // ranges that do not hold whole heads (a head count that 8 does not divide) differ in work by up to a factor of
+  // three.  More than four heads per XCD at a time no longer share its L2 once a head's codes exceed about 2 MB
+  // (16 interleaved heads of 16384 keys ran 13 % slower than four; up to 4096 keys 16 are 4 % faster than four).
+  // Sequences beyond 16384 tokens keep the head-by-head order in contiguous ranges: the imbalance shrinks with the
+  // tile count while four interleaved heads no longer share an XCD's L2 (N = 32768: 1.5 % slower interleaved).
   const int n_wg = SPLIT ? p.total_tiles * p.splits : p.total_tiles;
   const int per_xcd = (n_wg + 7) / 8;
   const int in_xcd = blockIdx.x / 8;
   int tile = (blockIdx.x % 8) * per_xcd + in_xcd;
-  if (tile >= n_wg) return;
   int split = 0;
-  if constexpr (SPLIT) { split = tile % p.splits; tile /= p.splits; }
   int bh, qb;
-  if (!SPLIT && CAUSAL && p.nQb <= 128 && per_xcd % p.nQb == 0) {
-    const int heads_here = per_xcd / p.nQb;
-    bh = (blockIdx.x % 8) * heads_here + in_xcd % heads_here;
-    qb = p.nQb - 1 - in_xcd / heads_here;
-    tile = bh * p.nQb;      // (only compared with the tile count below)
+  if (!SPLIT && CAUSAL && p.nQb <= 128) {
+    tile = blockIdx.x;
+    if (tile >= n_wg) return;
+    const int BH = p.total_tiles / p.nQb;
+    const int GS = p.nQb <= 32 ? 128 : 32;                      // heads per group
+    const int full = BH / GS;                                   // groups of GS heads; the last one may be smaller
+    int grp = tile / (GS * p.nQb), g = GS;
+    if (grp >= full) { grp = full; g = BH - full * GS; }
+    const int within = tile - grp * GS * p.nQb;
+    bh = grp * GS + within % g;
+    qb = p.nQb - 1 - within / g;
   } else {
+    if (tile >= n_wg) return;
+    if constexpr (SPLIT) { split = tile % p.splits; tile /= p.splits; }
     bh = tile / p.nQb;
     qb = CAUSAL ? p.nQb - 1 - tile % p.nQb : tile % p.nQb;   // heavy tiles first
   }

@@ -62,6 +62,19 @@ CONFIGS = {
 }
 
 
+def spec_of(name):
+    """A named configuration, or an ad-hoc shape written b<B>h<H>[k<H_kv>]n<N>[m<N_kv>]d<d><c|f> (c: causal, f: full),
+    e.g. b4h32n8192d128c: bf16, the value recipe of `prefill4k` (unit normal, channel offsets, 4 outlier channels)."""
+    if name in CONFIGS:
+        return CONFIGS[name]
+    import re
+    m = re.fullmatch(r"b(\d+)h(\d+)(?:k(\d+))?n(\d+)(?:m(\d+))?d(\d+)([cf])", name)
+    if not m:
+        raise KeyError(f"{name}: not a configuration ({', '.join(CONFIGS)}) and not of the form b4h32n8192d128c")
+    B, H, Hkv, N, Nkv, d = (int(x) if x else 0 for x in m.groups()[:6])
+    return WorkloadSpec(name, B, H, Hkv or H, N, d, "bf16", m.group(7) == "c", 3.0, 3.0, 4, 10.0, 1.0, 8, 0.0, Nkv)
+
+
 def round_to_dtype(x, dtype):
     """Round float32 values to the nearest fp16/bf16 value (ties to even), return float32."""
     x = np.ascontiguousarray(x, dtype=np.float32)
