@@ -455,19 +455,20 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   // ranges that do not hold whole heads (a head count that 8 does not divide) differ in work by up to a factor of
   // three.  More than four heads per XCD at a time no longer share its L2 once a head's codes exceed about 2 MB
   // (16 interleaved heads of 16384 keys ran 13 % slower than four; up to 4096 keys 16 are 4 % faster than four).
-  // Sequences beyond 16384 tokens keep the head-by-head order in contiguous ranges: the imbalance shrinks with the
-  // tile count while four interleaved heads no longer share an XCD's L2 (N = 32768: 1.5 % slower interleaved).
+  // Sequences beyond 16384 tokens take groups of 8 heads - one head per XCD at a time, heaviest tile first: four
+  // interleaved heads no longer share an XCD's L2 there (N = 32768: 1.5 % slower), and the equal shares still
+  // count when 8 does not divide the head count (28 heads of 32768 tokens: +4.5 %).
   const int n_wg = SPLIT ? p.total_tiles * p.splits : p.total_tiles;
   const int per_xcd = (n_wg + 7) / 8;
   const int in_xcd = blockIdx.x / 8;
   int tile = (blockIdx.x % 8) * per_xcd + in_xcd;
   int split = 0;
   int bh, qb;
-  if (!SPLIT && CAUSAL && p.nQb <= 128) {
+  if (!SPLIT && CAUSAL) {
     tile = blockIdx.x;
     if (tile >= n_wg) return;
     const int BH = p.total_tiles / p.nQb;
-    const int GS = p.nQb <= 32 ? 128 : 32;                      // heads per group
+    const int GS = p.nQb <= 32 ? 128 : (p.nQb <= 128 ? 32 : 8);  // heads per group
     const int full = BH / GS;                                   // groups of GS heads; the last one may be smaller
     int grp = tile / (GS * p.nQb), g = GS;
     if (grp >= full) { grp = full; g = BH - full * GS; }
