@@ -72,8 +72,15 @@ enum { SAGE_DT_FP16 = 0, SAGE_DT_BF16 = 1 };
    sequences); Delta-S is then within (d + 2) 2^-24 kappa sum_c |q_bar_c gamma(K)_c| of the exact value
    instead of correctly rounded.  That is far below the quantization noise of the method, but it moves
    the last bits of the scores, so once in about 10^5 scores the FP8 code of P~ comes out one step away
-   from what the exact Delta-S gives.  Off by default; ignored by the 8-bit mode. */
-enum { SAGE_FLAG_SMOOTH_V = 1, SAGE_FLAG_NO_SMOOTH_K = 2, SAGE_FLAG_NO_SMOOTH_Q = 4, SAGE_FLAG_FP32_DELTA_S = 8 };
+   from what the exact Delta-S gives.  Off by default; ignored by the 8-bit mode.
+   SAGE_FLAG_FP64_DELTA_S / SAGE_FLAG_DIGIT_DELTA_S: which exact form of the Delta-S product runs.  "Digit": both
+   factors are cut into 7-bit fixed-point digits (42 bits below each row's largest magnitude) and multiplied exactly on
+   the INT8 matrix unit; "FP64": the FP64 matrix instruction.  Both agree with the float64 inner product to the last bit
+   of the FP32 result except about once in 10^5 values.  With neither flag the library picks: digits, except when a key
+   block meets at most 16 block means ((H / H_kv) ceil(N / 128) <= 16), where one chain of FP64 instructions is cheaper.
+   Ignored by the 8-bit mode; FP32 wins over both, FP64 over digit. */
+enum { SAGE_FLAG_SMOOTH_V = 1, SAGE_FLAG_NO_SMOOTH_K = 2, SAGE_FLAG_NO_SMOOTH_Q = 4, SAGE_FLAG_FP32_DELTA_S = 8,
+       SAGE_FLAG_FP64_DELTA_S = 16, SAGE_FLAG_DIGIT_DELTA_S = 32 };
 /* Quantization granularity of Q and K (Sec. 3.2; the ablation of the paper's granularity table).
    SAGE_GROUPS_LANE: the default, the gfx950 counterpart of per-thread quantization (SAGE_Q_GROUP /
    SAGE_K_GROUP below).  SAGE_GROUPS_BLOCK: one scale per 128-query block and per 64-key block

@@ -15,6 +15,8 @@ SAGE_FLAG_SMOOTH_V = 1
 SAGE_FLAG_NO_SMOOTH_K = 2
 SAGE_FLAG_NO_SMOOTH_Q = 4
 SAGE_FLAG_FP32_DELTA_S = 8
+SAGE_FLAG_FP64_DELTA_S = 16
+SAGE_FLAG_DIGIT_DELTA_S = 32
 SAGE_GROUPS_LANE, SAGE_GROUPS_BLOCK, SAGE_GROUPS_FINE, SAGE_GROUPS_TOKEN, SAGE_GROUPS_TENSOR = 0, 1, 2, 3, 4
 _GROUPS = {"lane": 0, "block": 1, "fine": 2, "token": 3, "tensor": 4, 0: 0, 1: 1, 2: 2, 3: 3, 4: 4}
 _GROUP_SIZES = {0: (2, 16), 1: (2, 16), 2: (1, 4), 3: (1, 1), 4: (2, 16)}     # queries, keys per stored scale
@@ -118,8 +120,10 @@ def _ptr(t):
 
 def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
               smooth_v=False, group_map="lane", layout="HND", pv_format="e4m3", smooth_k=True, smooth_q=True,
-              fp32_delta_s=False, kv_stats=None, kv_splits=0):
-    """Fills a sage_attn_args from torch tensors q [B,H,N,d], k/v [B,H_kv,N_kv,d] (layout "HND") or
+              fp32_delta_s=False, kv_stats=None, kv_splits=0, delta_s=None):
+    """delta_s: None (the library picks between the two exact forms of the Delta-S product), "digits", "fp64", or "fp32"
+    (same as fp32_delta_s=True).
+    Fills a sage_attn_args from torch tensors q [B,H,N,d], k/v [B,H_kv,N_kv,d] (layout "HND") or
     q [B,N,H,d], k/v [B,N_kv,H_kv,d] (layout "NHD"), contiguous, on the GPU.  `workspace` is a uint8 GPU tensor (or None); `stream` a torch.cuda.Stream (None = the
     current one)."""
     for name, t in (("q", q), ("k", k), ("v", v)):
@@ -139,7 +143,8 @@ def make_args(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", wo
     a.B, a.H, a.H_kv, a.N, a.d = B, H, Hkv, N, d
     a.causal, a.sm_scale, a.mode, a.dtype = int(bool(causal)), float(sm_scale), _MODES[mode], _dtype_code(q)
     a.flags = ((SAGE_FLAG_SMOOTH_V if smooth_v else 0) | (0 if smooth_k else SAGE_FLAG_NO_SMOOTH_K) |
-               (0 if smooth_q else SAGE_FLAG_NO_SMOOTH_Q) | (SAGE_FLAG_FP32_DELTA_S if fp32_delta_s else 0))
+               (0 if smooth_q else SAGE_FLAG_NO_SMOOTH_Q) | (SAGE_FLAG_FP32_DELTA_S if (fp32_delta_s or delta_s == "fp32") else 0) |
+               (SAGE_FLAG_FP64_DELTA_S if delta_s == "fp64" else 0) | (SAGE_FLAG_DIGIT_DELTA_S if delta_s == "digits" else 0))
     a.group_map = _GROUPS[group_map]
     a.N_kv = Nk
     a.layout = _LAYOUTS[layout]
@@ -183,7 +188,7 @@ def _alloc_workspace(args, device):
 def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, stream=None,
                      smooth_v=False, group_map="lane", layout="HND", cu_seqlens_q=None, cu_seqlens_k=None,
                      max_seqlen_q=None, max_seqlen_k=None, return_lse=False, pv_format="e4m3", smooth_k=True,
-                     smooth_q=True, fp32_delta_s=False, kv_stats=None, kv_splits=0):
+                     smooth_q=True, fp32_delta_s=False, kv_stats=None, kv_splits=0, delta_s=None):
     """Whole forward pass.  Returns `out` (allocated if not given).  With cu_seqlens_q the batch is a packed
     variable-length one (see make_varlen_args) and `layout` is ignored.  With return_lse the result is
     (out, lse): lse float32 [B, H, N], or [H, total_q] for a variable-length batch."""
@@ -193,10 +198,10 @@ def sage_attn_fwd_ex(q, k, v, out=None, causal=False, sm_scale=0.0, mode="int4_f
         a = make_varlen_args(q, k, v, out, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, max_seqlen_k, causal=causal,
                              sm_scale=sm_scale, mode=mode, workspace=workspace, stream=stream, smooth_v=smooth_v,
                              group_map=group_map, pv_format=pv_format, smooth_k=smooth_k, smooth_q=smooth_q,
-                             fp32_delta_s=fp32_delta_s, kv_stats=kv_stats, kv_splits=kv_splits)
+                             fp32_delta_s=fp32_delta_s, kv_stats=kv_stats, kv_splits=kv_splits, delta_s=delta_s)
     else:
         a = make_args(q, k, v, out, causal, sm_scale, mode, workspace, stream, smooth_v, group_map, layout, pv_format,
-                      smooth_k, smooth_q, fp32_delta_s, kv_stats, kv_splits)
+                      smooth_k, smooth_q, fp32_delta_s, kv_stats, kv_splits, delta_s)
     lse = None
     if return_lse:
         shape = (a.H, q.shape[0]) if cu_seqlens_q is not None else (a.B, a.H, a.N)
@@ -313,11 +318,11 @@ def sage_attn_release():
 
 def sage_attn_quant(q, k, v, causal=False, sm_scale=0.0, mode="int4_fp8", workspace=None, want=None,
                     smooth_v=False, group_map="lane", pv_format="e4m3", smooth_k=True, smooth_q=True,
-                    fp32_delta_s=False, kv_stats=None):
+                    fp32_delta_s=False, kv_stats=None, delta_s=None):
     """Preprocessing only; returns (dict of torch tensors in plain layouts, args, workspace)."""
     a = make_args(q, k, v, None, causal, sm_scale, mode, workspace, smooth_v=smooth_v, group_map=group_map,
                   pv_format=pv_format, smooth_k=smooth_k, smooth_q=smooth_q, fp32_delta_s=fp32_delta_s,
-                  kv_stats=kv_stats)
+                  kv_stats=kv_stats, delta_s=delta_s)
     ws = _alloc_workspace(a, q.device) if workspace is None else workspace
     B, H, N, d = q.shape
     Hkv, Nk = k.shape[1], k.shape[2]

@@ -20,7 +20,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if (a->d != 64 && a->d != 128 && a->d != 256) return SAGE_ERR_UNSUPPORTED;
   if (a->mode != SAGE_MODE_INT4_FP8 && a->mode != SAGE_MODE_INT8_FP8) return SAGE_ERR_UNSUPPORTED;
   if (a->dtype != SAGE_DT_FP16 && a->dtype != SAGE_DT_BF16) return SAGE_ERR_UNSUPPORTED;
-  if ((a->flags & ~(SAGE_FLAG_SMOOTH_V | SAGE_FLAG_NO_SMOOTH_K | SAGE_FLAG_NO_SMOOTH_Q | SAGE_FLAG_FP32_DELTA_S)) != 0) return SAGE_ERR_UNSUPPORTED;
+  if ((a->flags & ~(SAGE_FLAG_SMOOTH_V | SAGE_FLAG_NO_SMOOTH_K | SAGE_FLAG_NO_SMOOTH_Q | SAGE_FLAG_FP32_DELTA_S | SAGE_FLAG_FP64_DELTA_S | SAGE_FLAG_DIGIT_DELTA_S)) != 0) return SAGE_ERR_UNSUPPORTED;
   if (a->group_map < SAGE_GROUPS_LANE || a->group_map > SAGE_GROUPS_TENSOR) return SAGE_ERR_UNSUPPORTED;
   if (a->layout != SAGE_LAYOUT_HND && a->layout != SAGE_LAYOUT_NHD) return SAGE_ERR_UNSUPPORTED;
   if (a->pv_format < SAGE_PV_E4M3 || a->pv_format > SAGE_PV_INT8) return SAGE_ERR_UNSUPPORTED;
@@ -51,6 +51,13 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   D->smooth_k = (a->flags & SAGE_FLAG_NO_SMOOTH_K) == 0;
   D->smooth_q = (a->flags & SAGE_FLAG_NO_SMOOTH_Q) == 0;
   D->ds32 = (a->flags & SAGE_FLAG_FP32_DELTA_S) != 0;
+  // Delta-S: digit products on the INT8 matrix unit, unless a key block meets at most 16 rows of block means (a decode
+  // step, a short chunk): one chain of FP64 matrix instructions is then cheaper than cutting the keys into digits
+  D->ds_mode = D->ds32 ? 1
+             : (a->flags & SAGE_FLAG_FP64_DELTA_S) != 0 ? 2
+             : (a->flags & SAGE_FLAG_DIGIT_DELTA_S) != 0 ? 0
+             : ((long long)(D->H / D->Hkv) * D->nQb <= 16 ? 2 : 0);
+
   D->stats_given = a->k_mean_in != nullptr;
   D->tensor_groups = a->group_map == SAGE_GROUPS_TENSOR;
   D->block_groups = a->group_map == SAGE_GROUPS_BLOCK || D->tensor_groups;

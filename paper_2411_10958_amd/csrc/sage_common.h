@@ -91,6 +91,7 @@ struct Dims {
   int causal, int4, bf16, smooth_v, block_groups, nhd;
   int smooth_k, smooth_q;   // 0: that mean is taken as zero (the paper's smoothing ablation)
   int ds32;                 // Delta-S accumulated in FP32 instead of FP64 (faster, approximate)
+  int ds_mode;              // how Delta-S is formed: 0 digit products on the INT8 matrix unit, 1 FP32, 2 FP64 matrix instructions
   int stats_given;          // mean(K) and delta_V come from the caller: no statistics pass
   int qg, kg;  // queries / keys per stored scale: 2 / 16 (lane and block maps), 1 / 4 (fine), 1 / 1 (token)
   float kappa; // fl32(sm_scale * log2 e)
@@ -132,7 +133,7 @@ struct Dims {
 //   v_sum, v_mean only with the smooth-V option (otherwise zero-sized).
 struct Workspace {
   size_t k_sum, v_sum, v_max, k_mean, v_mean, v_scale, q_mean, q_scale, k_scale, q_corr, q_head_scale,
-      k_head_scale, q_codes, k_codes, v_codes, delta_s, part_o, part_el, total;
+      k_head_scale, q_codes, k_codes, v_codes, delta_s, part_o, part_el, q_digits, q_dscale, total;
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -169,6 +170,9 @@ inline Workspace make_workspace(const Dims& D) {
   w.v_codes = take(BHkv * D.nKb * BKV * D.d);
   w.delta_s = take(D.int4 ? BH * D.nQb * D.nKb * BKV * sizeof(float) : 0);
   // partial results of a split key range: per (tile, chunk) 128 rows of d floats, and (offset, sum) per row
+  // digits of the block means for the Delta-S product: 6 planes of d bytes per (head, query block), and 2^E per row
+  w.q_digits = take(D.int4 ? BH * D.nQb * 6 * D.d : 0);
+  w.q_dscale = take(D.int4 ? BH * D.nQb * sizeof(float) : 0);
   w.part_o = take(D.splits > 1 ? BH * D.nQb * D.splits * BQ * D.d * sizeof(float) : 0);
   w.part_el = take(D.splits > 1 ? BH * D.nQb * D.splits * BQ * 2 * sizeof(float) : 0);
   w.total = off;
@@ -185,6 +189,8 @@ struct Ptrs {
   float* lse;
   int8_t *q_codes, *k_codes;
   uint8_t* v_codes;
+  unsigned char* q_digits;   // digits of the block means (Delta-S by digit products)
+  float* q_dscale;
 };
 
 inline Ptrs make_ptrs(const void* q, const void* k, const void* v, void* out, void* ws,
@@ -211,6 +217,8 @@ inline Ptrs make_ptrs(const void* q, const void* k, const void* v, void* out, vo
   p.delta_s = (float*)(b + w.delta_s);
   p.part_o = (float*)(b + w.part_o);
   p.part_el = (float*)(b + w.part_el);
+  p.q_digits = (unsigned char*)(b + w.q_digits);
+  p.q_dscale = (float*)(b + w.q_dscale);
   return p;
 }
 

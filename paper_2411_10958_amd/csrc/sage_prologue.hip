@@ -576,8 +576,80 @@ typedef double v4d __attribute__((ext_vector_type(4)));
 
 constexpr int DS_QROWS = 32;    // query-block means staged in LDS per pass: two 16-row MFMA tiles
 
-template <bool BF16, bool INT4, int D, bool DS32 = false>
-__global__ void __launch_bounds__(256, D == 256 ? 2 : 4) k_quant_k(const unsigned short* __restrict__ K,
+// How the Delta-S product is formed (template parameter DSM of k_quant_k):
+//   DS_DIGITS  both factors cut into 7-bit digits of a fixed-point number and multiplied digit by digit on the INT8
+//              matrix instruction: exact integer sums, recombined in float64 (the default),
+//   DS_FP32    v_mfma_f32_16x16x4_f32: faster still, approximate (an option of the boundary),
+//   DS_FP64    v_mfma_f64_16x16x4_f64: the reference form (an option of the boundary).
+//
+// DS_DIGITS.  A row x of d numbers (a block mean q_bar_i, or a smoothed key) with largest magnitude below 2^(E-1) is
+// written x_c = 2^E sum_a n_a[c] 2^(-7(a+1)) + rest, a = 0..5, with balanced digits |n_a| <= 64: n = rint(128 r),
+// r <- 128 r - n, starting from r = x 2^-E; every step is exact in FP32, and the rest is zero for every x_c whose
+// exponent is within 17 of the row's largest (smaller ones lose what lies below 2^(E-42)).  Then
+//   <x, y> = 2^(Ex+Ey) sum_{a,b} 2^(-7(a+b+2)) sum_c n_a[c] m_b[c],
+// the inner sums are integers below 2^21 that v_mfma_i32_16x16x64_i8 forms exactly, pairs with the same a + b share
+// an accumulator (below 2^24), and the pairs with a + b > 6 are left out: together less than 2^-40 of
+// |x|_max |y|_max d.  The result agrees with the float64 inner product far below its FP32 rounding, at a quarter of
+// the FP64 instruction's time, and - being INT8 matrix work - it runs alongside the vector work of the quantizers.
+enum { DS_DIGITS = 0, DS_FP32 = 1, DS_FP64 = 2 };
+constexpr int DS_ND = 6;                         // digits per number
+constexpr float DS_MAGIC = 12582912.0f;          // 1.5 * 2^23: adding it leaves rint() of a small number in the low mantissa bits
+
+// The DS_ND digit bytes of x (|x| < 0.5, already divided by 2^E) into byte `pos` of out[0..DS_ND)
+__device__ __forceinline__ void ds_digits(float r, unsigned (&out)[DS_ND], int pos) {
+#pragma unroll
+  for (int a = 0; a < DS_ND; ++a) {
+    const float sm = __fmaf_rn(r, 128.0f, DS_MAGIC);          // MAGIC + rint(128 r), exact
+    const float n = sm - DS_MAGIC;
+    r = __fmaf_rn(r, 128.0f, -n);                             // exact: what the digit leaves, scaled up
+    out[a] |= (__float_as_uint(sm) & 0xffu) << (8 * pos);     // two's-complement byte of the digit
+  }
+}
+// 2^-E and 2^E for a row whose largest magnitude is mx: E = exponent(mx) + 2, so that |x| 2^-E < 0.5.  A row of
+// zeros, or magnitudes of 2^125 and beyond (whose products overflow FP32 anyway), get 0 and 0: Delta-S = 0.
+__device__ __forceinline__ void ds_row_scale(float mx, float* down, float* up) {
+  const unsigned eb = __float_as_uint(mx) >> 23;              // biased exponent (mx >= 0)
+  const bool ok = mx > 0.0f && eb <= 251u;
+  *down = ok ? __uint_as_float((252u - eb) << 23) : 0.0f;
+  *up = ok ? __uint_as_float((eb + 2u) << 23) : 0.0f;
+}
+
+// Digits of the block means (DS_DIGITS): one wavefront per (batch, head, query block) row of q_mean.
+// q_digits: [row][digit a][channel] bytes; q_dscale: 2^E per row.
+template <int D>
+__global__ void __launch_bounds__(64) k_slice_q_mean(const float* __restrict__ q_mean, unsigned char* __restrict__ q_digits,
+                                                     float* __restrict__ q_dscale, int nrows) {
+  const int row = blockIdx.x, lane = threadIdx.x;
+  if (row >= nrows) return;
+  constexpr int PER = D / 64;                  // consecutive channels per lane
+  float x[PER];
+  float mx = 0.0f;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    x[e] = q_mean[(size_t)row * D + PER * lane + e];
+    mx = fmaxf(mx, fabsf(x[e]));               // (a NaN mean leaves the maximum alone; rows past a shorter sequence hold anything and are never read)
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  float down, up;
+  ds_row_scale(mx, &down, &up);
+  if (lane == 0) q_dscale[row] = up;
+  unsigned dg[DS_ND];
+#pragma unroll
+  for (int a = 0; a < DS_ND; ++a) dg[a] = 0u;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) ds_digits(x[e] * down, dg, e);
+#pragma unroll
+  for (int a = 0; a < DS_ND; ++a) {
+    unsigned char* dst = q_digits + ((size_t)row * DS_ND + a) * D + PER * lane;
+    if constexpr (PER == 4) *reinterpret_cast<unsigned*>(dst) = dg[a];
+    else if constexpr (PER == 2) *reinterpret_cast<unsigned short*>(dst) = (unsigned short)dg[a];
+    else *dst = (unsigned char)dg[a];
+  }
+}
+
+template <bool BF16, bool INT4, int D, int DSM = DS_DIGITS>
+__global__ void __launch_bounds__(256, D == 256 ? 2 : (INT4 && DSM == DS_DIGITS ? 3 : 4)) k_quant_k(const unsigned short* __restrict__ K,
                                                  const float* __restrict__ k_mean,
                                                  float* __restrict__ k_scale, int8_t* __restrict__ k_codes,
                                                  const float* __restrict__ q_mean,
@@ -585,7 +657,9 @@ __global__ void __launch_bounds__(256, D == 256 ? 2 : 4) k_quant_k(const unsigne
                                                  int nQb, int G, float kappa, int block_groups, int kg,
                                                  int causal, TensorMap km, SeqMap sm,
                                                  const float* __restrict__ head_scale, int stats_only,
-                                                 int zero_ds) {
+                                                 int zero_ds, const unsigned char* __restrict__ q_digits,
+                                                 const float* __restrict__ q_dscale) {
+  constexpr bool DS32 = DSM == DS_FP32, DSD = INT4 && DSM == DS_DIGITS;
   constexpr int CPL = D / 4;                       // channels per lane (32 or 16)
   constexpr int QMAX = INT4 ? 7 : 127;
   // LDS row of staged block means: channel c sits at column c + 16*(c / 32) when D = 128, so the
@@ -593,7 +667,12 @@ __global__ void __launch_bounds__(256, D == 256 ? 2 : 4) k_quant_k(const unsigne
   constexpr int SQW = D + (D >= 128 ? 48 : 0) + 1;
   constexpr int PADSH = D == 256 ? 6 : 5;          // 16 columns of padding after every 32 (d = 128) / 64 (d = 256) channels
   __shared__ uint4 s_codes[BKV * D / 16];          // the block's packed image
-  __shared__ float s_q[INT4 ? DS_QROWS : 1][SQW];
+  __shared__ float s_q[INT4 && !DSD ? DS_QROWS : 1][SQW];
+  // DS_DIGITS: a staged row is its DS_ND digit planes of D bytes; 16 bytes of padding make the 16 rows of an operand read
+  // start in 16 different bank groups
+  constexpr int ROWB = DS_ND * D + 16;
+  __shared__ __align__(16) unsigned char s_qd[DSD ? DS_QROWS : 1][DSD ? ROWB : 16];
+  __shared__ float s_qs[DS_QROWS];                 // 2^E of the staged rows
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int r16 = lane & 15, k4 = lane >> 4;
   const int kb = blockIdx.x;
@@ -622,40 +701,88 @@ __global__ void __launch_bounds__(256, D == 256 ? 2 : 4) k_quant_k(const unsigne
   // if 128 i + 127 + coff >= its first key: the passes of a head start with the one that holds
   // block (first key - coff) / 128
   const int p_first = causal && !flat ? (max(kb * BKV - coff, 0) / BQ) / DS_QROWS : 0;
-  auto next_pass = [&](int p) { return (p + 1) % npass_h >= p_first ? p + 1 : p + 1 + p_first; };
-  // row rr of pass p: query head (as a row of the [B H] axis) and query block; false for an empty row
-  auto pass_row = [&](int p, int rr, size_t* bh, int* i) {
-    if (flat) {
-      const int R = p * DS_QROWS + rr, g = R / max(nQs, 1);
-      *bh = bhkv * G + g;
-      *i = R - g * nQs;
-      return R < nrow;
-    }
-    *bh = bhkv * G + p / npass_h;
-    *i = (p % npass_h) * DS_QROWS + rr;
-    return *i < nQs;
+  // A pass is named by (head of the group, pass within the head), or by (0, pass) when flat; carried as a pair so
+  // that nothing in the pass loop divides.
+  struct PassId { int g, ph; };
+  const PassId pass_first = {0, p_first};
+  auto pass_ok = [&](PassId q) { return INT4 && (flat ? q.ph < npass : q.g < G); };
+  auto pass_next = [&](PassId q) {
+    PassId n = q;
+    if (flat || q.ph + 1 < npass_h) n.ph = q.ph + 1;
+    else { n.g = q.g + 1; n.ph = p_first; }
+    return n;
   };
-  float4 qpre[QPT];
-  auto load_q = [&](int p) {
+  const float inv_nqs = 1.0f / (float)max(nQs, 1);
+  // row rr of a pass: its index (head, query block) in the [B H][nQb] arrays, or -1 for an empty row
+  const int bh0 = (int)bhkv * G;
+  auto pass_row = [&](PassId q, int rr) {
+    if (flat) {
+      // (R + 1/2) / nQs never comes within rounding distance of an integer for the few thousand rows there can be
+      const int R = q.ph * DS_QROWS + rr, g = (int)(((float)R + 0.5f) * inv_nqs);
+      return R < nrow ? (bh0 + g) * nQb + (R - g * nQs) : -1;
+    }
+    const int i = q.ph * DS_QROWS + rr;
+    return i < nQs ? (bh0 + q.g) * nQb + i : -1;
+  };
+  constexpr int NCH = DS_ND * D / 16;              // 16-byte pieces of a row of digits
+  constexpr int QPD = DS_QROWS * NCH / 256;        // ... per thread per pass
+  float4 qpre[DSD ? 1 : QPT];
+  uint4 dpre[DSD ? QPD : 1];
+  float spre = 0.0f;
+  auto load_q = [&](PassId p) {
+    if constexpr (DSD) {
+      if (!flat) {
+        // the pass's rows are consecutive query blocks of one head: one contiguous piece of the digit array
+        const int row0 = (bh0 + p.g) * nQb + p.ph * DS_QROWS, rows = min(DS_QROWS, nQs - p.ph * DS_QROWS);
+        const uint4* src = reinterpret_cast<const uint4*>(q_digits + (size_t)row0 * (DS_ND * D));
 #pragma unroll
-    for (int k = 0; k < QPT; ++k) {
+        for (int k = 0; k < QPD; ++k) {
+          const int idx = t + k * 256;
+          dpre[k] = idx < rows * NCH ? src[idx] : make_uint4(0u, 0u, 0u, 0u);
+        }
+        if (t < DS_QROWS) spre = t < rows ? q_dscale[row0 + t] : 0.0f;
+        return;
+      }
+#pragma unroll
+      for (int k = 0; k < QPD; ++k) {
+        const int idx = t + k * 256, rr = idx / NCH, ch = idx % NCH;
+        const int row = pass_row(p, rr);
+        dpre[k] = row >= 0 ? *reinterpret_cast<const uint4*>(q_digits + (size_t)row * (DS_ND * D) + 16 * ch)
+                           : make_uint4(0u, 0u, 0u, 0u);
+      }
+      if (t < DS_QROWS) {
+        const int row = pass_row(p, t);
+        spre = row >= 0 ? q_dscale[row] : 0.0f;
+      }
+      return;
+    }
+#pragma unroll
+    for (int k = 0; k < (DSD ? 0 : QPT); ++k) {
       const int idx = t + k * 256, rr = idx / (D / 4), c4 = idx % (D / 4);
-      size_t bh;
-      int i;
-      qpre[k] = pass_row(p, rr, &bh, &i) ? *reinterpret_cast<const float4*>(q_mean + (bh * nQb + i) * D + 4 * c4)
-                                         : make_float4(0.f, 0.f, 0.f, 0.f);
+      const int row = pass_row(p, rr);
+      qpre[k] = row >= 0 ? *reinterpret_cast<const float4*>(q_mean + (size_t)row * D + 4 * c4)
+                         : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   };
   auto store_q = [&]() {
+    if constexpr (DSD) {
 #pragma unroll
-    for (int k = 0; k < QPT; ++k) {
+      for (int k = 0; k < QPD; ++k) {
+        const int idx = t + k * 256, rr = idx / NCH, ch = idx % NCH;
+        *reinterpret_cast<uint4*>(&s_qd[rr][16 * ch]) = dpre[k];
+      }
+      if (t < DS_QROWS) s_qs[t] = spre;
+      return;
+    }
+#pragma unroll
+    for (int k = 0; k < (DSD ? 0 : QPT); ++k) {
       const int idx = t + k * 256, rr = idx / (D / 4), c4 = idx % (D / 4);
       const int col = 4 * c4 + (D >= 128 ? 16 * ((4 * c4) >> PADSH) : 0);
       s_q[rr][col + 0] = qpre[k].x; s_q[rr][col + 1] = qpre[k].y;
       s_q[rr][col + 2] = qpre[k].z; s_q[rr][col + 3] = qpre[k].w;
     }
   };
-  if constexpr (INT4) load_q(p_first);
+  if constexpr (INT4) load_q(pass_first);
 
   float x[CPL];
   float mx = 0.0f;
@@ -682,6 +809,7 @@ __global__ void __launch_bounds__(256, D == 256 ? 2 : 4) k_quant_k(const unsigne
   // scale) the run of 4 keys, then (default) the wavefront's run of 16
   mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
   mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float mx_key = mx;                         // this key's largest magnitude (DS_DIGITS: its fixed-point exponent)
   if (kg >= 4) {
     mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
@@ -744,19 +872,100 @@ __global__ void __launch_bounds__(256, D == 256 ? 2 : 4) k_quant_k(const unsigne
     // what lets four workgroups share a CU
     const double kap = (double)kappa;
     const int qcol = c0 + (D >= 128 ? 16 * k4 : 0);
-    for (int p = p_first; p < npass; p = next_pass(p)) {
-      if (p > p_first) __syncthreads();            // everyone is done with the previous pass's rows
+    // DS_DIGITS: the digits of this lane's CPL smoothed values as B operands of v_mfma_i32_16x16x64_i8.  An operand is
+    // 16 bytes per lane; contraction slot (step st, lane group k4, byte j) is given channel CPL k4 + 16 st + j - any
+    // assignment is valid as long as the A operand uses the same one.
+    constexpr int NST = CPL / 16;
+    v4i bd[DSD ? DS_ND : 1][DSD ? NST : 1];
+    double key_up = 0.0;
+    if constexpr (DSD) {
+      float down, up;
+      ds_row_scale(mx_key, &down, &up);
+      key_up = (double)up * kap;                   // 2^E of the key, times kappa
+#pragma unroll
+      for (int st = 0; st < NST; ++st) {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          unsigned dg[DS_ND];
+#pragma unroll
+          for (int a = 0; a < DS_ND; ++a) dg[a] = 0u;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) ds_digits(x[16 * st + 4 * q4 + j] * down, dg, j);
+#pragma unroll
+          for (int a = 0; a < DS_ND; ++a) bd[a][st][q4] = (int)dg[a];
+        }
+      }
+      // (opaque to the compiler from here on: it would otherwise form the digits anew in every pass)
+#pragma unroll
+      for (int a = 0; a < DS_ND; ++a) {
+#pragma unroll
+        for (int st = 0; st < NST; ++st) asm volatile("" : "+v"(bd[a][st]));
+      }
+    }
+    bool first_pass = true;
+    for (PassId p = pass_first; pass_ok(p); p = pass_next(p)) {
+      if (!first_pass) __syncthreads();            // everyone is done with the previous pass's rows
+      first_pass = false;
       store_q();
       __syncthreads();
-      if (next_pass(p) < npass) load_q(next_pass(p));   // next pass, in flight under the MFMAs
+      if (pass_ok(pass_next(p))) load_q(pass_next(p));   // next pass, in flight under the MFMAs
       // rows 16..31 of the pass all empty (a short last pass): their chain of matrix instructions is left out
-      const bool upper = flat ? p * DS_QROWS + 16 < nrow : (p % npass_h) * DS_QROWS + 16 < nQs;
+      const bool upper = p.ph * DS_QROWS + 16 < (flat ? nrow : nQs);
+      // (not flat: the pass's rows are consecutive rows of the Delta-S array of one head)
+      const unsigned rowstride = (unsigned)nKb * BKV;
+      float* const out0 = delta_s + (size_t)((bh0 + p.g) * nQb + p.ph * DS_QROWS) * rowstride + (size_t)(n0 + r);
+      const int rows_here = nQs - p.ph * DS_QROWS;
+      const bool full = rows_here >= DS_QROWS;        // (all but a head's last pass)
       auto put = [&](int rr, float val) {
-        size_t bh;
-        int i;
-        if (pass_row(p, rr, &bh, &i)) delta_s[(bh * nQb + i) * (size_t)nKb * BKV + n0 + r] = val;
+        if (!flat) {
+          if (full || rr < rows_here) out0[(size_t)((unsigned)rr * rowstride)] = val;
+          return;
+        }
+        const int row = pass_row(p, rr);
+        if (row >= 0) delta_s[(size_t)row * rowstride + (size_t)(n0 + r)] = val;
       };
-      if constexpr (DS32) {
+      if constexpr (DSD) {
+        // accumulators by digit-pair weight: acc[k][rt] collects the pairs with a + b = k for row tile rt; result
+        // element v of lane l is row 4 (l / 16) + v, column l % 16
+        // one 16-row tile at a time (its seven accumulators are live only until its results are out)
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+          if (rt == 1 && !upper) break;
+          if (zero_ds) {     // (Q not smoothed: the block means are zero and so is Delta-S)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) put(16 * rt + 4 * k4 + v, 0.0f);
+            continue;
+          }
+          v4i acc[DS_ND + 1];
+#pragma unroll
+          for (int a = 0; a < DS_ND; ++a) {
+#pragma unroll
+            for (int st = 0; st < NST; ++st) {
+              const v4i qa = *reinterpret_cast<const v4i*>(&s_qd[16 * rt + r16][a * D + CPL * k4 + 16 * st]);
+#pragma unroll
+              for (int b = 0; b < DS_ND && a + b <= DS_ND; ++b) {
+                // the first pair of a weight starts from zero (a constant operand of the instruction)
+                const bool first = st == 0 && a == (a + b >= DS_ND ? a + b - (DS_ND - 1) : 0);
+                acc[a + b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(qa, bd[b][st], first ? v4i{0, 0, 0, 0} : acc[a + b], 0, 0, 0);
+              }
+            }
+          }
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int rr = 16 * rt + 4 * k4 + v;
+            // sum_k acc_k 2^(-7 (k + 2)): neighbours joined as integers first (128 acc_k + acc_{k+1} < 2^31), then
+            // float64, smallest weights first
+            static_assert(DS_ND == 6, "seven accumulators");
+            const int u0 = acc[0][v] * 128 + acc[1][v], u1 = acc[2][v] * 128 + acc[3][v],
+                      u2 = acc[4][v] * 128 + acc[5][v], u3 = acc[6][v];
+            double sum = (double)u3 * 0x1p-56;
+            sum = __fma_rn((double)u2, 0x1p-49, sum);
+            sum = __fma_rn((double)u1, 0x1p-35, sum);
+            sum = __fma_rn((double)u0, 0x1p-21, sum);
+            put(rr, (float)(sum * ((double)s_qs[rr] * key_up)));
+          }
+        }
+      } else if constexpr (DS32) {
         // Faster, approximate form (an option of the boundary): the same product on the FP32 form of the
         // instruction (result element v of lane l is row 4*(l/16) + v, column l%16).  FP32 accumulation:
         // within (d + 2) 2^-24 kappa sum_c |q_bar_c gamma(K)_c| of the exact value, about half a unit of 2^-24 of
@@ -990,16 +1199,22 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
     }
   };
   auto quant_k_pass = [&](const float* head_scale, int stats_only) {
-    if (INT4 && Dm.ds32)     // (the last template argument is written INT4 so that the 8-bit build has no FP32 Delta-S copy)
-      k_quant_k<BF16, INT4, D, INT4><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
-                                                                      P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
-                                                                      Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.kg,
-                                                                      Dm.causal, km, sm, head_scale, stats_only, !Dm.smooth_q);
-    else
-      k_quant_k<BF16, INT4, D><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean,
-                                                                  P.delta_s, Dm.N, Dm.Nk, Dm.nKb, Dm.nQb,
-                                                                  Dm.H / Dm.Hkv, Dm.kappa, Dm.block_groups, Dm.kg,
-                                                                  Dm.causal, km, sm, head_scale, stats_only, !Dm.smooth_q);
+#define SAGE_QK(DSM_)                                                                                                  \
+  k_quant_k<BF16, INT4, D, DSM_><<<dim3(Dm.nKb, BHkv), 256, 0, s>>>(k, P.k_mean, P.k_scale, P.k_codes, P.q_mean, P.delta_s, \
+                                                                    Dm.N, Dm.Nk, Dm.nKb, Dm.nQb, Dm.H / Dm.Hkv, Dm.kappa,  \
+                                                                    Dm.block_groups, Dm.kg, Dm.causal, km, sm, head_scale, \
+                                                                    stats_only, !Dm.smooth_q, P.q_digits, P.q_dscale)
+    // (the 8-bit build has no Delta-S: one instantiation, named by the default mode)
+    if (INT4 && Dm.ds_mode == DS_FP32) SAGE_QK(INT4 ? DS_FP32 : DS_DIGITS);
+    else if (INT4 && Dm.ds_mode == DS_FP64) SAGE_QK(INT4 ? DS_FP64 : DS_DIGITS);
+    else {
+      if (INT4 && Dm.smooth_q && !stats_only) {
+        const int nrows = BH * Dm.nQb;
+        k_slice_q_mean<D><<<nrows, 64, 0, s>>>(P.q_mean, P.q_digits, P.q_dscale, nrows);
+      }
+      SAGE_QK(DS_DIGITS);
+    }
+#undef SAGE_QK
   };
   if (!Dm.want_lse) quant_q();
   if (!Dm.stats_given) launch_stats_t<BF16, D>(Dm, P, s);     // else P.k_mean and P.v_scale are the caller's arrays

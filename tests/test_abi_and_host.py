@@ -72,7 +72,7 @@ def test_workspace_size_formula():
 
 def test_argument_errors_are_found_on_the_host():
     pa, lib = _lib()
-    bad = [dict(d=96), dict(d=512), dict(mode=2), dict(dtype=3), dict(flags=16), dict(flags=-1), dict(N=(1 << 24) + 1), dict(N_kv=(1 << 24) + 1), dict(group_map=5), dict(group_map=-1), dict(layout=2), dict(pv_format=3),
+    bad = [dict(d=96), dict(d=512), dict(mode=2), dict(dtype=3), dict(flags=64), dict(flags=-1), dict(N=(1 << 24) + 1), dict(N_kv=(1 << 24) + 1), dict(group_map=5), dict(group_map=-1), dict(layout=2), dict(pv_format=3),
            dict(pv_format=1, group_map=2)]
     for kw in bad:
         a = _args(pa, **kw)

@@ -71,11 +71,14 @@ def test_full_size_sampled_parity(name, mode):
             if "delta_s" in quant:
                 got_ds = quant["delta_s"][b, h][blocks].cpu().numpy().astype(np.float64)
                 ref_ds = pro["delta_s"][blocks].astype(np.float64)
-                ok = np.abs(got_ds - ref_ds) <= np.spacing(np.abs(ref_ds))
+                # the bar of the small cases: an exact inner product formed another way, one rounding to FP32 - at most
+                # the last bit of the FP32 value (its spacing, not that of the float64 copy), and rarely
+                diff = np.abs(got_ds - ref_ds)
                 if spec.causal:     # rows are computed up to the key a query block's group can see
                     seen = np.arange(spec.N)[None, :] < 4096 * (np.asarray(blocks)[:, None] // 32 + 1)
-                    ok |= ~seen
-                assert np.all(ok)
+                    diff = np.where(seen, diff, 0.0)
+                assert np.all(diff <= np.spacing(np.abs(pro["delta_s"][blocks])).astype(np.float64))
+                assert (diff > 0).mean() < 1e-3
         # int32 score accumulators of a few (query tile, key block) pairs through the MFMA path
         nkb = (spec.N + 63) // 64
         for qt in (blocks[0], blocks[-1]):

@@ -94,6 +94,31 @@ def test_prologue_bit_exact(N, d, dtype, H, Hkv, causal, mode):
                     assert not acc[ref.shape[0]:].any() and not acc[:, ref.shape[1]:].any()
 
 
+@pytest.mark.parametrize("form", ["digits", "fp64"])
+@pytest.mark.parametrize("N,d,dtype,H,Hkv,causal", [CASES[3], CASES[4], CASES[6], CASES[7], CASES[9], CASES[10],
+                                                    (4200, 64, "bf16", 2, 1, True),      # 33 query blocks: two passes per head, causal skipping
+                                                    (4100, 128, "fp16", 1, 1, False)])
+def test_both_exact_forms_of_delta_s(N, d, dtype, H, Hkv, causal, form):
+    """Delta-S (Sec. 3.1) by digit products on the INT8 matrix unit and by the FP64 matrix instruction, each forced: within
+    the last bit of the oracle's correctly rounded float64 inner product, and different from it at most once in 10^3."""
+    pa = _pa()
+    spec = _spec(N, d, dtype, H, Hkv, causal=causal)
+    data, (q, k, v) = _gpu_inputs(spec)
+    got, _, _ = pa.sage_attn_quant(q, k, v, causal=causal, want=("delta_s", "q_mean"), delta_s=form)
+    torch.cuda.synchronize()
+    ds = got["delta_s"].cpu().numpy()
+    g = H // Hkv
+    for h in range(H):
+        pro = so.quantize_head(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g])
+        D = pro["delta_s"].astype(np.float64)
+        diff = np.abs(ds[0, h].astype(np.float64) - D)
+        if causal:      # rows are defined up to the keys their queries can see (in groups of 32 blocks)
+            vis = np.arange(N)[None, :] < 4096 * (np.arange(D.shape[0])[:, None] // 32 + 1)
+            diff = np.where(vis, diff, 0.0)
+        assert np.all(diff <= np.spacing(np.abs(D.astype(np.float32))).astype(np.float64)), f"delta S ({form})"
+        assert (diff > 0).mean() < 1e-3
+
+
 @pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
 @pytest.mark.parametrize("N,d,dtype,H,Hkv,causal", CASES)
 def test_attention_output_matches_oracle(N, d, dtype, H, Hkv, causal, mode):
@@ -180,7 +205,7 @@ def test_smoothing_switched_off_matches_oracle(N, d, dtype, H, Hkv, causal, smoo
                 assert np.array_equal(got["q_mean"][b, h], pro["qbar"]), "q block means"
                 D = pro["delta_s"].astype(np.float64)
                 diff = np.abs(got["delta_s"][b, h].astype(np.float64) - D)
-                assert np.all(diff <= np.spacing(np.abs(D))), "delta S"
+                assert np.all(diff <= np.spacing(np.abs(D.astype(np.float32))).astype(np.float64)), "delta S"   # one unit of the FP32 value's last place
             else:
                 assert not got["q_mean"][b, h].any() and not got["delta_s"][b, h].any(), "no Q smoothing: zeros"
     out, lse = pa.sage_attn_fwd_ex(q, k, v, causal=causal, smooth_k=smooth_k, smooth_q=smooth_q, return_lse=True)
@@ -470,7 +495,7 @@ def test_other_key_length_matches_oracle(N, Nk, d, dtype, H, Hkv, causal, mode):
         if mode == "int4_fp8":
             D = pro["delta_s"].astype(np.float64)
             diff = np.abs(got["delta_s"][0, h].astype(np.float64) - D)
-            assert np.all(diff <= np.spacing(np.abs(D))), "delta S"
+            assert np.all(diff <= np.spacing(np.abs(D.astype(np.float32))).astype(np.float64)), "delta S"   # one unit of the FP32 value's last place
     parity.check_heads(wl.from_torch(out), data, causal, mode, dtype)
     full = np.stack([so.ref_attn_fp64(data["q"][0, h], data["k"][0, h // g], data["v"][0, h // g], causal)
                      for h in range(H)])

@@ -39,13 +39,15 @@ def test_preprocessing_fuzz(seed):
     smooth_k = bool(rng.random() >= 0.25)
     smooth_q = bool(rng.random() >= 0.25)
     fp32_ds = bool(rng.random() < 0.25)          # Delta-S accumulated in FP32: checked against its error bound instead
-    print(f"fuzz {seed}: d={d} H={H}/{Hkv} n={n} nk={nk} {dtype} {mode} {group_map} {pv} smooth v/k/q={smooth_v}/{smooth_k}/{smooth_q} fp32_ds={fp32_ds}",
+    # which exact form of the Delta-S product (from a generator of its own, so that the cases stay what they were)
+    ds_form = [None, "digits", "fp64"][int(np.random.default_rng(9000 + seed).integers(3))]
+    print(f"fuzz {seed}: d={d} H={H}/{Hkv} n={n} nk={nk} {dtype} {mode} {group_map} {pv} smooth v/k/q={smooth_v}/{smooth_k}/{smooth_q} fp32_ds={fp32_ds} ds_form={ds_form}",
           flush=True)
     qn, kn, vn = _awkward(rng, (H, n, d), dtype), _awkward(rng, (Hkv, nk, d), dtype), _awkward(rng, (Hkv, nk, d), dtype)
     dev = torch.device("cuda:0")
     q, k, v = (wl.to_torch(x[None], dtype, dev) for x in (qn, kn, vn))
     got, args, ws = pa.sage_attn_quant(q, k, v, mode=mode, group_map=group_map, pv_format=pv, smooth_v=smooth_v,
-                                       smooth_k=smooth_k, smooth_q=smooth_q, fp32_delta_s=fp32_ds)
+                                       smooth_k=smooth_k, smooth_q=smooth_q, fp32_delta_s=fp32_ds, delta_s=ds_form)
     torch.cuda.synchronize()
     got = {name: t.cpu().numpy() for name, t in got.items()}
     g = H // Hkv
@@ -72,7 +74,7 @@ def test_preprocessing_fuzz(seed):
                 continue
             D = pro["delta_s"].astype(np.float64)
             diff = np.abs(got["delta_s"][0, h].astype(np.float64) - D)
-            assert np.all(diff <= np.spacing(np.abs(D))), "delta S"
+            assert np.all(diff <= np.spacing(np.abs(D.astype(np.float32))).astype(np.float64)), "delta S"   # one unit of the FP32 value's last place
         elif int4:
             assert not got["delta_s"][0, h].any() and not got["q_mean"][0, h].any()
         # the integer score accumulators of one random (128-query tile, 64-key block) through the kernel's MFMA code
