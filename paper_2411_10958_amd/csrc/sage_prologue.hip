@@ -579,12 +579,12 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
 // (D/4)*(l/16) + cs - any assignment is valid as long as the A operand uses the same one - so
 // the smoothed keys feed the Delta-S product straight from the registers they were quantized in.
 //
-// Delta-S: D[i, t] = fl32(kappa * <q_bar_i, gamma(K)_t>), inner product in float64 so that the
-// value does not depend on summation order: a small GEMM [nQb x d] . [d x 64] per query head
-// of the KV group, walked 32 query blocks at a time (two independent accumulator chains).
-// v_mfma_f64_16x16x4_f64 sustains about 70 TFLOP/s on the whole chip and, unlike the low-precision
-// matrix instructions, does not run concurrently with other vector work of the SIMD, so this
-// phase costs its own MFMA time (2*nQb*N*d flops per head) on top of the quantization.
+// Delta-S: D[i, t] = fl32(kappa * <q_bar_i, gamma(K)_t>), the inner product formed exactly (or in float64) so that
+// the value does not depend on summation order: a small GEMM [nQb x d] . [d x 64] per query head of the KV group,
+// walked 32 query blocks ("a pass") at a time; three forms, template parameter DSM below.  The FP64 form:
+// v_mfma_f64_16x16x4_f64 sustains about 70 TFLOP/s on the whole chip and, unlike the low-precision matrix
+// instructions, does not run concurrently with other vector work of the SIMD, so it costs its own matrix time
+// (2*nQb*N*d flops per head) on top of the quantization.
 typedef double v4d __attribute__((ext_vector_type(4)));
 
 constexpr int DS_QROWS = 32;    // query-block means staged in LDS per pass: two 16-row MFMA tiles
