@@ -310,6 +310,62 @@ __global__ void k_finalize_vscale(const unsigned* __restrict__ v_max, float* __r
 }
 
 // ------------------------------------------------------------------------------------------
+// Fixed-point digits for the Delta-S product (the scheme is described at k_quant_k).
+constexpr int DS_ND = 6;                         // digits per number
+constexpr float DS_MAGIC = 12582912.0f;          // 1.5 * 2^23: adding it leaves rint() of a small number in the low mantissa bits
+
+// The DS_ND digit bytes of x (|x| < 0.5, already divided by 2^E) into byte `pos` of out[0..DS_ND)
+__device__ __forceinline__ void ds_digits(float r, unsigned (&out)[DS_ND], int pos) {
+#pragma unroll
+  for (int a = 0; a < DS_ND; ++a) {
+    const float sm = __fmaf_rn(r, 128.0f, DS_MAGIC);          // MAGIC + rint(128 r), exact
+    const float n = sm - DS_MAGIC;
+    r = __fmaf_rn(r, 128.0f, -n);                             // exact: what the digit leaves, scaled up
+    out[a] |= (__float_as_uint(sm) & 0xffu) << (8 * pos);     // two's-complement byte of the digit
+  }
+}
+// 2^-E and 2^E for a row whose largest magnitude is mx: E = exponent(mx) + 2, so that |x| 2^-E < 0.5.  A row of
+// zeros, or magnitudes of 2^125 and beyond (whose products overflow FP32 anyway), get 0 and 0: Delta-S = 0.
+__device__ __forceinline__ void ds_row_scale(float mx, float* down, float* up) {
+  const unsigned eb = __float_as_uint(mx) >> 23;              // biased exponent (mx >= 0)
+  const bool ok = mx > 0.0f && eb <= 251u;
+  *down = ok ? __uint_as_float((252u - eb) << 23) : 0.0f;
+  *up = ok ? __uint_as_float((eb + 2u) << 23) : 0.0f;
+}
+
+// Digits of one row of block means (DS_DIGITS), by one wavefront: `row` holds the D means (LDS or global), `digits`
+// receives [digit a][channel] bytes, `scale` 2^E.
+template <int D>
+__device__ __forceinline__ void ds_slice_row(const float* row, unsigned char* __restrict__ digits, float* __restrict__ scale,
+                                             int lane) {
+  constexpr int PER = D / 64;                  // consecutive channels per lane
+  float x[PER];
+  float mx = 0.0f;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    x[e] = row[PER * lane + e];
+    mx = fmaxf(mx, fabsf(x[e]));
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  float down, up;
+  ds_row_scale(mx, &down, &up);
+  if (lane == 0) *scale = up;
+  unsigned dg[DS_ND];
+#pragma unroll
+  for (int a = 0; a < DS_ND; ++a) dg[a] = 0u;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) ds_digits(x[e] * down, dg, e);
+#pragma unroll
+  for (int a = 0; a < DS_ND; ++a) {
+    unsigned char* dst = digits + a * D + PER * lane;
+    if constexpr (PER == 4) *reinterpret_cast<unsigned*>(dst) = dg[a];
+    else if constexpr (PER == 2) *reinterpret_cast<unsigned short*>(dst) = (unsigned short)dg[a];
+    else *dst = (unsigned char)dg[a];
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // KV head of query head bh (G query heads per KV head)
 __device__ inline size_t kv_head(const TensorMap& qm, unsigned bh, int G) {
   const unsigned b = bh / (unsigned)qm.heads, h = bh - b * (unsigned)qm.heads;
@@ -433,7 +489,8 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
                                                   int block_groups, int qg, TensorMap qm, SeqMap sm,
                                                   float* __restrict__ q_corr, const float* __restrict__ k_mean,
                                                   int G, float kappa, const float* __restrict__ head_scale,
-                                                  int stats_only, int smooth_q) {
+                                                  int stats_only, int smooth_q, unsigned char* __restrict__ q_digits,
+                                                  float* __restrict__ q_dscale) {
   constexpr int NCG = D / 8, NRG = 256 / NCG, RPT = BQ / NRG;   // load map: RPT rows x 8 channels
   constexpr int CPL = D / 4, CPC = CPL / 8;                      // quantization map: 2 rows x CPL channels
   constexpr int QMAX = 7;
@@ -488,6 +545,9 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
     q_mean[(bh * nQb + qb) * D + t] = m;
   }
   __syncthreads();
+  // the block mean cut into digits for the Delta-S product (first wavefront; the others go on)
+  if (q_digits && t < 64)
+    ds_slice_row<D>(s_mean, q_digits + (bh * nQb + qb) * (size_t)(DS_ND * D), q_dscale + (bh * nQb + qb), t);
 
   const int pair = t >> 2, c4 = t & 3;
   float x[2][CPL];
@@ -605,61 +665,6 @@ constexpr int DS_QROWS = 32;    // query-block means staged in LDS per pass: two
 // |x|_max |y|_max d.  The result agrees with the float64 inner product far below its FP32 rounding, at a quarter of
 // the FP64 instruction's time, and - being INT8 matrix work - it runs alongside the vector work of the quantizers.
 enum { DS_DIGITS = 0, DS_FP32 = 1, DS_FP64 = 2 };
-constexpr int DS_ND = 6;                         // digits per number
-constexpr float DS_MAGIC = 12582912.0f;          // 1.5 * 2^23: adding it leaves rint() of a small number in the low mantissa bits
-
-// The DS_ND digit bytes of x (|x| < 0.5, already divided by 2^E) into byte `pos` of out[0..DS_ND)
-__device__ __forceinline__ void ds_digits(float r, unsigned (&out)[DS_ND], int pos) {
-#pragma unroll
-  for (int a = 0; a < DS_ND; ++a) {
-    const float sm = __fmaf_rn(r, 128.0f, DS_MAGIC);          // MAGIC + rint(128 r), exact
-    const float n = sm - DS_MAGIC;
-    r = __fmaf_rn(r, 128.0f, -n);                             // exact: what the digit leaves, scaled up
-    out[a] |= (__float_as_uint(sm) & 0xffu) << (8 * pos);     // two's-complement byte of the digit
-  }
-}
-// 2^-E and 2^E for a row whose largest magnitude is mx: E = exponent(mx) + 2, so that |x| 2^-E < 0.5.  A row of
-// zeros, or magnitudes of 2^125 and beyond (whose products overflow FP32 anyway), get 0 and 0: Delta-S = 0.
-__device__ __forceinline__ void ds_row_scale(float mx, float* down, float* up) {
-  const unsigned eb = __float_as_uint(mx) >> 23;              // biased exponent (mx >= 0)
-  const bool ok = mx > 0.0f && eb <= 251u;
-  *down = ok ? __uint_as_float((252u - eb) << 23) : 0.0f;
-  *up = ok ? __uint_as_float((eb + 2u) << 23) : 0.0f;
-}
-
-// Digits of the block means (DS_DIGITS): one wavefront per (batch, head, query block) row of q_mean.
-// q_digits: [row][digit a][channel] bytes; q_dscale: 2^E per row.
-template <int D>
-__global__ void __launch_bounds__(64) k_slice_q_mean(const float* __restrict__ q_mean, unsigned char* __restrict__ q_digits,
-                                                     float* __restrict__ q_dscale, int nrows) {
-  const int row = blockIdx.x, lane = threadIdx.x;
-  if (row >= nrows) return;
-  constexpr int PER = D / 64;                  // consecutive channels per lane
-  float x[PER];
-  float mx = 0.0f;
-#pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    x[e] = q_mean[(size_t)row * D + PER * lane + e];
-    mx = fmaxf(mx, fabsf(x[e]));               // (a NaN mean leaves the maximum alone; rows past a shorter sequence hold anything and are never read)
-  }
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-  float down, up;
-  ds_row_scale(mx, &down, &up);
-  if (lane == 0) q_dscale[row] = up;
-  unsigned dg[DS_ND];
-#pragma unroll
-  for (int a = 0; a < DS_ND; ++a) dg[a] = 0u;
-#pragma unroll
-  for (int e = 0; e < PER; ++e) ds_digits(x[e] * down, dg, e);
-#pragma unroll
-  for (int a = 0; a < DS_ND; ++a) {
-    unsigned char* dst = q_digits + ((size_t)row * DS_ND + a) * D + PER * lane;
-    if constexpr (PER == 4) *reinterpret_cast<unsigned*>(dst) = dg[a];
-    else if constexpr (PER == 2) *reinterpret_cast<unsigned short*>(dst) = (unsigned short)dg[a];
-    else *dst = (unsigned char)dg[a];
-  }
-}
 
 template <bool BF16, bool INT4, int D, int DSM = DS_DIGITS>
 __global__ void __launch_bounds__(256, D == 256 ? 2 : (INT4 && DSM == DS_DIGITS ? 3 : 4)) k_quant_k(const unsigned short* __restrict__ K,
@@ -1194,7 +1199,8 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
     if constexpr (INT4)
       k_quant_q4<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_mean, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
                                                        Dm.block_groups, Dm.qg, qm, sm, corr, P.k_mean,
-                                                       Dm.H / Dm.Hkv, Dm.kappa, head_scale, stats_only, Dm.smooth_q);
+                                                       Dm.H / Dm.Hkv, Dm.kappa, head_scale, stats_only, Dm.smooth_q,
+                                                       Dm.ds_mode == DS_DIGITS && Dm.smooth_q ? P.q_digits : nullptr, P.q_dscale);
     else
       k_quant_q8<BF16, D><<<dim3(Dm.nQb, BH), 256, 0, s>>>(q, P.q_scale, P.q_codes, Dm.N, Dm.Nk, Dm.nQb,
                                                        Dm.block_groups, Dm.qg, qm, sm, corr, P.k_mean,
@@ -1221,10 +1227,6 @@ static hipError_t launch_prologue_t(const Dims& Dm, const Ptrs& P, hipStream_t s
     if (INT4 && Dm.ds_mode == DS_FP32) SAGE_QK(INT4 ? DS_FP32 : DS_DIGITS);
     else if (INT4 && Dm.ds_mode == DS_FP64) SAGE_QK(INT4 ? DS_FP64 : DS_DIGITS);
     else {
-      if (INT4 && Dm.smooth_q && !stats_only) {
-        const int nrows = BH * Dm.nQb;
-        k_slice_q_mean<D><<<nrows, 64, 0, s>>>(P.q_mean, P.q_digits, P.q_dscale, nrows);
-      }
       SAGE_QK(DS_DIGITS);
     }
 #undef SAGE_QK
