@@ -1,0 +1,76 @@
+"""CPU model of the fixed-point digit scheme the GPU path uses for the Delta-S product (Sec. 3.1: Delta-S =
+q_bar_i . gamma(K)^T), checked against the oracle's correctly rounded float64 product.
+
+The model is numpy integer arithmetic written for this test (it shares nothing with the HIP sources): every number of
+a row is divided by 2^E (E two above the exponent of the row's largest magnitude), cut into six balanced 7-bit digits,
+the digit planes are multiplied as exact integers, the pairs with digit indices a + b <= 6 are kept and recombined in
+float64.  What it pins is the choice of the scheme's two parameters: with them the result is within the last bit of
+the oracle's FP32 value everywhere on the awkward-value generator and differs from it at most once in 10^4 values."""
+import numpy as np
+
+import workloads as wl
+from oracle import sage_oracle as so
+
+f32, f64 = np.float32, np.float64
+
+
+def _digits(X, nd):
+    mx = np.abs(X).max(axis=1).astype(f32)
+    eb = (mx.view(np.uint32) >> 23).astype(np.int64)            # biased exponent of the row's largest magnitude
+    ok = mx > 0
+    down = np.where(ok, np.ldexp(1.0, 125 - eb), 0.0)           # 2^-E, E = (eb - 127) + 2
+    up = np.where(ok, np.ldexp(1.0, eb - 125), 0.0)
+    r = X.astype(f64) * down[:, None]                           # |r| < 1/2, exact
+    out = []
+    for _ in range(nd):
+        n = np.rint(r * 128.0)                                  # round-half-even, |n| <= 64
+        r = r * 128.0 - n                                       # exact
+        out.append(n.astype(np.int64))
+    return out, up
+
+
+def _digit_product(qbar, gK, kappa, nd, max_pair):
+    qd, qu = _digits(qbar, nd)
+    kd, ku = _digits(gK, nd)
+    acc = [np.zeros((qbar.shape[0], gK.shape[0]), np.int64) for _ in range(2 * nd - 1)]
+    for a in range(nd):
+        for b in range(nd):
+            if a + b <= max_pair:
+                acc[a + b] += qd[a] @ kd[b].T                   # exact integers
+    s = np.zeros(acc[0].shape, f64)
+    for k in range(min(max_pair, 2 * nd - 2), -1, -1):          # smallest weights first
+        s = acc[k].astype(f64) * 2.0 ** (-7 * (k + 2)) + s
+    return (s * (qu[:, None] * (ku[None, :] * f64(kappa)))).astype(f32)
+
+
+def test_six_digits_and_pairs_up_to_six_meet_the_last_bit_bar():
+    tot = beyond = differ = 0
+    for seed in range(6):
+        rng = np.random.default_rng(100 + seed)
+        d = 128 if seed % 2 else 64
+        dtype = "bf16" if seed % 3 else "fp16"
+        q = wl.awkward_values(rng, (1, 2048, d), dtype)[0]
+        k = wl.awkward_values(rng, (1, 2048, d), dtype)[0]
+        _, gK = so.smooth_k(k)
+        qbar, _ = so.smooth_q(q)
+        kappa = f32(f32(1.0 / np.sqrt(d)) * so.LOG2E_F32)
+        D = so.delta_s(qbar, gK, kappa)
+        G = _digit_product(qbar, gK, kappa, 6, 6)
+        diff = np.abs(G.astype(f64) - D.astype(f64))
+        tot += D.size
+        beyond += int((diff > np.spacing(np.abs(D)).astype(f64)).sum())
+        differ += int((diff > 0).sum())
+    print(f"  {tot} values: {differ} differ from the correctly rounded float64 product, {beyond} by more than the last bit")
+    assert beyond == 0
+    assert differ <= 1e-4 * tot
+
+
+def test_digits_represent_every_value_within_17_binades_of_the_row_maximum_exactly():
+    rng = np.random.default_rng(5)
+    X = (rng.uniform(0.5, 1.0, (64, 128)) * rng.choice([-1.0, 1.0], (64, 128)) * np.exp2(rng.integers(-17, 1, size=(64, 128)))).astype(f32)
+    X[:, 0] = 1.5                                               # the row's largest magnitude: exponent 0; the others lie in [2^-18, 1)
+    dg, up = _digits(X, 6)
+    back = sum(dg[a].astype(f64) * 2.0 ** (-7 * (a + 1)) for a in range(6)) * up[:, None]
+    small = np.abs(X) < 2.0 ** -17                              # exponent -18: one bit below the grid 2^-40
+    assert np.array_equal(back[~small].astype(f32), X[~small]) and (~small).sum() > 7000
+    assert all(np.abs(n).max() <= 64 for n in dg)
