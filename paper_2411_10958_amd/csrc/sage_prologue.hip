@@ -312,17 +312,25 @@ __global__ void k_finalize_vscale(const unsigned* __restrict__ v_max, float* __r
 // ------------------------------------------------------------------------------------------
 // Fixed-point digits for the Delta-S product (the scheme is described at k_quant_k).
 constexpr int DS_ND = 6;                         // digits per number
+constexpr int DS_MAXPAIR = 7;                    // digit pairs (a, b) with a + b up to this are multiplied: 30 of 36
 constexpr float DS_MAGIC = 12582912.0f;          // 1.5 * 2^23: adding it leaves rint() of a small number in the low mantissa bits
 
-// The DS_ND digit bytes of x (|x| < 0.5, already divided by 2^E) into byte `pos` of out[0..DS_ND)
-__device__ __forceinline__ void ds_digits(float r, unsigned (&out)[DS_ND], int pos) {
-#pragma unroll
-  for (int a = 0; a < DS_ND; ++a) {
-    const float sm = __fmaf_rn(r, 128.0f, DS_MAGIC);          // MAGIC + rint(128 r), exact
-    const float n = sm - DS_MAGIC;
-    r = __fmaf_rn(r, 128.0f, -n);                             // exact: what the digit leaves, scaled up
-    out[a] |= (__float_as_uint(sm) & 0xffu) << (8 * pos);     // two's-complement byte of the digit
-  }
+// The DS_ND digit bytes of y (|y| < 0.5: a value already divided by its row's 2^E) into byte `pos` of out[0..DS_ND).
+// y 2^42 is taken as two integers of 21 bits and a sign, N1 = rint(y 2^21) and N2 = rint((y 2^21 - N1) 2^21) (both
+// steps exact in FP32: adding 1.5 * 2^23 leaves the integer in the low mantissa bits), and each is cut into a signed
+// top digit (bits 14..21, -64..64) and two digits of 7 bits (0..127): y = sum_a n_a 2^(-7(a+1)) up to 2^-43.
+static_assert(DS_ND == 6, "two halves of three digits");
+__device__ __forceinline__ void ds_digits(float y, unsigned (&out)[DS_ND], int pos) {
+  const float s1 = __fmaf_rn(y, 0x1p21f, DS_MAGIC);           // MAGIC + N1
+  const float r = __fmaf_rn(y, 0x1p21f, -(s1 - DS_MAGIC));    // y 2^21 - N1, exact, |r| <= 1/2
+  const float s2 = __fmaf_rn(r, 0x1p21f, DS_MAGIC);           // MAGIC + N2
+  const unsigned b1 = __float_as_uint(s1), b2 = __float_as_uint(s2);   // low 22 bits: N in two's complement
+  out[0] |= ((b1 >> 14) & 0xffu) << (8 * pos);
+  out[1] |= ((b1 >> 7) & 0x7fu) << (8 * pos);
+  out[2] |= (b1 & 0x7fu) << (8 * pos);
+  out[3] |= ((b2 >> 14) & 0xffu) << (8 * pos);
+  out[4] |= ((b2 >> 7) & 0x7fu) << (8 * pos);
+  out[5] |= (b2 & 0x7fu) << (8 * pos);
 }
 // 2^-E and 2^E for a row whose largest magnitude is mx: E = exponent(mx) + 2, so that |x| 2^-E < 0.5.  A row of
 // zeros, or magnitudes of 2^125 and beyond (whose products overflow FP32 anyway), get 0 and 0: Delta-S = 0.
@@ -656,12 +664,12 @@ constexpr int DS_QROWS = 32;    // query-block means staged in LDS per pass: two
 //   DS_FP64    v_mfma_f64_16x16x4_f64: the reference form (an option of the boundary).
 //
 // DS_DIGITS.  A row x of d numbers (a block mean q_bar_i, or a smoothed key) with largest magnitude below 2^(E-1) is
-// written x_c = 2^E sum_a n_a[c] 2^(-7(a+1)) + rest, a = 0..5, with balanced digits |n_a| <= 64: n = rint(128 r),
-// r <- 128 r - n, starting from r = x 2^-E; every step is exact in FP32, and the rest is zero for every x_c whose
-// exponent is within 17 of the row's largest (smaller ones lose what lies below 2^(E-42)).  Then
+// written x_c = 2^E sum_a n_a[c] 2^(-7(a+1)) + rest, a = 0..5, with digits that fit a signed byte (ds_digits: n_0 and
+// n_3 in -64..64, the others in 0..127); the rest is zero for every x_c whose exponent is within 17 of the row's
+// largest (smaller ones lose what lies below 2^(E-42)).  Then
 //   <x, y> = 2^(Ex+Ey) sum_{a,b} 2^(-7(a+b+2)) sum_c n_a[c] m_b[c],
-// the inner sums are integers below 2^21 that v_mfma_i32_16x16x64_i8 forms exactly, pairs with the same a + b share
-// an accumulator (below 2^24), and the pairs with a + b > 6 are left out: together less than 2^-40 of
+// the inner sums are integers below 2^23 that v_mfma_i32_16x16x64_i8 forms exactly, pairs with the same a + b share
+// an accumulator (below 2^25), and the pairs with a + b > 7 are left out: together less than 2^-45 of
 // |x|_max |y|_max d.  The result agrees with the float64 inner product far below its FP32 rounding, at a quarter of
 // the FP64 instruction's time, and - being INT8 matrix work - it runs alongside the vector work of the quantizers.
 enum { DS_DIGITS = 0, DS_FP32 = 1, DS_FP64 = 2 };
@@ -954,14 +962,14 @@ __global__ void __launch_bounds__(256, D == 256 ? 2 : (INT4 && DSM == DS_DIGITS 
             for (int v = 0; v < 4; ++v) put(16 * rt + 4 * k4 + v, 0.0f);
             continue;
           }
-          v4i acc[DS_ND + 1];
+          v4i acc[DS_MAXPAIR + 1];
 #pragma unroll
           for (int a = 0; a < DS_ND; ++a) {
 #pragma unroll
             for (int st = 0; st < NST; ++st) {
               const v4i qa = *reinterpret_cast<const v4i*>(&s_qd[16 * rt + r16][a * D + CPL * k4 + 16 * st]);
 #pragma unroll
-              for (int b = 0; b < DS_ND && a + b <= DS_ND; ++b) {
+              for (int b = 0; b < DS_ND && a + b <= DS_MAXPAIR; ++b) {
                 // the first pair of a weight starts from zero (a constant operand of the instruction)
                 const bool first = st == 0 && a == (a + b >= DS_ND ? a + b - (DS_ND - 1) : 0);
                 acc[a + b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(qa, bd[b][st], first ? v4i{0, 0, 0, 0} : acc[a + b], 0, 0, 0);
@@ -971,12 +979,19 @@ __global__ void __launch_bounds__(256, D == 256 ? 2 : (INT4 && DSM == DS_DIGITS 
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             const int rr = 16 * rt + 4 * k4 + v;
-            // sum_k acc_k 2^(-7 (k + 2)): neighbours joined as integers first (128 acc_k + acc_{k+1} < 2^31), then
-            // float64, smallest weights first
-            static_assert(DS_ND == 6, "seven accumulators");
+            // sum_k acc_k 2^(-7 (k + 2)): neighbours joined as integers first (128 acc_k + acc_{k+1} < 2^31: with the
+            // digit ranges of ds_digits the largest is 128 acc_6 + acc_7 < 2^30.1 at d = 128; at d = 256 that one would
+            // not fit and stays apart), then float64, smallest weights first
+            static_assert(DS_ND == 6 && DS_MAXPAIR == 7, "eight accumulators");
             const int u0 = acc[0][v] * 128 + acc[1][v], u1 = acc[2][v] * 128 + acc[3][v],
-                      u2 = acc[4][v] * 128 + acc[5][v], u3 = acc[6][v];
-            double sum = (double)u3 * 0x1p-56;
+                      u2 = acc[4][v] * 128 + acc[5][v];
+            double sum;
+            if constexpr (D <= 128) {
+              sum = (double)(acc[6][v] * 128 + acc[7][v]) * 0x1p-63;
+            } else {
+              sum = (double)acc[7][v] * 0x1p-63;
+              sum = __fma_rn((double)acc[6][v], 0x1p-56, sum);
+            }
             sum = __fma_rn((double)u2, 0x1p-49, sum);
             sum = __fma_rn((double)u1, 0x1p-35, sum);
             sum = __fma_rn((double)u0, 0x1p-21, sum);
