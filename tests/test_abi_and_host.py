@@ -70,6 +70,25 @@ def test_workspace_size_formula():
     assert pa.sage_attn_workspace_bytes(_args(pa, flags=8)) == n          # FP32 Delta-S: same storage
 
 
+def test_key_split_policy():
+    """sage_attn_kv_splits (host logic only): the library splits the key range by itself only when a launch has fewer
+    than 256 tiles, into enough chunks for about 512 workgroups, at least 8 key blocks per chunk and at most 64; the
+    caller's number is honoured up to the same limits; finer group maps and other P~V data types never split."""
+    pa, _ = _lib()
+    S = lambda **kw: pa.sage_attn_kv_splits(_args(pa, **kw))
+    assert S() == 1                                                   # 4096 tiles: nothing to fill
+    assert S(B=1, H=1, H_kv=1) == 8                                       # 32 tiles, 64 key blocks: 8 blocks per chunk at least
+    assert S(B=1, H=8, H_kv=8, N=128, N_kv=32768) == 64                      # 8 tiles: 512 / 8 = 64 chunks of 8 blocks
+    assert S(B=4, H=32, H_kv=8, N=1, N_kv=32768, causal=1) == 4       # a decode step of 128 heads: 512 / 128
+    assert S(B=1, H=2, H_kv=2, N=1, N_kv=512) == 1                           # too few key blocks to cut
+    assert S(B=2, H=32, N=512) == 1                                   # 256 tiles: not split
+    assert S(B=2, H=32, N=512, kv_splits=3) == 1                      # ... and 8 key blocks cannot be cut into 3 chunks of 8
+    assert S(kv_splits=4) == 4 and S(kv_splits=64) == 8               # asked for: honoured up to one chunk per 8 blocks
+    assert S(B=1, H=1, H_kv=1, kv_splits=1) == 1                            # switched off
+    assert S(B=1, H=1, H_kv=1, group_map=2) == 1 and S(B=1, H=1, H_kv=1, pv_format=1) == 1
+    assert S(kv_splits=65) == 0 and S(kv_splits=-1) == 0              # invalid arguments
+
+
 def test_argument_errors_are_found_on_the_host():
     pa, lib = _lib()
     bad = [dict(d=96), dict(d=512), dict(mode=2), dict(dtype=3), dict(flags=64), dict(flags=-1), dict(N=(1 << 24) + 1), dict(N_kv=(1 << 24) + 1), dict(group_map=5), dict(group_map=-1), dict(layout=2), dict(pv_format=3),
