@@ -68,8 +68,10 @@ N_SEEDS = int(os.environ.get("SAGE_SWEEP_SEEDS", "48"))
 
 # Seeds kept as fixed regression cases whatever SAGE_SWEEP_SEEDS says.  7631: the dominant key of some rows has
 # an all-zero V row, so the whole output row lies below the smallest normal FP32 number, where the hardware
-# exponential's flush of subnormal results shows (the absolute floor of oracle/parity.py).
-REGRESSION_SEEDS = [7631]
+# exponential's flush of subnormal results shows (the absolute floor of oracle/parity.py).  1124: smooth V on
+# heavy-tailed values - the products of a channel cancel to a quarter of their magnitude, so the matrix
+# instruction's rounding, which is relative to that magnitude, is 5.1e-4 of the row norm (bar B's row scale).
+REGRESSION_SEEDS = [7631, 1124]
 
 
 @pytest.mark.parametrize("seed", list(range(N_SEEDS)) + [s for s in REGRESSION_SEEDS if s >= N_SEEDS])
