@@ -43,6 +43,8 @@ def _draw(rng):
     # inputs with awkward values (heads scaled by powers of two, all-zero tokens, channels and heads, ties, heavy
     # tails) instead of the workload generator's
     c["awkward"] = bool(rng.random() < 0.3)
+    # which exact form of the Delta-S product (None: the library's choice - the FP64 form at these sizes)
+    c["delta_s"] = [None, "digits", "fp64"][int(rng.integers(3))]
     return c
 
 
@@ -88,7 +90,7 @@ def test_option_combination_matches_oracle(seed):
     stats = pa.sage_attn_kv_stats(k, v, layout=c["layout"], pv_format=c["pv"]) if c["kv_stats"] else None
     res = pa.sage_attn_fwd_ex(q, k, v, causal=c["causal"], mode=c["mode"], smooth_v=c["smooth_v"], group_map=c["group_map"],
                               layout=c["layout"], pv_format=c["pv"], return_lse=c["lse"], smooth_k=c["smooth_k"],
-                              smooth_q=c["smooth_q"], kv_stats=stats)
+                              smooth_q=c["smooth_q"], kv_stats=stats, delta_s=c["delta_s"])
     torch.cuda.synchronize()
     out, lse = res if c["lse"] else (res, None)
     if c["layout"] == "NHD":
@@ -128,7 +130,7 @@ def test_packed_batch_combination_matches_oracle(seed):
         if c["kv_stats"] else None
     res = pa.sage_attn_fwd_ex(q, k, v, causal=c["causal"], mode=c["mode"], smooth_v=c["smooth_v"], group_map=c["group_map"],
                               pv_format=c["pv"], return_lse=c["lse"], cu_seqlens_q=cu(lens_q), cu_seqlens_k=cu(lens_k),
-                              smooth_k=c["smooth_k"], smooth_q=c["smooth_q"], kv_stats=stats)
+                              smooth_k=c["smooth_k"], smooth_q=c["smooth_q"], kv_stats=stats, delta_s=c["delta_s"])
     torch.cuda.synchronize()
     out, lse = res if c["lse"] else (res, None)
     off = np.concatenate([[0], np.cumsum(lens_q)])
