@@ -70,8 +70,12 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   // key range split (kv_splits): only where few tiles would leave the chip idle, at least 8 key blocks per chunk
   if (a->kv_splits < 0 || a->kv_splits > 64) return SAGE_ERR_INVALID_ARG;
   D->splits = 1;
+  D->pack = 0;
   if (D->kg == KGROUP && D->pvf == PV_E4M3 && a->kv_splits != 1) {
-    const long long tiles = (long long)a->B * a->H * nQb;
+    // short queries on grouped KV heads: the 2..8 query heads of a KV head share one tile when all their queries fit it
+    const int G = a->H / a->H_kv;
+    D->pack = G >= 2 && G <= 8 && (long long)G * a->N <= BQ && !a->cu_seqlens_q;
+    const long long tiles = D->pack ? (long long)a->B * a->H_kv : (long long)a->B * a->H * nQb;
     long long S = a->kv_splits > 1 ? a->kv_splits : (tiles < 256 ? (512 + tiles - 1) / tiles : 1);
     if (S > nKb / 8) S = nKb / 8;
     if (S > 64) S = 64;

@@ -424,9 +424,16 @@ __device__ __forceinline__ size_t lse_index(const AttnParams& p, const Seq& sq, 
   return ((size_t)b * p.H + h) * p.N + r;
 }
 
-template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, int PVF, bool SPLIT = false>
+// PACK (with SPLIT; short queries, grouped KV heads): a tile holds ALL queries of the G = H / H_kv query heads that
+// share one KV head - column c of the tile is query c % N of head c / N of the group (G N <= 128, G <= PACK_G) - so
+// the KV head's codes are walked once for the whole group instead of once per query head with 128 - N idle columns
+// each.  Everything that belongs to a query (its codes, scale, Delta-S row, output row) is then looked up per lane.
+constexpr int PACK_G = 8;             // query heads per KV head a packed tile takes at most (Delta-S rows per LDS stage)
+template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, int PVF, bool SPLIT = false, bool PACK = false>
 __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fwd(const AttnParams p) {
   constexpr bool OCC3 = attn_occupancy<D, GM, PVF>() >= (D == 256 ? 2 : 3);     // the form without a software pipeline
+  static_assert(!PACK || (SPLIT && OCC3 && GM == 0), "packed tiles come with the split key range and the default groups");
+  constexpr int DSR = PACK && INT4 ? PACK_G : 1;   // Delta-S rows per stage
   constexpr int KSC = GM == 0 ? 4 : (GM == 1 ? 16 : 64);    // key scales per block
   constexpr int QG = GM == 0 ? QGROUP : 1;                  // queries per scale
   constexpr int CT = D / 32;          // 32-channel tiles of the output
@@ -439,7 +446,7 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   // 29 KB, so that two workgroups fit a CU)
   constexpr int NST = (D == 256 && attn_occupancy<D, GM, PVF>() >= 2) ? 2 : 3;
   constexpr int PD = NST - 1;         // copies run this many blocks ahead
-  constexpr int XC = 32;              // chunks of the small part: 64 Delta-S floats, then up to 64 key scales
+  constexpr int XC = 16 * DSR + 16;   // chunks of the small part: DSR rows of 64 Delta-S floats, then up to 64 key scales
   constexpr int STAGE = KCK + KC + XC;   // chunks per stage: K^, V^, small part
   __shared__ v4i lds[NST][STAGE];
   __shared__ __align__(16) float s_vs[2][D];   // delta_V and (smooth-V option) mean(V) of this KV head, for the epilogue
@@ -482,6 +489,8 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
     qb = CAUSAL ? p.nQb - 1 - tile % p.nQb : tile % p.nQb;   // heavy tiles first
   }
   if (tile >= p.total_tiles) return;
+  // PACK: tiles count (batch, KV head) pairs; bh is the first query head of the tile's group
+  if constexpr (PACK) bh = (tile / p.Hkv) * p.H + (tile % p.Hkv) * (p.H / p.Hkv);
   const int b = bh / p.H, h = bh % p.H;
   const size_t bhkv = (size_t)b * p.Hkv + h / (p.H / p.Hkv);
   // this sequence's lengths (the launch's N, Nk unless the batch is a variable-length one; slab
@@ -504,8 +513,20 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   }
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int n = lane & 31, half = lane >> 5;
-  const int q_lo = qb * BQ + w * WQ;          // first query of this wavefront
-  const int query = q_lo + n;
+  // PACK: column w * 32 + n of the tile is query qi of head bh + hq; columns past the group's G N queries work on
+  // query 0 of the first head and write nothing
+  int hq = 0, qi = 0;
+  bool col_ok = true;
+  if constexpr (PACK) {
+    const int col = w * WQ + n;
+    col_ok = col < (p.H / p.Hkv) * p.N;
+    hq = col_ok ? col / p.N : 0;
+    qi = col_ok ? col - hq * p.N : 0;
+  }
+  const int q_lo = PACK ? 0 : qb * BQ + w * WQ;          // first query of this wavefront
+  const int q_hi = PACK ? p.N - 1 : q_lo + WQ - 1;       // ... and the last
+  const int query = PACK ? qi : q_lo + n;
+  const size_t bhq = (size_t)bh + hq;                    // this lane's query head
 
   const v4i* gk = reinterpret_cast<const v4i*>(p.k_codes + bhkv * (size_t)p.nKb * k_block_bytes(D, INT4));
   const v4i* gv = reinterpret_cast<const v4i*>(p.v_codes + bhkv * (size_t)p.nKb * BKV * D);
@@ -522,7 +543,7 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
     nblk = kc.j1;
     if (j_begin >= nblk) {                     // an empty chunk: offset -inf, sum 0 (the merge skips it)
       if (t < BQ) {
-        float* el = p.part_el + ((size_t)((bh * p.nQb + qb) * p.splits + split) * BQ + t) * 2;
+        float* el = p.part_el + ((size_t)((PACK ? tile : bh * p.nQb + qb) * p.splits + split) * BQ + t) * 2;
         el[0] = -INFINITY; el[1] = 0.0f;
       }
       return;
@@ -543,9 +564,17 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
     for (int i = 0; i < CPT; ++i)
       dma_b128(gv + (size_t)j * KC + i * 256, (unsigned)t * 16, sb + (unsigned)(KCK + i * 256 + 64 * w) * 16);
     if (w == 0) {
-      if constexpr (INT4) dma_b32(gd + (size_t)j * BKV, (unsigned)lane * 4, sb + (KCK + KC) * 16);
+      if constexpr (INT4) {
+        if constexpr (PACK) {          // one Delta-S row per query head of the group (consecutive heads, one row each)
+          const int G = p.H / p.Hkv;
+          for (int g = 0; g < G; ++g)
+            dma_b32(gd + (size_t)g * p.nKb * BKV + (size_t)j * BKV, (unsigned)lane * 4, sb + (KCK + KC) * 16 + 256u * g);
+        } else {
+          dma_b32(gd + (size_t)j * BKV, (unsigned)lane * 4, sb + (KCK + KC) * 16);
+        }
+      }
     } else if (w == 1) {
-      if (lane < KSC) dma_b32(gs + (size_t)j * KSC, (unsigned)lane * 4, sb + (KCK + KC) * 16 + 256);
+      if (lane < KSC) dma_b32(gs + (size_t)j * KSC, (unsigned)lane * 4, sb + (KCK + KC) * 16 + 256 * DSR);
     }
   };
   // Every wavefront issues at least MINC copies per block, in block order, and loads complete in
@@ -585,15 +614,19 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   constexpr int NP = qk_pieces<D, INT4>();
   qk_op qreg[NP];
   {
-    const v4i* gq = reinterpret_cast<const v4i*>(p.q_codes + ((size_t)bh * p.nQb + qb) * q_slab_bytes(D, INT4)) +
-                    (size_t)w * (q_slab_bytes(D, INT4) / 16 / (BQ / WQ));
+    // (PACK: the lane's query sits in 32-query slice qi / 32 of its own head's slab, at lane position qi % 32)
+    const int slice = PACK ? qi / WQ : w;
+    const int pos = PACK ? (qi % WQ) + 32 * half : lane;
+    const v4i* gq = reinterpret_cast<const v4i*>(p.q_codes + (bhq * p.nQb + qb) * q_slab_bytes(D, INT4)) +
+                    (size_t)slice * (q_slab_bytes(D, INT4) / 16 / (BQ / WQ));
 #pragma unroll
-    for (int s = 0; s < NP; ++s) qreg[s] = load_qk_operand<INT4>(gq, s, lane);
+    for (int s = 0; s < NP; ++s) qreg[s] = load_qk_operand<INT4>(gq, s, pos);
   }
-  const float dq = p.q_scale[((size_t)bh * p.nQb + qb) * (BQ / QG) + (w * WQ + n) / QG];
+  const int row_in_block = PACK ? qi : w * WQ + n;       // the query's place in its smoothing block
+  const float dq = p.q_scale[(bhq * p.nQb + qb) * (BQ / QG) + row_in_block / QG];
   // the row constant of the log-sum-exp output, fetched now so that the epilogue does not wait for it
   float lse_corr = 0.0f;
-  if (p.lse) lse_corr = p.q_corr[((size_t)bh * p.nQb + qb) * BQ + w * WQ + n];
+  if (p.lse) lse_corr = p.q_corr[(bhq * p.nQb + qb) * BQ + row_in_block];
 
   RowState<D> st;
 #pragma unroll
@@ -611,7 +644,7 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   int n_act = nblk;                                            // blocks with any visible key
   if (CAUSAL) {
     n_plain = min(n_plain, (q_lo + sq.coff + 1) / BKV);        // key0 + 63 <= q_lo + coff
-    n_act = min(nblk, (q_lo + sq.coff + WQ - 1) / BKV + 1);    // key0 <= q_lo + 31 + coff
+    n_act = min(nblk, (q_hi + sq.coff) / BKV + 1);             // key0 <= q_hi + coff
   }
   n_plain = __builtin_amdgcn_readfirstlane(n_plain);
   n_act = __builtin_amdgcn_readfirstlane(n_act);
@@ -657,7 +690,7 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   // (they are free once the previous block's exponentials of that tile are done)
   auto read_ds = [&](int stg, int kt) {
     if constexpr (INT4) {
-      const v4f* dsv = reinterpret_cast<const v4f*>(reinterpret_cast<const float*>(&lds[stg][KCK + KC]) + 32 * kt + 16 * half);
+      const v4f* dsv = reinterpret_cast<const v4f*>(reinterpret_cast<const float*>(&lds[stg][KCK + KC]) + 64 * hq + 32 * kt + 16 * half);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const v4f t4 = dsv[g];
@@ -667,7 +700,7 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
     }
   };
   auto read_scales = [&](int stg) {
-    const float* lx = reinterpret_cast<const float*>(&lds[stg][KCK + KC]);
+    const float* lx = reinterpret_cast<const float*>(&lds[stg][KCK + KC]) + 64 * (DSR - 1);
     if constexpr (GM == 0) {
       ks.s[0] = lx[64 + half];
       ks.s[1] = lx[66 + half];
@@ -851,8 +884,8 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   }
   if constexpr (SPLIT) {
     // a chunk of the keys: the sums stay under the chunk's own exponent offset and go to the merge kernel as they are
-    const size_t prow = (size_t)((bh * p.nQb + qb) * p.splits + split) * BQ + w * WQ + n;
-    if (query < sq.n) {
+    const size_t prow = (size_t)((PACK ? tile : bh * p.nQb + qb) * p.splits + split) * BQ + w * WQ + n;
+    if (PACK ? col_ok : query < sq.n) {
       if (half == 0) { p.part_el[prow * 2] = m_sub; p.part_el[prow * 2 + 1] = l_tot; }
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct) {
@@ -901,56 +934,75 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
 
 // Merge of the partial results of a tile's key chunks (Eq. 1 applied to disjoint key sets): under the largest of
 // the chunks' exponent offsets e* the sums add up with weights 2^(e_s - e*); then the epilogue of Algorithm 1.
-// One workgroup per tile, two threads per query row (half of the channels each).
-template <int D, bool BF16>
+// One workgroup per tile; a thread owns four channels of a row, d / 4 threads a row, and the workgroup walks the
+// tile's rows 1024 / d at a time - so a tile with few valid rows (a decode step) still spreads over a whole row of
+// threads, and a row's chunks are read as contiguous 4 d bytes.
+// PACK: the tiles of k_attn_fwd's packed form - row r of a tile is query r % N of head r / N of the KV head's group.
+template <int D, bool BF16, bool PACK = false>
 __global__ void __launch_bounds__(256) k_merge_splits(const AttnParams p) {
+  constexpr int TPR = D / 4, RP = 256 / TPR;      // threads per row, rows per pass
   const int tile = blockIdx.x;
-  const int bh = tile / p.nQb, qb = tile % p.nQb;
-  const int b = bh / p.H, h = bh % p.H;
-  const size_t bhkv = (size_t)b * p.Hkv + h / (p.H / p.Hkv);
-  const Seq sq = seq_of(p.seq, (unsigned)b, p.N, p.Nk);
-  if (qb * BQ >= sq.n || sq.nk == 0) return;   // (a sequence without keys was written by the attention kernel)
-  const int t = threadIdx.x, r = t >> 1, c_lo = (t & 1) * (D / 2);
-  const int query = qb * BQ + r;
-  if (query >= sq.n) return;
-  const size_t row0 = (size_t)tile * p.splits * BQ + r;       // this row in chunk 0; chunk s is s * BQ rows further
-  float e_max = -INFINITY;
-  for (int s = 0; s < p.splits; ++s) e_max = fmaxf(e_max, p.part_el[(row0 + (size_t)s * BQ) * 2]);
-  float l = 0.0f;
-  float acc[D / 2];
-#pragma unroll
-  for (int c = 0; c < D / 2; ++c) acc[c] = 0.0f;
-  for (int s = 0; s < p.splits; ++s) {
-    const size_t row = row0 + (size_t)s * BQ;
-    const float e = p.part_el[row * 2];
-    if (e == -INFINITY) continue;              // an empty chunk
-    const float wgt = __builtin_amdgcn_exp2f(e - e_max);
-    l = __fmaf_rn(wgt, p.part_el[row * 2 + 1], l);
-    const v4f* o = reinterpret_cast<const v4f*>(p.part_o + row * D + c_lo);
-#pragma unroll
-    for (int c = 0; c < D / 8; ++c) {
-      const v4f o4 = o[c];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) acc[4 * c + k] = __fmaf_rn(wgt, o4[k], acc[4 * c + k]);
+  const int t = threadIdx.x, c_lo = 4 * (t % TPR);
+  const int n_rows = PACK ? (p.H / p.Hkv) * p.N : BQ;
+  for (int r = t / TPR; r < n_rows; r += RP) {
+    int bh = tile / p.nQb, qb = tile % p.nQb, query = qb * BQ + r;
+    if constexpr (PACK) {
+      bh = (tile / p.Hkv) * p.H + (tile % p.Hkv) * (p.H / p.Hkv) + r / p.N;
+      qb = 0;
+      query = r % p.N;
     }
-  }
-  if (p.lse && (t & 1) == 0)
-    p.lse[lse_index(p, sq, b, h, query)] =
-        LN2 * ((e_max + __builtin_amdgcn_logf(l)) + p.q_corr[((size_t)bh * p.nQb + qb) * BQ + r]);
-  const float inv_l = __fdiv_rn(1.0f, l);
-  unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) +
-                         row_offset(p.om, head_offset(p.om, (unsigned)bh), (int)sq.q0 + query) + c_lo;
-  const float* vs = p.v_scale + bhkv * D + c_lo;
-  const float* vm = p.v_mean ? p.v_mean + bhkv * D + c_lo : nullptr;
+    const int b = bh / p.H, h = bh % p.H;
+    const size_t bhkv = (size_t)b * p.Hkv + h / (p.H / p.Hkv);
+    const Seq sq = seq_of(p.seq, (unsigned)b, p.N, p.Nk);
+    if (sq.nk == 0 || query >= sq.n) return;     // (rows ascend; a sequence without keys was written by the attention kernel)
+    const size_t row0 = (size_t)tile * p.splits * BQ + r;       // this row in chunk 0; chunk s is s * BQ rows further
+    float e_max = -INFINITY;
+    for (int s0 = 0; s0 < p.splits; s0 += 8) {
+      float e[8];
 #pragma unroll
-  for (int c = 0; c < D / 2; c += 4) {
+      for (int i = 0; i < 8; ++i) e[i] = p.part_el[(row0 + (size_t)min(s0 + i, p.splits - 1) * BQ) * 2];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) e_max = fmaxf(e_max, e[i]);
+    }
+    float l = 0.0f;
+    v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    // eight chunks at a time, all their loads issued before the first use (one round trip per eight chunks, not one
+    // per chunk); the chunks are summed in order
+    for (int s0 = 0; s0 < p.splits; s0 += 8) {
+      float e[8], lc[8];
+      v4f o4[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const size_t row = row0 + (size_t)min(s0 + i, p.splits - 1) * BQ;
+        e[i] = p.part_el[row * 2];
+        lc[i] = p.part_el[row * 2 + 1];
+        o4[i] = *reinterpret_cast<const v4f*>(p.part_o + row * D + c_lo);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (s0 + i >= p.splits || e[i] == -INFINITY) continue;     // (an empty chunk left its sums unwritten)
+        const float wgt = __builtin_amdgcn_exp2f(e[i] - e_max);
+        l = __fmaf_rn(wgt, lc[i], l);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[k] = __fmaf_rn(wgt, o4[i][k], acc[k]);
+      }
+    }
+    if (p.lse && c_lo == 0)
+      p.lse[lse_index(p, sq, b, h, query)] =
+          LN2 * ((e_max + __builtin_amdgcn_logf(l)) + p.q_corr[((size_t)bh * p.nQb + qb) * BQ + (query - qb * BQ)]);
+    const float inv_l = __fdiv_rn(1.0f, l);
+    unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) +
+                           row_offset(p.om, head_offset(p.om, (unsigned)bh), (int)sq.q0 + query) + c_lo;
+    const v4f vs = *reinterpret_cast<const v4f*>(p.v_scale + bhkv * D + c_lo);
     float o4[4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      o4[k] = __fmul_rn(__fmul_rn(acc[c + k], inv_l), vs[c + k]);
-      if (vm) o4[k] = __fadd_rn(o4[k], vm[c + k]);
+    for (int k = 0; k < 4; ++k) o4[k] = __fmul_rn(__fmul_rn(acc[k], inv_l), vs[k]);
+    if (p.v_mean) {
+      const v4f vm = *reinterpret_cast<const v4f*>(p.v_mean + bhkv * D + c_lo);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o4[k] = __fadd_rn(o4[k], vm[k]);
     }
-    *reinterpret_cast<uint2*>(orow + c) = make_uint2(pack16x2<BF16>(o4[0], o4[1]), pack16x2<BF16>(o4[2], o4[3]));
+    *reinterpret_cast<uint2*>(orow) = make_uint2(pack16x2<BF16>(o4[0], o4[1]), pack16x2<BF16>(o4[2], o4[3]));
   }
 }
 
@@ -1010,6 +1062,13 @@ static hipError_t launch_attention_g(const Dims& Dm, const Ptrs& P, hipStream_t 
   p.kappa = Dm.kappa;
   p.splits = Dm.splits; p.part_o = P.part_o; p.part_el = P.part_el;
   if constexpr (GM == 0 && PVF == PV_E4M3) {        // (the key split comes with the default groups and data type)
+    if (Dm.pack) {                                  // packed tiles: one per (batch, KV head), any number of chunks
+      p.total_tiles = Dm.B * Dm.Hkv;
+      const int grid = 8 * ((p.total_tiles * Dm.splits + 7) / 8);
+      k_attn_fwd<D, INT4, CAUSAL, BF16, GM, PVF, true, true><<<grid, 256, 0, s>>>(p);
+      k_merge_splits<D, BF16, true><<<p.total_tiles, 256, 0, s>>>(p);
+      return hipGetLastError();
+    }
     if (Dm.splits > 1) {
       const int grid = 8 * ((p.total_tiles * Dm.splits + 7) / 8);
       k_attn_fwd<D, INT4, CAUSAL, BF16, GM, PVF, true><<<grid, 256, 0, s>>>(p);

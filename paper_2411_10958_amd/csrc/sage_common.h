@@ -100,6 +100,7 @@ struct Dims {
   int pvf;      // data type of P~ and V: PV_E4M3, PV_E5M2 or PV_INT8
   int tensor_groups;  // one scale per (batch, head) tensor of Q and of K (implies block_groups)
   int splits;         // workgroups per query tile in the attention kernel (key range split; 1 = none)
+  int pack;           // the query heads of a KV head share one tile (short queries, grouped KV heads; with the split path)
 };
 
 // Workspace map (all offsets multiples of 256 bytes).
@@ -173,8 +174,9 @@ inline Workspace make_workspace(const Dims& D) {
   // digits of the block means for the Delta-S product: 6 planes of d bytes per (head, query block), and 2^E per row
   w.q_digits = take(D.int4 ? BH * D.nQb * 6 * D.d : 0);
   w.q_dscale = take(D.int4 ? BH * D.nQb * sizeof(float) : 0);
-  w.part_o = take(D.splits > 1 ? BH * D.nQb * D.splits * BQ * D.d * sizeof(float) : 0);
-  w.part_el = take(D.splits > 1 ? BH * D.nQb * D.splits * BQ * 2 * sizeof(float) : 0);
+  const size_t split_tiles = D.pack ? (size_t)D.B * D.Hkv : (D.splits > 1 ? BH * D.nQb : 0);
+  w.part_o = take(split_tiles * D.splits * BQ * D.d * sizeof(float));
+  w.part_el = take(split_tiles * D.splits * BQ * 2 * sizeof(float));
   w.total = off;
   return w;
 }

@@ -73,13 +73,19 @@ def test_workspace_size_formula():
 def test_key_split_policy():
     """sage_attn_kv_splits (host logic only): the library splits the key range by itself only when a launch has fewer
     than 256 tiles, into enough chunks for about 512 workgroups, at least 8 key blocks per chunk and at most 64; the
-    caller's number is honoured up to the same limits; finer group maps and other P~V data types never split."""
+    caller's number is honoured up to the same limits; finer group maps and other P~V data types never split.  Short
+    queries on grouped KV heads (2..8 query heads per KV head, all their queries within 128) count one tile per KV head."""
     pa, _ = _lib()
     S = lambda **kw: pa.sage_attn_kv_splits(_args(pa, **kw))
     assert S() == 1                                                   # 4096 tiles: nothing to fill
     assert S(B=1, H=1, H_kv=1) == 8                                       # 32 tiles, 64 key blocks: 8 blocks per chunk at least
     assert S(B=1, H=8, H_kv=8, N=128, N_kv=32768) == 64                      # 8 tiles: 512 / 8 = 64 chunks of 8 blocks
-    assert S(B=4, H=32, H_kv=8, N=1, N_kv=32768, causal=1) == 4       # a decode step of 128 heads: 512 / 128
+    # a decode step of 128 query heads on 32 KV heads: the 4 heads of a group share a tile, 32 tiles, 512 / 32 chunks
+    assert S(B=4, H=32, H_kv=8, N=1, N_kv=32768, causal=1) == 16
+    assert S(B=4, H=32, H_kv=8, N=32, N_kv=32768, causal=1) == 16     # 4 heads x 32 queries still fit one tile
+    assert S(B=4, H=32, H_kv=8, N=33, N_kv=32768, causal=1) == 4      # ... 33 do not: a tile per query head, 512 / 128
+    assert S(B=4, H=32, H_kv=2, N=1, N_kv=32768, causal=1) == 4       # 16 query heads per KV head: not packed
+    assert S(B=64, H=32, H_kv=8, N=1, N_kv=4096) == 1                 # 512 packed tiles fill the chip unsplit
     assert S(B=1, H=2, H_kv=2, N=1, N_kv=512) == 1                           # too few key blocks to cut
     assert S(B=2, H=32, N=512) == 1                                   # 256 tiles: not split
     assert S(B=2, H=32, N=512, kv_splits=3) == 1                      # ... and 8 key blocks cannot be cut into 3 chunks of 8

@@ -510,6 +510,12 @@ SPLIT_CASES = [
     (130, 1100, 64, "fp16", 2, 1, False, 3),      # two query tiles, the second one ragged
     (7, 1700, 256, "bf16", 2, 2, True, 0),
     (200, 1030, 128, "bf16", 1, 1, True, 5),      # chunks of different lengths per tile, a diagonal inside the last one
+    # grouped KV heads, all queries of a group within 128: the group's query heads share one tile
+    (1, 2100, 128, "bf16", 8, 1, True, 0),        # a decode step, 8 query heads per KV head
+    (16, 1600, 64, "fp16", 4, 2, True, 0),        # 2 heads x 16 queries: one wavefront's columns
+    (32, 1100, 128, "bf16", 4, 1, False, 2),      # 4 heads x 32 queries: the whole tile
+    (5, 1100, 256, "bf16", 6, 2, True, 0),        # 3 heads x 5 queries
+    (40, 1300, 128, "fp16", 3, 1, True, 4),       # 3 heads x 40 queries: heads straddle the wavefronts' column ranges
 ]
 
 
