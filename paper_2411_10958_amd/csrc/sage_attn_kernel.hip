@@ -646,6 +646,10 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
     n_plain = min(n_plain, (q_lo + sq.coff + 1) / BKV);        // key0 + 63 <= q_lo + coff
     n_act = min(nblk, (q_hi + sq.coff) / BKV + 1);             // key0 <= q_hi + coff
   }
+  if constexpr (PACK) {
+    // a wavefront whose 32 columns all lie past the group's queries only keeps up the copies and the barriers
+    if (w * WQ >= (p.H / p.Hkv) * p.N) n_plain = n_act = j_begin;
+  }
   n_plain = __builtin_amdgcn_readfirstlane(n_plain);
   n_act = __builtin_amdgcn_readfirstlane(n_act);
 
