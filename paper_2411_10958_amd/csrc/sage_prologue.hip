@@ -237,23 +237,25 @@ __global__ void __launch_bounds__(256) k_v_absmax(const unsigned short* __restri
 
 // k_mean = fl32(sum / N) (Eq. 2), delta_V = fl32(max|V| / 448) (Sec. 3.3); with the smooth-V option
 // this call produces v_mean = fl32(sum / N) instead of delta_V, which k_finalize_vscale adds later.
+constexpr int FIN_ENT = 16, FIN_PARTS = 16;     // k_finalize_stats: entries per workgroup, threads per entry (256 threads)
 __global__ void k_finalize_stats(const double* __restrict__ k_sum, const double* __restrict__ v_sum,
                                  const unsigned* __restrict__ v_max, float* __restrict__ k_mean,
                                  float* __restrict__ v_mean, float* __restrict__ v_scale, int n, int Nq, int N,
                                  int d, int Hkv, int nchunk, SeqMap sm, float code_max, int smooth_k) {
-  // 64 (head, channel) entries per workgroup, four threads each: thread part p sums chunks p, p + 4, ... (the sums
-  // are exact in float64, so their order does not matter) and the four meet in LDS
-  __shared__ double s_k[4][64], s_v[4][64];
-  __shared__ float s_m[4][64];
-  const int e = threadIdx.x & 63, part = threadIdx.x >> 6;
-  const int i = blockIdx.x * 64 + e;
+  // FIN_ENT (head, channel) entries per workgroup, FIN_PARTS threads each: thread part p sums chunks p, p + FIN_PARTS,
+  // ... (the sums are exact in float64, so their order does not matter) and the parts meet in LDS.  Many threads per
+  // entry because a long key range leaves many chunks (128 at 32 k keys) and a thread's loads are one round trip each.
+  __shared__ double s_k[FIN_PARTS][FIN_ENT], s_v[FIN_PARTS][FIN_ENT];
+  __shared__ float s_m[FIN_PARTS][FIN_ENT];
+  const int e = threadIdx.x % FIN_ENT, part = threadIdx.x / FIN_ENT;
+  const int i = blockIdx.x * FIN_ENT + e;
   double ks = 0.0, vs = 0.0;
   float vm = 0.0f;
   if (i < n) {
     const int head = i / d, c = i - head * d;
     const size_t p0 = (size_t)head * nchunk * d + c;
 #pragma unroll 4
-    for (int ch = part; ch < nchunk; ch += 4) {
+    for (int ch = part; ch < nchunk; ch += FIN_PARTS) {
       ks += k_sum[p0 + (size_t)ch * d];
       if (v_sum) vs += v_sum[p0 + (size_t)ch * d];
       else vm = fmaxf(vm, __uint_as_float(v_max[p0 + (size_t)ch * d]));
@@ -264,9 +266,13 @@ __global__ void k_finalize_stats(const double* __restrict__ k_sum, const double*
   if (part == 0 && i < n) {
     const int head = i / d;
     const int nk = seq_of(sm, (unsigned)(head / Hkv), Nq, N).nk;      // this sequence's key count
-    ks = (s_k[0][e] + s_k[1][e]) + (s_k[2][e] + s_k[3][e]);
-    vs = (s_v[0][e] + s_v[1][e]) + (s_v[2][e] + s_v[3][e]);
-    vm = fmaxf(fmaxf(s_m[0][e], s_m[1][e]), fmaxf(s_m[2][e], s_m[3][e]));
+    ks = 0.0; vs = 0.0; vm = 0.0f;
+#pragma unroll
+    for (int q = 0; q < FIN_PARTS; ++q) {
+      ks += s_k[q][e];
+      vs += s_v[q][e];
+      vm = fmaxf(vm, s_m[q][e]);
+    }
     k_mean[i] = nk > 0 && smooth_k ? (float)(ks / (double)nk) : 0.0f;   // smoothing of K off: mean 0
     if (v_sum) v_mean[i] = nk > 0 ? (float)(vs / (double)nk) : 0.0f;
     else v_scale[i] = __fdiv_rn(vm, code_max);
@@ -1185,13 +1191,13 @@ static void launch_stats_t(const Dims& Dm, const Ptrs& P, hipStream_t s) {
   const float code_max = Dm.pvf == PV_INT8 ? INT8_PV_MAX : (Dm.pvf == PV_E5M2 ? E5M2_MAX : E4M3_MAX);
   if (Dm.smooth_v) {
     k_col_stats<BF16, D, true><<<gstat, 256, 0, s>>>(k, v, P.k_sum, P.v_sum, P.v_max, Dm.N, Dm.Nk, km, sm);
-    k_finalize_stats<<<(nstat + 63) / 64, 256, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
+    k_finalize_stats<<<(nstat + FIN_ENT - 1) / FIN_ENT, FIN_ENT * FIN_PARTS, 0, s>>>(P.k_sum, P.v_sum, P.v_max, P.k_mean, P.v_mean, P.v_scale,
                                                         nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max, Dm.smooth_k);
     k_v_absmax<BF16, D><<<gstat, 256, 0, s>>>(v, P.v_mean, P.v_max, Dm.N, Dm.Nk, km, sm);
     k_finalize_vscale<<<(nstat + 255) / 256, 256, 0, s>>>(P.v_max, P.v_scale, nstat, Dm.d, nchunk, code_max);
   } else {
     k_col_stats<BF16, D, false><<<gstat, 256, 0, s>>>(k, v, P.k_sum, nullptr, P.v_max, Dm.N, Dm.Nk, km, sm);
-    k_finalize_stats<<<(nstat + 63) / 64, 256, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
+    k_finalize_stats<<<(nstat + FIN_ENT - 1) / FIN_ENT, FIN_ENT * FIN_PARTS, 0, s>>>(P.k_sum, nullptr, P.v_max, P.k_mean, nullptr, P.v_scale,
                                                         nstat, Dm.N, Dm.Nk, Dm.d, Dm.Hkv, nchunk, sm, code_max, Dm.smooth_k);
   }
 }
