@@ -428,7 +428,6 @@ __device__ __forceinline__ size_t lse_index(const AttnParams& p, const Seq& sq, 
 // share one KV head - column c of the tile is query c % N of head c / N of the group (G N <= 128, G <= PACK_G) - so
 // the KV head's codes are walked once for the whole group instead of once per query head with 128 - N idle columns
 // each.  Everything that belongs to a query (its codes, scale, Delta-S row, output row) is then looked up per lane.
-constexpr int PACK_G = 8;             // query heads per KV head a packed tile takes at most (Delta-S rows per LDS stage)
 template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, int PVF, bool SPLIT = false, bool PACK = false>
 __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fwd(const AttnParams p) {
   constexpr bool OCC3 = attn_occupancy<D, GM, PVF>() >= (D == 256 ? 2 : 3);     // the form without a software pipeline

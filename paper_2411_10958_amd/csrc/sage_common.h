@@ -13,6 +13,7 @@ constexpr int BKV = 64;      // keys per block = level-1 accumulation block (b_k
 constexpr int WQ = 32;       // queries per wavefront (one 32x32 MFMA column tile)
 constexpr int QGROUP = 2;    // queries per quantization group (default group map)
 constexpr int KGROUP = 16;   // keys per quantization group (default group map)
+constexpr int PACK_G = 8;    // query heads per KV head that may share one attention tile (Delta-S rows per LDS stage)
 constexpr float E4M3_MAX = 448.0f;
 constexpr int MAX_TOKENS = 1 << 24;   // per sequence; keeps token and tile arithmetic inside 32-bit integers
 constexpr int STAT_ROWS = 256;  // tokens per workgroup of the column-statistics pass
