@@ -496,8 +496,11 @@ __global__ void __launch_bounds__(256) k_quant_q8(const unsigned short* __restri
 //    conversion per query instead of per-element table look-ups and 6-bit shifts.
 // LDS rows are kept as 16-byte chunks with the chunk index XOR-ed by the row's group number, which
 // makes both maps conflict-free for d = 128.
+// LDS: the raw rows (32 KB at d = 128), which the packed code image takes over once every thread holds its values in
+// registers, and one row of column sums per wavefront (the row groups of a wavefront are summed by lane exchanges
+// first) - 37 KB, so that four workgroups share a CU and their loads, arithmetic and stores overlap.
 template <bool BF16, int D>
-__global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restrict__ Q,
+__global__ void __launch_bounds__(256, D == 256 ? 2 : 4) k_quant_q4(const unsigned short* __restrict__ Q,
                                                   float* __restrict__ q_mean, float* __restrict__ q_scale,
                                                   int8_t* __restrict__ q_codes, int N, int Nk, int nQb,
                                                   int block_groups, int qg, TensorMap qm, SeqMap sm,
@@ -509,11 +512,9 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
   constexpr int CPL = D / 4, CPC = CPL / 8;                      // quantization map: 2 rows x CPL channels
   constexpr int QMAX = 7;
   constexpr int SLAB = (int)q_slab_bytes(D, true);
-  constexpr int SUMS = (int)sizeof(double) * NRG * D;
-  __shared__ uint4 s_raw[BQ * NCG];
-  // the column sums, and later (everyone past them) the packed code image of the slab
-  __shared__ __align__(16) unsigned char s_buf[SLAB > SUMS ? SLAB : SUMS];
-  double (*s_sum)[D] = reinterpret_cast<double (*)[D]>(s_buf);
+  __shared__ uint4 s_raw[BQ * NCG];           // the raw rows; later the packed code image of the slab
+  static_assert(SLAB <= (int)sizeof(uint4) * BQ * NCG, "the code image fits where the raw rows were");
+  __shared__ double s_sum[4][D];              // column sums, one row per wavefront
   __shared__ __align__(16) float s_mean[D];
   __shared__ float s_bmax[4];
   const int t = threadIdx.x;
@@ -547,13 +548,22 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
 #pragma unroll
       for (int e = 0; e < 8; ++e) cs[e] += (double)x8[e];
     }
+    // a wavefront holds 64 / NCG row groups (lane = (rg % (64 / NCG)) * NCG + cg): summed by lane exchanges first
+    // (float64 sums of 16-bit values are exact: the order of the additions does not matter)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s_sum[rg][cg * 8 + e] = cs[e];
+    for (int e = 0; e < 8; ++e) {
+#pragma unroll
+      for (int o = NCG; o < 64; o <<= 1) cs[e] += __shfl_xor(cs[e], o, 64);
+    }
+    if ((t & 63) < NCG) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s_sum[t >> 6][cg * 8 + e] = cs[e];
+    }
   }
   __syncthreads();
   if (t < D) {
     double sm = 0.0;
-    for (int g = 0; g < NRG; ++g) sm += s_sum[g][t];
+    for (int g = 0; g < 4; ++g) sm += s_sum[g][t];
     const float m = smooth_q ? (float)(sm / (double)valid) : 0.0f;   // smoothing of Q off: mean 0
     s_mean[t] = m;
     q_mean[(bh * nQb + qb) * D + t] = m;
@@ -604,7 +614,8 @@ __global__ void __launch_bounds__(256) k_quant_q4(const unsigned short* __restri
     __syncthreads();
     mxr[0] = mxr[1] = fmaxf(fmaxf(s_bmax[0], s_bmax[1]), fmaxf(s_bmax[2], s_bmax[3]));
   }
-  uint8_t* img = s_buf;                  // everyone is past the column sums
+  __syncthreads();                       // every thread holds its rows in registers: the image may take their place
+  uint8_t* img = reinterpret_cast<uint8_t*>(s_raw);
   // the thread's CPL channels of a query are one MFMA lane payload of 32 codes (d = 128), half of one (d = 64) or
   // two of them (d = 256: both lane halves of one operand)
   constexpr int NPL = CPL > 32 ? CPL / 32 : 1, CPP = CPL / NPL;     // payloads per query and thread, codes in each
