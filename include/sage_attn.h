@@ -157,8 +157,8 @@ typedef struct sage_attn_args {
                               decides (it splits when there are fewer than 256 tiles; sage_attn_kv_splits tells);
                               1: never; 2..64: this many (cut to one chunk per 8 key blocks at most).  Default groups
                               (SAGE_GROUPS_LANE, _BLOCK, _TENSOR) and SAGE_PV_E4M3 only, else 1.
-                              With 2..8 query heads per KV head whose queries all fit one tile (N * H / H_kv <= 128, no
-                              cu_seqlens) and kv_splits != 1, a tile is a KV head: its query heads share the tile's 128
+                              With 2..8 query heads per KV head whose queries all fit one tile (N * H / H_kv <= 128,
+                              N the longest sequence's) and kv_splits != 1, a tile is a KV head: its query heads share the tile's 128
                               columns, so the KV head's codes are walked once for the group (tiles = B * H_kv; also when
                               the chunk count comes out as 1).  Same arithmetic per query, same chunk rule.
                               Chunks of a tile: with nblk its key blocks (those up to its last query's last visible key

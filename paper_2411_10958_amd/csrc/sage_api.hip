@@ -74,7 +74,7 @@ int validate(const sage_attn_args* a, Dims* D, bool need_io) {
   if (D->kg == KGROUP && D->pvf == PV_E4M3 && a->kv_splits != 1) {
     // short queries on grouped KV heads: the 2..8 query heads of a KV head share one tile when all their queries fit it
     const int G = a->H / a->H_kv;
-    D->pack = G >= 2 && G <= PACK_G && (long long)G * a->N <= BQ && !a->cu_seqlens_q;
+    D->pack = G >= 2 && G <= PACK_G && (long long)G * a->N <= BQ;     // (a->N: the longest sequence's queries)
     const long long tiles = D->pack ? (long long)a->B * a->H_kv : (long long)a->B * a->H * nQb;
     long long S = a->kv_splits > 1 ? a->kv_splits : (tiles < 256 ? (512 + tiles - 1) / tiles : 1);
     if (S > nKb / 8) S = nKb / 8;

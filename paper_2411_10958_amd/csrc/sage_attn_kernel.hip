@@ -425,7 +425,8 @@ __device__ __forceinline__ size_t lse_index(const AttnParams& p, const Seq& sq, 
 }
 
 // PACK (with SPLIT; short queries, grouped KV heads): a tile holds ALL queries of the G = H / H_kv query heads that
-// share one KV head - column c of the tile is query c % N of head c / N of the group (G N <= 128, G <= PACK_G) - so
+// share one KV head - column c of the tile is query c % n of head c / n of the group, n the sequence's query count
+// (G N <= 128 for the longest sequence, G <= PACK_G) - so
 // the KV head's codes are walked once for the whole group instead of once per query head with 128 - N idle columns
 // each.  Everything that belongs to a query (its codes, scale, Delta-S row, output row) is then looked up per lane.
 template <int D, bool INT4, bool CAUSAL, bool BF16, int GM, int PVF, bool SPLIT = false, bool PACK = false>
@@ -500,14 +501,16 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   const int t = threadIdx.x, lane = t & 63;
   if (sq.nk == 0) {                            // no keys at all: the rows are defined as zeros
     if (SPLIT && split != 0) return;           // (written once; the merge kernel leaves such a tile alone)
-    unsigned short* o = reinterpret_cast<unsigned short*>(p.out) + head_offset(p.om, (unsigned)bh);
-    for (int idx = t; idx < BQ * (D / 8); idx += 256) {
-      const int row = qb * BQ + idx / (D / 8);
-      if (row < sq.n)
-        *reinterpret_cast<uint4*>(o + row_offset(p.om, 0, (int)sq.q0 + row) + (idx % (D / 8)) * 8) =
-            make_uint4(0u, 0u, 0u, 0u);
+    for (int g = 0; g < (PACK ? p.H / p.Hkv : 1); ++g) {        // (PACK: the tile's rows belong to the whole group)
+      unsigned short* o = reinterpret_cast<unsigned short*>(p.out) + head_offset(p.om, (unsigned)(bh + g));
+      for (int idx = t; idx < BQ * (D / 8); idx += 256) {
+        const int row = qb * BQ + idx / (D / 8);
+        if (row < sq.n)
+          *reinterpret_cast<uint4*>(o + row_offset(p.om, 0, (int)sq.q0 + row) + (idx % (D / 8)) * 8) =
+              make_uint4(0u, 0u, 0u, 0u);
+      }
+      if (p.lse && t < BQ && qb * BQ + t < sq.n) p.lse[lse_index(p, sq, b, h + g, qb * BQ + t)] = -INFINITY;
     }
-    if (p.lse && t < BQ && qb * BQ + t < sq.n) p.lse[lse_index(p, sq, b, h, qb * BQ + t)] = -INFINITY;
     return;
   }
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -518,12 +521,12 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   bool col_ok = true;
   if constexpr (PACK) {
     const int col = w * WQ + n;
-    col_ok = col < (p.H / p.Hkv) * p.N;
-    hq = col_ok ? col / p.N : 0;
-    qi = col_ok ? col - hq * p.N : 0;
+    col_ok = col < (p.H / p.Hkv) * sq.n;      // (sq.n >= 1 here)
+    hq = col_ok ? col / sq.n : 0;
+    qi = col_ok ? col - hq * sq.n : 0;
   }
   const int q_lo = PACK ? 0 : qb * BQ + w * WQ;          // first query of this wavefront
-  const int q_hi = PACK ? p.N - 1 : q_lo + WQ - 1;       // ... and the last
+  const int q_hi = PACK ? sq.n - 1 : q_lo + WQ - 1;      // ... and the last
   const int query = PACK ? qi : q_lo + n;
   const size_t bhq = (size_t)bh + hq;                    // this lane's query head
 
@@ -647,7 +650,7 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
   }
   if constexpr (PACK) {
     // a wavefront whose 32 columns all lie past the group's queries only keeps up the copies and the barriers
-    if (w * WQ >= (p.H / p.Hkv) * p.N) n_plain = n_act = j_begin;
+    if (w * WQ >= (p.H / p.Hkv) * sq.n) n_plain = n_act = j_begin;
   }
   n_plain = __builtin_amdgcn_readfirstlane(n_plain);
   n_act = __builtin_amdgcn_readfirstlane(n_act);
@@ -940,23 +943,25 @@ __global__ void __launch_bounds__(256, (attn_occupancy<D, GM, PVF>())) k_attn_fw
 // One workgroup per tile; a thread owns four channels of a row, d / 4 threads a row, and the workgroup walks the
 // tile's rows 1024 / d at a time - so a tile with few valid rows (a decode step) still spreads over a whole row of
 // threads, and a row's chunks are read as contiguous 4 d bytes.
-// PACK: the tiles of k_attn_fwd's packed form - row r of a tile is query r % N of head r / N of the KV head's group.
+// PACK: the tiles of k_attn_fwd's packed form - row r of a tile is query r % n of head r / n of the KV head's group
+// (n: the sequence's query count).
 template <int D, bool BF16, bool PACK = false>
 __global__ void __launch_bounds__(256) k_merge_splits(const AttnParams p) {
   constexpr int TPR = D / 4, RP = 256 / TPR;      // threads per row, rows per pass
   const int tile = blockIdx.x;
   const int t = threadIdx.x, c_lo = 4 * (t % TPR);
-  const int n_rows = PACK ? (p.H / p.Hkv) * p.N : BQ;
-  for (int r = t / TPR; r < n_rows; r += RP) {
+  for (int r = t / TPR; r < BQ; r += RP) {
     int bh = tile / p.nQb, qb = tile % p.nQb, query = qb * BQ + r;
+    if constexpr (PACK) bh = (tile / p.Hkv) * p.H + (tile % p.Hkv) * (p.H / p.Hkv);      // the group's first head
+    const Seq sq = seq_of(p.seq, (unsigned)(bh / p.H), p.N, p.Nk);
     if constexpr (PACK) {
-      bh = (tile / p.Hkv) * p.H + (tile % p.Hkv) * (p.H / p.Hkv) + r / p.N;
+      if (sq.n <= 0 || r >= (p.H / p.Hkv) * sq.n) return;
+      bh += r / sq.n;
       qb = 0;
-      query = r % p.N;
+      query = r % sq.n;
     }
     const int b = bh / p.H, h = bh % p.H;
     const size_t bhkv = (size_t)b * p.Hkv + h / (p.H / p.Hkv);
-    const Seq sq = seq_of(p.seq, (unsigned)b, p.N, p.Nk);
     if (sq.nk == 0 || query >= sq.n) return;     // (rows ascend; a sequence without keys was written by the attention kernel)
     const size_t row0 = (size_t)tile * p.splits * BQ + r;       // this row in chunk 0; chunk s is s * BQ rows further
     float e_max = -INFINITY;

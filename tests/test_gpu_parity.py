@@ -638,6 +638,49 @@ def test_varlen_batch_equals_one_sequence_at_a_time(lens_q, lens_k, d, dtype, H,
     assert checked
 
 
+PACKED_DECODE_CASES = [
+    # lens_q, lens_k, d, dtype, H, Hkv, causal, kv_splits: few queries per sequence on grouped KV heads - the query heads
+    # of a KV head share one tile per sequence
+    ([1, 1, 1, 1], [1100, 1300, 2048, 70], 128, "bf16", 8, 2, True, 2),            # decode steps against caches of different lengths
+    ([3, 8, 0, 1, 5], [1500, 1200, 900, 0, 1024], 64, "fp16", 4, 2, True, 2),      # a sequence without queries, one without keys
+    ([16, 2], [640, 1280], 128, "bf16", 6, 2, False, 2),
+]
+
+
+@pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
+@pytest.mark.parametrize("lens_q,lens_k,d,dtype,H,Hkv,causal,kv_splits", PACKED_DECODE_CASES)
+def test_varlen_batch_of_short_queries_on_grouped_kv_heads(lens_q, lens_k, d, dtype, H, Hkv, causal, kv_splits, mode):
+    """Every sequence against the oracle walking the same key chunks, and bit-identical to the sequence passed alone
+    where the chunk count of the two calls is the same (enough key blocks for it in the sequence itself)."""
+    pa = _pa()
+    seqs, q, k, v, cu_q, cu_k = _packed_batch(lens_q, lens_k, d, dtype, H, Hkv, causal)
+    S = min(kv_splits, ((max(lens_k) + 63) // 64) // 8)
+    assert S >= 2 and (H // Hkv) * max(lens_q) <= 128
+    print(f"packed decode case q={lens_q} k={lens_k} d={d} {dtype} H={H}/{Hkv} causal={causal} mode={mode}: {S} chunks", flush=True)
+    out, lse = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, cu_seqlens_q=cu_q, cu_seqlens_k=cu_k, kv_splits=kv_splits,
+                                   return_lse=True)
+    torch.cuda.synchronize()
+    oq, ok = np.concatenate([[0], np.cumsum(lens_q)]), np.concatenate([[0], np.cumsum(lens_k)])
+    for b, (n, nk) in enumerate(zip(lens_q, lens_k)):
+        part = out[oq[b]:oq[b + 1]]
+        if n == 0:
+            continue
+        if nk == 0:
+            assert torch.count_nonzero(part) == 0
+            continue
+        qn, kn, vn = seqs[b]
+        pros = parity.check_heads(wl.from_torch(part).transpose(1, 0, 2)[None], dict(q=qn[None], k=kn[None], v=vn[None]),
+                                  causal, mode, dtype, want_lse=True, splits=S)
+        for h in range(H):
+            _lse_close(lse[h, oq[b]:oq[b + 1]].cpu().numpy(), pros[0][h]["lse"], pros[0][h])
+        if (nk + 63) // 64 >= 8 * kv_splits:
+            alone = pa.sage_attn_fwd_ex(q[oq[b]:oq[b + 1]].unsqueeze(0).contiguous(), k[ok[b]:ok[b + 1]].unsqueeze(0).contiguous(),
+                                        v[ok[b]:ok[b + 1]].unsqueeze(0).contiguous(), causal=causal, mode=mode, layout="NHD",
+                                        kv_splits=kv_splits)
+            torch.cuda.synchronize()
+            assert torch.equal(alone[0], part), f"sequence {b}"
+
+
 # ---- row log-sum-exp (the weight for merging results over disjoint key sets) ---------------------
 LSE_CASES = [
     # N, N_kv, d, dtype, H, Hkv, causal
