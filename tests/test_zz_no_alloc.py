@@ -18,8 +18,8 @@ def _pa():
     return pa
 
 
-def _inputs(N, d, H, Hkv, causal, seed):
-    spec = wl.WorkloadSpec(f"s{N}x{d}", 1, H, Hkv, N, d, "bf16", causal, 3.0, 1.5, 2, 10.0, 1.0, 77)
+def _inputs(N, d, H, Hkv, causal, seed, Nk=None):
+    spec = wl.WorkloadSpec(f"s{N}x{d}", 1, H, Hkv, N, d, "bf16", causal, 3.0, 1.5, 2, 10.0, 1.0, 77, 0.0, Nk or 0)
     data = wl.make_inputs(spec, seed)
     dev = torch.device("cuda:0")
     return tuple(wl.to_torch(data[n], spec.dtype, dev) for n in "qkv")
@@ -28,10 +28,13 @@ def _inputs(N, d, H, Hkv, causal, seed):
 @pytest.mark.parametrize("mode", ["int4_fp8", "int8_fp8"])
 def test_static_workspace_entry_point_equals_fwd_ex(mode):
     pa = _pa()
-    calls = [(1000, 128, 4, 2, True, 0), (333, 128, 2, 1, True, 1), (200, 64, 2, 2, False, 2)]   # larger first
-    for N, d, H, Hkv, causal, seed in calls:
-        print(f"static workspace: N={N} d={d} H={H}/{Hkv} causal={causal} mode={mode}", flush=True)
-        q, k, v = _inputs(N, d, H, Hkv, causal, seed)
+    # larger first; the last two split the key range (partial results in the shared array), the very last with the
+    # query heads of a KV head in one tile
+    calls = [(1000, 128, 4, 2, True, 0, None), (333, 128, 2, 1, True, 1, None), (200, 64, 2, 2, False, 2, None),
+             (40, 128, 2, 2, True, 3, 1500), (3, 128, 8, 2, True, 4, 1200)]
+    for N, d, H, Hkv, causal, seed, Nk in calls:
+        print(f"static workspace: N={N} N_kv={Nk or N} d={d} H={H}/{Hkv} causal={causal} mode={mode}", flush=True)
+        q, k, v = _inputs(N, d, H, Hkv, causal, seed, Nk)
         want, want_lse = pa.sage_attn_fwd_ex(q, k, v, causal=causal, mode=mode, return_lse=True)
         out = torch.full_like(q, 3.0)
         lse = torch.empty_like(want_lse)
